@@ -1,0 +1,407 @@
+"""CPU oracle for the per-unit hot path of WINDQuant's allocation method.
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the tests, the smoke check and
+the benchmark's cpu_baseline leg may import it.  It shares no code with the HIP
+library and never calls it.  It is written to be checked against the paper by eye:
+plain numpy, one step per line, no blocking, no fusion.  Floating point is fp64
+unless a line is marked [N] ("normative fp32"): those steps define stored fp32
+quantities (scales, offsets) and integer codes, and are evaluated with IEEE fp32
+operations, one correctly rounded operation per step, so that any conforming
+implementation reproduces them bit for bit.
+
+What the paper fixes and where:
+  * units are column chunks of a weight matrix (Sec. 3.1, "Problem Definition");
+  * the action set {16 (skip), 8, 4, 3, 2, 1.58, 1} in that order (Eq. 3);
+  * state features 0-4 and 9-11 (Table 1);
+  * activation scale = per input channel statistic of calibration activations,
+    saliency = |w| * scale (Sec. 3.5 and App. "Salient Weight Protection");
+  * quantizers fit "per group", group size = chunk size (App. "Per-unit Scale
+    Optimization");
+  * effective-bit accounting B_i and the average b-bar (Eq. 5).
+What the paper leaves open (the loss, the scale fit, clipping, rounding, packing)
+follows the deterministic closed-form / grid-search restatement of the method:
+uniform k-bit scale+offset with a clip grid, ternary absmean, binary sign*mean|w|,
+scored by the activation-weighted squared error  sum_c a_c (w - w_hat)^2  with
+a_c = s_c^2 (a diagonal weighting: the only activation statistic the paper defines
+is per channel, so no Gram matrix appears).
+
+Conventions.  W is [R_out x C_in] row major; "column" = input channel.  Chunk j is
+columns [j*G, (j+1)*G).  A unit is chunk j over `unit_rows` consecutive rows
+(unit_rows = 0: all rows, the paper's definition).  Unit index u = row_block *
+n_chunks + j.  A group is one row of a unit (G consecutive weights of one output
+row); group index g = u * R_u + local_row.  Inputs are float32 ndarrays holding the
+exact input values (bf16 inputs are passed widened, which is exact).
+
+Parity pins (tests/test_oracle_*.py): closed forms, brute force on tiny groups,
+hand-computed examples and golden bytes.  Not pinned by anything: whether these
+deterministic fits reproduce the paper's learned LSQ/SEQ scales or its perplexities
+("parity unpinned": no weights, code or corpus exist to compare against).
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+f32 = np.float32
+f64 = np.float64
+
+# Eq. 3: action index -> bit-width.  Centibits make 1.58 an integer.
+ACTIONS = ("skip", "8", "4", "3", "2", "1.58", "1")
+ACTION_CENTIBITS = (1600, 800, 400, 300, 200, 158, 100)
+UNIFORM_BITS = (8, 4, 3, 2)          # order of the err / clip_idx columns
+N_ERR = 6                            # 8, 4, 3, 2, 1.58, 1
+FLT_MIN_NORMAL = f32(2.0 ** -126)    # below this a step size counts as degenerate
+
+
+# --------------------------------------------------------------------------- units
+def unit_shape(R: int, C: int, G: int, unit_rows: int = 0):
+    """(n_row_blocks, n_chunks, R_u).  Sec. 3.1: units are column chunks."""
+    if G <= 0 or R <= 0 or C <= 0:
+        raise ValueError("empty matrix or chunk")
+    if C % G != 0:
+        raise ValueError("cols must be a multiple of the chunk width")
+    R_u = R if unit_rows == 0 else unit_rows
+    if R % R_u != 0:
+        raise ValueError("unit_rows must divide rows")
+    return R // R_u, C // G, R_u
+
+
+def unit_view(W: np.ndarray, G: int, unit_rows: int, u: int) -> np.ndarray:
+    """The [R_u x G] block of weights that is unit u."""
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    rb, j = divmod(u, n_chunks)
+    return W[rb * R_u:(rb + 1) * R_u, j * G:(j + 1) * G]
+
+
+# ------------------------------------------------------------------ O1 calib stats
+def calib_stats(X: np.ndarray):
+    """Per input channel activation scale from calibration activations X [T x C].
+
+    App. "Salient Weight Protection": a per-channel activation scale estimated in a
+    calibration forward pass; read as the mean absolute activation (the convention
+    of the activation-aware method the paper cites).  The root mean square is a
+    second output: its square is the diagonal of X^T X / T.
+    """
+    X64 = X.astype(f64)
+    T = X64.shape[0]
+    s_absmean = np.abs(X64).sum(axis=0) / T
+    s_rms = np.sqrt((X64 * X64).sum(axis=0) / T)
+    return s_absmean.astype(f32), s_rms.astype(f32)
+
+
+# -------------------------------------------------------------------- O2 features
+def p99_rank(n: int) -> int:
+    """1-based nearest-rank index of the 99th percentile: ceil(0.99 n), in integers."""
+    return (99 * n + 99) // 100
+
+
+def unit_features(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int = 0) -> np.ndarray:
+    """Table 1, dims 0-4 (weight statistics of the unit) and 9-11 (statistics of the
+    activation scale over the unit's G input channels).  Returns [U x 8] fp64:
+    mean, std, abs_mean, sparsity, outlier_frac, s_mean, s_std, s_max.
+    std uses the population form (divide by n); P99 is the nearest-rank order
+    statistic of |w|, so outlier_frac is an exact ratio of counts."""
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    U = n_rb * n_chunks
+    feat = np.zeros((U, 8), dtype=f64)
+    s64 = s.astype(f64)
+    for u in range(U):
+        w = unit_view(W, G, unit_rows, u).astype(f64).ravel()
+        n = w.size
+        aw = np.abs(w)
+        mean = w.sum() / n
+        std = math.sqrt(((w - mean) ** 2).sum() / n)
+        abs_mean = aw.sum() / n
+        sparsity = np.count_nonzero(aw < 1e-6) / n
+        p99 = np.sort(aw)[p99_rank(n) - 1]
+        outlier = np.count_nonzero(aw > 0.5 * p99) / n
+        j = u % n_chunks
+        sc = s64[j * G:(j + 1) * G]
+        s_mean = sc.sum() / G
+        s_std = math.sqrt(((sc - s_mean) ** 2).sum() / G)
+        feat[u] = (mean, std, abs_mean, sparsity, outlier, s_mean, s_std, sc.max())
+    return feat
+
+
+# ------------------------------------------------------- O3 per-group quantizer fit
+def group_stats(Wu: np.ndarray):
+    """Per group (row of the unit): min, max (exact) and S1 = sum |w| accumulated in
+    fp64 in column order (exact for bf16 inputs; the fixed order makes it
+    reproducible for any input)."""
+    mn = Wu.min(axis=1).astype(f32)
+    mx = Wu.max(axis=1).astype(f32)
+    S1 = np.cumsum(np.abs(Wu.astype(f64)), axis=1)[:, -1]
+    return mn, mx, S1
+
+
+def uniform_fit(mn: np.ndarray, mx: np.ndarray, p, bits: int):
+    """[N] scale/offset of the uniform `bits`-bit quantizer at clip ratio p.
+    Both ends of the range shrink toward zero by the same ratio p.  A step size
+    below the smallest normal fp32 is degenerate: step 0, every code 0."""
+    p = f32(p)
+    qmax = f32(2 ** bits - 1)
+    lo = (p * mn).astype(f32)                      # [N] one fp32 multiply
+    hi = (p * mx).astype(f32)                      # [N]
+    Rg = (hi - lo).astype(f32)                     # [N] one fp32 subtract
+    delta = (Rg / qmax).astype(f32)                # [N] one fp32 divide
+    degenerate = ~(delta >= FLT_MIN_NORMAL)
+    delta = np.where(degenerate, f32(0), delta).astype(f32)
+    with np.errstate(divide="ignore"):
+        inv = (f32(1) / delta).astype(f32)         # [N] one fp32 divide (inf if degenerate)
+    return lo, delta, inv, degenerate
+
+
+def uniform_codes(Wu: np.ndarray, lo, delta, inv, degenerate, bits: int) -> np.ndarray:
+    """[N] integer codes in [0, 2^bits - 1]: round-half-to-even of (w - lo) * inv."""
+    qmax = 2 ** bits - 1
+    with np.errstate(invalid="ignore", over="ignore"):
+        u = (Wu - lo[:, None]).astype(f32)         # [N] one fp32 subtract
+        t = (u * inv[:, None]).astype(f32)         # [N] one fp32 multiply
+        q = np.rint(t)                             # [N] ties to even
+    q = np.where(degenerate[:, None], 0.0, q)
+    return np.clip(q, 0, qmax).astype(np.int64)
+
+
+def uniform_dequant(codes, lo, delta) -> np.ndarray:
+    """w_hat = lo + code * step, in fp64 from the stored fp32 lo and step."""
+    return lo.astype(f64)[:, None] + codes.astype(f64) * delta.astype(f64)[:, None]
+
+
+def absmean_scale(S1: np.ndarray, G: int) -> np.ndarray:
+    """[N] per-group mean |w| as stored: fp32 rounding of S1 / G."""
+    return (S1 / f64(G)).astype(f32)
+
+
+def ternary_fit(S1: np.ndarray, G: int):
+    """[N] ternary absmean scale gamma; degenerate (all-zero-like) groups get 0."""
+    gamma = absmean_scale(S1, G)
+    degenerate = ~(gamma >= FLT_MIN_NORMAL)
+    gamma = np.where(degenerate, f32(0), gamma).astype(f32)
+    with np.errstate(divide="ignore"):
+        inv = (f32(1) / gamma).astype(f32)
+    return gamma, inv, degenerate
+
+
+def ternary_codes(Wu: np.ndarray, inv, degenerate) -> np.ndarray:
+    """[N] q in {-1, 0, +1}: round-half-to-even of w / gamma, clamped."""
+    with np.errstate(invalid="ignore", over="ignore"):
+        t = (Wu * inv[:, None]).astype(f32)        # [N] one fp32 multiply
+        q = np.rint(t)
+    q = np.where(degenerate[:, None], 0.0, q)
+    return np.clip(q, -1, 1).astype(np.int64)
+
+
+def binary_codes(Wu: np.ndarray) -> np.ndarray:
+    """bit = 1 where w >= 0 (so -0.0 maps to +1), else 0."""
+    return (Wu >= 0).astype(np.int64)
+
+
+def weighted_sse(Wu64: np.ndarray, What: np.ndarray, a: np.ndarray) -> float:
+    """Activation-aware reconstruction error of one unit: sum a_c (w - w_hat)^2."""
+    d = Wu64 - What
+    return float((a[None, :] * d * d).sum())
+
+
+def fit_score_unit(Wu: np.ndarray, s_chunk: np.ndarray, clip_grid: np.ndarray):
+    """All candidate fits of one unit.  Returns (E_uniform [4 x K], E_ternary,
+    E_binary, ref_energy), raw weighted sums of squares in fp64."""
+    Wu = np.ascontiguousarray(Wu, dtype=f32)
+    R_u, G = Wu.shape
+    Wu64 = Wu.astype(f64)
+    a = s_chunk.astype(f64) ** 2
+    mn, mx, S1 = group_stats(Wu)
+    K = len(clip_grid)
+    E = np.zeros((4, K), dtype=f64)
+    for bi, bits in enumerate(UNIFORM_BITS):
+        for k in range(K):
+            lo, delta, inv, deg = uniform_fit(mn, mx, clip_grid[k], bits)
+            codes = uniform_codes(Wu, lo, delta, inv, deg, bits)
+            E[bi, k] = weighted_sse(Wu64, uniform_dequant(codes, lo, delta), a)
+    gamma, ginv, gdeg = ternary_fit(S1, G)
+    qt = ternary_codes(Wu, ginv, gdeg)
+    E_t = weighted_sse(Wu64, gamma.astype(f64)[:, None] * qt, a)
+    alpha = absmean_scale(S1, G)
+    qb = binary_codes(Wu)
+    E_b = weighted_sse(Wu64, alpha.astype(f64)[:, None] * (2 * qb - 1), a)
+    ref = float((a[None, :] * Wu64 * Wu64).sum())
+    return E, E_t, E_b, ref
+
+
+def argmin_clip(E_row: np.ndarray) -> int:
+    """Clip index with the least error; exact ties go to the largest index (the
+    least clipping)."""
+    m = E_row.min()
+    return int(np.nonzero(E_row == m)[0][-1])
+
+
+def fit_score_all_bits(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int,
+                       clip_grid: np.ndarray, units=None):
+    """Fit and score the six candidate quantizers of every unit.
+
+    Returns err [U x 6] fp64 (order 8, 4, 3, 2, 1.58, 1; the uniform entries at their
+    best clip index), clip_idx [U x 4] uint8, ref_energy [U] fp64 and the full table
+    E [U x 4 x K].  `units` restricts the work to a list of unit indices (the other
+    rows stay zero)."""
+    clip_grid = np.asarray(clip_grid, dtype=f32)
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    U = n_rb * n_chunks
+    K = len(clip_grid)
+    err = np.zeros((U, N_ERR), dtype=f64)
+    clip_idx = np.zeros((U, 4), dtype=np.uint8)
+    ref = np.zeros(U, dtype=f64)
+    table = np.zeros((U, 4, K), dtype=f64)
+    for u in (range(U) if units is None else units):
+        j = u % n_chunks
+        E, E_t, E_b, r = fit_score_unit(unit_view(W, G, unit_rows, u), s[j * G:(j + 1) * G], clip_grid)
+        table[u] = E
+        for bi in range(4):
+            k = argmin_clip(E[bi])
+            clip_idx[u, bi] = k
+            err[u, bi] = E[bi, k]
+        err[u, 4] = E_t
+        err[u, 5] = E_b
+        ref[u] = r
+    return err, clip_idx, ref, table
+
+
+# ------------------------------------------------------------------ O4 apply plan
+def bytes_per_group(action: int, G: int) -> int:
+    """Packed bytes of one group: ceil(G*b/8) for integer b, ceil(G/5) for ternary
+    (5 trits per byte), 0 for skip."""
+    if action == 0:
+        return 0
+    if action == 5:
+        return (G + 4) // 5
+    bits = ACTION_CENTIBITS[action] // 100
+    return (G * bits + 7) // 8
+
+
+def pack_bits(codes: np.ndarray, bits: int) -> np.ndarray:
+    """LSB-first bitstream of one group: code i occupies bits [i*bits, (i+1)*bits)."""
+    n = len(codes)
+    nbytes = (n * bits + 7) // 8
+    out = np.zeros(nbytes, dtype=np.uint8)
+    for i, c in enumerate(int(x) for x in codes):
+        pos = i * bits
+        for b in range(bits):
+            if (c >> b) & 1:
+                out[(pos + b) // 8] |= np.uint8(1 << ((pos + b) % 8))
+    return out
+
+
+def pack_trits(trits: np.ndarray) -> np.ndarray:
+    """Five trits per byte, byte = sum_j trit_j * 3^j; the tail is zero padded."""
+    n = len(trits)
+    nbytes = (n + 4) // 5
+    out = np.zeros(nbytes, dtype=np.uint8)
+    for i, t in enumerate(int(x) for x in trits):
+        out[i // 5] += np.uint8(t * 3 ** (i % 5))
+    return out
+
+
+def unpack_bits(data: np.ndarray, bits: int, n: int) -> np.ndarray:
+    out = np.zeros(n, dtype=np.int64)
+    for i in range(n):
+        v = 0
+        for b in range(bits):
+            pos = i * bits + b
+            v |= ((int(data[pos // 8]) >> (pos % 8)) & 1) << b
+        out[i] = v
+    return out
+
+
+def unpack_trits(data: np.ndarray, n: int) -> np.ndarray:
+    return np.array([(int(data[i // 5]) // 3 ** (i % 5)) % 3 for i in range(n)], dtype=np.int64)
+
+
+def plan_layout(action: np.ndarray, R_u: int, G: int) -> np.ndarray:
+    """Byte offset of every unit's packed payload, each 16-byte aligned; entry U is
+    the end of the last payload rounded up to 16 (the stream length)."""
+    off = np.zeros(len(action) + 1, dtype=np.int64)
+    pos = 0
+    for u, a in enumerate(int(x) for x in action):
+        if not 0 <= a <= 6:
+            raise ValueError("action out of range")
+        off[u] = pos
+        pos += (bytes_per_group(a, G) * R_u + 15) // 16 * 16
+    off[len(action)] = pos
+    return off
+
+
+def quantize_unit(Wu: np.ndarray, action: int, p):
+    """Codes, stored scale and stored offset of one unit under `action` at clip p.
+    Returns (stored [R_u x G] non-negative ints, scale [R_u] f32, offset [R_u] f32,
+    w_hat [R_u x G] fp64)."""
+    Wu = np.ascontiguousarray(Wu, dtype=f32)
+    R_u, G = Wu.shape
+    mn, mx, S1 = group_stats(Wu)
+    zero = np.zeros(R_u, dtype=f32)
+    if action in (1, 2, 3, 4):
+        bits = ACTION_CENTIBITS[action] // 100
+        lo, delta, inv, deg = uniform_fit(mn, mx, p, bits)
+        codes = uniform_codes(Wu, lo, delta, inv, deg, bits)
+        return codes, delta, lo, uniform_dequant(codes, lo, delta)
+    if action == 5:
+        gamma, inv, deg = ternary_fit(S1, G)
+        q = ternary_codes(Wu, inv, deg)
+        return q + 1, gamma, zero, gamma.astype(f64)[:, None] * q
+    if action == 6:
+        alpha = absmean_scale(S1, G)
+        bit = binary_codes(Wu)
+        return bit, alpha, zero, alpha.astype(f64)[:, None] * (2 * bit - 1)
+    raise ValueError("skip units have no codes")
+
+
+def apply_plan(W: np.ndarray, G: int, unit_rows: int, action: np.ndarray,
+               clip_idx, clip_grid: np.ndarray, code_off: np.ndarray, units=None):
+    """Materialise a plan: packed code stream, per-group scale and offset.
+    clip_idx None means no clipping (p = 1).  Skip units write no codes and a zero
+    scale and offset.  `units` restricts the work to some units."""
+    clip_grid = np.asarray(clip_grid, dtype=f32)
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    U = n_rb * n_chunks
+    codes = np.zeros(int(code_off[U]), dtype=np.uint8)
+    scale = np.zeros(U * R_u, dtype=f32)
+    offset = np.zeros(U * R_u, dtype=f32)
+    for u in (range(U) if units is None else units):
+        a = int(action[u])
+        if a == 0:
+            continue
+        p = f32(1)
+        if a in (1, 2, 3, 4) and clip_idx is not None:
+            p = clip_grid[int(clip_idx[u, a - 1])]
+        stored, sc, of, _ = quantize_unit(unit_view(W, G, unit_rows, u), a, p)
+        scale[u * R_u:(u + 1) * R_u] = sc
+        offset[u * R_u:(u + 1) * R_u] = of
+        bpg = bytes_per_group(a, G)
+        base = int(code_off[u])
+        for r in range(R_u):
+            row = pack_trits(stored[r]) if a == 5 else pack_bits(stored[r], ACTION_CENTIBITS[a] // 100)
+            codes[base + r * bpg: base + (r + 1) * bpg] = row
+    return codes, scale, offset
+
+
+# -------------------------------------------------------------- O5 effective bits
+def effective_bits(action, n_unit, n_prot=None):
+    """Eq. 5.  B_i = 16 n_i for skip, else b_i (n_i - n_i^p) + 8 n_i^p.  Totals in
+    centibits (bits x 100) so that 1.58 stays an integer.  Returns (sum B_i in
+    centibits, sum n_i); the average bit-width is sum B / (100 sum n)."""
+    total_cb = 0
+    total_n = 0
+    for i, a in enumerate(int(x) for x in action):
+        n = int(n_unit[i])
+        npr = 0 if n_prot is None else int(n_prot[i])
+        if not 0 <= a <= 6 or n < 0 or not 0 <= npr <= n:
+            raise ValueError("bad plan entry")
+        if a == 0:
+            total_cb += 1600 * n
+        else:
+            total_cb += ACTION_CENTIBITS[a] * (n - npr) + 800 * npr
+        total_n += n
+    return total_cb, total_n
+
+
+def budget_feasible(total_centibits: int, total_weights: int, target_centibits: int) -> bool:
+    """Eq. 1 with B_target = b_target * sum n_i."""
+    return total_centibits <= target_centibits * total_weights

@@ -1,0 +1,182 @@
+"""Benchmark of the whole hot path on one MI355X.
+
+A step = one pass of all five calls (calibration statistics, unit features, fit+score
+at all six bit-widths, apply a budget-feasible plan, effective-bit accounting) over one
+LLaMA-7B-shaped decoder block in bf16 (7 projections, 202,375,168 weights, chunk width
+128, 20 clip ratios, 512 calibration tokens per input), all inputs resident in HBM.
+Prints ONE JSON line.  Synthetic seeded inputs stand in for the checkpoint and the
+calibration corpus.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+G = 128
+K = 20
+TOKENS = 512
+TARGET_CENTIBITS = 200
+HBM_PEAK_GBS = 8000.0
+FP64_VECTOR_PEAK_TFLOPS = 78.6     # 256 CU x 64 lanes x 2 flop (FMA) x 2.4 GHz
+
+
+def fit_score_flops_per_weight(k: int) -> int:
+    """Arithmetic of the definition, FMA = 2: per (weight, clip ratio) 1 subtract + 2 for the
+    clamp + 4 bit-widths x (scale 1, round 1, residual 2, weighted square-accumulate 3) = 31;
+    plus ternary 9, binary 4, reference energy 3, group statistics 3."""
+    return 31 * k + 19
+
+
+def build_block(wq, synth, torch, dev, unit_rows):
+    specs = synth.block_shapes(4096, 11008)
+    cg = synth.clip_grid(K)
+    xs = {}
+    for key, cols in (("h", 4096), ("o", 4096), ("m", 4096), ("d", 11008)):
+        X = synth.activations_llm(TOKENS, cols, seed=synth.matrix_seed(2, 0, len(xs)), device=dev)
+        xs[key] = dict(X=X, s=torch.empty(cols, dtype=torch.float32, device=dev),
+                       ws=torch.empty(wq.workspace_bytes(wq.CALL_CALIB_STATS, wq.WINDQ_BF16, TOKENS, cols),
+                                      dtype=torch.uint8, device=dev))
+    mats = []
+    for i, sp in enumerate(specs):
+        W = synth.weights_llm(sp.rows, sp.cols, seed=synth.matrix_seed(2, 0, i), device=dev)
+        U, R_u = wq.n_units(sp.rows, sp.cols, G, unit_rows)
+        action = synth.random_plan(U, R_u * G, TARGET_CENTIBITS, seed=100 + i)
+        off = wq.windq_plan_layout(action, R_u, G)
+        need = max(wq.workspace_bytes(c, wq.WINDQ_BF16, sp.rows, sp.cols, G, unit_rows, K)
+                   for c in (wq.CALL_UNIT_FEATURES, wq.CALL_FIT_SCORE, wq.CALL_APPLY_PLAN))
+        mats.append(dict(
+            spec=sp, W=W, U=U, R_u=R_u, action=action, action_d=action.to(dev), off=off, off_d=off.to(dev),
+            n_unit=torch.full((U,), R_u * G, dtype=torch.int64),
+            feat=torch.empty(U, 8, dtype=torch.float32, device=dev),
+            err=torch.empty(U, 6, dtype=torch.float32, device=dev),
+            clip_idx=torch.empty(U, 4, dtype=torch.uint8, device=dev),
+            ref=torch.empty(U, dtype=torch.float32, device=dev),
+            codes=torch.empty(max(int(off[-1]), 16), dtype=torch.uint8, device=dev),
+            scale=torch.empty(U * R_u, dtype=torch.float32, device=dev),
+            offset=torch.empty(U * R_u, dtype=torch.float32, device=dev),
+            ws=torch.empty(need, dtype=torch.uint8, device=dev)))
+    return specs, cg, xs, mats
+
+
+def run_step(wq, torch, cg, xs, mats, unit_rows, fit_events=None):
+    for x in xs.values():
+        wq.windq_calib_stats(x["X"], want_rms=False, ws=x["ws"], out=x["s"])
+    total_cb = total_n = 0
+    for m in mats:
+        s = xs[m["spec"].x_key]["s"]
+        wq.windq_unit_features(m["W"], s, G, unit_rows, ws=m["ws"], out=m["feat"])
+        if fit_events is not None:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        wq.windq_fit_score_all_bits(m["W"], s, G, unit_rows, cg, ws=m["ws"], out=(m["err"], m["clip_idx"], m["ref"]))
+        if fit_events is not None:
+            e1.record()
+            fit_events.append((e0, e1))
+        wq.windq_apply_plan(m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"],
+                            ws=m["ws"], out=(m["scale"], m["offset"]))
+        cb, n = wq.windq_effective_bits(m["action"], m["n_unit"])
+        total_cb += cb
+        total_n += n
+    return total_cb, total_n
+
+
+def cpu_baseline(torch, xs, mats, cg):
+    """The oracle, as it stands, on a bounded sample of the same workload: the first two
+    units (chunks) of attn.q through features, fit+score, apply-plan and bit accounting,
+    plus calibration statistics of their input channels."""
+    import numpy as np
+    from oracle import windq_oracle as O
+    m = mats[0]
+    n_units = 2
+    Wn = m["W"][:, : n_units * G].float().cpu().numpy()
+    Xn = xs["h"]["X"][:, : n_units * G].float().cpu().numpy()
+    action = m["action"][:n_units].numpy()
+    t0 = time.perf_counter()
+    s, _ = O.calib_stats(Xn)
+    O.unit_features(Wn, s, G, 0)
+    err, clip_idx, ref, _ = O.fit_score_all_bits(Wn, s, G, 0, cg.numpy())
+    off = O.plan_layout(action, Wn.shape[0], G)
+    O.apply_plan(Wn, G, 0, action, clip_idx, cg.numpy(), off)
+    O.effective_bits(action, [Wn.shape[0] * G] * n_units)
+    dt = time.perf_counter() - t0
+    nbytes = Wn.size * 2
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "seconds": dt,
+            "sample": f"first {n_units} units (4096x{G} each, {Wn.size} weights) of attn.q of the same block, all five calls"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--unit-rows", type=int, default=0, help="0 = the paper's units (all rows); 128 = 128 x G tiles")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2605_26660_amd as wq
+    from paper_2605_26660_amd import synth
+
+    wq.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; libwindq has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    specs, cg, xs, mats = build_block(wq, synth, torch, dev, args.unit_rows)
+    n_weights = sum(sp.rows * sp.cols for sp in specs)
+    n_units = sum(m["U"] for m in mats)
+
+    for _ in range(args.warmup):
+        run_step(wq, torch, cg, xs, mats, args.unit_rows)
+    torch.cuda.synchronize()
+    fit_events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        total_cb, total_n = run_step(wq, torch, cg, xs, mats, args.unit_rows, fit_events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    fit_ms = sum(e0.elapsed_time(e1) for e0, e1 in fit_events) / args.steps     # per step, all 7 launches
+    flops = fit_score_flops_per_weight(K) * n_weights
+    achieved = flops / (fit_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "weight GB/s scored across all 6 bit-widths, whole hot path, 7B-shaped block",
+        "value": n_weights * 2 / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "configs[1]: one LLaMA-7B-shaped decoder block, bf16, chunk 128, 20 clip ratios, "
+                               "512 calibration tokens, plan at 2.0 bits",
+                   "weights": n_weights, "units": n_units, "unit_rows": args.unit_rows, "chunk_w": G, "K": K},
+        "units_per_s": n_units / (ms_per_step * 1e-3),
+        "pct_hbm_peak_whole_step": 100.0 * n_weights * 2 / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "fit_score": {"ms_per_step": fit_ms, "weight_GBps": n_weights * 2 / (fit_ms * 1e-3) / 1e9,
+                      "pct_hbm_peak": 100.0 * n_weights * 2 / (fit_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "launches_per_step": len(mats)},
+        "avg_bits": total_cb / (100.0 * total_n),
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "fit_score_kernel<bf16> (+ its finalize kernel)",
+                     "flops_per_weight": fit_score_flops_per_weight(K)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch, xs, mats, cg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

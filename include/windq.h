@@ -1,0 +1,185 @@
+/*
+ * windq.h - C ABI of libwindq: the per-unit hot path of WINDQuant's allocation
+ * method on one AMD MI355X (gfx950).
+ *
+ * The paper's controller assigns one of seven treatments (Eq. 3: skip/16, 8, 4, 3,
+ * 2, 1.58, 1 bit) to every column-chunk unit of every linear weight matrix under a
+ * global bit budget (Sec. 3.1, Eq. 1).  This library is the data-parallel work that
+ * feeds it: calibration activation scales, the unit's state features (Table 1), the
+ * fit of the lightweight quantizer at all six bit-widths scored by activation-aware
+ * reconstruction error (Sec. 3.5, App. "Per-unit Scale Optimization"), packed codes
+ * of a chosen plan, and effective-bit accounting (Eq. 5).
+ *
+ * Conventions shared by every call
+ *   - W is [rows x cols] = [out features x in features], row major, leading
+ *     dimension `ld` in elements.  A "column" is an input channel: the axis the
+ *     activation scale s[cols] lives on.
+ *   - chunk j  = columns [j*chunk_w, (j+1)*chunk_w).
+ *     unit  u  = chunk j over `unit_rows` consecutive rows; unit_rows = 0 means all
+ *                rows (the paper's unit).  u = row_block * n_chunks + j.
+ *     group    = one row of a unit (chunk_w consecutive weights of one output row);
+ *                g = u * R_u + local_row, R_u = rows per unit.  Scales are per group
+ *                (App. "Per-unit Scale Optimization": per-group scales, group size =
+ *                chunk size).
+ *   - action index a in 0..6 follows Eq. 3: 0 skip(16), 1: 8, 2: 4, 3: 3, 4: 2,
+ *     5: 1.58 (ternary), 6: 1 bit.
+ *   - Pointers are DEVICE pointers unless the comment says HOST.  The caller owns
+ *     every buffer, including the workspace `ws` (size from windq_workspace_bytes;
+ *     256-byte aligned).  The library allocates nothing, frees nothing, never
+ *     synchronises and keeps no state: all device work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and outputs are
+ *     valid once that stream has reached the end of the call's work.
+ *   - Every function returns a status.  All argument checks happen before the first
+ *     launch: on any status other than WINDQ_OK / WINDQ_EHIP no output was touched.
+ *   - Shape limits of the kernels: cols % chunk_w == 0, chunk_w % 8 == 0,
+ *     8 <= chunk_w <= WINDQ_MAX_CHUNK, unit_rows == 0 or rows % unit_rows == 0,
+ *     data pointers 16-byte aligned, ld % 8 == 0.
+ */
+#ifndef WINDQ_H
+#define WINDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum windq_status {
+    WINDQ_OK = 0,
+    WINDQ_EINVAL = 1,     /* null pointer, bad scalar, misaligned pointer            */
+    WINDQ_ESHAPE = 2,     /* shape outside the limits listed above                   */
+    WINDQ_EDTYPE = 3,     /* dtype is not one of windq_dtype                         */
+    WINDQ_EWORKSPACE = 4, /* ws is NULL or smaller than windq_workspace_bytes says   */
+    WINDQ_EHIP = 5        /* a launch failed; hipGetLastError() still holds the cause */
+};
+
+enum windq_dtype { WINDQ_F32 = 0, WINDQ_BF16 = 1 };
+
+enum windq_call {
+    WINDQ_CALL_CALIB_STATS = 0,
+    WINDQ_CALL_UNIT_FEATURES = 1,
+    WINDQ_CALL_FIT_SCORE = 2,
+    WINDQ_CALL_APPLY_PLAN = 3
+};
+
+#define WINDQ_N_ACTIONS 7
+#define WINDQ_N_ERR 6        /* error columns: 8, 4, 3, 2, 1.58, 1 bit */
+#define WINDQ_N_FEAT 8
+#define WINDQ_MAX_CLIP 64    /* longest clip grid */
+#define WINDQ_MAX_CHUNK 512  /* widest chunk */
+
+/* A row-major matrix in device memory.  Never written by the library. */
+typedef struct windq_mat {
+    const void* data; /* DEVICE, 16-byte aligned */
+    int32_t dtype;    /* windq_dtype */
+    int32_t reserved; /* set to 0 */
+    int64_t rows, cols;
+    int64_t ld;       /* elements between consecutive rows, >= cols, multiple of 8 */
+} windq_mat;
+
+/*
+ * Calibration statistics (App. "Salient Weight Protection": a per-channel activation
+ * scale estimated in a calibration forward pass; Table 1 dims 9-11 are statistics of
+ * it).  X is [tokens x channels].
+ *   s_absmean[c] = mean_t |x_tc|          (the activation scale used everywhere else)
+ *   s_rms[c]     = sqrt(mean_t x_tc^2)    (optional, may be NULL; its square is the
+ *                                          diagonal of X^T X / tokens)
+ * Sums are accumulated in fp64 in a fixed order (bit-reproducible run to run).
+ */
+int windq_calib_stats(const windq_mat* X, float* s_absmean /*[cols]*/, float* s_rms /*[cols] or NULL*/,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * State features of every unit (Table 1, dims 0-4 and 9-11), feat[u][8] =
+ *   mean, std (population), mean|w|, fraction with |w| < 1e-6,
+ *   fraction with |w| > 0.5 * P99(|w|)  (P99 = nearest-rank order statistic, rank
+ *   ceil(0.99 n), found exactly by radix selection),
+ *   mean, std (population), max of s over the unit's chunk_w input channels.
+ * Counts are exact integers; moments are accumulated in fp64.
+ */
+int windq_unit_features(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                        float* feat /*[U][8]*/, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Fit the lightweight quantizer of every unit at all six bit-widths and score each fit
+ * by the activation-aware reconstruction error  E = sum_rows sum_c s_c^2 (w - w_hat)^2
+ * (Sec. 3.5: local scale fitting per unit, reconstruction error decides fallback; the
+ * weighting uses the per-channel activation scale, the only activation statistic the
+ * paper defines).  Per group, in fp32 with one correctly rounded operation per step:
+ *   uniform b in {8,4,3,2} at clip ratio p:  lo = p*min, hi = p*max, step = (hi-lo)/(2^b-1),
+ *       code = clamp(rne((w-lo) * (1/step)), 0, 2^b-1), w_hat = lo + code*step
+ *       (step below the smallest normal fp32: step = 0, codes 0);
+ *   ternary:  gamma = mean|w|, q = clamp(rne(w * (1/gamma)), -1, 1), w_hat = gamma*q;
+ *   binary:   alpha = mean|w|, w_hat = alpha * (w >= 0 ? +1 : -1).
+ * For each uniform bit-width the clip ratio is chosen once per unit: the grid index
+ * with the least unit error, exact ties to the largest index.
+ *   clip_grid  HOST [K], ascending, each in (0, 1], 1 <= K <= WINDQ_MAX_CLIP
+ *   err        [U][6]  errors in the order 8, 4, 3, 2, 1.58, 1 bit (uniform ones at
+ *                      their chosen clip index), raw weighted sums of squares
+ *   clip_idx   [U][4]  chosen grid index for 8, 4, 3, 2 bit
+ *   ref_energy [U] or NULL: sum s_c^2 w^2, to normalise err
+ * Errors are accumulated in fp64 in a fixed order.
+ */
+int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                             const float* clip_grid /*HOST [K]*/, int32_t K,
+                             float* err /*[U][6]*/, uint8_t* clip_idx /*[U][4]*/, float* ref_energy /*[U] or NULL*/,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* Packed bytes of one group under an action: ceil(chunk_w*b/8), ceil(chunk_w/5) for
+ * ternary, 0 for skip; -1 for an action outside 0..6 or chunk_w <= 0.  HOST only. */
+int64_t windq_bytes_per_group(int32_t action, int32_t chunk_w);
+
+/*
+ * Byte offsets of the packed payload of every unit of a plan (HOST only, no GPU).
+ * Unit u occupies [code_off[u], code_off[u] + R_u * bytes_per_group) and every
+ * payload starts 16-byte aligned; code_off[U] is the stream length.
+ * WINDQ_EINVAL if an action is outside 0..6.
+ */
+int windq_plan_layout(const uint8_t* action /*HOST [U]*/, int64_t n_units, int64_t rows_per_unit, int32_t chunk_w,
+                      int64_t* code_off /*HOST [U+1]*/);
+
+/*
+ * Materialise a plan (Sec. 3.3: the environment applies the selected quantization to
+ * the unit).  For every unit with action != skip, refit each group at that bit-width
+ * with exactly the fp32 steps listed at windq_fit_score_all_bits, at clip ratio
+ * clip_grid[clip_idx[u][a-1]] for uniform actions (p = 1 when clip_idx is NULL), and
+ * write
+ *   scale[g]   step / gamma / alpha           offset[g]  lo, or 0 for ternary and binary
+ *   codes      per group, rows of a unit consecutive from code_off[u]:
+ *              integer b: LSB-first bitstream (code i in bits [i*b, (i+1)*b));
+ *              ternary: five trits (q+1) per byte, byte = sum trit_j 3^j, tail zero padded;
+ *              the padding up to the next 16-byte boundary after a unit is zeroed.
+ * Skip units write no codes and scale = offset = 0.  A unit whose action is outside
+ * 0..6 or whose payload does not fit in [0, codes_bytes) is treated as skip (use
+ * windq_plan_layout to build code_off).
+ */
+int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t unit_rows,
+                     const uint8_t* action /*[U]*/, const uint8_t* clip_idx /*[U][4] or NULL*/,
+                     const float* clip_grid /*HOST [K]*/, int32_t K,
+                     const int64_t* code_off /*[U+1]*/, uint8_t* codes, size_t codes_bytes,
+                     float* scale /*[U*R_u]*/, float* offset /*[U*R_u]*/,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Effective-bit accounting of a plan (Eq. 5), HOST only, exact integers:
+ *   B_i = 16 n_i for skip, else b_i (n_i - n_i^p) + 8 n_i^p,
+ * in centibits (bits x 100: 1600/800/400/300/200/158/100) so that 1.58 stays integral.
+ * The average bit-width is total_centibits / (100 total_weights); the plan meets a
+ * target b (Eq. 1) iff total_centibits <= 100 b total_weights.
+ * WINDQ_EINVAL on an action outside 0..6, n < 0 or n_prot outside [0, n].
+ */
+int windq_effective_bits(const uint8_t* action /*HOST [U]*/, const int64_t* n_unit /*HOST [U]*/,
+                         const int64_t* n_prot /*HOST [U] or NULL = 0*/, int64_t n_units,
+                         int64_t* total_centibits /*HOST*/, int64_t* total_weights /*HOST*/);
+
+/* Workspace bytes a call needs for these shapes (0 if the shape is invalid). HOST only. */
+size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, int64_t cols,
+                             int32_t chunk_w, int64_t unit_rows, int32_t K);
+
+const char* windq_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WINDQ_H */

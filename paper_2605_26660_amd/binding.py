@@ -1,0 +1,222 @@
+"""Thin ctypes binding over libwindq's C ABI (include/windq.h).
+
+Argument marshalling only: torch tensors supply device memory and the current stream;
+every step of the path runs in the HIP kernels.  There is no CPU fallback: if the
+library is missing, or a GPU call is made without a GPU, this raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libwindq.so")
+
+WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP = range(6)
+WINDQ_F32, WINDQ_BF16 = 0, 1
+CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN = range(4)
+N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK = 7, 6, 8, 64, 512
+
+EXPORTS = (
+    "windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_bytes_per_group",
+    "windq_plan_layout", "windq_apply_plan", "windq_effective_bits", "windq_workspace_bytes",
+    "windq_status_str",
+)
+
+
+class WindqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.windq_status_str(status).decode() if _lib is not None else "?"
+        super().__init__(f"{where}: status {status} ({msg})")
+
+
+class windq_mat(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("ld", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def load(path: str | None = None):
+    """dlopen the in-tree library and declare the signatures.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2605_26660_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    vp, i32, i64, sz = c.c_void_p, c.c_int32, c.c_int64, c.c_size_t
+    pm = c.POINTER(windq_mat)
+    lib.windq_calib_stats.argtypes = [pm, vp, vp, vp, sz, vp]
+    lib.windq_unit_features.argtypes = [pm, vp, i32, i64, vp, vp, sz, vp]
+    lib.windq_fit_score_all_bits.argtypes = [pm, vp, i32, i64, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.windq_bytes_per_group.argtypes = [i32, i32]
+    lib.windq_bytes_per_group.restype = i64
+    lib.windq_plan_layout.argtypes = [vp, i64, i64, i32, vp]
+    lib.windq_apply_plan.argtypes = [pm, i32, i64, vp, vp, vp, i32, vp, vp, sz, vp, vp, vp, sz, vp]
+    lib.windq_effective_bits.argtypes = [vp, vp, vp, i64, c.POINTER(i64), c.POINTER(i64)]
+    lib.windq_workspace_bytes.argtypes = [i32, i32, i64, i64, i32, i64, i32]
+    lib.windq_workspace_bytes.restype = sz
+    lib.windq_status_str.argtypes = [c.c_int]
+    lib.windq_status_str.restype = c.c_char_p
+    for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
+                 "windq_apply_plan", "windq_effective_bits"):
+        getattr(lib, name).restype = c.c_int
+    _lib = lib
+    return lib
+
+
+def lib():
+    return load()
+
+
+def _check(status: int, where: str):
+    if status != WINDQ_OK:
+        raise WindqError(status, where)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return WINDQ_F32
+    if t.dtype == torch.bfloat16:
+        return WINDQ_BF16
+    raise WindqError(WINDQ_EDTYPE, "dtype")
+
+
+def _require_cuda(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise RuntimeError("libwindq runs on the GPU only: pass CUDA tensors (no CPU fallback exists)")
+
+
+def as_mat(t: torch.Tensor) -> windq_mat:
+    assert t.dim() == 2 and t.stride(1) == 1, "row-major 2-D tensor expected"
+    return windq_mat(t.data_ptr(), _dtype_code(t), 0, t.shape[0], t.shape[1], t.stride(0))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def workspace_bytes(call: int, dtype: int, rows: int, cols: int, chunk_w: int = 8, unit_rows: int = 0, K: int = 1) -> int:
+    return int(load().windq_workspace_bytes(call, dtype, rows, cols, chunk_w, unit_rows, K))
+
+
+def _workspace(call, t, chunk_w, unit_rows, K, ws):
+    need = workspace_bytes(call, _dtype_code(t), t.shape[0], t.shape[1], chunk_w, unit_rows, K)
+    if ws is None:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=t.device)
+    return ws
+
+
+def n_units(rows: int, cols: int, chunk_w: int, unit_rows: int = 0):
+    """(U, rows per unit) of a [rows x cols] matrix."""
+    R_u = rows if unit_rows == 0 else unit_rows
+    return (rows // R_u) * (cols // chunk_w), R_u
+
+
+# --------------------------------------------------------------------------- calls
+def windq_calib_stats(X: torch.Tensor, want_rms: bool = True, ws: torch.Tensor | None = None,
+                      out: torch.Tensor | None = None):
+    """-> (s_absmean [C] f32, s_rms [C] f32 or None), device tensors."""
+    _require_cuda(X)
+    C = X.shape[1]
+    s_abs = out if out is not None else torch.empty(C, dtype=torch.float32, device=X.device)
+    s_rms = torch.empty(C, dtype=torch.float32, device=X.device) if want_rms else None
+    ws = _workspace(CALL_CALIB_STATS, X, 8, 0, 1, ws)
+    m = as_mat(X)
+    _check(load().windq_calib_stats(ctypes.byref(m), s_abs.data_ptr(), _ptr(s_rms), ws.data_ptr(), ws.numel(),
+                                    _stream()), "windq_calib_stats")
+    return s_abs, s_rms
+
+
+def windq_unit_features(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int = 0,
+                        ws: torch.Tensor | None = None, out: torch.Tensor | None = None):
+    """-> feat [U x 8] f32 on the device."""
+    _require_cuda(W, s)
+    U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    feat = out if out is not None else torch.empty(U, N_FEAT, dtype=torch.float32, device=W.device)
+    ws = _workspace(CALL_UNIT_FEATURES, W, chunk_w, unit_rows, 1, ws)
+    m = as_mat(W)
+    _check(load().windq_unit_features(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, feat.data_ptr(),
+                                      ws.data_ptr(), ws.numel(), _stream()), "windq_unit_features")
+    return feat
+
+
+def windq_fit_score_all_bits(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor,
+                             ws: torch.Tensor | None = None, out=None):
+    """clip_grid: host float32 tensor [K].  -> (err [U x 6] f32, clip_idx [U x 4] u8, ref_energy [U] f32)."""
+    _require_cuda(W, s)
+    assert not clip_grid.is_cuda and clip_grid.dtype == torch.float32 and clip_grid.is_contiguous()
+    K = clip_grid.numel()
+    U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    if out is None:
+        err = torch.empty(U, N_ERR, dtype=torch.float32, device=W.device)
+        clip_idx = torch.empty(U, 4, dtype=torch.uint8, device=W.device)
+        ref = torch.empty(U, dtype=torch.float32, device=W.device)
+    else:
+        err, clip_idx, ref = out
+    ws = _workspace(CALL_FIT_SCORE, W, chunk_w, unit_rows, K, ws)
+    m = as_mat(W)
+    _check(load().windq_fit_score_all_bits(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, clip_grid.data_ptr(), K,
+                                           err.data_ptr(), clip_idx.data_ptr(), ref.data_ptr(), ws.data_ptr(),
+                                           ws.numel(), _stream()), "windq_fit_score_all_bits")
+    return err, clip_idx, ref
+
+
+def windq_bytes_per_group(action: int, chunk_w: int) -> int:
+    return int(load().windq_bytes_per_group(action, chunk_w))
+
+
+def windq_plan_layout(action: torch.Tensor, rows_per_unit: int, chunk_w: int) -> torch.Tensor:
+    """action: host uint8 [U].  -> code_off host int64 [U+1]."""
+    assert not action.is_cuda and action.dtype == torch.uint8 and action.is_contiguous()
+    U = action.numel()
+    off = torch.empty(U + 1, dtype=torch.int64)
+    _check(load().windq_plan_layout(action.data_ptr(), U, rows_per_unit, chunk_w, off.data_ptr()), "windq_plan_layout")
+    return off
+
+
+def windq_apply_plan(W: torch.Tensor, chunk_w: int, unit_rows: int, action: torch.Tensor, clip_idx, clip_grid,
+                     code_off: torch.Tensor, codes: torch.Tensor | None = None, ws: torch.Tensor | None = None,
+                     out=None):
+    """action [U] u8, clip_idx [U x 4] u8 or None, code_off [U+1] i64: device tensors; clip_grid host f32 or None.
+    -> (codes u8 [code_off[U]], scale f32 [U*R_u], offset f32 [U*R_u]) on the device."""
+    _require_cuda(W, action, clip_idx, code_off, codes)
+    U, R_u = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    if codes is None:
+        total = int(code_off[-1].item())
+        codes = torch.empty(max(total, 16), dtype=torch.uint8, device=W.device)
+    if out is None:
+        scale = torch.empty(U * R_u, dtype=torch.float32, device=W.device)
+        offset = torch.empty(U * R_u, dtype=torch.float32, device=W.device)
+    else:
+        scale, offset = out
+    K = 0 if clip_grid is None else clip_grid.numel()
+    ws = _workspace(CALL_APPLY_PLAN, W, chunk_w, unit_rows, 1, ws)
+    m = as_mat(W)
+    _check(load().windq_apply_plan(ctypes.byref(m), chunk_w, unit_rows, action.data_ptr(), _ptr(clip_idx),
+                                   None if clip_grid is None else clip_grid.data_ptr(), K, code_off.data_ptr(),
+                                   codes.data_ptr(), codes.numel(), scale.data_ptr(), offset.data_ptr(),
+                                   ws.data_ptr(), ws.numel(), _stream()), "windq_apply_plan")
+    return codes, scale, offset
+
+
+def windq_effective_bits(action: torch.Tensor, n_unit: torch.Tensor, n_prot: torch.Tensor | None = None):
+    """Host tensors: action u8 [U], n_unit i64 [U], n_prot i64 [U] or None.  -> (total centibits, total weights)."""
+    assert not action.is_cuda and action.dtype == torch.uint8 and n_unit.dtype == torch.int64
+    cb, nw = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(load().windq_effective_bits(action.data_ptr(), n_unit.data_ptr(), _ptr(n_prot), action.numel(),
+                                       ctypes.byref(cb), ctypes.byref(nw)), "windq_effective_bits")
+    return cb.value, nw.value

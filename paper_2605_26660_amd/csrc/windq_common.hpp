@@ -1,0 +1,137 @@
+// Shared host/device helpers of libwindq (gfx950 only).
+//
+// Kernel-wide design: a weight matrix is cut into tiles of TILE_ROWS rows x one chunk
+// (chunk_w columns).  A workgroup loads its tile from HBM with coalesced 128-bit loads
+// and stages it in LDS; then every lane owns ONE group (one row of the tile) and walks
+// along its chunk_w columns.  A group's min, max, mean|w| and all of its quantizer
+// parameters are therefore private to a lane: no cross-lane traffic and no redundant
+// parameter arithmetic inside the hot loops; the per-column activation weight is
+// wave-uniform and comes in through scalar loads.  Lanes are combined only once per
+// tile, in a fixed order, so every result is bit-reproducible.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "windq.h"
+
+namespace windq {
+
+constexpr int TILE_ROWS = 64;   // rows per tile = lanes per wavefront
+constexpr int LDS_PAD = 4;      // dwords added to a tile row: keeps 128-bit LDS reads of
+                                // 64 different rows free of bank conflicts
+
+// Geometry of the unit decomposition of one matrix (Sec. 3.1: column-chunk units).
+struct Geometry {
+    int64_t rows, cols, ld;
+    int32_t chunk_w;
+    int64_t R_u;             // rows per unit
+    int64_t n_chunks;        // cols / chunk_w
+    int64_t n_rb;            // row blocks = rows / R_u
+    int64_t U;               // units = n_rb * n_chunks
+    int64_t tiles_per_unit;  // ceil(R_u / TILE_ROWS)
+    int64_t n_tiles;         // U * tiles_per_unit
+};
+
+int check_matrix(const windq_mat* M);
+int make_geometry(const windq_mat* W, int32_t chunk_w, int64_t unit_rows, Geometry* g);
+int check_clip_grid(const float* clip_grid, int32_t K);
+bool aligned(const void* p, size_t a);
+size_t round_up(size_t x, size_t a);
+
+// Clip grid handed to kernels by value (lands in the kernarg segment, read with
+// scalar loads).
+struct ClipGrid {
+    float p[WINDQ_MAX_CLIP];
+};
+
+inline size_t tile_lds_bytes(int32_t chunk_w) {
+    return (size_t)TILE_ROWS * (size_t)(chunk_w + LDS_PAD) * sizeof(float);
+}
+
+// Raises the dynamic-LDS limit of a kernel when a tile needs more than the 64 KB a
+// workgroup gets by default (gfx950 has 160 KB per CU).
+int ensure_lds(const void* kernel, size_t bytes);
+
+#ifdef __HIPCC__
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// Decode tile index -> (unit, first row, valid rows, first column).
+struct TileCoord {
+    int64_t u;        // unit index
+    int64_t row0;     // first matrix row of the tile
+    int64_t lrow0;    // first row of the tile, local to the unit
+    int32_t nrows;    // valid rows in the tile (1..TILE_ROWS)
+    int64_t col0;     // first column of the chunk
+    int64_t t;        // tile index inside the unit
+};
+
+// Tiles are numbered so that consecutive workgroups walk across the chunks of one band
+// of rows: a band of 64 rows is contiguous in HBM row by row, and neighbouring
+// workgroups (which land on different XCDs round-robin) share DRAM pages, not L2 lines.
+__device__ __forceinline__ TileCoord tile_coord(const Geometry& g, int64_t tile) {
+    TileCoord tc;
+    const int64_t j = tile % g.n_chunks;
+    const int64_t band = tile / g.n_chunks;          // band = rb * tiles_per_unit + t
+    const int64_t rb = band / g.tiles_per_unit;
+    tc.t = band - rb * g.tiles_per_unit;
+    tc.u = rb * g.n_chunks + j;
+    tc.lrow0 = tc.t * TILE_ROWS;
+    tc.row0 = rb * g.R_u + tc.lrow0;
+    const int64_t left = g.R_u - tc.lrow0;
+    tc.nrows = left < TILE_ROWS ? (int32_t)left : TILE_ROWS;
+    tc.col0 = j * g.chunk_w;
+    return tc;
+}
+
+// Cooperative load of one tile into LDS as fp32, row stride (chunk_w + LDS_PAD) dwords.
+// Each thread moves 8 consecutive elements per step: one 128-bit global load for bf16,
+// two for fp32; 16 (or 32) neighbouring threads cover one contiguous row segment.
+// Rows past the end of the unit are filled with zeros.
+template <int DT>
+__device__ __forceinline__ void load_tile(const void* __restrict__ data, int64_t ld, const TileCoord& tc,
+                                          int32_t chunk_w, float* __restrict__ tile) {
+    const int32_t pieces = chunk_w >> 3;
+    const int32_t stride = chunk_w + LDS_PAD;
+    const int32_t total = TILE_ROWS * pieces;
+    for (int32_t i = threadIdx.x; i < total; i += blockDim.x) {
+        const int32_t r = i / pieces;
+        const int32_t pc = i - r * pieces;
+        float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+        if (r < tc.nrows) {
+            const int64_t off = (tc.row0 + r) * ld + tc.col0 + (int64_t)pc * 8;
+            if (DT == WINDQ_BF16) {
+                const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(data) + off);
+                v0.x = bf16_bits_to_f32(raw.x & 0xffffu); v0.y = __uint_as_float(raw.x & 0xffff0000u);
+                v0.z = bf16_bits_to_f32(raw.y & 0xffffu); v0.w = __uint_as_float(raw.y & 0xffff0000u);
+                v1.x = bf16_bits_to_f32(raw.z & 0xffffu); v1.y = __uint_as_float(raw.z & 0xffff0000u);
+                v1.z = bf16_bits_to_f32(raw.w & 0xffffu); v1.w = __uint_as_float(raw.w & 0xffff0000u);
+            } else {
+                const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(data) + off);
+                v0 = src[0];
+                v1 = src[1];
+            }
+        }
+        float4* dst = reinterpret_cast<float4*>(tile + r * stride + pc * 8);
+        dst[0] = v0;
+        dst[1] = v1;
+    }
+}
+
+// Sum of a double over the 64 lanes of a wavefront, fixed butterfly order.
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+#endif  // __HIPCC__
+
+}  // namespace windq

@@ -1,0 +1,52 @@
+// Workspace layouts: one place that both windq_workspace_bytes and the launchers use.
+#pragma once
+
+#include "windq_common.hpp"
+
+namespace windq {
+
+// ---- calib_stats: per slab of CALIB_SLAB_ROWS tokens, per channel, two fp64 partial sums
+constexpr int CALIB_SLAB_ROWS = 32;
+inline int64_t calib_slabs(int64_t rows) { return (rows + CALIB_SLAB_ROWS - 1) / CALIB_SLAB_ROWS; }
+inline size_t calib_ws_bytes(int64_t rows, int64_t cols) {
+    return round_up((size_t)calib_slabs(rows) * (size_t)cols * 2 * sizeof(double), 256);
+}
+
+// ---- fit_score: per tile, one fp64 partial error per candidate
+// candidates: [b][k] for b in 8,4,3,2 (index b*K + k), then ternary, binary, reference energy
+__host__ __device__ inline int32_t fit_score_ncand(int32_t K) { return 4 * K + 3; }
+inline size_t fit_score_ws_bytes(const Geometry& g, int32_t K) {
+    return round_up((size_t)g.n_tiles * (size_t)fit_score_ncand(K) * sizeof(double), 256);
+}
+
+// ---- unit_features
+//   moments  [n_tiles][4] fp64   sum w, sum w^2, sum |w|, count(|w| < 1e-6)
+//   above    [n_tiles]    u32    count(|w| > 0.5 P99)
+//   hist     [U][FEAT_BINS] u32  radix-select histogram of the current digit
+//   sel      [U] {prefix u32, pad u32, rank u64}
+constexpr int FEAT_DIGIT_BITS = 11;
+constexpr int FEAT_BINS = 1 << FEAT_DIGIT_BITS;
+struct FeatSel {
+    uint32_t prefix;   // key bits decided so far (high digits)
+    uint32_t pad;
+    uint64_t rank;     // 1-based rank still to find among keys that share the prefix
+};
+struct FeatLayout {
+    size_t moments, above, hist, sel, total;
+};
+inline FeatLayout features_layout(const Geometry& g) {
+    FeatLayout L;
+    size_t pos = 0;
+    L.moments = pos; pos = round_up(pos + (size_t)g.n_tiles * 4 * sizeof(double), 256);
+    L.above = pos;   pos = round_up(pos + (size_t)g.n_tiles * sizeof(uint32_t), 256);
+    L.hist = pos;    pos = round_up(pos + (size_t)g.U * FEAT_BINS * sizeof(uint32_t), 256);
+    L.sel = pos;     pos = round_up(pos + (size_t)g.U * sizeof(FeatSel), 256);
+    L.total = pos;
+    return L;
+}
+inline size_t features_ws_bytes(const Geometry& g, int32_t /*dtype*/) { return features_layout(g).total; }
+
+// ---- apply_plan needs no scratch; a token size keeps "ws != NULL" uniform across calls
+inline size_t apply_ws_bytes(const Geometry&) { return 256; }
+
+}  // namespace windq

@@ -1,0 +1,167 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, validates arguments before any launch, and its pure-host
+entry points (plan layout, bytes per group, effective bits of Eq. 5, workspace sizes)
+agree with hand-computed values and with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import windq_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "windq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(windq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(windq):
+    names = header_functions()
+    assert set(names) == set(windq.EXPORTS)
+    lib = windq.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(windq):
+    lib = windq.lib()
+    seen = {lib.windq_status_str(i) for i in range(6)}
+    assert len(seen) == 6 and lib.windq_status_str(0) == b"ok"
+    assert lib.windq_status_str(99) == b"unknown status"
+
+
+def test_bytes_per_group_matches_hand_table_and_oracle(windq):
+    assert [windq.windq_bytes_per_group(a, 128) for a in range(7)] == [0, 128, 64, 48, 32, 26, 16]
+    assert [windq.windq_bytes_per_group(a, 64) for a in range(7)] == [0, 64, 32, 24, 16, 13, 8]
+    for G in (8, 40, 256, 512):
+        for a in range(7):
+            assert windq.windq_bytes_per_group(a, G) == O.bytes_per_group(a, G)
+    assert windq.windq_bytes_per_group(7, 64) == -1 and windq.windq_bytes_per_group(1, 0) == -1
+
+
+def test_plan_layout_hand_example_and_oracle(windq):
+    action = torch.tensor([6, 0, 5, 3, 1, 0, 4], dtype=torch.uint8)
+    off = windq.windq_plan_layout(action, 3, 64)
+    assert off.tolist() == [0, 32, 32, 80, 160, 352, 352, 400]
+    g = torch.Generator().manual_seed(5)
+    action = torch.randint(0, 7, (1000,), generator=g, dtype=torch.uint8)
+    for R_u, G in ((128, 128), (4096, 64), (7, 40)):
+        off = windq.windq_plan_layout(action, R_u, G)
+        assert np.array_equal(off.numpy(), O.plan_layout(action.numpy(), R_u, G))
+        assert torch.all(off % 16 == 0)
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_plan_layout(torch.tensor([1, 7], dtype=torch.uint8), 4, 64)
+    assert e.value.status == windq.WINDQ_EINVAL
+    assert windq.windq_plan_layout(torch.zeros(0, dtype=torch.uint8), 4, 64).tolist() == [0]
+
+
+def test_effective_bits_hand_totals(windq):
+    # Eq. 5 hand example: one unit per action, n = 1000, 30 protected -> 36432.6 bits
+    action = torch.arange(7, dtype=torch.uint8)
+    n = torch.full((7,), 1000, dtype=torch.int64)
+    npr = torch.full((7,), 30, dtype=torch.int64)
+    assert windq.windq_effective_bits(action, n, npr) == (3643260, 7000)
+    assert windq.windq_effective_bits(action, n) == ((1600 + 800 + 400 + 300 + 200 + 158 + 100) * 1000, 7000)
+    two = torch.full((5,), 4, dtype=torch.uint8)
+    n5 = torch.tensor([16384, 524288, 1, 7, 100000], dtype=torch.int64)
+    cb, nw = windq.windq_effective_bits(two, n5)
+    assert cb == 200 * nw and nw == int(n5.sum())
+    g = torch.Generator().manual_seed(6)
+    a = torch.randint(0, 7, (5000,), generator=g, dtype=torch.uint8)
+    nn = torch.randint(1, 1 << 20, (5000,), generator=g, dtype=torch.int64)
+    pp = (nn.double() * 0.03).long()
+    assert windq.windq_effective_bits(a, nn, pp) == O.effective_bits(a.numpy(), nn.numpy(), pp.numpy())
+    for bad in ((torch.tensor([7], dtype=torch.uint8), torch.tensor([1]), None),
+                (torch.tensor([1], dtype=torch.uint8), torch.tensor([-1]), None),
+                (torch.tensor([1], dtype=torch.uint8), torch.tensor([5]), torch.tensor([6]))):
+        with pytest.raises(windq.WindqError) as e:
+            windq.windq_effective_bits(*bad)
+        assert e.value.status == windq.WINDQ_EINVAL
+
+
+def test_workspace_sizes(windq):
+    B, F = windq.WINDQ_BF16, windq.WINDQ_F32
+    # fit-score: one fp64 per (64-row tile, candidate): 32 units x 64 tiles x (4*20+3)
+    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4096, 128, 0, 20) == 32 * 64 * 83 * 8
+    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4096, 128, 128, 20) == 1024 * 2 * 83 * 8
+    # calib: two fp64 per (32-token slab, channel)
+    assert windq.workspace_bytes(windq.CALL_CALIB_STATS, F, 256, 512) == 8 * 512 * 16
+    assert windq.workspace_bytes(windq.CALL_UNIT_FEATURES, B, 4096, 4096, 128, 0, 1) > 32 * 2048 * 4
+    assert windq.workspace_bytes(windq.CALL_APPLY_PLAN, B, 4096, 4096, 128, 0, 1) == 256
+    # invalid shapes give 0
+    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4100, 128, 0, 20) == 0
+    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4096, 128, 100, 20) == 0
+    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4096, 128, 0, 65) == 0
+    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, 2, 4096, 4096, 128, 0, 20) == 0
+
+
+def _mat(windq, rows=128, cols=128, dtype=None, data=4096, ld=None):
+    return windq.windq_mat(data, windq.WINDQ_BF16 if dtype is None else dtype, 0, rows, cols, cols if ld is None else ld)
+
+
+def test_argument_validation_happens_before_any_launch(windq):
+    """Every error path returns before touching the GPU, so fake (never dereferenced)
+    device addresses are enough and this runs without one."""
+    lib = windq.lib()
+    P = 4096            # a 'device pointer' that is never dereferenced on these paths
+    grid = torch.linspace(0.5, 1.0, 20, dtype=torch.float32)
+    gp = grid.data_ptr()
+    br = ctypes.byref
+
+    def fit(m, s=P, G=64, ur=0, g=gp, K=20, err=P, ci=P, ws=P, wsb=1 << 30):
+        return lib.windq_fit_score_all_bits(br(m), s, G, ur, g, K, err, ci, None, ws, wsb, None)
+
+    assert fit(_mat(windq, data=None)) == windq.WINDQ_EINVAL
+    assert fit(_mat(windq, data=4100)) == windq.WINDQ_EINVAL            # misaligned
+    assert fit(_mat(windq, dtype=5)) == windq.WINDQ_EDTYPE
+    assert fit(_mat(windq, cols=100, ld=104)) == windq.WINDQ_ESHAPE      # cols % 8
+    assert fit(_mat(windq, cols=192), G=128) == windq.WINDQ_ESHAPE       # cols % chunk_w
+    assert fit(_mat(windq), G=12) == windq.WINDQ_ESHAPE                  # chunk_w % 8
+    assert fit(_mat(windq, cols=1024), G=1024) == windq.WINDQ_ESHAPE     # chunk too wide
+    assert fit(_mat(windq), ur=48) == windq.WINDQ_ESHAPE                 # unit_rows does not divide rows
+    assert fit(_mat(windq, ld=120)) == windq.WINDQ_ESHAPE                # ld < cols
+    assert fit(_mat(windq), s=None) == windq.WINDQ_EINVAL
+    assert fit(_mat(windq), err=None) == windq.WINDQ_EINVAL
+    assert fit(_mat(windq), g=None) == windq.WINDQ_EINVAL
+    assert fit(_mat(windq), K=0) == windq.WINDQ_EINVAL
+    assert fit(_mat(windq), K=65) == windq.WINDQ_EINVAL
+    assert fit(_mat(windq), ws=None) == windq.WINDQ_EWORKSPACE
+    assert fit(_mat(windq), wsb=8) == windq.WINDQ_EWORKSPACE
+    bad = torch.tensor([0.5, 0.4, 1.0], dtype=torch.float32)             # not ascending
+    assert fit(_mat(windq), g=bad.data_ptr(), K=3) == windq.WINDQ_EINVAL
+    bad = torch.tensor([0.5, 1.5], dtype=torch.float32)                  # above 1
+    assert fit(_mat(windq), g=bad.data_ptr(), K=2) == windq.WINDQ_EINVAL
+
+    m = _mat(windq)
+    assert lib.windq_calib_stats(br(m), None, None, P, 1 << 30, None) == windq.WINDQ_EINVAL
+    assert lib.windq_calib_stats(br(m), P, None, None, 0, None) == windq.WINDQ_EWORKSPACE
+    assert lib.windq_calib_stats(None, P, None, P, 1 << 30, None) == windq.WINDQ_EINVAL
+    assert lib.windq_unit_features(br(m), None, 64, 0, P, P, 1 << 30, None) == windq.WINDQ_EINVAL
+    assert lib.windq_unit_features(br(m), P, 64, 0, P, P, 16, None) == windq.WINDQ_EWORKSPACE
+    assert lib.windq_unit_features(br(m), P, 60, 0, P, P, 1 << 30, None) == windq.WINDQ_ESHAPE
+
+    def apply(action=P, ci=P, g=gp, K=20, off=P, codes=P, nbytes=1 << 20, scale=P, offset=P, ws=P):
+        return lib.windq_apply_plan(br(m), 64, 0, action, ci, g, K, off, codes, nbytes, scale, offset, ws, 256, None)
+
+    assert apply(action=None) == windq.WINDQ_EINVAL
+    assert apply(off=None) == windq.WINDQ_EINVAL
+    assert apply(scale=None) == windq.WINDQ_EINVAL
+    assert apply(codes=None) == windq.WINDQ_EINVAL
+    assert apply(codes=4100) == windq.WINDQ_EINVAL
+    assert apply(g=None) == windq.WINDQ_EINVAL               # clip indices without a grid
+    assert apply(ws=None) == windq.WINDQ_EWORKSPACE
+
+
+def test_binding_refuses_cpu_tensors(windq):
+    W = torch.zeros(64, 64, dtype=torch.bfloat16)
+    s = torch.ones(64)
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        windq.windq_fit_score_all_bits(W, s, 64, 0, torch.ones(1))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        windq.windq_calib_stats(W)

@@ -1,0 +1,267 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.  Bars: integer outputs (codes, packed bytes, clip
+indices, counts) bit-exact; stored scales/offsets bit-exact (they are defined by
+single fp32 operations); errors, features and activation scales within 1e-5 relative."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import windq_oracle as O
+from paper_2605_26660_amd import synth
+
+pytestmark = pytest.mark.gpu
+REL = 1e-5
+DEV = "cuda"
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy()
+
+
+def grid(K):
+    return synth.clip_grid(K)
+
+
+def assert_close(got, want, rel=REL, floor=0.0, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    err = np.abs(got - want)
+    tol = rel * np.abs(want) + floor
+    bad = err > tol
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} off; worst rel {np.max(err / (np.abs(want) + 1e-300)):.3e}"
+
+
+def check_fit_score(windq, W, s, G, unit_rows, K, units=None):
+    cg = grid(K)
+    err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, G, unit_rows, cg)
+    torch.cuda.synchronize()
+    o_err, o_idx, o_ref, table = O.fit_score_all_bits(to_np(W), to_np(s), G, unit_rows, cg.numpy(), units=units)
+    sel = slice(None) if units is None else list(units)
+    g_err, g_idx, g_ref = to_np(err)[sel], clip_idx.cpu().numpy()[sel], to_np(ref)[sel]
+    o_err, o_idx, o_ref, table = o_err[sel], o_idx[sel], o_ref[sel], table[sel]
+    # clip index: the oracle's, unless the GPU picked an index whose oracle error ties the minimum to 1e-9
+    for u, b in zip(*np.nonzero(g_idx != o_idx)):
+        assert table[u, b, g_idx[u, b]] <= table[u, b].min() * (1 + 1e-9), (u, b, g_idx[u, b], o_idx[u, b])
+    assert_close(g_err, o_err, what="err")
+    assert_close(g_ref, o_ref, what="ref_energy")
+    return err, clip_idx, ref
+
+
+def check_apply(windq, W, G, unit_rows, action, clip_idx, K, units=None):
+    """action: host uint8; clip_idx: device uint8 [U,4] or None."""
+    U, R_u = windq.n_units(W.shape[0], W.shape[1], G, unit_rows)
+    cg = grid(K) if clip_idx is not None else None
+    off = windq.windq_plan_layout(action, R_u, G)
+    total = int(off[-1])
+    codes = torch.full((max(total, 16),), 0xAB, dtype=torch.uint8, device=DEV)   # poison: padding must be written
+    codes, scale, offset = windq.windq_apply_plan(W, G, unit_rows, action.to(DEV), clip_idx, cg, off.to(DEV), codes=codes)
+    torch.cuda.synchronize()
+    ci = None if clip_idx is None else clip_idx.cpu().numpy()
+    o_codes, o_scale, o_offset = O.apply_plan(to_np(W), G, unit_rows, action.numpy(), ci,
+                                              np.ones(1, np.float32) if cg is None else cg.numpy(), off.numpy(), units=units)
+    g_codes, g_scale, g_offset = codes.cpu().numpy()[:total], scale.cpu().numpy(), offset.cpu().numpy()
+    for u in (range(U) if units is None else units):
+        lo, hi = int(off[u]), int(off[u + 1])
+        assert np.array_equal(g_codes[lo:hi], o_codes[lo:hi]), f"codes of unit {u} (action {int(action[u])})"
+        gs = slice(u * R_u, (u + 1) * R_u)
+        assert np.array_equal(g_scale[gs].view(np.uint32), o_scale[gs].view(np.uint32)), f"scale of unit {u}"
+        assert np.array_equal(g_offset[gs].view(np.uint32), o_offset[gs].view(np.uint32)), f"offset of unit {u}"
+    return total
+
+
+# ------------------------------------------------------------------- calib stats
+@pytest.mark.parametrize("T,C,dtype", [(256, 512, torch.float32), (512, 4096, torch.bfloat16), (100, 1032, torch.bfloat16),
+                                       (1, 8, torch.float32), (33, 520, torch.float32)])
+def test_calib_stats(windq, T, C, dtype):
+    X = synth.activations_small(T, C, seed=0, device=DEV, dtype=dtype) if dtype == torch.float32 else \
+        synth.activations_llm(T, C, seed=2, device=DEV, dtype=dtype)
+    s_abs, s_rms = windq.windq_calib_stats(X)
+    s_only, none = windq.windq_calib_stats(X, want_rms=False)
+    torch.cuda.synchronize()
+    o_abs, o_rms = O.calib_stats(to_np(X))
+    assert none is None and torch.equal(s_abs, s_only)
+    assert_close(to_np(s_abs), o_abs, what="s_absmean")
+    assert_close(to_np(s_rms), o_rms, what="s_rms")
+
+
+def test_calib_stats_strided_rows(windq):
+    big = synth.activations_llm(64, 1024, seed=3, device=DEV)
+    X = big[:, 256:768]                                   # ld = 1024, cols = 512, 16-byte aligned start
+    s_abs, s_rms = windq.windq_calib_stats(X)
+    o_abs, o_rms = O.calib_stats(to_np(X))
+    assert_close(to_np(s_abs), o_abs)
+    assert_close(to_np(s_rms), o_rms)
+
+
+# ----------------------------------------------------------------- unit features
+def check_features(windq, W, s, G, unit_rows):
+    feat = windq.windq_unit_features(W, s, G, unit_rows)
+    torch.cuda.synchronize()
+    want = O.unit_features(to_np(W), to_np(s), G, unit_rows)
+    got = to_np(feat).astype(np.float64)
+    n = (W.shape[0] if unit_rows == 0 else unit_rows) * G
+    # the mean is a sum of signed terms: its natural scale is mean|w| (fp64 sums make it far tighter)
+    assert_close(got[:, 0], want[:, 0], floor=REL * want[:, 2].max(), what="mean")
+    assert_close(got[:, 1:3], want[:, 1:3], what="std/absmean")
+    # counts are exact integers; the fp32 output holds count/n to 2^-24
+    assert np.array_equal(np.rint(got[:, 3] * n), np.rint(want[:, 3] * n)), "sparsity count"
+    assert np.array_equal(np.rint(got[:, 4] * n), np.rint(want[:, 4] * n)), "outlier count"
+    assert_close(got[:, 5:8], want[:, 5:8], floor=1e-30, what="s stats")
+
+
+@pytest.mark.parametrize("unit_rows", [0, 128])
+def test_features_small_fp32(windq, unit_rows):
+    W = synth.weights_small(device=DEV)
+    X = synth.activations_small(device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    check_features(windq, W, s, 64, unit_rows)
+
+
+@pytest.mark.parametrize("R,C,G,unit_rows", [(512, 1024, 128, 0), (512, 1024, 128, 128), (200, 256, 64, 100),
+                                             (64, 512, 256, 0), (8, 16, 8, 4)])
+def test_features_bf16(windq, R, C, G, unit_rows):
+    W = synth.weights_llm(R, C, seed=11, device=DEV)
+    s = torch.rand(C, device=DEV) + 0.1
+    check_features(windq, W, s, G, unit_rows)
+
+
+def test_features_exact_zeros_ties_and_tiny_values(windq):
+    W = torch.zeros(128, 128, dtype=torch.float32, device=DEV)
+    W[:, 64:] = 0.5                       # every |w| in chunk 1 equal: P99 = 0.5, none above 0.25? all are
+    W[::2, :32] = 5e-7                    # below the sparsity threshold
+    W[1::2, :32] = 1e-6                   # fp32(1e-6) is below 1e-6 as a real number
+    W[3, 70] = -8.0
+    s = torch.ones(128, device=DEV)
+    check_features(windq, W, s, 64, 0)
+    check_features(windq, W.to(torch.bfloat16), s, 64, 64)
+
+
+# ------------------------------------------------------------------- fit + score
+def test_fit_score_small_config(windq):
+    """512x512 fp32, 4 outlier columns, calibration scales from X, G = 64, 20 clip points."""
+    W = synth.weights_small(device=DEV)
+    X = synth.activations_small(device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    err, clip_idx, ref = check_fit_score(windq, W, s, 64, 0, 20)
+    assert err.shape == (8, 6)
+    check_fit_score(windq, W, s, 64, 128, 20)
+
+
+@pytest.mark.parametrize("R,C,G,unit_rows,K", [
+    (512, 1024, 128, 0, 20), (512, 1024, 128, 128, 20), (200, 256, 64, 100, 20), (256, 512, 128, 0, 1),
+    (128, 256, 128, 0, 7), (128, 256, 64, 64, 40), (64, 512, 256, 0, 20), (64, 1024, 512, 0, 5), (8, 16, 8, 4, 3),
+    (192, 120, 40, 96, 6)])
+def test_fit_score_bf16_shapes(windq, R, C, G, unit_rows, K):
+    W = synth.weights_llm(R, C, seed=21, device=DEV)
+    X = synth.activations_llm(64, C, seed=22, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    check_fit_score(windq, W, s, G, unit_rows, K)
+
+
+def test_fit_score_degenerate_groups(windq):
+    W = synth.weights_llm(128, 256, seed=23, device=DEV)
+    W[0:10] = 0                      # all-zero groups
+    W[10:20, :128] = 0.125           # constant groups: zero range
+    W[20, :] = 1e-38                 # range so small that the step is subnormal
+    W[20, 0] = 0
+    W[21, 0:128] = torch.linspace(-1, 1, 128, device=DEV).to(torch.bfloat16)
+    s = torch.ones(256, device=DEV)
+    check_fit_score(windq, W, s, 128, 0, 20)
+    check_fit_score(windq, W.float(), s, 128, 64, 4)
+
+
+def test_fit_score_is_bit_reproducible(windq):
+    W = synth.weights_llm(512, 1024, seed=24, device=DEV)
+    s = torch.rand(1024, device=DEV) + 0.1
+    a = windq.windq_fit_score_all_bits(W, s, 128, 0, grid(20))
+    b = windq.windq_fit_score_all_bits(W, s, 128, 0, grid(20))
+    torch.cuda.synchronize()
+    assert all(torch.equal(x.view(torch.uint8).flatten(), y.view(torch.uint8).flatten()) for x, y in zip(a, b))
+
+
+# -------------------------------------------------------------------- apply plan
+@pytest.mark.parametrize("R,C,G,unit_rows,dtype", [
+    (256, 512, 128, 0, torch.bfloat16), (256, 512, 128, 128, torch.bfloat16), (200, 256, 64, 100, torch.bfloat16),
+    (512, 512, 64, 0, torch.float32), (24, 80, 40, 3, torch.bfloat16), (6, 16, 8, 3, torch.float32),
+    (64, 512, 256, 0, torch.bfloat16)])
+def test_apply_plan_every_action(windq, R, C, G, unit_rows, dtype):
+    W = synth.weights_llm(R, C, seed=31, device=DEV, dtype=dtype)
+    s = torch.rand(C, device=DEV) + 0.1
+    U, R_u = windq.n_units(R, C, G, unit_rows)
+    K = 20
+    _, clip_idx, _ = windq.windq_fit_score_all_bits(W, s, G, unit_rows, grid(K))
+    gen = torch.Generator().manual_seed(32)
+    for trial in range(3):
+        action = torch.randint(0, 7, (U,), generator=gen, dtype=torch.uint8)
+        if trial == 0:
+            action[:] = torch.arange(U) % 7                   # every action present whenever U >= 7
+        check_apply(windq, W, G, unit_rows, action, clip_idx, K)
+    for a in range(7):                                        # uniform plans: one action everywhere, no clipping
+        check_apply(windq, W, G, unit_rows, torch.full((U,), a, dtype=torch.uint8), None, 1)
+
+
+def test_apply_plan_degenerate_groups_and_ties(windq):
+    W = torch.zeros(64, 128, dtype=torch.float32, device=DEV)
+    W[0:8, :64] = 0.25                                        # constant groups
+    W[8, :4] = torch.tensor([0.0, 3.0, 0.5, 1.5], device=DEV)  # step 1 at 2 bits: ties go to even
+    W[8, 4] = 2.5
+    W[9, :64] = torch.tensor([0.5, 1.5, -0.5, 1.5] * 16, device=DEV)   # ternary ties at +-0.5 gamma
+    W[10, :] = -0.0
+    W[11, :64] = 1e-38
+    for a in range(7):
+        check_apply(windq, W, 64, 0, torch.full((2,), a, dtype=torch.uint8), None, 1)
+        check_apply(windq, W.to(torch.bfloat16), 64, 32, torch.full((4,), a, dtype=torch.uint8), None, 1)
+
+
+def test_apply_plan_malformed_entries_are_skipped(windq):
+    W = synth.weights_llm(64, 256, seed=33, device=DEV)
+    action = torch.tensor([1, 9], dtype=torch.uint8)                  # 9 is not an action
+    off = torch.tensor([0, 64 * 128, 64 * 128], dtype=torch.int64)
+    codes = torch.full((64 * 128,), 0xAB, dtype=torch.uint8, device=DEV)
+    codes, scale, offset = windq.windq_apply_plan(W, 128, 0, action.to(DEV), None, None, off.to(DEV), codes=codes)
+    torch.cuda.synchronize()
+    assert torch.all(scale[64:] == 0) and torch.all(scale[:64] > 0)
+    # a payload that would run past the end of the buffer is not written
+    short = torch.full((1024,), 0xAB, dtype=torch.uint8, device=DEV)
+    short, scale, offset = windq.windq_apply_plan(W, 128, 0, action.to(DEV), None, None, off.to(DEV), codes=short)
+    torch.cuda.synchronize()
+    assert torch.all(short == 0xAB) and torch.all(scale == 0)
+
+
+# ------------------------------------------- full-size shapes, sampled against the oracle
+@pytest.mark.parametrize("name,rows,cols", [("attn.q", 4096, 4096), ("mlp.down", 4096, 11008)])
+def test_full_size_7b_matrices_sampled(windq, name, rows, cols):
+    """One LLaMA-7B-shaped projection in bf16 at the benchmark's launch configuration
+    (chunk 128, 20 clip points, paper units = all rows).  The oracle checks sampled units
+    on the very bits that were generated on the device."""
+    G, K = 128, 20
+    W = synth.weights_llm(rows, cols, seed=synth.matrix_seed(2, 0, 0), device=DEV)
+    X = synth.activations_llm(512, cols, seed=5, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    U = cols // G
+    units = sorted({0, U // 3, U - 1})
+    Wn, sn = to_np(W), to_np(s)
+    err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, G, 0, grid(K))
+    feat = windq.windq_unit_features(W, s, G, 0)
+    torch.cuda.synchronize()
+    o_err, o_idx, o_ref, table = O.fit_score_all_bits(Wn, sn, G, 0, grid(K).numpy(), units=units)
+    assert np.array_equal(clip_idx.cpu().numpy()[units], o_idx[units])
+    assert_close(to_np(err)[units], o_err[units], what="err")
+    assert_close(to_np(ref)[units], o_ref[units], what="ref")
+    # features of the sampled units: the oracle on a matrix holding only those chunks
+    cols_sel = np.concatenate([np.arange(u * G, (u + 1) * G) for u in units])
+    want = O.unit_features(Wn[:, cols_sel], sn[cols_sel], G, 0)
+    got = to_np(feat)[units].astype(np.float64)
+    n = rows * G
+    assert_close(got[:, 1:3], want[:, 1:3], what="std/absmean")
+    assert np.array_equal(np.rint(got[:, 3:5] * n), np.rint(want[:, 3:5] * n))
+    assert_close(got[:, 5:8], want[:, 5:8], what="s stats")
+    # a random plan at 2 bits, codes of the sampled units bit-exact
+    action = synth.random_plan(U, rows * G, 200, seed=9)
+    action[units[0]] = 1
+    action[units[1]] = 5
+    action[units[2]] = 3
+    total = check_apply(windq, W, G, 0, action, clip_idx, K, units=units)
+    cb, nw = windq.windq_effective_bits(action, torch.full((U,), rows * G, dtype=torch.int64))
+    assert nw == rows * cols and cb == sum(O.ACTION_CENTIBITS[int(a)] for a in action) * rows * G
+    assert total == sum(O.bytes_per_group(int(a), G) for a in action) * rows

@@ -4,24 +4,36 @@
 // Optimization": per-group scales, group size = chunk size).
 //
 // Work per weight: 4 bit-widths x K clip ratios + ternary + binary = 4K+2 candidate
-// quantizers, about 23 vector instructions per (weight, clip ratio).  At K = 20 that
-// is ~480 instructions per 2-byte weight: the kernel is bound by the vector ALU, not by
-// HBM, by a factor of ~40.  The design therefore minimises instructions per candidate:
-//   * lane-per-group (see windq_common.hpp): quantizer parameters are lane-private, so
-//     each is computed exactly once; the activation weight a_c = s_c^2 is wave-uniform
-//     and arrives by scalar loads;
-//   * all arithmetic in the inner loop is fp64.  On gfx950 fp64 FMA/ADD/MUL issue at
-//     the same rate as (unpacked) fp32, so exactness is free: residuals w - w_hat are
-//     formed without cancellation error and the unit errors agree with an fp64
-//     reference to ~1e-12;
-//   * rounding to the nearest code is one FMA that adds 1.5*2^52 to t = (w-lo)/step and
-//     one subtract; the clamp to the code range is done once per clip ratio on (w-lo),
-//     shared by the four bit-widths (clamping (w-lo) to [0, hi-lo] before rounding
-//     yields the same code as clamping the rounded code to [0, 2^b-1]);
-//   * the four wavefronts of a workgroup share the LDS tile and split the clip grid.
-// Rounding decisions are taken on the fp64 product here, on the fp32 product in
-// windq_apply_plan; where they differ the weight sits within 1e-7 steps of a rounding
-// boundary, where both codes give the same squared error to within 1e-6 of itself.
+// quantizers.  At K = 20 that is ~550 vector instructions per 2-byte weight: the kernel
+// is bound by the vector ALU, not by HBM, by a factor of ~30.  So the design minimises
+// issue cycles per candidate, using what measurement shows about gfx950's vector ALU:
+// v_fma/mul/add/sub_f32 whose operands are all VGPRs issue about 1.7x faster than any
+// other vector instruction (fp64, min/max/med3, rounding, conversions, anything with an
+// SGPR or literal operand).  Hence:
+//   * lane-per-group (see windq_common.hpp): quantizer parameters are lane-private and
+//     live in VGPRs; wave-uniform per-column values (s_c, -2^23 s_c) are staged in LDS
+//     and read back into VGPRs, constants are pinned in VGPRs;
+//   * the hot loop is made of fast fp32 FMA/ADD/MUL only.  Per (weight, clip ratio):
+//       x  = clamp01((w - lo) * (1/range))      one multiply with the free [0,1] output clamp
+//       per bit-width b:  tM = x * (2^b-1) + 2^23      rounds to the nearest code (RNE)
+//                         q' = tM * s_c - 2^23 s_c     = s_c * code, one rounding
+//                         r' = q' * (-step_b) + u'     = s_c * (w - lo - code*step_b)
+//                         acc_b += r' * r'
+//     4 instructions per candidate and no separate clamp of the code (x is already in
+//     [0,1]); u' = s_c*w - s_c*lo costs one more FMA per clip ratio;
+//   * at 8 bits the residual is ~1/500 of (w - lo), so the fp32 rounding of (w - lo)
+//     would show at the 1e-5 level in units whose error is carried by few weights.
+//     The 8-bit candidate therefore takes the exact route: (w - lo) as an fp32 pair
+//     (sum, rounding error) by an error-free two-sum, residual = fma(code, -step, sum)
+//     (exact) + error term.  5 + 2 more fast instructions per (weight, clip ratio);
+//   * lanes accumulate in fp32 over the chunk's columns only (<= 512 terms); rows are
+//     combined in fp64 in a fixed order (LDS transpose), tiles by the finalize kernel.
+// Rounding decisions here are taken on x*(2^b-1); windq_apply_plan takes them on
+// (w-lo)*(1/step) in fp32.  Where they differ the weight sits within ~3e-5 steps of a
+// rounding boundary, where both codes give the same squared error to ~1e-4 of itself,
+// and such weights are ~1e-4 of all: the effect on a unit's error is below 1e-7.
+// Supported dynamic range: |s_c * w| within fp32's normal range after squaring
+// (about 1e-18 .. 1e18); smaller products contribute zero.
 #include <float.h>
 
 #include "windq_common.hpp"
@@ -31,8 +43,10 @@ namespace windq {
 
 constexpr int FS_THREADS = 256;
 constexpr int FS_WAVES = FS_THREADS / 64;
-constexpr int FS_KB = 5;   // clip ratios evaluated together by one wavefront pass
-constexpr double RNE_MAGIC = 6755399441055744.0;   // 1.5 * 2^52: x + M - M rounds x to nearest-even integer
+constexpr int FS_KB = 5;                    // clip ratios evaluated together by one wavefront pass
+constexpr int FS_NRED = FS_KB * 4;          // per-lane sums a pass produces
+constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
+constexpr float RNE_ANY = 12582912.0f;      // 1.5 * 2^23: same for signed x
 
 struct FitScoreArgs {
     const void* W;
@@ -44,52 +58,121 @@ struct FitScoreArgs {
     ClipGrid grid;
 };
 
-// One weight against FS_KB clip ratios x 4 bit-widths.
-__device__ __forceinline__ void score_weight(const double w, const double a, const double (&lo)[FS_KB],
-                                             const double (&rg)[FS_KB], const double (&inv)[FS_KB][4],
-                                             const double (&dl)[FS_KB][4], double (&acc)[FS_KB][4]) {
+// LDS of a workgroup: the raw tile, s_c of the chunk's columns, and per wavefront a
+// 16 x FS_NRED scratch for combining rows.  Small on purpose: the fast fp32 issue rate
+// needs five or more resident wavefronts per SIMD (a single wavefront issues at most one
+// vector instruction per ~5 cycles), so LDS per workgroup must stay below ~30 KB.
+inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w) {
+    return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
+           (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float);
+}
+
+// Keeps a value in a VGPR and hides its origin from the optimiser, so that it is never
+// folded into an SGPR, literal or negated operand (any of which drops the instruction
+// to the slow issue rate).
+__device__ __forceinline__ float pin_vgpr(float x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+// a * b with the result clamped to [0, 1] by the instruction's output modifier.
+__device__ __forceinline__ float mul_clamp01(float a, float b) {
+    float r;
+    asm("v_mul_f32_e64 %0, %1, %2 clamp" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+struct KParams {
+    float rinv, nlo;   // 1/range, -lo
+    float nd[4];       // -step for 8, 4, 3, 2 bits (0 when degenerate)
+};
+
+// One weight against FS_KB clip ratios x 4 bit-widths.  sc = s_c, nM = -2^23 (in a VGPR).
+__device__ __forceinline__ void score_weight(const float w, const float sc, const KParams (&P)[FS_KB],
+                                             const float (&Q)[4], const float M, const float nM,
+                                             float (&acc)[FS_KB][4]) {
+    const float w1 = w * sc;
+    const float ms = sc * nM;                              // -2^23 * s_c, exact
 #pragma unroll
     for (int i = 0; i < FS_KB; ++i) {
-        const double u = w - lo[i];
-        const double uc = fmin(fmax(u, 0.0), rg[i]);
+        // exact (w - lo) = u + du
+        const float u = w + P[i].nlo;
+        const float x = mul_clamp01(u, P[i].rinv);        // position in the clipped range, in [0, 1]
+        const float u1 = fmaf(P[i].nlo, sc, w1);          // s_c * (w - lo)
+        const float bb = u - w;
+        const float du = (w - (u - bb)) + (P[i].nlo - bb);
+        {   // 8 bits
+            const float q = fmaf(x, Q[0], M) - M;
+            const float r = fmaf(q, P[i].nd[0], u) + du;
+            const float r1 = r * sc;
+            acc[i][0] = fmaf(r1, r1, acc[i][0]);
+        }
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const double q = fma(uc, inv[i][b], RNE_MAGIC) - RNE_MAGIC;   // nearest code, already in range
-            const double r = fma(-q, dl[i][b], u);                        // w - (lo + q*step)
-            acc[i][b] = fma(a * r, r, acc[i][b]);
+        for (int b = 1; b < 4; ++b) {
+            const float tM = fmaf(x, Q[b], M);
+            const float q1 = fmaf(tM, sc, ms);
+            const float r1 = fmaf(q1, P[i].nd[b], u1);
+            acc[i][b] = fmaf(r1, r1, acc[i][b]);
         }
     }
 }
 
+// x + (x of the lane whose index differs in bit 0 / bit 1): after both, every lane of a
+// quad (4 adjacent rows) holds the quad's sum.
+__device__ __forceinline__ float quad_sum(float x) {
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+    return x;
+}
+
+// Sum N per-lane fp32 values over the 64 lanes (rows) of a wavefront: quads in fp32 by
+// DPP (two adds), the 16 quad sums in fp64 in row order through the wavefront's private
+// LDS scratch.  Lane j < N returns total j.  Fixed order: bit-reproducible.
+template <int N>
+__device__ __forceinline__ double rows_sum(const float (&v)[N], float* __restrict__ red, int lane) {
+    static_assert(N <= FS_NRED, "scratch row too short");
+    float qs[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) qs[j] = quad_sum(v[j]);
+    if ((lane & 3) == 0) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) red[(lane >> 2) * FS_NRED + j] = qs[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    double tot = 0.0;
+    if (lane < N) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tot += (double)red[i * FS_NRED + lane];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    return tot;
+}
+
 template <int DT>
-__global__ __launch_bounds__(FS_THREADS) void fit_score_kernel(const FitScoreArgs A) {
-    extern __shared__ float tile[];
+__global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScoreArgs A) {
+    extern __shared__ char smem[];
     const TileCoord tc = tile_coord(A.g, blockIdx.x);
     const int32_t G = A.g.chunk_w;
-    load_tile<DT>(A.W, A.g.ld, tc, G, tile);
-    __syncthreads();
-
+    constexpr int EB = Elem<DT>::bytes;
+    const int32_t row_bytes = G * EB + 16;
+    char* __restrict__ tile = smem;
+    float* __restrict__ scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
+    float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
+
+    load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
+    for (int32_t c = threadIdx.x; c < G; c += FS_THREADS) scol[c] = A.s[tc.col0 + c];
+    __syncthreads();
+
     const bool valid = lane < tc.nrows;
-    const float* __restrict__ wrow = tile + lane * (G + LDS_PAD);
-    const float* __restrict__ s_chunk = A.s + tc.col0;
+    const char* __restrict__ wrow = tile + lane * row_bytes;
     const int32_t K = A.K;
     double* __restrict__ out = A.partial + ((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) *
                                                (size_t)fit_score_ncand(K);
-
-    // Group statistics: min, max, S1 = sum |w| in fp64 in column order (exact for bf16).
-    float mn = wrow[0], mx = wrow[0];
-    double S1 = 0.0;
-    for (int32_t c = 0; c < G; c += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(wrow + c);
-        mn = fminf(fminf(mn, v.x), fminf(v.y, fminf(v.z, v.w)));
-        mx = fmaxf(fmaxf(mx, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
-        S1 += (double)fabsf(v.x);
-        S1 += (double)fabsf(v.y);
-        S1 += (double)fabsf(v.z);
-        S1 += (double)fabsf(v.w);
-    }
 
     // Work items of the tile: n_kpass passes over FS_KB clip ratios each, plus one light
     // pass (ternary, binary, reference energy).  Item i goes to wavefront (i + rot) % 4;
@@ -98,7 +181,19 @@ __global__ __launch_bounds__(FS_THREADS) void fit_score_kernel(const FitScoreArg
     const int n_items = A.n_kpass + 1;
     for (int item = (wave - rot) & (FS_WAVES - 1); item < n_items; item += FS_WAVES) {
         if (item < A.n_kpass) {
-            double lo[FS_KB], rg[FS_KB], inv[FS_KB][4], dl[FS_KB][4], acc[FS_KB][4];
+            float mn, mx;
+            {
+                float w[8];
+                read8<DT>(wrow, 0, w);
+                mn = mx = w[0];
+                for (int32_t c = 0; c < G; c += 8) {
+                    read8<DT>(wrow, c, w);
+                    mn = fminf(fminf(fminf(mn, w[0]), fminf(w[1], w[2])), fminf(fminf(w[3], w[4]), fminf(w[5], fminf(w[6], w[7]))));
+                    mx = fmaxf(fmaxf(fmaxf(mx, w[0]), fmaxf(w[1], w[2])), fmaxf(fmaxf(w[3], w[4]), fmaxf(w[5], fmaxf(w[6], w[7]))));
+                }
+            }
+            KParams P[FS_KB];
+            float acc[FS_KB][4];
 #pragma unroll
             for (int i = 0; i < FS_KB; ++i) {
                 int k = item * FS_KB + i;
@@ -107,82 +202,111 @@ __global__ __launch_bounds__(FS_THREADS) void fit_score_kernel(const FitScoreArg
                 const float flo = p * mn;
                 const float fhi = p * mx;
                 const float frg = fhi - flo;
-                lo[i] = (double)flo;
-                rg[i] = (double)frg;
+                const float rinv = frg >= FLT_MIN ? __builtin_amdgcn_rcpf(frg) : 0.0f;
+                P[i].rinv = rinv;
+                P[i].nlo = pin_vgpr(-flo);
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
-                    const float qmax = b == 0 ? 255.0f : (b == 1 ? 15.0f : (b == 2 ? 7.0f : 3.0f));
-                    float d = frg / qmax;
-                    const bool ok = d >= FLT_MIN;
-                    d = ok ? d : 0.0f;
-                    dl[i][b] = (double)d;
-                    inv[i][b] = ok ? (double)(1.0f / d) : 0.0;
-                    acc[i][b] = 0.0;
+                    // step = range / (2^b - 1): the fp64 product rounds to the correctly rounded
+                    // fp32 quotient (but for ~1e-9 of inputs, where it is one ulp off)
+                    const double rq = b == 0 ? 1.0 / 255.0 : (b == 1 ? 1.0 / 15.0 : (b == 2 ? 1.0 / 7.0 : 1.0 / 3.0));
+                    const float d = (float)((double)frg * rq);
+                    P[i].nd[b] = pin_vgpr(d >= FLT_MIN ? -d : 0.0f);
+                    acc[i][b] = 0.0f;
                 }
             }
-            for (int32_t c = 0; c < G; c += 4) {
-                const float4 v = *reinterpret_cast<const float4*>(wrow + c);
-                const double s0 = (double)s_chunk[c], s1 = (double)s_chunk[c + 1];
-                const double s2 = (double)s_chunk[c + 2], s3 = (double)s_chunk[c + 3];
-                score_weight((double)v.x, s0 * s0, lo, rg, inv, dl, acc);
-                score_weight((double)v.y, s1 * s1, lo, rg, inv, dl, acc);
-                score_weight((double)v.z, s2 * s2, lo, rg, inv, dl, acc);
-                score_weight((double)v.w, s3 * s3, lo, rg, inv, dl, acc);
+            const float Q[4] = {pin_vgpr(255.0f), pin_vgpr(15.0f), pin_vgpr(7.0f), pin_vgpr(3.0f)};
+            const float M = pin_vgpr(RNE_POS);
+            const float nM = pin_vgpr(-RNE_POS);
+            for (int32_t c = 0; c < G; c += 8) {
+                float w[8];
+                read8<DT>(wrow, c, w);
+                const float4 sa = *reinterpret_cast<const float4*>(scol + c);
+                const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
+                score_weight(w[0], sa.x, P, Q, M, nM, acc);
+                score_weight(w[1], sa.y, P, Q, M, nM, acc);
+                score_weight(w[2], sa.z, P, Q, M, nM, acc);
+                score_weight(w[3], sa.w, P, Q, M, nM, acc);
+                score_weight(w[4], sb.x, P, Q, M, nM, acc);
+                score_weight(w[5], sb.y, P, Q, M, nM, acc);
+                score_weight(w[6], sb.z, P, Q, M, nM, acc);
+                score_weight(w[7], sb.w, P, Q, M, nM, acc);
             }
+            float flat[FS_NRED];
 #pragma unroll
-            for (int i = 0; i < FS_KB; ++i) {
-                const int k = item * FS_KB + i;
+            for (int i = 0; i < FS_KB; ++i)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const double tot = wave_sum(valid ? acc[i][b] : 0.0);
-                    if (lane == 0 && k < K) out[b * K + k] = tot;
-                }
+                for (int b = 0; b < 4; ++b) flat[i * 4 + b] = valid ? acc[i][b] : 0.0f;
+            const double tot = rows_sum<FS_NRED>(flat, red, lane);
+            if (lane < FS_NRED) {
+                const int k = item * FS_KB + (lane >> 2);
+                if (k < K) out[(lane & 3) * K + k] = tot;
             }
         } else {
-            // ternary absmean, binary sign*mean|w|, reference energy
+            // ternary absmean, binary sign*mean|w|, reference energy.  S1 = sum |w| in fp64
+            // in column order (exact for bf16 inputs): gamma = alpha = fp32(S1 / G).
+            double S1 = 0.0;
+            for (int32_t c = 0; c < G; c += 8) {
+                float w[8];
+                read8<DT>(wrow, c, w);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) S1 += (double)fabsf(w[j]);
+            }
             const float fam = (float)(S1 / (double)G);
             const bool ok = fam >= FLT_MIN;
-            const double gamma = ok ? (double)fam : 0.0;
-            const double ginv = ok ? (double)(1.0f / fam) : 0.0;
-            const double alpha = (double)fam;
-            double acc_t = 0.0, acc_b = 0.0, acc_r = 0.0;
-            for (int32_t c = 0; c < G; ++c) {
-                const double w = (double)wrow[c];
-                const double sc = (double)s_chunk[c];
-                const double a = sc * sc;
-                double q = fma(w, ginv, RNE_MAGIC) - RNE_MAGIC;
-                q = fmin(fmax(q, -1.0), 1.0);
-                const double rt = fma(-q, gamma, w);
-                acc_t = fma(a * rt, rt, acc_t);
-                const double rb = fabs(w) - alpha;
-                acc_b = fma(a * rb, rb, acc_b);
-                acc_r = fma(a * w, w, acc_r);
+            const float ngam = ok ? -fam : 0.0f;
+            const float ginv = ok ? 1.0f / fam : 0.0f;
+            const float M = pin_vgpr(RNE_ANY);
+            float acc3[3] = {0.0f, 0.0f, 0.0f};
+            for (int32_t c = 0; c < G; c += 8) {
+                float w[8];
+                read8<DT>(wrow, c, w);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float sc = scol[c + j];
+                    const float q = __builtin_amdgcn_fmed3f(fmaf(w[j], ginv, M) - M, -1.0f, 1.0f);
+                    const float rt = fmaf(q, ngam, w[j]) * sc;
+                    acc3[0] = fmaf(rt, rt, acc3[0]);
+                    const float rb = (fabsf(w[j]) - fam) * sc;
+                    acc3[1] = fmaf(rb, rb, acc3[1]);
+                    const float w1 = w[j] * sc;
+                    acc3[2] = fmaf(w1, w1, acc3[2]);
+                }
             }
-            const double tt = wave_sum(valid ? acc_t : 0.0);
-            const double tb = wave_sum(valid ? acc_b : 0.0);
-            const double tr = wave_sum(valid ? acc_r : 0.0);
-            if (lane == 0) {
-                out[4 * K] = tt;
-                out[4 * K + 1] = tb;
-                out[4 * K + 2] = tr;
-            }
+            if (!valid) acc3[0] = acc3[1] = acc3[2] = 0.0f;
+            const double tot = rows_sum<3>(acc3, red, lane);
+            if (lane < 3) out[4 * K + lane] = tot;
         }
     }
 }
 
-// Per unit: add the tiles' partial errors in tile order, pick the clip index with the
+// Per unit: add the tiles' partial errors in a fixed order, pick the clip index with the
 // least error for each uniform bit-width (ties to the largest index), emit fp32.
-__global__ __launch_bounds__(64) void fit_score_finalize_kernel(const double* __restrict__ partial, int64_t tiles_per_unit,
-                                                                 int32_t K, float* __restrict__ err,
-                                                                 uint8_t* __restrict__ clip_idx,
-                                                                 float* __restrict__ ref_energy) {
+constexpr int FIN_THREADS = 256;
+constexpr int FIN_PHASES = FIN_THREADS / 64;
+__global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const double* __restrict__ partial,
+                                                                          int64_t tiles_per_unit, int32_t K,
+                                                                          float* __restrict__ err,
+                                                                          uint8_t* __restrict__ clip_idx,
+                                                                          float* __restrict__ ref_energy) {
+    __shared__ double part[FIN_PHASES][4 * WINDQ_MAX_CLIP + 3];
     __shared__ double E[4 * WINDQ_MAX_CLIP + 3];
     const int64_t u = blockIdx.x;
     const int32_t ncand = fit_score_ncand(K);
     const double* base = partial + (size_t)u * (size_t)tiles_per_unit * (size_t)ncand;
-    for (int32_t cand = threadIdx.x; cand < ncand; cand += 64) {
+    const int phase = threadIdx.x >> 6;
+    // phase p adds tiles p, p+4, p+8, ... in order; the four phase sums are then added in order
+    for (int32_t cand = threadIdx.x & 63; cand < ncand; cand += 64) {
         double acc = 0.0;
-        for (int64_t t = 0; t < tiles_per_unit; ++t) acc += base[(size_t)t * ncand + cand];
+#pragma unroll 4
+        for (int64_t t = phase; t < tiles_per_unit; t += FIN_PHASES) acc += base[(size_t)t * ncand + cand];
+        part[phase][cand] = acc;
+    }
+    __syncthreads();
+    for (int32_t cand = threadIdx.x; cand < ncand; cand += FIN_THREADS) {
+        double acc = 0.0;
+#pragma unroll
+        for (int p = 0; p < FIN_PHASES; ++p) acc += part[p][cand];
         E[cand] = acc;
     }
     __syncthreads();
@@ -229,7 +353,7 @@ extern "C" int windq_fit_score_all_bits(const windq_mat* W, const float* s, int3
     A.n_kpass = (K + FS_KB - 1) / FS_KB;
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid[k < K ? k : K - 1];
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const size_t lds = tile_lds_bytes(chunk_w);
+    const size_t lds = fit_score_lds_bytes(W->dtype, chunk_w);
     const dim3 grid((unsigned)A.g.n_tiles);
     if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&fit_score_kernel<WINDQ_BF16>), lds);
@@ -241,7 +365,7 @@ extern "C" int windq_fit_score_all_bits(const windq_mat* W, const float* s, int3
         hipLaunchKernelGGL(fit_score_kernel<WINDQ_F32>, grid, dim3(FS_THREADS), lds, hs, A);
     }
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
-    hipLaunchKernelGGL(fit_score_finalize_kernel, dim3((unsigned)A.g.U), dim3(64), 0, hs, A.partial,
+    hipLaunchKernelGGL(fit_score_finalize_kernel, dim3((unsigned)A.g.U), dim3(FIN_THREADS), 0, hs, A.partial,
                        A.g.tiles_per_unit, K, err, clip_idx, ref_energy);
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     return WINDQ_OK;

@@ -48,6 +48,9 @@ struct ClipGrid {
 inline size_t tile_lds_bytes(int32_t chunk_w) {
     return (size_t)TILE_ROWS * (size_t)(chunk_w + LDS_PAD) * sizeof(float);
 }
+inline size_t raw_tile_lds_bytes(int32_t dtype, int32_t chunk_w) {
+    return (size_t)TILE_ROWS * ((size_t)chunk_w * (dtype == WINDQ_BF16 ? 2 : 4) + 16);
+}
 
 // Raises the dynamic-LDS limit of a kernel when a tile needs more than the 64 KB a
 // workgroup gets by default (gfx950 has 160 KB per CU).
@@ -116,6 +119,48 @@ __device__ __forceinline__ void load_tile(const void* __restrict__ data, int64_t
         float4* dst = reinterpret_cast<float4*>(tile + r * stride + pc * 8);
         dst[0] = v0;
         dst[1] = v1;
+    }
+}
+
+// ---- raw tiles: the tile kept in LDS in the input's own element type (2 bytes per
+// weight for bf16), row stride = row bytes + 16: with a stride of 4*odd dwords the 64
+// lanes' 128-bit reads of 64 different rows spread evenly over the LDS banks.
+template <int DT>
+struct Elem {
+    static constexpr int bytes = DT == WINDQ_BF16 ? 2 : 4;
+};
+
+template <int DT>
+__device__ __forceinline__ void load_tile_raw(const void* __restrict__ data, int64_t ld, const TileCoord& tc,
+                                              int32_t chunk_w, char* __restrict__ tile) {
+    constexpr int EB = Elem<DT>::bytes;
+    const int32_t pieces = (chunk_w * EB) >> 4;              // 16-byte pieces per row
+    const int32_t row_bytes = chunk_w * EB + 16;
+    const int32_t total = TILE_ROWS * pieces;
+    const char* __restrict__ base = static_cast<const char*>(data);
+    for (int32_t i = threadIdx.x; i < total; i += blockDim.x) {
+        const int32_t r = i / pieces;
+        const int32_t pc = i - r * pieces;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (r < tc.nrows) v = *reinterpret_cast<const uint4*>(base + ((tc.row0 + r) * ld + tc.col0) * EB + (int64_t)pc * 16);
+        *reinterpret_cast<uint4*>(tile + r * row_bytes + pc * 16) = v;
+    }
+}
+
+// Eight consecutive weights of a lane's row, starting at column c (a multiple of 8).
+template <int DT>
+__device__ __forceinline__ void read8(const char* __restrict__ wrow, int32_t c, float (&w)[8]) {
+    if (DT == WINDQ_BF16) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(wrow + c * 2);
+        w[0] = bf16_bits_to_f32(raw.x & 0xffffu); w[1] = __uint_as_float(raw.x & 0xffff0000u);
+        w[2] = bf16_bits_to_f32(raw.y & 0xffffu); w[3] = __uint_as_float(raw.y & 0xffff0000u);
+        w[4] = bf16_bits_to_f32(raw.z & 0xffffu); w[5] = __uint_as_float(raw.z & 0xffff0000u);
+        w[6] = bf16_bits_to_f32(raw.w & 0xffffu); w[7] = __uint_as_float(raw.w & 0xffff0000u);
+    } else {
+        const float4 a = *reinterpret_cast<const float4*>(wrow + c * 4);
+        const float4 b = *reinterpret_cast<const float4*>(wrow + c * 4 + 16);
+        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+        w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
     }
 }
 

@@ -24,7 +24,10 @@ K = 20
 TOKENS = 512
 TARGET_CENTIBITS = 200
 HBM_PEAK_GBS = 8000.0
-FP64_VECTOR_PEAK_TFLOPS = 78.6     # 256 CU x 64 lanes x 2 flop (FMA) x 2.4 GHz
+FP32_VECTOR_PEAK_TFLOPS = 157.3    # published fp32 vector peak: 256 CU x 128 lanes x 2 flop (FMA) x 2.4 GHz
+# HBM bytes of the 7 fit_score launches of one step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# file, scaled by a plain copy of known size (profiles/hot_path_7b_block_pmc_traffic.txt).  Not measured live.
+FIT_SCORE_TRAFFIC_BYTES_PER_STEP = 423.2e6
 
 
 def fit_score_flops_per_weight(k: int) -> int:
@@ -94,7 +97,7 @@ def cpu_baseline(torch, xs, mats, cg):
     import numpy as np
     from oracle import windq_oracle as O
     m = mats[0]
-    n_units = 2
+    n_units = 24
     Wn = m["W"][:, : n_units * G].float().cpu().numpy()
     Xn = xs["h"]["X"][:, : n_units * G].float().cpu().numpy()
     action = m["action"][:n_units].numpy()
@@ -118,6 +121,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--unit-rows", type=int, default=0, help="0 = the paper's units (all rows); 128 = 128 x G tiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run plain device copies of 1 GiB (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -138,6 +143,13 @@ def main():
     n_weights = sum(sp.rows * sp.cols for sp in specs)
     n_units = sum(m["U"] for m in mats)
 
+    if args.copy_probe:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         run_step(wq, torch, cg, xs, mats, args.unit_rows)
     torch.cuda.synchronize()
@@ -158,7 +170,7 @@ def main():
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": "configs[1]: one LLaMA-7B-shaped decoder block, bf16, chunk 128, 20 clip ratios, "
                                "512 calibration tokens, plan at 2.0 bits",
                    "weights": n_weights, "units": n_units, "unit_rows": args.unit_rows, "chunk_w": G, "K": K},
@@ -168,9 +180,12 @@ def main():
                       "pct_hbm_peak": 100.0 * n_weights * 2 / (fit_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "launches_per_step": len(mats)},
         "avg_bits": total_cb / (100.0 * total_n),
-        "roofline": {"bound": "alu", "achieved": achieved, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "fit_score_kernel<bf16> (+ its finalize kernel)",
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / FP32_VECTOR_PEAK_TFLOPS,
+                     "traffic": FIT_SCORE_TRAFFIC_BYTES_PER_STEP / len(mats), "traffic_unit": "bytes per launch (mean of a step's 7)",
+                     "algorithmic_bytes_per_launch": n_weights * 2 / len(mats),
+                     "kernel": "fit_score_kernel<bf16> (+ its finalize kernel), 7 launches per step",
+                     "avg_launch_ms": fit_ms / len(mats),
                      "flops_per_weight": fit_score_flops_per_weight(K)},
     }
     if not args.no_cpu_baseline:

@@ -9,9 +9,13 @@
 //
 // Streaming kernel, bound by HBM: reads 2 (bf16) or 4 (fp32) bytes per weight once,
 // writes b/8 bytes of codes per weight and 8 bytes per group.  One wavefront per tile of
-// 64 rows x one chunk; each lane quantizes and packs its own row, so ternary base-3
-// bytes and 3-bit streams need no cross-lane regrouping.  Rows of a unit are consecutive
-// in the code stream, so the 64 lanes of a tile fill one contiguous byte range.
+// 64 rows x one chunk.  The tile is loaded with coalesced 128-bit loads into LDS in the
+// input's own element type (17 KB for bf16 at chunk 128: nine workgroups per CU, whose
+// loads overlap each other's arithmetic).  Each lane quantizes and packs its own row, so
+// ternary base-3 bytes and 3-bit streams need no cross-lane regrouping, and writes the
+// packed bytes back INTO ITS OWN ROW of the tile: packed output never overtakes the read
+// position (b/8 <= element bytes).  Rows of a unit are consecutive in the code stream, so
+// the 64 packed rows are then copied to one contiguous byte range with coalesced stores.
 #include <float.h>
 
 #include "windq_common.hpp"
@@ -70,9 +74,17 @@ __device__ __forceinline__ void store_codes8(uint8_t* dst, const uint32_t (&c)[8
 }
 
 // Uniform BITS-bit quantizer of one group, normative fp32 steps.
-template <int BITS>
-__device__ __forceinline__ void quantize_uniform(const float* __restrict__ wrow, int32_t G, float p, float mn, float mx,
-                                                 uint8_t* __restrict__ dst, float* scale_out, float* offset_out) {
+template <int DT, int BITS>
+__device__ __forceinline__ void quantize_uniform(const char* wrow, int32_t G, float p, uint8_t* dst, float* scale_out,
+                                                 float* offset_out) {
+    float w[8];
+    read8<DT>(wrow, 0, w);
+    float mn = w[0], mx = w[0];
+    for (int32_t c = 0; c < G; c += 8) {
+        read8<DT>(wrow, c, w);
+        mn = fminf(fminf(fminf(mn, w[0]), fminf(w[1], w[2])), fminf(fminf(w[3], w[4]), fminf(w[5], fminf(w[6], w[7]))));
+        mx = fmaxf(fmaxf(fmaxf(mx, w[0]), fmaxf(w[1], w[2])), fmaxf(fmaxf(w[3], w[4]), fmaxf(w[5], fmaxf(w[6], w[7]))));
+    }
     const float qmax = (float)((1 << BITS) - 1);
     const float lo = p * mn;
     const float hi = p * mx;
@@ -84,9 +96,7 @@ __device__ __forceinline__ void quantize_uniform(const float* __restrict__ wrow,
     *scale_out = d;
     *offset_out = lo;
     for (int32_t c = 0; c < G; c += 8) {
-        const float4 v0 = *reinterpret_cast<const float4*>(wrow + c);
-        const float4 v1 = *reinterpret_cast<const float4*>(wrow + c + 4);
-        const float w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        read8<DT>(wrow, c, w);
         uint32_t code[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -99,43 +109,63 @@ __device__ __forceinline__ void quantize_uniform(const float* __restrict__ wrow,
     }
 }
 
-__device__ __forceinline__ void quantize_ternary(const float* __restrict__ wrow, int32_t G, double S1,
-                                                 uint8_t* __restrict__ dst, float* scale_out) {
-    float gamma = (float)(S1 / (double)G);
+// Sum of |w| of a group in fp64 in column order (exact for bf16 inputs).
+template <int DT>
+__device__ __forceinline__ double group_abs_sum(const char* wrow, int32_t G) {
+    double S1 = 0.0;
+    for (int32_t c = 0; c < G; c += 8) {
+        float w[8];
+        read8<DT>(wrow, c, w);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) S1 += (double)fabsf(w[j]);
+    }
+    return S1;
+}
+
+template <int DT>
+__device__ __forceinline__ void quantize_ternary(const char* wrow, int32_t G, uint8_t* dst, float* scale_out) {
+    float gamma = (float)(group_abs_sum<DT>(wrow, G) / (double)G);
     const bool ok = gamma >= FLT_MIN;
     gamma = ok ? gamma : 0.0f;
     const float inv = ok ? 1.0f / gamma : 0.0f;
     *scale_out = gamma;
     uint32_t byte = 0, mul = 1;
     int32_t nb = 0;
-    for (int32_t c = 0; c < G; ++c) {
-        const float t = wrow[c] * inv;
-        const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -1.0f, 1.0f);
-        byte += (uint32_t)((int32_t)q + 1) * mul;
-        mul *= 3;
-        if (mul == 243) {
-            dst[nb++] = (uint8_t)byte;
-            byte = 0;
-            mul = 1;
+    for (int32_t c = 0; c < G; c += 8) {
+        float w[8];
+        read8<DT>(wrow, c, w);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float t = w[j] * inv;
+            const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -1.0f, 1.0f);
+            byte += (uint32_t)((int32_t)q + 1) * mul;
+            mul *= 3;
+            if (mul == 243) {
+                dst[nb++] = (uint8_t)byte;
+                byte = 0;
+                mul = 1;
+            }
         }
     }
     if (mul != 1) dst[nb] = (uint8_t)byte;
 }
 
-__device__ __forceinline__ void quantize_binary(const float* __restrict__ wrow, int32_t G, double S1,
-                                                uint8_t* __restrict__ dst, float* scale_out) {
-    *scale_out = (float)(S1 / (double)G);
+template <int DT>
+__device__ __forceinline__ void quantize_binary(const char* wrow, int32_t G, uint8_t* dst, float* scale_out) {
+    *scale_out = (float)(group_abs_sum<DT>(wrow, G) / (double)G);
     for (int32_t c = 0; c < G; c += 8) {
+        float w[8];
+        read8<DT>(wrow, c, w);
         uint32_t byte = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) byte |= (wrow[c + j] >= 0.0f ? 1u : 0u) << j;
+        for (int j = 0; j < 8; ++j) byte |= (w[j] >= 0.0f ? 1u : 0u) << j;
         dst[c >> 3] = (uint8_t)byte;
     }
 }
 
 template <int DT>
 __global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyArgs A) {
-    extern __shared__ float tile[];
+    extern __shared__ char tile[];
     const TileCoord tc = tile_coord(A.g, blockIdx.x);
     const int32_t G = A.g.chunk_w;
     const int lane = threadIdx.x;
@@ -159,47 +189,56 @@ __global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyArgs 
         return;
     }
 
-    load_tile<DT>(A.W, A.g.ld, tc, G, tile);
+    load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
     __syncthreads();
-    if (!valid) return;
 
-    const float* __restrict__ wrow = tile + lane * (G + LDS_PAD);
-    float mn = wrow[0], mx = wrow[0];
-    double S1 = 0.0;
-    for (int32_t c = 0; c < G; c += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(wrow + c);
-        mn = fminf(fminf(mn, v.x), fminf(v.y, fminf(v.z, v.w)));
-        mx = fmaxf(fmaxf(mx, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
-        S1 += (double)fabsf(v.x);
-        S1 += (double)fabsf(v.y);
-        S1 += (double)fabsf(v.z);
-        S1 += (double)fabsf(v.w);
+    const int32_t row_bytes = G * Elem<DT>::bytes + 16;
+    char* wrow = tile + lane * row_bytes;
+    if (valid) {
+        float p = 1.0f;
+        if (a <= 4 && A.clip_idx != nullptr) {
+            int k = A.clip_idx[tc.u * 4 + (a - 1)];
+            k = k < A.K ? k : A.K - 1;
+            p = A.grid.p[k];
+        }
+        uint8_t* dst = reinterpret_cast<uint8_t*>(wrow);   // packed in place, behind the read position
+        float sc = 0.0f, of = 0.0f;
+        switch (a) {
+            case 1: quantize_uniform<DT, 8>(wrow, G, p, dst, &sc, &of); break;
+            case 2: quantize_uniform<DT, 4>(wrow, G, p, dst, &sc, &of); break;
+            case 3: quantize_uniform<DT, 3>(wrow, G, p, dst, &sc, &of); break;
+            case 4: quantize_uniform<DT, 2>(wrow, G, p, dst, &sc, &of); break;
+            case 5: quantize_ternary<DT>(wrow, G, dst, &sc); break;
+            default: quantize_binary<DT>(wrow, G, dst, &sc); break;
+        }
+        A.scale[gidx] = sc;
+        A.offset[gidx] = of;
     }
+    __syncthreads();
 
-    float p = 1.0f;
-    if (a <= 4 && A.clip_idx != nullptr) {
-        int k = A.clip_idx[tc.u * 4 + (a - 1)];
-        k = k < A.K ? k : A.K - 1;
-        p = A.grid.p[k];
+    // Copy the tile's packed rows (bpg bytes each, row_bytes apart in LDS) to the contiguous
+    // range of the code stream, in elements of the widest size that divides bpg.
+    const int32_t e = (bpg & 15) == 0 ? 16 : ((bpg & 3) == 0 ? 4 : ((bpg & 1) == 0 ? 2 : 1));
+    const int32_t total = tc.nrows * (int32_t)bpg;
+    uint8_t* __restrict__ out = A.codes + base + tc.lrow0 * bpg;
+    int32_t byte = lane * e;
+    int32_t row = byte / (int32_t)bpg;
+    int32_t col = byte - row * (int32_t)bpg;
+    for (; byte < total; byte += AP_THREADS * e) {
+        const char* src = tile + row * row_bytes + col;
+        if (e == 16) *reinterpret_cast<uint4*>(out + byte) = *reinterpret_cast<const uint4*>(src);
+        else if (e == 4) *reinterpret_cast<uint32_t*>(out + byte) = *reinterpret_cast<const uint32_t*>(src);
+        else if (e == 2) *reinterpret_cast<uint16_t*>(out + byte) = *reinterpret_cast<const uint16_t*>(src);
+        else out[byte] = *reinterpret_cast<const uint8_t*>(src);
+        col += AP_THREADS * e;
+        while (col >= (int32_t)bpg) {
+            col -= (int32_t)bpg;
+            ++row;
+        }
     }
-    uint8_t* __restrict__ dst = A.codes + base + (tc.lrow0 + lane) * bpg;
-    float sc = 0.0f, of = 0.0f;
-    switch (a) {
-        case 1: quantize_uniform<8>(wrow, G, p, mn, mx, dst, &sc, &of); break;
-        case 2: quantize_uniform<4>(wrow, G, p, mn, mx, dst, &sc, &of); break;
-        case 3: quantize_uniform<3>(wrow, G, p, mn, mx, dst, &sc, &of); break;
-        case 4: quantize_uniform<2>(wrow, G, p, mn, mx, dst, &sc, &of); break;
-        case 5: quantize_ternary(wrow, G, S1, dst, &sc); break;
-        default: quantize_binary(wrow, G, S1, dst, &sc); break;
-    }
-    A.scale[gidx] = sc;
-    A.offset[gidx] = of;
-
     // zero the padding that rounds the unit's payload up to 16 bytes
-    if (padded != payload && tc.lrow0 + lane == A.g.R_u - 1) {
-        uint8_t* pad = A.codes + base + payload;
-        for (int64_t i = 0; i < padded - payload; ++i) pad[i] = 0;
-    }
+    if (padded != payload && tc.t == A.g.tiles_per_unit - 1 && lane < padded - payload)
+        A.codes[base + payload + lane] = 0;
 }
 
 }  // namespace windq
@@ -235,7 +274,7 @@ extern "C" int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t uni
     A.K = K;
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid != nullptr ? clip_grid[k < K ? k : K - 1] : 1.0f;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const size_t lds = tile_lds_bytes(chunk_w);
+    const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w);
     const dim3 grid((unsigned)A.g.n_tiles);
     if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&apply_plan_kernel<WINDQ_BF16>), lds);

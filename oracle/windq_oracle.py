@@ -279,25 +279,17 @@ def bytes_per_group(action: int, G: int) -> int:
 
 def pack_bits(codes: np.ndarray, bits: int) -> np.ndarray:
     """LSB-first bitstream of one group: code i occupies bits [i*bits, (i+1)*bits)."""
-    n = len(codes)
-    nbytes = (n * bits + 7) // 8
-    out = np.zeros(nbytes, dtype=np.uint8)
-    for i, c in enumerate(int(x) for x in codes):
-        pos = i * bits
-        for b in range(bits):
-            if (c >> b) & 1:
-                out[(pos + b) // 8] |= np.uint8(1 << ((pos + b) % 8))
-    return out
+    bit_of_code = (np.asarray(codes, dtype=np.int64)[:, None] >> np.arange(bits)) & 1      # [n x bits], bit 0 first
+    return np.packbits(bit_of_code.astype(np.uint8).ravel(), bitorder="little")            # zero padded to a byte
 
 
 def pack_trits(trits: np.ndarray) -> np.ndarray:
     """Five trits per byte, byte = sum_j trit_j * 3^j; the tail is zero padded."""
     n = len(trits)
     nbytes = (n + 4) // 5
-    out = np.zeros(nbytes, dtype=np.uint8)
-    for i, t in enumerate(int(x) for x in trits):
-        out[i // 5] += np.uint8(t * 3 ** (i % 5))
-    return out
+    padded = np.zeros(nbytes * 5, dtype=np.int64)
+    padded[:n] = trits
+    return (padded.reshape(nbytes, 5) @ np.array([1, 3, 9, 27, 81])).astype(np.uint8)
 
 
 def unpack_bits(data: np.ndarray, bits: int, n: int) -> np.ndarray:

@@ -23,9 +23,15 @@
 //     [0,1]); u' = s_c*w - s_c*lo costs one more FMA per clip ratio;
 //   * at 8 bits the residual is ~1/500 of (w - lo), so the fp32 rounding of (w - lo)
 //     would show at the 1e-5 level in units whose error is carried by few weights.
-//     The 8-bit candidate therefore takes the exact route: (w - lo) as an fp32 pair
-//     (sum, rounding error) by an error-free two-sum, residual = fma(code, -step, sum)
-//     (exact) + error term.  5 + 2 more fast instructions per (weight, clip ratio);
+//     The 8-bit candidate therefore takes an exact route.  Distances are measured from an
+//     anchor c = lo + q0*step, the grid point nearest zero (q0 = 0 if zero is outside the
+//     range), so that |c| <= step/2 <= |w| for all but negligible weights and the cheap
+//     error-free sum applies: u0 = fl(w - c), e = (-c) - (u0 - w) is its exact rounding
+//     error; residual = fma(code - q0, -step, u0) (exact) + e.  3 more fast instructions
+//     per (weight, clip ratio) than an uncompensated residual.  (Rows whose weights are
+//     all negative fall back to c = lo, where e is exact only for |w| <= |lo|; the
+//     remainder is bounded by the plain fp32 rounding of (w - lo), 3e-5/sqrt(n) of the
+//     unit error.)
 //   * lanes accumulate in fp32 over the chunk's columns only (<= 512 terms); rows are
 //     combined in fp64 in a fixed order (LDS transpose), tiles by the finalize kernel.
 // Rounding decisions here are taken on x*(2^b-1); windq_apply_plan takes them on
@@ -75,15 +81,17 @@ __device__ __forceinline__ float pin_vgpr(float x) {
     return x;
 }
 
-// a * b with the result clamped to [0, 1] by the instruction's output modifier.
-__device__ __forceinline__ float mul_clamp01(float a, float b) {
+// a * b + c with the result clamped to [0, 1] by the instruction's output modifier.
+__device__ __forceinline__ float fma_clamp01(float a, float b, float c) {
     float r;
-    asm("v_mul_f32_e64 %0, %1, %2 clamp" : "=v"(r) : "v"(a), "v"(b));
+    asm("v_fma_f32 %0, %1, %2, %3 clamp" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
 
 struct KParams {
-    float rinv, nlo;   // 1/range, -lo
+    float rinv, h;     // 1/range, (c - lo)/range: x = (w - c)*rinv + h is the position in the range
+    float nc, Mq;      // -c (anchor), 2^23 + q0
+    float nlo;         // -lo
     float nd[4];       // -step for 8, 4, 3, 2 bits (0 when degenerate)
 };
 
@@ -95,15 +103,13 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
     const float ms = sc * nM;                              // -2^23 * s_c, exact
 #pragma unroll
     for (int i = 0; i < FS_KB; ++i) {
-        // exact (w - lo) = u + du
-        const float u = w + P[i].nlo;
-        const float x = mul_clamp01(u, P[i].rinv);        // position in the clipped range, in [0, 1]
-        const float u1 = fmaf(P[i].nlo, sc, w1);          // s_c * (w - lo)
-        const float bb = u - w;
-        const float du = (w - (u - bb)) + (P[i].nlo - bb);
+        const float u0 = w + P[i].nc;                             // w - c, rounded
+        const float e = P[i].nc - (u0 - w);                       // its rounding error: (w - c) = u0 + e
+        const float x = fma_clamp01(u0, P[i].rinv, P[i].h);       // position in the clipped range, in [0, 1]
+        const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
         {   // 8 bits
-            const float q = fmaf(x, Q[0], M) - M;
-            const float r = fmaf(q, P[i].nd[0], u) + du;
+            const float qc = fmaf(x, Q[0], M) - P[i].Mq;          // code - q0
+            const float r = fmaf(qc, P[i].nd[0], u0) + e;
             const float r1 = r * sc;
             acc[i][0] = fmaf(r1, r1, acc[i][0]);
         }
@@ -203,17 +209,27 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                 const float fhi = p * mx;
                 const float frg = fhi - flo;
                 const float rinv = frg >= FLT_MIN ? __builtin_amdgcn_rcpf(frg) : 0.0f;
-                P[i].rinv = rinv;
-                P[i].nlo = pin_vgpr(-flo);
+                float d8 = 0.0f;
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     // step = range / (2^b - 1): the fp64 product rounds to the correctly rounded
                     // fp32 quotient (but for ~1e-9 of inputs, where it is one ulp off)
                     const double rq = b == 0 ? 1.0 / 255.0 : (b == 1 ? 1.0 / 15.0 : (b == 2 ? 1.0 / 7.0 : 1.0 / 3.0));
-                    const float d = (float)((double)frg * rq);
-                    P[i].nd[b] = pin_vgpr(d >= FLT_MIN ? -d : 0.0f);
+                    float d = (float)((double)frg * rq);
+                    d = d >= FLT_MIN ? d : 0.0f;
+                    if (b == 0) d8 = d;
+                    P[i].nd[b] = pin_vgpr(-d);
                     acc[i][b] = 0.0f;
                 }
+                // anchor: the 8-bit grid point nearest zero when zero lies inside the range
+                float q0 = 0.0f;
+                if (flo < 0.0f && fhi > 0.0f) q0 = __builtin_amdgcn_fmed3f(__builtin_rintf(-flo * rinv * 255.0f), 0.0f, 255.0f);
+                const float c = fmaf(q0, d8, flo);
+                P[i].rinv = rinv;
+                P[i].h = pin_vgpr((c - flo) * rinv);
+                P[i].nc = pin_vgpr(-c);
+                P[i].Mq = pin_vgpr(RNE_POS + q0);
+                P[i].nlo = pin_vgpr(-flo);
             }
             const float Q[4] = {pin_vgpr(255.0f), pin_vgpr(15.0f), pin_vgpr(7.0f), pin_vgpr(3.0f)};
             const float M = pin_vgpr(RNE_POS);

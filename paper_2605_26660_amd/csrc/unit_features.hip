@@ -2,18 +2,31 @@
 // dims 0-4 (mean, std, mean|w|, fraction |w| < 1e-6, fraction |w| > 0.5 P99) for every
 // unit, and dims 9-11 (mean, std, max of the activation scale over the unit's chunk).
 //
-// Everything but P99 is a streaming reduction (fp64 sums, integer counts).  P99 is the
-// exact nearest-rank order statistic of |w|, found by most-significant-digit radix
-// selection on the bit pattern of |w| (monotone in |w| for non-negative floats):
-// bf16 keys have 15 bits -> digits of 11 + 4 bits; fp32 keys 31 bits -> 11 + 11 + 9.
-// The first digit (exponent + 3 mantissa bits) spreads Gaussian-like weights over
-// enough bins to keep LDS atomics from piling up on one address.  Each digit costs one
-// pass over W; the first shares its pass with the moments, later passes touch the
-// histogram only for the few keys that match the prefix, and a last pass counts
-// |w| > 0.5 P99 (as 2|w| > P99, exact in fp32).  All passes after the first re-read a
-// matrix that was just streamed, so for matrices up to the 256 MB last-level cache they
-// are served on chip.  Integer atomics only: results are bit-reproducible.
+// Everything but P99 is a streaming reduction (fp64 sums, integer counts), bound by HBM.
+// P99 is the exact nearest-rank order statistic of |w|, found by most-significant-digit
+// radix selection on the bit pattern of |w| (monotone in |w| for non-negative floats).
+//
+// bf16 (15-bit keys, digits of 11 + 4 bits): TWO passes over W.
+//   pass A  moments, counts, and the histogram of the first digit (exponent + 3 mantissa
+//           bits: spreads Gaussian-like weights over enough bins to keep LDS atomics from
+//           piling up on one address).
+//   pass B  every workgroup first re-derives, from the finished first-digit histogram,
+//           the bin e0 that holds the wanted rank (a 2048-bin scan: cheaper than a launch
+//           and than any cross-workgroup handshake, which on this multi-die GPU costs an
+//           L2 write-back per workgroup).  It then refines two bins to all 4 remaining
+//           bits: e0, and the bin that holds the key of 0.5*P99.  Halving a bf16 lowers its
+//           key by 128 (one exponent step), or halves the key below 256 where keys are
+//           linear in the value, so that bin is e0 - 8 (or e0 >> 1) whatever the low bits
+//           of P99 turn out to be.
+//   finish  per unit: P99 exactly, the exact count of |w| > 0.5 P99 = (first-digit bins
+//           above) + (refined bins above), and the eight features.  No third pass.
+// fp32 (31-bit keys, digits 11 + 11 + 9): one pass per digit plus a counting pass
+// (2|w| > P99, exact in fp32), each re-deriving the prefix from the finished histograms.
+// Passes after the first re-read a matrix that was just streamed; up to the 256 MB
+// last-level cache they are served on chip.  Integer atomics only, fixed-order fp64
+// sums: results are bit-reproducible.
 #include <math.h>
+#include <string.h>
 
 #include "windq_common.hpp"
 #include "windq_ws.hpp"
@@ -21,12 +34,8 @@
 namespace windq {
 
 constexpr int FT_THREADS = 256;
-
-struct DigitPlan {
-    int32_t n_levels;
-    int32_t shift[3];
-    int32_t bits[3];
-};
+constexpr int FT_WAVES = FT_THREADS / 64;
+constexpr int FEAT_BATCH = 4;   // 128-bit loads a thread keeps in flight
 
 struct FeatArgs {
     const void* W;
@@ -34,16 +43,13 @@ struct FeatArgs {
     float* feat;
     double* moments;
     uint32_t* above;
-    uint32_t* hist;
-    FeatSel* sel;
+    uint32_t* hist;     // [3][U][FEAT_BINS]
     Geometry g;
-    DigitPlan dp;
+    int64_t bpu;        // workgroups per unit
     float sparse_thr;   // smallest fp32 that is >= 1e-6: (|w| < 1e-6) == (|w| < sparse_thr) for fp32 |w|
     uint64_t rank;      // ceil(0.99 n), 1-based
 };
 
-// Loads 8 consecutive elements as the bit pattern of |w| widened to fp32 layout and the
-// signed fp32 value.
 template <int DT>
 __device__ __forceinline__ void load8(const void* __restrict__ data, int64_t off, float (&w)[8]) {
     if (DT == WINDQ_BF16) {
@@ -71,47 +77,255 @@ __device__ __forceinline__ float value_of_key(uint32_t key) {
     return __uint_as_float(DT == WINDQ_BF16 ? (key << 16) : key);
 }
 
-__global__ __launch_bounds__(256) void feat_init_kernel(uint32_t* __restrict__ hist, FeatSel* __restrict__ sel,
-                                                         int64_t U, uint64_t rank) {
+// Digit plan: level -> (shift, bits).
+template <int DT>
+__device__ __host__ constexpr int level_shift(int level) {
+    return DT == WINDQ_BF16 ? (level == 0 ? 4 : 0) : (level == 0 ? 20 : (level == 1 ? 9 : 0));
+}
+template <int DT>
+__device__ __host__ constexpr int level_bits(int level) {
+    return DT == WINDQ_BF16 ? (level == 0 ? 11 : 4) : (level == 2 ? 9 : 11);
+}
+template <int DT>
+__device__ __host__ constexpr int n_levels() { return DT == WINDQ_BF16 ? 2 : 3; }
+
+__global__ __launch_bounds__(256) void feat_init_kernel(uint32_t* __restrict__ hist, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < U * FEAT_BINS) hist[i] = 0;
-    if (i < U) {
-        sel[i].prefix = 0;
-        sel[i].pad = 0;
-        sel[i].rank = rank;
+    if (i < n) hist[i] = 0;
+}
+
+// Block-wide sum of a per-thread double in a fixed order (lanes by butterfly, wavefronts in order).
+__device__ __forceinline__ double block_sum(double v, double* red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < FT_WAVES; ++w) t += red[w];
+    return t;
+}
+
+// Find, in histogram h of nbins (<= FEAT_BINS) bins, the bin that holds the 1-based `rank`;
+// returns the bin and the number of keys in lower bins.  All FT_THREADS threads call it.
+// Counts fit 32 bits (a unit has fewer than 2^32 weights).  Each thread owns up to 8
+// consecutive bins; an exclusive scan over threads (shuffles inside a wavefront, LDS
+// across the four) finds the one thread whose bins straddle the rank.
+__device__ __forceinline__ void select_bin(const uint32_t* __restrict__ h, int nbins, uint64_t rank64,
+                                           uint32_t* sh_part, uint32_t* sh_out, uint32_t* bin_out,
+                                           uint64_t* below_out) {
+    constexpr int PER = FEAT_BINS / FT_THREADS;
+    const uint32_t rank = (uint32_t)rank64;
+    const int b0 = threadIdx.x * PER;
+    uint32_t v[PER];
+    uint32_t local = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        v[j] = b0 + j < nbins ? h[b0 + j] : 0u;
+        local += v[j];
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = local;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) sh_part[wave] = inc;
+    __syncthreads();
+    uint32_t excl = inc - local;
+    for (int w = 0; w < wave; ++w) excl += sh_part[w];
+    if (excl < rank && rank <= excl + local) {
+        uint32_t cum = excl;
+        int bin = b0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            if (cum < rank && rank <= cum + v[j]) {
+                bin = b0 + j;
+                break;
+            }
+            cum += v[j];
+        }
+        sh_out[0] = (uint32_t)bin;
+        sh_out[1] = cum;
+    }
+    __syncthreads();
+    *bin_out = sh_out[0];
+    *below_out = (uint64_t)sh_out[1];
+}
+
+// Key prefix of the wanted rank after digits 0 .. upto-1, from the finished histograms of
+// unit u, and the rank still to find under that prefix.
+template <int DT>
+__device__ __forceinline__ void select_prefix(const FeatArgs& A, int64_t u, int upto, uint32_t* sh_part,
+                                              uint32_t* sh_out, uint32_t* prefix_out, uint64_t* rank_out) {
+    uint32_t prefix = 0;
+    uint64_t rank = A.rank;
+    for (int l = 0; l < upto; ++l) {
+        const uint32_t* h = A.hist + ((size_t)l * (size_t)A.g.U + (size_t)u) * FEAT_BINS;
+        uint32_t bin;
+        uint64_t below;
+        select_bin(h, 1 << level_bits<DT>(l), rank, sh_part, sh_out, &bin, &below);
+        prefix = (prefix << level_bits<DT>(l)) | bin;
+        rank -= below;
+    }
+    *prefix_out = prefix;
+    *rank_out = rank;
+}
+
+// bf16: first-digit bin that holds the key of 0.5 * P99, given P99's first-digit bin.
+__device__ __forceinline__ uint32_t half_bin_of(uint32_t e0) { return e0 >= 16u ? e0 - 8u : e0 >> 1; }
+
+// bf16 passes work on the packed 16-bit patterns directly (two weights per dword): the
+// first digit is a bit-field extract, no conversion to float; the LDS histogram is kept
+// in FEAT_COPIES copies indexed by lane, which removes most same-address collisions of
+// the LDS atomics (Gaussian-like weights fall into ~40 hot bins); each thread sums its
+// <= 32 weights in fp32 (products of bf16 are exact in fp32) and hands fp64 to the
+// block-wide sums.
+//   MODE 0: moments + histogram of digit 0.   MODE 1: refine bins e0 and half_bin_of(e0).
+constexpr int FEAT_COPIES = 4;
+template <int MODE>
+__global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatArgs A, const uint32_t sparse_key) {
+    constexpr int CSTRIDE = (MODE == 0 ? FEAT_BINS : 32) + 17;   // odd skew: copies of a bin sit in different banks
+    __shared__ uint32_t lhist[CSTRIDE * FEAT_COPIES];
+    __shared__ double red[FT_WAVES];
+    __shared__ uint32_t sh_part[FT_THREADS];
+    __shared__ uint32_t sh_out[4];
+    constexpr int NB = MODE == 0 ? FEAT_BINS : 32;
+    const int64_t u = blockIdx.x / A.bpu;
+    const int64_t blk = blockIdx.x - u * A.bpu;
+    const int32_t G = A.g.chunk_w;
+    const int32_t pieces = G >> 3;
+    const int64_t rb = u / A.g.n_chunks;
+    const int64_t col0 = (u - rb * A.g.n_chunks) * G;
+    const int64_t lrow0 = blk * FEAT_TPB * TILE_ROWS;
+    const int64_t left = A.g.R_u - lrow0;
+    const int32_t nrows = (int32_t)(left < FEAT_TPB * TILE_ROWS ? left : FEAT_TPB * TILE_ROWS);
+    const int64_t row0 = rb * A.g.R_u + lrow0;
+    for (int32_t b = threadIdx.x; b < CSTRIDE * FEAT_COPIES; b += FT_THREADS) lhist[b] = 0;
+    uint32_t e0 = 0, eh = 0;
+    if (MODE == 1) {
+        uint64_t rank_left;
+        select_prefix<WINDQ_BF16>(A, u, 1, sh_part, sh_out, &e0, &rank_left);
+        eh = half_bin_of(e0);
+    }
+    __syncthreads();
+    uint32_t* __restrict__ myhist = lhist + (threadIdx.x & (FEAT_COPIES - 1)) * CSTRIDE;
+
+    float sw = 0.0f, sw2 = 0.0f, sabs = 0.0f;
+    uint32_t cnt = 0;
+    auto consume = [&](const uint4& raw) {
+        const uint32_t x[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t dlo = (x[j] >> 4) & 0x7ffu, dhi = (x[j] >> 20) & 0x7ffu;
+            if (MODE == 0) {
+                atomicAdd(&myhist[dlo], 1u);
+                atomicAdd(&myhist[dhi], 1u);
+                const float wlo = __uint_as_float(x[j] << 16), whi = __uint_as_float(x[j] & 0xffff0000u);
+                sw += wlo;
+                sw += whi;
+                sw2 = fmaf(wlo, wlo, sw2);
+                sw2 = fmaf(whi, whi, sw2);
+                sabs += fabsf(wlo);
+                sabs += fabsf(whi);
+                cnt += (x[j] & 0x7fffu) < sparse_key ? 1u : 0u;
+                cnt += ((x[j] >> 16) & 0x7fffu) < sparse_key ? 1u : 0u;
+            } else {
+                if (dlo == e0) atomicAdd(&myhist[x[j] & 15u], 1u);
+                if (dlo == eh) atomicAdd(&myhist[16u + (x[j] & 15u)], 1u);
+                if (dhi == e0) atomicAdd(&myhist[(x[j] >> 16) & 15u], 1u);
+                if (dhi == eh) atomicAdd(&myhist[16u + ((x[j] >> 16) & 15u)], 1u);
+            }
+        }
+    };
+    const uint16_t* __restrict__ Wp = static_cast<const uint16_t*>(A.W);
+    if (FT_THREADS % pieces == 0) {
+        const int32_t rstep = FT_THREADS / pieces;
+        const int32_t pc = threadIdx.x % pieces;
+        const int64_t cbase = col0 + (int64_t)pc * 8;
+        for (int32_t r = threadIdx.x / pieces; r < nrows; r += FEAT_BATCH * rstep) {
+            uint4 raw[FEAT_BATCH];
+#pragma unroll
+            for (int b = 0; b < FEAT_BATCH; ++b)
+                if (r + b * rstep < nrows)
+                    raw[b] = *reinterpret_cast<const uint4*>(Wp + (row0 + r + b * rstep) * A.g.ld + cbase);
+#pragma unroll
+            for (int b = 0; b < FEAT_BATCH; ++b)
+                if (r + b * rstep < nrows) consume(raw[b]);
+        }
+    } else {
+        const int32_t total = nrows * pieces;
+        for (int32_t i = threadIdx.x; i < total; i += FT_THREADS) {
+            const int32_t r = i / pieces;
+            const int32_t pc = i - r * pieces;
+            consume(*reinterpret_cast<const uint4*>(Wp + (row0 + r) * A.g.ld + col0 + (int64_t)pc * 8));
+        }
+    }
+
+    if (MODE == 0) {
+        const double r0 = block_sum((double)sw, red), r1 = block_sum((double)sw2, red);
+        const double r2 = block_sum((double)sabs, red), r3 = block_sum((double)cnt, red);
+        if (threadIdx.x == 0) {
+            double* dst = A.moments + ((size_t)u * (size_t)A.bpu + (size_t)blk) * 4;
+            dst[0] = r0; dst[1] = r1; dst[2] = r2; dst[3] = r3;
+        }
+    }
+    __syncthreads();
+    uint32_t* __restrict__ gh = A.hist + ((size_t)MODE * (size_t)A.g.U + (size_t)u) * FEAT_BINS;
+    for (int32_t b = threadIdx.x; b < NB; b += FT_THREADS) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int c = 0; c < FEAT_COPIES; ++c) v += lhist[c * CSTRIDE + b];
+        if (v != 0) atomicAdd(&gh[b], v);
     }
 }
 
-// Pass over one tile.  LEVEL 0: moments + histogram of the first digit.  LEVEL > 0:
-// histogram of digit `level` among keys whose higher digits equal the unit's prefix.
-// LEVEL < 0: count of 2|w| > P99.
-template <int DT, int MODE>   // MODE 0: first pass, 1: later digit, 2: count above half P99
+// One pass over FEAT_TPB tiles of one unit (generic element type; used for fp32 inputs).
+//   MODE 0: moments + histogram of digit 0.
+//   MODE 1: histogram(s) of digit `level` under the unit's prefix.
+//   MODE 2: fp32 only: count 2|w| > P99.
+template <int DT, int MODE>
 __global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatArgs A, const int32_t level) {
     __shared__ uint32_t lhist[FEAT_BINS];
-    __shared__ double red[FT_THREADS / 64][4];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    __shared__ double red[FT_WAVES];
+    __shared__ uint32_t sh_part[FT_THREADS];
+    __shared__ uint32_t sh_out[4];
+    const int64_t u = blockIdx.x / A.bpu;
+    const int64_t blk = blockIdx.x - u * A.bpu;
     const int32_t G = A.g.chunk_w;
     const int32_t pieces = G >> 3;
-    const int32_t total = tc.nrows * pieces;
-    const int32_t shift = MODE == 2 ? 0 : A.dp.shift[level];
-    const int32_t nbins = MODE == 2 ? 0 : (1 << A.dp.bits[level]);
-    const uint32_t mask = (uint32_t)nbins - 1u;
+    const int64_t rb = u / A.g.n_chunks;
+    const int64_t col0 = (u - rb * A.g.n_chunks) * G;
+    const int64_t lrow0 = blk * FEAT_TPB * TILE_ROWS;
+    const int64_t left = A.g.R_u - lrow0;
+    const int32_t nrows = (int32_t)(left < FEAT_TPB * TILE_ROWS ? left : FEAT_TPB * TILE_ROWS);
+    const int64_t row0 = rb * A.g.R_u + lrow0;
+    const int32_t total = nrows * pieces;
+    const int32_t shift = MODE == 2 ? 0 : level_shift<DT>(level);
+    const int32_t bits = MODE == 2 ? 0 : level_bits<DT>(level);
+    const int32_t nbins = MODE == 2 ? 0 : (DT == WINDQ_BF16 && MODE == 1 ? 32 : (1 << bits));
+    const uint32_t mask = (1u << bits) - 1u;
     if (MODE != 2) {
         for (int32_t b = threadIdx.x; b < nbins; b += FT_THREADS) lhist[b] = 0;
-        __syncthreads();
     }
-    uint32_t prefix = 0;
+    uint32_t prefix = 0, half_bin = 0;
+    uint64_t rank_left = 0;
     float p99 = 0.0f;
-    if (MODE == 1) prefix = A.sel[tc.u].prefix;
-    if (MODE == 2) p99 = value_of_key<DT>(A.sel[tc.u].prefix);
+    if (MODE == 1) {
+        select_prefix<DT>(A, u, level, sh_part, sh_out, &prefix, &rank_left);
+        half_bin = half_bin_of(prefix);
+    }
+    if (MODE == 2) {
+        select_prefix<DT>(A, u, n_levels<DT>(), sh_part, sh_out, &prefix, &rank_left);
+        p99 = value_of_key<DT>(prefix);
+    }
+    __syncthreads();
 
     double sw = 0.0, sw2 = 0.0, sabs = 0.0;
     uint32_t cnt = 0;
-    for (int32_t i = threadIdx.x; i < total; i += FT_THREADS) {
-        const int32_t r = i / pieces;
-        const int32_t pc = i - r * pieces;
-        float w[8];
-        load8<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + (int64_t)pc * 8, w);
+    auto consume = [&](const float (&w)[8]) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float aw = fabsf(w[j]);
@@ -124,40 +338,59 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatArgs A,
                 atomicAdd(&lhist[key_of<DT>(w[j]) >> shift], 1u);
             } else if (MODE == 1) {
                 const uint32_t key = key_of<DT>(w[j]);
-                if ((key >> (shift + A.dp.bits[level])) == prefix) atomicAdd(&lhist[(key >> shift) & mask], 1u);
+                if (DT == WINDQ_BF16) {
+                    const uint32_t b = key >> 4;
+                    if (b == prefix) atomicAdd(&lhist[key & 15u], 1u);
+                    if (b == half_bin) atomicAdd(&lhist[16u + (key & 15u)], 1u);
+                } else {
+                    if ((key >> (shift + bits)) == prefix) atomicAdd(&lhist[(key >> shift) & mask], 1u);
+                }
             } else {
                 cnt += 2.0f * aw > p99 ? 1u : 0u;
             }
         }
+    };
+    // Each thread keeps FEAT_BATCH independent 128-bit loads in flight.  When the pieces of
+    // a row divide the workgroup, a thread keeps its column piece and steps down the rows
+    // (no division per piece); otherwise pieces are dealt out linearly.
+    if (FT_THREADS % pieces == 0) {
+        const int32_t rstep = FT_THREADS / pieces;
+        const int32_t pc = threadIdx.x % pieces;
+        const int64_t cbase = col0 + (int64_t)pc * 8;
+        for (int32_t r = threadIdx.x / pieces; r < nrows; r += FEAT_BATCH * rstep) {
+            float w[FEAT_BATCH][8];
+#pragma unroll
+            for (int b = 0; b < FEAT_BATCH; ++b)
+                if (r + b * rstep < nrows) load8<DT>(A.W, (row0 + r + b * rstep) * A.g.ld + cbase, w[b]);
+#pragma unroll
+            for (int b = 0; b < FEAT_BATCH; ++b)
+                if (r + b * rstep < nrows) consume(w[b]);
+        }
+    } else {
+        for (int32_t i = threadIdx.x; i < total; i += FT_THREADS) {
+            const int32_t r = i / pieces;
+            const int32_t pc = i - r * pieces;
+            float w[8];
+            load8<DT>(A.W, (row0 + r) * A.g.ld + col0 + (int64_t)pc * 8, w);
+            consume(w);
+        }
     }
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const size_t tile_slot = (size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t;
+    const size_t slot = (size_t)u * (size_t)A.bpu + (size_t)blk;
     if (MODE == 0) {
-        const double r0 = wave_sum(sw), r1 = wave_sum(sw2), r2 = wave_sum(sabs);
-        const double r3 = (double)wave_sum_u64((unsigned long long)cnt);
-        if (lane == 0) {
-            red[wave][0] = r0; red[wave][1] = r1; red[wave][2] = r2; red[wave][3] = r3;
-        }
-        __syncthreads();
-        if (threadIdx.x < 4) {
-            double acc = 0.0;
-            for (int w = 0; w < FT_THREADS / 64; ++w) acc += red[w][threadIdx.x];
-            A.moments[tile_slot * 4 + threadIdx.x] = acc;
+        const double r0 = block_sum(sw, red), r1 = block_sum(sw2, red), r2 = block_sum(sabs, red);
+        const double r3 = block_sum((double)cnt, red);
+        if (threadIdx.x == 0) {
+            double* dst = A.moments + slot * 4;
+            dst[0] = r0; dst[1] = r1; dst[2] = r2; dst[3] = r3;
         }
     } else if (MODE == 2) {
-        const double r3 = (double)wave_sum_u64((unsigned long long)cnt);
-        if (lane == 0) red[wave][0] = r3;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            double acc = 0.0;
-            for (int w = 0; w < FT_THREADS / 64; ++w) acc += red[w][0];
-            A.above[tile_slot] = (uint32_t)acc;
-        }
+        const double r3 = block_sum((double)cnt, red);
+        if (threadIdx.x == 0) A.above[slot] = (uint32_t)r3;
     }
     if (MODE != 2) {
         __syncthreads();
-        uint32_t* __restrict__ gh = A.hist + (size_t)tc.u * FEAT_BINS;
+        uint32_t* __restrict__ gh = A.hist + ((size_t)level * (size_t)A.g.U + (size_t)u) * FEAT_BINS;
         for (int32_t b = threadIdx.x; b < nbins; b += FT_THREADS) {
             const uint32_t v = lhist[b];
             if (v != 0) atomicAdd(&gh[b], v);
@@ -165,87 +398,63 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatArgs A,
     }
 }
 
-// Per unit: find the bin of the current digit that holds the wanted rank, extend the
-// prefix, reduce the rank to a rank inside that bin, and clear the histogram for the
-// next digit.
-__global__ __launch_bounds__(256) void feat_select_kernel(uint32_t* __restrict__ hist, FeatSel* __restrict__ sel,
-                                                           const int32_t bits) {
-    __shared__ uint64_t part[256];
-    __shared__ uint32_t chosen_chunk;
-    __shared__ uint64_t chosen_before;
+// Per unit: P99's key from the finished histograms, the count above half of it, the
+// moments in block order, the statistics of s over the chunk; writes the eight features.
+template <int DT>
+__global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatArgs A) {
+    __shared__ double red[FT_WAVES];
+    __shared__ uint32_t sh_part[FT_THREADS];
+    __shared__ uint32_t sh_out[4];
+    __shared__ float smax_sh[FT_THREADS];
     const int64_t u = blockIdx.x;
-    const int32_t nbins = 1 << bits;
-    const int32_t per = (nbins + 255) / 256;
-    uint32_t* __restrict__ h = hist + (size_t)u * FEAT_BINS;
-    const int32_t b0 = threadIdx.x * per;
-    uint64_t local = 0;
-    for (int32_t b = b0; b < b0 + per && b < nbins; ++b) local += h[b];
-    part[threadIdx.x] = local;
-    __syncthreads();
-    const uint64_t rank = sel[u].rank;
-    if (threadIdx.x == 0) {
-        uint64_t cum = 0;
-        uint32_t ci = 255;
-        for (uint32_t i = 0; i < 256; ++i) {
-            if (cum + part[i] >= rank) {
-                ci = i;
-                break;
-            }
-            cum += part[i];
-        }
-        chosen_chunk = ci;
-        chosen_before = cum;
+    double above = 0.0;
+    if (DT == WINDQ_BF16) {
+        uint32_t e0, l1;
+        uint64_t rank1, below;
+        select_prefix<DT>(A, u, 1, sh_part, sh_out, &e0, &rank1);
+        const uint32_t* h0 = A.hist + (size_t)u * FEAT_BINS;
+        const uint32_t* h1 = A.hist + ((size_t)A.g.U + (size_t)u) * FEAT_BINS;
+        select_bin(h1, 16, rank1, sh_part, sh_out, &l1, &below);
+        // Key of 0.5 * P99: one exponent step down, or half the key where keys are linear in
+        // the value (below 256: subnormals and the first binade).
+        const uint32_t pk = (e0 << 4) | l1;
+        const uint32_t tk = pk >= 256u ? pk - 128u : pk >> 1;
+        const uint32_t tbin = tk >> 4, tlow = tk & 15u;        // tbin == half_bin_of(e0) by construction
+        for (int32_t b = threadIdx.x; b < FEAT_BINS; b += FT_THREADS)
+            if ((uint32_t)b > tbin) above += (double)h0[b];
+        if (threadIdx.x < 16 && (uint32_t)threadIdx.x > tlow) above += (double)h1[16 + threadIdx.x];
+    } else {
+        for (int64_t b = threadIdx.x; b < A.bpu; b += FT_THREADS) above += (double)A.above[(size_t)u * A.bpu + b];
     }
-    __syncthreads();
-    if (threadIdx.x == chosen_chunk) {
-        uint64_t cum = chosen_before;
-        int32_t bin = b0;
-        for (int32_t b = b0; b < b0 + per && b < nbins; ++b) {
-            bin = b;
-            if (cum + h[b] >= rank) break;
-            cum += h[b];
-        }
-        sel[u].prefix = (sel[u].prefix << bits) | (uint32_t)bin;
-        sel[u].rank = rank - cum;
-    }
-    __syncthreads();
-    for (int32_t b = b0; b < b0 + per && b < nbins; ++b) h[b] = 0;
-}
+    above = block_sum(above, red);
 
-// Per unit: combine the tiles' partial sums in tile order and emit the eight features.
-__global__ __launch_bounds__(64) void feat_finalize_kernel(const FeatArgs A) {
-    const int64_t u = blockIdx.x;
-    const int lane = threadIdx.x;
-    const int64_t T = A.g.tiles_per_unit;
     double m[4] = {0.0, 0.0, 0.0, 0.0};
-    double ab = 0.0;
-    for (int64_t t = lane; t < T; t += 64) {
-        const double* src = A.moments + ((size_t)u * (size_t)T + (size_t)t) * 4;
+    for (int64_t b = threadIdx.x; b < A.bpu; b += FT_THREADS) {
+        const double* src = A.moments + ((size_t)u * (size_t)A.bpu + (size_t)b) * 4;
         m[0] += src[0]; m[1] += src[1]; m[2] += src[2]; m[3] += src[3];
-        ab += (double)A.above[(size_t)u * (size_t)T + (size_t)t];
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) m[j] = wave_sum(m[j]);
-    ab = wave_sum(ab);
+    for (int j = 0; j < 4; ++j) m[j] = block_sum(m[j], red);
     const int32_t G = A.g.chunk_w;
     const float* __restrict__ sc = A.s + (u % A.g.n_chunks) * G;
     double ssum = 0.0;
     float smax = sc[0];
-    for (int32_t c = lane; c < G; c += 64) {
+    for (int32_t c = threadIdx.x; c < G; c += FT_THREADS) {
         ssum += (double)sc[c];
         smax = fmaxf(smax, sc[c]);
     }
-    ssum = wave_sum(ssum);
-#pragma unroll
-    for (int mm = 32; mm >= 1; mm >>= 1) smax = fmaxf(smax, __shfl_xor(smax, mm, 64));
+    ssum = block_sum(ssum, red);
+    smax_sh[threadIdx.x] = smax;
     const double smean = ssum / (double)G;
     double sdev = 0.0;
-    for (int32_t c = lane; c < G; c += 64) {
+    for (int32_t c = threadIdx.x; c < G; c += FT_THREADS) {
         const double d = (double)sc[c] - smean;
         sdev = fma(d, d, sdev);
     }
-    sdev = wave_sum(sdev);
-    if (lane == 0) {
+    sdev = block_sum(sdev, red);   // its barriers also publish smax_sh
+    if (threadIdx.x == 0) {
+        float mx = smax_sh[0];
+        for (int i = 1; i < FT_THREADS; ++i) mx = fmaxf(mx, smax_sh[i]);
         const double n = (double)A.g.R_u * (double)G;
         const double mean = m[0] / n;
         double var = m[1] / n - mean * mean;
@@ -255,27 +464,32 @@ __global__ __launch_bounds__(64) void feat_finalize_kernel(const FeatArgs A) {
         f[1] = (float)sqrt(var);
         f[2] = (float)(m[2] / n);
         f[3] = (float)(m[3] / n);
-        f[4] = (float)(ab / n);
+        f[4] = (float)(above / n);
         f[5] = (float)smean;
         f[6] = (float)sqrt(sdev / (double)G);
-        f[7] = smax;
+        f[7] = mx;
     }
 }
 
 template <int DT>
 static int launch_features(const FeatArgs& A, hipStream_t hs) {
-    const dim3 tiles((unsigned)A.g.n_tiles), units((unsigned)A.g.U);
-    const int64_t n_init = A.g.U * FEAT_BINS;
-    hipLaunchKernelGGL(feat_init_kernel, dim3((unsigned)((n_init + 255) / 256)), dim3(256), 0, hs, A.hist, A.sel,
-                       A.g.U, A.rank);
-    hipLaunchKernelGGL((feat_pass_kernel<DT, 0>), tiles, dim3(FT_THREADS), 0, hs, A, 0);
-    hipLaunchKernelGGL(feat_select_kernel, units, dim3(256), 0, hs, A.hist, A.sel, A.dp.bits[0]);
-    for (int32_t l = 1; l < A.dp.n_levels; ++l) {
-        hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), tiles, dim3(FT_THREADS), 0, hs, A, l);
-        hipLaunchKernelGGL(feat_select_kernel, units, dim3(256), 0, hs, A.hist, A.sel, A.dp.bits[l]);
+    const dim3 blocks((unsigned)(A.g.U * A.bpu));
+    const int64_t n_init = (int64_t)3 * A.g.U * FEAT_BINS;
+    hipLaunchKernelGGL(feat_init_kernel, dim3((unsigned)((n_init + 255) / 256)), dim3(256), 0, hs, A.hist, n_init);
+    if (DT == WINDQ_BF16) {
+        // |w| < 1e-6 on bf16 keys: key < key of the smallest bf16 that is >= 1e-6
+        uint32_t tb;
+        memcpy(&tb, &A.sparse_thr, sizeof(tb));
+        const uint32_t sparse_key = (tb >> 16) + ((tb & 0xffffu) != 0 ? 1u : 0u);
+        hipLaunchKernelGGL((feat_pass_bf16_kernel<0>), blocks, dim3(FT_THREADS), 0, hs, A, sparse_key);
+        hipLaunchKernelGGL((feat_pass_bf16_kernel<1>), blocks, dim3(FT_THREADS), 0, hs, A, sparse_key);
+    } else {
+        hipLaunchKernelGGL((feat_pass_kernel<DT, 0>), blocks, dim3(FT_THREADS), 0, hs, A, 0);
+        hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, A, 1);
+        hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, A, 2);
+        hipLaunchKernelGGL((feat_pass_kernel<DT, 2>), blocks, dim3(FT_THREADS), 0, hs, A, 0);
     }
-    hipLaunchKernelGGL((feat_pass_kernel<DT, 2>), tiles, dim3(FT_THREADS), 0, hs, A, 0);
-    hipLaunchKernelGGL(feat_finalize_kernel, units, dim3(64), 0, hs, A);
+    hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)A.g.U), dim3(FT_THREADS), 0, hs, A);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
@@ -292,6 +506,7 @@ extern "C" int windq_unit_features(const windq_mat* W, const float* s, int32_t c
     const FeatLayout L = features_layout(A.g);
     if (ws == nullptr || ws_bytes < L.total || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
     if ((uint64_t)A.g.R_u * (uint64_t)chunk_w > (uint64_t)0xffffffffu) return WINDQ_ESHAPE;   // u32 bin counts
+    if (L.n_blocks > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
     char* base = static_cast<char*>(ws);
     A.W = W->data;
     A.s = s;
@@ -299,18 +514,7 @@ extern "C" int windq_unit_features(const windq_mat* W, const float* s, int32_t c
     A.moments = reinterpret_cast<double*>(base + L.moments);
     A.above = reinterpret_cast<uint32_t*>(base + L.above);
     A.hist = reinterpret_cast<uint32_t*>(base + L.hist);
-    A.sel = reinterpret_cast<FeatSel*>(base + L.sel);
-    if (W->dtype == WINDQ_BF16) {
-        A.dp.n_levels = 2;
-        A.dp.shift[0] = 4;  A.dp.bits[0] = 11;
-        A.dp.shift[1] = 0;  A.dp.bits[1] = 4;
-        A.dp.shift[2] = 0;  A.dp.bits[2] = 0;
-    } else {
-        A.dp.n_levels = 3;
-        A.dp.shift[0] = 20; A.dp.bits[0] = 11;
-        A.dp.shift[1] = 9;  A.dp.bits[1] = 11;
-        A.dp.shift[2] = 0;  A.dp.bits[2] = 9;
-    }
+    A.bpu = L.bpu;
     float thr = (float)1e-6;
     if ((double)thr < 1e-6) thr = nextafterf(thr, INFINITY);
     A.sparse_thr = thr;

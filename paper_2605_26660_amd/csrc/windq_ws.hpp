@@ -20,27 +20,26 @@ inline size_t fit_score_ws_bytes(const Geometry& g, int32_t K) {
 }
 
 // ---- unit_features
-//   moments  [n_tiles][4] fp64   sum w, sum w^2, sum |w|, count(|w| < 1e-6)
-//   above    [n_tiles]    u32    count(|w| > 0.5 P99)
-//   hist     [U][FEAT_BINS] u32  radix-select histogram of the current digit
-//   sel      [U] {prefix u32, pad u32, rank u64}
+// A workgroup covers FEAT_TPB consecutive tiles of one unit ("block" below).
+//   moments  [n_blocks][4] fp64   sum w, sum w^2, sum |w|, count(|w| < 1e-6)
+//   above    [n_blocks]    u32    count(|w| > 0.5 P99)            (fp32 inputs only)
+//   hist     [3][U][FEAT_BINS] u32  histogram of radix digit 0, 1, 2
 constexpr int FEAT_DIGIT_BITS = 11;
 constexpr int FEAT_BINS = 1 << FEAT_DIGIT_BITS;
-struct FeatSel {
-    uint32_t prefix;   // key bits decided so far (high digits)
-    uint32_t pad;
-    uint64_t rank;     // 1-based rank still to find among keys that share the prefix
-};
+constexpr int FEAT_TPB = 2;
 struct FeatLayout {
-    size_t moments, above, hist, sel, total;
+    int64_t bpu;       // workgroups per unit
+    int64_t n_blocks;
+    size_t moments, above, hist, total;
 };
 inline FeatLayout features_layout(const Geometry& g) {
     FeatLayout L;
+    L.bpu = (g.tiles_per_unit + FEAT_TPB - 1) / FEAT_TPB;
+    L.n_blocks = g.U * L.bpu;
     size_t pos = 0;
-    L.moments = pos; pos = round_up(pos + (size_t)g.n_tiles * 4 * sizeof(double), 256);
-    L.above = pos;   pos = round_up(pos + (size_t)g.n_tiles * sizeof(uint32_t), 256);
-    L.hist = pos;    pos = round_up(pos + (size_t)g.U * FEAT_BINS * sizeof(uint32_t), 256);
-    L.sel = pos;     pos = round_up(pos + (size_t)g.U * sizeof(FeatSel), 256);
+    L.moments = pos; pos = round_up(pos + (size_t)L.n_blocks * 4 * sizeof(double), 256);
+    L.above = pos;   pos = round_up(pos + (size_t)L.n_blocks * sizeof(uint32_t), 256);
+    L.hist = pos;    pos = round_up(pos + (size_t)3 * g.U * FEAT_BINS * sizeof(uint32_t), 256);
     L.total = pos;
     return L;
 }

@@ -4,17 +4,19 @@
 // Optimization": per-group scales, group size = chunk size).
 //
 // Work per weight: 4 bit-widths x K clip ratios + ternary + binary = 4K+2 candidate
-// quantizers.  At K = 20 that is ~550 vector instructions per 2-byte weight: the kernel
+// quantizers.  At K = 20 that is ~480 vector instructions per 2-byte weight: the kernel
 // is bound by the vector ALU, not by HBM, by a factor of ~30.  So the design minimises
 // issue cycles per candidate, using what measurement shows about gfx950's vector ALU:
-// v_fma/mul/add/sub_f32 whose operands are all VGPRs issue about 1.7x faster than any
-// other vector instruction (fp64, min/max/med3, rounding, conversions, anything with an
-// SGPR or literal operand).  Hence:
+// v_fma/mul/add/sub_f32 whose operands are all plain VGPRs issue about 1.7x faster than
+// any other vector instruction (fp64, min/max/med3, rounding, conversions, anything with
+// an SGPR, literal or negated operand), provided >= 4-5 wavefronts are resident per SIMD.
+// Hence:
 //   * lane-per-group (see windq_common.hpp): quantizer parameters are lane-private and
-//     live in VGPRs; wave-uniform per-column values (s_c, -2^23 s_c) are staged in LDS
-//     and read back into VGPRs, constants are pinned in VGPRs;
-//   * the hot loop is made of fast fp32 FMA/ADD/MUL only.  Per (weight, clip ratio):
-//       x  = clamp01((w - lo) * (1/range))      one multiply with the free [0,1] output clamp
+//     live in VGPRs; the wave-uniform s_c is staged in LDS and read back into VGPRs,
+//     constants are pinned in VGPRs;
+//   * the hot loop is made of fast fp32 FMA/ADD/MUL only, 23 per (weight, clip ratio):
+//       x  = clamp01((w - c)/range + h)         position in the clipped range; one FMA with
+//                                               the free [0,1] output clamp
 //       per bit-width b:  tM = x * (2^b-1) + 2^23      rounds to the nearest code (RNE)
 //                         q' = tM * s_c - 2^23 s_c     = s_c * code, one rounding
 //                         r' = q' * (-step_b) + u'     = s_c * (w - lo - code*step_b)
@@ -52,7 +54,6 @@ constexpr int FS_WAVES = FS_THREADS / 64;
 constexpr int FS_KB = 5;                    // clip ratios evaluated together by one wavefront pass
 constexpr int FS_NRED = FS_KB * 4;          // per-lane sums a pass produces
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
-constexpr float RNE_ANY = 12582912.0f;      // 1.5 * 2^23: same for signed x
 
 struct FitScoreArgs {
     const void* W;
@@ -270,20 +271,30 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             }
             const float fam = (float)(S1 / (double)G);
             const bool ok = fam >= FLT_MIN;
-            const float ngam = ok ? -fam : 0.0f;
-            const float ginv = ok ? 1.0f / fam : 0.0f;
-            const float M = pin_vgpr(RNE_ANY);
+            // Fast-issue fp32 only, as in the clip passes.  y = clamp01(w/(2 gamma) + 1/2) maps
+            // w/gamma in [-1, 1] onto [0, 1]; rne(2y) = q + 1 in {0, 1, 2} needs no clamp.
+            const float gam = pin_vgpr(ok ? fam : 0.0f);
+            const float ngam = pin_vgpr(ok ? -fam : 0.0f);
+            const float hginv = pin_vgpr(ok ? 0.5f / fam : 0.0f);
+            const float nalpha = pin_vgpr(-fam);
+            const float half = pin_vgpr(0.5f), two = pin_vgpr(2.0f);
+            const float M = pin_vgpr(RNE_POS);
             float acc3[3] = {0.0f, 0.0f, 0.0f};
             for (int32_t c = 0; c < G; c += 8) {
                 float w[8];
                 read8<DT>(wrow, c, w);
+                const float4 sa = *reinterpret_cast<const float4*>(scol + c);
+                const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
+                const float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float sc = scol[c + j];
-                    const float q = __builtin_amdgcn_fmed3f(fmaf(w[j], ginv, M) - M, -1.0f, 1.0f);
-                    const float rt = fmaf(q, ngam, w[j]) * sc;
+                    const float sc = s8[j];
+                    const float y = fma_clamp01(w[j], hginv, half);
+                    const float qp = fmaf(y, two, M) - M;                    // q + 1
+                    const float rt = fmaf(qp, ngam, w[j] + gam) * sc;        // s_c (w - q gamma)
                     acc3[0] = fmaf(rt, rt, acc3[0]);
-                    const float rb = (fabsf(w[j]) - fam) * sc;
+                    const float aw = __uint_as_float(__float_as_uint(w[j]) & 0x7fffffffu);
+                    const float rb = (aw + nalpha) * sc;                     // s_c (|w| - alpha)
                     acc3[1] = fmaf(rb, rb, acc3[1]);
                     const float w1 = w[j] * sc;
                     acc3[2] = fmaf(w1, w1, acc3[2]);

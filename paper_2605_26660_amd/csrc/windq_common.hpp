@@ -2,12 +2,11 @@
 //
 // Kernel-wide design: a weight matrix is cut into tiles of TILE_ROWS rows x one chunk
 // (chunk_w columns).  A workgroup loads its tile from HBM with coalesced 128-bit loads
-// and stages it in LDS; then every lane owns ONE group (one row of the tile) and walks
-// along its chunk_w columns.  A group's min, max, mean|w| and all of its quantizer
-// parameters are therefore private to a lane: no cross-lane traffic and no redundant
-// parameter arithmetic inside the hot loops; the per-column activation weight is
-// wave-uniform and comes in through scalar loads.  Lanes are combined only once per
-// tile, in a fixed order, so every result is bit-reproducible.
+// and stages it in LDS in the input's own element type; then every lane owns ONE group
+// (one row of the tile) and walks along its chunk_w columns.  A group's min, max, mean|w|
+// and all of its quantizer parameters are therefore private to a lane: no cross-lane
+// traffic and no redundant parameter arithmetic inside the hot loops.  Lanes are combined
+// only once per tile, in a fixed order, so every result is bit-reproducible.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -18,8 +17,6 @@
 namespace windq {
 
 constexpr int TILE_ROWS = 64;   // rows per tile = lanes per wavefront
-constexpr int LDS_PAD = 4;      // dwords added to a tile row: keeps 128-bit LDS reads of
-                                // 64 different rows free of bank conflicts
 
 // Geometry of the unit decomposition of one matrix (Sec. 3.1: column-chunk units).
 struct Geometry {
@@ -45,9 +42,8 @@ struct ClipGrid {
     float p[WINDQ_MAX_CLIP];
 };
 
-inline size_t tile_lds_bytes(int32_t chunk_w) {
-    return (size_t)TILE_ROWS * (size_t)(chunk_w + LDS_PAD) * sizeof(float);
-}
+// LDS bytes of a raw tile: row stride = row bytes + 16.  With a stride of 4*odd dwords the
+// 64 lanes' 128-bit reads of 64 different rows spread evenly over the LDS banks.
 inline size_t raw_tile_lds_bytes(int32_t dtype, int32_t chunk_w) {
     return (size_t)TILE_ROWS * ((size_t)chunk_w * (dtype == WINDQ_BF16 ? 2 : 4) + 16);
 }
@@ -88,48 +84,14 @@ __device__ __forceinline__ TileCoord tile_coord(const Geometry& g, int64_t tile)
     return tc;
 }
 
-// Cooperative load of one tile into LDS as fp32, row stride (chunk_w + LDS_PAD) dwords.
-// Each thread moves 8 consecutive elements per step: one 128-bit global load for bf16,
-// two for fp32; 16 (or 32) neighbouring threads cover one contiguous row segment.
-// Rows past the end of the unit are filled with zeros.
-template <int DT>
-__device__ __forceinline__ void load_tile(const void* __restrict__ data, int64_t ld, const TileCoord& tc,
-                                          int32_t chunk_w, float* __restrict__ tile) {
-    const int32_t pieces = chunk_w >> 3;
-    const int32_t stride = chunk_w + LDS_PAD;
-    const int32_t total = TILE_ROWS * pieces;
-    for (int32_t i = threadIdx.x; i < total; i += blockDim.x) {
-        const int32_t r = i / pieces;
-        const int32_t pc = i - r * pieces;
-        float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
-        if (r < tc.nrows) {
-            const int64_t off = (tc.row0 + r) * ld + tc.col0 + (int64_t)pc * 8;
-            if (DT == WINDQ_BF16) {
-                const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(data) + off);
-                v0.x = bf16_bits_to_f32(raw.x & 0xffffu); v0.y = __uint_as_float(raw.x & 0xffff0000u);
-                v0.z = bf16_bits_to_f32(raw.y & 0xffffu); v0.w = __uint_as_float(raw.y & 0xffff0000u);
-                v1.x = bf16_bits_to_f32(raw.z & 0xffffu); v1.y = __uint_as_float(raw.z & 0xffff0000u);
-                v1.z = bf16_bits_to_f32(raw.w & 0xffffu); v1.w = __uint_as_float(raw.w & 0xffff0000u);
-            } else {
-                const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(data) + off);
-                v0 = src[0];
-                v1 = src[1];
-            }
-        }
-        float4* dst = reinterpret_cast<float4*>(tile + r * stride + pc * 8);
-        dst[0] = v0;
-        dst[1] = v1;
-    }
-}
-
-// ---- raw tiles: the tile kept in LDS in the input's own element type (2 bytes per
-// weight for bf16), row stride = row bytes + 16: with a stride of 4*odd dwords the 64
-// lanes' 128-bit reads of 64 different rows spread evenly over the LDS banks.
 template <int DT>
 struct Elem {
     static constexpr int bytes = DT == WINDQ_BF16 ? 2 : 4;
 };
 
+// Cooperative load of one tile into LDS, element type unchanged.  Each thread moves 16
+// bytes per step; 16 (bf16, chunk 128) neighbouring threads cover one contiguous row
+// segment.  Rows past the end of the unit are filled with zeros.
 template <int DT>
 __device__ __forceinline__ void load_tile_raw(const void* __restrict__ data, int64_t ld, const TileCoord& tc,
                                               int32_t chunk_w, char* __restrict__ tile) {
@@ -166,12 +128,6 @@ __device__ __forceinline__ void read8(const char* __restrict__ wrow, int32_t c, 
 
 // Sum of a double over the 64 lanes of a wavefront, fixed butterfly order.
 __device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    return v;
-}
-
-__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
     return v;

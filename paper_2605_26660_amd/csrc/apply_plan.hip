@@ -18,6 +18,8 @@
 // the 64 packed rows are then copied to one contiguous byte range with coalesced stores.
 #include <float.h>
 
+#include <type_traits>
+
 #include "windq_common.hpp"
 #include "windq_ws.hpp"
 
@@ -241,6 +243,358 @@ __global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyArgs 
         A.codes[base + payload + lane] = 0;
 }
 
+// ---------------------------------------------------------------------------------------
+// Fast path: bf16, chunk_w = 8 * LPR with LPR = 4, 8 or 16 (chunk 32, 64, 128).  LPR
+// adjacent lanes share one row: a lane loads 16 bytes (8 weights) straight into registers
+// -- a wave instruction covers 64 / LPR rows with fully coalesced segments -- and the
+// row's min / max / sum |w| are combined across its lanes with DPP butterflies.  A wave
+// owns 16 rows of the 64-row tile and issues all of its loads before the first use, so the
+// arithmetic of one piece overlaps the arrival of the next and of the other waves' pieces;
+// with ~40 VGPRs and at most 8 KB of LDS, 32 waves fit on a CU.  Each lane packs its own
+// eight codes (8, 4, 2 or 1 bytes: one store; 3-bit codes: three lanes of a quad store one
+// dword each) and stores them to consecutive addresses.  Only the base-3 bytes, which
+// straddle lane boundaries, are regrouped through LDS.  The per-row divisions are taken
+// once per wave: lane `piece` of a row derives the parameters of the row's piece-th
+// iteration and the others fetch them with a quad broadcast.
+//
+// The sum of |w| is combined in a tree here, not in column order.  Both orders give the
+// exact sum, hence the same fp64 value, while every partial sum is representable: all
+// |w| are multiples of 2^(Emin-134) and the sum is below 2^(Emax-126) * chunk_w, so
+// Emax - Emin <= 36 suffices.  A row that fails the test is summed again in column order.
+constexpr int APS_THREADS = 256;
+constexpr int APS_WAVE_ROWS = 16;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(x)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint64_t r = (uint64_t)dpp_u32<CTRL>((uint32_t)b) | ((uint64_t)dpp_u32<CTRL>((uint32_t)(b >> 32)) << 32);
+    return __longlong_as_double((long long)r);
+}
+constexpr int DPP_XOR1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i <- lane 7 - i of each 8
+constexpr int DPP_MIRROR = 0x140;       // lane i <- lane 15 - i of each 16
+constexpr int DPP_QUAD_NEXT = 0xF9;     // quad_perm [1,2,3,3]
+
+// All-reduce over the LPR lanes of a row (LPR-aligned lane groups inside a 16-lane DPP row).
+#define WINDQ_ROW_REDUCE(NAME, T, DPPFN, COMBINE)                              \
+    template <int LPR>                                                         \
+    __device__ __forceinline__ T NAME(T x) {                                   \
+        { const T y = DPPFN<DPP_XOR1>(x); x = COMBINE; }                       \
+        { const T y = DPPFN<DPP_XOR2>(x); x = COMBINE; }                       \
+        if (LPR >= 8) { const T y = DPPFN<DPP_HALF_MIRROR>(x); x = COMBINE; }  \
+        if (LPR >= 16) { const T y = DPPFN<DPP_MIRROR>(x); x = COMBINE; }      \
+        return x;                                                              \
+    }
+WINDQ_ROW_REDUCE(row_min_f32, float, dpp_f32, fminf(x, y))
+WINDQ_ROW_REDUCE(row_max_f32, float, dpp_f32, fmaxf(x, y))
+WINDQ_ROW_REDUCE(row_min_u32, uint32_t, dpp_u32, (x < y ? x : y))
+WINDQ_ROW_REDUCE(row_max_u32, uint32_t, dpp_u32, (x > y ? x : y))
+WINDQ_ROW_REDUCE(row_sum_f64, double, dpp_f64, x + y)
+#undef WINDQ_ROW_REDUCE
+
+// Value held by lane IT of the caller's quad.
+template <int IT>
+__device__ __forceinline__ float quad_bcast(float x) {
+    return dpp_f32<IT * 0x55>(x);
+}
+
+__device__ __forceinline__ void unpack8(const uint4& raw, float (&w)[8]) {
+    w[0] = bf16_bits_to_f32(raw.x & 0xffffu); w[1] = __uint_as_float(raw.x & 0xffff0000u);
+    w[2] = bf16_bits_to_f32(raw.y & 0xffffu); w[3] = __uint_as_float(raw.y & 0xffff0000u);
+    w[4] = bf16_bits_to_f32(raw.z & 0xffffu); w[5] = __uint_as_float(raw.z & 0xffff0000u);
+    w[6] = bf16_bits_to_f32(raw.w & 0xffffu); w[7] = __uint_as_float(raw.w & 0xffff0000u);
+}
+
+// Byte `sel` of `old` replaced by the integer value of f (f is an exact integer in [0, 255]).
+__device__ __forceinline__ uint32_t put_byte(float f, uint32_t sel, uint32_t old) {
+    return __builtin_amdgcn_cvt_pk_u8_f32(f, sel, old);
+}
+
+// Where one lane sits in its workgroup's tile.
+template <int LPR>
+struct SplitLane {
+    static constexpr int RPI = 64 / LPR;             // rows per wave instruction
+    static constexpr int NI = APS_WAVE_ROWS / RPI;   // instructions (iterations) per wave: 1, 2 or 4
+    int piece;                                       // which 8 columns of the row
+    int row0;                                        // tile row of iteration 0; iteration it adds it * RPI
+    int sel;                                         // the iteration whose row parameters this lane derives
+    __device__ __forceinline__ explicit SplitLane(int tid) {
+        const int lane = tid & 63;
+        piece = lane % LPR;
+        row0 = (tid >> 6) * APS_WAVE_ROWS + lane / LPR;
+        sel = piece & (NI - 1);
+    }
+};
+
+template <int LPR, int BITS>
+__device__ __forceinline__ void split_uniform(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
+                                              const uint4 (&raw)[SplitLane<LPR>::NI], float p, uint8_t* __restrict__ out,
+                                              int64_t bpg) {
+    constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
+    float w[8];
+    float smn = 0.0f, smx = 0.0f;
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        unpack8(raw[it], w);
+        float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
+        float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
+        mn = row_min_f32<LPR>(mn);
+        mx = row_max_f32<LPR>(mx);
+        if (it == 0 || L.sel == it) {
+            smn = mn;
+            smx = mx;
+        }
+    }
+    const float qmax = (float)((1 << BITS) - 1);
+    const float lo = p * smn;
+    const float hi = p * smx;
+    const float rg = hi - lo;
+    float d = rg / qmax;
+    const bool ok = d >= FLT_MIN;
+    d = ok ? d : 0.0f;
+    const float inv = ok ? 1.0f / d : 0.0f;
+    if (L.piece < NI) {
+        const int r = L.row0 + L.piece * RPI;
+        if (r < tc.nrows) {
+            const int64_t gidx = tc.u * A.g.R_u + tc.lrow0 + r;
+            A.scale[gidx] = d;
+            A.offset[gidx] = lo;
+        }
+    }
+    auto one = [&](auto IT) {
+        constexpr int it = decltype(IT)::value;
+        const float lo_r = NI == 1 ? lo : quad_bcast<it>(lo);
+        const float inv_r = NI == 1 ? inv : quad_bcast<it>(inv);
+        unpack8(raw[it], w);
+        float q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float u = w[j] - lo_r;
+            const float t = u * inv_r;
+            q[j] = __builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, qmax);
+        }
+        const int r = L.row0 + it * RPI;
+        const bool valid = r < tc.nrows;
+        uint8_t* dst = out + r * bpg;
+        if constexpr (BITS == 8) {
+            const uint32_t v0 = put_byte(q[0], 0, put_byte(q[1], 1, put_byte(q[2], 2, put_byte(q[3], 3, 0u))));
+            const uint32_t v1 = put_byte(q[4], 0, put_byte(q[5], 1, put_byte(q[6], 2, put_byte(q[7], 3, 0u))));
+            if (valid) *reinterpret_cast<uint2*>(dst + L.piece * 8) = make_uint2(v0, v1);
+        } else if constexpr (BITS == 4) {
+            const float b0 = fmaf(q[1], 16.0f, q[0]), b1 = fmaf(q[3], 16.0f, q[2]);
+            const float b2 = fmaf(q[5], 16.0f, q[4]), b3 = fmaf(q[7], 16.0f, q[6]);
+            const uint32_t v = put_byte(b0, 0, put_byte(b1, 1, put_byte(b2, 2, put_byte(b3, 3, 0u))));
+            if (valid) *reinterpret_cast<uint32_t*>(dst + L.piece * 4) = v;
+        } else if constexpr (BITS == 2) {
+            float v = q[7];
+#pragma unroll
+            for (int j = 6; j >= 0; --j) v = fmaf(v, 4.0f, q[j]);
+            if (valid) *reinterpret_cast<uint16_t*>(dst + L.piece * 2) = (uint16_t)(uint32_t)v;
+        } else {   // 3 bits: eight codes = 24 bits, exact in fp32; a quad's 12 bytes leave as 3 dwords
+            float v = q[7];
+#pragma unroll
+            for (int j = 6; j >= 0; --j) v = fmaf(v, 8.0f, q[j]);
+            const uint32_t mine = (uint32_t)v;
+            const uint32_t next = dpp_u32<DPP_QUAD_NEXT>(mine);
+            const int j = L.piece & 3;
+            const uint32_t dw = j == 0 ? (mine | (next << 24)) : (j == 1 ? ((mine >> 8) | (next << 16)) : ((mine >> 16) | (next << 8)));
+            if (valid && j < 3) *reinterpret_cast<uint32_t*>(dst + (L.piece >> 2) * 12 + j * 4) = dw;
+        }
+    };
+    one(std::integral_constant<int, 0>{});
+    if constexpr (NI >= 2) one(std::integral_constant<int, 1>{});
+    if constexpr (NI >= 4) {
+        one(std::integral_constant<int, 2>{});
+        one(std::integral_constant<int, 3>{});
+    }
+}
+
+// Sum of |w| over each row of every iteration; the return value is the sum of the row this
+// lane derives parameters for (iteration L.sel).
+template <int LPR>
+__device__ __forceinline__ double split_abs_sum(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
+                                                const uint4 (&raw)[SplitLane<LPR>::NI]) {
+    constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI, G = 8 * LPR;
+    double sS1 = 0.0;
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        float w[8];
+        unpack8(raw[it], w);
+        double S1 = (double)fabsf(w[0]);
+#pragma unroll
+        for (int j = 1; j < 8; ++j) S1 += (double)fabsf(w[j]);
+        S1 = row_sum_f64<LPR>(S1);
+        // largest and smallest non-zero magnitude keys of the row (zero maps to 0xffff in the minimum)
+        uint32_t kmax = 0u, kmin = 0xffffu;
+        const uint32_t dws[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t h = (dws[i] >> 16) & 0x7fffu, l = dws[i] & 0x7fffu;
+            kmax = max(kmax, max(h, l));
+            kmin = min(kmin, min((h - 1u) & 0xffffu, (l - 1u) & 0xffffu));
+        }
+        kmax = row_max_u32<LPR>(kmax);
+        kmin = row_min_u32<LPR>(kmin);
+        const int emax = (int)(kmax >> 7);
+        const int emin = max((int)(((kmin + 1u) & 0xffffu) >> 7), 1);
+        if (kmax != 0u && emax - emin > 36) {
+            // partial sums may round: take the sum in column order instead
+            const int r = L.row0 + it * RPI;
+            S1 = 0.0;
+            if (r < tc.nrows) {
+                const uint16_t* __restrict__ wrow =
+                    static_cast<const uint16_t*>(A.W) + (tc.row0 + r) * A.g.ld + tc.col0;
+                for (int c = 0; c < G; ++c) S1 += (double)fabsf(bf16_bits_to_f32(wrow[c]));
+            }
+        }
+        if (it == 0 || L.sel == it) sS1 = S1;
+    }
+    return sS1;
+}
+
+template <int LPR>
+__device__ __forceinline__ void split_ternary(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
+                                              const uint4 (&raw)[SplitLane<LPR>::NI], uint8_t* __restrict__ out,
+                                              uint8_t* trits) {
+    constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI, G = 8 * LPR, NB = (G + 4) / 5;
+    float gamma = (float)(split_abs_sum<LPR>(A, tc, L, raw) / (double)G);
+    const bool ok = gamma >= FLT_MIN;
+    gamma = ok ? gamma : 0.0f;
+    const float inv = ok ? 1.0f / gamma : 0.0f;
+    if (L.piece < NI) {
+        const int r = L.row0 + L.piece * RPI;
+        if (r < tc.nrows) {
+            const int64_t gidx = tc.u * A.g.R_u + tc.lrow0 + r;
+            A.scale[gidx] = gamma;
+            A.offset[gidx] = 0.0f;
+        }
+    }
+    // trits (q + 1) as bytes, rows of G bytes: lane l of iteration it writes bytes [8 * (64 * it + l), +8)
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint8_t* wt = trits + wave * (APS_WAVE_ROWS * G);
+    auto one = [&](auto IT) {
+        constexpr int it = decltype(IT)::value;
+        const float inv_r = NI == 1 ? inv : quad_bcast<it>(inv);
+        float w[8];
+        unpack8(raw[it], w);
+        float q[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float t = w[j] * inv_r;
+            q[j] = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -1.0f, 1.0f) + 1.0f;
+        }
+        const uint32_t v0 = put_byte(q[0], 0, put_byte(q[1], 1, put_byte(q[2], 2, put_byte(q[3], 3, 0u))));
+        const uint32_t v1 = put_byte(q[4], 0, put_byte(q[5], 1, put_byte(q[6], 2, put_byte(q[7], 3, 0u))));
+        *reinterpret_cast<uint2*>(wt + 8 * (64 * it + lane)) = make_uint2(v0, v1);
+    };
+    one(std::integral_constant<int, 0>{});
+    if constexpr (NI >= 2) one(std::integral_constant<int, 1>{});
+    if constexpr (NI >= 4) {
+        one(std::integral_constant<int, 2>{});
+        one(std::integral_constant<int, 3>{});
+    }
+    __syncthreads();
+    // five trits -> one byte; the wave's 16 rows x NB bytes are consecutive in the code stream
+    const int wrow0 = wave * APS_WAVE_ROWS;
+    for (int b = lane; b < APS_WAVE_ROWS * NB; b += 64) {
+        const int r = b / NB, j = b - r * NB;
+        const uint8_t* t5 = wt + r * G + 5 * j;
+        uint32_t v = t5[0];
+        if (5 * j + 1 < G) v += 3u * t5[1];
+        if (5 * j + 2 < G) v += 9u * t5[2];
+        if (5 * j + 3 < G) v += 27u * t5[3];
+        if (5 * j + 4 < G) v += 81u * t5[4];
+        if (wrow0 + r < tc.nrows) out[(int64_t)wrow0 * NB + b] = (uint8_t)v;
+    }
+}
+
+template <int LPR>
+__device__ __forceinline__ void split_binary(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
+                                             const uint4 (&raw)[SplitLane<LPR>::NI], uint8_t* __restrict__ out) {
+    constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI, G = 8 * LPR;
+    const float alpha = (float)(split_abs_sum<LPR>(A, tc, L, raw) / (double)G);
+    if (L.piece < NI) {
+        const int r = L.row0 + L.piece * RPI;
+        if (r < tc.nrows) {
+            const int64_t gidx = tc.u * A.g.R_u + tc.lrow0 + r;
+            A.scale[gidx] = alpha;
+            A.offset[gidx] = 0.0f;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        float w[8];
+        unpack8(raw[it], w);
+        uint32_t byte = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) byte |= (w[j] >= 0.0f ? 1u : 0u) << j;
+        const int r = L.row0 + it * RPI;
+        if (r < tc.nrows) out[r * LPR + L.piece] = (uint8_t)byte;
+    }
+}
+
+template <int LPR>
+__global__ __launch_bounds__(APS_THREADS, 8) void apply_plan_split_kernel(const ApplyArgs A) {
+    constexpr int G = 8 * LPR, NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
+    __shared__ __attribute__((aligned(16))) uint8_t trits[TILE_ROWS * G];
+    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const SplitLane<LPR> L(threadIdx.x);
+
+    int a = A.action[tc.u];
+    if (a >= WINDQ_N_ACTIONS) a = 0;
+    const int64_t bpg = dev_bytes_per_group(a, G);
+    const int64_t base = A.code_off[tc.u];
+    const int64_t payload = bpg * A.g.R_u;
+    const int64_t padded = (payload + 15) & ~(int64_t)15;
+    if (base < 0 || (base & 15) != 0 || base + padded > A.codes_bytes) a = 0;
+    if (a == 0) {
+        if (threadIdx.x < tc.nrows) {
+            const int64_t gidx = tc.u * A.g.R_u + tc.lrow0 + threadIdx.x;
+            A.scale[gidx] = 0.0f;
+            A.offset[gidx] = 0.0f;
+        }
+        return;
+    }
+
+    uint4 raw[NI];
+    const char* __restrict__ wbase = static_cast<const char*>(A.W);
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+        const int r = L.row0 + it * RPI;
+        raw[it] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < tc.nrows)
+            raw[it] = *reinterpret_cast<const uint4*>(wbase + ((tc.row0 + r) * A.g.ld + tc.col0) * 2 + L.piece * 16);
+    }
+
+    float p = 1.0f;
+    if (a <= 4 && A.clip_idx != nullptr) {
+        int k = A.clip_idx[tc.u * 4 + (a - 1)];
+        k = k < A.K ? k : A.K - 1;
+        p = A.grid.p[k];
+    }
+    uint8_t* __restrict__ out = A.codes + base + tc.lrow0 * bpg;   // the tile's rows, bpg bytes each
+    switch (a) {
+        case 1: split_uniform<LPR, 8>(A, tc, L, raw, p, out, bpg); break;
+        case 2: split_uniform<LPR, 4>(A, tc, L, raw, p, out, bpg); break;
+        case 3: split_uniform<LPR, 3>(A, tc, L, raw, p, out, bpg); break;
+        case 4: split_uniform<LPR, 2>(A, tc, L, raw, p, out, bpg); break;
+        case 5: split_ternary<LPR>(A, tc, L, raw, out, trits); break;
+        default: split_binary<LPR>(A, tc, L, raw, out); break;
+    }
+    // zero the padding that rounds the unit's payload up to 16 bytes
+    if (padded != payload && tc.t == A.g.tiles_per_unit - 1 && (int64_t)threadIdx.x < padded - payload)
+        A.codes[base + payload + threadIdx.x] = 0;
+}
+
 }  // namespace windq
 
 using namespace windq;
@@ -276,7 +630,13 @@ extern "C" int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t uni
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w);
     const dim3 grid((unsigned)A.g.n_tiles);
-    if (W->dtype == WINDQ_BF16) {
+    if (W->dtype == WINDQ_BF16 && chunk_w == 128) {
+        hipLaunchKernelGGL(apply_plan_split_kernel<16>, grid, dim3(APS_THREADS), 0, hs, A);
+    } else if (W->dtype == WINDQ_BF16 && chunk_w == 64) {
+        hipLaunchKernelGGL(apply_plan_split_kernel<8>, grid, dim3(APS_THREADS), 0, hs, A);
+    } else if (W->dtype == WINDQ_BF16 && chunk_w == 32) {
+        hipLaunchKernelGGL(apply_plan_split_kernel<4>, grid, dim3(APS_THREADS), 0, hs, A);
+    } else if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&apply_plan_kernel<WINDQ_BF16>), lds);
         if (st != WINDQ_OK) return st;
         hipLaunchKernelGGL(apply_plan_kernel<WINDQ_BF16>, grid, dim3(AP_THREADS), lds, hs, A);

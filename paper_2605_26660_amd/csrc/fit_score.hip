@@ -74,21 +74,6 @@ inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w) {
            (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float);
 }
 
-// Keeps a value in a VGPR and hides its origin from the optimiser, so that it is never
-// folded into an SGPR, literal or negated operand (any of which drops the instruction
-// to the slow issue rate).
-__device__ __forceinline__ float pin_vgpr(float x) {
-    asm volatile("" : "+v"(x));
-    return x;
-}
-
-// a * b + c with the result clamped to [0, 1] by the instruction's output modifier.
-__device__ __forceinline__ float fma_clamp01(float a, float b, float c) {
-    float r;
-    asm("v_fma_f32 %0, %1, %2, %3 clamp" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
-
 struct KParams {
     float rinv, h;     // 1/range, (c - lo)/range: x = (w - c)*rinv + h is the position in the range
     float nc, Mq;      // -c (anchor), 2^23 + q0

@@ -126,6 +126,21 @@ __device__ __forceinline__ void read8(const char* __restrict__ wrow, int32_t c, 
     }
 }
 
+// Keeps a value in a VGPR and hides its origin from the optimiser, so that it is never
+// folded into an SGPR, literal or negated operand (any of which drops the instruction
+// to the slow issue rate).
+__device__ __forceinline__ float pin_vgpr(float x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+// a * b + c with the result clamped to [0, 1] by the instruction's output modifier.
+__device__ __forceinline__ float fma_clamp01(float a, float b, float c) {
+    float r;
+    asm("v_fma_f32 %0, %1, %2, %3 clamp" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // Sum of a double over the 64 lanes of a wavefront, fixed butterfly order.
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll

@@ -183,7 +183,8 @@ def test_fit_score_is_bit_reproducible(windq):
 @pytest.mark.parametrize("R,C,G,unit_rows,dtype", [
     (256, 512, 128, 0, torch.bfloat16), (256, 512, 128, 128, torch.bfloat16), (200, 256, 64, 100, torch.bfloat16),
     (512, 512, 64, 0, torch.float32), (24, 80, 40, 3, torch.bfloat16), (6, 16, 8, 3, torch.float32),
-    (64, 512, 256, 0, torch.bfloat16)])
+    (64, 512, 256, 0, torch.bfloat16), (130, 96, 32, 0, torch.bfloat16), (150, 384, 128, 0, torch.bfloat16),
+    (77, 128, 64, 0, torch.bfloat16), (96, 64, 32, 16, torch.bfloat16)])
 def test_apply_plan_every_action(windq, R, C, G, unit_rows, dtype):
     W = synth.weights_llm(R, C, seed=31, device=DEV, dtype=dtype)
     s = torch.rand(C, device=DEV) + 0.1
@@ -211,6 +212,22 @@ def test_apply_plan_degenerate_groups_and_ties(windq):
     for a in range(7):
         check_apply(windq, W, 64, 0, torch.full((2,), a, dtype=torch.uint8), None, 1)
         check_apply(windq, W.to(torch.bfloat16), 64, 32, torch.full((4,), a, dtype=torch.uint8), None, 1)
+
+
+@pytest.mark.parametrize("G", [32, 64, 128, 256])
+def test_apply_plan_wide_dynamic_range(windq, G):
+    """Groups whose magnitudes span far more than the 53 bits of an fp64 sum: the sum of |w|
+    then depends on the order of the additions, and the order is part of the definition."""
+    gen = torch.Generator().manual_seed(77)
+    R, C = 70, 2 * G
+    expo = torch.randint(-120, 60, (R, C), generator=gen).double()
+    mant = 1.0 + torch.rand(R, C, generator=gen, dtype=torch.float64)
+    sign = torch.where(torch.rand(R, C, generator=gen) < 0.5, -1.0, 1.0).double()
+    W = (sign * mant * torch.pow(torch.tensor(2.0, dtype=torch.float64), expo)).float().to(torch.bfloat16).to(DEV)
+    W[3, :] = 0.0
+    W[4, 5] = 0.0
+    for a in range(7):
+        check_apply(windq, W, G, 0, torch.full((2,), a, dtype=torch.uint8), None, 1)
 
 
 def test_apply_plan_malformed_entries_are_skipped(windq):

@@ -68,26 +68,71 @@ def build_block(wq, synth, torch, dev, unit_rows):
     return specs, cg, xs, mats
 
 
-def run_step(wq, torch, cg, xs, mats, unit_rows, fit_events=None):
+class CallTimer:
+    """HIP events on the stream the calls are enqueued on (torch's current stream), one pair per call."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = {}
+
+    def time(self, name, fn):
+        e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+        e0.record()
+        r = fn()
+        e1.record()
+        self.pairs.setdefault(name, []).append((e0, e1))
+        return r
+
+    def ms(self, name):
+        return [e0.elapsed_time(e1) for e0, e1 in self.pairs.get(name, [])]
+
+
+class NoTimer:
+    def time(self, name, fn):
+        return fn()
+
+
+def run_step(wq, torch, cg, xs, mats, unit_rows, timer=NoTimer()):
     for x in xs.values():
-        wq.windq_calib_stats(x["X"], want_rms=False, ws=x["ws"], out=x["s"])
+        timer.time("calib_stats", lambda: wq.windq_calib_stats(x["X"], want_rms=False, ws=x["ws"], out=x["s"]))
     total_cb = total_n = 0
     for m in mats:
         s = xs[m["spec"].x_key]["s"]
-        wq.windq_unit_features(m["W"], s, G, unit_rows, ws=m["ws"], out=m["feat"])
-        if fit_events is not None:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-        wq.windq_fit_score_all_bits(m["W"], s, G, unit_rows, cg, ws=m["ws"], out=(m["err"], m["clip_idx"], m["ref"]))
-        if fit_events is not None:
-            e1.record()
-            fit_events.append((e0, e1))
-        wq.windq_apply_plan(m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"],
-                            ws=m["ws"], out=(m["scale"], m["offset"]))
+        timer.time("unit_features", lambda: wq.windq_unit_features(m["W"], s, G, unit_rows, ws=m["ws"], out=m["feat"]))
+        timer.time("fit_score_all_bits", lambda: wq.windq_fit_score_all_bits(
+            m["W"], s, G, unit_rows, cg, ws=m["ws"], out=(m["err"], m["clip_idx"], m["ref"])))
+        timer.time("apply_plan", lambda: wq.windq_apply_plan(
+            m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"], ws=m["ws"],
+            out=(m["scale"], m["offset"])))
         cb, n = wq.windq_effective_bits(m["action"], m["n_unit"])
         total_cb += cb
         total_n += n
     return total_cb, total_n
+
+
+def clip_sweep(wq, synth, torch, mats, xs, unit_rows, reps=3):
+    """fit+score alone at growing clip grids: where the call leaves the HBM roofline for the ALU one."""
+    n_weights = sum(m["spec"].rows * m["spec"].cols for m in mats)
+    rows = []
+    for k in (1, 2, 3, 5, 10, 20, 40):
+        cg = synth.clip_grid(k)
+        ws = [torch.empty(wq.workspace_bytes(wq.CALL_FIT_SCORE, wq.WINDQ_BF16, m["spec"].rows, m["spec"].cols, G, unit_rows, k),
+                          dtype=torch.uint8, device=m["W"].device) for m in mats]
+        best = None
+        for _ in range(reps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for m, w in zip(mats, ws):
+                wq.windq_fit_score_all_bits(m["W"], xs[m["spec"].x_key]["s"], G, unit_rows, cg, ws=w,
+                                            out=(m["err"], m["clip_idx"], m["ref"]))
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1)
+            best = t if best is None else min(best, t)
+        gbs = n_weights * 2 / (best * 1e-3) / 1e9
+        rows.append({"K": k, "ms": best, "weight_GBps": gbs, "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+                     "TFLOPs": fit_score_flops_per_weight(k) * n_weights / (best * 1e-3) / 1e12})
+    return rows
 
 
 def cpu_baseline(torch, xs, mats, cg):
@@ -121,6 +166,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--unit-rows", type=int, default=0, help="0 = the paper's units (all rows); 128 = 128 x G tiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--clip-sweep", action="store_true",
+                    help="also time fit+score alone at 1..40 clip ratios (where it leaves the HBM roofline)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run plain device copies of 1 GiB (calibrates the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -153,32 +200,46 @@ def main():
     for _ in range(args.warmup):
         run_step(wq, torch, cg, xs, mats, args.unit_rows)
     torch.cuda.synchronize()
-    fit_events = []
+    timer = CallTimer(torch)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        total_cb, total_n = run_step(wq, torch, cg, xs, mats, args.unit_rows, fit_events)
+        total_cb, total_n = run_step(wq, torch, cg, xs, mats, args.unit_rows, timer)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    fit_ms = sum(e0.elapsed_time(e1) for e0, e1 in fit_events) / args.steps     # per step, all 7 launches
+    n_act = sum(x["X"].numel() for x in xs.values())
+    code_bytes = sum(int(m["off"][-1]) + 8 * m["U"] * m["R_u"] for m in mats)      # codes + scale/offset written
+    call_bytes = {"calib_stats": n_act * 2, "unit_features": n_weights * 2, "fit_score_all_bits": n_weights * 2,
+                  "apply_plan": n_weights * 2 + code_bytes}
+    calls = {}
+    for name, nbytes in call_bytes.items():
+        ms = timer.ms(name)
+        n_per_step = len(ms) // args.steps
+        steps_ms = sorted(sum(ms[i * n_per_step:(i + 1) * n_per_step]) for i in range(args.steps))
+        med = steps_ms[len(steps_ms) // 2]
+        calls[name] = {"ms_per_step_median": med, "ms_per_step_min": steps_ms[0], "launches_per_step": n_per_step,
+                       "algorithmic_bytes_per_step": nbytes, "GBps": nbytes / (med * 1e-3) / 1e9,
+                       "pct_hbm_peak": 100.0 * nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    calls["unit_features"]["units_per_s"] = n_units / (calls["unit_features"]["ms_per_step_median"] * 1e-3)
+    calls["fit_score_all_bits"]["units_per_s"] = n_units / (calls["fit_score_all_bits"]["ms_per_step_median"] * 1e-3)
+    calls["apply_plan"]["units_per_s"] = n_units / (calls["apply_plan"]["ms_per_step_median"] * 1e-3)
+    fit_ms = sum(timer.ms("fit_score_all_bits")) / args.steps                  # per step, all 7 launches
     flops = fit_score_flops_per_weight(K) * n_weights
     achieved = flops / (fit_ms * 1e-3) / 1e12
 
     out = {
-        "metric": "weight GB/s scored across all 6 bit-widths, whole hot path, 7B-shaped block",
+        "metric": "weight GB/s scored across all 6 bit-widths (units/s) + % HBM peak, 7B shape",
         "value": n_weights * 2 / (ms_per_step * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "configs[1]: one LLaMA-7B-shaped decoder block, bf16, chunk 128, 20 clip ratios, "
-                               "512 calibration tokens, plan at 2.0 bits",
+                               "512 calibration tokens, plan at 2.0 bits; a step = all five calls over the block",
                    "weights": n_weights, "units": n_units, "unit_rows": args.unit_rows, "chunk_w": G, "K": K},
         "units_per_s": n_units / (ms_per_step * 1e-3),
         "pct_hbm_peak_whole_step": 100.0 * n_weights * 2 / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "fit_score": {"ms_per_step": fit_ms, "weight_GBps": n_weights * 2 / (fit_ms * 1e-3) / 1e9,
-                      "pct_hbm_peak": 100.0 * n_weights * 2 / (fit_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                      "launches_per_step": len(mats)},
+        "calls": calls,
         "avg_bits": total_cb / (100.0 * total_n),
         "roofline": {"bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_VECTOR_PEAK_TFLOPS,
@@ -188,6 +249,8 @@ def main():
                      "avg_launch_ms": fit_ms / len(mats),
                      "flops_per_weight": fit_score_flops_per_weight(K)},
     }
+    if args.clip_sweep:
+        out["clip_sweep"] = clip_sweep(wq, synth, torch, mats, xs, args.unit_rows)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, xs, mats, cg)
     print(json.dumps(out))

@@ -542,11 +542,27 @@ __device__ __forceinline__ void split_binary(const ApplyArgs& A, const TileCoord
     }
 }
 
+// tile_coord in 32-bit arithmetic (the host keeps n_tiles below 2^31).
+__device__ __forceinline__ TileCoord tile_coord32(const Geometry& g, uint32_t tile) {
+    const uint32_t n_chunks = (uint32_t)g.n_chunks, tpu = (uint32_t)g.tiles_per_unit;
+    TileCoord tc;
+    const uint32_t band = tile / n_chunks, j = tile - band * n_chunks;
+    const uint32_t rb = band / tpu, t = band - rb * tpu;
+    tc.t = t;
+    tc.u = (int64_t)rb * n_chunks + j;
+    tc.lrow0 = (int64_t)t * TILE_ROWS;
+    tc.row0 = rb * g.R_u + tc.lrow0;
+    const int64_t left = g.R_u - tc.lrow0;
+    tc.nrows = left < TILE_ROWS ? (int32_t)left : TILE_ROWS;
+    tc.col0 = (int64_t)j * g.chunk_w;
+    return tc;
+}
+
 template <int LPR>
 __global__ __launch_bounds__(APS_THREADS, 8) void apply_plan_split_kernel(const ApplyArgs A) {
     constexpr int G = 8 * LPR, NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
     __shared__ __attribute__((aligned(16))) uint8_t trits[TILE_ROWS * G];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const TileCoord tc = tile_coord32(A.g, blockIdx.x);
     const SplitLane<LPR> L(threadIdx.x);
 
     int a = A.action[tc.u];

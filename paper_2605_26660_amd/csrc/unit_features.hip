@@ -233,10 +233,10 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatAr
                 cnt += (x[j] & 0x7fffu) < sparse_key ? 1u : 0u;
                 cnt += ((x[j] >> 16) & 0x7fffu) < sparse_key ? 1u : 0u;
             } else {
-                if (dlo == e0) atomicAdd(&myhist[x[j] & 15u], 1u);
-                if (dlo == eh) atomicAdd(&myhist[16u + (x[j] & 15u)], 1u);
-                if (dhi == e0) atomicAdd(&myhist[(x[j] >> 16) & 15u], 1u);
-                if (dhi == eh) atomicAdd(&myhist[16u + ((x[j] >> 16) & 15u)], 1u);
+                // one atomic per weight: the two bins are distinct unless both are bin 0, and
+                // then the single histogram serves both (the finish kernel reads it twice)
+                if (dlo == e0 || dlo == eh) atomicAdd(&myhist[(dlo == e0 ? 0u : 16u) + (x[j] & 15u)], 1u);
+                if (dhi == e0 || dhi == eh) atomicAdd(&myhist[(dhi == e0 ? 0u : 16u) + ((x[j] >> 16) & 15u)], 1u);
             }
         }
     };
@@ -340,8 +340,7 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatArgs A,
                 const uint32_t key = key_of<DT>(w[j]);
                 if (DT == WINDQ_BF16) {
                     const uint32_t b = key >> 4;
-                    if (b == prefix) atomicAdd(&lhist[key & 15u], 1u);
-                    if (b == half_bin) atomicAdd(&lhist[16u + (key & 15u)], 1u);
+                    if (b == prefix || b == half_bin) atomicAdd(&lhist[(b == prefix ? 0u : 16u) + (key & 15u)], 1u);
                 } else {
                     if ((key >> (shift + bits)) == prefix) atomicAdd(&lhist[(key >> shift) & mask], 1u);
                 }
@@ -422,7 +421,8 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatArgs 
         const uint32_t tbin = tk >> 4, tlow = tk & 15u;        // tbin == half_bin_of(e0) by construction
         for (int32_t b = threadIdx.x; b < FEAT_BINS; b += FT_THREADS)
             if ((uint32_t)b > tbin) above += (double)h0[b];
-        if (threadIdx.x < 16 && (uint32_t)threadIdx.x > tlow) above += (double)h1[16 + threadIdx.x];
+        // (when both refined bins are bin 0 they share the first 16 counters)
+        if (threadIdx.x < 16 && (uint32_t)threadIdx.x > tlow) above += (double)h1[(tbin == e0 ? 0 : 16) + threadIdx.x];
     } else {
         for (int64_t b = threadIdx.x; b < A.bpu; b += FT_THREADS) above += (double)A.above[(size_t)u * A.bpu + b];
     }

@@ -71,11 +71,14 @@ def build_block(wq, synth, torch, dev, unit_rows):
 class CallTimer:
     """HIP events on the stream the calls are enqueued on (torch's current stream), one pair per call."""
 
-    def __init__(self, torch):
+    def __init__(self, torch, only=None):
         self.torch = torch
         self.pairs = {}
+        self.only = only
 
     def time(self, name, fn):
+        if self.only is not None and name not in self.only:
+            return fn()
         e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
         e0.record()
         r = fn()
@@ -135,35 +138,35 @@ def clip_sweep(wq, synth, torch, mats, xs, unit_rows, reps=3):
     return rows
 
 
-def cpu_baseline(torch, xs, mats, cg):
-    """The oracle, as it stands, on a bounded sample of the same workload: the first two
-    units (chunks) of attn.q through features, fit+score, apply-plan and bit accounting,
-    plus calibration statistics of their input channels."""
-    import numpy as np
+def cpu_baseline(torch, xs, mats, cg, unit_rows):
+    """The oracle, as it stands, on a bounded sample of the same workload: the three
+    4096 x 4096 projections that read the block input (attn.q, attn.k, attn.v: 96 units)
+    through features, fit+score, apply-plan and bit accounting, plus the calibration
+    statistics of their input."""
     from oracle import windq_oracle as O
-    m = mats[0]
-    n_units = 24
-    Wn = m["W"][:, : n_units * G].float().cpu().numpy()
-    Xn = xs["h"]["X"][:, : n_units * G].float().cpu().numpy()
-    action = m["action"][:n_units].numpy()
+    Xn = xs["h"]["X"].float().cpu().numpy()
+    sample = mats[:3]
+    host = [(m["W"].float().cpu().numpy(), m["action"].numpy(), m["R_u"]) for m in sample]
+    n_w = 0
     t0 = time.perf_counter()
     s, _ = O.calib_stats(Xn)
-    O.unit_features(Wn, s, G, 0)
-    err, clip_idx, ref, _ = O.fit_score_all_bits(Wn, s, G, 0, cg.numpy())
-    off = O.plan_layout(action, Wn.shape[0], G)
-    O.apply_plan(Wn, G, 0, action, clip_idx, cg.numpy(), off)
-    O.effective_bits(action, [Wn.shape[0] * G] * n_units)
+    for Wn, action, R_u in host:
+        O.unit_features(Wn, s, G, unit_rows)
+        err, clip_idx, ref, _ = O.fit_score_all_bits(Wn, s, G, unit_rows, cg.numpy())
+        off = O.plan_layout(action, R_u, G)
+        O.apply_plan(Wn, G, unit_rows, action, clip_idx, cg.numpy(), off)
+        O.effective_bits(action, [R_u * G] * len(action))
+        n_w += Wn.size
     dt = time.perf_counter() - t0
-    nbytes = Wn.size * 2
-    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "seconds": dt,
-            "sample": f"first {n_units} units (4096x{G} each, {Wn.size} weights) of attn.q of the same block, all five calls"}
+    return {"value": n_w * 2 / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "seconds": dt,
+            "sample": f"attn.q, attn.k, attn.v of the same block ({sum(m['U'] for m in sample)} units, {n_w} weights), all five calls"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--unit-rows", type=int, default=0, help="0 = the paper's units (all rows); 128 = 128 x G tiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--clip-sweep", action="store_true",
@@ -200,13 +203,20 @@ def main():
     for _ in range(args.warmup):
         run_step(wq, torch, cg, xs, mats, args.unit_rows)
     torch.cuda.synchronize()
-    timer = CallTimer(torch)
+    # timed region: K whole steps; only the dominant call carries events (for the roofline)
+    fit_timer = CallTimer(torch, only=("fit_score_all_bits",))
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        total_cb, total_n = run_step(wq, torch, cg, xs, mats, args.unit_rows, timer)
+        total_cb, total_n = run_step(wq, torch, cg, xs, mats, args.unit_rows, fit_timer)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    # after it, the same steps again with an event pair around every call (the pairs cost ~7 % of a step,
+    # so this pass does not count toward `value`)
+    timer = CallTimer(torch)
+    for _ in range(args.steps):
+        run_step(wq, torch, cg, xs, mats, args.unit_rows, timer)
+    torch.cuda.synchronize()
     n_act = sum(x["X"].numel() for x in xs.values())
     code_bytes = sum(int(m["off"][-1]) + 8 * m["U"] * m["R_u"] for m in mats)      # codes + scale/offset written
     call_bytes = {"calib_stats": n_act * 2, "unit_features": n_weights * 2, "fit_score_all_bits": n_weights * 2,
@@ -223,7 +233,7 @@ def main():
     calls["unit_features"]["units_per_s"] = n_units / (calls["unit_features"]["ms_per_step_median"] * 1e-3)
     calls["fit_score_all_bits"]["units_per_s"] = n_units / (calls["fit_score_all_bits"]["ms_per_step_median"] * 1e-3)
     calls["apply_plan"]["units_per_s"] = n_units / (calls["apply_plan"]["ms_per_step_median"] * 1e-3)
-    fit_ms = sum(timer.ms("fit_score_all_bits")) / args.steps                  # per step, all 7 launches
+    fit_ms = sum(fit_timer.ms("fit_score_all_bits")) / args.steps              # per step, all 7 launches
     flops = fit_score_flops_per_weight(K) * n_weights
     achieved = flops / (fit_ms * 1e-3) / 1e12
 
@@ -239,7 +249,7 @@ def main():
                    "weights": n_weights, "units": n_units, "unit_rows": args.unit_rows, "chunk_w": G, "K": K},
         "units_per_s": n_units / (ms_per_step * 1e-3),
         "pct_hbm_peak_whole_step": 100.0 * n_weights * 2 / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "calls": calls,
+        "calls": calls, "calls_note": "separate pass after the timed region, an event pair around every call",
         "avg_bits": total_cb / (100.0 * total_n),
         "roofline": {"bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_VECTOR_PEAK_TFLOPS,
@@ -252,7 +262,7 @@ def main():
     if args.clip_sweep:
         out["clip_sweep"] = clip_sweep(wq, synth, torch, mats, xs, args.unit_rows)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(torch, xs, mats, cg)
+        out["cpu_baseline"] = cpu_baseline(torch, xs, mats, cg, args.unit_rows)
     print(json.dumps(out))
 
 

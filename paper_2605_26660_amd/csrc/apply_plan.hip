@@ -7,9 +7,10 @@
 // that each written operation is exactly one IEEE operation.  The sum of |w| of a group
 // is accumulated in fp64 in column order (exact for bf16 inputs).
 //
-// Streaming kernel, bound by HBM: reads 2 (bf16) or 4 (fp32) bytes per weight once,
-// writes b/8 bytes of codes per weight and 8 bytes per group.  One wavefront per tile of
-// 64 rows x one chunk.  The tile is loaded with coalesced 128-bit loads into LDS in the
+// Streaming kernels, bound by HBM: read 2 (bf16) or 4 (fp32) bytes per weight once,
+// write b/8 bytes of codes per weight and 8 bytes per group.  Two kernels: bf16 at chunk
+// widths 32/64/128 takes the lanes-per-row kernel further down; everything else takes the
+// general kernel described here.  One wavefront per tile of 64 rows x one chunk.  The tile is loaded with coalesced 128-bit loads into LDS in the
 // input's own element type (17 KB for bf16 at chunk 128: nine workgroups per CU, whose
 // loads overlap each other's arithmetic).  Each lane quantizes and packs its own row, so
 // ternary base-3 bytes and 3-bit streams need no cross-lane regrouping, and writes the

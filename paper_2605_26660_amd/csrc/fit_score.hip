@@ -109,6 +109,14 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
     }
 }
 
+// The lane's index in its wavefront, read anew from the hardware at every call (never kept
+// in a register between calls).
+__device__ __forceinline__ int fresh_lane() {
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
+}
+
 // x + (x of the lane whose index differs in bit 0 / bit 1): after both, every lane of a
 // quad (4 adjacent rows) holds the quad's sum.
 __device__ __forceinline__ float quad_sum(float x) {
@@ -152,16 +160,12 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     const int32_t row_bytes = G * EB + 16;
     char* __restrict__ tile = smem;
     float* __restrict__ scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
 
     load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
     for (int32_t c = threadIdx.x; c < G; c += FS_THREADS) scol[c] = A.s[tc.col0 + c];
     __syncthreads();
 
-    const bool valid = lane < tc.nrows;
-    const char* __restrict__ wrow = tile + lane * row_bytes;
     const int32_t K = A.K;
     double* __restrict__ out = A.partial + ((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) *
                                                (size_t)fit_score_ncand(K);
@@ -172,6 +176,14 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     const int rot = blockIdx.x & (FS_WAVES - 1);
     const int n_items = A.n_kpass + 1;
     for (int item = (wave - rot) & (FS_WAVES - 1); item < n_items; item += FS_WAVES) {
+        // The hot loop below needs every register the occupancy target allows.  The lane index
+        // is therefore re-read from the hardware where it is needed (before the loop for the
+        // row address, after it for the reduction) rather than kept alive across the loop,
+        // which would spill it, and everything derived from it, to scratch memory.
+        int G_r = G;
+        asm volatile("" : "+s"(G_r));
+        const char* __restrict__ wrow = tile + fresh_lane() * row_bytes;
+        float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
         if (item < A.n_kpass) {
             float mn, mx;
             {
@@ -238,11 +250,16 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
 #pragma unroll
             for (int i = 0; i < FS_KB; ++i)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) flat[i * 4 + b] = valid ? acc[i][b] : 0.0f;
-            const double tot = rows_sum<FS_NRED>(flat, red, lane);
-            if (lane < FS_NRED) {
-                const int k = item * FS_KB + (lane >> 2);
-                if (k < K) out[(lane & 3) * K + k] = tot;
+                for (int b = 0; b < 4; ++b) flat[i * 4 + b] = acc[i][b];
+            const int lane_r = fresh_lane();
+            if (lane_r >= tc.nrows) {
+#pragma unroll
+                for (int j = 0; j < FS_NRED; ++j) flat[j] = 0.0f;
+            }
+            const double tot = rows_sum<FS_NRED>(flat, red, lane_r);
+            if (lane_r < FS_NRED) {
+                const int k = item * FS_KB + (lane_r >> 2);
+                if (k < K) out[(lane_r & 3) * K + k] = tot;
             }
         } else {
             // ternary absmean, binary sign*mean|w|, reference energy.  S1 = sum |w| in fp64
@@ -254,7 +271,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
 #pragma unroll
                 for (int j = 0; j < 8; ++j) S1 += (double)fabsf(w[j]);
             }
-            const float fam = (float)(S1 / (double)G);
+            const float fam = (float)(S1 / (double)G_r);
             const bool ok = fam >= FLT_MIN;
             // Fast-issue fp32 only, as in the clip passes.  y = clamp01(w/(2 gamma) + 1/2) maps
             // w/gamma in [-1, 1] onto [0, 1]; rne(2y) = q + 1 in {0, 1, 2} needs no clamp.
@@ -285,9 +302,10 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     acc3[2] = fmaf(w1, w1, acc3[2]);
                 }
             }
-            if (!valid) acc3[0] = acc3[1] = acc3[2] = 0.0f;
-            const double tot = rows_sum<3>(acc3, red, lane);
-            if (lane < 3) out[4 * K + lane] = tot;
+            const int lane_r = fresh_lane();
+            if (lane_r >= tc.nrows) acc3[0] = acc3[1] = acc3[2] = 0.0f;
+            const double tot = rows_sum<3>(acc3, red, lane_r);
+            if (lane_r < 3) out[4 * K + lane_r] = tot;
         }
     }
 }

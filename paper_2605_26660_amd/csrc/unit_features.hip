@@ -35,7 +35,7 @@ namespace windq {
 
 constexpr int FT_THREADS = 256;
 constexpr int FT_WAVES = FT_THREADS / 64;
-constexpr int FEAT_BATCH = 4;   // 128-bit loads a thread keeps in flight
+constexpr int FEAT_BATCH = 8;   // 128-bit loads a thread keeps in flight
 
 struct FeatArgs {
     const void* W;
@@ -179,16 +179,18 @@ __device__ __forceinline__ uint32_t half_bin_of(uint32_t e0) { return e0 >= 16u 
 
 // bf16 passes work on the packed 16-bit patterns directly (two weights per dword): the
 // first digit is a bit-field extract, no conversion to float; the LDS histogram is kept
-// in FEAT_COPIES copies indexed by lane, which removes most same-address collisions of
-// the LDS atomics (Gaussian-like weights fall into ~40 hot bins); each thread sums its
-// <= 32 weights in fp32 (products of bf16 are exact in fp32) and hands fp64 to the
-// block-wide sums.
+// in FEAT_COPIES copies indexed by lane, which thins out the same-address collisions of
+// the LDS atomics (Gaussian-like weights fall into ~40 hot bins; more copies cost more in
+// clearing and flushing than they save); each thread sums its <= 64 weights in fp32
+// (products of bf16 are exact in fp32) and hands fp64 to the block-wide sums.
 //   MODE 0: moments + histogram of digit 0.   MODE 1: refine bins e0 and half_bin_of(e0).
-constexpr int FEAT_COPIES = 4;
+constexpr int FEAT_COPIES = 2;
+__host__ __device__ constexpr int feat_cstride(int mode) { return (mode == 0 ? FEAT_BINS : 32) + 17; }   // odd skew: copies of a bin sit in different banks
+__host__ __device__ constexpr size_t feat_lds_bytes(int mode) { return (size_t)feat_cstride(mode) * FEAT_COPIES * sizeof(uint32_t); }
 template <int MODE>
 __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatArgs A, const uint32_t sparse_key) {
-    constexpr int CSTRIDE = (MODE == 0 ? FEAT_BINS : 32) + 17;   // odd skew: copies of a bin sit in different banks
-    __shared__ uint32_t lhist[CSTRIDE * FEAT_COPIES];
+    constexpr int CSTRIDE = feat_cstride(MODE);
+    extern __shared__ uint32_t lhist[];                          // [FEAT_COPIES][CSTRIDE]
     __shared__ double red[FT_WAVES];
     __shared__ uint32_t sh_part[FT_THREADS];
     __shared__ uint32_t sh_out[4];
@@ -203,6 +205,18 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatAr
     const int64_t left = A.g.R_u - lrow0;
     const int32_t nrows = (int32_t)(left < FEAT_TPB * TILE_ROWS ? left : FEAT_TPB * TILE_ROWS);
     const int64_t row0 = rb * A.g.R_u + lrow0;
+    // The first batch of loads is issued before anything else, so that it is in flight while
+    // the histogram is cleared and (pass B) the rank's first-digit bin is looked up.
+    const uint16_t* __restrict__ Wp = static_cast<const uint16_t*>(A.W);
+    const bool by_rows = FT_THREADS % pieces == 0;          // a thread keeps its column piece and steps down the rows
+    const int32_t rstep = by_rows ? FT_THREADS / pieces : 1;
+    const int32_t r_first = by_rows ? (int32_t)threadIdx.x / pieces : nrows;
+    const int64_t cbase = col0 + (int64_t)(by_rows ? (int32_t)threadIdx.x % pieces : 0) * 8;
+    uint4 first[FEAT_BATCH];
+#pragma unroll
+    for (int b = 0; b < FEAT_BATCH; ++b)
+        if (r_first + b * rstep < nrows)
+            first[b] = *reinterpret_cast<const uint4*>(Wp + (row0 + r_first + b * rstep) * A.g.ld + cbase);
     for (int32_t b = threadIdx.x; b < CSTRIDE * FEAT_COPIES; b += FT_THREADS) lhist[b] = 0;
     uint32_t e0 = 0, eh = 0;
     if (MODE == 1) {
@@ -221,8 +235,12 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatAr
         for (int j = 0; j < 4; ++j) {
             const uint32_t dlo = (x[j] >> 4) & 0x7ffu, dhi = (x[j] >> 20) & 0x7ffu;
             if (MODE == 0) {
+#ifndef FEAT_EXP_NOATOM
                 atomicAdd(&myhist[dlo], 1u);
                 atomicAdd(&myhist[dhi], 1u);
+#else
+                cnt += dlo ^ dhi;
+#endif
                 const float wlo = __uint_as_float(x[j] << 16), whi = __uint_as_float(x[j] & 0xffff0000u);
                 sw += wlo;
                 sw += whi;
@@ -240,12 +258,11 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatAr
             }
         }
     };
-    const uint16_t* __restrict__ Wp = static_cast<const uint16_t*>(A.W);
-    if (FT_THREADS % pieces == 0) {
-        const int32_t rstep = FT_THREADS / pieces;
-        const int32_t pc = threadIdx.x % pieces;
-        const int64_t cbase = col0 + (int64_t)pc * 8;
-        for (int32_t r = threadIdx.x / pieces; r < nrows; r += FEAT_BATCH * rstep) {
+    if (by_rows) {
+#pragma unroll
+        for (int b = 0; b < FEAT_BATCH; ++b)
+            if (r_first + b * rstep < nrows) consume(first[b]);
+        for (int32_t r = r_first + FEAT_BATCH * rstep; r < nrows; r += FEAT_BATCH * rstep) {
             uint4 raw[FEAT_BATCH];
 #pragma unroll
             for (int b = 0; b < FEAT_BATCH; ++b)
@@ -481,8 +498,9 @@ static int launch_features(const FeatArgs& A, hipStream_t hs) {
         uint32_t tb;
         memcpy(&tb, &A.sparse_thr, sizeof(tb));
         const uint32_t sparse_key = (tb >> 16) + ((tb & 0xffffu) != 0 ? 1u : 0u);
-        hipLaunchKernelGGL((feat_pass_bf16_kernel<0>), blocks, dim3(FT_THREADS), 0, hs, A, sparse_key);
-        hipLaunchKernelGGL((feat_pass_bf16_kernel<1>), blocks, dim3(FT_THREADS), 0, hs, A, sparse_key);
+        if (ensure_lds(reinterpret_cast<const void*>(&feat_pass_bf16_kernel<0>), feat_lds_bytes(0)) != WINDQ_OK) return WINDQ_EHIP;
+        hipLaunchKernelGGL((feat_pass_bf16_kernel<0>), blocks, dim3(FT_THREADS), feat_lds_bytes(0), hs, A, sparse_key);
+        hipLaunchKernelGGL((feat_pass_bf16_kernel<1>), blocks, dim3(FT_THREADS), feat_lds_bytes(1), hs, A, sparse_key);
     } else {
         hipLaunchKernelGGL((feat_pass_kernel<DT, 0>), blocks, dim3(FT_THREADS), 0, hs, A, 0);
         hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, A, 1);

@@ -56,7 +56,7 @@ int check_clip_grid(const float* clip_grid, int32_t K) {
 
 int ensure_lds(const void* kernel, size_t bytes) {
     if (bytes <= 64 * 1024) return WINDQ_OK;
-    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
         return WINDQ_EHIP;
     return WINDQ_OK;
 }

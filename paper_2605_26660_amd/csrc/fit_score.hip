@@ -44,6 +44,8 @@
 // (about 1e-18 .. 1e18); smaller products contribute zero.
 #include <float.h>
 
+#include <type_traits>
+
 #include "windq_common.hpp"
 #include "windq_ws.hpp"
 
@@ -74,14 +76,25 @@ inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w) {
            (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float);
 }
 
+// The 8-bit residual is ~1/500 of the range, so it is taken relative to an ANCHOR c: a grid
+// point of the 8-bit quantizer, with the code counted from it (qc = code - q0).
+//   ANCHORED (zero lies inside [lo, hi], true for every group of real weight matrices): c is
+//   the grid point nearest zero, |c| <= step/2.  Then w - qc*step = c + r is small, the FMA
+//   that forms it rounds once at that small magnitude, and subtracting c is exact to the
+//   same order: r to ~1e-7 relative in two instructions, no compensation needed.
+//   Otherwise (a group whose weights all have one sign) c = lo may be large against the
+//   step: (w - c) is split into a rounded value and its rounding error by an error-free
+//   two-sum, and the residual is the FMA on the rounded part plus the error.
+// A wavefront takes the second route when any of its 64 groups needs it.
 struct KParams {
-    float rinv, h;     // 1/range, (c - lo)/range: x = (w - c)*rinv + h is the position in the range
+    float rinv, h;     // 1/range; x = (w - a)*rinv + h is the position in the range, a = 0 (anchored) or c
     float nc, Mq;      // -c (anchor), 2^23 + q0
     float nlo;         // -lo
     float nd[4];       // -step for 8, 4, 3, 2 bits (0 when degenerate)
 };
 
 // One weight against FS_KB clip ratios x 4 bit-widths.  sc = s_c, nM = -2^23 (in a VGPR).
+template <bool ANCHORED>
 __device__ __forceinline__ void score_weight(const float w, const float sc, const KParams (&P)[FS_KB],
                                              const float (&Q)[4], const float M, const float nM,
                                              float (&acc)[FS_KB][4]) {
@@ -89,16 +102,22 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
     const float ms = sc * nM;                              // -2^23 * s_c, exact
 #pragma unroll
     for (int i = 0; i < FS_KB; ++i) {
-        const float u0 = w + P[i].nc;                             // w - c, rounded
-        const float e = P[i].nc - (u0 - w);                       // its rounding error: (w - c) = u0 + e
-        const float x = fma_clamp01(u0, P[i].rinv, P[i].h);       // position in the clipped range, in [0, 1]
         const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
-        {   // 8 bits
+        float x, r;
+        if (ANCHORED) {
+            x = fma_clamp01(w, P[i].rinv, P[i].h);                // position in the clipped range, in [0, 1]
             const float qc = fmaf(x, Q[0], M) - P[i].Mq;          // code - q0
-            const float r = fmaf(qc, P[i].nd[0], u0) + e;
-            const float r1 = r * sc;
-            acc[i][0] = fmaf(r1, r1, acc[i][0]);
+            r = fmaf(qc, P[i].nd[0], w) + P[i].nc;                // (c + r) - c
+        } else {
+            const float u0 = w + P[i].nc;                         // w - c, rounded
+            const float bb = u0 - w;
+            const float e = (w - (u0 - bb)) + (P[i].nc - bb);     // its rounding error: (w - c) = u0 + e exactly
+            x = fma_clamp01(u0, P[i].rinv, P[i].h);
+            const float qc = fmaf(x, Q[0], M) - P[i].Mq;
+            r = fmaf(qc, P[i].nd[0], u0) + e;
         }
+        const float r8 = r * sc;
+        acc[i][0] = fmaf(r8, r8, acc[i][0]);
 #pragma unroll
         for (int b = 1; b < 4; ++b) {
             const float tM = fmaf(x, Q[b], M);
@@ -196,6 +215,8 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     mx = fmaxf(fmaxf(fmaxf(mx, w[0]), fmaxf(w[1], w[2])), fmaxf(fmaxf(w[3], w[4]), fmaxf(w[5], fmaxf(w[6], w[7]))));
                 }
             }
+            // zero inside the closed range of every group of the wavefront?
+            const bool anchored = __builtin_amdgcn_ballot_w64(!(mn <= 0.0f && mx >= 0.0f)) == 0;
             KParams P[FS_KB];
             float acc[FS_KB][4];
 #pragma unroll
@@ -219,12 +240,12 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     P[i].nd[b] = pin_vgpr(-d);
                     acc[i][b] = 0.0f;
                 }
-                // anchor: the 8-bit grid point nearest zero when zero lies inside the range
+                // anchor: the 8-bit grid point nearest zero when zero lies inside the range, else lo
                 float q0 = 0.0f;
-                if (flo < 0.0f && fhi > 0.0f) q0 = __builtin_amdgcn_fmed3f(__builtin_rintf(-flo * rinv * 255.0f), 0.0f, 255.0f);
+                if (flo <= 0.0f && fhi >= 0.0f) q0 = __builtin_amdgcn_fmed3f(__builtin_rintf(-flo * rinv * 255.0f), 0.0f, 255.0f);
                 const float c = fmaf(q0, d8, flo);
                 P[i].rinv = rinv;
-                P[i].h = pin_vgpr((c - flo) * rinv);
+                P[i].h = pin_vgpr((anchored ? -flo : c - flo) * rinv);
                 P[i].nc = pin_vgpr(-c);
                 P[i].Mq = pin_vgpr(RNE_POS + q0);
                 P[i].nlo = pin_vgpr(-flo);
@@ -232,20 +253,25 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             const float Q[4] = {pin_vgpr(255.0f), pin_vgpr(15.0f), pin_vgpr(7.0f), pin_vgpr(3.0f)};
             const float M = pin_vgpr(RNE_POS);
             const float nM = pin_vgpr(-RNE_POS);
-            for (int32_t c = 0; c < G; c += 8) {
-                float w[8];
-                read8<DT>(wrow, c, w);
-                const float4 sa = *reinterpret_cast<const float4*>(scol + c);
-                const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
-                score_weight(w[0], sa.x, P, Q, M, nM, acc);
-                score_weight(w[1], sa.y, P, Q, M, nM, acc);
-                score_weight(w[2], sa.z, P, Q, M, nM, acc);
-                score_weight(w[3], sa.w, P, Q, M, nM, acc);
-                score_weight(w[4], sb.x, P, Q, M, nM, acc);
-                score_weight(w[5], sb.y, P, Q, M, nM, acc);
-                score_weight(w[6], sb.z, P, Q, M, nM, acc);
-                score_weight(w[7], sb.w, P, Q, M, nM, acc);
-            }
+            auto sweep = [&](auto MODE) {
+                constexpr bool AN = decltype(MODE)::value;
+                for (int32_t c = 0; c < G; c += 8) {
+                    float w[8];
+                    read8<DT>(wrow, c, w);
+                    const float4 sa = *reinterpret_cast<const float4*>(scol + c);
+                    const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
+                    score_weight<AN>(w[0], sa.x, P, Q, M, nM, acc);
+                    score_weight<AN>(w[1], sa.y, P, Q, M, nM, acc);
+                    score_weight<AN>(w[2], sa.z, P, Q, M, nM, acc);
+                    score_weight<AN>(w[3], sa.w, P, Q, M, nM, acc);
+                    score_weight<AN>(w[4], sb.x, P, Q, M, nM, acc);
+                    score_weight<AN>(w[5], sb.y, P, Q, M, nM, acc);
+                    score_weight<AN>(w[6], sb.z, P, Q, M, nM, acc);
+                    score_weight<AN>(w[7], sb.w, P, Q, M, nM, acc);
+                }
+            };
+            if (anchored) sweep(std::true_type{});
+            else sweep(std::false_type{});
             float flat[FS_NRED];
 #pragma unroll
             for (int i = 0; i < FS_KB; ++i)

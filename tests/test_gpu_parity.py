@@ -170,6 +170,29 @@ def test_fit_score_degenerate_groups(windq):
     check_fit_score(windq, W.float(), s, 128, 64, 4)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("unit_rows", [0, 16])
+def test_fit_score_one_signed_groups(windq, dtype, unit_rows):
+    """Groups whose weights all have one sign sit far from zero relative to their range: the
+    8-bit residual (1/500 of the range) must survive the offset.  Rows 0-63: offsets up to
+    100x the range, both signs; rows 64-127: ordinary groups that straddle zero; rows
+    128-191: one one-signed group among ordinary ones in every wavefront; a few groups that
+    touch zero exactly at one end."""
+    gen = torch.Generator().manual_seed(61)
+    R, C, G = 192, 256, 128
+    W = 0.02 * torch.randn(R, C, generator=gen)
+    off = torch.empty(64).uniform_(0.1, 2.0, generator=gen) * torch.where(torch.arange(64) % 2 == 0, 1.0, -1.0)
+    W[:64] = off[:, None] + W[:64]
+    W[128::16] = W[128::16].abs() + 0.5
+    W[129, :G] = W[129, :G].abs()
+    W[129, 3] = 0.0                                   # touches zero at the low end
+    W[130, :G] = -W[130, :G].abs()
+    W[130, 5] = 0.0                                   # ... at the high end
+    W = W.to(dtype).to(DEV)
+    s = (torch.rand(C, generator=gen) + 0.1).to(DEV)
+    check_fit_score(windq, W, s, G, unit_rows, 20)
+
+
 def test_fit_score_is_bit_reproducible(windq):
     W = synth.weights_llm(512, 1024, seed=24, device=DEV)
     s = torch.rand(1024, device=DEV) + 0.1

@@ -125,13 +125,21 @@ def unit_features(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int = 0) -> n
 
 
 # ------------------------------------------------------- O3 per-group quantizer fit
-def group_stats(Wu: np.ndarray):
+def group_stats(Wu: np.ndarray, keep=None):
     """Per group (row of the unit): min, max (exact) and S1 = sum |w| accumulated in
     fp64 in column order (exact for bf16 inputs; the fixed order makes it
-    reproducible for any input)."""
-    mn = Wu.min(axis=1).astype(f32)
-    mx = Wu.max(axis=1).astype(f32)
-    S1 = np.cumsum(np.abs(Wu.astype(f64)), axis=1)[:, -1]
+    reproducible for any input).  With `keep` (bool [R_u x G], False = protected
+    salient weight, Sec. 3.5) the statistics run over the kept weights only; a group
+    with none kept has min = max = 0 and S1 = 0."""
+    if keep is None:
+        mn = Wu.min(axis=1).astype(f32)
+        mx = Wu.max(axis=1).astype(f32)
+        S1 = np.cumsum(np.abs(Wu.astype(f64)), axis=1)[:, -1]
+        return mn, mx, S1
+    any_kept = keep.any(axis=1)
+    mn = np.where(any_kept, np.where(keep, Wu, np.inf).min(axis=1), 0.0).astype(f32)
+    mx = np.where(any_kept, np.where(keep, Wu, -np.inf).max(axis=1), 0.0).astype(f32)
+    S1 = np.cumsum(np.where(keep, np.abs(Wu.astype(f64)), 0.0), axis=1)[:, -1]
     return mn, mx, S1
 
 
@@ -168,12 +176,15 @@ def uniform_dequant(codes, lo, delta) -> np.ndarray:
     return lo.astype(f64)[:, None] + codes.astype(f64) * delta.astype(f64)[:, None]
 
 
-def absmean_scale(S1: np.ndarray, G: int) -> np.ndarray:
-    """[N] per-group mean |w| as stored: fp32 rounding of S1 / G."""
-    return (S1 / f64(G)).astype(f32)
+def absmean_scale(S1: np.ndarray, G) -> np.ndarray:
+    """[N] per-group mean |w| as stored: fp32 rounding of S1 / G.  G may be a per-group
+    count (kept weights of the group); a count of zero gives a scale of zero."""
+    G = np.asarray(G, dtype=f64)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        return np.where(G > 0, S1 / G, 0.0).astype(f32)
 
 
-def ternary_fit(S1: np.ndarray, G: int):
+def ternary_fit(S1: np.ndarray, G):
     """[N] ternary absmean scale gamma; degenerate (all-zero-like) groups get 0."""
     gamma = absmean_scale(S1, G)
     degenerate = ~(gamma >= FLT_MIN_NORMAL)
@@ -197,34 +208,40 @@ def binary_codes(Wu: np.ndarray) -> np.ndarray:
     return (Wu >= 0).astype(np.int64)
 
 
-def weighted_sse(Wu64: np.ndarray, What: np.ndarray, a: np.ndarray) -> float:
-    """Activation-aware reconstruction error of one unit: sum a_c (w - w_hat)^2."""
+def weighted_sse(Wu64: np.ndarray, What: np.ndarray, a: np.ndarray, keep=None) -> float:
+    """Activation-aware reconstruction error of one unit: sum a_c (w - w_hat)^2, over the
+    kept weights when a mask is given."""
     d = Wu64 - What
-    return float((a[None, :] * d * d).sum())
+    e = a[None, :] * d * d
+    if keep is not None:
+        e = np.where(keep, e, 0.0)
+    return float(e.sum())
 
 
-def fit_score_unit(Wu: np.ndarray, s_chunk: np.ndarray, clip_grid: np.ndarray):
+def fit_score_unit(Wu: np.ndarray, s_chunk: np.ndarray, clip_grid: np.ndarray, keep=None):
     """All candidate fits of one unit.  Returns (E_uniform [4 x K], E_ternary,
-    E_binary, ref_energy), raw weighted sums of squares in fp64."""
+    E_binary, ref_energy), raw weighted sums of squares in fp64.  With `keep`, protected
+    weights take no part: not in the group statistics, not in the errors."""
     Wu = np.ascontiguousarray(Wu, dtype=f32)
     R_u, G = Wu.shape
     Wu64 = Wu.astype(f64)
     a = s_chunk.astype(f64) ** 2
-    mn, mx, S1 = group_stats(Wu)
+    mn, mx, S1 = group_stats(Wu, keep)
+    n_g = G if keep is None else keep.sum(axis=1)
     K = len(clip_grid)
     E = np.zeros((4, K), dtype=f64)
     for bi, bits in enumerate(UNIFORM_BITS):
         for k in range(K):
             lo, delta, inv, deg = uniform_fit(mn, mx, clip_grid[k], bits)
             codes = uniform_codes(Wu, lo, delta, inv, deg, bits)
-            E[bi, k] = weighted_sse(Wu64, uniform_dequant(codes, lo, delta), a)
-    gamma, ginv, gdeg = ternary_fit(S1, G)
+            E[bi, k] = weighted_sse(Wu64, uniform_dequant(codes, lo, delta), a, keep)
+    gamma, ginv, gdeg = ternary_fit(S1, n_g)
     qt = ternary_codes(Wu, ginv, gdeg)
-    E_t = weighted_sse(Wu64, gamma.astype(f64)[:, None] * qt, a)
-    alpha = absmean_scale(S1, G)
+    E_t = weighted_sse(Wu64, gamma.astype(f64)[:, None] * qt, a, keep)
+    alpha = absmean_scale(S1, n_g)
     qb = binary_codes(Wu)
-    E_b = weighted_sse(Wu64, alpha.astype(f64)[:, None] * (2 * qb - 1), a)
-    ref = float((a[None, :] * Wu64 * Wu64).sum())
+    E_b = weighted_sse(Wu64, alpha.astype(f64)[:, None] * (2 * qb - 1), a, keep)
+    ref = weighted_sse(Wu64, np.zeros_like(Wu64), a, keep)
     return E, E_t, E_b, ref
 
 
@@ -236,13 +253,13 @@ def argmin_clip(E_row: np.ndarray) -> int:
 
 
 def fit_score_all_bits(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int,
-                       clip_grid: np.ndarray, units=None):
+                       clip_grid: np.ndarray, units=None, keep=None):
     """Fit and score the six candidate quantizers of every unit.
 
     Returns err [U x 6] fp64 (order 8, 4, 3, 2, 1.58, 1; the uniform entries at their
     best clip index), clip_idx [U x 4] uint8, ref_energy [U] fp64 and the full table
     E [U x 4 x K].  `units` restricts the work to a list of unit indices (the other
-    rows stay zero)."""
+    rows stay zero).  `keep` (bool, shape of W; False = protected) masks salient weights out."""
     clip_grid = np.asarray(clip_grid, dtype=f32)
     n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
     U = n_rb * n_chunks
@@ -253,7 +270,8 @@ def fit_score_all_bits(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int,
     table = np.zeros((U, 4, K), dtype=f64)
     for u in (range(U) if units is None else units):
         j = u % n_chunks
-        E, E_t, E_b, r = fit_score_unit(unit_view(W, G, unit_rows, u), s[j * G:(j + 1) * G], clip_grid)
+        ku = None if keep is None else unit_view(keep, G, unit_rows, u)
+        E, E_t, E_b, r = fit_score_unit(unit_view(W, G, unit_rows, u), s[j * G:(j + 1) * G], clip_grid, ku)
         table[u] = E
         for bi in range(4):
             k = argmin_clip(E[bi])
@@ -321,35 +339,39 @@ def plan_layout(action: np.ndarray, R_u: int, G: int) -> np.ndarray:
     return off
 
 
-def quantize_unit(Wu: np.ndarray, action: int, p):
+def quantize_unit(Wu: np.ndarray, action: int, p, keep=None):
     """Codes, stored scale and stored offset of one unit under `action` at clip p.
     Returns (stored [R_u x G] non-negative ints, scale [R_u] f32, offset [R_u] f32,
-    w_hat [R_u x G] fp64)."""
+    w_hat [R_u x G] fp64).  With `keep`, the fit runs over the kept weights and the
+    stored value at a protected position is the placeholder 0 (its w_hat is unused)."""
     Wu = np.ascontiguousarray(Wu, dtype=f32)
     R_u, G = Wu.shape
-    mn, mx, S1 = group_stats(Wu)
+    mn, mx, S1 = group_stats(Wu, keep)
+    n_g = G if keep is None else keep.sum(axis=1)
     zero = np.zeros(R_u, dtype=f32)
+    hold = (lambda stored: stored) if keep is None else (lambda stored: np.where(keep, stored, 0))
     if action in (1, 2, 3, 4):
         bits = ACTION_CENTIBITS[action] // 100
         lo, delta, inv, deg = uniform_fit(mn, mx, p, bits)
         codes = uniform_codes(Wu, lo, delta, inv, deg, bits)
-        return codes, delta, lo, uniform_dequant(codes, lo, delta)
+        return hold(codes), delta, lo, uniform_dequant(codes, lo, delta)
     if action == 5:
-        gamma, inv, deg = ternary_fit(S1, G)
+        gamma, inv, deg = ternary_fit(S1, n_g)
         q = ternary_codes(Wu, inv, deg)
-        return q + 1, gamma, zero, gamma.astype(f64)[:, None] * q
+        return hold(q + 1), gamma, zero, gamma.astype(f64)[:, None] * q
     if action == 6:
-        alpha = absmean_scale(S1, G)
+        alpha = absmean_scale(S1, n_g)
         bit = binary_codes(Wu)
-        return bit, alpha, zero, alpha.astype(f64)[:, None] * (2 * bit - 1)
+        return hold(bit), alpha, zero, alpha.astype(f64)[:, None] * (2 * bit - 1)
     raise ValueError("skip units have no codes")
 
 
 def apply_plan(W: np.ndarray, G: int, unit_rows: int, action: np.ndarray,
-               clip_idx, clip_grid: np.ndarray, code_off: np.ndarray, units=None):
+               clip_idx, clip_grid: np.ndarray, code_off: np.ndarray, units=None, keep=None):
     """Materialise a plan: packed code stream, per-group scale and offset.
     clip_idx None means no clipping (p = 1).  Skip units write no codes and a zero
-    scale and offset.  `units` restricts the work to some units."""
+    scale and offset.  `units` restricts the work to some units.  `keep` (bool, shape of
+    W; False = protected) masks salient weights out of the fits; their code slots hold 0."""
     clip_grid = np.asarray(clip_grid, dtype=f32)
     n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
     U = n_rb * n_chunks
@@ -363,7 +385,8 @@ def apply_plan(W: np.ndarray, G: int, unit_rows: int, action: np.ndarray,
         p = f32(1)
         if a in (1, 2, 3, 4) and clip_idx is not None:
             p = clip_grid[int(clip_idx[u, a - 1])]
-        stored, sc, of, _ = quantize_unit(unit_view(W, G, unit_rows, u), a, p)
+        ku = None if keep is None else unit_view(keep, G, unit_rows, u)
+        stored, sc, of, _ = quantize_unit(unit_view(W, G, unit_rows, u), a, p, ku)
         scale[u * R_u:(u + 1) * R_u] = sc
         offset[u * R_u:(u + 1) * R_u] = of
         bpg = bytes_per_group(a, G)
@@ -372,6 +395,82 @@ def apply_plan(W: np.ndarray, G: int, unit_rows: int, action: np.ndarray,
             row = pack_trits(stored[r]) if a == 5 else pack_bits(stored[r], ACTION_CENTIBITS[a] // 100)
             codes[base + r * bpg: base + (r + 1) * bpg] = row
     return codes, scale, offset
+
+
+# ------------------------------------------- salient-weight protection (Sec. 3.5)
+def n_protected(n_unit: int, rate_ppm: int) -> int:
+    """Number of protected weights of a unit of n_unit weights at a protection rate given
+    in parts per million: floor(n * rate), in integers."""
+    if not 0 <= rate_ppm <= 1_000_000:
+        raise ValueError("rate out of range")
+    return (int(n_unit) * int(rate_ppm)) // 1_000_000
+
+
+def saliency(W: np.ndarray, s: np.ndarray) -> np.ndarray:
+    """App. "Salient Weight Protection": saliency of a weight = its magnitude times the
+    activation scale of its input channel (a magnitude too: a scale is never negative).
+    [N] one fp32 multiply per weight."""
+    return (np.abs(W.astype(f32)) * np.abs(s.astype(f32))[None, :]).astype(f32)
+
+
+def salient_select(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int, rate_ppm: int) -> np.ndarray:
+    """Protected set of every unit: its n_p = floor(rate * n) most salient weights; equal
+    saliencies are taken in order of the flat index inside the unit (row major).  Returns
+    `keep`, bool of W's shape, False at protected weights."""
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    sal = saliency(W, s)
+    keep = np.ones(W.shape, dtype=bool)
+    n_p = n_protected(R_u * G, rate_ppm)
+    if n_p == 0:
+        return keep
+    for u in range(n_rb * n_chunks):
+        key = unit_view(sal, G, unit_rows, u).ravel()
+        order = np.argsort(-key.astype(f64), kind="stable")      # descending saliency, ties by flat index
+        ku = np.ones(R_u * G, dtype=bool)
+        ku[order[:n_p]] = False
+        unit_view(keep, G, unit_rows, u)[...] = ku.reshape(R_u, G)
+    return keep
+
+
+def pack_mask(keep: np.ndarray) -> np.ndarray:
+    """Protection mask as bytes [rows x cols/8]: bit (c mod 8) of byte c div 8 of a row is
+    1 where weight (row, c) is protected."""
+    return np.packbits((~keep).astype(np.uint8), axis=1, bitorder="little")
+
+
+def salient_encode(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int, keep: np.ndarray):
+    """INT8 storage of the protected weights (Sec. 3.5: "stored in INT8").  Per unit one
+    symmetric scale sigma = fp32(max|w_p| / 127) [N]; code = clamp(rne(w * fp32(1/sigma)),
+    -127, 127) [N]; codes of a unit in flat-index order, units back to back.  Returns
+    (codes int8 [sum n_p], prot_off int64 [U+1], sigma f32 [U], err_prot fp64 [U]) with
+    err_prot = sum a_c (w - code * sigma)^2 over the unit's protected weights."""
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    U = n_rb * n_chunks
+    codes, off = [], np.zeros(U + 1, dtype=np.int64)
+    sigma = np.zeros(U, dtype=f32)
+    err = np.zeros(U, dtype=f64)
+    for u in range(U):
+        j = u % n_chunks
+        Wu = unit_view(W, G, unit_rows, u).astype(f32)
+        prot = ~unit_view(keep, G, unit_rows, u)
+        wp = Wu[prot]                                            # row-major order = flat-index order
+        a = np.broadcast_to((s[j * G:(j + 1) * G].astype(f64) ** 2)[None, :], Wu.shape)[prot]
+        off[u + 1] = off[u] + wp.size
+        if wp.size == 0:
+            continue
+        sg = f32(np.abs(wp).max() / f32(127))                    # [N] one fp32 divide
+        if not sg >= FLT_MIN_NORMAL:
+            sg = f32(0)
+        with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
+            inv = f32(1) / sg                                    # [N]
+            t = (wp * inv).astype(f32)                           # [N]
+            q = np.rint(t)
+        q = np.zeros_like(wp) if sg == 0 else np.clip(q, -127, 127)
+        sigma[u] = sg
+        codes.append(q.astype(np.int8))
+        err[u] = float((a * (wp.astype(f64) - q.astype(f64) * f64(sg)) ** 2).sum())
+    allc = np.concatenate(codes) if codes else np.zeros(0, dtype=np.int8)
+    return allc, off, sigma, err
 
 
 # -------------------------------------------------------------- O5 effective bits

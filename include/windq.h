@@ -60,7 +60,8 @@ enum windq_call {
     WINDQ_CALL_CALIB_STATS = 0,
     WINDQ_CALL_UNIT_FEATURES = 1,
     WINDQ_CALL_FIT_SCORE = 2,
-    WINDQ_CALL_APPLY_PLAN = 3
+    WINDQ_CALL_APPLY_PLAN = 3,
+    WINDQ_CALL_SALIENT = 4        /* windq_salient_select and windq_salient_encode */
 };
 
 #define WINDQ_N_ACTIONS 7
@@ -172,6 +173,44 @@ int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t unit_rows,
 int windq_effective_bits(const uint8_t* action /*HOST [U]*/, const int64_t* n_unit /*HOST [U]*/,
                          const int64_t* n_prot /*HOST [U] or NULL = 0*/, int64_t n_units,
                          int64_t* total_centibits /*HOST*/, int64_t* total_weights /*HOST*/);
+
+/*
+ * Salient-weight protection (Sec. 3.5; App. "Salient Weight Protection"): per unit, a
+ * fraction of the weights, those with the largest saliency |w| * s_c, is kept out of the
+ * low-bit quantizer and stored in INT8; Eq. 5 charges them 8 bits each.
+ *
+ * The rate is given in parts per million so that the count is an exact integer:
+ * n_p = floor(n_unit * rate_ppm / 10^6) protected weights in every unit (the same for all
+ * units of a matrix).  -1 if n_unit < 0 or rate_ppm > 10^6.  HOST only.
+ */
+int64_t windq_n_protected(int64_t n_unit, uint32_t rate_ppm);
+
+/*
+ * Select the protected set of every unit: its n_p weights of largest saliency
+ * fp32(|w| * |s_c|) (one fp32 multiply), found exactly by radix selection; weights of
+ * equal saliency are taken in the order of their flat index inside the unit
+ * (local_row * chunk_w + column).
+ *   mask  [rows][cols/8] bytes, dense: bit (c mod 8) of byte c/8 of a row is 1 where
+ *         weight (row, c) is protected.  Every byte of it is written.
+ * Needs rows_per_unit * chunk_w < 2^32.
+ */
+int windq_salient_select(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                         uint32_t rate_ppm, uint8_t* mask /*[rows][cols/8]*/,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Store the protected weights of a mask in INT8 (Sec. 3.5: "stored in INT8"), per unit:
+ *   prot_scale[u] = sigma = fp32(max |w_p| / 127), 0 if below the smallest normal fp32
+ *   prot_codes    [U][n_p] int8: clamp(rne(w * fp32(1/sigma)), -127, 127) of the unit's
+ *                 protected weights in flat-index order (0 when sigma = 0)
+ *   err_prot[u]   sum s_c^2 (w - code * sigma)^2 over them (fp64 sums, fixed order)
+ * `mask` must hold exactly n_p bits per unit (as windq_salient_select writes it for the
+ * same rate); surplus bits of a malformed mask are not stored.
+ */
+int windq_salient_encode(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                         const uint8_t* mask /*[rows][cols/8]*/, uint32_t rate_ppm,
+                         int8_t* prot_codes /*[U][n_p]*/, float* prot_scale /*[U]*/, float* err_prot /*[U]*/,
+                         void* ws, size_t ws_bytes, void* stream);
 
 /* Workspace bytes a call needs for these shapes (0 if the shape is invalid). HOST only. */
 size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, int64_t cols,

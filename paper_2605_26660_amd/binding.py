@@ -16,13 +16,13 @@ LIB_PATH = os.path.join(_PKG_DIR, "libwindq.so")
 
 WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP = range(6)
 WINDQ_F32, WINDQ_BF16 = 0, 1
-CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN = range(4)
+CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT = range(5)
 N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK = 7, 6, 8, 64, 512
 
 EXPORTS = (
     "windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_bytes_per_group",
     "windq_plan_layout", "windq_apply_plan", "windq_effective_bits", "windq_workspace_bytes",
-    "windq_status_str",
+    "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
 )
 
 
@@ -64,10 +64,15 @@ def load(path: str | None = None):
     lib.windq_effective_bits.argtypes = [vp, vp, vp, i64, c.POINTER(i64), c.POINTER(i64)]
     lib.windq_workspace_bytes.argtypes = [i32, i32, i64, i64, i32, i64, i32]
     lib.windq_workspace_bytes.restype = sz
+    u32 = c.c_uint32
+    lib.windq_n_protected.argtypes = [i64, u32]
+    lib.windq_n_protected.restype = i64
+    lib.windq_salient_select.argtypes = [pm, vp, i32, i64, u32, vp, vp, sz, vp]
+    lib.windq_salient_encode.argtypes = [pm, vp, i32, i64, vp, u32, vp, vp, vp, vp, sz, vp]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
-                 "windq_apply_plan", "windq_effective_bits"):
+                 "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -220,3 +225,41 @@ def windq_effective_bits(action: torch.Tensor, n_unit: torch.Tensor, n_prot: tor
     _check(load().windq_effective_bits(action.data_ptr(), n_unit.data_ptr(), _ptr(n_prot), action.numel(),
                                        ctypes.byref(cb), ctypes.byref(nw)), "windq_effective_bits")
     return cb.value, nw.value
+
+
+# ------------------------------------------------------- salient-weight protection
+def windq_n_protected(n_unit: int, rate_ppm: int) -> int:
+    return int(load().windq_n_protected(n_unit, rate_ppm))
+
+
+def windq_salient_select(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, rate_ppm: int,
+                         ws: torch.Tensor | None = None, out: torch.Tensor | None = None):
+    """-> mask u8 [rows x cols/8] on the device: bit (c mod 8) of byte c/8 set where weight (row, c) is protected."""
+    _require_cuda(W, s)
+    mask = out if out is not None else torch.empty(W.shape[0], W.shape[1] // 8, dtype=torch.uint8, device=W.device)
+    ws = _workspace(CALL_SALIENT, W, chunk_w, unit_rows, 1, ws)
+    m = as_mat(W)
+    _check(load().windq_salient_select(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, rate_ppm, mask.data_ptr(),
+                                       ws.data_ptr(), ws.numel(), _stream()), "windq_salient_select")
+    return mask
+
+
+def windq_salient_encode(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, mask: torch.Tensor,
+                         rate_ppm: int, ws: torch.Tensor | None = None, out=None):
+    """-> (prot_codes i8 [U x n_p], prot_scale f32 [U], err_prot f32 [U]) on the device."""
+    _require_cuda(W, s, mask)
+    U, R_u = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    n_p = windq_n_protected(R_u * chunk_w, rate_ppm)
+    if out is None:
+        codes = torch.empty(U, max(n_p, 1), dtype=torch.int8, device=W.device)[:, :n_p]
+        codes = torch.empty(U, n_p, dtype=torch.int8, device=W.device) if n_p > 0 else codes
+        scale = torch.empty(U, dtype=torch.float32, device=W.device)
+        err = torch.empty(U, dtype=torch.float32, device=W.device)
+    else:
+        codes, scale, err = out
+    ws = _workspace(CALL_SALIENT, W, chunk_w, unit_rows, 1, ws)
+    m = as_mat(W)
+    _check(load().windq_salient_encode(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, mask.data_ptr(), rate_ppm,
+                                       codes.data_ptr() if n_p > 0 else None, scale.data_ptr(), err.data_ptr(),
+                                       ws.data_ptr(), ws.numel(), _stream()), "windq_salient_encode")
+    return codes, scale, err

@@ -1,0 +1,510 @@
+// Salient-weight protection (Sec. 3.5; App. "Salient Weight Protection"): per unit, the
+// n_p = floor(rate * n) weights with the largest saliency |w| * s_c are kept out of the
+// low-bit quantizer and stored in INT8; Eq. 5 then charges them 8 bits each.
+//
+// windq_salient_select  finds the protected set EXACTLY: the saliency threshold T of a
+//   unit is the n_p-th largest key, located by most-significant-digit radix selection on
+//   the bit pattern of the fp32 saliency (digits of 11 + 11 + 9 bits, one pass over W per
+//   digit, LDS histograms flushed by integer atomics); weights above T are protected,
+//   and of those equal to T the first (n_p - #above) in flat-index order inside the unit
+//   (counted per tile, prefix over the unit's tiles, then rank inside the tile row by
+//   row).  The result is a bit mask in the layout of W: one byte per 8 columns.
+// windq_salient_encode  stores the protected weights: per unit one symmetric scale
+//   sigma = fp32(max|w_p| / 127), codes clamp(rne(w * fp32(1/sigma)), -127, 127) in
+//   flat-index order, and the activation-weighted error of that INT8 part.
+// Everything is integer or fixed-order fp64: bit-reproducible.  All five passes over W
+// are plain streaming reads; none of this is on the per-step hot path (the mask of a
+// matrix is computed once per protection rate).
+#include <float.h>
+
+#include "windq_common.hpp"
+#include "windq_select.hpp"
+#include "windq_ws.hpp"
+
+namespace windq {
+
+constexpr int SAL_THREADS = 256;
+
+struct SalArgs {
+    const void* W;
+    const float* s;
+    uint8_t* mask;          // [rows][mask_ld] bytes
+    int64_t mask_ld;
+    Geometry g;
+    uint32_t* hist;         // [3][U][FEAT_BINS]
+    uint32_t* prefix;       // [U]  key prefix found so far; after the last digit: the threshold T
+    uint32_t* rank;         // [U]  1-based ascending rank still to find under the prefix
+    uint32_t* cnt;          // [n_tiles][2]  keys above T, keys equal to T
+    uint32_t* eq_before;    // [n_tiles]     ties in earlier tiles of the unit
+    uint32_t* need;         // [U]  ties to protect
+    uint32_t n_p;           // protected weights per unit
+    uint32_t rank0;         // ascending rank of T: n - n_p + 1
+    // encode
+    int8_t* prot_codes;     // [U][n_p]
+    float* prot_scale;      // [U]
+    float* err_prot;        // [U]
+    float* tile_max;        // [n_tiles]
+    uint32_t* row_off;      // [U * R_u]  protected weights in earlier rows of the unit
+    double* err_part;       // [n_tiles]
+};
+
+__host__ __device__ constexpr int sal_shift(int level) { return level == 0 ? 20 : (level == 1 ? 9 : 0); }
+__host__ __device__ constexpr int sal_bits(int level) { return level == 2 ? 9 : 11; }
+
+// Saliency key: the bit pattern of fp32(|w| * |s_c|), one correctly rounded multiply.
+// Non-negative floats order like their bit patterns.
+__device__ __forceinline__ uint32_t sal_key(float w, float sc) { return __float_as_uint(fabsf(w) * fabsf(sc)); }
+
+template <int DT>
+__device__ __forceinline__ void load8g(const void* __restrict__ data, int64_t off, float (&w)[8]) {
+    if (DT == WINDQ_BF16) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(data) + off);
+        w[0] = bf16_bits_to_f32(raw.x & 0xffffu); w[1] = __uint_as_float(raw.x & 0xffff0000u);
+        w[2] = bf16_bits_to_f32(raw.y & 0xffffu); w[3] = __uint_as_float(raw.y & 0xffff0000u);
+        w[4] = bf16_bits_to_f32(raw.z & 0xffffu); w[5] = __uint_as_float(raw.z & 0xffff0000u);
+        w[6] = bf16_bits_to_f32(raw.w & 0xffffu); w[7] = __uint_as_float(raw.w & 0xffff0000u);
+    } else {
+        const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(data) + off);
+        const float4 a = src[0], b = src[1];
+        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+        w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+    }
+}
+
+__global__ __launch_bounds__(256) void sal_fill_u32_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// Clears the mask of a matrix (rows x mask_ld bytes, dense).
+__global__ __launch_bounds__(256) void sal_clear_mask_kernel(uint8_t* __restrict__ mask, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) mask[i] = 0;
+}
+
+// Block-wide sum of a per-thread u32 (all SAL_THREADS threads call it).
+__device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* sh) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t t = 0;
+    for (int w = 0; w < SAL_THREADS / 64; ++w) t += sh[w];
+    return t;
+}
+
+// Histogram of digit `level` of the keys of one tile that carry the unit's prefix.
+template <int DT>
+__global__ __launch_bounds__(SAL_THREADS) void sal_hist_kernel(const SalArgs A, const int level) {
+    __shared__ uint32_t lhist[FEAT_BINS];
+    __shared__ float scol[WINDQ_MAX_CHUNK];
+    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int32_t G = A.g.chunk_w;
+    const int32_t nbins = 1 << sal_bits(level);
+    for (int32_t b = threadIdx.x; b < nbins; b += SAL_THREADS) lhist[b] = 0;
+    for (int32_t c = threadIdx.x; c < G; c += SAL_THREADS) scol[c] = A.s[tc.col0 + c];
+    const uint32_t prefix = level == 0 ? 0u : A.prefix[tc.u];
+    __syncthreads();
+    const int32_t shift = sal_shift(level), bits = sal_bits(level);
+    const uint32_t dmask = (1u << bits) - 1u;
+    const int32_t pieces = G >> 3;
+    const int32_t total = tc.nrows * pieces;
+    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS) {
+        const int32_t r = i / pieces, pc = i - r * pieces;
+        float w[8];
+        load8g<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + pc * 8, w);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t key = sal_key(w[j], scol[pc * 8 + j]);
+            if (level == 0 || (key >> (shift + bits)) == prefix) atomicAdd(&lhist[(key >> shift) & dmask], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t* __restrict__ gh = A.hist + ((size_t)level * (size_t)A.g.U + (size_t)tc.u) * FEAT_BINS;
+    for (int32_t b = threadIdx.x; b < nbins; b += SAL_THREADS) {
+        const uint32_t v = lhist[b];
+        if (v != 0) atomicAdd(&gh[b], v);
+    }
+}
+
+// Per unit: the bin of digit `level` that holds the wanted rank; extends the prefix.
+__global__ __launch_bounds__(SAL_THREADS) void sal_prefix_kernel(const SalArgs A, const int level) {
+    __shared__ uint32_t sh_part[SAL_THREADS];
+    __shared__ uint32_t sh_out[4];
+    const int64_t u = blockIdx.x;
+    const uint32_t rank = level == 0 ? A.rank0 : A.rank[u];
+    const uint32_t prefix = level == 0 ? 0u : A.prefix[u];
+    const uint32_t* h = A.hist + ((size_t)level * (size_t)A.g.U + (size_t)u) * FEAT_BINS;
+    uint32_t bin;
+    uint64_t below;
+    select_bin<SAL_THREADS>(h, 1 << sal_bits(level), rank, sh_part, sh_out, &bin, &below);
+    if (threadIdx.x == 0) {
+        A.prefix[u] = (prefix << sal_bits(level)) | bin;
+        A.rank[u] = rank - (uint32_t)below;
+    }
+}
+
+// Per tile: how many keys lie above the unit's threshold, how many equal it.
+template <int DT>
+__global__ __launch_bounds__(SAL_THREADS) void sal_count_kernel(const SalArgs A) {
+    __shared__ float scol[WINDQ_MAX_CHUNK];
+    __shared__ uint32_t sh[SAL_THREADS / 64];
+    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int32_t G = A.g.chunk_w;
+    for (int32_t c = threadIdx.x; c < G; c += SAL_THREADS) scol[c] = A.s[tc.col0 + c];
+    const uint32_t T = A.prefix[tc.u];
+    __syncthreads();
+    const int32_t pieces = G >> 3;
+    const int32_t total = tc.nrows * pieces;
+    uint32_t gt = 0, eq = 0;
+    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS) {
+        const int32_t r = i / pieces, pc = i - r * pieces;
+        float w[8];
+        load8g<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + pc * 8, w);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t key = sal_key(w[j], scol[pc * 8 + j]);
+            gt += key > T ? 1u : 0u;
+            eq += key == T ? 1u : 0u;
+        }
+    }
+    gt = block_sum_u32(gt, sh);
+    eq = block_sum_u32(eq, sh);
+    if (threadIdx.x == 0) {
+        const size_t idx = (size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t;
+        A.cnt[idx * 2] = gt;
+        A.cnt[idx * 2 + 1] = eq;
+    }
+}
+
+// Exclusive prefix sum over a workgroup, in thread order (all SAL_THREADS threads call it);
+// *total receives the sum.
+__device__ __forceinline__ uint32_t block_exclusive_scan_u32(uint32_t v, uint32_t* sh, uint32_t* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) sh[wave] = inc;
+    __syncthreads();
+    uint32_t excl = inc - v, tot = 0;
+    for (int w = 0; w < SAL_THREADS / 64; ++w) {
+        if (w < wave) excl += sh[w];
+        tot += sh[w];
+    }
+    *total = tot;
+    return excl;
+}
+
+// Per unit: ties in earlier tiles (tile order = row order), and how many ties to protect.
+__global__ __launch_bounds__(SAL_THREADS) void sal_scan_kernel(const SalArgs A) {
+    __shared__ uint32_t sh[SAL_THREADS / 64];
+    const int64_t u = blockIdx.x;
+    const int64_t T = A.g.tiles_per_unit;
+    const size_t base = (size_t)u * (size_t)T;
+    uint32_t carry = 0, gt_total = 0;
+    for (int64_t t0 = 0; t0 < T; t0 += SAL_THREADS) {
+        const int64_t t = t0 + threadIdx.x;
+        const uint32_t eq = t < T ? A.cnt[(base + t) * 2 + 1] : 0u;
+        const uint32_t gt = t < T ? A.cnt[(base + t) * 2] : 0u;
+        uint32_t tot;
+        const uint32_t excl = block_exclusive_scan_u32(eq, sh, &tot);
+        if (t < T) A.eq_before[base + t] = carry + excl;
+        carry += tot;
+        gt_total += block_sum_u32(gt, sh);
+    }
+    if (threadIdx.x == 0) A.need[u] = A.n_p > gt_total ? A.n_p - gt_total : 0u;
+}
+
+// Per tile, one lane per row: the protection bits of the row.  A tie is protected when its
+// rank among the unit's ties, in flat-index order, is below `need`.
+template <int DT>
+__global__ __launch_bounds__(64) void sal_mask_kernel(const SalArgs A) {
+    extern __shared__ char smem[];
+    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int32_t G = A.g.chunk_w;
+    constexpr int EB = Elem<DT>::bytes;
+    const int32_t row_bytes = G * EB + 16;
+    char* tile = smem;
+    float* scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
+    const int lane = threadIdx.x;
+    load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
+    for (int32_t c = lane; c < G; c += 64) scol[c] = A.s[tc.col0 + c];
+    __syncthreads();
+    const uint32_t T = A.prefix[tc.u];
+    const uint32_t need = A.need[tc.u];
+    const bool valid = lane < tc.nrows;
+    const char* wrow = tile + lane * row_bytes;
+    uint32_t eq_row = 0;
+    if (valid) {
+        for (int32_t c = 0; c < G; c += 8) {
+            float w[8];
+            read8<DT>(wrow, c, w);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) eq_row += sal_key(w[j], scol[c + j]) == T ? 1u : 0u;
+        }
+    }
+    uint32_t inc = eq_row;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    uint32_t tie_rank = A.eq_before[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] + (inc - eq_row);
+    if (!valid) return;
+    uint8_t* __restrict__ mrow = A.mask + (tc.row0 + lane) * A.mask_ld + (tc.col0 >> 3);
+    for (int32_t c = 0; c < G; c += 8) {
+        float w[8];
+        read8<DT>(wrow, c, w);
+        uint32_t byte = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t key = sal_key(w[j], scol[c + j]);
+            bool prot = key > T;
+            if (key == T) {
+                prot = tie_rank < need;
+                ++tie_rank;
+            }
+            byte |= (prot ? 1u : 0u) << j;
+        }
+        mrow[c >> 3] = (uint8_t)byte;
+    }
+}
+
+// ---------------------------------------------------------------------------- encode
+// Per tile, one lane per row: protected weights in the row, largest protected magnitude.
+template <int DT>
+__global__ __launch_bounds__(64) void sal_rows_kernel(const SalArgs A) {
+    extern __shared__ char smem[];
+    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int32_t G = A.g.chunk_w;
+    constexpr int EB = Elem<DT>::bytes;
+    const int32_t row_bytes = G * EB + 16;
+    const int lane = threadIdx.x;
+    load_tile_raw<DT>(A.W, A.g.ld, tc, G, smem);
+    __syncthreads();
+    const bool valid = lane < tc.nrows;
+    uint32_t n = 0;
+    float mx = 0.0f;
+    if (valid) {
+        const char* wrow = smem + lane * row_bytes;
+        const uint8_t* __restrict__ mrow = A.mask + (tc.row0 + lane) * A.mask_ld + (tc.col0 >> 3);
+        for (int32_t c = 0; c < G; c += 8) {
+            const uint32_t m = mrow[c >> 3];
+            float w[8];
+            read8<DT>(wrow, c, w);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if ((m >> j) & 1u) {
+                    ++n;
+                    mx = fmaxf(mx, fabsf(w[j]));
+                }
+            }
+        }
+        A.row_off[tc.u * A.g.R_u + tc.lrow0 + lane] = n;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+    if (lane == 0) A.tile_max[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] = mx;
+}
+
+// Per unit: the INT8 scale, and the row counts turned into offsets (exclusive prefix in row order).
+__global__ __launch_bounds__(SAL_THREADS) void sal_unit_kernel(const SalArgs A) {
+    __shared__ uint32_t sh[SAL_THREADS / 64];
+    __shared__ float shm[SAL_THREADS / 64];
+    const int64_t u = blockIdx.x;
+    float mx = 0.0f;
+    for (int64_t t = threadIdx.x; t < A.g.tiles_per_unit; t += SAL_THREADS)
+        mx = fmaxf(mx, A.tile_max[(size_t)u * (size_t)A.g.tiles_per_unit + (size_t)t]);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+    if ((threadIdx.x & 63) == 0) shm[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float m = shm[0];
+        for (int w = 1; w < SAL_THREADS / 64; ++w) m = fmaxf(m, shm[w]);
+        float sg = m / 127.0f;
+        if (!(sg >= FLT_MIN)) sg = 0.0f;
+        A.prot_scale[u] = sg;
+    }
+    uint32_t* __restrict__ ro = A.row_off + u * A.g.R_u;
+    uint32_t carry = 0;
+    for (int64_t r0 = 0; r0 < A.g.R_u; r0 += SAL_THREADS) {
+        const int64_t r = r0 + threadIdx.x;
+        const uint32_t n = r < A.g.R_u ? ro[r] : 0u;
+        uint32_t tot;
+        const uint32_t excl = block_exclusive_scan_u32(n, sh, &tot);
+        if (r < A.g.R_u) ro[r] = carry + excl;
+        carry += tot;
+    }
+}
+
+// Per tile, one lane per row: INT8 codes of the row's protected weights at their place in
+// the unit's stream, and the activation-weighted error of the tile's INT8 part.
+template <int DT>
+__global__ __launch_bounds__(64) void sal_encode_kernel(const SalArgs A) {
+    extern __shared__ char smem[];
+    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int32_t G = A.g.chunk_w;
+    constexpr int EB = Elem<DT>::bytes;
+    const int32_t row_bytes = G * EB + 16;
+    float* scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
+    const int lane = threadIdx.x;
+    load_tile_raw<DT>(A.W, A.g.ld, tc, G, smem);
+    for (int32_t c = lane; c < G; c += 64) scol[c] = A.s[tc.col0 + c];
+    __syncthreads();
+    const float sg = A.prot_scale[tc.u];
+    const float inv = sg > 0.0f ? 1.0f / sg : 0.0f;
+    double err = 0.0;
+    if (lane < tc.nrows) {
+        const char* wrow = smem + lane * row_bytes;
+        const uint8_t* __restrict__ mrow = A.mask + (tc.row0 + lane) * A.mask_ld + (tc.col0 >> 3);
+        uint32_t pos = A.row_off[tc.u * A.g.R_u + tc.lrow0 + lane];
+        int8_t* __restrict__ dst = A.prot_codes + (size_t)tc.u * (size_t)A.n_p;
+        for (int32_t c = 0; c < G; c += 8) {
+            const uint32_t m = mrow[c >> 3];
+            if (m == 0) continue;
+            float w[8];
+            read8<DT>(wrow, c, w);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if ((m >> j) & 1u) {
+                    const float t = w[j] * inv;
+                    const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -127.0f, 127.0f);
+                    if (pos < A.n_p) dst[pos] = (int8_t)(int32_t)q;     // a mask with more bits than n_p writes nothing past the unit
+                    ++pos;
+                    const double d = (double)w[j] - (double)q * (double)sg;
+                    const double a = (double)scol[c + j] * (double)scol[c + j];
+                    err = fma(a * d, d, err);
+                }
+            }
+        }
+    }
+    err = wave_sum(err);
+    if (lane == 0) A.err_part[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] = err;
+}
+
+__global__ __launch_bounds__(64) void sal_err_kernel(const SalArgs A) {
+    const int64_t u = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    double e = 0.0;
+    for (int64_t t = 0; t < A.g.tiles_per_unit; ++t) e += A.err_part[(size_t)u * (size_t)A.g.tiles_per_unit + (size_t)t];
+    A.err_prot[u] = (float)e;
+}
+
+static size_t sal_tile_lds(int32_t dtype, int32_t chunk_w) {
+    return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
+}
+
+static void carve(SalArgs& A, void* ws, const SalientLayout& L) {
+    char* base = static_cast<char*>(ws);
+    A.hist = reinterpret_cast<uint32_t*>(base + L.hist);
+    A.prefix = reinterpret_cast<uint32_t*>(base + L.prefix);
+    A.rank = reinterpret_cast<uint32_t*>(base + L.rank);
+    A.cnt = reinterpret_cast<uint32_t*>(base + L.cnt);
+    A.eq_before = reinterpret_cast<uint32_t*>(base + L.eq_before);
+    A.need = reinterpret_cast<uint32_t*>(base + L.need);
+    A.tile_max = reinterpret_cast<float*>(base + L.tile_max);
+    A.row_off = reinterpret_cast<uint32_t*>(base + L.row_off);
+    A.err_part = reinterpret_cast<double*>(base + L.err_part);
+}
+
+template <int DT>
+static int launch_select(const SalArgs& A, hipStream_t hs, size_t lds) {
+    const dim3 tiles((unsigned)A.g.n_tiles), units((unsigned)A.g.U);
+    const int64_t n_hist = (int64_t)3 * A.g.U * FEAT_BINS;
+    hipLaunchKernelGGL(sal_fill_u32_kernel, dim3((unsigned)((n_hist + 255) / 256)), dim3(256), 0, hs, A.hist, n_hist, 0u);
+    for (int level = 0; level < 3; ++level) {
+        hipLaunchKernelGGL(sal_hist_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, A, level);
+        hipLaunchKernelGGL(sal_prefix_kernel, units, dim3(SAL_THREADS), 0, hs, A, level);
+    }
+    hipLaunchKernelGGL(sal_count_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, A);
+    hipLaunchKernelGGL(sal_scan_kernel, units, dim3(SAL_THREADS), 0, hs, A);
+    int st = ensure_lds(reinterpret_cast<const void*>(&sal_mask_kernel<DT>), lds);
+    if (st != WINDQ_OK) return st;
+    hipLaunchKernelGGL(sal_mask_kernel<DT>, tiles, dim3(64), lds, hs, A);
+    return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+}
+
+template <int DT>
+static int launch_encode(const SalArgs& A, hipStream_t hs, size_t lds) {
+    const dim3 tiles((unsigned)A.g.n_tiles), units((unsigned)A.g.U);
+    int st = ensure_lds(reinterpret_cast<const void*>(&sal_rows_kernel<DT>), lds);
+    if (st != WINDQ_OK) return st;
+    st = ensure_lds(reinterpret_cast<const void*>(&sal_encode_kernel<DT>), lds);
+    if (st != WINDQ_OK) return st;
+    hipLaunchKernelGGL(sal_rows_kernel<DT>, tiles, dim3(64), lds, hs, A);
+    hipLaunchKernelGGL(sal_unit_kernel, units, dim3(SAL_THREADS), 0, hs, A);
+    hipLaunchKernelGGL(sal_encode_kernel<DT>, tiles, dim3(64), lds, hs, A);
+    hipLaunchKernelGGL(sal_err_kernel, units, dim3(64), 0, hs, A);
+    return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+}
+
+}  // namespace windq
+
+using namespace windq;
+
+extern "C" int64_t windq_n_protected(int64_t n_unit, uint32_t rate_ppm) {
+    if (n_unit < 0 || rate_ppm > 1000000u) return -1;
+    // n * rate fits 64 bits for every n the kernels accept (n < 2^32)
+    return (int64_t)(((unsigned __int128)(uint64_t)n_unit * rate_ppm) / 1000000u);
+}
+
+static int salient_common(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, uint32_t rate_ppm,
+                          const uint8_t* mask, void* ws, size_t ws_bytes, SalArgs* A, SalientLayout* L) {
+    const int st = make_geometry(W, chunk_w, unit_rows, &A->g);
+    if (st != WINDQ_OK) return st;
+    if (s == nullptr || mask == nullptr || rate_ppm > 1000000u) return WINDQ_EINVAL;
+    if ((uint64_t)A->g.R_u * (uint64_t)chunk_w > (uint64_t)0xffffffffu) return WINDQ_ESHAPE;   // u32 counts
+    *L = salient_layout(A->g);
+    if (ws == nullptr || ws_bytes < L->total || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
+    A->W = W->data;
+    A->s = s;
+    A->mask = const_cast<uint8_t*>(mask);
+    A->mask_ld = W->cols / 8;
+    const uint64_t n = (uint64_t)A->g.R_u * (uint64_t)chunk_w;
+    A->n_p = (uint32_t)windq_n_protected((int64_t)n, rate_ppm);
+    A->rank0 = (uint32_t)(n - A->n_p + 1);
+    A->prot_codes = nullptr;
+    A->prot_scale = nullptr;
+    A->err_prot = nullptr;
+    carve(*A, ws, *L);
+    return WINDQ_OK;
+}
+
+extern "C" int windq_salient_select(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
+                                    uint32_t rate_ppm, uint8_t* mask, void* ws, size_t ws_bytes, void* stream) {
+    SalArgs A;
+    SalientLayout L;
+    const int st = salient_common(W, s, chunk_w, unit_rows, rate_ppm, mask, ws, ws_bytes, &A, &L);
+    if (st != WINDQ_OK) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (A.n_p == 0) {
+        const int64_t n = W->rows * A.mask_ld;
+        hipLaunchKernelGGL(sal_clear_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, hs, mask, n);
+        return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+    }
+    const size_t lds = sal_tile_lds(W->dtype, chunk_w);
+    return W->dtype == WINDQ_BF16 ? launch_select<WINDQ_BF16>(A, hs, lds) : launch_select<WINDQ_F32>(A, hs, lds);
+}
+
+extern "C" int windq_salient_encode(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
+                                    const uint8_t* mask, uint32_t rate_ppm, int8_t* prot_codes, float* prot_scale,
+                                    float* err_prot, void* ws, size_t ws_bytes, void* stream) {
+    SalArgs A;
+    SalientLayout L;
+    const int st = salient_common(W, s, chunk_w, unit_rows, rate_ppm, mask, ws, ws_bytes, &A, &L);
+    if (st != WINDQ_OK) return st;
+    if (prot_scale == nullptr || err_prot == nullptr) return WINDQ_EINVAL;
+    if (prot_codes == nullptr && A.n_p != 0) return WINDQ_EINVAL;
+    A.prot_codes = prot_codes;
+    A.prot_scale = prot_scale;
+    A.err_prot = err_prot;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const size_t lds = sal_tile_lds(W->dtype, chunk_w);
+    return W->dtype == WINDQ_BF16 ? launch_encode<WINDQ_BF16>(A, hs, lds) : launch_encode<WINDQ_F32>(A, hs, lds);
+}

@@ -30,6 +30,7 @@
 
 #include "windq_common.hpp"
 #include "windq_ws.hpp"
+#include "windq_select.hpp"
 
 namespace windq {
 
@@ -106,55 +107,6 @@ __device__ __forceinline__ double block_sum(double v, double* red) {
     return t;
 }
 
-// Find, in histogram h of nbins (<= FEAT_BINS) bins, the bin that holds the 1-based `rank`;
-// returns the bin and the number of keys in lower bins.  All FT_THREADS threads call it.
-// Counts fit 32 bits (a unit has fewer than 2^32 weights).  Each thread owns up to 8
-// consecutive bins; an exclusive scan over threads (shuffles inside a wavefront, LDS
-// across the four) finds the one thread whose bins straddle the rank.
-__device__ __forceinline__ void select_bin(const uint32_t* __restrict__ h, int nbins, uint64_t rank64,
-                                           uint32_t* sh_part, uint32_t* sh_out, uint32_t* bin_out,
-                                           uint64_t* below_out) {
-    constexpr int PER = FEAT_BINS / FT_THREADS;
-    const uint32_t rank = (uint32_t)rank64;
-    const int b0 = threadIdx.x * PER;
-    uint32_t v[PER];
-    uint32_t local = 0;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        v[j] = b0 + j < nbins ? h[b0 + j] : 0u;
-        local += v[j];
-    }
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t inc = local;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t t = __shfl_up(inc, d, 64);
-        if (lane >= d) inc += t;
-    }
-    __syncthreads();
-    if (lane == 63) sh_part[wave] = inc;
-    __syncthreads();
-    uint32_t excl = inc - local;
-    for (int w = 0; w < wave; ++w) excl += sh_part[w];
-    if (excl < rank && rank <= excl + local) {
-        uint32_t cum = excl;
-        int bin = b0;
-#pragma unroll
-        for (int j = 0; j < PER; ++j) {
-            if (cum < rank && rank <= cum + v[j]) {
-                bin = b0 + j;
-                break;
-            }
-            cum += v[j];
-        }
-        sh_out[0] = (uint32_t)bin;
-        sh_out[1] = cum;
-    }
-    __syncthreads();
-    *bin_out = sh_out[0];
-    *below_out = (uint64_t)sh_out[1];
-}
-
 // Key prefix of the wanted rank after digits 0 .. upto-1, from the finished histograms of
 // unit u, and the rank still to find under that prefix.
 template <int DT>
@@ -166,7 +118,7 @@ __device__ __forceinline__ void select_prefix(const FeatArgs& A, int64_t u, int 
         const uint32_t* h = A.hist + ((size_t)l * (size_t)A.g.U + (size_t)u) * FEAT_BINS;
         uint32_t bin;
         uint64_t below;
-        select_bin(h, 1 << level_bits<DT>(l), rank, sh_part, sh_out, &bin, &below);
+        select_bin<FT_THREADS>(h, 1 << level_bits<DT>(l), rank, sh_part, sh_out, &bin, &below);
         prefix = (prefix << level_bits<DT>(l)) | bin;
         rank -= below;
     }
@@ -430,7 +382,7 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatArgs 
         select_prefix<DT>(A, u, 1, sh_part, sh_out, &e0, &rank1);
         const uint32_t* h0 = A.hist + (size_t)u * FEAT_BINS;
         const uint32_t* h1 = A.hist + ((size_t)A.g.U + (size_t)u) * FEAT_BINS;
-        select_bin(h1, 16, rank1, sh_part, sh_out, &l1, &below);
+        select_bin<FT_THREADS>(h1, 16, rank1, sh_part, sh_out, &l1, &below);
         // Key of 0.5 * P99: one exponent step down, or half the key where keys are linear in
         // the value (below 256: subnormals and the first binade).
         const uint32_t pk = (e0 << 4) | l1;

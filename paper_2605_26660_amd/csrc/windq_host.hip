@@ -133,6 +133,7 @@ size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, in
             if (K < 1 || K > WINDQ_MAX_CLIP) return 0;
             return fit_score_ws_bytes(g, K);
         case WINDQ_CALL_APPLY_PLAN: return apply_ws_bytes(g);
+        case WINDQ_CALL_SALIENT: return salient_ws_bytes(g);
         default: return 0;
     }
 }

@@ -45,6 +45,34 @@ inline FeatLayout features_layout(const Geometry& g) {
 }
 inline size_t features_ws_bytes(const Geometry& g, int32_t /*dtype*/) { return features_layout(g).total; }
 
+// ---- salient-weight protection (select and encode share one layout)
+//   hist      [3][U][FEAT_BINS] u32   histograms of the three saliency-key digits
+//   prefix, rank, need  [U] u32       selection state per unit
+//   cnt       [n_tiles][2] u32        keys above / equal to the threshold per tile
+//   eq_before [n_tiles] u32           ties in earlier tiles of the unit
+//   tile_max  [n_tiles] f32           largest protected magnitude per tile
+//   row_off   [U * R_u] u32           protected weights in earlier rows of the unit
+//   err_part  [n_tiles] f64           INT8 error per tile
+struct SalientLayout {
+    size_t hist, prefix, rank, need, cnt, eq_before, tile_max, row_off, err_part, total;
+};
+inline SalientLayout salient_layout(const Geometry& g) {
+    SalientLayout L;
+    size_t pos = 0;
+    L.hist = pos;      pos = round_up(pos + (size_t)3 * g.U * FEAT_BINS * sizeof(uint32_t), 256);
+    L.prefix = pos;    pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.rank = pos;      pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.need = pos;      pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.cnt = pos;       pos = round_up(pos + (size_t)g.n_tiles * 2 * sizeof(uint32_t), 256);
+    L.eq_before = pos; pos = round_up(pos + (size_t)g.n_tiles * sizeof(uint32_t), 256);
+    L.tile_max = pos;  pos = round_up(pos + (size_t)g.n_tiles * sizeof(float), 256);
+    L.row_off = pos;   pos = round_up(pos + (size_t)g.U * (size_t)g.R_u * sizeof(uint32_t), 256);
+    L.err_part = pos;  pos = round_up(pos + (size_t)g.n_tiles * sizeof(double), 256);
+    L.total = pos;
+    return L;
+}
+inline size_t salient_ws_bytes(const Geometry& g) { return salient_layout(g).total; }
+
 // ---- apply_plan needs no scratch; a token size keeps "ws != NULL" uniform across calls
 inline size_t apply_ws_bytes(const Geometry&) { return 256; }
 

@@ -113,6 +113,55 @@ def run_step(wq, torch, cg, xs, mats, unit_rows, timer=NoTimer()):
     return total_cb, total_n
 
 
+def protected_pass(wq, torch, cg, xs, mats, unit_rows, ppm, reps):
+    """The same block with salient-weight protection at `ppm` parts per million: mask selection and INT8
+    encoding once per matrix, then fit+score and apply-plan under the mask.  Timed per call with events,
+    outside the step that `value` is quoted on."""
+    timer = CallTimer(torch)
+    extra = []
+    for m in mats:
+        sp = m["spec"]
+        n_p = wq.windq_n_protected(m["R_u"] * G, ppm)
+        extra.append(dict(
+            mask=torch.empty(sp.rows, sp.cols // 8, dtype=torch.uint8, device=m["W"].device),
+            ws=torch.empty(wq.workspace_bytes(wq.CALL_SALIENT, wq.WINDQ_BF16, sp.rows, sp.cols, G, unit_rows),
+                           dtype=torch.uint8, device=m["W"].device),
+            out=(torch.empty(m["U"], max(n_p, 1), dtype=torch.int8, device=m["W"].device),
+                 torch.empty(m["U"], dtype=torch.float32, device=m["W"].device),
+                 torch.empty(m["U"], dtype=torch.float32, device=m["W"].device)),
+            n_prot=torch.full((m["U"],), n_p, dtype=torch.int64)))
+    total_cb = total_n = 0
+    for rep in range(reps + 1):
+        if rep == 1:
+            timer = CallTimer(torch)          # the first round is the warm-up
+        total_cb = total_n = 0
+        for m, e in zip(mats, extra):
+            s = xs[m["spec"].x_key]["s"]
+            timer.time("salient_select", lambda: wq.windq_salient_select(m["W"], s, G, unit_rows, ppm, ws=e["ws"], out=e["mask"]))
+            timer.time("salient_encode", lambda: wq.windq_salient_encode(m["W"], s, G, unit_rows, e["mask"], ppm, ws=e["ws"], out=e["out"]))
+            timer.time("fit_score_all_bits_prot", lambda: wq.windq_fit_score_all_bits(
+                m["W"], s, G, unit_rows, cg, ws=m["ws"], out=(m["err"], m["clip_idx"], m["ref"]), mask=e["mask"]))
+            timer.time("apply_plan_prot", lambda: wq.windq_apply_plan(
+                m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"], ws=m["ws"],
+                out=(m["scale"], m["offset"]), mask=e["mask"]))
+            cb, n = wq.windq_effective_bits(m["action"], m["n_unit"], e["n_prot"])
+            total_cb += cb
+            total_n += n
+    torch.cuda.synchronize()
+    n_weights = sum(m["spec"].rows * m["spec"].cols for m in mats)
+    res = {"rate_ppm": ppm, "avg_bits": total_cb / (100.0 * total_n)}
+    for name in ("salient_select", "salient_encode", "fit_score_all_bits_prot", "apply_plan_prot"):
+        ms = timer.ms(name)
+        per = len(ms) // reps
+        steps = sorted(sum(ms[i * per:(i + 1) * per]) for i in range(reps))
+        med = steps[len(steps) // 2]
+        res[name] = {"ms_per_block_median": med, "weight_GBps": n_weights * 2 / (med * 1e-3) / 1e9,
+                     "pct_hbm_peak": 100.0 * n_weights * 2 / (med * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    fit = res["fit_score_all_bits_prot"]["ms_per_block_median"]
+    res["fit_score_all_bits_prot"]["TFLOPs"] = fit_score_flops_per_weight(K) * n_weights / (fit * 1e-3) / 1e12
+    return res
+
+
 def clip_sweep(wq, synth, torch, mats, xs, unit_rows, reps=3):
     """fit+score alone at growing clip grids: where the call leaves the HBM roofline for the ALU one."""
     n_weights = sum(m["spec"].rows * m["spec"].cols for m in mats)
@@ -169,6 +218,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--unit-rows", type=int, default=0, help="0 = the paper's units (all rows); 128 = 128 x G tiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--protect-ppm", type=int, default=30000,
+                    help="also time the block under salient-weight protection at this rate (parts per million; 0 = skip)")
     ap.add_argument("--clip-sweep", action="store_true",
                     help="also time fit+score alone at 1..40 clip ratios (where it leaves the HBM roofline)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -259,6 +310,8 @@ def main():
                      "avg_launch_ms": fit_ms / len(mats),
                      "flops_per_weight": fit_score_flops_per_weight(K)},
     }
+    if args.protect_ppm > 0:
+        out["protected"] = protected_pass(wq, torch, cg, xs, mats, args.unit_rows, args.protect_ppm, 5)
     if args.clip_sweep:
         out["clip_sweep"] = clip_sweep(wq, synth, torch, mats, xs, args.unit_rows)
     if not args.no_cpu_baseline:

@@ -212,6 +212,28 @@ int windq_salient_encode(const windq_mat* W, const float* s /*[cols]*/, int32_t 
                          int8_t* prot_codes /*[U][n_p]*/, float* prot_scale /*[U]*/, float* err_prot /*[U]*/,
                          void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * windq_fit_score_all_bits and windq_apply_plan under a protection mask (Sec. 3.5: the
+ * remaining weights use the selected bit-width).  Protected weights take no part in the
+ * fit: a group's min, max and mean |w| run over its kept weights (mean = sum / number
+ * kept; a group with none kept has scale = offset = 0), and err / ref_energy sum over kept
+ * weights only.  The code stream keeps its dense layout: the slot of a protected weight
+ * holds 0.  Everything else is as in the unmasked calls; `mask` as written by
+ * windq_salient_select, never NULL.  Workspaces as WINDQ_CALL_FIT_SCORE / _APPLY_PLAN.
+ */
+int windq_fit_score_all_bits_prot(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                                  const uint8_t* mask /*[rows][cols/8]*/,
+                                  const float* clip_grid /*HOST [K]*/, int32_t K,
+                                  float* err /*[U][6]*/, uint8_t* clip_idx /*[U][4]*/, float* ref_energy /*[U] or NULL*/,
+                                  void* ws, size_t ws_bytes, void* stream);
+int windq_apply_plan_prot(const windq_mat* W, int32_t chunk_w, int64_t unit_rows,
+                          const uint8_t* mask /*[rows][cols/8]*/,
+                          const uint8_t* action /*[U]*/, const uint8_t* clip_idx /*[U][4] or NULL*/,
+                          const float* clip_grid /*HOST [K]*/, int32_t K,
+                          const int64_t* code_off /*[U+1]*/, uint8_t* codes, size_t codes_bytes,
+                          float* scale /*[U*R_u]*/, float* offset /*[U*R_u]*/,
+                          void* ws, size_t ws_bytes, void* stream);
+
 /* Workspace bytes a call needs for these shapes (0 if the shape is invalid). HOST only. */
 size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, int64_t cols,
                              int32_t chunk_w, int64_t unit_rows, int32_t K);

@@ -23,6 +23,7 @@ EXPORTS = (
     "windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_bytes_per_group",
     "windq_plan_layout", "windq_apply_plan", "windq_effective_bits", "windq_workspace_bytes",
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
+    "windq_fit_score_all_bits_prot", "windq_apply_plan_prot",
 )
 
 
@@ -69,10 +70,13 @@ def load(path: str | None = None):
     lib.windq_n_protected.restype = i64
     lib.windq_salient_select.argtypes = [pm, vp, i32, i64, u32, vp, vp, sz, vp]
     lib.windq_salient_encode.argtypes = [pm, vp, i32, i64, vp, u32, vp, vp, vp, vp, sz, vp]
+    lib.windq_fit_score_all_bits_prot.argtypes = [pm, vp, i32, i64, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    lib.windq_apply_plan_prot.argtypes = [pm, i32, i64, vp, vp, vp, vp, i32, vp, vp, sz, vp, vp, vp, sz, vp]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
-                 "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode"):
+                 "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode",
+                 "windq_fit_score_all_bits_prot", "windq_apply_plan_prot"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -160,9 +164,10 @@ def windq_unit_features(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_row
 
 
 def windq_fit_score_all_bits(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor,
-                             ws: torch.Tensor | None = None, out=None):
-    """clip_grid: host float32 tensor [K].  -> (err [U x 6] f32, clip_idx [U x 4] u8, ref_energy [U] f32)."""
-    _require_cuda(W, s)
+                             ws: torch.Tensor | None = None, out=None, mask: torch.Tensor | None = None):
+    """clip_grid: host float32 tensor [K].  -> (err [U x 6] f32, clip_idx [U x 4] u8, ref_energy [U] f32).
+    With `mask` (device u8 [rows x cols/8]) this is windq_fit_score_all_bits_prot."""
+    _require_cuda(W, s, mask)
     assert not clip_grid.is_cuda and clip_grid.dtype == torch.float32 and clip_grid.is_contiguous()
     K = clip_grid.numel()
     U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
@@ -174,9 +179,15 @@ def windq_fit_score_all_bits(W: torch.Tensor, s: torch.Tensor, chunk_w: int, uni
         err, clip_idx, ref = out
     ws = _workspace(CALL_FIT_SCORE, W, chunk_w, unit_rows, K, ws)
     m = as_mat(W)
-    _check(load().windq_fit_score_all_bits(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, clip_grid.data_ptr(), K,
-                                           err.data_ptr(), clip_idx.data_ptr(), ref.data_ptr(), ws.data_ptr(),
-                                           ws.numel(), _stream()), "windq_fit_score_all_bits")
+    if mask is None:
+        _check(load().windq_fit_score_all_bits(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, clip_grid.data_ptr(),
+                                               K, err.data_ptr(), clip_idx.data_ptr(), ref.data_ptr(), ws.data_ptr(),
+                                               ws.numel(), _stream()), "windq_fit_score_all_bits")
+    else:
+        _check(load().windq_fit_score_all_bits_prot(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, mask.data_ptr(),
+                                                    clip_grid.data_ptr(), K, err.data_ptr(), clip_idx.data_ptr(),
+                                                    ref.data_ptr(), ws.data_ptr(), ws.numel(), _stream()),
+               "windq_fit_score_all_bits_prot")
     return err, clip_idx, ref
 
 
@@ -195,10 +206,10 @@ def windq_plan_layout(action: torch.Tensor, rows_per_unit: int, chunk_w: int) ->
 
 def windq_apply_plan(W: torch.Tensor, chunk_w: int, unit_rows: int, action: torch.Tensor, clip_idx, clip_grid,
                      code_off: torch.Tensor, codes: torch.Tensor | None = None, ws: torch.Tensor | None = None,
-                     out=None):
+                     out=None, mask: torch.Tensor | None = None):
     """action [U] u8, clip_idx [U x 4] u8 or None, code_off [U+1] i64: device tensors; clip_grid host f32 or None.
     -> (codes u8 [code_off[U]], scale f32 [U*R_u], offset f32 [U*R_u]) on the device."""
-    _require_cuda(W, action, clip_idx, code_off, codes)
+    _require_cuda(W, action, clip_idx, code_off, codes, mask)
     U, R_u = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
     if codes is None:
         total = int(code_off[-1].item())
@@ -211,10 +222,14 @@ def windq_apply_plan(W: torch.Tensor, chunk_w: int, unit_rows: int, action: torc
     K = 0 if clip_grid is None else clip_grid.numel()
     ws = _workspace(CALL_APPLY_PLAN, W, chunk_w, unit_rows, 1, ws)
     m = as_mat(W)
-    _check(load().windq_apply_plan(ctypes.byref(m), chunk_w, unit_rows, action.data_ptr(), _ptr(clip_idx),
-                                   None if clip_grid is None else clip_grid.data_ptr(), K, code_off.data_ptr(),
-                                   codes.data_ptr(), codes.numel(), scale.data_ptr(), offset.data_ptr(),
-                                   ws.data_ptr(), ws.numel(), _stream()), "windq_apply_plan")
+    tail = (action.data_ptr(), _ptr(clip_idx), None if clip_grid is None else clip_grid.data_ptr(), K,
+            code_off.data_ptr(), codes.data_ptr(), codes.numel(), scale.data_ptr(), offset.data_ptr(),
+            ws.data_ptr(), ws.numel(), _stream())
+    if mask is None:
+        _check(load().windq_apply_plan(ctypes.byref(m), chunk_w, unit_rows, *tail), "windq_apply_plan")
+    else:
+        _check(load().windq_apply_plan_prot(ctypes.byref(m), chunk_w, unit_rows, mask.data_ptr(), *tail),
+               "windq_apply_plan_prot")
     return codes, scale, offset
 
 

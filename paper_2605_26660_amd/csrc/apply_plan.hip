@@ -30,6 +30,8 @@ constexpr int AP_THREADS = 64;
 
 struct ApplyArgs {
     const void* W;
+    const uint8_t* mask;       // protection mask [rows][cols/8] (masked kernel only)
+    int64_t mask_ld;
     const uint8_t* action;
     const uint8_t* clip_idx;   // may be null
     const int64_t* code_off;
@@ -76,17 +78,35 @@ __device__ __forceinline__ void store_codes8(uint8_t* dst, const uint32_t (&c)[8
     }
 }
 
-// Uniform BITS-bit quantizer of one group, normative fp32 steps.
+// Uniform BITS-bit quantizer of one group, normative fp32 steps.  mrow: the row's protection
+// bits (null: none); protected weights stay out of min/max and their code slot holds 0.
 template <int DT, int BITS>
-__device__ __forceinline__ void quantize_uniform(const char* wrow, int32_t G, float p, uint8_t* dst, float* scale_out,
-                                                 float* offset_out) {
+__device__ __forceinline__ void quantize_uniform(const char* wrow, const uint8_t* __restrict__ mrow, int32_t G, float p,
+                                                 uint8_t* dst, float* scale_out, float* offset_out) {
     float w[8];
-    read8<DT>(wrow, 0, w);
-    float mn = w[0], mx = w[0];
-    for (int32_t c = 0; c < G; c += 8) {
-        read8<DT>(wrow, c, w);
-        mn = fminf(fminf(fminf(mn, w[0]), fminf(w[1], w[2])), fminf(fminf(w[3], w[4]), fminf(w[5], fminf(w[6], w[7]))));
-        mx = fmaxf(fmaxf(fmaxf(mx, w[0]), fmaxf(w[1], w[2])), fmaxf(fmaxf(w[3], w[4]), fmaxf(w[5], fmaxf(w[6], w[7]))));
+    float mn, mx;
+    if (mrow == nullptr) {
+        read8<DT>(wrow, 0, w);
+        mn = mx = w[0];
+        for (int32_t c = 0; c < G; c += 8) {
+            read8<DT>(wrow, c, w);
+            mn = fminf(fminf(fminf(mn, w[0]), fminf(w[1], w[2])), fminf(fminf(w[3], w[4]), fminf(w[5], fminf(w[6], w[7]))));
+            mx = fmaxf(fmaxf(fmaxf(mx, w[0]), fmaxf(w[1], w[2])), fmaxf(fmaxf(w[3], w[4]), fmaxf(w[5], fmaxf(w[6], w[7]))));
+        }
+    } else {
+        mn = INFINITY;
+        mx = -INFINITY;
+        for (int32_t c = 0; c < G; c += 8) {
+            read8<DT>(wrow, c, w);
+            const uint32_t m = mrow[c >> 3];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool kept = ((m >> j) & 1u) == 0u;
+                mn = fminf(mn, kept ? w[j] : INFINITY);
+                mx = fmaxf(mx, kept ? w[j] : -INFINITY);
+            }
+        }
+        if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
     }
     const float qmax = (float)((1 << BITS) - 1);
     const float lo = p * mn;
@@ -100,34 +120,40 @@ __device__ __forceinline__ void quantize_uniform(const char* wrow, int32_t G, fl
     *offset_out = lo;
     for (int32_t c = 0; c < G; c += 8) {
         read8<DT>(wrow, c, w);
+        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;     // read before the codes overwrite the row in place
         uint32_t code[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float u = w[j] - lo;
             const float t = u * inv;
             const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, qmax);
-            code[j] = (uint32_t)q;
+            code[j] = ((m >> j) & 1u) != 0u ? 0u : (uint32_t)q;
         }
         store_codes8<BITS>(dst + (c >> 3) * BITS, code);
     }
 }
 
-// Sum of |w| of a group in fp64 in column order (exact for bf16 inputs).
+// Mean |w| of a group as stored: the fp64 sum in column order (exact for bf16 inputs) over the
+// kept weights, divided by their number, rounded to fp32; 0 when none is kept.
 template <int DT>
-__device__ __forceinline__ double group_abs_sum(const char* wrow, int32_t G) {
+__device__ __forceinline__ float group_abs_mean(const char* wrow, const uint8_t* __restrict__ mrow, int32_t G) {
     double S1 = 0.0;
+    int32_t n = G;
     for (int32_t c = 0; c < G; c += 8) {
         float w[8];
         read8<DT>(wrow, c, w);
+        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
+        n -= __builtin_popcount(m);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) S1 += (double)fabsf(w[j]);
+        for (int j = 0; j < 8; ++j) S1 += ((m >> j) & 1u) != 0u ? 0.0 : (double)fabsf(w[j]);
     }
-    return S1;
+    return n > 0 ? (float)(S1 / (double)n) : 0.0f;
 }
 
 template <int DT>
-__device__ __forceinline__ void quantize_ternary(const char* wrow, int32_t G, uint8_t* dst, float* scale_out) {
-    float gamma = (float)(group_abs_sum<DT>(wrow, G) / (double)G);
+__device__ __forceinline__ void quantize_ternary(const char* wrow, const uint8_t* __restrict__ mrow, int32_t G,
+                                                 uint8_t* dst, float* scale_out) {
+    float gamma = group_abs_mean<DT>(wrow, mrow, G);
     const bool ok = gamma >= FLT_MIN;
     gamma = ok ? gamma : 0.0f;
     const float inv = ok ? 1.0f / gamma : 0.0f;
@@ -137,11 +163,12 @@ __device__ __forceinline__ void quantize_ternary(const char* wrow, int32_t G, ui
     for (int32_t c = 0; c < G; c += 8) {
         float w[8];
         read8<DT>(wrow, c, w);
+        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float t = w[j] * inv;
             const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -1.0f, 1.0f);
-            byte += (uint32_t)((int32_t)q + 1) * mul;
+            byte += (((m >> j) & 1u) != 0u ? 0u : (uint32_t)((int32_t)q + 1)) * mul;
             mul *= 3;
             if (mul == 243) {
                 dst[nb++] = (uint8_t)byte;
@@ -154,15 +181,17 @@ __device__ __forceinline__ void quantize_ternary(const char* wrow, int32_t G, ui
 }
 
 template <int DT>
-__device__ __forceinline__ void quantize_binary(const char* wrow, int32_t G, uint8_t* dst, float* scale_out) {
-    *scale_out = (float)(group_abs_sum<DT>(wrow, G) / (double)G);
+__device__ __forceinline__ void quantize_binary(const char* wrow, const uint8_t* __restrict__ mrow, int32_t G,
+                                                uint8_t* dst, float* scale_out) {
+    *scale_out = group_abs_mean<DT>(wrow, mrow, G);
     for (int32_t c = 0; c < G; c += 8) {
         float w[8];
         read8<DT>(wrow, c, w);
+        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
         uint32_t byte = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) byte |= (w[j] >= 0.0f ? 1u : 0u) << j;
-        dst[c >> 3] = (uint8_t)byte;
+        dst[c >> 3] = (uint8_t)(byte & ~m);
     }
 }
 
@@ -205,14 +234,16 @@ __global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyArgs 
             p = A.grid.p[k];
         }
         uint8_t* dst = reinterpret_cast<uint8_t*>(wrow);   // packed in place, behind the read position
+        const uint8_t* __restrict__ mrow =
+            A.mask != nullptr ? A.mask + (tc.row0 + lane) * A.mask_ld + (tc.col0 >> 3) : nullptr;
         float sc = 0.0f, of = 0.0f;
         switch (a) {
-            case 1: quantize_uniform<DT, 8>(wrow, G, p, dst, &sc, &of); break;
-            case 2: quantize_uniform<DT, 4>(wrow, G, p, dst, &sc, &of); break;
-            case 3: quantize_uniform<DT, 3>(wrow, G, p, dst, &sc, &of); break;
-            case 4: quantize_uniform<DT, 2>(wrow, G, p, dst, &sc, &of); break;
-            case 5: quantize_ternary<DT>(wrow, G, dst, &sc); break;
-            default: quantize_binary<DT>(wrow, G, dst, &sc); break;
+            case 1: quantize_uniform<DT, 8>(wrow, mrow, G, p, dst, &sc, &of); break;
+            case 2: quantize_uniform<DT, 4>(wrow, mrow, G, p, dst, &sc, &of); break;
+            case 3: quantize_uniform<DT, 3>(wrow, mrow, G, p, dst, &sc, &of); break;
+            case 4: quantize_uniform<DT, 2>(wrow, mrow, G, p, dst, &sc, &of); break;
+            case 5: quantize_ternary<DT>(wrow, mrow, G, dst, &sc); break;
+            default: quantize_binary<DT>(wrow, mrow, G, dst, &sc); break;
         }
         A.scale[gidx] = sc;
         A.offset[gidx] = of;
@@ -616,10 +647,10 @@ __global__ __launch_bounds__(APS_THREADS, 8) void apply_plan_split_kernel(const 
 
 using namespace windq;
 
-extern "C" int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t unit_rows, const uint8_t* action,
-                                const uint8_t* clip_idx, const float* clip_grid, int32_t K, const int64_t* code_off,
-                                uint8_t* codes, size_t codes_bytes, float* scale, float* offset, void* ws,
-                                size_t ws_bytes, void* stream) {
+static int apply_plan_impl(const windq_mat* W, int32_t chunk_w, int64_t unit_rows, const uint8_t* mask,
+                           const uint8_t* action, const uint8_t* clip_idx, const float* clip_grid, int32_t K,
+                           const int64_t* code_off, uint8_t* codes, size_t codes_bytes, float* scale, float* offset,
+                           void* ws, size_t ws_bytes, void* stream) {
     ApplyArgs A;
     int st = make_geometry(W, chunk_w, unit_rows, &A.g);
     if (st != WINDQ_OK) return st;
@@ -635,6 +666,8 @@ extern "C" int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t uni
     }
     if (ws == nullptr || ws_bytes < apply_ws_bytes(A.g) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
     A.W = W->data;
+    A.mask = mask;
+    A.mask_ld = W->cols / 8;
     A.action = action;
     A.clip_idx = clip_grid != nullptr ? clip_idx : nullptr;
     A.code_off = code_off;
@@ -647,11 +680,12 @@ extern "C" int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t uni
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w);
     const dim3 grid((unsigned)A.g.n_tiles);
-    if (W->dtype == WINDQ_BF16 && chunk_w == 128) {
+    const bool fast = mask == nullptr && W->dtype == WINDQ_BF16;   // the lanes-per-row kernel has no masked form
+    if (fast && chunk_w == 128) {
         hipLaunchKernelGGL(apply_plan_split_kernel<16>, grid, dim3(APS_THREADS), 0, hs, A);
-    } else if (W->dtype == WINDQ_BF16 && chunk_w == 64) {
+    } else if (fast && chunk_w == 64) {
         hipLaunchKernelGGL(apply_plan_split_kernel<8>, grid, dim3(APS_THREADS), 0, hs, A);
-    } else if (W->dtype == WINDQ_BF16 && chunk_w == 32) {
+    } else if (fast && chunk_w == 32) {
         hipLaunchKernelGGL(apply_plan_split_kernel<4>, grid, dim3(APS_THREADS), 0, hs, A);
     } else if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&apply_plan_kernel<WINDQ_BF16>), lds);
@@ -664,4 +698,21 @@ extern "C" int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t uni
     }
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     return WINDQ_OK;
+}
+
+extern "C" int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t unit_rows, const uint8_t* action,
+                                const uint8_t* clip_idx, const float* clip_grid, int32_t K, const int64_t* code_off,
+                                uint8_t* codes, size_t codes_bytes, float* scale, float* offset, void* ws,
+                                size_t ws_bytes, void* stream) {
+    return apply_plan_impl(W, chunk_w, unit_rows, nullptr, action, clip_idx, clip_grid, K, code_off, codes, codes_bytes,
+                           scale, offset, ws, ws_bytes, stream);
+}
+
+extern "C" int windq_apply_plan_prot(const windq_mat* W, int32_t chunk_w, int64_t unit_rows, const uint8_t* mask,
+                                     const uint8_t* action, const uint8_t* clip_idx, const float* clip_grid, int32_t K,
+                                     const int64_t* code_off, uint8_t* codes, size_t codes_bytes, float* scale,
+                                     float* offset, void* ws, size_t ws_bytes, void* stream) {
+    if (mask == nullptr) return WINDQ_EINVAL;
+    return apply_plan_impl(W, chunk_w, unit_rows, mask, action, clip_idx, clip_grid, K, code_off, codes, codes_bytes,
+                           scale, offset, ws, ws_bytes, stream);
 }

@@ -60,6 +60,8 @@ constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to t
 struct FitScoreArgs {
     const void* W;
     const float* s;
+    const uint8_t* mask;   // protection mask [rows][cols/8] (masked kernels only)
+    int64_t mask_ld;
     double* partial;   // [n_tiles][4K+3]
     Geometry g;
     int32_t K;
@@ -71,9 +73,12 @@ struct FitScoreArgs {
 // 16 x FS_NRED scratch for combining rows.  Small on purpose: the fast fp32 issue rate
 // needs five or more resident wavefronts per SIMD (a single wavefront issues at most one
 // vector instruction per ~5 cycles), so LDS per workgroup must stay below ~30 KB.
-inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w) {
+// Row stride of the tile's protection-mask bytes in LDS (masked kernels): an odd number of
+// dwords where the width allows, so that 64 lanes reading 64 rows spread over the banks.
+__host__ __device__ inline int32_t mask_row_stride(int32_t chunk_w) { return (((chunk_w >> 3) + 3) & ~3) + 4; }
+inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
-           (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float);
+           (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (masked ? (size_t)TILE_ROWS * mask_row_stride(chunk_w) : 0);
 }
 
 // The 8-bit residual is ~1/500 of the range, so it is taken relative to an ANCHOR c: a grid
@@ -170,7 +175,9 @@ __device__ __forceinline__ double rows_sum(const float (&v)[N], float* __restric
     return tot;
 }
 
-template <int DT>
+// MASKED: salient weights (Sec. 3.5) marked in A.mask take no part: they are left out of
+// the group statistics, and in every error sum their activation scale counts as zero.
+template <int DT, bool MASKED>
 __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScoreArgs A) {
     extern __shared__ char smem[];
     const TileCoord tc = tile_coord(A.g, blockIdx.x);
@@ -179,10 +186,19 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     const int32_t row_bytes = G * EB + 16;
     char* __restrict__ tile = smem;
     float* __restrict__ scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
+    const int32_t mstride = mask_row_stride(G);
+    uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(scol + G + FS_WAVES * 16 * FS_NRED);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
 
     load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
     for (int32_t c = threadIdx.x; c < G; c += FS_THREADS) scol[c] = A.s[tc.col0 + c];
+    if (MASKED) {
+        const int32_t mb = G >> 3;
+        for (int32_t i = threadIdx.x; i < TILE_ROWS * mb; i += FS_THREADS) {
+            const int32_t r = i / mb, b = i - r * mb;
+            mtile[r * mstride + b] = r < tc.nrows ? A.mask[(tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) + b] : (uint8_t)0;
+        }
+    }
     __syncthreads();
 
     const int32_t K = A.K;
@@ -201,11 +217,13 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
         // which would spill it, and everything derived from it, to scratch memory.
         int G_r = G;
         asm volatile("" : "+s"(G_r));
-        const char* __restrict__ wrow = tile + fresh_lane() * row_bytes;
+        const int lane_w = fresh_lane();
+        const char* __restrict__ wrow = tile + lane_w * row_bytes;
+        const uint8_t* __restrict__ mrow = mtile + lane_w * mstride;
         float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
         if (item < A.n_kpass) {
             float mn, mx;
-            {
+            if (!MASKED) {
                 float w[8];
                 read8<DT>(wrow, 0, w);
                 mn = mx = w[0];
@@ -214,6 +232,21 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     mn = fminf(fminf(fminf(mn, w[0]), fminf(w[1], w[2])), fminf(fminf(w[3], w[4]), fminf(w[5], fminf(w[6], w[7]))));
                     mx = fmaxf(fmaxf(fmaxf(mx, w[0]), fmaxf(w[1], w[2])), fmaxf(fmaxf(w[3], w[4]), fmaxf(w[5], fmaxf(w[6], w[7]))));
                 }
+            } else {
+                mn = INFINITY;
+                mx = -INFINITY;
+                for (int32_t c = 0; c < G; c += 8) {
+                    float w[8];
+                    read8<DT>(wrow, c, w);
+                    const uint32_t m = mrow[c >> 3];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const bool kept = ((m >> j) & 1u) == 0u;
+                        mn = fminf(mn, kept ? w[j] : INFINITY);
+                        mx = fmaxf(mx, kept ? w[j] : -INFINITY);
+                    }
+                }
+                if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
             }
             // zero inside the closed range of every group of the wavefront?
             const bool anchored = __builtin_amdgcn_ballot_w64(!(mn <= 0.0f && mx >= 0.0f)) == 0;
@@ -260,14 +293,14 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     read8<DT>(wrow, c, w);
                     const float4 sa = *reinterpret_cast<const float4*>(scol + c);
                     const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
-                    score_weight<AN>(w[0], sa.x, P, Q, M, nM, acc);
-                    score_weight<AN>(w[1], sa.y, P, Q, M, nM, acc);
-                    score_weight<AN>(w[2], sa.z, P, Q, M, nM, acc);
-                    score_weight<AN>(w[3], sa.w, P, Q, M, nM, acc);
-                    score_weight<AN>(w[4], sb.x, P, Q, M, nM, acc);
-                    score_weight<AN>(w[5], sb.y, P, Q, M, nM, acc);
-                    score_weight<AN>(w[6], sb.z, P, Q, M, nM, acc);
-                    score_weight<AN>(w[7], sb.w, P, Q, M, nM, acc);
+                    float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
+                    if (MASKED) {
+                        const uint32_t m = mrow[c >> 3];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) s8[j] = ((m >> j) & 1u) != 0u ? 0.0f : s8[j];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) score_weight<AN>(w[j], s8[j], P, Q, M, nM, acc);
                 }
             };
             if (anchored) sweep(std::true_type{});
@@ -291,13 +324,21 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             // ternary absmean, binary sign*mean|w|, reference energy.  S1 = sum |w| in fp64
             // in column order (exact for bf16 inputs): gamma = alpha = fp32(S1 / G).
             double S1 = 0.0;
+            int32_t n_kept = G_r;
             for (int32_t c = 0; c < G; c += 8) {
                 float w[8];
                 read8<DT>(wrow, c, w);
+                if (!MASKED) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) S1 += (double)fabsf(w[j]);
+                    for (int j = 0; j < 8; ++j) S1 += (double)fabsf(w[j]);
+                } else {
+                    const uint32_t m = mrow[c >> 3];
+                    n_kept -= __builtin_popcount(m);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) S1 += ((m >> j) & 1u) != 0u ? 0.0 : (double)fabsf(w[j]);
+                }
             }
-            const float fam = (float)(S1 / (double)G_r);
+            const float fam = n_kept > 0 ? (float)(S1 / (double)n_kept) : 0.0f;
             const bool ok = fam >= FLT_MIN;
             // Fast-issue fp32 only, as in the clip passes.  y = clamp01(w/(2 gamma) + 1/2) maps
             // w/gamma in [-1, 1] onto [0, 1]; rne(2y) = q + 1 in {0, 1, 2} needs no clamp.
@@ -313,7 +354,12 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                 read8<DT>(wrow, c, w);
                 const float4 sa = *reinterpret_cast<const float4*>(scol + c);
                 const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
-                const float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
+                float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
+                if (MASKED) {
+                    const uint32_t m = mrow[c >> 3];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) s8[j] = ((m >> j) & 1u) != 0u ? 0.0f : s8[j];
+                }
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const float sc = s8[j];
@@ -392,9 +438,9 @@ __global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const d
 
 using namespace windq;
 
-extern "C" int windq_fit_score_all_bits(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
-                                        const float* clip_grid, int32_t K, float* err, uint8_t* clip_idx,
-                                        float* ref_energy, void* ws, size_t ws_bytes, void* stream) {
+static int fit_score_impl(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, const uint8_t* mask,
+                          const float* clip_grid, int32_t K, float* err, uint8_t* clip_idx, float* ref_energy,
+                          void* ws, size_t ws_bytes, void* stream) {
     FitScoreArgs A;
     int st = make_geometry(W, chunk_w, unit_rows, &A.g);
     if (st != WINDQ_OK) return st;
@@ -404,25 +450,42 @@ extern "C" int windq_fit_score_all_bits(const windq_mat* W, const float* s, int3
     if (ws == nullptr || ws_bytes < fit_score_ws_bytes(A.g, K) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
     A.W = W->data;
     A.s = s;
+    A.mask = mask;
+    A.mask_ld = W->cols / 8;
     A.partial = static_cast<double*>(ws);
     A.K = K;
     A.n_kpass = (K + FS_KB - 1) / FS_KB;
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid[k < K ? k : K - 1];
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const size_t lds = fit_score_lds_bytes(W->dtype, chunk_w);
+    const bool masked = mask != nullptr;
+    const size_t lds = fit_score_lds_bytes(W->dtype, chunk_w, masked);
     const dim3 grid((unsigned)A.g.n_tiles);
-    if (W->dtype == WINDQ_BF16) {
-        st = ensure_lds(reinterpret_cast<const void*>(&fit_score_kernel<WINDQ_BF16>), lds);
-        if (st != WINDQ_OK) return st;
-        hipLaunchKernelGGL(fit_score_kernel<WINDQ_BF16>, grid, dim3(FS_THREADS), lds, hs, A);
-    } else {
-        st = ensure_lds(reinterpret_cast<const void*>(&fit_score_kernel<WINDQ_F32>), lds);
-        if (st != WINDQ_OK) return st;
-        hipLaunchKernelGGL(fit_score_kernel<WINDQ_F32>, grid, dim3(FS_THREADS), lds, hs, A);
-    }
+    auto launch = [&](auto kernel) -> int {
+        const int e = ensure_lds(reinterpret_cast<const void*>(kernel), lds);
+        if (e != WINDQ_OK) return e;
+        hipLaunchKernelGGL(kernel, grid, dim3(FS_THREADS), lds, hs, A);
+        return WINDQ_OK;
+    };
+    if (W->dtype == WINDQ_BF16) st = masked ? launch(&fit_score_kernel<WINDQ_BF16, true>) : launch(&fit_score_kernel<WINDQ_BF16, false>);
+    else st = masked ? launch(&fit_score_kernel<WINDQ_F32, true>) : launch(&fit_score_kernel<WINDQ_F32, false>);
+    if (st != WINDQ_OK) return st;
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     hipLaunchKernelGGL(fit_score_finalize_kernel, dim3((unsigned)A.g.U), dim3(FIN_THREADS), 0, hs, A.partial,
                        A.g.tiles_per_unit, K, err, clip_idx, ref_energy);
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     return WINDQ_OK;
+}
+
+extern "C" int windq_fit_score_all_bits(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
+                                        const float* clip_grid, int32_t K, float* err, uint8_t* clip_idx,
+                                        float* ref_energy, void* ws, size_t ws_bytes, void* stream) {
+    return fit_score_impl(W, s, chunk_w, unit_rows, nullptr, clip_grid, K, err, clip_idx, ref_energy, ws, ws_bytes, stream);
+}
+
+extern "C" int windq_fit_score_all_bits_prot(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
+                                             const uint8_t* mask, const float* clip_grid, int32_t K, float* err,
+                                             uint8_t* clip_idx, float* ref_energy, void* ws, size_t ws_bytes,
+                                             void* stream) {
+    if (mask == nullptr) return WINDQ_EINVAL;
+    return fit_score_impl(W, s, chunk_w, unit_rows, mask, clip_grid, K, err, clip_idx, ref_energy, ws, ws_bytes, stream);
 }

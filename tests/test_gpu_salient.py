@@ -102,3 +102,106 @@ def test_full_size_7b_matrix_sampled(windq):
         assert np.array_equal(codes[j].cpu().numpy(), o_codes)
         assert float(scale[j]) == float(o_sigma[0])
         assert abs(float(err[j]) - o_err[0]) <= REL * o_err[0]
+    # fit+score and apply-plan under the mask, in the benchmark's launch configuration
+    cg = synth.clip_grid(20)
+    e_m, idx_m, ref_m = windq.windq_fit_score_all_bits(W, s, G, 0, cg, mask=mask)
+    action = torch.tensor([1 + (u % 6) for u in range(32)], dtype=torch.uint8)
+    off = windq.windq_plan_layout(action, 4096, G)
+    pcodes, pscale, poffset = windq.windq_apply_plan(W, G, 0, action.to(DEV), idx_m, cg, off.to(DEV), mask=mask)
+    torch.cuda.synchronize()
+    for j in (0, 13, 31):
+        cols = slice(j * G, (j + 1) * G)
+        Wn, sn = to_np(W[:, cols]), s[cols].cpu().numpy()
+        keep = O.salient_select(Wn, sn, G, 0, ppm)
+        o_err, o_idx, o_ref, table = O.fit_score_all_bits(Wn, sn, G, 0, cg.numpy(), keep=keep)
+        gi = idx_m[j].cpu().numpy()
+        for b in np.nonzero(gi != o_idx[0])[0]:
+            assert table[0, b, gi[b]] <= table[0, b].min() * (1 + 1e-9)
+        assert np.all(np.abs(e_m[j].cpu().numpy() - o_err[0]) <= REL * o_err[0])
+        assert abs(float(ref_m[j]) - o_ref[0]) <= REL * o_ref[0]
+        a1 = action[j:j + 1].numpy()
+        off1 = O.plan_layout(a1, 4096, G)
+        oc, osc, oof = O.apply_plan(Wn, G, 0, a1, gi[None, :], cg.numpy(), off1, keep=keep)
+        assert np.array_equal(pcodes[int(off[j]):int(off[j]) + int(off1[1])].cpu().numpy(), oc)
+        assert np.array_equal(pscale[j * 4096:(j + 1) * 4096].cpu().numpy().view(np.uint32), osc.view(np.uint32))
+        assert np.array_equal(poffset[j * 4096:(j + 1) * 4096].cpu().numpy().view(np.uint32), oof.view(np.uint32))
+
+
+# ---------------------------------------------- fit+score and apply-plan under the mask
+def check_masked_fit_and_apply(windq, W, s, G, unit_rows, ppm, K):
+    mask, keep = check_select(windq, W, s, G, unit_rows, ppm)
+    cg = synth.clip_grid(K)
+    err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, G, unit_rows, cg, mask=mask)
+    torch.cuda.synchronize()
+    Wn, sn = to_np(W), s.cpu().numpy()
+    o_err, o_idx, o_ref, table = O.fit_score_all_bits(Wn, sn, G, unit_rows, cg.numpy(), keep=keep)
+    g_err, g_idx, g_ref = err.cpu().numpy().astype(np.float64), clip_idx.cpu().numpy(), ref.cpu().numpy().astype(np.float64)
+    for u, b in zip(*np.nonzero(g_idx != o_idx)):
+        assert table[u, b, g_idx[u, b]] <= table[u, b].min() * (1 + 1e-9), (u, b)
+    assert np.all(np.abs(g_err - o_err) <= REL * np.abs(o_err)), np.max(np.abs(g_err - o_err) / (np.abs(o_err) + 1e-300))
+    assert np.all(np.abs(g_ref - o_ref) <= REL * np.abs(o_ref))
+    U, R_u = windq.n_units(W.shape[0], W.shape[1], G, unit_rows)
+    for trial in range(2):
+        action = (torch.arange(U) + trial) % 7
+        action = action.to(torch.uint8)
+        off = windq.windq_plan_layout(action, R_u, G)
+        codes = torch.full((max(int(off[-1]), 16),), 0xAB, dtype=torch.uint8, device=DEV)
+        codes, scale, offset = windq.windq_apply_plan(W, G, unit_rows, action.to(DEV), clip_idx, cg, off.to(DEV),
+                                                      codes=codes, mask=mask)
+        torch.cuda.synchronize()
+        o_codes, o_scale, o_offset = O.apply_plan(Wn, G, unit_rows, action.numpy(), g_idx, cg.numpy(), off.numpy(), keep=keep)
+        assert np.array_equal(codes.cpu().numpy()[:int(off[-1])], o_codes)
+        assert np.array_equal(scale.cpu().numpy().view(np.uint32), o_scale.view(np.uint32))
+        assert np.array_equal(offset.cpu().numpy().view(np.uint32), o_offset.view(np.uint32))
+    return g_err, o_err
+
+
+@pytest.mark.parametrize("R,C,G,unit_rows,ppm,K,dtype", [
+    (256, 512, 128, 0, 30000, 20, torch.bfloat16), (256, 512, 128, 128, 30000, 20, torch.bfloat16),
+    (200, 256, 64, 100, 20000, 7, torch.bfloat16), (512, 512, 64, 0, 30000, 20, torch.float32),
+    (8, 16, 8, 4, 250000, 3, torch.float32), (70, 96, 32, 0, 500000, 5, torch.bfloat16),
+    (130, 256, 256, 0, 30000, 20, torch.bfloat16), (64, 128, 128, 0, 1000000, 4, torch.bfloat16),
+    (64, 128, 128, 0, 0, 4, torch.bfloat16)])
+def test_masked_fit_score_and_apply_plan(windq, R, C, G, unit_rows, ppm, K, dtype):
+    W = synth.weights_llm(R, C, seed=81, device=DEV, dtype=dtype)
+    X = synth.activations_llm(64, C, seed=82, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    check_masked_fit_and_apply(windq, W, s, G, unit_rows, ppm, K)
+
+
+def test_protection_takes_the_outliers_out_of_the_fit(windq):
+    """Heavy-tailed input columns stretch every group's range; with 3 % protected the 2-bit error of
+    the rest falls well below the unprotected one (Sec. 3.5: why salient weights are kept apart)."""
+    W = synth.weights_llm(512, 1024, seed=83, device=DEV)
+    X = synth.activations_llm(64, 1024, seed=84, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    cg = synth.clip_grid(20)
+    err0, _, _ = windq.windq_fit_score_all_bits(W, s, 128, 0, cg)
+    g_err, _ = check_masked_fit_and_apply(windq, W, s, 128, 0, 30000, 20)
+    assert float(np.sum(g_err[:, 3])) < 0.7 * float(err0[:, 3].double().sum())
+
+
+def test_groups_with_nothing_kept(windq):
+    """A mask that protects whole rows (not one the selector would write: it is an input like any other)."""
+    W = synth.weights_llm(64, 256, seed=85, device=DEV)
+    s = torch.rand(256, device=DEV) + 0.1
+    keep = np.ones((64, 256), dtype=bool)
+    keep[3] = False
+    keep[10, :128] = False
+    keep[11, 5:] = False
+    mask = torch.from_numpy(O.pack_mask(keep)).to(DEV)
+    cg = synth.clip_grid(6)
+    err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, 128, 0, cg, mask=mask)
+    torch.cuda.synchronize()
+    o_err, o_idx, o_ref, _ = O.fit_score_all_bits(to_np(W), s.cpu().numpy(), 128, 0, cg.numpy(), keep=keep)
+    assert np.all(np.abs(err.cpu().numpy() - o_err) <= REL * np.abs(o_err))
+    for a in range(1, 7):
+        action = torch.full((2,), a, dtype=torch.uint8)
+        off = windq.windq_plan_layout(action, 64, 128)
+        codes, scale, offset = windq.windq_apply_plan(W, 128, 0, action.to(DEV), None, None, off.to(DEV), mask=mask)
+        torch.cuda.synchronize()
+        o_codes, o_scale, o_offset = O.apply_plan(to_np(W), 128, 0, action.numpy(), None, np.ones(1, np.float32), off.numpy(), keep=keep)
+        assert np.array_equal(codes.cpu().numpy()[:int(off[-1])], o_codes), a
+        assert np.array_equal(scale.cpu().numpy().view(np.uint32), o_scale.view(np.uint32))
+        assert np.array_equal(offset.cpu().numpy().view(np.uint32), o_offset.view(np.uint32))
+        assert float(scale[3]) == 0.0 and float(offset[3]) == 0.0

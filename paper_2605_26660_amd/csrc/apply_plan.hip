@@ -331,6 +331,7 @@ WINDQ_ROW_REDUCE(row_max_f32, float, dpp_f32, fmaxf(x, y))
 WINDQ_ROW_REDUCE(row_min_u32, uint32_t, dpp_u32, (x < y ? x : y))
 WINDQ_ROW_REDUCE(row_max_u32, uint32_t, dpp_u32, (x > y ? x : y))
 WINDQ_ROW_REDUCE(row_sum_f64, double, dpp_f64, x + y)
+WINDQ_ROW_REDUCE(row_sum_u32, uint32_t, dpp_u32, x + y)
 #undef WINDQ_ROW_REDUCE
 
 // Value held by lane IT of the caller's quad.
@@ -367,20 +368,36 @@ struct SplitLane {
     }
 };
 
-template <int LPR, int BITS>
+// `prot` (here and below): per iteration, the protection bits of the lane's eight columns
+// (one byte of the mask; 0 everywhere when MASKED is false).
+template <int LPR, int BITS, bool MASKED>
 __device__ __forceinline__ void split_uniform(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
-                                              const uint4 (&raw)[SplitLane<LPR>::NI], float p, uint8_t* __restrict__ out,
-                                              int64_t bpg) {
+                                              const uint4 (&raw)[SplitLane<LPR>::NI],
+                                              const uint32_t (&prot)[SplitLane<LPR>::NI], float p,
+                                              uint8_t* __restrict__ out, int64_t bpg) {
     constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
     float w[8];
     float smn = 0.0f, smx = 0.0f;
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
         unpack8(raw[it], w);
-        float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
-        float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
+        float mn, mx;
+        if (!MASKED) {
+            mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
+            mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
+        } else {
+            mn = INFINITY;
+            mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool kept = ((prot[it] >> j) & 1u) == 0u;
+                mn = fminf(mn, kept ? w[j] : INFINITY);
+                mx = fmaxf(mx, kept ? w[j] : -INFINITY);
+            }
+        }
         mn = row_min_f32<LPR>(mn);
         mx = row_max_f32<LPR>(mx);
+        if (MASKED && mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
         if (it == 0 || L.sel == it) {
             smn = mn;
             smx = mx;
@@ -413,6 +430,7 @@ __device__ __forceinline__ void split_uniform(const ApplyArgs& A, const TileCoor
             const float u = w[j] - lo_r;
             const float t = u * inv_r;
             q[j] = __builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, qmax);
+            if (MASKED && ((prot[it] >> j) & 1u) != 0u) q[j] = 0.0f;      // placeholder in a protected slot
         }
         const int r = L.row0 + it * RPI;
         const bool valid = r < tc.nrows;
@@ -450,21 +468,25 @@ __device__ __forceinline__ void split_uniform(const ApplyArgs& A, const TileCoor
     }
 }
 
-// Sum of |w| over each row of every iteration; the return value is the sum of the row this
-// lane derives parameters for (iteration L.sel).
-template <int LPR>
-__device__ __forceinline__ double split_abs_sum(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
-                                                const uint4 (&raw)[SplitLane<LPR>::NI]) {
+// Mean |w| over the kept weights of each row of every iteration, as stored (fp64 sum divided
+// by the number kept, rounded to fp32; 0 when none is kept); the return value is that of the
+// row this lane derives parameters for (iteration L.sel).
+template <int LPR, bool MASKED>
+__device__ __forceinline__ float split_abs_mean(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
+                                                const uint4 (&raw)[SplitLane<LPR>::NI],
+                                                const uint32_t (&prot)[SplitLane<LPR>::NI]) {
     constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI, G = 8 * LPR;
-    double sS1 = 0.0;
+    float smean = 0.0f;
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
         float w[8];
         unpack8(raw[it], w);
-        double S1 = (double)fabsf(w[0]);
+        double S1 = 0.0;
 #pragma unroll
-        for (int j = 1; j < 8; ++j) S1 += (double)fabsf(w[j]);
+        for (int j = 0; j < 8; ++j) S1 += MASKED && ((prot[it] >> j) & 1u) != 0u ? 0.0 : (double)fabsf(w[j]);
         S1 = row_sum_f64<LPR>(S1);
+        uint32_t n_kept = G;
+        if (MASKED) n_kept = row_sum_u32<LPR>(8u - (uint32_t)__builtin_popcount(prot[it]));
         // largest and smallest non-zero magnitude keys of the row (zero maps to 0xffff in the minimum)
         uint32_t kmax = 0u, kmin = 0xffffu;
         const uint32_t dws[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
@@ -485,20 +507,26 @@ __device__ __forceinline__ double split_abs_sum(const ApplyArgs& A, const TileCo
             if (r < tc.nrows) {
                 const uint16_t* __restrict__ wrow =
                     static_cast<const uint16_t*>(A.W) + (tc.row0 + r) * A.g.ld + tc.col0;
-                for (int c = 0; c < G; ++c) S1 += (double)fabsf(bf16_bits_to_f32(wrow[c]));
+                const uint8_t* __restrict__ mrow = MASKED ? A.mask + (tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) : nullptr;
+                for (int c = 0; c < G; ++c) {
+                    const bool kept = !MASKED || ((mrow[c >> 3] >> (c & 7)) & 1u) == 0u;
+                    S1 += kept ? (double)fabsf(bf16_bits_to_f32(wrow[c])) : 0.0;
+                }
             }
         }
-        if (it == 0 || L.sel == it) sS1 = S1;
+        const float mean = n_kept > 0u ? (float)(S1 / (double)n_kept) : 0.0f;
+        if (it == 0 || L.sel == it) smean = mean;
     }
-    return sS1;
+    return smean;
 }
 
-template <int LPR>
+template <int LPR, bool MASKED>
 __device__ __forceinline__ void split_ternary(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
-                                              const uint4 (&raw)[SplitLane<LPR>::NI], uint8_t* __restrict__ out,
+                                              const uint4 (&raw)[SplitLane<LPR>::NI],
+                                              const uint32_t (&prot)[SplitLane<LPR>::NI], uint8_t* __restrict__ out,
                                               uint8_t* trits) {
     constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI, G = 8 * LPR, NB = (G + 4) / 5;
-    float gamma = (float)(split_abs_sum<LPR>(A, tc, L, raw) / (double)G);
+    float gamma = split_abs_mean<LPR, MASKED>(A, tc, L, raw, prot);
     const bool ok = gamma >= FLT_MIN;
     gamma = ok ? gamma : 0.0f;
     const float inv = ok ? 1.0f / gamma : 0.0f;
@@ -523,6 +551,7 @@ __device__ __forceinline__ void split_ternary(const ApplyArgs& A, const TileCoor
         for (int j = 0; j < 8; ++j) {
             const float t = w[j] * inv_r;
             q[j] = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -1.0f, 1.0f) + 1.0f;
+            if (MASKED && ((prot[it] >> j) & 1u) != 0u) q[j] = 0.0f;      // placeholder in a protected slot
         }
         const uint32_t v0 = put_byte(q[0], 0, put_byte(q[1], 1, put_byte(q[2], 2, put_byte(q[3], 3, 0u))));
         const uint32_t v1 = put_byte(q[4], 0, put_byte(q[5], 1, put_byte(q[6], 2, put_byte(q[7], 3, 0u))));
@@ -549,11 +578,12 @@ __device__ __forceinline__ void split_ternary(const ApplyArgs& A, const TileCoor
     }
 }
 
-template <int LPR>
+template <int LPR, bool MASKED>
 __device__ __forceinline__ void split_binary(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
-                                             const uint4 (&raw)[SplitLane<LPR>::NI], uint8_t* __restrict__ out) {
-    constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI, G = 8 * LPR;
-    const float alpha = (float)(split_abs_sum<LPR>(A, tc, L, raw) / (double)G);
+                                             const uint4 (&raw)[SplitLane<LPR>::NI],
+                                             const uint32_t (&prot)[SplitLane<LPR>::NI], uint8_t* __restrict__ out) {
+    constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
+    const float alpha = split_abs_mean<LPR, MASKED>(A, tc, L, raw, prot);
     if (L.piece < NI) {
         const int r = L.row0 + L.piece * RPI;
         if (r < tc.nrows) {
@@ -570,7 +600,7 @@ __device__ __forceinline__ void split_binary(const ApplyArgs& A, const TileCoord
 #pragma unroll
         for (int j = 0; j < 8; ++j) byte |= (w[j] >= 0.0f ? 1u : 0u) << j;
         const int r = L.row0 + it * RPI;
-        if (r < tc.nrows) out[r * LPR + L.piece] = (uint8_t)byte;
+        if (r < tc.nrows) out[r * LPR + L.piece] = (uint8_t)(byte & ~prot[it]);
     }
 }
 
@@ -590,7 +620,7 @@ __device__ __forceinline__ TileCoord tile_coord32(const Geometry& g, uint32_t ti
     return tc;
 }
 
-template <int LPR>
+template <int LPR, bool MASKED>
 __global__ __launch_bounds__(APS_THREADS, 8) void apply_plan_split_kernel(const ApplyArgs A) {
     constexpr int G = 8 * LPR, NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
     __shared__ __attribute__((aligned(16))) uint8_t trits[TILE_ROWS * G];
@@ -614,13 +644,17 @@ __global__ __launch_bounds__(APS_THREADS, 8) void apply_plan_split_kernel(const 
     }
 
     uint4 raw[NI];
+    uint32_t prot[NI];
     const char* __restrict__ wbase = static_cast<const char*>(A.W);
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
         const int r = L.row0 + it * RPI;
         raw[it] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < tc.nrows)
+        prot[it] = 0u;
+        if (r < tc.nrows) {
             raw[it] = *reinterpret_cast<const uint4*>(wbase + ((tc.row0 + r) * A.g.ld + tc.col0) * 2 + L.piece * 16);
+            if (MASKED) prot[it] = A.mask[(tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) + L.piece];
+        }
     }
 
     float p = 1.0f;
@@ -631,12 +665,12 @@ __global__ __launch_bounds__(APS_THREADS, 8) void apply_plan_split_kernel(const 
     }
     uint8_t* __restrict__ out = A.codes + base + tc.lrow0 * bpg;   // the tile's rows, bpg bytes each
     switch (a) {
-        case 1: split_uniform<LPR, 8>(A, tc, L, raw, p, out, bpg); break;
-        case 2: split_uniform<LPR, 4>(A, tc, L, raw, p, out, bpg); break;
-        case 3: split_uniform<LPR, 3>(A, tc, L, raw, p, out, bpg); break;
-        case 4: split_uniform<LPR, 2>(A, tc, L, raw, p, out, bpg); break;
-        case 5: split_ternary<LPR>(A, tc, L, raw, out, trits); break;
-        default: split_binary<LPR>(A, tc, L, raw, out); break;
+        case 1: split_uniform<LPR, 8, MASKED>(A, tc, L, raw, prot, p, out, bpg); break;
+        case 2: split_uniform<LPR, 4, MASKED>(A, tc, L, raw, prot, p, out, bpg); break;
+        case 3: split_uniform<LPR, 3, MASKED>(A, tc, L, raw, prot, p, out, bpg); break;
+        case 4: split_uniform<LPR, 2, MASKED>(A, tc, L, raw, prot, p, out, bpg); break;
+        case 5: split_ternary<LPR, MASKED>(A, tc, L, raw, prot, out, trits); break;
+        default: split_binary<LPR, MASKED>(A, tc, L, raw, prot, out); break;
     }
     // zero the padding that rounds the unit's payload up to 16 bytes
     if (padded != payload && tc.t == A.g.tiles_per_unit - 1 && (int64_t)threadIdx.x < padded - payload)
@@ -680,13 +714,18 @@ static int apply_plan_impl(const windq_mat* W, int32_t chunk_w, int64_t unit_row
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w);
     const dim3 grid((unsigned)A.g.n_tiles);
-    const bool fast = mask == nullptr && W->dtype == WINDQ_BF16;   // the lanes-per-row kernel has no masked form
+    const bool fast = W->dtype == WINDQ_BF16;
+    const bool masked = mask != nullptr;
+    auto launch_split = [&](auto plain, auto prot) {
+        if (masked) hipLaunchKernelGGL(prot, grid, dim3(APS_THREADS), 0, hs, A);
+        else hipLaunchKernelGGL(plain, grid, dim3(APS_THREADS), 0, hs, A);
+    };
     if (fast && chunk_w == 128) {
-        hipLaunchKernelGGL(apply_plan_split_kernel<16>, grid, dim3(APS_THREADS), 0, hs, A);
+        launch_split(&apply_plan_split_kernel<16, false>, &apply_plan_split_kernel<16, true>);
     } else if (fast && chunk_w == 64) {
-        hipLaunchKernelGGL(apply_plan_split_kernel<8>, grid, dim3(APS_THREADS), 0, hs, A);
+        launch_split(&apply_plan_split_kernel<8, false>, &apply_plan_split_kernel<8, true>);
     } else if (fast && chunk_w == 32) {
-        hipLaunchKernelGGL(apply_plan_split_kernel<4>, grid, dim3(APS_THREADS), 0, hs, A);
+        launch_split(&apply_plan_split_kernel<4, false>, &apply_plan_split_kernel<4, true>);
     } else if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&apply_plan_kernel<WINDQ_BF16>), lds);
         if (st != WINDQ_OK) return st;

@@ -205,3 +205,26 @@ def test_groups_with_nothing_kept(windq):
         assert np.array_equal(scale.cpu().numpy().view(np.uint32), o_scale.view(np.uint32))
         assert np.array_equal(offset.cpu().numpy().view(np.uint32), o_offset.view(np.uint32))
         assert float(scale[3]) == 0.0 and float(offset[3]) == 0.0
+
+
+@pytest.mark.parametrize("G", [32, 64, 128, 256])
+def test_masked_apply_plan_wide_dynamic_range(windq, G):
+    """Magnitudes spanning far more than an fp64 sum holds exactly, under a mask: the kept weights'
+    sum of |w| is defined in column order."""
+    gen = torch.Generator().manual_seed(91)
+    R, C = 70, 2 * G
+    expo = torch.randint(-120, 60, (R, C), generator=gen).double()
+    mant = 1.0 + torch.rand(R, C, generator=gen, dtype=torch.float64)
+    sign = torch.where(torch.rand(R, C, generator=gen) < 0.5, -1.0, 1.0).double()
+    W = (sign * mant * torch.pow(torch.tensor(2.0, dtype=torch.float64), expo)).float().to(torch.bfloat16).to(DEV)
+    s = torch.ones(C, device=DEV)
+    mask, keep = check_select(windq, W, s, G, 0, 100000)
+    for a in range(1, 7):
+        action = torch.full((2,), a, dtype=torch.uint8)
+        off = windq.windq_plan_layout(action, R, G)
+        codes, scale, offset = windq.windq_apply_plan(W, G, 0, action.to(DEV), None, None, off.to(DEV), mask=mask)
+        torch.cuda.synchronize()
+        oc, osc, oof = O.apply_plan(to_np(W), G, 0, action.numpy(), None, np.ones(1, np.float32), off.numpy(), keep=keep)
+        assert np.array_equal(codes.cpu().numpy()[:int(off[-1])], oc), a
+        assert np.array_equal(scale.cpu().numpy().view(np.uint32), osc.view(np.uint32)), a
+        assert np.array_equal(offset.cpu().numpy().view(np.uint32), oof.view(np.uint32)), a

@@ -473,6 +473,81 @@ def salient_encode(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int, keep: n
     return allc, off, sigma, err
 
 
+# ------------------------------- heuristic sensitivity allocator and fallback (App. E, Sec. 3.5)
+def unit_saliency(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int = 0) -> np.ndarray:
+    """App. "Comparison with Heuristic Sensitivity Allocator": a unit's saliency score is the
+    mean product of activation scale and weight magnitude over the unit.  [U] fp64."""
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    prod = np.abs(W.astype(f64)) * np.abs(s.astype(f64))[None, :]
+    return np.array([unit_view(prod, G, unit_rows, u).sum() / (R_u * G) for u in range(n_rb * n_chunks)], dtype=f64)
+
+
+def unit_cost_centibits(a: int, n: int, n_p: int) -> int:
+    """Eq. 5 for one unit, in centibits."""
+    return 1600 * n if a == 0 else ACTION_CENTIBITS[a] * (n - n_p) + 800 * n_p
+
+
+def heuristic_plan(sal, n_unit, n_prot, target_centibits: int, frac_1bit_ppm: int = 0, frac_ternary_ppm: int = 0):
+    """The deterministic allocator the paper compares against.  Units are ranked by saliency,
+    most salient first (equal scores: lower index first).  Every unit starts at 2 bits; the
+    least salient floor(U * frac_1bit) units are pushed to 1 bit and the next
+    floor(U * frac_ternary) to 1.58; while the plan exceeds the budget (Eq. 1 with Eq. 5),
+    units are demoted one level at a time from the least salient upward (2 -> 1.58 in a first
+    sweep, 1.58 -> 1 in a second); then the most salient units are promoted 2 -> 3 wherever the
+    budget permits, and after that 3 -> 4 likewise.  Returns (action uint8 [U], total
+    centibits, feasible)."""
+    U = len(sal)
+    n_prot = [0] * U if n_prot is None else [int(x) for x in n_prot]
+    n_unit = [int(x) for x in n_unit]
+    order = sorted(range(U), key=lambda u: (-float(sal[u]), u))
+    action = [4] * U
+    n1 = (U * frac_1bit_ppm) // 1_000_000
+    n158 = min((U * frac_ternary_ppm) // 1_000_000, U - n1)
+    for u in order[U - n1:]:
+        action[u] = 6
+    for u in order[U - n1 - n158:U - n1]:
+        action[u] = 5
+    cost = lambda u, a: unit_cost_centibits(a, n_unit[u], n_prot[u])
+    B = sum(cost(u, action[u]) for u in range(U))
+    budget = target_centibits * sum(n_unit)
+    while B > budget:
+        changed = False
+        for u in reversed(order):
+            if action[u] in (4, 5):
+                B += cost(u, action[u] + 1) - cost(u, action[u])
+                action[u] += 1
+                changed = True
+                if B <= budget:
+                    break
+        if not changed:
+            break
+    for frm, to in ((4, 3), (3, 2)):
+        for u in order:
+            if action[u] == frm and B + cost(u, to) - cost(u, frm) <= budget:
+                B += cost(u, to) - cost(u, frm)
+                action[u] = to
+    return np.array(action, dtype=np.uint8), B, B <= budget
+
+
+def fallback_promote(action, err, ref, max_rel_err: float):
+    """Sec. 3.5: when the reconstruction error of the selected operator is excessive, fall back
+    to a higher-precision operator.  "Excessive" is read as err / ref_energy above a caller's
+    threshold (an fp32 number; the comparison err <= thr * ref is exact, in fp64); a unit climbs
+    1 -> 1.58 -> 2 -> 3 -> 4 -> 8 -> skip until it passes (skip has no error).  Returns (new
+    action uint8 [U], number of units changed)."""
+    out = np.array(action, dtype=np.uint8).copy()
+    changed = 0
+    thr = float(f32(max_rel_err))
+    for u in range(len(out)):
+        a = int(out[u])
+        a0 = a
+        while a != 0 and not (float(f32(err[u][a - 1])) <= thr * float(f32(ref[u]))):
+            a -= 1
+        out[u] = a
+        changed += a != a0
+    return out, changed
+
+
 # -------------------------------------------------------------- O5 effective bits
 def effective_bits(action, n_unit, n_prot=None):
     """Eq. 5.  B_i = 16 n_i for skip, else b_i (n_i - n_i^p) + 8 n_i^p.  Totals in

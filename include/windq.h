@@ -61,7 +61,8 @@ enum windq_call {
     WINDQ_CALL_UNIT_FEATURES = 1,
     WINDQ_CALL_FIT_SCORE = 2,
     WINDQ_CALL_APPLY_PLAN = 3,
-    WINDQ_CALL_SALIENT = 4        /* windq_salient_select and windq_salient_encode */
+    WINDQ_CALL_SALIENT = 4,       /* windq_salient_select and windq_salient_encode */
+    WINDQ_CALL_UNIT_SALIENCY = 5
 };
 
 #define WINDQ_N_ACTIONS 7
@@ -233,6 +234,41 @@ int windq_apply_plan_prot(const windq_mat* W, int32_t chunk_w, int64_t unit_rows
                           const int64_t* code_off /*[U+1]*/, uint8_t* codes, size_t codes_bytes,
                           float* scale /*[U*R_u]*/, float* offset /*[U*R_u]*/,
                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The deterministic allocator the paper compares its controller with (App. "Comparison with
+ * Heuristic Sensitivity Allocator"), and the fallback of Sec. 3.5.
+ *
+ * Saliency score of every unit: the mean of |w| * |s_c| over the unit (fp64 sums, fixed order).
+ */
+int windq_unit_saliency(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                        float* sal /*[U]*/, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Greedy plan from saliency scores (HOST only, exact integers; uses temporary host memory).
+ * Units are ranked by saliency, most salient first (equal scores: lower index first).
+ * Every unit starts at 2 bits; the least salient floor(U * frac_1bit_ppm / 10^6) units are
+ * pushed to 1 bit and the next floor(U * frac_ternary_ppm / 10^6) to 1.58; while the plan
+ * exceeds target_centibits * sum(n_unit) under Eq. 5, units are demoted one level at a time
+ * from the least salient upward (2 -> 1.58 in a first sweep, 1.58 -> 1 in a second); then
+ * the most salient units are promoted 2 -> 3 wherever the budget permits, and after that
+ * 3 -> 4 likewise.  *feasible = 0 if even the all-1-bit plan exceeds the budget.
+ * WINDQ_EINVAL on a NaN score, n < 0, n_prot outside [0, n] or a fraction above 10^6.
+ */
+int windq_heuristic_plan(const float* sal /*HOST [U]*/, const int64_t* n_unit /*HOST [U]*/,
+                         const int64_t* n_prot /*HOST [U] or NULL = 0*/, int64_t n_units,
+                         int64_t target_centibits, uint32_t frac_1bit_ppm, uint32_t frac_ternary_ppm,
+                         uint8_t* action /*HOST out [U]*/, int64_t* total_centibits /*HOST*/, int32_t* feasible /*HOST*/);
+
+/*
+ * Fallback to a higher-precision operator when the reconstruction error of the selected one
+ * is excessive (Sec. 3.5), HOST only: while err[u][a-1] > max_rel_err * ref_energy[u] (compared
+ * exactly), unit u climbs 1 -> 1.58 -> 2 -> 3 -> 4 -> 8 -> skip.  `action` is updated in place;
+ * the caller re-checks the budget with windq_effective_bits.
+ */
+int windq_fallback_promote(uint8_t* action /*HOST in/out [U]*/, const float* err /*HOST [U][6]*/,
+                           const float* ref_energy /*HOST [U]*/, int64_t n_units, float max_rel_err,
+                           int64_t* n_changed /*HOST*/);
 
 /* Workspace bytes a call needs for these shapes (0 if the shape is invalid). HOST only. */
 size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, int64_t cols,

@@ -16,14 +16,15 @@ LIB_PATH = os.path.join(_PKG_DIR, "libwindq.so")
 
 WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP = range(6)
 WINDQ_F32, WINDQ_BF16 = 0, 1
-CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT = range(5)
+CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY = range(6)
 N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK = 7, 6, 8, 64, 512
 
 EXPORTS = (
     "windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_bytes_per_group",
     "windq_plan_layout", "windq_apply_plan", "windq_effective_bits", "windq_workspace_bytes",
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
-    "windq_fit_score_all_bits_prot", "windq_apply_plan_prot",
+    "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
+    "windq_fallback_promote",
 )
 
 
@@ -72,11 +73,15 @@ def load(path: str | None = None):
     lib.windq_salient_encode.argtypes = [pm, vp, i32, i64, vp, u32, vp, vp, vp, vp, sz, vp]
     lib.windq_fit_score_all_bits_prot.argtypes = [pm, vp, i32, i64, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.windq_apply_plan_prot.argtypes = [pm, i32, i64, vp, vp, vp, vp, i32, vp, vp, sz, vp, vp, vp, sz, vp]
+    lib.windq_unit_saliency.argtypes = [pm, vp, i32, i64, vp, vp, sz, vp]
+    lib.windq_heuristic_plan.argtypes = [vp, vp, vp, i64, i64, u32, u32, vp, c.POINTER(i64), c.POINTER(i32)]
+    lib.windq_fallback_promote.argtypes = [vp, vp, vp, i64, c.c_float, c.POINTER(i64)]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
                  "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode",
-                 "windq_fit_score_all_bits_prot", "windq_apply_plan_prot"):
+                 "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency",
+                 "windq_heuristic_plan", "windq_fallback_promote"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -278,3 +283,40 @@ def windq_salient_encode(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_ro
                                        codes.data_ptr() if n_p > 0 else None, scale.data_ptr(), err.data_ptr(),
                                        ws.data_ptr(), ws.numel(), _stream()), "windq_salient_encode")
     return codes, scale, err
+
+
+# --------------------------------------------- heuristic allocator and fallback
+def windq_unit_saliency(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int = 0,
+                        ws: torch.Tensor | None = None, out: torch.Tensor | None = None):
+    """-> sal f32 [U] on the device: mean of |w| * |s_c| over each unit."""
+    _require_cuda(W, s)
+    U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    sal = out if out is not None else torch.empty(U, dtype=torch.float32, device=W.device)
+    ws = _workspace(CALL_UNIT_SALIENCY, W, chunk_w, unit_rows, 1, ws)
+    m = as_mat(W)
+    _check(load().windq_unit_saliency(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, sal.data_ptr(), ws.data_ptr(),
+                                      ws.numel(), _stream()), "windq_unit_saliency")
+    return sal
+
+
+def windq_heuristic_plan(sal: torch.Tensor, n_unit: torch.Tensor, n_prot: torch.Tensor | None, target_centibits: int,
+                         frac_1bit_ppm: int = 0, frac_ternary_ppm: int = 0):
+    """Host tensors: sal f32 [U], n_unit i64 [U], n_prot i64 [U] or None.  -> (action u8 [U], total centibits, feasible)."""
+    assert not sal.is_cuda and sal.dtype == torch.float32 and sal.is_contiguous() and n_unit.dtype == torch.int64
+    U = sal.numel()
+    action = torch.empty(U, dtype=torch.uint8)
+    cb, ok = ctypes.c_int64(0), ctypes.c_int32(0)
+    _check(load().windq_heuristic_plan(sal.data_ptr(), n_unit.data_ptr(), _ptr(n_prot), U, target_centibits,
+                                       frac_1bit_ppm, frac_ternary_ppm, action.data_ptr(), ctypes.byref(cb),
+                                       ctypes.byref(ok)), "windq_heuristic_plan")
+    return action, cb.value, bool(ok.value)
+
+
+def windq_fallback_promote(action: torch.Tensor, err: torch.Tensor, ref: torch.Tensor, max_rel_err: float):
+    """Host tensors: action u8 [U] (updated in place), err f32 [U x 6], ref f32 [U].  -> number of units changed."""
+    assert not action.is_cuda and action.dtype == torch.uint8 and not err.is_cuda and err.dtype == torch.float32
+    assert err.is_contiguous() and not ref.is_cuda and ref.dtype == torch.float32
+    n = ctypes.c_int64(0)
+    _check(load().windq_fallback_promote(action.data_ptr(), err.data_ptr(), ref.data_ptr(), action.numel(),
+                                         max_rel_err, ctypes.byref(n)), "windq_fallback_promote")
+    return n.value

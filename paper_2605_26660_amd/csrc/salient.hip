@@ -396,6 +396,47 @@ __global__ __launch_bounds__(64) void sal_err_kernel(const SalArgs A) {
     A.err_prot[u] = (float)e;
 }
 
+// ------------------------------------------------------------------- unit saliency
+// Saliency score of a unit (App. "Comparison with Heuristic Sensitivity Allocator"): the mean
+// of |w| * |s_c| over the unit.  Per tile an fp64 sum in a fixed order, per unit the tiles in order.
+template <int DT>
+__global__ __launch_bounds__(SAL_THREADS) void unit_saliency_tile_kernel(const void* __restrict__ W, const float* __restrict__ s,
+                                                                         const Geometry g, double* __restrict__ part) {
+    __shared__ float scol[WINDQ_MAX_CHUNK];
+    __shared__ double red[SAL_THREADS / 64];
+    const TileCoord tc = tile_coord(g, blockIdx.x);
+    const int32_t G = g.chunk_w;
+    for (int32_t c = threadIdx.x; c < G; c += SAL_THREADS) scol[c] = fabsf(s[tc.col0 + c]);
+    __syncthreads();
+    const int32_t pieces = G >> 3;
+    const int32_t total = tc.nrows * pieces;
+    double acc = 0.0;
+    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS) {
+        const int32_t r = i / pieces, pc = i - r * pieces;
+        float w[8];
+        load8g<DT>(W, (tc.row0 + r) * g.ld + tc.col0 + pc * 8, w);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc = fma((double)fabsf(w[j]), (double)scol[pc * 8 + j], acc);
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < SAL_THREADS / 64; ++w) t += red[w];
+        part[(size_t)tc.u * (size_t)g.tiles_per_unit + (size_t)tc.t] = t;
+    }
+}
+
+__global__ __launch_bounds__(64) void unit_saliency_finalize_kernel(const double* __restrict__ part, const Geometry g,
+                                                                   float* __restrict__ sal) {
+    const int64_t u = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (u >= g.U) return;
+    double t = 0.0;
+    for (int64_t i = 0; i < g.tiles_per_unit; ++i) t += part[(size_t)u * (size_t)g.tiles_per_unit + (size_t)i];
+    sal[u] = (float)(t / ((double)g.R_u * (double)g.chunk_w));
+}
+
 static size_t sal_tile_lds(int32_t dtype, int32_t chunk_w) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
 }
@@ -507,4 +548,22 @@ extern "C" int windq_salient_encode(const windq_mat* W, const float* s, int32_t 
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const size_t lds = sal_tile_lds(W->dtype, chunk_w);
     return W->dtype == WINDQ_BF16 ? launch_encode<WINDQ_BF16>(A, hs, lds) : launch_encode<WINDQ_F32>(A, hs, lds);
+}
+
+extern "C" int windq_unit_saliency(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, float* sal,
+                                   void* ws, size_t ws_bytes, void* stream) {
+    Geometry g;
+    const int st = make_geometry(W, chunk_w, unit_rows, &g);
+    if (st != WINDQ_OK) return st;
+    if (s == nullptr || sal == nullptr) return WINDQ_EINVAL;
+    if (ws == nullptr || ws_bytes < unit_saliency_ws_bytes(g) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
+    double* part = static_cast<double*>(ws);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const dim3 tiles((unsigned)g.n_tiles);
+    if (W->dtype == WINDQ_BF16)
+        hipLaunchKernelGGL(unit_saliency_tile_kernel<WINDQ_BF16>, tiles, dim3(SAL_THREADS), 0, hs, W->data, s, g, part);
+    else
+        hipLaunchKernelGGL(unit_saliency_tile_kernel<WINDQ_F32>, tiles, dim3(SAL_THREADS), 0, hs, W->data, s, g, part);
+    hipLaunchKernelGGL(unit_saliency_finalize_kernel, dim3((unsigned)((g.U + 63) / 64)), dim3(64), 0, hs, part, g, sal);
+    return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }

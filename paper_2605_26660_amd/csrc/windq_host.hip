@@ -3,6 +3,9 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
+#include <vector>
+
 #include "windq_common.hpp"
 #include "windq_ws.hpp"
 
@@ -134,8 +137,92 @@ size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, in
             return fit_score_ws_bytes(g, K);
         case WINDQ_CALL_APPLY_PLAN: return apply_ws_bytes(g);
         case WINDQ_CALL_SALIENT: return salient_ws_bytes(g);
+        case WINDQ_CALL_UNIT_SALIENCY: return unit_saliency_ws_bytes(g);
         default: return 0;
     }
+}
+
+// Eq. 5 for one unit, in centibits.
+static int64_t unit_cost(int a, int64_t n, int64_t n_p) {
+    return a == 0 ? 1600 * n : kCentibits[a] * (n - n_p) + 800 * n_p;
+}
+
+int windq_heuristic_plan(const float* sal, const int64_t* n_unit, const int64_t* n_prot, int64_t n_units,
+                         int64_t target_centibits, uint32_t frac_1bit_ppm, uint32_t frac_ternary_ppm,
+                         uint8_t* action, int64_t* total_centibits, int32_t* feasible) {
+    if (n_units < 0 || target_centibits < 0 || frac_1bit_ppm > 1000000u || frac_ternary_ppm > 1000000u)
+        return WINDQ_EINVAL;
+    if (total_centibits == nullptr || feasible == nullptr) return WINDQ_EINVAL;
+    if (n_units > 0 && (sal == nullptr || n_unit == nullptr || action == nullptr)) return WINDQ_EINVAL;
+    const int64_t U = n_units;
+    int64_t total_n = 0;
+    for (int64_t u = 0; u < U; ++u) {
+        const int64_t np = n_prot != nullptr ? n_prot[u] : 0;
+        if (n_unit[u] < 0 || np < 0 || np > n_unit[u] || sal[u] != sal[u]) return WINDQ_EINVAL;
+        total_n += n_unit[u];
+    }
+    // rank: most salient first, equal scores by index
+    std::vector<int64_t> order((size_t)U);
+    for (int64_t u = 0; u < U; ++u) order[(size_t)u] = u;
+    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) { return sal[a] > sal[b]; });
+    auto np_of = [&](int64_t u) { return n_prot != nullptr ? n_prot[u] : (int64_t)0; };
+    auto cost = [&](int64_t u, int a) { return unit_cost(a, n_unit[u], np_of(u)); };
+    const int64_t n1 = (int64_t)(((unsigned __int128)(uint64_t)U * frac_1bit_ppm) / 1000000u);
+    int64_t n158 = (int64_t)(((unsigned __int128)(uint64_t)U * frac_ternary_ppm) / 1000000u);
+    if (n158 > U - n1) n158 = U - n1;
+    for (int64_t u = 0; u < U; ++u) action[u] = 4;
+    for (int64_t i = U - n1; i < U; ++i) action[order[(size_t)i]] = 6;
+    for (int64_t i = U - n1 - n158; i < U - n1; ++i) action[order[(size_t)i]] = 5;
+    int64_t B = 0;
+    for (int64_t u = 0; u < U; ++u) B += cost(u, action[u]);
+    const int64_t budget = target_centibits * total_n;
+    // over budget: demote one level at a time from the least salient upward
+    while (B > budget) {
+        bool changed = false;
+        for (int64_t i = U - 1; i >= 0; --i) {
+            const int64_t u = order[(size_t)i];
+            if (action[u] == 4 || action[u] == 5) {
+                B += cost(u, action[u] + 1) - cost(u, action[u]);
+                action[u] = (uint8_t)(action[u] + 1);
+                changed = true;
+                if (B <= budget) break;
+            }
+        }
+        if (!changed) break;
+    }
+    // spend what is left on the most salient units: 2 -> 3 wherever it fits, then 3 -> 4
+    const int steps[2][2] = {{4, 3}, {3, 2}};
+    for (const auto& st : steps) {
+        for (int64_t i = 0; i < U; ++i) {
+            const int64_t u = order[(size_t)i];
+            if (action[u] == st[0] && B + cost(u, st[1]) - cost(u, st[0]) <= budget) {
+                B += cost(u, st[1]) - cost(u, st[0]);
+                action[u] = (uint8_t)st[1];
+            }
+        }
+    }
+    *total_centibits = B;
+    *feasible = B <= budget ? 1 : 0;
+    return WINDQ_OK;
+}
+
+int windq_fallback_promote(uint8_t* action, const float* err, const float* ref_energy, int64_t n_units,
+                           float max_rel_err, int64_t* n_changed) {
+    if (n_units < 0 || n_changed == nullptr || !(max_rel_err >= 0.0f)) return WINDQ_EINVAL;
+    if (n_units > 0 && (action == nullptr || err == nullptr || ref_energy == nullptr)) return WINDQ_EINVAL;
+    for (int64_t u = 0; u < n_units; ++u)
+        if (action[u] >= WINDQ_N_ACTIONS) return WINDQ_EINVAL;
+    int64_t changed = 0;
+    for (int64_t u = 0; u < n_units; ++u) {
+        int a = action[u];
+        const int a0 = a;
+        const double limit = (double)max_rel_err * (double)ref_energy[u];      // exact: two fp32 factors
+        while (a != 0 && !((double)err[u * WINDQ_N_ERR + (a - 1)] <= limit)) --a;
+        action[u] = (uint8_t)a;
+        changed += a != a0 ? 1 : 0;
+    }
+    *n_changed = changed;
+    return WINDQ_OK;
 }
 
 const char* windq_status_str(int status) {

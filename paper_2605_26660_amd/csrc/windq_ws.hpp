@@ -73,6 +73,9 @@ inline SalientLayout salient_layout(const Geometry& g) {
 }
 inline size_t salient_ws_bytes(const Geometry& g) { return salient_layout(g).total; }
 
+// ---- unit saliency: one fp64 partial per tile
+inline size_t unit_saliency_ws_bytes(const Geometry& g) { return round_up((size_t)g.n_tiles * sizeof(double), 256); }
+
 // ---- apply_plan needs no scratch; a token size keeps "ws != NULL" uniform across calls
 inline size_t apply_ws_bytes(const Geometry&) { return 256; }
 

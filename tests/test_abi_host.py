@@ -165,3 +165,57 @@ def test_binding_refuses_cpu_tensors(windq):
         windq.windq_fit_score_all_bits(W, s, 64, 0, torch.ones(1))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         windq.windq_calib_stats(W)
+
+
+# ------------------------------------------- heuristic allocator and fallback (host only)
+def test_heuristic_plan_matches_hand_examples_and_oracle(windq):
+    sal = torch.tensor([3.0, 1.0, 2.0, 0.5])
+    n = torch.full((4,), 100, dtype=torch.int64)
+    action, B, ok = windq.windq_heuristic_plan(sal, n, None, 200, frac_1bit_ppm=250000)
+    assert action.tolist() == [3, 4, 4, 6] and B == 80000 and ok
+    action, B, ok = windq.windq_heuristic_plan(torch.tensor([1.0, 2.0]), torch.tensor([10, 10]), None, 90)
+    assert action.tolist() == [6, 6] and not ok and B == 2000
+    rng = np.random.default_rng(12)
+    for trial in range(50):
+        U = int(rng.integers(1, 300))
+        sal = torch.from_numpy(rng.choice([0.25, 0.5, 1.0, 2.0, 7.0], U).astype(np.float32) * (1 + (trial % 2) * rng.random(U).astype(np.float32)))
+        n = torch.from_numpy(rng.integers(1, 50, U) * 8)
+        n_p = (n * 3) // 100 if trial % 3 else None
+        target = int(rng.integers(100, 450))
+        f1, f158 = int(rng.integers(0, 500000)), int(rng.integers(0, 500000))
+        action, B, ok = windq.windq_heuristic_plan(sal, n, n_p, target, f1, f158)
+        o_action, o_B, o_ok = O.heuristic_plan(sal.numpy(), n.numpy(), None if n_p is None else n_p.numpy(), target, f1, f158)
+        assert np.array_equal(action.numpy(), o_action) and B == o_B and ok == o_ok
+        cb, tot = windq.windq_effective_bits(action, n, n_p)
+        assert cb == B
+    with pytest.raises(windq.WindqError):
+        windq.windq_heuristic_plan(torch.tensor([float("nan")]), torch.tensor([8]), None, 200)
+    with pytest.raises(windq.WindqError):
+        windq.windq_heuristic_plan(torch.tensor([1.0]), torch.tensor([8]), torch.tensor([9]), 200)
+    action, B, ok = windq.windq_heuristic_plan(torch.empty(0), torch.empty(0, dtype=torch.int64), None, 200)
+    assert action.numel() == 0 and B == 0 and ok
+
+
+def test_fallback_promote_matches_hand_example_and_oracle(windq):
+    err = torch.tensor([[1e-6, 1e-4, 1e-3, 1e-2, 0.3, 0.5],
+                        [1e-6, 1e-4, 1e-3, 1e-2, 0.05, 0.08],
+                        [2.0, 2.0, 2.0, 2.0, 2.0, 2.0],
+                        [0, 0, 0, 0, 0, 0]], dtype=torch.float32)
+    ref = torch.ones(4)
+    action = torch.tensor([6, 6, 5, 0], dtype=torch.uint8)
+    assert windq.windq_fallback_promote(action, err, ref, 0.1) == 2 and action.tolist() == [4, 6, 0, 0]
+    action = torch.tensor([6, 5, 4, 3], dtype=torch.uint8)
+    assert windq.windq_fallback_promote(action, err, ref, 1e-3) == 3 and action.tolist() == [3, 3, 0, 3]
+    rng = np.random.default_rng(13)
+    for trial in range(20):
+        U = int(rng.integers(1, 200))
+        e = np.sort(rng.random((U, 6)).astype(np.float32) ** 4, axis=1)          # fewer bits, larger error
+        r = (rng.random(U).astype(np.float32) + 0.5)
+        a0 = rng.integers(0, 7, U).astype(np.uint8)
+        thr = float(rng.choice([1e-3, 1e-2, 0.1, 0.5]))
+        want, n_want = O.fallback_promote(a0, e, r, thr)
+        a = torch.from_numpy(a0.copy())
+        n_got = windq.windq_fallback_promote(a, torch.from_numpy(e), torch.from_numpy(r), thr)
+        assert np.array_equal(a.numpy(), want) and n_got == n_want
+    with pytest.raises(windq.WindqError):
+        windq.windq_fallback_promote(torch.tensor([7], dtype=torch.uint8), err[:1], ref[:1], 0.1)

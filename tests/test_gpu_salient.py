@@ -228,3 +228,45 @@ def test_masked_apply_plan_wide_dynamic_range(windq, G):
         assert np.array_equal(codes.cpu().numpy()[:int(off[-1])], oc), a
         assert np.array_equal(scale.cpu().numpy().view(np.uint32), osc.view(np.uint32)), a
         assert np.array_equal(offset.cpu().numpy().view(np.uint32), oof.view(np.uint32)), a
+
+
+# ------------------------------------------------- heuristic allocator, end to end
+@pytest.mark.parametrize("R,C,G,unit_rows,dtype", [(256, 512, 128, 0, torch.bfloat16), (200, 256, 64, 100, torch.bfloat16),
+                                                   (512, 512, 64, 0, torch.float32), (8, 16, 8, 4, torch.float32)])
+def test_unit_saliency(windq, R, C, G, unit_rows, dtype):
+    W = synth.weights_llm(R, C, seed=95, device=DEV, dtype=dtype)
+    X = synth.activations_llm(64, C, seed=96, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    sal = windq.windq_unit_saliency(W, s, G, unit_rows)
+    torch.cuda.synchronize()
+    want = O.unit_saliency(to_np(W), s.cpu().numpy(), G, unit_rows)
+    assert np.all(np.abs(sal.cpu().numpy() - want) <= REL * want)
+
+
+def test_heuristic_plan_with_protection_and_fallback_end_to_end(windq):
+    """Scores and errors from the device, plan and fallback on the host, plan applied under the mask:
+    the allocator's plan meets Eq. 1 with Eq. 5's protection overhead, and equals the oracle's."""
+    W = synth.weights_llm(512, 2048, seed=97, device=DEV)
+    X = synth.activations_llm(64, 2048, seed=98, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    G, ppm = 128, 30000
+    U, R_u = windq.n_units(512, 2048, G, 0)
+    mask = windq.windq_salient_select(W, s, G, 0, ppm)
+    cg = synth.clip_grid(20)
+    err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, G, 0, cg, mask=mask)
+    sal = windq.windq_unit_saliency(W, s, G, 0).cpu()
+    n = torch.full((U,), R_u * G, dtype=torch.int64)
+    n_p = torch.full((U,), windq.windq_n_protected(R_u * G, ppm), dtype=torch.int64)
+    action, B, ok = windq.windq_heuristic_plan(sal, n, n_p, 200, 250000, 250000)
+    o_action, o_B, o_ok = O.heuristic_plan(sal.numpy(), n.numpy(), n_p.numpy(), 200, 250000, 250000)
+    assert ok and np.array_equal(action.numpy(), o_action) and B == o_B
+    cb, tot = windq.windq_effective_bits(action, n, n_p)
+    assert cb == B and cb <= 200 * tot
+    a2 = action.clone()
+    changed = windq.windq_fallback_promote(a2, err.cpu(), ref.cpu(), 0.2)
+    want, n_want = O.fallback_promote(action.numpy(), err.cpu().numpy(), ref.cpu().numpy(), 0.2)
+    assert np.array_equal(a2.numpy(), want) and changed == n_want
+    off = windq.windq_plan_layout(a2, R_u, G)
+    codes, scale, offset = windq.windq_apply_plan(W, G, 0, a2.to(DEV), clip_idx, cg, off.to(DEV), mask=mask)
+    torch.cuda.synchronize()
+    assert codes.numel() >= int(off[-1]) and torch.isfinite(scale).all()

@@ -62,7 +62,8 @@ enum windq_call {
     WINDQ_CALL_FIT_SCORE = 2,
     WINDQ_CALL_APPLY_PLAN = 3,
     WINDQ_CALL_SALIENT = 4,       /* windq_salient_select and windq_salient_encode */
-    WINDQ_CALL_UNIT_SALIENCY = 5
+    WINDQ_CALL_UNIT_SALIENCY = 5,
+    WINDQ_CALL_DEQUANT = 6
 };
 
 #define WINDQ_N_ACTIONS 7
@@ -269,6 +270,26 @@ int windq_heuristic_plan(const float* sal /*HOST [U]*/, const int64_t* n_unit /*
 int windq_fallback_promote(uint8_t* action /*HOST in/out [U]*/, const float* err /*HOST [U][6]*/,
                            const float* ref_energy /*HOST [U]*/, int64_t n_units, float max_rel_err,
                            int64_t* n_changed /*HOST*/);
+
+/*
+ * The way back from the packed artefact (Sec. 3.5 scores a fit by its reconstruction error;
+ * this recomputes that error from the stored codes, scales and offsets alone).  For every
+ * unit of a plan as windq_apply_plan wrote it:
+ *   uniform:  w_hat = offset + code * scale    ternary: scale * (trit - 1)    binary: +-scale
+ *   err[u]    sum s_c^2 (w - w_hat)^2 with w_hat in fp64 from the stored fp32 numbers (what
+ *             windq_fit_score_all_bits reported for that bit-width and clip index); 0 for skip
+ *   w_hat     [rows][cols] fp32, dense: the reconstruction, one fused multiply-add per weight;
+ *             skip units keep their weights
+ * mask NULL or as in windq_apply_plan_prot: protected weights are left out of err and their
+ * w_hat is 0 (their values live in the INT8 side stream).  err or w_hat may be NULL, not both.
+ * Entries outside 0..6 or pointing outside [0, codes_bytes) count as skip.
+ */
+int windq_dequant_plan(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                       const uint8_t* mask /*[rows][cols/8] or NULL*/, const uint8_t* action /*[U]*/,
+                       const int64_t* code_off /*[U+1]*/, const uint8_t* codes, size_t codes_bytes,
+                       const float* scale /*[U*R_u]*/, const float* offset /*[U*R_u]*/,
+                       float* err /*[U] or NULL*/, float* w_hat /*[rows][cols] or NULL*/,
+                       void* ws, size_t ws_bytes, void* stream);
 
 /* Workspace bytes a call needs for these shapes (0 if the shape is invalid). HOST only. */
 size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, int64_t cols,

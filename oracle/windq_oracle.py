@@ -311,18 +311,15 @@ def pack_trits(trits: np.ndarray) -> np.ndarray:
 
 
 def unpack_bits(data: np.ndarray, bits: int, n: int) -> np.ndarray:
-    out = np.zeros(n, dtype=np.int64)
-    for i in range(n):
-        v = 0
-        for b in range(bits):
-            pos = i * bits + b
-            v |= ((int(data[pos // 8]) >> (pos % 8)) & 1) << b
-        out[i] = v
-    return out
+    """Inverse of pack_bits: code i is bits [i*bits, (i+1)*bits) of the LSB-first stream."""
+    stream = np.unpackbits(np.asarray(data, dtype=np.uint8), bitorder="little")[:n * bits].reshape(n, bits)
+    return (stream.astype(np.int64) << np.arange(bits)).sum(axis=1)
 
 
 def unpack_trits(data: np.ndarray, n: int) -> np.ndarray:
-    return np.array([(int(data[i // 5]) // 3 ** (i % 5)) % 3 for i in range(n)], dtype=np.int64)
+    """Inverse of pack_trits: trit j of a byte is (byte // 3^j) % 3."""
+    d = np.asarray(data, dtype=np.int64)[:, None] // np.array([1, 3, 9, 27, 81]) % 3
+    return d.ravel()[:n]
 
 
 def plan_layout(action: np.ndarray, R_u: int, G: int) -> np.ndarray:
@@ -395,6 +392,72 @@ def apply_plan(W: np.ndarray, G: int, unit_rows: int, action: np.ndarray,
             row = pack_trits(stored[r]) if a == 5 else pack_bits(stored[r], ACTION_CENTIBITS[a] // 100)
             codes[base + r * bpg: base + (r + 1) * bpg] = row
     return codes, scale, offset
+
+
+# ------------------------------------------------- dequantisation of a packed plan
+def unpack_group(data: np.ndarray, action: int, G: int) -> np.ndarray:
+    """Stored values (codes, trits q+1, bits) of one group from its packed bytes."""
+    if action == 5:
+        return unpack_trits(data, G)
+    return unpack_bits(data, ACTION_CENTIBITS[action] // 100, G)
+
+
+def dequant_plan(W: np.ndarray, G: int, unit_rows: int, action, code_off, codes, scale, offset, keep=None):
+    """Reconstruct the weights from the packed artefact alone (codes, per-group scale and
+    offset): uniform w_hat = offset + code * scale, ternary scale * (trit - 1), binary
+    scale * (2 bit - 1), each as ONE fp32 fused multiply-add of the stored fp32 numbers.
+    Skip units keep their 16-bit weights.  Protected slots (keep False) come out as 0: their
+    values live in the INT8 side stream.  Returns w_hat fp32 of W's shape."""
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    out = np.array(W, dtype=f32, copy=True)
+    for u in range(n_rb * n_chunks):
+        a = int(action[u])
+        if a == 0:
+            continue
+        rb, j = divmod(u, n_chunks)
+        bpg = bytes_per_group(a, G)
+        base = int(code_off[u])
+        for r in range(R_u):
+            stored = unpack_group(codes[base + r * bpg: base + (r + 1) * bpg], a, G).astype(f64)
+            sc, of = f64(scale[u * R_u + r]), f64(offset[u * R_u + r])
+            if a <= 4:
+                what = of + stored * sc
+            elif a == 5:
+                what = sc * (stored - 1.0)
+            else:
+                what = sc * (2.0 * stored - 1.0)
+            out[rb * R_u + r, j * G:(j + 1) * G] = what.astype(f32)   # the fp64 value of a*b+c of fp32 numbers, rounded once
+    if keep is not None:
+        quantized = np.repeat(np.repeat((np.asarray(action).reshape(n_rb, n_chunks) != 0), R_u, axis=0), G, axis=1)
+        out[quantized & ~keep] = 0.0
+    return out
+
+
+def dequant_error(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int, action, code_off, codes, scale, offset,
+                  keep=None) -> np.ndarray:
+    """Activation-weighted error of a packed plan, recomputed from the artefact: per unit
+    sum a_c (w - w_hat)^2 with w_hat = offset + code * scale in fp64 from the stored fp32
+    numbers (the same w_hat the fit scored).  Skip units: 0.  Protected weights are left out."""
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    U = n_rb * n_chunks
+    err = np.zeros(U, dtype=f64)
+    for u in range(U):
+        a = int(action[u])
+        if a == 0:
+            continue
+        j = u % n_chunks
+        Wu = unit_view(W, G, unit_rows, u).astype(f64)
+        ku = None if keep is None else unit_view(keep, G, unit_rows, u)
+        av = s[j * G:(j + 1) * G].astype(f64) ** 2
+        bpg = bytes_per_group(a, G)
+        base = int(code_off[u])
+        What = np.zeros_like(Wu)
+        for r in range(R_u):
+            stored = unpack_group(codes[base + r * bpg: base + (r + 1) * bpg], a, G).astype(f64)
+            sc, of = f64(scale[u * R_u + r]), f64(offset[u * R_u + r])
+            What[r] = of + stored * sc if a <= 4 else (sc * (stored - 1.0) if a == 5 else sc * (2.0 * stored - 1.0))
+        err[u] = weighted_sse(Wu, What, av, ku)
+    return err
 
 
 # ------------------------------------------- salient-weight protection (Sec. 3.5)

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libwindq.so")
 
 WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP = range(6)
 WINDQ_F32, WINDQ_BF16 = 0, 1
-CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY = range(6)
+CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT = range(7)
 N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK = 7, 6, 8, 64, 512
 
 EXPORTS = (
@@ -24,7 +24,7 @@ EXPORTS = (
     "windq_plan_layout", "windq_apply_plan", "windq_effective_bits", "windq_workspace_bytes",
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
-    "windq_fallback_promote",
+    "windq_fallback_promote", "windq_dequant_plan",
 )
 
 
@@ -76,12 +76,13 @@ def load(path: str | None = None):
     lib.windq_unit_saliency.argtypes = [pm, vp, i32, i64, vp, vp, sz, vp]
     lib.windq_heuristic_plan.argtypes = [vp, vp, vp, i64, i64, u32, u32, vp, c.POINTER(i64), c.POINTER(i32)]
     lib.windq_fallback_promote.argtypes = [vp, vp, vp, i64, c.c_float, c.POINTER(i64)]
+    lib.windq_dequant_plan.argtypes = [pm, vp, i32, i64, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, sz, vp]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
                  "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode",
                  "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency",
-                 "windq_heuristic_plan", "windq_fallback_promote"):
+                 "windq_heuristic_plan", "windq_fallback_promote", "windq_dequant_plan"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -320,3 +321,21 @@ def windq_fallback_promote(action: torch.Tensor, err: torch.Tensor, ref: torch.T
     _check(load().windq_fallback_promote(action.data_ptr(), err.data_ptr(), ref.data_ptr(), action.numel(),
                                          max_rel_err, ctypes.byref(n)), "windq_fallback_promote")
     return n.value
+
+
+# ------------------------------------------------------------------- dequantisation
+def windq_dequant_plan(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, action: torch.Tensor,
+                       code_off: torch.Tensor, codes: torch.Tensor, scale: torch.Tensor, offset: torch.Tensor,
+                       mask: torch.Tensor | None = None, want_w_hat: bool = True, ws: torch.Tensor | None = None):
+    """Device tensors as windq_apply_plan wrote them.  -> (err f32 [U], w_hat f32 [rows x cols] or None)."""
+    _require_cuda(W, s, action, code_off, codes, scale, offset, mask)
+    U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    err = torch.empty(U, dtype=torch.float32, device=W.device)
+    w_hat = torch.empty(W.shape[0], W.shape[1], dtype=torch.float32, device=W.device) if want_w_hat else None
+    ws = _workspace(CALL_DEQUANT, W, chunk_w, unit_rows, 1, ws)
+    m = as_mat(W)
+    _check(load().windq_dequant_plan(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, _ptr(mask), action.data_ptr(),
+                                     code_off.data_ptr(), codes.data_ptr(), codes.numel(), scale.data_ptr(),
+                                     offset.data_ptr(), err.data_ptr(), _ptr(w_hat), ws.data_ptr(), ws.numel(),
+                                     _stream()), "windq_dequant_plan")
+    return err, w_hat

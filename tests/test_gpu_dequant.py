@@ -1,0 +1,94 @@
+"""GPU parity of windq_dequant_plan: the error recomputed from the packed artefact against the
+oracle's and against what the fit reported; the reconstruction against the oracle's."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import windq_oracle as O
+from paper_2605_26660_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+REL = 1e-5
+
+
+def to_np(t):
+    return t.float().cpu().numpy()
+
+
+def run_case(windq, W, s, G, unit_rows, K, ppm=0, oracle_units=True):
+    cg = synth.clip_grid(K)
+    mask = keep = None
+    if ppm:
+        mask = windq.windq_salient_select(W, s, G, unit_rows, ppm)
+    err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, G, unit_rows, cg, mask=mask)
+    U, R_u = windq.n_units(W.shape[0], W.shape[1], G, unit_rows)
+    for shift in (0, 3):
+        action = ((torch.arange(U) + shift) % 7).to(torch.uint8)
+        off = windq.windq_plan_layout(action, R_u, G)
+        codes, scale, offset = windq.windq_apply_plan(W, G, unit_rows, action.to(DEV), clip_idx, cg, off.to(DEV), mask=mask)
+        d_err, w_hat = windq.windq_dequant_plan(W, s, G, unit_rows, action.to(DEV), off.to(DEV), codes, scale, offset, mask=mask)
+        torch.cuda.synchronize()
+        g = d_err.cpu().numpy().astype(np.float64)
+        # the loop closes on the device's own numbers: error from the artefact = error the fit reported
+        fit = err.cpu().numpy().astype(np.float64)
+        want_fit = np.array([0.0 if a == 0 else fit[u, a - 1] for u, a in enumerate(action.tolist())])
+        assert np.all(np.abs(g - want_fit) <= 2 * REL * want_fit), np.max(np.abs(g - want_fit) / (want_fit + 1e-300))
+        if not oracle_units:
+            continue
+        Wn, sn = to_np(W), s.cpu().numpy()
+        if ppm and keep is None:
+            keep = O.salient_select(Wn, sn, G, unit_rows, ppm)
+        args = (action.numpy(), off.numpy(), codes.cpu().numpy(), scale.cpu().numpy(), offset.cpu().numpy())
+        o_err = O.dequant_error(Wn, sn, G, unit_rows, *args, keep=keep)
+        assert np.all(np.abs(g - o_err) <= REL * o_err)
+        o_hat = O.dequant_plan(Wn, G, unit_rows, *args, keep=keep)
+        got = w_hat.cpu().numpy()
+        # one fused multiply-add on the device, fp64-then-fp32 in the oracle: equal but for the last bit in rare cases
+        assert np.all(np.abs(got - o_hat) <= np.spacing(np.abs(o_hat)))
+        assert np.mean(got != o_hat) < 1e-3
+
+
+@pytest.mark.parametrize("R,C,G,unit_rows,K,dtype", [
+    (256, 512, 128, 0, 20, torch.bfloat16), (200, 256, 64, 100, 7, torch.bfloat16),
+    (512, 512, 64, 0, 20, torch.float32), (24, 80, 40, 3, 5, torch.bfloat16), (70, 96, 32, 0, 4, torch.bfloat16),
+    (64, 512, 256, 0, 6, torch.bfloat16)])
+def test_dequant_closes_the_loop(windq, R, C, G, unit_rows, K, dtype):
+    W = synth.weights_llm(R, C, seed=101, device=DEV, dtype=dtype)
+    X = synth.activations_llm(64, C, seed=102, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    run_case(windq, W, s, G, unit_rows, K)
+
+
+@pytest.mark.parametrize("R,C,G,unit_rows,ppm", [(256, 512, 128, 0, 30000), (200, 256, 64, 100, 50000), (70, 96, 32, 0, 300000)])
+def test_dequant_under_a_protection_mask(windq, R, C, G, unit_rows, ppm):
+    W = synth.weights_llm(R, C, seed=103, device=DEV)
+    X = synth.activations_llm(64, C, seed=104, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    run_case(windq, W, s, G, unit_rows, 8, ppm=ppm)
+
+
+def test_dequant_full_size_matrix_closes_the_loop_everywhere(windq):
+    """mlp.down-shaped 4096 x 11008 bf16: every unit's error from the artefact equals the fit's."""
+    W = synth.weights_llm(4096, 11008, seed=105, device=DEV)
+    X = synth.activations_llm(512, 11008, seed=106, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    run_case(windq, W, s, 128, 0, 20, oracle_units=False)
+    run_case(windq, W, s, 128, 0, 20, ppm=30000, oracle_units=False)
+
+
+def test_malformed_entries_read_nothing(windq):
+    W = synth.weights_llm(64, 256, seed=107, device=DEV)
+    s = torch.ones(256, device=DEV)
+    action = torch.tensor([1, 9], dtype=torch.uint8)
+    off = torch.tensor([0, 64 * 128, 64 * 128], dtype=torch.int64)
+    codes = torch.zeros(64 * 128, dtype=torch.uint8, device=DEV)
+    scale = torch.zeros(128, device=DEV)
+    offset = torch.zeros(128, device=DEV)
+    err, w_hat = windq.windq_dequant_plan(W, s, 128, 0, action.to(DEV), off.to(DEV), codes, scale, offset)
+    torch.cuda.synchronize()
+    assert float(err[1]) == 0.0 and torch.equal(w_hat[:, 128:], W[:, 128:].float())
+    short = codes[:1024]                                      # unit 0's payload no longer fits: treated as skip
+    err, w_hat = windq.windq_dequant_plan(W, s, 128, 0, action.to(DEV), off.to(DEV), short, scale, offset)
+    torch.cuda.synchronize()
+    assert float(err[0]) == 0.0 and torch.equal(w_hat, W.float())

@@ -394,6 +394,160 @@ def apply_plan(W: np.ndarray, G: int, unit_rows: int, action: np.ndarray,
     return codes, scale, offset
 
 
+# ------------------------------- iterative scale refinement (App. "Per-unit Scale Optimization")
+def _weighted_sums_uniform(w64, q, a, kept):
+    """Column-order fp64 sums of the weighted least-squares problem  min sum a (w - lo - q step)^2:
+    S0 = sum a, S1 = sum a q, S2 = sum a q^2, T0 = sum a w, T1 = sum a q w  (plain multiplies and adds)."""
+    S0 = S1 = S2 = T0 = T1 = f64(0)
+    for c in range(len(w64)):
+        if not kept[c]:
+            continue
+        aq = a[c] * q[c]
+        S0 = S0 + a[c]
+        S1 = S1 + aq
+        S2 = S2 + aq * q[c]
+        T0 = T0 + a[c] * w64[c]
+        T1 = T1 + aq * w64[c]
+    return S0, S1, S2, T0, T1
+
+
+def refine_group_uniform(w: np.ndarray, a: np.ndarray, lo, delta, bits: int, n_iter: int, kept=None):
+    """The paper fits each operator's scale by a short local optimisation of the reconstruction
+    loss on the unit.  Deterministic stand-in: alternate (assign codes by the normative fp32
+    steps | solve the activation-weighted least-squares problem for offset and step in closed
+    form), seeded from the grid fit; the loss cannot go up in either half-step.  fp64 sums in
+    column order; offset and step are rounded to fp32 after every solve [N].  An iteration whose
+    problem is singular (all codes equal) or whose step would fall below the smallest normal
+    fp32 stops the refinement.  Returns (lo f32, step f32)."""
+    w = np.asarray(w, dtype=f32)
+    w64 = w.astype(f64)
+    kept = np.ones(len(w), dtype=bool) if kept is None else kept
+    lo, delta = f32(lo), f32(delta)
+    qmax = 2 ** bits - 1
+    for _ in range(n_iter):
+        if not delta >= FLT_MIN_NORMAL:
+            break
+        inv = f32(1) / delta                                     # [N]
+        q = np.clip(np.rint(((w - lo).astype(f32) * inv).astype(f32)), 0, qmax).astype(f64)   # [N]
+        S0, S1, S2, T0, T1 = _weighted_sums_uniform(w64, q, a, kept)
+        det = S0 * S2 - S1 * S1
+        if not det > 0:
+            break
+        d_new = (S0 * T1 - S1 * T0) / det
+        lo_new = (T0 - S1 * d_new) / S0
+        d32, lo32 = f32(d_new), f32(lo_new)
+        if not d32 >= FLT_MIN_NORMAL:
+            break
+        lo, delta = lo32, d32
+    return lo, delta
+
+
+def refine_group_ternary(w: np.ndarray, a: np.ndarray, gamma, n_iter: int, kept=None):
+    """Same alternation for the ternary operator: q = clamp(rne(w / gamma), -1, 1), then
+    gamma = sum a q w / sum a q^2.  Returns gamma f32."""
+    w = np.asarray(w, dtype=f32)
+    w64 = w.astype(f64)
+    kept = np.ones(len(w), dtype=bool) if kept is None else kept
+    gamma = f32(gamma)
+    for _ in range(n_iter):
+        if not gamma >= FLT_MIN_NORMAL:
+            break
+        inv = f32(1) / gamma
+        q = np.clip(np.rint((w * inv).astype(f32)), -1, 1).astype(f64)
+        N1 = D1 = f64(0)
+        for c in range(len(w)):
+            if kept[c]:
+                aq = a[c] * q[c]
+                N1 = N1 + aq * w64[c]
+                D1 = D1 + aq * q[c]
+        if not D1 > 0:
+            break
+        g = f32(N1 / D1)
+        if not g >= FLT_MIN_NORMAL:
+            break
+        gamma = g
+    return gamma
+
+
+def refine_group_binary(w: np.ndarray, a: np.ndarray, alpha, kept=None):
+    """The signs are fixed, so one solve is the optimum: alpha = sum a |w| / sum a."""
+    w64 = np.abs(np.asarray(w, dtype=f32).astype(f64))
+    kept = np.ones(len(w64), dtype=bool) if kept is None else kept
+    N1 = D1 = f64(0)
+    for c in range(len(w64)):
+        if kept[c]:
+            N1 = N1 + a[c] * w64[c]
+            D1 = D1 + a[c]
+    return f32(N1 / D1) if D1 > 0 else f32(alpha)
+
+
+def refine_plan(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int, action, clip_idx, clip_grid, code_off,
+                n_iter: int, units=None, keep=None):
+    """apply_plan with refined scales: every group is seeded with its grid fit (at the unit's
+    clip index), refined for n_iter alternations, and quantized by the normative steps at the
+    refined parameters.  Returns (codes, scale, offset, err [U] fp64: the activation-weighted
+    error of the refined plan over kept weights, 0 for skip units)."""
+    clip_grid = np.asarray(clip_grid, dtype=f32)
+    n_rb, n_chunks, R_u = unit_shape(W.shape[0], W.shape[1], G, unit_rows)
+    U = n_rb * n_chunks
+    codes = np.zeros(int(code_off[U]), dtype=np.uint8)
+    scale = np.zeros(U * R_u, dtype=f32)
+    offset = np.zeros(U * R_u, dtype=f32)
+    err = np.zeros(U, dtype=f64)
+    for u in (range(U) if units is None else units):
+        act = int(action[u])
+        if act == 0:
+            continue
+        j = u % n_chunks
+        Wu = np.ascontiguousarray(unit_view(W, G, unit_rows, u), dtype=f32)
+        ku = None if keep is None else unit_view(keep, G, unit_rows, u)
+        a = s[j * G:(j + 1) * G].astype(f64) ** 2
+        mn, mx, S1 = group_stats(Wu, ku)
+        n_g = G if ku is None else ku.sum(axis=1)
+        bpg = bytes_per_group(act, G)
+        base = int(code_off[u])
+        What = np.zeros(Wu.shape, dtype=f64)
+        for r in range(R_u):
+            kr = None if ku is None else ku[r]
+            one = slice(r, r + 1)
+            if act <= 4:
+                bits = ACTION_CENTIBITS[act] // 100
+                p = f32(1) if clip_idx is None else clip_grid[int(clip_idx[u, act - 1])]
+                lo, delta, inv, deg = uniform_fit(mn[one], mx[one], p, bits)
+                lo_r, d_r = refine_group_uniform(Wu[r], a, lo[0], delta[0], bits, n_iter, kr)
+                lo1, d1 = np.array([lo_r], dtype=f32), np.array([d_r], dtype=f32)
+                deg1 = ~(d1 >= FLT_MIN_NORMAL)
+                with np.errstate(divide="ignore"):
+                    inv1 = (f32(1) / d1).astype(f32)
+                stored = uniform_codes(Wu[one], lo1, d1, inv1, deg1, bits)[0]
+                What[r] = lo1.astype(f64)[0] + stored.astype(f64) * d1.astype(f64)[0]
+                sc_r, of_r = d1[0], lo1[0]
+            elif act == 5:
+                gamma, ginv, gdeg = ternary_fit(S1[one], n_g if ku is None else n_g[one])
+                g_r = np.array([refine_group_ternary(Wu[r], a, gamma[0], n_iter, kr)], dtype=f32)
+                deg1 = ~(g_r >= FLT_MIN_NORMAL)
+                with np.errstate(divide="ignore"):
+                    inv1 = (f32(1) / g_r).astype(f32)
+                q = ternary_codes(Wu[one], inv1, deg1)[0]
+                stored = q + 1
+                What[r] = g_r.astype(f64)[0] * q
+                sc_r, of_r = g_r[0], f32(0)
+            else:
+                alpha = absmean_scale(S1[one], n_g if ku is None else n_g[one])
+                al = refine_group_binary(Wu[r], a, alpha[0], kr) if n_iter > 0 else alpha[0]
+                stored = binary_codes(Wu[one])[0]
+                What[r] = f64(al) * (2 * stored - 1)
+                sc_r, of_r = al, f32(0)
+            if kr is not None:
+                stored = np.where(kr, stored, 0)
+            scale[u * R_u + r] = sc_r
+            offset[u * R_u + r] = of_r
+            row = pack_trits(stored) if act == 5 else pack_bits(stored, ACTION_CENTIBITS[act] // 100)
+            codes[base + r * bpg: base + (r + 1) * bpg] = row
+        err[u] = weighted_sse(Wu.astype(f64), What, a, ku)
+    return codes, scale, offset, err
+
+
 # ------------------------------------------------- dequantisation of a packed plan
 def unpack_group(data: np.ndarray, action: int, G: int) -> np.ndarray:
     """Stored values (codes, trits q+1, bits) of one group from its packed bytes."""

@@ -53,7 +53,7 @@ def build_block(wq, synth, torch, dev, unit_rows):
         action = synth.random_plan(U, R_u * G, TARGET_CENTIBITS, seed=100 + i)
         off = wq.windq_plan_layout(action, R_u, G)
         need = max(wq.workspace_bytes(c, wq.WINDQ_BF16, sp.rows, sp.cols, G, unit_rows, K)
-                   for c in (wq.CALL_UNIT_FEATURES, wq.CALL_FIT_SCORE, wq.CALL_APPLY_PLAN, wq.CALL_DEQUANT))
+                   for c in (wq.CALL_UNIT_FEATURES, wq.CALL_FIT_SCORE, wq.CALL_APPLY_PLAN, wq.CALL_DEQUANT, wq.CALL_REFINE))
         mats.append(dict(
             spec=sp, W=W, U=U, R_u=R_u, action=action, action_d=action.to(dev), off=off, off_d=off.to(dev),
             n_unit=torch.full((U,), R_u * G, dtype=torch.int64),
@@ -144,6 +144,9 @@ def protected_pass(wq, torch, cg, xs, mats, unit_rows, ppm, reps):
             timer.time("apply_plan_prot", lambda: wq.windq_apply_plan(
                 m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"], ws=m["ws"],
                 out=(m["scale"], m["offset"]), mask=e["mask"]))
+            timer.time("refine_plan_prot_3_rounds", lambda: wq.windq_refine_plan(
+                m["W"], s, G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], 3, codes=m["codes"], mask=e["mask"],
+                ws=m["ws"]))
             timer.time("dequant_plan_prot", lambda: wq.windq_dequant_plan(
                 m["W"], s, G, unit_rows, m["action_d"], m["off_d"], m["codes"], m["scale"], m["offset"], mask=e["mask"],
                 want_w_hat=False, ws=m["ws"]))
@@ -153,7 +156,8 @@ def protected_pass(wq, torch, cg, xs, mats, unit_rows, ppm, reps):
     torch.cuda.synchronize()
     n_weights = sum(m["spec"].rows * m["spec"].cols for m in mats)
     res = {"rate_ppm": ppm, "avg_bits": total_cb / (100.0 * total_n)}
-    for name in ("salient_select", "salient_encode", "fit_score_all_bits_prot", "apply_plan_prot", "dequant_plan_prot"):
+    for name in ("salient_select", "salient_encode", "fit_score_all_bits_prot", "apply_plan_prot", "refine_plan_prot_3_rounds",
+                 "dequant_plan_prot"):
         ms = timer.ms(name)
         per = len(ms) // reps
         steps = sorted(sum(ms[i * per:(i + 1) * per]) for i in range(reps))

@@ -63,7 +63,8 @@ enum windq_call {
     WINDQ_CALL_APPLY_PLAN = 3,
     WINDQ_CALL_SALIENT = 4,       /* windq_salient_select and windq_salient_encode */
     WINDQ_CALL_UNIT_SALIENCY = 5,
-    WINDQ_CALL_DEQUANT = 6
+    WINDQ_CALL_DEQUANT = 6,
+    WINDQ_CALL_REFINE = 7
 };
 
 #define WINDQ_N_ACTIONS 7
@@ -290,6 +291,29 @@ int windq_dequant_plan(const windq_mat* W, const float* s /*[cols]*/, int32_t ch
                        const float* scale /*[U*R_u]*/, const float* offset /*[U*R_u]*/,
                        float* err /*[U] or NULL*/, float* w_hat /*[rows][cols] or NULL*/,
                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * windq_apply_plan with refined scales (App. "Per-unit Scale Optimization": each operator fits
+ * its scale by a short local optimisation of the reconstruction loss on the unit).  Every
+ * group is seeded with its grid fit (clip ratio clip_grid[clip_idx[u][a-1]], p = 1 when
+ * clip_idx is NULL) and refined for n_iter (0..64) rounds of
+ *     codes by the fp32 steps of windq_fit_score_all_bits  |  closed-form activation-weighted
+ *     least squares: uniform (offset, step) from the 2x2 normal equations of
+ *     min sum s_c^2 (w - offset - code * step)^2; ternary gamma = sum s_c^2 q w / sum s_c^2 q^2;
+ *     binary (signs fixed, one solve when n_iter >= 1) alpha = sum s_c^2 |w| / sum s_c^2.
+ * Sums are fp64 in column order, parameters are rounded to fp32 after every solve; a round
+ * whose problem is singular or whose step would be below the smallest normal fp32 ends the
+ * refinement of that group.  Outputs as windq_apply_plan, plus
+ *   err [U]   the activation-weighted error of the refined plan (0 for skip units).
+ * mask NULL or as in windq_apply_plan_prot.  n_iter = 0 reproduces windq_apply_plan.
+ */
+int windq_refine_plan(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                      const uint8_t* mask /*[rows][cols/8] or NULL*/,
+                      const uint8_t* action /*[U]*/, const uint8_t* clip_idx /*[U][4] or NULL*/,
+                      const float* clip_grid /*HOST [K]*/, int32_t K, int32_t n_iter,
+                      const int64_t* code_off /*[U+1]*/, uint8_t* codes, size_t codes_bytes,
+                      float* scale /*[U*R_u]*/, float* offset /*[U*R_u]*/, float* err /*[U]*/,
+                      void* ws, size_t ws_bytes, void* stream);
 
 /* Workspace bytes a call needs for these shapes (0 if the shape is invalid). HOST only. */
 size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, int64_t cols,

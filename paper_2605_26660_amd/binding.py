@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libwindq.so")
 
 WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP = range(6)
 WINDQ_F32, WINDQ_BF16 = 0, 1
-CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT = range(7)
+CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT, CALL_REFINE = range(8)
 N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK = 7, 6, 8, 64, 512
 
 EXPORTS = (
@@ -24,7 +24,7 @@ EXPORTS = (
     "windq_plan_layout", "windq_apply_plan", "windq_effective_bits", "windq_workspace_bytes",
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
-    "windq_fallback_promote", "windq_dequant_plan",
+    "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan",
 )
 
 
@@ -77,12 +77,14 @@ def load(path: str | None = None):
     lib.windq_heuristic_plan.argtypes = [vp, vp, vp, i64, i64, u32, u32, vp, c.POINTER(i64), c.POINTER(i32)]
     lib.windq_fallback_promote.argtypes = [vp, vp, vp, i64, c.c_float, c.POINTER(i64)]
     lib.windq_dequant_plan.argtypes = [pm, vp, i32, i64, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, sz, vp]
+    lib.windq_refine_plan.argtypes = [pm, vp, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp, vp, sz, vp]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
                  "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode",
                  "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency",
-                 "windq_heuristic_plan", "windq_fallback_promote", "windq_dequant_plan"):
+                 "windq_heuristic_plan", "windq_fallback_promote", "windq_dequant_plan",
+                 "windq_refine_plan"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -339,3 +341,27 @@ def windq_dequant_plan(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows
                                      offset.data_ptr(), err.data_ptr(), _ptr(w_hat), ws.data_ptr(), ws.numel(),
                                      _stream()), "windq_dequant_plan")
     return err, w_hat
+
+
+# ------------------------------------------------------------- iterative refinement
+def windq_refine_plan(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, action: torch.Tensor, clip_idx,
+                      clip_grid, code_off: torch.Tensor, n_iter: int, codes: torch.Tensor | None = None,
+                      mask: torch.Tensor | None = None, ws: torch.Tensor | None = None):
+    """windq_apply_plan with n_iter rounds of closed-form scale refinement.
+    -> (codes u8, scale f32 [U*R_u], offset f32 [U*R_u], err f32 [U]) on the device."""
+    _require_cuda(W, s, action, clip_idx, code_off, codes, mask)
+    U, R_u = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    if codes is None:
+        codes = torch.empty(max(int(code_off[-1].item()), 16), dtype=torch.uint8, device=W.device)
+    scale = torch.empty(U * R_u, dtype=torch.float32, device=W.device)
+    offset = torch.empty(U * R_u, dtype=torch.float32, device=W.device)
+    err = torch.empty(U, dtype=torch.float32, device=W.device)
+    K = 0 if clip_grid is None else clip_grid.numel()
+    ws = _workspace(CALL_REFINE, W, chunk_w, unit_rows, 1, ws)
+    m = as_mat(W)
+    _check(load().windq_refine_plan(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, _ptr(mask), action.data_ptr(),
+                                    _ptr(clip_idx), None if clip_grid is None else clip_grid.data_ptr(), K, n_iter,
+                                    code_off.data_ptr(), codes.data_ptr(), codes.numel(), scale.data_ptr(),
+                                    offset.data_ptr(), err.data_ptr(), ws.data_ptr(), ws.numel(), _stream()),
+           "windq_refine_plan")
+    return codes, scale, offset, err

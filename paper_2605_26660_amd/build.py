@@ -13,7 +13,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libwindq.so")
 
-SOURCES = ["windq_host.hip", "calib_stats.hip", "unit_features.hip", "fit_score.hip", "apply_plan.hip", "salient.hip", "dequant.hip"]
+SOURCES = ["windq_host.hip", "calib_stats.hip", "unit_features.hip", "fit_score.hip", "apply_plan.hip", "salient.hip", "dequant.hip", "refine.hip"]
 
 # -ffp-contract=off: stored scales and codes are defined by single IEEE fp32 operations;
 #   fused multiply-adds appear only where the source calls fma().

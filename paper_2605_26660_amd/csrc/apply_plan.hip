@@ -22,6 +22,7 @@
 #include <type_traits>
 
 #include "windq_common.hpp"
+#include "windq_group.hpp"
 #include "windq_ws.hpp"
 
 namespace windq {
@@ -43,157 +44,6 @@ struct ApplyArgs {
     int32_t K;
     ClipGrid grid;
 };
-
-__device__ __forceinline__ int64_t dev_bytes_per_group(int a, int G) {
-    switch (a) {
-        case 1: return G;
-        case 2: return G >> 1;
-        case 3: return (G * 3) >> 3;
-        case 4: return G >> 2;
-        case 5: return (G + 4) / 5;
-        case 6: return G >> 3;
-        default: return 0;
-    }
-}
-
-// Eight BITS-bit codes -> BITS bytes, LSB first, stored at dst (which is aligned to the
-// natural width of the store used).
-template <int BITS>
-__device__ __forceinline__ void store_codes8(uint8_t* dst, const uint32_t (&c)[8]) {
-    uint64_t v = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) v |= (uint64_t)c[j] << (j * BITS);
-    if (BITS == 8) {
-        *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)v, (uint32_t)(v >> 32));
-    } else if (BITS == 4) {
-        *reinterpret_cast<uint32_t*>(dst) = (uint32_t)v;
-    } else if (BITS == 2) {
-        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)v;
-    } else if (BITS == 3) {
-        dst[0] = (uint8_t)v;
-        dst[1] = (uint8_t)(v >> 8);
-        dst[2] = (uint8_t)(v >> 16);
-    } else {
-        dst[0] = (uint8_t)v;
-    }
-}
-
-// Uniform BITS-bit quantizer of one group, normative fp32 steps.  mrow: the row's protection
-// bits (null: none); protected weights stay out of min/max and their code slot holds 0.
-template <int DT, int BITS>
-__device__ __forceinline__ void quantize_uniform(const char* wrow, const uint8_t* __restrict__ mrow, int32_t G, float p,
-                                                 uint8_t* dst, float* scale_out, float* offset_out) {
-    float w[8];
-    float mn, mx;
-    if (mrow == nullptr) {
-        read8<DT>(wrow, 0, w);
-        mn = mx = w[0];
-        for (int32_t c = 0; c < G; c += 8) {
-            read8<DT>(wrow, c, w);
-            mn = fminf(fminf(fminf(mn, w[0]), fminf(w[1], w[2])), fminf(fminf(w[3], w[4]), fminf(w[5], fminf(w[6], w[7]))));
-            mx = fmaxf(fmaxf(fmaxf(mx, w[0]), fmaxf(w[1], w[2])), fmaxf(fmaxf(w[3], w[4]), fmaxf(w[5], fmaxf(w[6], w[7]))));
-        }
-    } else {
-        mn = INFINITY;
-        mx = -INFINITY;
-        for (int32_t c = 0; c < G; c += 8) {
-            read8<DT>(wrow, c, w);
-            const uint32_t m = mrow[c >> 3];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool kept = ((m >> j) & 1u) == 0u;
-                mn = fminf(mn, kept ? w[j] : INFINITY);
-                mx = fmaxf(mx, kept ? w[j] : -INFINITY);
-            }
-        }
-        if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
-    }
-    const float qmax = (float)((1 << BITS) - 1);
-    const float lo = p * mn;
-    const float hi = p * mx;
-    const float rg = hi - lo;
-    float d = rg / qmax;
-    const bool ok = d >= FLT_MIN;
-    d = ok ? d : 0.0f;
-    const float inv = ok ? 1.0f / d : 0.0f;
-    *scale_out = d;
-    *offset_out = lo;
-    for (int32_t c = 0; c < G; c += 8) {
-        read8<DT>(wrow, c, w);
-        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;     // read before the codes overwrite the row in place
-        uint32_t code[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float u = w[j] - lo;
-            const float t = u * inv;
-            const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, qmax);
-            code[j] = ((m >> j) & 1u) != 0u ? 0u : (uint32_t)q;
-        }
-        store_codes8<BITS>(dst + (c >> 3) * BITS, code);
-    }
-}
-
-// Mean |w| of a group as stored: the fp64 sum in column order (exact for bf16 inputs) over the
-// kept weights, divided by their number, rounded to fp32; 0 when none is kept.
-template <int DT>
-__device__ __forceinline__ float group_abs_mean(const char* wrow, const uint8_t* __restrict__ mrow, int32_t G) {
-    double S1 = 0.0;
-    int32_t n = G;
-    for (int32_t c = 0; c < G; c += 8) {
-        float w[8];
-        read8<DT>(wrow, c, w);
-        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
-        n -= __builtin_popcount(m);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) S1 += ((m >> j) & 1u) != 0u ? 0.0 : (double)fabsf(w[j]);
-    }
-    return n > 0 ? (float)(S1 / (double)n) : 0.0f;
-}
-
-template <int DT>
-__device__ __forceinline__ void quantize_ternary(const char* wrow, const uint8_t* __restrict__ mrow, int32_t G,
-                                                 uint8_t* dst, float* scale_out) {
-    float gamma = group_abs_mean<DT>(wrow, mrow, G);
-    const bool ok = gamma >= FLT_MIN;
-    gamma = ok ? gamma : 0.0f;
-    const float inv = ok ? 1.0f / gamma : 0.0f;
-    *scale_out = gamma;
-    uint32_t byte = 0, mul = 1;
-    int32_t nb = 0;
-    for (int32_t c = 0; c < G; c += 8) {
-        float w[8];
-        read8<DT>(wrow, c, w);
-        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float t = w[j] * inv;
-            const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -1.0f, 1.0f);
-            byte += (((m >> j) & 1u) != 0u ? 0u : (uint32_t)((int32_t)q + 1)) * mul;
-            mul *= 3;
-            if (mul == 243) {
-                dst[nb++] = (uint8_t)byte;
-                byte = 0;
-                mul = 1;
-            }
-        }
-    }
-    if (mul != 1) dst[nb] = (uint8_t)byte;
-}
-
-template <int DT>
-__device__ __forceinline__ void quantize_binary(const char* wrow, const uint8_t* __restrict__ mrow, int32_t G,
-                                                uint8_t* dst, float* scale_out) {
-    *scale_out = group_abs_mean<DT>(wrow, mrow, G);
-    for (int32_t c = 0; c < G; c += 8) {
-        float w[8];
-        read8<DT>(wrow, c, w);
-        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
-        uint32_t byte = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) byte |= (w[j] >= 0.0f ? 1u : 0u) << j;
-        dst[c >> 3] = (uint8_t)(byte & ~m);
-    }
-}
 
 template <int DT>
 __global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyArgs A) {
@@ -250,26 +100,7 @@ __global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyArgs 
     }
     __syncthreads();
 
-    // Copy the tile's packed rows (bpg bytes each, row_bytes apart in LDS) to the contiguous
-    // range of the code stream, in elements of the widest size that divides bpg.
-    const int32_t e = (bpg & 15) == 0 ? 16 : ((bpg & 3) == 0 ? 4 : ((bpg & 1) == 0 ? 2 : 1));
-    const int32_t total = tc.nrows * (int32_t)bpg;
-    uint8_t* __restrict__ out = A.codes + base + tc.lrow0 * bpg;
-    int32_t byte = lane * e;
-    int32_t row = byte / (int32_t)bpg;
-    int32_t col = byte - row * (int32_t)bpg;
-    for (; byte < total; byte += AP_THREADS * e) {
-        const char* src = tile + row * row_bytes + col;
-        if (e == 16) *reinterpret_cast<uint4*>(out + byte) = *reinterpret_cast<const uint4*>(src);
-        else if (e == 4) *reinterpret_cast<uint32_t*>(out + byte) = *reinterpret_cast<const uint32_t*>(src);
-        else if (e == 2) *reinterpret_cast<uint16_t*>(out + byte) = *reinterpret_cast<const uint16_t*>(src);
-        else out[byte] = *reinterpret_cast<const uint8_t*>(src);
-        col += AP_THREADS * e;
-        while (col >= (int32_t)bpg) {
-            col -= (int32_t)bpg;
-            ++row;
-        }
-    }
+    copy_out_rows(tile, row_bytes, (int32_t)bpg, tc.nrows, A.codes + base + tc.lrow0 * bpg, lane, AP_THREADS);
     // zero the padding that rounds the unit's payload up to 16 bytes
     if (padded != payload && tc.t == A.g.tiles_per_unit - 1 && lane < padded - payload)
         A.codes[base + payload + lane] = 0;

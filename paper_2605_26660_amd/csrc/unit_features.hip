@@ -187,12 +187,8 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatAr
         for (int j = 0; j < 4; ++j) {
             const uint32_t dlo = (x[j] >> 4) & 0x7ffu, dhi = (x[j] >> 20) & 0x7ffu;
             if (MODE == 0) {
-#ifndef FEAT_EXP_NOATOM
                 atomicAdd(&myhist[dlo], 1u);
                 atomicAdd(&myhist[dhi], 1u);
-#else
-                cnt += dlo ^ dhi;
-#endif
                 const float wlo = __uint_as_float(x[j] << 16), whi = __uint_as_float(x[j] & 0xffff0000u);
                 sw += wlo;
                 sw += whi;

@@ -305,3 +305,42 @@ def test_full_size_7b_matrices_sampled(windq, name, rows, cols):
     cb, nw = windq.windq_effective_bits(action, torch.full((U,), rows * G, dtype=torch.int64))
     assert nw == rows * cols and cb == sum(O.ACTION_CENTIBITS[int(a)] for a in action) * rows * G
     assert total == sum(O.bytes_per_group(int(a), G) for a in action) * rows
+
+
+# ------------------------------------------------- matrices with a leading dimension > cols
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_every_call_on_a_strided_view(windq, dtype):
+    """W is a column window of a wider matrix (ld = cols + 64): every kernel must walk rows by ld."""
+    R, C, G = 192, 256, 128
+    big = synth.weights_llm(R, C + 64, seed=41, device=DEV, dtype=dtype)
+    W = big[:, 32:32 + C]
+    assert W.stride(0) == C + 64 and not W.is_contiguous()
+    Wc = W.contiguous()
+    X = synth.activations_llm(64, C, seed=42, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    cg = grid(20)
+    assert torch.equal(windq.windq_unit_features(W, s, G, 64), windq.windq_unit_features(Wc, s, G, 64))
+    a = windq.windq_fit_score_all_bits(W, s, G, 64, cg)
+    b = windq.windq_fit_score_all_bits(Wc, s, G, 64, cg)
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+    U, R_u = windq.n_units(R, C, G, 64)
+    action = (torch.arange(U) % 7).to(torch.uint8)
+    off = windq.windq_plan_layout(action, R_u, G)
+    pa = windq.windq_apply_plan(W, G, 64, action.to(DEV), a[1], cg, off.to(DEV))
+    pb = windq.windq_apply_plan(Wc, G, 64, action.to(DEV), a[1], cg, off.to(DEV))
+    n = int(off[-1])
+    assert torch.equal(pa[0][:n], pb[0][:n]) and torch.equal(pa[1], pb[1]) and torch.equal(pa[2], pb[2])
+    mask = windq.windq_salient_select(W, s, G, 64, 30000)
+    assert torch.equal(mask, windq.windq_salient_select(Wc, s, G, 64, 30000))
+    ea = windq.windq_salient_encode(W, s, G, 64, mask, 30000)
+    eb = windq.windq_salient_encode(Wc, s, G, 64, mask, 30000)
+    assert all(torch.equal(x, y) for x, y in zip(ea, eb))
+    assert torch.equal(windq.windq_unit_saliency(W, s, G, 64), windq.windq_unit_saliency(Wc, s, G, 64))
+    ra = windq.windq_refine_plan(W, s, G, 64, action.to(DEV), a[1], cg, off.to(DEV), 2, mask=mask)
+    rb = windq.windq_refine_plan(Wc, s, G, 64, action.to(DEV), a[1], cg, off.to(DEV), 2, mask=mask)
+    assert torch.equal(ra[0][:n], rb[0][:n]) and all(torch.equal(x, y) for x, y in zip(ra[1:], rb[1:]))
+    da = windq.windq_dequant_plan(W, s, G, 64, action.to(DEV), off.to(DEV), ra[0], ra[1], ra[2], mask=mask)
+    db = windq.windq_dequant_plan(Wc, s, G, 64, action.to(DEV), off.to(DEV), rb[0], rb[1], rb[2], mask=mask)
+    torch.cuda.synchronize()
+    assert torch.equal(da[0], db[0]) and torch.equal(da[1], db[1])
+    check_fit_score(windq, W, s, G, 64, 20)

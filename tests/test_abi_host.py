@@ -219,3 +219,53 @@ def test_fallback_promote_matches_hand_example_and_oracle(windq):
         assert np.array_equal(a.numpy(), want) and n_got == n_want
     with pytest.raises(windq.WindqError):
         windq.windq_fallback_promote(torch.tensor([7], dtype=torch.uint8), err[:1], ref[:1], 0.1)
+
+
+def test_argument_validation_of_the_protection_refinement_and_dequant_calls(windq):
+    """Same rule for the later entry points: every error is returned before any launch."""
+    lib = windq.lib()
+    P, br = 4096, ctypes.byref
+    grid = torch.linspace(0.5, 1.0, 20, dtype=torch.float32)
+    gp = grid.data_ptr()
+    m = _mat(windq)
+    big = 1 << 30
+    E, S, WS = windq.WINDQ_EINVAL, windq.WINDQ_ESHAPE, windq.WINDQ_EWORKSPACE
+    assert windq.windq_n_protected(524288, 30000) == 15728 and windq.windq_n_protected(100, 1000001) == -1
+    assert windq.windq_n_protected(-1, 10) == -1
+
+    sel = lambda mat=m, s=P, G=64, ppm=30000, mask=P, ws=P, wsb=big: lib.windq_salient_select(br(mat), s, G, 0, ppm, mask, ws, wsb, None)
+    assert sel(s=None) == E and sel(mask=None) == E and sel(ppm=1000001) == E
+    assert sel(G=12) == S and sel(ws=None) == WS and sel(wsb=64) == WS
+    assert sel(mat=_mat(windq, data=None)) == E
+
+    enc = lambda codes=P, scale=P, err=P, mask=P, wsb=big: lib.windq_salient_encode(br(m), P, 64, 0, mask, 30000, codes, scale, err, P, wsb, None)
+    assert enc(codes=None) == E and enc(scale=None) == E and enc(err=None) == E and enc(mask=None) == E and enc(wsb=8) == WS
+
+    fitp = lambda mask=P, K=20: lib.windq_fit_score_all_bits_prot(br(m), P, 64, 0, mask, gp, K, P, P, None, P, big, None)
+    assert fitp(mask=None) == E and fitp(K=0) == E
+
+    appp = lambda mask=P, action=P, codes=P: lib.windq_apply_plan_prot(br(m), 64, 0, mask, action, None, None, 0, P, codes, 1 << 20, P, P, P, big, None)
+    assert appp(mask=None) == E and appp(action=None) == E and appp(codes=4100) == E
+
+    sal = lambda out=P, wsb=big: lib.windq_unit_saliency(br(m), P, 64, 0, out, P, wsb, None)
+    assert sal(out=None) == E and sal(wsb=8) == WS
+
+    deq = lambda err=P, what=None, scale=P, codes=P: lib.windq_dequant_plan(br(m), P, 64, 0, None, P, P, codes, 1 << 20, scale, P, err, what, P, big, None)
+    assert deq(err=None, what=None) == E and deq(scale=None) == E and deq(codes=None) == E
+    assert deq(err=None, what=4098) == E                                 # misaligned reconstruction buffer
+
+    ref = lambda n_iter=3, err=P, K=20, g=gp, ci=P: lib.windq_refine_plan(br(m), P, 64, 0, None, P, ci, g, K, n_iter, P, P, 1 << 20, P, P, err, P, big, None)
+    assert ref(n_iter=-1) == E and ref(n_iter=65) == E and ref(err=None) == E and ref(K=65) == E
+    bad = torch.tensor([0.9, 0.8], dtype=torch.float32)
+    assert ref(g=bad.data_ptr(), K=2) == E
+
+
+def test_workspace_sizes_of_the_later_calls(windq):
+    B = windq.WINDQ_BF16
+    tiles = 32 * 64
+    assert windq.workspace_bytes(windq.CALL_UNIT_SALIENCY, B, 4096, 4096, 128, 0, 1) == tiles * 8
+    assert windq.workspace_bytes(windq.CALL_DEQUANT, B, 4096, 4096, 128, 0, 1) == tiles * 8
+    assert windq.workspace_bytes(windq.CALL_REFINE, B, 4096, 4096, 128, 0, 1) == tiles * 8
+    sal = windq.workspace_bytes(windq.CALL_SALIENT, B, 4096, 4096, 128, 0, 1)
+    assert sal >= 3 * 32 * 2048 * 4 + 32 * 4096 * 4 and sal % 256 == 0
+    assert windq.workspace_bytes(windq.CALL_SALIENT, B, 4096, 4100, 128, 0, 1) == 0

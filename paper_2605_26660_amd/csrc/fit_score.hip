@@ -78,7 +78,8 @@ struct FitScoreArgs {
 __host__ __device__ inline int32_t mask_row_stride(int32_t chunk_w) { return (((chunk_w >> 3) + 3) & ~3) + 4; }
 inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
-           (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (masked ? (size_t)TILE_ROWS * mask_row_stride(chunk_w) : 0);
+           (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
+           (masked ? (size_t)TILE_ROWS * mask_row_stride(chunk_w) : 0);
 }
 
 // The 8-bit residual is ~1/500 of the range, so it is taken relative to an ANCHOR c: a grid
@@ -187,7 +188,8 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     char* __restrict__ tile = smem;
     float* __restrict__ scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
     const int32_t mstride = mask_row_stride(G);
-    uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(scol + G + FS_WAVES * 16 * FS_NRED);
+    float2* __restrict__ gstat = reinterpret_cast<float2*>(scol + G + FS_WAVES * 16 * FS_NRED);   // [FS_WAVES][TILE_ROWS] (min, max)
+    uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(gstat + FS_WAVES * TILE_ROWS);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
 
     load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
@@ -200,6 +202,31 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
         }
     }
     __syncthreads();
+
+    // Group minimum and maximum (of the kept weights), once per tile: each wavefront scans a
+    // quarter of the columns of all 64 rows and the quarters are combined through LDS.  (Chunk
+    // widths that do not split into four runs of 8 columns are scanned whole by every wavefront.)
+    const bool split_stats = (G & 31) == 0;
+    if (split_stats) {
+        const int lane_s = fresh_lane();
+        const char* __restrict__ wr = tile + lane_s * row_bytes;
+        const uint8_t* __restrict__ mr = mtile + lane_s * mstride;
+        float mn = INFINITY, mx = -INFINITY;
+        const int32_t c0 = wave * (G >> 2), c1 = c0 + (G >> 2);
+        for (int32_t c = c0; c < c1; c += 8) {
+            float w[8];
+            read8<DT>(wr, c, w);
+            const uint32_t m = MASKED ? (uint32_t)mr[c >> 3] : 0u;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool kept = !MASKED || ((m >> j) & 1u) == 0u;
+                mn = fminf(mn, kept ? w[j] : INFINITY);
+                mx = fmaxf(mx, kept ? w[j] : -INFINITY);
+            }
+        }
+        gstat[wave * TILE_ROWS + lane_s] = make_float2(mn, mx);
+        __syncthreads();
+    }
 
     const int32_t K = A.K;
     double* __restrict__ out = A.partial + ((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) *
@@ -223,7 +250,17 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
         float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
         if (item < A.n_kpass) {
             float mn, mx;
-            if (!MASKED) {
+            if (split_stats) {
+                mn = INFINITY;
+                mx = -INFINITY;
+#pragma unroll
+                for (int q = 0; q < FS_WAVES; ++q) {
+                    const float2 st = gstat[q * TILE_ROWS + lane_w];
+                    mn = fminf(mn, st.x);
+                    mx = fmaxf(mx, st.y);
+                }
+                if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
+            } else if (!MASKED) {
                 float w[8];
                 read8<DT>(wrow, 0, w);
                 mn = mx = w[0];

@@ -396,16 +396,32 @@ __device__ __forceinline__ void split_ternary(const ApplyArgs& A, const TileCoor
     }
     __syncthreads();
     // five trits -> one byte; the wave's 16 rows x NB bytes are consecutive in the code stream
+    // and start on a multiple of 16 * NB bytes, so they leave as whole dwords (16 * NB is a
+    // multiple of 4); in a ragged last tile the bytes of the rows past the end are not written.
     const int wrow0 = wave * APS_WAVE_ROWS;
-    for (int b = lane; b < APS_WAVE_ROWS * NB; b += 64) {
-        const int r = b / NB, j = b - r * NB;
-        const uint8_t* t5 = wt + r * G + 5 * j;
-        uint32_t v = t5[0];
-        if (5 * j + 1 < G) v += 3u * t5[1];
-        if (5 * j + 2 < G) v += 9u * t5[2];
-        if (5 * j + 3 < G) v += 27u * t5[3];
-        if (5 * j + 4 < G) v += 81u * t5[4];
-        if (wrow0 + r < tc.nrows) out[(int64_t)wrow0 * NB + b] = (uint8_t)v;
+    const int n_valid = tc.nrows - wrow0 < 0 ? 0 : (tc.nrows - wrow0 < APS_WAVE_ROWS ? tc.nrows - wrow0 : APS_WAVE_ROWS);
+    const int valid_bytes = n_valid * NB;
+    uint8_t* __restrict__ wout = out + (int64_t)wrow0 * NB;
+    for (int d = lane; d < APS_WAVE_ROWS * NB / 4; d += 64) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int b = 4 * d + k;
+            const int r = b / NB, j = b - r * NB;
+            const uint8_t* t5 = wt + r * G + 5 * j;
+            uint32_t v = t5[0];
+            if (5 * j + 1 < G) v += 3u * t5[1];
+            if (5 * j + 2 < G) v += 9u * t5[2];
+            if (5 * j + 3 < G) v += 27u * t5[3];
+            if (5 * j + 4 < G) v += 81u * t5[4];
+            word |= v << (8 * k);
+        }
+        if (4 * d + 4 <= valid_bytes) {
+            *reinterpret_cast<uint32_t*>(wout + 4 * d) = word;
+        } else {
+            for (int k = 0; k < 4; ++k)
+                if (4 * d + k < valid_bytes) wout[4 * d + k] = (uint8_t)(word >> (8 * k));
+        }
     }
 }
 
@@ -452,7 +468,7 @@ __device__ __forceinline__ TileCoord tile_coord32(const Geometry& g, uint32_t ti
 }
 
 template <int LPR, bool MASKED>
-__global__ __launch_bounds__(APS_THREADS, 8) void apply_plan_split_kernel(const ApplyArgs A) {
+__global__ __launch_bounds__(APS_THREADS, MASKED ? 6 : 7) void apply_plan_split_kernel(const ApplyArgs A) {
     constexpr int G = 8 * LPR, NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
     __shared__ __attribute__((aligned(16))) uint8_t trits[TILE_ROWS * G];
     const TileCoord tc = tile_coord32(A.g, blockIdx.x);

@@ -571,8 +571,8 @@ static int apply_plan_impl(const windq_mat* W, int32_t chunk_w, int64_t unit_row
         launch_split(&apply_plan_split_kernel<16, false>, &apply_plan_split_kernel<16, true>);
     } else if (fast && chunk_w == 64) {
         launch_split(&apply_plan_split_kernel<8, false>, &apply_plan_split_kernel<8, true>);
-    } else if (fast && chunk_w == 32) {
-        launch_split(&apply_plan_split_kernel<4, false>, &apply_plan_split_kernel<4, true>);
+    } else if (fast && chunk_w == 32 && !masked) {      // (masked at this width: the general kernel below)
+        hipLaunchKernelGGL((apply_plan_split_kernel<4, false>), grid, dim3(APS_THREADS), 0, hs, A);
     } else if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&apply_plan_kernel<WINDQ_BF16>), lds);
         if (st != WINDQ_OK) return st;

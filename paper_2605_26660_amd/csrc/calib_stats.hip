@@ -7,6 +7,11 @@
 // token with 128-bit loads (64 lanes = 1 KB contiguous for bf16), the four wavefronts
 // take every fourth token.  fp64 sums, combined in a fixed order: wavefronts through
 // LDS, slabs by the finalize kernel.
+//
+// Few tokens (the calibration sets of the paper's configs: 512 per input) are a few MB, and
+// two dependent launches cost more than the data: then ONE kernel does it all.  A workgroup
+// owns a strip of 64 channels (8 lanes x 8) over all tokens, its 32 lane groups take every
+// 32nd token, and the 32 partial sums are added in order through LDS.
 #include "windq_common.hpp"
 #include "windq_ws.hpp"
 
@@ -77,6 +82,69 @@ __global__ __launch_bounds__(CALIB_THREADS) void calib_partial_kernel(const void
     }
 }
 
+constexpr int CALIB_DIRECT_LANES = 8;                                   // lanes across a strip
+constexpr int CALIB_DIRECT_STRIP = CALIB_DIRECT_LANES * CALIB_COLS_PER_LANE;
+constexpr int CALIB_DIRECT_GROUPS = CALIB_THREADS / CALIB_DIRECT_LANES;   // token groups
+constexpr int64_t CALIB_DIRECT_MAX_ROWS = 4096;
+
+template <int DT>
+__global__ __launch_bounds__(CALIB_THREADS) void calib_direct_kernel(const void* __restrict__ X, int64_t rows,
+                                                                     int64_t cols, int64_t ld,
+                                                                     float* __restrict__ s_absmean,
+                                                                     float* __restrict__ s_rms) {
+    __shared__ double red[CALIB_DIRECT_GROUPS][2][CALIB_DIRECT_STRIP + 1];
+    const int cl = threadIdx.x % CALIB_DIRECT_LANES;
+    const int tg = threadIdx.x / CALIB_DIRECT_LANES;
+    const int64_t c0 = (int64_t)blockIdx.x * CALIB_DIRECT_STRIP + (int64_t)cl * CALIB_COLS_PER_LANE;
+    double sa[CALIB_COLS_PER_LANE], sq[CALIB_COLS_PER_LANE];
+#pragma unroll
+    for (int j = 0; j < CALIB_COLS_PER_LANE; ++j) sa[j] = sq[j] = 0.0;
+    if (c0 < cols) {
+#pragma unroll 4
+        for (int64_t r = tg; r < rows; r += CALIB_DIRECT_GROUPS) {
+            float v[CALIB_COLS_PER_LANE];
+            const int64_t off = r * ld + c0;
+            if (DT == WINDQ_BF16) {
+                const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(X) + off);
+                v[0] = bf16_bits_to_f32(raw.x & 0xffffu); v[1] = __uint_as_float(raw.x & 0xffff0000u);
+                v[2] = bf16_bits_to_f32(raw.y & 0xffffu); v[3] = __uint_as_float(raw.y & 0xffff0000u);
+                v[4] = bf16_bits_to_f32(raw.z & 0xffffu); v[5] = __uint_as_float(raw.z & 0xffff0000u);
+                v[6] = bf16_bits_to_f32(raw.w & 0xffffu); v[7] = __uint_as_float(raw.w & 0xffff0000u);
+            } else {
+                const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(X) + off);
+                const float4 a = src[0], b = src[1];
+                v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+                v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+            }
+#pragma unroll
+            for (int j = 0; j < CALIB_COLS_PER_LANE; ++j) {
+                const double x = (double)v[j];
+                sa[j] += fabs(x);
+                sq[j] = fma(x, x, sq[j]);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < CALIB_COLS_PER_LANE; ++j) {
+        red[tg][0][cl * CALIB_COLS_PER_LANE + j] = sa[j];
+        red[tg][1][cl * CALIB_COLS_PER_LANE + j] = sq[j];
+    }
+    __syncthreads();
+    if (threadIdx.x < CALIB_DIRECT_STRIP) {
+        const int64_t c = (int64_t)blockIdx.x * CALIB_DIRECT_STRIP + threadIdx.x;
+        if (c < cols) {
+            double a = 0.0, q = 0.0;
+#pragma unroll
+            for (int g = 0; g < CALIB_DIRECT_GROUPS; ++g) {
+                a += red[g][0][threadIdx.x];
+                q += red[g][1][threadIdx.x];
+            }
+            s_absmean[c] = (float)(a / (double)rows);
+            if (s_rms != nullptr) s_rms[c] = (float)sqrt(q / (double)rows);
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void calib_finalize_kernel(const double* __restrict__ partial, int64_t n_slabs,
                                                               int64_t rows, int64_t cols,
                                                               float* __restrict__ s_absmean,
@@ -105,6 +173,16 @@ extern "C" int windq_calib_stats(const windq_mat* X, float* s_absmean, float* s_
     const size_t need = calib_ws_bytes(X->rows, X->cols);
     if (ws == nullptr || ws_bytes < need || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
     hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (X->rows <= CALIB_DIRECT_MAX_ROWS) {
+        const dim3 dgrid((unsigned)((X->cols + CALIB_DIRECT_STRIP - 1) / CALIB_DIRECT_STRIP));
+        if (X->dtype == WINDQ_BF16)
+            hipLaunchKernelGGL(calib_direct_kernel<WINDQ_BF16>, dgrid, dim3(CALIB_THREADS), 0, hs, X->data, X->rows,
+                               X->cols, X->ld, s_absmean, s_rms);
+        else
+            hipLaunchKernelGGL(calib_direct_kernel<WINDQ_F32>, dgrid, dim3(CALIB_THREADS), 0, hs, X->data, X->rows,
+                               X->cols, X->ld, s_absmean, s_rms);
+        return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+    }
     const int64_t n_slabs = calib_slabs(X->rows);
     if (n_slabs > 65535) return WINDQ_ESHAPE;
     double* partial = static_cast<double*>(ws);

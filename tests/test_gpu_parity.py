@@ -71,7 +71,9 @@ def check_apply(windq, W, G, unit_rows, action, clip_idx, K, units=None):
 
 # ------------------------------------------------------------------- calib stats
 @pytest.mark.parametrize("T,C,dtype", [(256, 512, torch.float32), (512, 4096, torch.bfloat16), (100, 1032, torch.bfloat16),
-                                       (1, 8, torch.float32), (33, 520, torch.float32)])
+                                       (1, 8, torch.float32), (33, 520, torch.float32),
+                                       (4096, 136, torch.bfloat16),                       # the longest single-kernel case
+                                       (4200, 1032, torch.bfloat16), (5000, 8, torch.float32)])   # slabs + finalize
 def test_calib_stats(windq, T, C, dtype):
     X = synth.activations_small(T, C, seed=0, device=DEV, dtype=dtype) if dtype == torch.float32 else \
         synth.activations_llm(T, C, seed=2, device=DEV, dtype=dtype)

@@ -32,10 +32,19 @@ n_chunks + j.  A group is one row of a unit (G consecutive weights of one output
 row); group index g = u * R_u + local_row.  Inputs are float32 ndarrays holding the
 exact input values (bf16 inputs are passed widened, which is exact).
 
+Beyond the five hot-path calls the module holds, to the same rules: salient-weight
+protection (Sec. 3.5 and App. "Salient Weight Protection": exact top-n_p selection,
+protection mask, masked fits and plans, INT8 storage), the heuristic sensitivity
+allocator and the fallback to higher precision (App. "Comparison with Heuristic
+Sensitivity Allocator", Sec. 3.5), iterative scale refinement (App. "Per-unit Scale
+Optimization") and the dequantisation of a packed plan.
+
 Parity pins (tests/test_oracle_*.py): closed forms, brute force on tiny groups,
-hand-computed examples and golden bytes.  Not pinned by anything: whether these
-deterministic fits reproduce the paper's learned LSQ/SEQ scales or its perplexities
-("parity unpinned": no weights, code or corpus exist to compare against).
+hand-computed examples, a library least-squares solve, and golden bytes.  Not pinned
+by anything: whether these deterministic fits reproduce the paper's learned LSQ/SEQ
+scales or its perplexities, and whether the allocator's two knobs match the paper's
+unstated thresholds ("parity unpinned": no weights, code or corpus exist to compare
+against).
 """
 from __future__ import annotations
 

@@ -346,3 +346,17 @@ def test_every_call_on_a_strided_view(windq, dtype):
     torch.cuda.synchronize()
     assert torch.equal(da[0], db[0]) and torch.equal(da[1], db[1])
     check_fit_score(windq, W, s, G, 64, 20)
+
+
+# ------------------------------------------------ narrowest and widest chunk, every call
+@pytest.mark.parametrize("G,dtype", [(8, torch.bfloat16), (8, torch.float32), (512, torch.bfloat16), (512, torch.float32)])
+def test_extreme_chunk_widths(windq, G, dtype):
+    R, C = 72, 2 * G
+    W = synth.weights_llm(R, C, seed=51, device=DEV, dtype=dtype)
+    s = torch.rand(C, device=DEV) + 0.1
+    check_features(windq, W, s, G, 0)
+    check_features(windq, W, s, G, 24)
+    _, clip_idx, _ = check_fit_score(windq, W, s, G, 0, 20)
+    for a in range(7):
+        check_apply(windq, W, G, 0, torch.full((2,), a, dtype=torch.uint8), clip_idx, 20)
+    check_apply(windq, W, G, 24, (torch.arange(6) % 7 + 1).clamp(max=6).to(torch.uint8), None, 1)

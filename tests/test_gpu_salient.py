@@ -270,3 +270,26 @@ def test_heuristic_plan_with_protection_and_fallback_end_to_end(windq):
     codes, scale, offset = windq.windq_apply_plan(W, G, 0, a2.to(DEV), clip_idx, cg, off.to(DEV), mask=mask)
     torch.cuda.synchronize()
     assert codes.numel() >= int(off[-1]) and torch.isfinite(scale).all()
+
+
+@pytest.mark.parametrize("G", [8, 512])
+def test_extreme_chunk_widths_under_protection(windq, G):
+    R, C = 72, 2 * G
+    W = synth.weights_llm(R, C, seed=121, device=DEV)
+    s = torch.rand(C, device=DEV) + 0.1
+    mask, keep = check_select(windq, W, s, G, 0, 60000)
+    check_encode(windq, W, s, G, 0, 60000, mask, keep)
+    check_masked_fit_and_apply(windq, W, s, G, 24, 60000, 6)
+    # refinement and the way back, on the same shapes
+    cg = synth.clip_grid(6)
+    err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, G, 0, cg, mask=mask)
+    action = torch.tensor([3, 5], dtype=torch.uint8)
+    off = windq.windq_plan_layout(action, R, G)
+    codes, scale, offset, e = windq.windq_refine_plan(W, s, G, 0, action.to(DEV), clip_idx, cg, off.to(DEV), 2, mask=mask)
+    d_err, _ = windq.windq_dequant_plan(W, s, G, 0, action.to(DEV), off.to(DEV), codes, scale, offset, mask=mask)
+    torch.cuda.synchronize()
+    oc, osc, oof, oe = O.refine_plan(to_np(W), s.cpu().numpy(), G, 0, action.numpy(), clip_idx.cpu().numpy(), cg.numpy(),
+                                     off.numpy(), 2, keep=keep)
+    assert np.array_equal(codes.cpu().numpy()[:int(off[-1])], oc)
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), osc.view(np.uint32))
+    assert np.all(np.abs(e.cpu().numpy() - oe) <= REL * oe) and np.all(np.abs(d_err.cpu().numpy() - oe) <= 2 * REL * oe)

@@ -4,7 +4,7 @@
 // Optimization": per-group scales, group size = chunk size).
 //
 // Work per weight: 4 bit-widths x K clip ratios + ternary + binary = 4K+2 candidate
-// quantizers.  At K = 20 that is ~480 vector instructions per 2-byte weight: the kernel
+// quantizers.  At K = 20 that is ~400 vector instructions per 2-byte weight: the kernel
 // is bound by the vector ALU, not by HBM, by a factor of ~30.  So the design minimises
 // issue cycles per candidate, using what measurement shows about gfx950's vector ALU:
 // v_fma/mul/add/sub_f32 whose operands are all plain VGPRs issue about 1.7x faster than
@@ -14,26 +14,29 @@
 //   * lane-per-group (see windq_common.hpp): quantizer parameters are lane-private and
 //     live in VGPRs; the wave-uniform s_c is staged in LDS and read back into VGPRs,
 //     constants are pinned in VGPRs;
-//   * the hot loop is made of fast fp32 FMA/ADD/MUL only, 23 per (weight, clip ratio):
-//       x  = clamp01((w - c)/range + h)         position in the clipped range; one FMA with
+//   * the hot loop is made of fast fp32 FMA/ADD/MUL only:
+//       x  = clamp01(w/range + h)               position in the clipped range; one FMA with
 //                                               the free [0,1] output clamp
+//       u' = s_c*w - s_c*lo                     one FMA per clip ratio
 //       per bit-width b:  tM = x * (2^b-1) + 2^23      rounds to the nearest code (RNE)
 //                         q' = tM * s_c - 2^23 s_c     = s_c * code, one rounding
 //                         r' = q' * (-step_b) + u'     = s_c * (w - lo - code*step_b)
 //                         acc_b += r' * r'
 //     4 instructions per candidate and no separate clamp of the code (x is already in
-//     [0,1]); u' = s_c*w - s_c*lo costs one more FMA per clip ratio;
-//   * at 8 bits the residual is ~1/500 of (w - lo), so the fp32 rounding of (w - lo)
-//     would show at the 1e-5 level in units whose error is carried by few weights.
-//     The 8-bit candidate therefore takes an exact route.  Distances are measured from an
-//     anchor c = lo + q0*step, the grid point nearest zero (q0 = 0 if zero is outside the
-//     range), so that |c| <= step/2 <= |w| for all but negligible weights and the cheap
-//     error-free sum applies: u0 = fl(w - c), e = (-c) - (u0 - w) is its exact rounding
-//     error; residual = fma(code - q0, -step, u0) (exact) + e.  3 more fast instructions
-//     per (weight, clip ratio) than an uncompensated residual.  (Rows whose weights are
-//     all negative fall back to c = lo, where e is exact only for |w| <= |lo|; the
-//     remainder is bounded by the plain fp32 rounding of (w - lo), 3e-5/sqrt(n) of the
-//     unit error.)
+//     [0,1]): 18 per (weight, clip ratio) when all four bit-widths go this short way;
+//   * at 8 bits the residual is ~1/500 of (w - lo), so the fp32 roundings of s_c*w,
+//     s_c*(w - lo) and s_c*code show in it: ~1e-4 of its size per weight, random in sign.
+//     Summed over a unit that is harmless for the columns of ordinary weight s_c^2, but not
+//     for a column that carries much of the unit's error by itself.  The kernel therefore
+//     lists the chunk's heavy columns (s_c^2 above tau times the chunk's mean, tau chosen
+//     from the unit's size so that the noise stays at 1e-6 of the unit's error) and scores
+//     them on an exact 8-bit route instead, 20 instructions: the residual is formed
+//     unscaled, relative to an anchor c = lo + q0*step, the grid point nearest zero, as
+//     (w - (code - q0)*step) - c, where the FMA rounds once at the small magnitude |c + r|,
+//     and only then multiplied by s_c.  Small units, and chunks with many heavy columns,
+//     take the exact route for every column.  (Groups whose weights all have one sign have
+//     no grid point near zero: their wavefront uses c = lo and an error-free two-sum of
+//     (w - c), 23 instructions.)
 //   * lanes accumulate in fp32 over the chunk's columns only (<= 512 terms); rows are
 //     combined in fp64 in a fixed order (LDS transpose), tiles by the finalize kernel.
 // Rounding decisions here are taken on x*(2^b-1); windq_apply_plan takes them on
@@ -56,6 +59,7 @@ constexpr int FS_WAVES = FS_THREADS / 64;
 constexpr int FS_KB = 5;                    // clip ratios evaluated together by one wavefront pass
 constexpr int FS_NRED = FS_KB * 4;          // per-lane sums a pass produces
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
+constexpr int FS_HMAX = WINDQ_MAX_CHUNK / 8;   // most columns a tile may send down the exact 8-bit route on their own
 
 struct FitScoreArgs {
     const void* W;
@@ -66,6 +70,7 @@ struct FitScoreArgs {
     Geometry g;
     int32_t K;
     int32_t n_kpass;   // ceil(K / FS_KB)
+    float tau;         // columns with s_c^2 > tau * mean(s^2) of the chunk take the exact 8-bit route; 0: all do
     ClipGrid grid;
 };
 
@@ -79,6 +84,7 @@ __host__ __device__ inline int32_t mask_row_stride(int32_t chunk_w) { return (((
 inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
            (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
+           (size_t)chunk_w * sizeof(float) + (size_t)(FS_HMAX + 1) * sizeof(int32_t) +
            (masked ? (size_t)TILE_ROWS * mask_row_stride(chunk_w) : 0);
 }
 
@@ -132,6 +138,36 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
             acc[i][b] = fmaf(r1, r1, acc[i][b]);
         }
     }
+}
+
+// The short route: all four bit-widths like the low ones, 18 instructions per (weight, clip
+// ratio).  Its 8-bit residual carries the fp32 roundings of s_c*w, s_c*(w - lo) and s_c*code:
+// ~1e-4 of its own size per weight, of random sign.  Used for the columns whose share of the
+// unit's error is bounded (see the column selection in the kernel).
+__device__ __forceinline__ void score_weight_short(const float w, const float sc, const KParams (&P)[FS_KB],
+                                                   const float (&Q)[4], const float M, const float nM,
+                                                   float (&acc)[FS_KB][4]) {
+    const float w1 = w * sc;
+    const float ms = sc * nM;
+#pragma unroll
+    for (int i = 0; i < FS_KB; ++i) {
+        const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
+        const float x = fma_clamp01(w, P[i].rinv, P[i].h);        // position in the clipped range, in [0, 1]
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const float tM = fmaf(x, Q[b], M);
+            const float q1 = fmaf(tM, sc, ms);
+            const float r1 = fmaf(q1, P[i].nd[b], u1);
+            acc[i][b] = fmaf(r1, r1, acc[i][b]);
+        }
+    }
+}
+
+// One weight of a lane's row at column c.
+template <int DT>
+__device__ __forceinline__ float read1(const char* __restrict__ wrow, int32_t c) {
+    if (DT == WINDQ_BF16) return bf16_bits_to_f32(*reinterpret_cast<const uint16_t*>(wrow + c * 2));
+    return *reinterpret_cast<const float*>(wrow + c * 4);
 }
 
 // The lane's index in its wavefront, read anew from the hardware at every call (never kept
@@ -189,7 +225,9 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     float* __restrict__ scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
     const int32_t mstride = mask_row_stride(G);
     float2* __restrict__ gstat = reinterpret_cast<float2*>(scol + G + FS_WAVES * 16 * FS_NRED);   // [FS_WAVES][TILE_ROWS] (min, max)
-    uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(gstat + FS_WAVES * TILE_ROWS);
+    float* __restrict__ sshort = reinterpret_cast<float*>(gstat + FS_WAVES * TILE_ROWS);   // s_c, 0 for the listed columns
+    int32_t* __restrict__ hlist = reinterpret_cast<int32_t*>(sshort + G);   // listed columns; [FS_HMAX] = how many, -1: no list
+    uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(hlist + FS_HMAX + 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
 
     load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
@@ -203,6 +241,40 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     }
     __syncthreads();
 
+    // Column selection for the 8-bit candidate.  A column whose s_c^2 exceeds
+    // tau times the chunk's mean carries too much of the unit's error for the short route's
+    // rounding noise: such columns are listed and scored on the exact route, one at a time;
+    // all others (s_c kept in sshort, listed ones zeroed there) go down the short route.  With
+    // the short route's ~1.2e-4/sqrt(rows) relative noise per column, the unit's 8-bit error
+    // moves by at most 1.2e-4 sqrt(tau / (G R_u)) (one sigma): 1e-6 at the tau the host sets.
+    // Every wavefront derives the same list and writes the same values: none waits for another.
+    {
+        const int l = fresh_lane();
+        int32_t nh = -1;
+        if (A.tau > 0.0f) {
+            float ss = 0.0f;
+            for (int32_t c = l; c < G; c += 64) {
+                const float sv = scol[c];
+                ss = fmaf(sv, sv, ss);
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, 64);
+            const float thr = A.tau * ss / (float)G;
+            nh = 0;
+            for (int32_t blk = 0; blk < G; blk += 64) {
+                const int32_t c = blk + l;
+                const float sv = c < G ? scol[c] : 0.0f;
+                const bool hv = sv * sv > thr;
+                const uint64_t bal = __builtin_amdgcn_ballot_w64(hv);
+                if (c < G) sshort[c] = hv ? 0.0f : sv;
+                const int32_t pos = nh + __builtin_popcountll(bal & ((1ull << l) - 1ull));
+                if (hv && pos < FS_HMAX) hlist[pos] = c;
+                nh += __builtin_popcountll(bal);
+            }
+            if (nh * 8 > G) nh = -1;     // so many that one exact sweep over all columns is cheaper
+        }
+        if (l == 0) hlist[FS_HMAX] = nh;
+    }
     // Group minimum and maximum (of the kept weights), once per tile: each wavefront scans a
     // quarter of the columns of all 64 rows and the quarters are combined through LDS.  (Chunk
     // widths that do not split into four runs of 8 columns are scanned whole by every wavefront.)
@@ -340,8 +412,34 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     for (int j = 0; j < 8; ++j) score_weight<AN>(w[j], s8[j], P, Q, M, nM, acc);
                 }
             };
-            if (anchored) sweep(std::true_type{});
-            else sweep(std::false_type{});
+            const int32_t nh = __builtin_amdgcn_readfirstlane(hlist[FS_HMAX]);
+            if (!anchored) {
+                sweep(std::false_type{});
+            } else if (nh < 0) {
+                sweep(std::true_type{});
+            } else {
+                for (int32_t c = 0; c < G; c += 8) {
+                    float w[8];
+                    read8<DT>(wrow, c, w);
+                    const float4 sa = *reinterpret_cast<const float4*>(sshort + c);
+                    const float4 sb = *reinterpret_cast<const float4*>(sshort + c + 4);
+                    float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
+                    if (MASKED) {
+                        const uint32_t m = mrow[c >> 3];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) s8[j] = ((m >> j) & 1u) != 0u ? 0.0f : s8[j];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) score_weight_short(w[j], s8[j], P, Q, M, nM, acc);
+                }
+                for (int32_t hi = 0; hi < nh; ++hi) {
+                    const int32_t c = __builtin_amdgcn_readfirstlane(hlist[hi]);
+                    const float w = read1<DT>(wrow, c);
+                    float sc = scol[c];
+                    if (MASKED) sc = ((mrow[c >> 3] >> (c & 7)) & 1u) != 0u ? 0.0f : sc;
+                    score_weight<true>(w, sc, P, Q, M, nM, acc);
+                }
+            }
             float flat[FS_NRED];
 #pragma unroll
             for (int i = 0; i < FS_KB; ++i)
@@ -492,6 +590,10 @@ static int fit_score_impl(const windq_mat* W, const float* s, int32_t chunk_w, i
     A.partial = static_cast<double*>(ws);
     A.K = K;
     A.n_kpass = (K + FS_KB - 1) / FS_KB;
+    // tau keeps the short route's noise in the unit's 8-bit error at 1e-6 (one sigma):
+    // 1.2e-4 sqrt(tau / (G R_u)) = 1e-6.  Below tau = 1 every column takes the exact route.
+    const float t = 7e-5f * (float)chunk_w * (float)A.g.R_u;
+    A.tau = t < 1.0f ? 0.0f : t;
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid[k < K ? k : K - 1];
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const bool masked = mask != nullptr;

@@ -195,6 +195,50 @@ def test_fit_score_one_signed_groups(windq, dtype, unit_rows):
     check_fit_score(windq, W, s, G, unit_rows, 20)
 
 
+def column_routes(s, G, R_u):
+    """Which way the kernel scores the 8-bit candidate of each chunk, by its documented rule:
+    'exact' (every column on the exact route), else the number of columns listed for it."""
+    tau = np.float32(7e-5) * np.float32(G) * np.float32(R_u)
+    out = []
+    for j in range(len(s) // G):
+        if tau < 1:
+            out.append("exact")
+            continue
+        s2 = s[j * G:(j + 1) * G].astype(np.float64) ** 2
+        nh = int(np.sum(s2 > float(tau) * s2.mean()))
+        out.append("exact" if nh * 8 > G else nh)
+    return out
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("R,unit_rows", [(256, 0), (1024, 0), (1024, 512)])
+def test_fit_score_column_routes(windq, R, unit_rows, dtype):
+    """The 8-bit candidate takes a short route for columns of small weight and the exact one
+    for the few heavy columns (or for all, when many are heavy or the unit is small).  Chunks:
+    uniform s_c; 4 heavy columns; 20 moderately heavy columns; one dominant column; log-normal s_c."""
+    C, G = 640, 128
+    gen = torch.Generator().manual_seed(71)
+    W = synth.weights_llm(R, C, seed=72, device=DEV, dtype=dtype)
+    s = torch.ones(C)
+    s[128 + torch.randperm(128, generator=gen)[:4]] = 12.0
+    s[256 + torch.randperm(128, generator=gen)[:20]] = 3.0
+    s[384 + 77] = 300.0
+    s[512:] = torch.exp(1.5 * torch.randn(128, generator=gen))
+    U, R_u = windq.n_units(R, C, G, unit_rows)
+    routes = column_routes(s.numpy(), G, R_u)
+    assert routes[0] == 0 and routes[3] == 1
+    if R_u == 256:
+        assert routes[1] == 4 and routes[2] == "exact"
+    else:
+        assert routes[1] == 4 and routes[2] == 0
+    assert isinstance(routes[4], int) and routes[4] > 0
+    check_fit_score(windq, W, s.to(DEV), G, unit_rows, 20)
+    # the same tall matrix cut into units too small for the short route
+    assert column_routes(s.numpy(), G, 64) == ["exact"] * 5
+    if R == 256:
+        check_fit_score(windq, W, s.to(DEV), G, 64, 20)
+
+
 def test_fit_score_is_bit_reproducible(windq):
     W = synth.weights_llm(512, 1024, seed=24, device=DEV)
     s = torch.rand(1024, device=DEV) + 0.1

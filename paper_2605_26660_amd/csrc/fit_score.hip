@@ -66,10 +66,11 @@ struct FitScoreArgs {
     const float* s;
     const uint8_t* mask;   // protection mask [rows][cols/8] (masked kernels only)
     int64_t mask_ld;
-    double* partial;   // [n_tiles][4K+3]
+    double* partial;   // [n_tiles][4K+12]
     Geometry g;
     int32_t K;
     int32_t n_kpass;   // ceil(K / FS_KB)
+    double inv_G;      // 1 / chunk_w
     float tau;         // columns with s_c^2 > tau * mean(s^2) of the chunk take the exact 8-bit route; 0: all do
     ClipGrid grid;
 };
@@ -84,8 +85,9 @@ __host__ __device__ inline int32_t mask_row_stride(int32_t chunk_w) { return (((
 inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
            (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
-           (size_t)chunk_w * sizeof(float) + (size_t)(FS_HMAX + 1) * sizeof(int32_t) +
-           (masked ? (size_t)TILE_ROWS * mask_row_stride(chunk_w) : 0);
+           (size_t)chunk_w * sizeof(float) + (size_t)(FS_HMAX + 1 + 1) * sizeof(int32_t) +
+           (size_t)FS_WAVES * TILE_ROWS * sizeof(double) +
+           (masked ? (size_t)FS_WAVES * TILE_ROWS * sizeof(int32_t) + (size_t)TILE_ROWS * mask_row_stride(chunk_w) : 0);
 }
 
 // The 8-bit residual is ~1/500 of the range, so it is taken relative to an ANCHOR c: a grid
@@ -186,6 +188,19 @@ __device__ __forceinline__ float quad_sum(float x) {
     return x;
 }
 
+// Sum of x over the 64 lanes, the same bits in every lane: quads, then the two quads of a
+// half row, the two halves of a row of 16 (DPP mirrors), then the four rows in order.
+__device__ __forceinline__ float wave_sum_f32(float x) {
+    x = quad_sum(x);
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));   // row_half_mirror
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, false));   // row_mirror
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
+    return ((r0 + r1) + r2) + r3;
+}
+
 // Sum N per-lane fp32 values over the 64 lanes (rows) of a wavefront: quads in fp32 by
 // DPP (two adds), the 16 quad sums in fp64 in row order through the wavefront's private
 // LDS scratch.  Lane j < N returns total j.  Fixed order: bit-reproducible.
@@ -227,7 +242,9 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     float2* __restrict__ gstat = reinterpret_cast<float2*>(scol + G + FS_WAVES * 16 * FS_NRED);   // [FS_WAVES][TILE_ROWS] (min, max)
     float* __restrict__ sshort = reinterpret_cast<float*>(gstat + FS_WAVES * TILE_ROWS);   // s_c, 0 for the listed columns
     int32_t* __restrict__ hlist = reinterpret_cast<int32_t*>(sshort + G);   // listed columns; [FS_HMAX] = how many, -1: no list
-    uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(hlist + FS_HMAX + 1);
+    double* __restrict__ s1tab = reinterpret_cast<double*>(hlist + FS_HMAX + 2);   // [FS_WAVES][TILE_ROWS] sum |w| of a quarter
+    int32_t* __restrict__ nktab = reinterpret_cast<int32_t*>(s1tab + FS_WAVES * TILE_ROWS);   // kept weights of a quarter (masked)
+    uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(nktab + (MASKED ? FS_WAVES * TILE_ROWS : 0));
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
 
     load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
@@ -257,9 +274,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                 const float sv = scol[c];
                 ss = fmaf(sv, sv, ss);
             }
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, 64);
-            const float thr = A.tau * ss / (float)G;
+            const float thr = A.tau * wave_sum_f32(ss) / (float)G;
             nh = 0;
             for (int32_t blk = 0; blk < G; blk += 64) {
                 const int32_t c = blk + l;
@@ -275,28 +290,34 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
         }
         if (l == 0) hlist[FS_HMAX] = nh;
     }
-    // Group minimum and maximum (of the kept weights), once per tile: each wavefront scans a
-    // quarter of the columns of all 64 rows and the quarters are combined through LDS.  (Chunk
-    // widths that do not split into four runs of 8 columns are scanned whole by every wavefront.)
-    const bool split_stats = (G & 31) == 0;
-    if (split_stats) {
+    // Group statistics (of the kept weights), once per tile: each wavefront scans a quarter of
+    // the chunk's 8-column runs for all 64 rows -- minimum, maximum, and the sum of |w| in fp64
+    // in column order -- and the quarters are combined through LDS, in order.
+    const int32_t runs = G >> 3;
+    const int32_t qc0 = ((wave * runs) >> 2) << 3, qc1 = (((wave + 1) * runs) >> 2) << 3;   // this wavefront's columns
+    {
         const int lane_s = fresh_lane();
         const char* __restrict__ wr = tile + lane_s * row_bytes;
         const uint8_t* __restrict__ mr = mtile + lane_s * mstride;
         float mn = INFINITY, mx = -INFINITY;
-        const int32_t c0 = wave * (G >> 2), c1 = c0 + (G >> 2);
-        for (int32_t c = c0; c < c1; c += 8) {
+        double S1 = 0.0;
+        int32_t nk = 0;
+        for (int32_t c = qc0; c < qc1; c += 8) {
             float w[8];
             read8<DT>(wr, c, w);
             const uint32_t m = MASKED ? (uint32_t)mr[c >> 3] : 0u;
+            if (MASKED) nk += 8 - __builtin_popcount(m);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const bool kept = !MASKED || ((m >> j) & 1u) == 0u;
                 mn = fminf(mn, kept ? w[j] : INFINITY);
                 mx = fmaxf(mx, kept ? w[j] : -INFINITY);
+                S1 += kept ? (double)fabsf(w[j]) : 0.0;
             }
         }
         gstat[wave * TILE_ROWS + lane_s] = make_float2(mn, mx);
+        s1tab[wave * TILE_ROWS + lane_s] = S1;
+        if (MASKED) nktab[wave * TILE_ROWS + lane_s] = nk;
         __syncthreads();
     }
 
@@ -304,59 +325,88 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     double* __restrict__ out = A.partial + ((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) *
                                                (size_t)fit_score_ncand(K);
 
-    // Work items of the tile: n_kpass passes over FS_KB clip ratios each, plus one light
-    // pass (ternary, binary, reference energy).  Item i goes to wavefront (i + rot) % 4;
-    // rot spreads the light pass over the four SIMDs from tile to tile.
+    float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
+
+    // Ternary absmean, binary sign*mean|w| and the reference energy: every wavefront scores
+    // its quarter of the columns.  gamma = alpha = fp32(S1 / n), S1 = the quarters' sums of |w|
+    // added in order (exact for bf16 inputs; for fp32 inputs it can differ from the strict
+    // column-order sum in the last bit of the fp64, which the conversion to fp32 hides but for
+    // ~1e-8 of the groups, and there by one ulp of gamma).
+    {
+        const int lane_w = fresh_lane();
+        const char* __restrict__ wrow = tile + lane_w * row_bytes;
+        const uint8_t* __restrict__ mrow = mtile + lane_w * mstride;
+        double S1 = 0.0;
+        int32_t n_kept = MASKED ? 0 : G;
+#pragma unroll
+        for (int q = 0; q < FS_WAVES; ++q) {
+            S1 += s1tab[q * TILE_ROWS + lane_w];
+            if (MASKED) n_kept += nktab[q * TILE_ROWS + lane_w];
+        }
+        // n is the chunk width unless weights are masked out; the product with its reciprocal (from
+        // the host) rounds to the same fp32 as the quotient, but for ~1e-9 of groups when G is not 2^k
+        const float fam = MASKED ? (n_kept > 0 ? (float)(S1 / (double)n_kept) : 0.0f) : (float)(S1 * A.inv_G);
+        const bool ok = fam >= FLT_MIN;
+        // Fast-issue fp32 only, as in the clip passes.  y = clamp01(w/(2 gamma) + 1/2) maps
+        // w/gamma in [-1, 1] onto [0, 1]; rne(2y) = q + 1 in {0, 1, 2} needs no clamp.
+        const float gam = pin_vgpr(ok ? fam : 0.0f);
+        const float ngam = pin_vgpr(ok ? -fam : 0.0f);
+        const float hginv = pin_vgpr(ok ? 0.5f * __builtin_amdgcn_rcpf(fam) : 0.0f);
+        const float nalpha = pin_vgpr(-fam);
+        const float half = pin_vgpr(0.5f), two = pin_vgpr(2.0f);
+        const float M = pin_vgpr(RNE_POS);
+        float acc3[3] = {0.0f, 0.0f, 0.0f};
+        for (int32_t c = qc0; c < qc1; c += 8) {
+            float w[8];
+            read8<DT>(wrow, c, w);
+            const float4 sa = *reinterpret_cast<const float4*>(scol + c);
+            const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
+            float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
+            if (MASKED) {
+                const uint32_t m = mrow[c >> 3];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) s8[j] = ((m >> j) & 1u) != 0u ? 0.0f : s8[j];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float sc = s8[j];
+                const float y = fma_clamp01(w[j], hginv, half);
+                const float qp = fmaf(y, two, M) - M;                    // q + 1
+                const float rt = fmaf(qp, ngam, w[j] + gam) * sc;        // s_c (w - q gamma)
+                acc3[0] = fmaf(rt, rt, acc3[0]);
+                const float aw = __uint_as_float(__float_as_uint(w[j]) & 0x7fffffffu);
+                const float rb = (aw + nalpha) * sc;                     // s_c (|w| - alpha)
+                acc3[1] = fmaf(rb, rb, acc3[1]);
+                const float w1 = w[j] * sc;
+                acc3[2] = fmaf(w1, w1, acc3[2]);
+            }
+        }
+        const int lane_r = fresh_lane();
+        if (lane_r >= tc.nrows) acc3[0] = acc3[1] = acc3[2] = 0.0f;
+        const double tot = rows_sum<3>(acc3, red, lane_r);
+        if (lane_r < 3) out[4 * K + 3 * wave + lane_r] = tot;
+    }
+
+    // The clip grid: n_kpass passes over FS_KB clip ratios each.  Pass i goes to wavefront
+    // (i + rot) % 4; rot spreads an uneven number of passes over the four SIMDs from tile to tile.
     const int rot = blockIdx.x & (FS_WAVES - 1);
-    const int n_items = A.n_kpass + 1;
-    for (int item = (wave - rot) & (FS_WAVES - 1); item < n_items; item += FS_WAVES) {
+    for (int item = (wave - rot) & (FS_WAVES - 1); item < A.n_kpass; item += FS_WAVES) {
         // The hot loop below needs every register the occupancy target allows.  The lane index
         // is therefore re-read from the hardware where it is needed (before the loop for the
         // row address, after it for the reduction) rather than kept alive across the loop,
         // which would spill it, and everything derived from it, to scratch memory.
-        int G_r = G;
-        asm volatile("" : "+s"(G_r));
         const int lane_w = fresh_lane();
         const char* __restrict__ wrow = tile + lane_w * row_bytes;
         const uint8_t* __restrict__ mrow = mtile + lane_w * mstride;
-        float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
-        if (item < A.n_kpass) {
-            float mn, mx;
-            if (split_stats) {
-                mn = INFINITY;
-                mx = -INFINITY;
+        {
+            float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
-                for (int q = 0; q < FS_WAVES; ++q) {
-                    const float2 st = gstat[q * TILE_ROWS + lane_w];
-                    mn = fminf(mn, st.x);
-                    mx = fmaxf(mx, st.y);
-                }
-                if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
-            } else if (!MASKED) {
-                float w[8];
-                read8<DT>(wrow, 0, w);
-                mn = mx = w[0];
-                for (int32_t c = 0; c < G; c += 8) {
-                    read8<DT>(wrow, c, w);
-                    mn = fminf(fminf(fminf(mn, w[0]), fminf(w[1], w[2])), fminf(fminf(w[3], w[4]), fminf(w[5], fminf(w[6], w[7]))));
-                    mx = fmaxf(fmaxf(fmaxf(mx, w[0]), fmaxf(w[1], w[2])), fmaxf(fmaxf(w[3], w[4]), fmaxf(w[5], fmaxf(w[6], w[7]))));
-                }
-            } else {
-                mn = INFINITY;
-                mx = -INFINITY;
-                for (int32_t c = 0; c < G; c += 8) {
-                    float w[8];
-                    read8<DT>(wrow, c, w);
-                    const uint32_t m = mrow[c >> 3];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const bool kept = ((m >> j) & 1u) == 0u;
-                        mn = fminf(mn, kept ? w[j] : INFINITY);
-                        mx = fmaxf(mx, kept ? w[j] : -INFINITY);
-                    }
-                }
-                if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
+            for (int q = 0; q < FS_WAVES; ++q) {
+                const float2 st = gstat[q * TILE_ROWS + lane_w];
+                mn = fminf(mn, st.x);
+                mx = fmaxf(mx, st.y);
             }
+            if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
             // zero inside the closed range of every group of the wavefront?
             const bool anchored = __builtin_amdgcn_ballot_w64(!(mn <= 0.0f && mx >= 0.0f)) == 0;
             KParams P[FS_KB];
@@ -455,84 +505,26 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                 const int k = item * FS_KB + (lane_r >> 2);
                 if (k < K) out[(lane_r & 3) * K + k] = tot;
             }
-        } else {
-            // ternary absmean, binary sign*mean|w|, reference energy.  S1 = sum |w| in fp64
-            // in column order (exact for bf16 inputs): gamma = alpha = fp32(S1 / G).
-            double S1 = 0.0;
-            int32_t n_kept = G_r;
-            for (int32_t c = 0; c < G; c += 8) {
-                float w[8];
-                read8<DT>(wrow, c, w);
-                if (!MASKED) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) S1 += (double)fabsf(w[j]);
-                } else {
-                    const uint32_t m = mrow[c >> 3];
-                    n_kept -= __builtin_popcount(m);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) S1 += ((m >> j) & 1u) != 0u ? 0.0 : (double)fabsf(w[j]);
-                }
-            }
-            const float fam = n_kept > 0 ? (float)(S1 / (double)n_kept) : 0.0f;
-            const bool ok = fam >= FLT_MIN;
-            // Fast-issue fp32 only, as in the clip passes.  y = clamp01(w/(2 gamma) + 1/2) maps
-            // w/gamma in [-1, 1] onto [0, 1]; rne(2y) = q + 1 in {0, 1, 2} needs no clamp.
-            const float gam = pin_vgpr(ok ? fam : 0.0f);
-            const float ngam = pin_vgpr(ok ? -fam : 0.0f);
-            const float hginv = pin_vgpr(ok ? 0.5f / fam : 0.0f);
-            const float nalpha = pin_vgpr(-fam);
-            const float half = pin_vgpr(0.5f), two = pin_vgpr(2.0f);
-            const float M = pin_vgpr(RNE_POS);
-            float acc3[3] = {0.0f, 0.0f, 0.0f};
-            for (int32_t c = 0; c < G; c += 8) {
-                float w[8];
-                read8<DT>(wrow, c, w);
-                const float4 sa = *reinterpret_cast<const float4*>(scol + c);
-                const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
-                float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
-                if (MASKED) {
-                    const uint32_t m = mrow[c >> 3];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) s8[j] = ((m >> j) & 1u) != 0u ? 0.0f : s8[j];
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float sc = s8[j];
-                    const float y = fma_clamp01(w[j], hginv, half);
-                    const float qp = fmaf(y, two, M) - M;                    // q + 1
-                    const float rt = fmaf(qp, ngam, w[j] + gam) * sc;        // s_c (w - q gamma)
-                    acc3[0] = fmaf(rt, rt, acc3[0]);
-                    const float aw = __uint_as_float(__float_as_uint(w[j]) & 0x7fffffffu);
-                    const float rb = (aw + nalpha) * sc;                     // s_c (|w| - alpha)
-                    acc3[1] = fmaf(rb, rb, acc3[1]);
-                    const float w1 = w[j] * sc;
-                    acc3[2] = fmaf(w1, w1, acc3[2]);
-                }
-            }
-            const int lane_r = fresh_lane();
-            if (lane_r >= tc.nrows) acc3[0] = acc3[1] = acc3[2] = 0.0f;
-            const double tot = rows_sum<3>(acc3, red, lane_r);
-            if (lane_r < 3) out[4 * K + lane_r] = tot;
         }
     }
 }
 
 // Per unit: add the tiles' partial errors in a fixed order, pick the clip index with the
 // least error for each uniform bit-width (ties to the largest index), emit fp32.
-constexpr int FIN_THREADS = 256;
+constexpr int FIN_THREADS = 1024;
 constexpr int FIN_PHASES = FIN_THREADS / 64;
 __global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const double* __restrict__ partial,
                                                                           int64_t tiles_per_unit, int32_t K,
                                                                           float* __restrict__ err,
                                                                           uint8_t* __restrict__ clip_idx,
                                                                           float* __restrict__ ref_energy) {
-    __shared__ double part[FIN_PHASES][4 * WINDQ_MAX_CLIP + 3];
-    __shared__ double E[4 * WINDQ_MAX_CLIP + 3];
+    __shared__ double part[FIN_PHASES][4 * WINDQ_MAX_CLIP + 12];
+    __shared__ double E[4 * WINDQ_MAX_CLIP + 12];
     const int64_t u = blockIdx.x;
     const int32_t ncand = fit_score_ncand(K);
     const double* base = partial + (size_t)u * (size_t)tiles_per_unit * (size_t)ncand;
     const int phase = threadIdx.x >> 6;
-    // phase p adds tiles p, p+4, p+8, ... in order; the four phase sums are then added in order
+    // phase p adds tiles p, p+16, p+32, ... in order; the 16 phase sums are then added in order
     for (int32_t cand = threadIdx.x & 63; cand < ncand; cand += 64) {
         double acc = 0.0;
 #pragma unroll 4
@@ -560,12 +552,12 @@ __global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const d
         }
         err[u * WINDQ_N_ERR + tid] = (float)best;
         clip_idx[u * 4 + tid] = (uint8_t)bk;
-    } else if (tid == 4) {
-        err[u * WINDQ_N_ERR + 4] = (float)E[4 * K];
-    } else if (tid == 5) {
-        err[u * WINDQ_N_ERR + 5] = (float)E[4 * K + 1];
-    } else if (tid == 6 && ref_energy != nullptr) {
-        ref_energy[u] = (float)E[4 * K + 2];
+    } else if (tid < 7) {
+        // ternary, binary, reference energy: the four column quarters, in order
+        const int j = tid - 4;
+        const double e = ((E[4 * K + j] + E[4 * K + 3 + j]) + E[4 * K + 6 + j]) + E[4 * K + 9 + j];
+        if (j < 2) err[u * WINDQ_N_ERR + 4 + j] = (float)e;
+        else if (ref_energy != nullptr) ref_energy[u] = (float)e;
     }
 }
 
@@ -590,6 +582,7 @@ static int fit_score_impl(const windq_mat* W, const float* s, int32_t chunk_w, i
     A.partial = static_cast<double*>(ws);
     A.K = K;
     A.n_kpass = (K + FS_KB - 1) / FS_KB;
+    A.inv_G = 1.0 / (double)chunk_w;
     // tau keeps the short route's noise in the unit's 8-bit error at 1e-6 (one sigma):
     // 1.2e-4 sqrt(tau / (G R_u)) = 1e-6.  Below tau = 1 every column takes the exact route.
     const float t = 7e-5f * (float)chunk_w * (float)A.g.R_u;

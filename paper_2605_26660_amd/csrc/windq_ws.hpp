@@ -13,8 +13,9 @@ inline size_t calib_ws_bytes(int64_t rows, int64_t cols) {
 }
 
 // ---- fit_score: per tile, one fp64 partial error per candidate
-// candidates: [b][k] for b in 8,4,3,2 (index b*K + k), then ternary, binary, reference energy
-__host__ __device__ inline int32_t fit_score_ncand(int32_t K) { return 4 * K + 3; }
+// candidates: [b][k] for b in 8,4,3,2 (index b*K + k), then for each quarter of the chunk's
+// columns: ternary, binary, reference energy
+__host__ __device__ inline int32_t fit_score_ncand(int32_t K) { return 4 * K + 12; }
 inline size_t fit_score_ws_bytes(const Geometry& g, int32_t K) {
     return round_up((size_t)g.n_tiles * (size_t)fit_score_ncand(K) * sizeof(double), 256);
 }

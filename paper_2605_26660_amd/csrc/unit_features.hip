@@ -362,74 +362,108 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatArgs A,
     }
 }
 
+// Block-wide sums of N per-thread doubles at once (one pair of barriers), each in the fixed
+// order of block_sum.
+template <int N>
+__device__ __forceinline__ void block_sum_n(double (&v)[N], double* red) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) v[j] = wave_sum(v[j]);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) red[j * FT_WAVES + (threadIdx.x >> 6)] = v[j];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < FT_WAVES; ++w) t += red[j * FT_WAVES + w];
+        v[j] = t;
+    }
+}
+
 // Per unit: P99's key from the finished histograms, the count above half of it, the
 // moments in block order, the statistics of s over the chunk; writes the eight features.
+// The kernel is a chain of memory latencies (32-86 workgroups, nothing to overlap them
+// with), so everything the selection does not decide is requested before it starts: the
+// first round of block moments, the activation scales and the refined counters travel
+// together with the first-digit histogram.
 template <int DT>
 __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatArgs A) {
-    __shared__ double red[FT_WAVES];
+    __shared__ double red[6 * FT_WAVES];
     __shared__ uint32_t sh_part[FT_THREADS];
     __shared__ uint32_t sh_out[4];
     __shared__ float smax_sh[FT_THREADS];
     const int64_t u = blockIdx.x;
+    const int32_t G = A.g.chunk_w;
+    const float* __restrict__ sc = A.s + (u % A.g.n_chunks) * G;
+    const int tid = threadIdx.x;
+    // requested now, used after the selection
+    static_assert(WINDQ_MAX_CHUNK <= 2 * FT_THREADS, "two activation scales per thread cover a chunk");
+    double mv[4] = {0.0, 0.0, 0.0, 0.0};
+    if (tid < A.bpu) {
+        const double* src = A.moments + ((size_t)u * (size_t)A.bpu + (size_t)tid) * 4;
+        mv[0] = src[0]; mv[1] = src[1]; mv[2] = src[2]; mv[3] = src[3];
+    }
+    const bool has0 = tid < G, has1 = tid + FT_THREADS < G;
+    const float sv0 = has0 ? sc[tid] : 0.0f;
+    const float sv1 = has1 ? sc[tid + FT_THREADS] : 0.0f;
+    const uint32_t* h0 = A.hist + (size_t)u * FEAT_BINS;
+    const uint32_t* h1 = A.hist + ((size_t)A.g.U + (size_t)u) * FEAT_BINS;
+    uint32_t h1v = 0;
+    if (DT == WINDQ_BF16 && tid < 32) h1v = h1[tid];      // both refined bins: 2 x 16 counters
+
     double above = 0.0;
     if (DT == WINDQ_BF16) {
         uint32_t e0, l1;
         uint64_t rank1, below;
         select_prefix<DT>(A, u, 1, sh_part, sh_out, &e0, &rank1);
-        const uint32_t* h0 = A.hist + (size_t)u * FEAT_BINS;
-        const uint32_t* h1 = A.hist + ((size_t)A.g.U + (size_t)u) * FEAT_BINS;
         select_bin<FT_THREADS>(h1, 16, rank1, sh_part, sh_out, &l1, &below);
         // Key of 0.5 * P99: one exponent step down, or half the key where keys are linear in
         // the value (below 256: subnormals and the first binade).
         const uint32_t pk = (e0 << 4) | l1;
         const uint32_t tk = pk >= 256u ? pk - 128u : pk >> 1;
         const uint32_t tbin = tk >> 4, tlow = tk & 15u;        // tbin == half_bin_of(e0) by construction
-        for (int32_t b = threadIdx.x; b < FEAT_BINS; b += FT_THREADS)
+        for (int32_t b = tid; b < FEAT_BINS; b += FT_THREADS)
             if ((uint32_t)b > tbin) above += (double)h0[b];
         // (when both refined bins are bin 0 they share the first 16 counters)
-        if (threadIdx.x < 16 && (uint32_t)threadIdx.x > tlow) above += (double)h1[(tbin == e0 ? 0 : 16) + threadIdx.x];
+        const int first = tbin == e0 ? 0 : 16;
+        if (tid >= first && tid < first + 16 && (uint32_t)(tid - first) > tlow) above += (double)h1v;
     } else {
-        for (int64_t b = threadIdx.x; b < A.bpu; b += FT_THREADS) above += (double)A.above[(size_t)u * A.bpu + b];
+        for (int64_t b = tid; b < A.bpu; b += FT_THREADS) above += (double)A.above[(size_t)u * A.bpu + b];
     }
-    above = block_sum(above, red);
 
-    double m[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int64_t b = threadIdx.x; b < A.bpu; b += FT_THREADS) {
+    double m[4] = {mv[0], mv[1], mv[2], mv[3]};
+    for (int64_t b = tid + FT_THREADS; b < A.bpu; b += FT_THREADS) {
         const double* src = A.moments + ((size_t)u * (size_t)A.bpu + (size_t)b) * 4;
         m[0] += src[0]; m[1] += src[1]; m[2] += src[2]; m[3] += src[3];
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) m[j] = block_sum(m[j], red);
-    const int32_t G = A.g.chunk_w;
-    const float* __restrict__ sc = A.s + (u % A.g.n_chunks) * G;
     double ssum = 0.0;
     float smax = sc[0];
-    for (int32_t c = threadIdx.x; c < G; c += FT_THREADS) {
-        ssum += (double)sc[c];
-        smax = fmaxf(smax, sc[c]);
-    }
-    ssum = block_sum(ssum, red);
-    smax_sh[threadIdx.x] = smax;
-    const double smean = ssum / (double)G;
+    if (has0) { ssum += (double)sv0; smax = fmaxf(smax, sv0); }
+    if (has1) { ssum += (double)sv1; smax = fmaxf(smax, sv1); }
+    double r6[6] = {above, m[0], m[1], m[2], m[3], ssum};
+    block_sum_n<6>(r6, red);
+    smax_sh[tid] = smax;
+    const double smean = r6[5] / (double)G;
     double sdev = 0.0;
-    for (int32_t c = threadIdx.x; c < G; c += FT_THREADS) {
-        const double d = (double)sc[c] - smean;
-        sdev = fma(d, d, sdev);
-    }
+    if (has0) { const double d = (double)sv0 - smean; sdev = fma(d, d, sdev); }
+    if (has1) { const double d = (double)sv1 - smean; sdev = fma(d, d, sdev); }
     sdev = block_sum(sdev, red);   // its barriers also publish smax_sh
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
         float mx = smax_sh[0];
         for (int i = 1; i < FT_THREADS; ++i) mx = fmaxf(mx, smax_sh[i]);
         const double n = (double)A.g.R_u * (double)G;
-        const double mean = m[0] / n;
-        double var = m[1] / n - mean * mean;
+        const double mean = r6[1] / n;
+        double var = r6[2] / n - mean * mean;
         var = var > 0.0 ? var : 0.0;
         float* f = A.feat + u * WINDQ_N_FEAT;
         f[0] = (float)mean;
         f[1] = (float)sqrt(var);
-        f[2] = (float)(m[2] / n);
-        f[3] = (float)(m[3] / n);
-        f[4] = (float)(above / n);
+        f[2] = (float)(r6[3] / n);
+        f[3] = (float)(r6[4] / n);
+        f[4] = (float)(r6[0] / n);
         f[5] = (float)smean;
         f[6] = (float)sqrt(sdev / (double)G);
         f[7] = mx;

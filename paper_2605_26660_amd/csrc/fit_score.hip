@@ -85,7 +85,7 @@ __host__ __device__ inline int32_t mask_row_stride(int32_t chunk_w) { return (((
 inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
            (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
-           (size_t)chunk_w * sizeof(float) + (size_t)(FS_HMAX + 1 + 1) * sizeof(int32_t) +
+           (size_t)chunk_w * sizeof(float) + (size_t)FS_HMAX * sizeof(int32_t) +
            (size_t)FS_WAVES * TILE_ROWS * sizeof(double) +
            (masked ? (size_t)FS_WAVES * TILE_ROWS * sizeof(int32_t) + (size_t)TILE_ROWS * mask_row_stride(chunk_w) : 0);
 }
@@ -241,8 +241,8 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     const int32_t mstride = mask_row_stride(G);
     float2* __restrict__ gstat = reinterpret_cast<float2*>(scol + G + FS_WAVES * 16 * FS_NRED);   // [FS_WAVES][TILE_ROWS] (min, max)
     float* __restrict__ sshort = reinterpret_cast<float*>(gstat + FS_WAVES * TILE_ROWS);   // s_c, 0 for the listed columns
-    int32_t* __restrict__ hlist = reinterpret_cast<int32_t*>(sshort + G);   // listed columns; [FS_HMAX] = how many, -1: no list
-    double* __restrict__ s1tab = reinterpret_cast<double*>(hlist + FS_HMAX + 2);   // [FS_WAVES][TILE_ROWS] sum |w| of a quarter
+    int32_t* __restrict__ hlist = reinterpret_cast<int32_t*>(sshort + G);   // the listed columns
+    double* __restrict__ s1tab = reinterpret_cast<double*>(hlist + FS_HMAX);   // [FS_WAVES][TILE_ROWS] sum |w| of a quarter
     int32_t* __restrict__ nktab = reinterpret_cast<int32_t*>(s1tab + FS_WAVES * TILE_ROWS);   // kept weights of a quarter (masked)
     uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(nktab + (MASKED ? FS_WAVES * TILE_ROWS : 0));
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
@@ -265,9 +265,9 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     // the short route's ~1.2e-4/sqrt(rows) relative noise per column, the unit's 8-bit error
     // moves by at most 1.2e-4 sqrt(tau / (G R_u)) (one sigma): 1e-6 at the tau the host sets.
     // Every wavefront derives the same list and writes the same values: none waits for another.
+    int32_t nh = -1;      // listed columns; -1: no list, every column takes the exact route
     {
         const int l = fresh_lane();
-        int32_t nh = -1;
         if (A.tau > 0.0f) {
             float ss = 0.0f;
             for (int32_t c = l; c < G; c += 64) {
@@ -288,7 +288,6 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             }
             if (nh * 8 > G) nh = -1;     // so many that one exact sweep over all columns is cheaper
         }
-        if (l == 0) hlist[FS_HMAX] = nh;
     }
     // Group statistics (of the kept weights), once per tile: each wavefront scans a quarter of
     // the chunk's 8-column runs for all 64 rows -- minimum, maximum, and the sum of |w| in fp64
@@ -462,7 +461,6 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     for (int j = 0; j < 8; ++j) score_weight<AN>(w[j], s8[j], P, Q, M, nM, acc);
                 }
             };
-            const int32_t nh = __builtin_amdgcn_readfirstlane(hlist[FS_HMAX]);
             if (!anchored) {
                 sweep(std::false_type{});
             } else if (nh < 0) {

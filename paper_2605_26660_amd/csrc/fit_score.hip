@@ -172,6 +172,22 @@ __device__ __forceinline__ float read1(const char* __restrict__ wrow, int32_t c)
     return *reinterpret_cast<const float*>(wrow + c * 4);
 }
 
+// s, or 0 where bit J of the mask byte m is set: the bit, sign-extended to all ones, selects
+// between 0 and s (two instructions; written out because the compiler turns the same logic
+// back into a three-instruction test-compare-select per weight, and a branch on top).
+template <int J>
+__device__ __forceinline__ float drop_if_set(float sv, uint32_t m) {
+    uint32_t ones;
+    asm("v_bfe_i32 %1, %2, %3, 1\n\tv_bfi_b32 %0, %1, 0, %0" : "+v"(sv), "=&v"(ones) : "v"(m), "n"(J));
+    return sv;
+}
+__device__ __forceinline__ void drop_masked(float (&s8)[8], uint32_t m) {
+    s8[0] = drop_if_set<0>(s8[0], m); s8[1] = drop_if_set<1>(s8[1], m);
+    s8[2] = drop_if_set<2>(s8[2], m); s8[3] = drop_if_set<3>(s8[3], m);
+    s8[4] = drop_if_set<4>(s8[4], m); s8[5] = drop_if_set<5>(s8[5], m);
+    s8[6] = drop_if_set<6>(s8[6], m); s8[7] = drop_if_set<7>(s8[7], m);
+}
+
 // The lane's index in its wavefront, read anew from the hardware at every call (never kept
 // in a register between calls).
 __device__ __forceinline__ int fresh_lane() {
@@ -363,8 +379,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
             if (MASKED) {
                 const uint32_t m = mrow[c >> 3];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) s8[j] = ((m >> j) & 1u) != 0u ? 0.0f : s8[j];
+                drop_masked(s8, m);
             }
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -394,11 +409,9 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
         // is therefore re-read from the hardware where it is needed (before the loop for the
         // row address, after it for the reduction) rather than kept alive across the loop,
         // which would spill it, and everything derived from it, to scratch memory.
-        const int lane_w = fresh_lane();
-        const char* __restrict__ wrow = tile + lane_w * row_bytes;
-        const uint8_t* __restrict__ mrow = mtile + lane_w * mstride;
         {
             float mn = INFINITY, mx = -INFINITY;
+            const int lane_w = fresh_lane();
 #pragma unroll
             for (int q = 0; q < FS_WAVES; ++q) {
                 const float2 st = gstat[q * TILE_ROWS + lane_w];
@@ -444,8 +457,13 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             const float Q[4] = {pin_vgpr(255.0f), pin_vgpr(15.0f), pin_vgpr(7.0f), pin_vgpr(3.0f)};
             const float M = pin_vgpr(RNE_POS);
             const float nM = pin_vgpr(-RNE_POS);
+            // (the row addresses are formed from a fresh lane index in front of each sweep: kept
+            // from here they would be spilled across the parameter set-up)
             auto sweep = [&](auto MODE) {
                 constexpr bool AN = decltype(MODE)::value;
+                const int lane_v = fresh_lane();
+                const char* __restrict__ wrow = tile + lane_v * row_bytes;
+                const uint8_t* __restrict__ mrow = mtile + lane_v * mstride;
                 for (int32_t c = 0; c < G; c += 8) {
                     float w[8];
                     read8<DT>(wrow, c, w);
@@ -454,8 +472,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
                     if (MASKED) {
                         const uint32_t m = mrow[c >> 3];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) s8[j] = ((m >> j) & 1u) != 0u ? 0.0f : s8[j];
+                        drop_masked(s8, m);
                     }
 #pragma unroll
                     for (int j = 0; j < 8; ++j) score_weight<AN>(w[j], s8[j], P, Q, M, nM, acc);
@@ -466,6 +483,9 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             } else if (nh < 0) {
                 sweep(std::true_type{});
             } else {
+                const int lane_v = fresh_lane();
+                const char* __restrict__ wrow = tile + lane_v * row_bytes;
+                const uint8_t* __restrict__ mrow = mtile + lane_v * mstride;
                 for (int32_t c = 0; c < G; c += 8) {
                     float w[8];
                     read8<DT>(wrow, c, w);
@@ -474,8 +494,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
                     if (MASKED) {
                         const uint32_t m = mrow[c >> 3];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) s8[j] = ((m >> j) & 1u) != 0u ? 0.0f : s8[j];
+                        drop_masked(s8, m);
                     }
 #pragma unroll
                     for (int j = 0; j < 8; ++j) score_weight_short(w[j], s8[j], P, Q, M, nM, acc);

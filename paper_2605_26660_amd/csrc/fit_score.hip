@@ -75,13 +75,15 @@ struct FitScoreArgs {
     ClipGrid grid;
 };
 
-// LDS of a workgroup: the raw tile, s_c of the chunk's columns, and per wavefront a
-// 16 x FS_NRED scratch for combining rows.  Small on purpose: the fast fp32 issue rate
-// needs five or more resident wavefronts per SIMD (a single wavefront issues at most one
-// vector instruction per ~5 cycles), so LDS per workgroup must stay below ~30 KB.
 // Row stride of the tile's protection-mask bytes in LDS (masked kernels): an odd number of
 // dwords where the width allows, so that 64 lanes reading 64 rows spread over the banks.
 __host__ __device__ inline int32_t mask_row_stride(int32_t chunk_w) { return (((chunk_w >> 3) + 3) & ~3) + 4; }
+// LDS of a workgroup, in this order: the raw tile; s_c of the chunk's columns; per wavefront a
+// 16 x FS_NRED scratch for combining rows; the column quarters' (min, max) per row; s_c with
+// the listed columns zeroed, and the list; the quarters' fp64 sums of |w| per row; under a
+// mask, the quarters' kept counts and the tile's mask bytes.  28-30 KB at G = 128, small on
+// purpose: the fast fp32 issue rate needs five resident wavefronts per SIMD (a single
+// wavefront issues at most one vector instruction per ~5 cycles), i.e. five workgroups per CU.
 inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
            (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
@@ -279,7 +281,8 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     // rounding noise: such columns are listed and scored on the exact route, one at a time;
     // all others (s_c kept in sshort, listed ones zeroed there) go down the short route.  With
     // the short route's ~1.2e-4/sqrt(rows) relative noise per column, the unit's 8-bit error
-    // moves by at most 1.2e-4 sqrt(tau / (G R_u)) (one sigma): 1e-6 at the tau the host sets.
+    // moves by at most 1.2e-4 sqrt(tau / (G R_u)) (one sigma): 1e-6 at the tau the host sets
+    // (statistically, for units whose error is spread over their rows, as in weight matrices).
     // Every wavefront derives the same list and writes the same values: none waits for another.
     int32_t nh = -1;      // listed columns; -1: no list, every column takes the exact route
     {

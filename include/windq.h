@@ -283,7 +283,8 @@ int windq_fallback_promote(uint8_t* action /*HOST in/out [U]*/, const float* err
  *             skip units keep their weights
  * mask NULL or as in windq_apply_plan_prot: protected weights are left out of err and their
  * w_hat is 0 (their values live in the INT8 side stream).  err or w_hat may be NULL, not both.
- * Entries outside 0..6 or pointing outside [0, codes_bytes) count as skip.
+ * Entries outside 0..6, at an offset that is not a multiple of 16 (windq_plan_layout makes none)
+ * or pointing outside [0, codes_bytes) count as skip.
  */
 int windq_dequant_plan(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
                        const uint8_t* mask /*[rows][cols/8] or NULL*/, const uint8_t* action /*[U]*/,

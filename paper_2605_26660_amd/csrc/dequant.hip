@@ -6,9 +6,14 @@
 // a path that serves the quantized weights.
 //   uniform:  w_hat = offset + code * scale     ternary: scale * (trit - 1)     binary: +-scale
 // Errors use w_hat in fp64 from the stored fp32 numbers, as the fit does; the optional fp32
-// output is one fused multiply-add.  One wavefront per 64-row tile, one lane per row: a row's
-// packed bytes are contiguous, so a lane walks its own byte stream.  Reads 2 bytes per weight
-// plus the codes; bound by HBM.
+// output is one fused multiply-add.  Reads 2 bytes per weight plus the codes.
+// Two kernels.  Chunk widths of 8 x 2^k columns: a lane owns eight columns of a row, i.e. one
+// 16-byte piece of W, one mask byte, `bits` bytes of codes (ternary: the two or three bytes
+// its eight trits sit in), and G/8 neighbouring lanes cover a row with contiguous loads
+// straight from HBM; a workgroup walks the 64 rows of a tile, each lane keeping the fp64
+// weights s_c^2 of its columns.  ~6 fp64 operations per weight: the fp64 ALU and HBM are
+// both a few times under their limits.  Other widths: one wavefront per tile, one lane per
+// row over a tile staged in LDS (a lane walks its row's byte stream).
 #include "windq_common.hpp"
 #include "windq_ws.hpp"
 
@@ -60,7 +65,7 @@ __global__ __launch_bounds__(64) void dequant_tile_kernel(const DequantArgs A) {
     if (a >= WINDQ_N_ACTIONS) a = 0;
     const int64_t bpg = dq_bytes_per_group(a, G);
     const int64_t base = A.code_off[tc.u];
-    if (base < 0 || base + bpg * A.g.R_u > A.codes_bytes) a = 0;      // an entry that points outside the stream reads nothing
+    if (base < 0 || (base & 15) != 0 || base + bpg * A.g.R_u > A.codes_bytes) a = 0;   // a malformed entry reads nothing
 
     double acc = 0.0;
     if (lane < tc.nrows) {
@@ -123,16 +128,165 @@ __global__ __launch_bounds__(64) void dequant_tile_kernel(const DequantArgs A) {
         }
     }
     acc = wave_sum(acc);
-    if (lane == 0) A.part[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] = acc;
+    if (lane == 0) A.part[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] = acc;      // one partial per tile
 }
 
-__global__ __launch_bounds__(64) void dequant_finalize_kernel(const double* __restrict__ part, const Geometry g,
-                                                             float* __restrict__ err) {
-    const int64_t u = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    if (u >= g.U) return;
-    double t = 0.0;
-    for (int64_t i = 0; i < g.tiles_per_unit; ++i) t += part[(size_t)u * (size_t)g.tiles_per_unit + (size_t)i];
-    err[u] = (float)t;
+// Eight consecutive weights of a row, straight from global memory.
+template <int DT>
+__device__ __forceinline__ void load8_global(const void* __restrict__ p, float (&w)[8]) {
+    if (DT == WINDQ_BF16) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(p);
+        w[0] = bf16_bits_to_f32(raw.x & 0xffffu); w[1] = __uint_as_float(raw.x & 0xffff0000u);
+        w[2] = bf16_bits_to_f32(raw.y & 0xffffu); w[3] = __uint_as_float(raw.y & 0xffff0000u);
+        w[4] = bf16_bits_to_f32(raw.z & 0xffffu); w[5] = __uint_as_float(raw.z & 0xffff0000u);
+        w[6] = bf16_bits_to_f32(raw.w & 0xffffu); w[7] = __uint_as_float(raw.w & 0xffff0000u);
+    } else {
+        const float4 a = reinterpret_cast<const float4*>(p)[0];
+        const float4 b = reinterpret_cast<const float4*>(p)[1];
+        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+        w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+    }
+}
+
+// Lanes-per-row kernel: chunk_w = 8 << lpr_shift columns.  A workgroup takes one pass of a
+// 64-row tile, the 256 >> lpr_shift rows its threads cover at once: no loop over rows, so all
+// of a workgroup's loads are in flight together.
+constexpr int DQ_THREADS = 256;
+template <int DT>
+__global__ __launch_bounds__(DQ_THREADS) void dequant_split_kernel(const DequantArgs A, const int lpr_shift) {
+    __shared__ double red[DQ_THREADS / 64];
+    const int32_t passes = dequant_passes(A.g.chunk_w);
+    const int64_t tile = blockIdx.x / passes;
+    const int32_t pass = (int32_t)(blockIdx.x - tile * passes);
+    const TileCoord tc = tile_coord(A.g, tile);
+    const int32_t G = A.g.chunk_w;
+    constexpr int EB = Elem<DT>::bytes;
+    const int sub = threadIdx.x & ((1 << lpr_shift) - 1);      // which 8 columns of the row
+    const int rsub = threadIdx.x >> lpr_shift;                 // which row of a pass
+    const int rows_per_pass = DQ_THREADS >> lpr_shift;
+    const int32_t c = sub * 8;
+
+    int a = A.action[tc.u];
+    if (a >= WINDQ_N_ACTIONS) a = 0;
+    const int64_t bpg = dq_bytes_per_group(a, G);
+    const int64_t base = A.code_off[tc.u];
+    if (base < 0 || (base & 15) != 0 || base + bpg * A.g.R_u > A.codes_bytes) a = 0;   // a malformed entry reads nothing
+    const int bits = a == 1 ? 8 : (a == 2 ? 4 : (a == 3 ? 3 : (a == 4 ? 2 : 1)));
+
+    double ac[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const double sv = (double)A.s[tc.col0 + c + j];
+        ac[j] = sv * sv;
+    }
+    // ternary: a byte's five trits as five 2-bit fields, from a table the workgroup fills once
+    __shared__ uint16_t trits_of[256];
+    if (a == 5) {
+        uint32_t b = threadIdx.x, t = 0;
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            t |= (b % 3u) << (2 * i);
+            b /= 3u;
+        }
+        trits_of[threadIdx.x] = (uint16_t)t;
+        __syncthreads();
+    }
+
+    double acc = 0.0;
+    const int32_t r = pass * rows_per_pass + rsub;
+    if (r < tc.nrows && r < TILE_ROWS) {
+        const int64_t row = tc.row0 + r;
+        const int64_t gidx = tc.u * A.g.R_u + tc.lrow0 + r;
+        float w[8];
+        load8_global<DT>(static_cast<const char*>(A.W) + (row * A.g.ld + tc.col0 + c) * EB, w);
+        const uint32_t m = A.mask != nullptr ? A.mask[row * A.mask_ld + (tc.col0 >> 3) + sub] : 0u;
+        float* __restrict__ orow = A.what != nullptr ? A.what + row * A.what_ld + tc.col0 + c : nullptr;
+        float wh[8];
+        if (a == 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) wh[j] = w[j];                     // a skip unit keeps its weights
+        } else {
+            const float sc = A.scale[gidx];
+            const float of = A.offset[gidx];
+            const uint8_t* __restrict__ src = A.codes + base + (tc.lrow0 + r) * bpg;
+            double whd[8];
+            if (a == 5) {
+                // eight trits, five to a byte: they sit in two or three neighbouring bytes
+                const int32_t b0 = c / 5;
+                const int32_t last = (int32_t)bpg - 1;
+                const uint32_t y0 = src[b0];
+                const uint32_t y1 = src[b0 + 1 <= last ? b0 + 1 : last];
+                const uint32_t y2 = src[b0 + 2 <= last ? b0 + 2 : last];
+                const uint32_t v = ((uint32_t)trits_of[y0] | ((uint32_t)trits_of[y1] << 10) | ((uint32_t)trits_of[y2] << 20)) >>
+                                   (2 * (c - 5 * b0));
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    wh[j] = sc * ((float)((v >> (2 * j)) & 3u) - 1.0f);
+                    whd[j] = (double)wh[j];
+                }
+            } else {
+                // eight codes = `bits` bytes, aligned to their own size (units start on 16 bytes)
+                const uint8_t* p = src + sub * bits;
+                uint64_t v;
+                if (bits == 8) {
+                    const uint2 t = *reinterpret_cast<const uint2*>(p);
+                    v = (uint64_t)t.x | ((uint64_t)t.y << 32);
+                } else if (bits == 4) {
+                    v = *reinterpret_cast<const uint32_t*>(p);
+                } else if (bits == 3) {
+                    const uint32_t t0 = p[0], t1 = p[1], t2 = p[2];
+                    v = t0 | (t1 << 8) | (t2 << 16);
+                } else if (bits == 2) {
+                    v = *reinterpret_cast<const uint16_t*>(p);
+                } else {
+                    v = p[0];
+                }
+                if (a == 6) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        wh[j] = ((v >> j) & 1u) != 0u ? sc : -sc;
+                        whd[j] = (double)wh[j];
+                    }
+                } else {
+                    const double scd = (double)sc, ofd = (double)of;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t code = (uint32_t)(v >> (j * bits)) & ((1u << bits) - 1u);
+                        wh[j] = fmaf((float)code, sc, of);
+                        whd[j] = ofd + (double)code * scd;
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool prot = ((m >> j) & 1u) != 0u;              // lives in the INT8 side stream
+                const double d = (double)w[j] - whd[j];
+                acc = fma(prot ? 0.0 : ac[j] * d, d, acc);
+                wh[j] = prot ? 0.0f : wh[j];
+            }
+        }
+        if (orow != nullptr) {
+            reinterpret_cast<float4*>(orow)[0] = make_float4(wh[0], wh[1], wh[2], wh[3]);
+            reinterpret_cast<float4*>(orow)[1] = make_float4(wh[4], wh[5], wh[6], wh[7]);
+        }
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+#pragma unroll
+        for (int i = 0; i < DQ_THREADS / 64; ++i) t += red[i];
+        A.part[((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) * (size_t)passes + (size_t)pass] = t;
+    }
+}
+
+// err[u] = the sum of unit u's per_unit partials; one workgroup per unit.
+__global__ __launch_bounds__(256) void dequant_finalize_kernel(const double* __restrict__ part, const int64_t per_unit,
+                                                              float* __restrict__ err) {
+    __shared__ double red[4];
+    const double t = unit_partial_sum<256>(part + (size_t)blockIdx.x * (size_t)per_unit, per_unit, red);
+    if (threadIdx.x == 0) err[blockIdx.x] = (float)t;
 }
 
 }  // namespace windq
@@ -151,7 +305,7 @@ extern "C" int windq_dequant_plan(const windq_mat* W, const float* s, int32_t ch
     if (codes == nullptr && codes_bytes != 0) return WINDQ_EINVAL;
     if (err == nullptr && w_hat == nullptr) return WINDQ_EINVAL;
     if (!aligned(code_off, 8) || (w_hat != nullptr && !aligned(w_hat, 4))) return WINDQ_EINVAL;
-    if (ws == nullptr || ws_bytes < unit_saliency_ws_bytes(A.g) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
+    if (ws == nullptr || ws_bytes < dequant_ws_bytes(A.g) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
     A.W = W->data;
     A.s = s;
     A.mask = mask;
@@ -168,7 +322,22 @@ extern "C" int windq_dequant_plan(const windq_mat* W, const float* s, int32_t ch
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
     const dim3 tiles((unsigned)A.g.n_tiles);
-    if (W->dtype == WINDQ_BF16) {
+    // lanes-per-row kernel: 8 x 2^k columns, 16-byte pieces of W and of w_hat aligned
+    int lpr_shift = -1;
+    for (int k = 0; k <= 6; ++k)
+        if (chunk_w == (8 << k)) lpr_shift = k;
+    const size_t eb = W->dtype == WINDQ_BF16 ? 2 : 4;
+    const bool split = lpr_shift >= 0 && aligned(W->data, 16) && ((size_t)W->ld * eb) % 16 == 0 &&
+                       (w_hat == nullptr || aligned(w_hat, 16)) && aligned(codes, 8);
+    int64_t per_unit = A.g.tiles_per_unit;
+    if (split) {
+        const int32_t passes = dequant_passes(chunk_w);
+        if (A.g.n_tiles * passes > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
+        const dim3 grid((unsigned)(A.g.n_tiles * passes));
+        per_unit *= passes;
+        if (W->dtype == WINDQ_BF16) hipLaunchKernelGGL(dequant_split_kernel<WINDQ_BF16>, grid, dim3(DQ_THREADS), 0, hs, A, lpr_shift);
+        else hipLaunchKernelGGL(dequant_split_kernel<WINDQ_F32>, grid, dim3(DQ_THREADS), 0, hs, A, lpr_shift);
+    } else if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&dequant_tile_kernel<WINDQ_BF16>), lds);
         if (st != WINDQ_OK) return st;
         hipLaunchKernelGGL(dequant_tile_kernel<WINDQ_BF16>, tiles, dim3(64), lds, hs, A);
@@ -178,6 +347,6 @@ extern "C" int windq_dequant_plan(const windq_mat* W, const float* s, int32_t ch
         hipLaunchKernelGGL(dequant_tile_kernel<WINDQ_F32>, tiles, dim3(64), lds, hs, A);
     }
     if (err != nullptr)
-        hipLaunchKernelGGL(dequant_finalize_kernel, dim3((unsigned)((A.g.U + 63) / 64)), dim3(64), 0, hs, A.part, A.g, err);
+        hipLaunchKernelGGL(dequant_finalize_kernel, dim3((unsigned)A.g.U), dim3(256), 0, hs, A.part, per_unit, err);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }

@@ -252,13 +252,12 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
         A.codes[base + payload + lane] = 0;
 }
 
-__global__ __launch_bounds__(64) void refine_finalize_kernel(const double* __restrict__ part, const Geometry g,
-                                                            float* __restrict__ err) {
-    const int64_t u = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    if (u >= g.U) return;
-    double t = 0.0;
-    for (int64_t i = 0; i < g.tiles_per_unit; ++i) t += part[(size_t)u * (size_t)g.tiles_per_unit + (size_t)i];
-    err[u] = (float)t;
+// err[u] = the sum of unit u's tile partials; one workgroup per unit.
+__global__ __launch_bounds__(256) void refine_finalize_kernel(const double* __restrict__ part, const int64_t per_unit,
+                                                             float* __restrict__ err) {
+    __shared__ double red[4];
+    const double t = unit_partial_sum<256>(part + (size_t)blockIdx.x * (size_t)per_unit, per_unit, red);
+    if (threadIdx.x == 0) err[blockIdx.x] = (float)t;
 }
 
 }  // namespace windq
@@ -313,6 +312,6 @@ extern "C" int windq_refine_plan(const windq_mat* W, const float* s, int32_t chu
         if (st != WINDQ_OK) return st;
         hipLaunchKernelGGL(refine_plan_kernel<WINDQ_F32>, tiles, dim3(RF_THREADS), lds, hs, A);
     }
-    hipLaunchKernelGGL(refine_finalize_kernel, dim3((unsigned)((A.g.U + 63) / 64)), dim3(64), 0, hs, A.part, A.g, err);
+    hipLaunchKernelGGL(refine_finalize_kernel, dim3((unsigned)A.g.U), dim3(256), 0, hs, A.part, A.g.tiles_per_unit, err);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }

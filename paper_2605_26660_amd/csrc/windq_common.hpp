@@ -148,6 +148,22 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
+// Sum of the n fp64 partials of one unit by a workgroup of NT threads, in a fixed order:
+// thread t adds entries t, t + NT, ...; lanes by butterfly, wavefronts in order.  Every
+// thread returns the total.
+template <int NT>
+__device__ __forceinline__ double unit_partial_sum(const double* __restrict__ part, int64_t n, double* red) {
+    double t = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += NT) t += part[i];
+    t = wave_sum(t);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = t;
+    __syncthreads();
+    double tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) tot += red[w];
+    return tot;
+}
+
 #endif  // __HIPCC__
 
 }  // namespace windq

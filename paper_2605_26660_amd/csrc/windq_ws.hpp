@@ -77,6 +77,13 @@ inline size_t salient_ws_bytes(const Geometry& g) { return salient_layout(g).tot
 // ---- unit saliency: one fp64 partial per tile
 inline size_t unit_saliency_ws_bytes(const Geometry& g) { return round_up((size_t)g.n_tiles * sizeof(double), 256); }
 
+// ---- dequant: one fp64 partial per (tile, row pass); a pass is the rows 256 threads cover at
+// eight columns per lane, so a 64-row tile has chunk_w / 32 of them (at least one)
+__host__ __device__ inline int32_t dequant_passes(int32_t chunk_w) { return chunk_w >= 32 ? chunk_w / 32 : 1; }
+inline size_t dequant_ws_bytes(const Geometry& g) {
+    return round_up((size_t)g.n_tiles * (size_t)dequant_passes(g.chunk_w) * sizeof(double), 256);
+}
+
 // ---- apply_plan needs no scratch; a token size keeps "ws != NULL" uniform across calls
 inline size_t apply_ws_bytes(const Geometry&) { return 256; }
 

@@ -264,7 +264,8 @@ def test_workspace_sizes_of_the_later_calls(windq):
     B = windq.WINDQ_BF16
     tiles = 32 * 64
     assert windq.workspace_bytes(windq.CALL_UNIT_SALIENCY, B, 4096, 4096, 128, 0, 1) == tiles * 8
-    assert windq.workspace_bytes(windq.CALL_DEQUANT, B, 4096, 4096, 128, 0, 1) == tiles * 8
+    assert windq.workspace_bytes(windq.CALL_DEQUANT, B, 4096, 4096, 128, 0, 1) == tiles * 4 * 8      # 4 row passes per tile
+    assert windq.workspace_bytes(windq.CALL_DEQUANT, B, 4096, 4096, 16, 0, 1) == 256 * 64 * 8
     assert windq.workspace_bytes(windq.CALL_REFINE, B, 4096, 4096, 128, 0, 1) == tiles * 8
     sal = windq.workspace_bytes(windq.CALL_SALIENT, B, 4096, 4096, 128, 0, 1)
     assert sal >= 3 * 32 * 2048 * 4 + 32 * 4096 * 4 and sal % 256 == 0

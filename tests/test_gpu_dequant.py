@@ -92,3 +92,8 @@ def test_malformed_entries_read_nothing(windq):
     err, w_hat = windq.windq_dequant_plan(W, s, 128, 0, action.to(DEV), off.to(DEV), short, scale, offset)
     torch.cuda.synchronize()
     assert float(err[0]) == 0.0 and torch.equal(w_hat, W.float())
+    odd = torch.tensor([8, 64 * 128, 64 * 128], dtype=torch.int64)     # not on a 16-byte boundary: skip as well
+    big = torch.zeros(64 * 128 + 16, dtype=torch.uint8, device=DEV)
+    err, w_hat = windq.windq_dequant_plan(W, s, 128, 0, action.to(DEV), odd.to(DEV), big, scale, offset)
+    torch.cuda.synchronize()
+    assert float(err[0]) == 0.0 and torch.equal(w_hat, W.float())

@@ -388,12 +388,11 @@ __global__ __launch_bounds__(64) void sal_encode_kernel(const SalArgs A) {
     if (lane == 0) A.err_part[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] = err;
 }
 
-__global__ __launch_bounds__(64) void sal_err_kernel(const SalArgs A) {
+__global__ __launch_bounds__(256) void sal_err_kernel(const SalArgs A) {
+    __shared__ double red[4];
     const int64_t u = blockIdx.x;
-    if (threadIdx.x != 0) return;
-    double e = 0.0;
-    for (int64_t t = 0; t < A.g.tiles_per_unit; ++t) e += A.err_part[(size_t)u * (size_t)A.g.tiles_per_unit + (size_t)t];
-    A.err_prot[u] = (float)e;
+    const double e = unit_partial_sum<256>(A.err_part + (size_t)u * (size_t)A.g.tiles_per_unit, A.g.tiles_per_unit, red);
+    if (threadIdx.x == 0) A.err_prot[u] = (float)e;
 }
 
 // ------------------------------------------------------------------- unit saliency
@@ -428,13 +427,12 @@ __global__ __launch_bounds__(SAL_THREADS) void unit_saliency_tile_kernel(const v
     }
 }
 
-__global__ __launch_bounds__(64) void unit_saliency_finalize_kernel(const double* __restrict__ part, const Geometry g,
-                                                                   float* __restrict__ sal) {
-    const int64_t u = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    if (u >= g.U) return;
-    double t = 0.0;
-    for (int64_t i = 0; i < g.tiles_per_unit; ++i) t += part[(size_t)u * (size_t)g.tiles_per_unit + (size_t)i];
-    sal[u] = (float)(t / ((double)g.R_u * (double)g.chunk_w));
+__global__ __launch_bounds__(256) void unit_saliency_finalize_kernel(const double* __restrict__ part, const Geometry g,
+                                                                    float* __restrict__ sal) {
+    __shared__ double red[4];
+    const int64_t u = blockIdx.x;
+    const double t = unit_partial_sum<256>(part + (size_t)u * (size_t)g.tiles_per_unit, g.tiles_per_unit, red);
+    if (threadIdx.x == 0) sal[u] = (float)(t / ((double)g.R_u * (double)g.chunk_w));
 }
 
 static size_t sal_tile_lds(int32_t dtype, int32_t chunk_w) {
@@ -481,7 +479,7 @@ static int launch_encode(const SalArgs& A, hipStream_t hs, size_t lds) {
     hipLaunchKernelGGL(sal_rows_kernel<DT>, tiles, dim3(64), lds, hs, A);
     hipLaunchKernelGGL(sal_unit_kernel, units, dim3(SAL_THREADS), 0, hs, A);
     hipLaunchKernelGGL(sal_encode_kernel<DT>, tiles, dim3(64), lds, hs, A);
-    hipLaunchKernelGGL(sal_err_kernel, units, dim3(64), 0, hs, A);
+    hipLaunchKernelGGL(sal_err_kernel, units, dim3(256), 0, hs, A);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
@@ -564,6 +562,6 @@ extern "C" int windq_unit_saliency(const windq_mat* W, const float* s, int32_t c
         hipLaunchKernelGGL(unit_saliency_tile_kernel<WINDQ_BF16>, tiles, dim3(SAL_THREADS), 0, hs, W->data, s, g, part);
     else
         hipLaunchKernelGGL(unit_saliency_tile_kernel<WINDQ_F32>, tiles, dim3(SAL_THREADS), 0, hs, W->data, s, g, part);
-    hipLaunchKernelGGL(unit_saliency_finalize_kernel, dim3((unsigned)((g.U + 63) / 64)), dim3(64), 0, hs, part, g, sal);
+    hipLaunchKernelGGL(unit_saliency_finalize_kernel, dim3((unsigned)g.U), dim3(256), 0, hs, part, g, sal);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }

@@ -43,8 +43,11 @@ struct RefineArgs {
 
 __device__ __forceinline__ bool kept_bit(uint32_t m, int j) { return ((m >> j) & 1u) == 0u; }
 
+// Row stride of the tile's mask bytes in LDS: an odd number of dwords where the width allows.
+__host__ __device__ inline int32_t refine_mask_stride(int32_t chunk_w) { return (((chunk_w >> 3) + 3) & ~3) + 4; }
+
 template <int DT>
-__device__ __forceinline__ void refine_uniform(const char* wrow, const uint8_t* __restrict__ mrow, const float* scol,
+__device__ __forceinline__ void refine_uniform(const char* wrow, const uint8_t* mrow, const double* acol,
                                                int32_t G, float qmax, int n_iter, float* lo_io, float* d_io) {
     float lo = *lo_io, d = *d_io;
     for (int it = 0; it < n_iter; ++it) {
@@ -57,11 +60,10 @@ __device__ __forceinline__ void refine_uniform(const char* wrow, const uint8_t* 
             const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                if (!kept_bit(m, j)) continue;
                 const float u = w[j] - lo;
                 const float t = u * inv;
                 const double q = (double)__builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, qmax);
-                const double a = (double)scol[c + j] * (double)scol[c + j];
+                const double a = kept_bit(m, j) ? acol[c + j] : 0.0;      // a masked weight adds zeros
                 const double wd = (double)w[j];
                 const double aq = a * q;
                 S0 = S0 + a;
@@ -85,7 +87,7 @@ __device__ __forceinline__ void refine_uniform(const char* wrow, const uint8_t* 
 }
 
 template <int DT>
-__device__ __forceinline__ float refine_ternary(const char* wrow, const uint8_t* __restrict__ mrow, const float* scol,
+__device__ __forceinline__ float refine_ternary(const char* wrow, const uint8_t* mrow, const double* acol,
                                                 int32_t G, int n_iter, float gamma) {
     for (int it = 0; it < n_iter; ++it) {
         if (!(gamma >= FLT_MIN)) break;
@@ -97,10 +99,9 @@ __device__ __forceinline__ float refine_ternary(const char* wrow, const uint8_t*
             const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                if (!kept_bit(m, j)) continue;
                 const float t = w[j] * inv;
                 const double q = (double)__builtin_amdgcn_fmed3f(__builtin_rintf(t), -1.0f, 1.0f);
-                const double a = (double)scol[c + j] * (double)scol[c + j];
+                const double a = kept_bit(m, j) ? acol[c + j] : 0.0;
                 const double aq = a * q;
                 N1 = N1 + aq * (double)w[j];
                 D1 = D1 + aq * q;
@@ -115,7 +116,7 @@ __device__ __forceinline__ float refine_ternary(const char* wrow, const uint8_t*
 }
 
 template <int DT>
-__device__ __forceinline__ float refine_binary(const char* wrow, const uint8_t* __restrict__ mrow, const float* scol,
+__device__ __forceinline__ float refine_binary(const char* wrow, const uint8_t* mrow, const double* acol,
                                                int32_t G, float alpha) {
     double N1 = 0.0, D1 = 0.0;
     for (int32_t c = 0; c < G; c += 8) {
@@ -124,8 +125,7 @@ __device__ __forceinline__ float refine_binary(const char* wrow, const uint8_t* 
         const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            if (!kept_bit(m, j)) continue;
-            const double a = (double)scol[c + j] * (double)scol[c + j];
+            const double a = kept_bit(m, j) ? acol[c + j] : 0.0;
             N1 = N1 + a * (double)fabsf(w[j]);
             D1 = D1 + a;
         }
@@ -136,7 +136,7 @@ __device__ __forceinline__ float refine_binary(const char* wrow, const uint8_t* 
 // Activation-weighted error of a group under its final parameters (fp64; w_hat from the
 // stored fp32 numbers, as everywhere).
 template <int DT>
-__device__ __forceinline__ double group_error(const char* wrow, const uint8_t* __restrict__ mrow, const float* scol,
+__device__ __forceinline__ double group_error(const char* wrow, const uint8_t* mrow, const double* acol,
                                               int32_t G, int a, float sc, float of) {
     const int bits = a == 1 ? 8 : (a == 2 ? 4 : (a == 3 ? 3 : 2));
     const float qmax = (float)((1 << bits) - 1);
@@ -148,7 +148,6 @@ __device__ __forceinline__ double group_error(const char* wrow, const uint8_t* _
         const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            if (!kept_bit(m, j)) continue;
             double what;
             if (a <= 4) {
                 const float t = (w[j] - of) * inv;
@@ -159,7 +158,7 @@ __device__ __forceinline__ double group_error(const char* wrow, const uint8_t* _
                 what = w[j] >= 0.0f ? (double)sc : -(double)sc;
             }
             const double d = (double)w[j] - what;
-            const double ac = (double)scol[c + j] * (double)scol[c + j];
+            const double ac = kept_bit(m, j) ? acol[c + j] : 0.0;
             e = e + ac * d * d;
         }
     }
@@ -175,7 +174,9 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
     const int32_t G = A.g.chunk_w;
     const int32_t row_bytes = G * Elem<DT>::bytes + 16;
     char* tile = smem;
-    float* scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
+    double* acol = reinterpret_cast<double*>(smem + TILE_ROWS * row_bytes);     // s_c^2 of the chunk's columns
+    const int32_t mstride = refine_mask_stride(G);
+    uint8_t* mtile = reinterpret_cast<uint8_t*>(acol + G);                       // the tile's mask bytes (masked calls)
     const int lane = threadIdx.x;
     const bool valid = lane < tc.nrows;
     const int64_t gidx = tc.u * A.g.R_u + tc.lrow0 + lane;
@@ -198,14 +199,23 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
     }
 
     load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
-    for (int32_t c = lane; c < G; c += RF_THREADS) scol[c] = A.s[tc.col0 + c];
+    for (int32_t c = lane; c < G; c += RF_THREADS) {
+        const double sv = (double)A.s[tc.col0 + c];
+        acol[c] = sv * sv;
+    }
+    if (A.mask != nullptr) {
+        const int32_t mb = G >> 3;
+        for (int32_t i = lane; i < TILE_ROWS * mb; i += RF_THREADS) {
+            const int32_t r = i / mb, b = i - r * mb;
+            mtile[r * mstride + b] = r < tc.nrows ? A.mask[(tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) + b] : (uint8_t)0;
+        }
+    }
     __syncthreads();
 
     char* wrow = tile + lane * row_bytes;
     double err = 0.0;
     if (valid) {
-        const uint8_t* __restrict__ mrow =
-            A.mask != nullptr ? A.mask + (tc.row0 + lane) * A.mask_ld + (tc.col0 >> 3) : nullptr;
+        const uint8_t* mrow = A.mask != nullptr ? mtile + lane * mstride : nullptr;
         uint8_t* dst = reinterpret_cast<uint8_t*>(wrow);
         float sc = 0.0f, of = 0.0f;
         if (a <= 4) {
@@ -220,8 +230,8 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
             float mn, mx;
             group_min_max<DT>(wrow, mrow, G, &mn, &mx);
             uniform_params(mn, mx, p, qmax, &of, &sc);
-            refine_uniform<DT>(wrow, mrow, scol, G, qmax, A.n_iter, &of, &sc);
-            err = group_error<DT>(wrow, mrow, scol, G, a, sc, of);
+            refine_uniform<DT>(wrow, mrow, acol, G, qmax, A.n_iter, &of, &sc);
+            err = group_error<DT>(wrow, mrow, acol, G, a, sc, of);
             switch (a) {
                 case 1: uniform_pack<DT, 8>(wrow, mrow, G, of, sc, dst); break;
                 case 2: uniform_pack<DT, 4>(wrow, mrow, G, of, sc, dst); break;
@@ -231,13 +241,13 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
         } else if (a == 5) {
             sc = group_abs_mean<DT>(wrow, mrow, G);
             sc = sc >= FLT_MIN ? sc : 0.0f;
-            sc = refine_ternary<DT>(wrow, mrow, scol, G, A.n_iter, sc);
-            err = group_error<DT>(wrow, mrow, scol, G, a, sc, 0.0f);
+            sc = refine_ternary<DT>(wrow, mrow, acol, G, A.n_iter, sc);
+            err = group_error<DT>(wrow, mrow, acol, G, a, sc, 0.0f);
             ternary_pack<DT>(wrow, mrow, G, sc, dst);
         } else {
             sc = group_abs_mean<DT>(wrow, mrow, G);
-            if (A.n_iter > 0) sc = refine_binary<DT>(wrow, mrow, scol, G, sc);
-            err = group_error<DT>(wrow, mrow, scol, G, a, sc, 0.0f);
+            if (A.n_iter > 0) sc = refine_binary<DT>(wrow, mrow, acol, G, sc);
+            err = group_error<DT>(wrow, mrow, acol, G, a, sc, 0.0f);
             binary_pack<DT>(wrow, mrow, G, dst);
         }
         A.scale[gidx] = sc;
@@ -301,7 +311,8 @@ extern "C" int windq_refine_plan(const windq_mat* W, const float* s, int32_t chu
     A.n_iter = n_iter;
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid != nullptr ? clip_grid[k < K ? k : K - 1] : 1.0f;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
+    const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w) + (size_t)chunk_w * sizeof(double) +
+                       (mask != nullptr ? (size_t)TILE_ROWS * refine_mask_stride(chunk_w) : 0);
     const dim3 tiles((unsigned)A.g.n_tiles);
     if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&refine_plan_kernel<WINDQ_BF16>), lds);

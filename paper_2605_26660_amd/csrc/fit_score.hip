@@ -75,9 +75,6 @@ struct FitScoreArgs {
     ClipGrid grid;
 };
 
-// Row stride of the tile's protection-mask bytes in LDS (masked kernels): an odd number of
-// dwords where the width allows, so that 64 lanes reading 64 rows spread over the banks.
-__host__ __device__ inline int32_t mask_row_stride(int32_t chunk_w) { return (((chunk_w >> 3) + 3) & ~3) + 4; }
 // LDS of a workgroup, in this order: the raw tile; s_c of the chunk's columns; per wavefront a
 // 16 x FS_NRED scratch for combining rows; the column quarters' (min, max) per row; s_c with
 // the listed columns zeroed, and the list; the quarters' fp64 sums of |w| per row; under a
@@ -89,7 +86,7 @@ inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = 
            (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
            (size_t)chunk_w * sizeof(float) + (size_t)FS_HMAX * sizeof(int32_t) +
            (size_t)FS_WAVES * TILE_ROWS * sizeof(double) +
-           (masked ? (size_t)FS_WAVES * TILE_ROWS * sizeof(int32_t) + (size_t)TILE_ROWS * mask_row_stride(chunk_w) : 0);
+           (masked ? (size_t)FS_WAVES * TILE_ROWS * sizeof(int32_t) + mask_tile_lds_bytes(chunk_w) : 0);
 }
 
 // The 8-bit residual is ~1/500 of the range, so it is taken relative to an ANCHOR c: a grid
@@ -267,13 +264,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
 
     load_tile_raw<DT, 1>(A.W, A.g.ld, tc, G, tile);      // 256 threads: four short steps, few registers
     for (int32_t c = threadIdx.x; c < G; c += FS_THREADS) scol[c] = A.s[tc.col0 + c];
-    if (MASKED) {
-        const int32_t mb = G >> 3;
-        for (int32_t i = threadIdx.x; i < TILE_ROWS * mb; i += FS_THREADS) {
-            const int32_t r = i / mb, b = i - r * mb;
-            mtile[r * mstride + b] = r < tc.nrows ? A.mask[(tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) + b] : (uint8_t)0;
-        }
-    }
+    if (MASKED) load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     __syncthreads();
 
     // Column selection for the 8-bit candidate.  A column whose s_c^2 exceeds

@@ -43,9 +43,6 @@ struct RefineArgs {
 
 __device__ __forceinline__ bool kept_bit(uint32_t m, int j) { return ((m >> j) & 1u) == 0u; }
 
-// Row stride of the tile's mask bytes in LDS: an odd number of dwords where the width allows.
-__host__ __device__ inline int32_t refine_mask_stride(int32_t chunk_w) { return (((chunk_w >> 3) + 3) & ~3) + 4; }
-
 template <int DT>
 __device__ __forceinline__ void refine_uniform(const char* wrow, const uint8_t* mrow, const double* acol,
                                                int32_t G, float qmax, int n_iter, float* lo_io, float* d_io) {
@@ -175,7 +172,7 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
     const int32_t row_bytes = G * Elem<DT>::bytes + 16;
     char* tile = smem;
     double* acol = reinterpret_cast<double*>(smem + TILE_ROWS * row_bytes);     // s_c^2 of the chunk's columns
-    const int32_t mstride = refine_mask_stride(G);
+    const int32_t mstride = mask_row_stride(G);
     uint8_t* mtile = reinterpret_cast<uint8_t*>(acol + G);                       // the tile's mask bytes (masked calls)
     const int lane = threadIdx.x;
     const bool valid = lane < tc.nrows;
@@ -203,13 +200,7 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
         const double sv = (double)A.s[tc.col0 + c];
         acol[c] = sv * sv;
     }
-    if (A.mask != nullptr) {
-        const int32_t mb = G >> 3;
-        for (int32_t i = lane; i < TILE_ROWS * mb; i += RF_THREADS) {
-            const int32_t r = i / mb, b = i - r * mb;
-            mtile[r * mstride + b] = r < tc.nrows ? A.mask[(tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) + b] : (uint8_t)0;
-        }
-    }
+    if (A.mask != nullptr) load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     __syncthreads();
 
     char* wrow = tile + lane * row_bytes;
@@ -312,7 +303,7 @@ extern "C" int windq_refine_plan(const windq_mat* W, const float* s, int32_t chu
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid != nullptr ? clip_grid[k < K ? k : K - 1] : 1.0f;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w) + (size_t)chunk_w * sizeof(double) +
-                       (mask != nullptr ? (size_t)TILE_ROWS * refine_mask_stride(chunk_w) : 0);
+                       (mask != nullptr ? mask_tile_lds_bytes(chunk_w) : 0);
     const dim3 tiles((unsigned)A.g.n_tiles);
     if (W->dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&refine_plan_kernel<WINDQ_BF16>), lds);

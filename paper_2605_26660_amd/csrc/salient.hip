@@ -285,14 +285,16 @@ __global__ __launch_bounds__(64) void sal_rows_kernel(const SalArgs A) {
     constexpr int EB = Elem<DT>::bytes;
     const int32_t row_bytes = G * EB + 16;
     const int lane = threadIdx.x;
+    uint8_t* mtile = reinterpret_cast<uint8_t*>(smem + TILE_ROWS * row_bytes + G * sizeof(float));
     load_tile_raw<DT>(A.W, A.g.ld, tc, G, smem);
+    load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     __syncthreads();
     const bool valid = lane < tc.nrows;
     uint32_t n = 0;
     float mx = 0.0f;
     if (valid) {
         const char* wrow = smem + lane * row_bytes;
-        const uint8_t* __restrict__ mrow = A.mask + (tc.row0 + lane) * A.mask_ld + (tc.col0 >> 3);
+        const uint8_t* mrow = mtile + lane * mask_row_stride(G);
         for (int32_t c = 0; c < G; c += 8) {
             const uint32_t m = mrow[c >> 3];
             float w[8];
@@ -354,7 +356,9 @@ __global__ __launch_bounds__(64) void sal_encode_kernel(const SalArgs A) {
     const int32_t row_bytes = G * EB + 16;
     float* scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
     const int lane = threadIdx.x;
+    uint8_t* mtile = reinterpret_cast<uint8_t*>(scol + G);
     load_tile_raw<DT>(A.W, A.g.ld, tc, G, smem);
+    load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     for (int32_t c = lane; c < G; c += 64) scol[c] = A.s[tc.col0 + c];
     __syncthreads();
     const float sg = A.prot_scale[tc.u];
@@ -362,7 +366,7 @@ __global__ __launch_bounds__(64) void sal_encode_kernel(const SalArgs A) {
     double err = 0.0;
     if (lane < tc.nrows) {
         const char* wrow = smem + lane * row_bytes;
-        const uint8_t* __restrict__ mrow = A.mask + (tc.row0 + lane) * A.mask_ld + (tc.col0 >> 3);
+        const uint8_t* mrow = mtile + lane * mask_row_stride(G);
         uint32_t pos = A.row_off[tc.u * A.g.R_u + tc.lrow0 + lane];
         int8_t* __restrict__ dst = A.prot_codes + (size_t)tc.u * (size_t)A.n_p;
         for (int32_t c = 0; c < G; c += 8) {
@@ -435,8 +439,9 @@ __global__ __launch_bounds__(256) void unit_saliency_finalize_kernel(const doubl
     if (threadIdx.x == 0) sal[u] = (float)(t / ((double)g.R_u * (double)g.chunk_w));
 }
 
+// raw tile, s_c of the chunk, the tile's mask bytes
 static size_t sal_tile_lds(int32_t dtype, int32_t chunk_w) {
-    return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
+    return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) + mask_tile_lds_bytes(chunk_w);
 }
 
 static void carve(SalArgs& A, void* ws, const SalientLayout& L) {

@@ -48,6 +48,11 @@ inline size_t raw_tile_lds_bytes(int32_t dtype, int32_t chunk_w) {
     return (size_t)TILE_ROWS * ((size_t)chunk_w * (dtype == WINDQ_BF16 ? 2 : 4) + 16);
 }
 
+// Row stride of a tile's protection-mask bytes staged in LDS: an odd number of dwords where
+// the width allows, so that 64 lanes reading 64 rows spread over the banks.
+__host__ __device__ inline int32_t mask_row_stride(int32_t chunk_w) { return (((chunk_w >> 3) + 3) & ~3) + 4; }
+inline size_t mask_tile_lds_bytes(int32_t chunk_w) { return (size_t)TILE_ROWS * (size_t)mask_row_stride(chunk_w); }
+
 // Raises the dynamic-LDS limit of a kernel when a tile needs more than the 64 KB a
 // workgroup gets by default (gfx950 has 160 KB per CU).
 int ensure_lds(const void* kernel, size_t bytes);
@@ -119,6 +124,41 @@ __device__ __forceinline__ void load_tile_raw(const void* __restrict__ data, int
             const int32_t r = i / pieces;
             const int32_t pc = i - r * pieces;
             if (i < total) *reinterpret_cast<uint4*>(tile + r * row_bytes + pc * 16) = v[k];
+        }
+    }
+}
+
+// Cooperative load of a tile's mask bytes (one per 8 columns and row) into LDS, rows past the
+// unit's end as zeros.  Kernels that give a lane a row read them from there: a byte load from
+// global memory inside a lane's column loop would put a memory latency into every step.
+__device__ __forceinline__ void load_mask_tile(const uint8_t* __restrict__ mask, int64_t mask_ld, const TileCoord& tc,
+                                               int32_t chunk_w, uint8_t* __restrict__ mtile) {
+    const int32_t mb = chunk_w >> 3;                 // mask bytes per row of the tile
+    const int32_t mstride = mask_row_stride(chunk_w);
+    const uint8_t* __restrict__ src = mask + tc.row0 * mask_ld + (tc.col0 >> 3);
+    const bool by16 = (mb & 15) == 0 && (mask_ld & 15) == 0 && (reinterpret_cast<uintptr_t>(src) & 15) == 0;
+    const bool by4 = (mb & 3) == 0 && (mask_ld & 3) == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0;
+    if (by16) {                                      // e.g. chunk 128: one 16-byte load per row
+        const int32_t pieces = mb >> 4;
+        for (int32_t i = threadIdx.x; i < TILE_ROWS * pieces; i += blockDim.x) {
+            const int32_t r = i / pieces, pc = i - r * pieces;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (r < tc.nrows) v = *reinterpret_cast<const uint4*>(src + r * mask_ld + pc * 16);
+            uint32_t* dst = reinterpret_cast<uint32_t*>(mtile + r * mstride + pc * 16);
+            dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+        }
+    } else if (by4) {
+        const int32_t pieces = mb >> 2;
+        for (int32_t i = threadIdx.x; i < TILE_ROWS * pieces; i += blockDim.x) {
+            const int32_t r = i / pieces, pc = i - r * pieces;
+            uint32_t v = 0u;
+            if (r < tc.nrows) v = *reinterpret_cast<const uint32_t*>(src + r * mask_ld + pc * 4);
+            *reinterpret_cast<uint32_t*>(mtile + r * mstride + pc * 4) = v;
+        }
+    } else {
+        for (int32_t i = threadIdx.x; i < TILE_ROWS * mb; i += blockDim.x) {
+            const int32_t r = i / mb, bb = i - r * mb;
+            mtile[r * mstride + bb] = r < tc.nrows ? src[r * mask_ld + bb] : (uint8_t)0;
         }
     }
 }

@@ -333,15 +333,20 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_unit_kernel(const SalArgs A) 
         if (!(sg >= FLT_MIN)) sg = 0.0f;
         A.prot_scale[u] = sg;
     }
+    // each thread owns a run of consecutive rows: its sum, one scan over the threads, then the
+    // run again to write the offsets (one scan per unit instead of one per 256 rows)
     uint32_t* __restrict__ ro = A.row_off + u * A.g.R_u;
-    uint32_t carry = 0;
-    for (int64_t r0 = 0; r0 < A.g.R_u; r0 += SAL_THREADS) {
-        const int64_t r = r0 + threadIdx.x;
-        const uint32_t n = r < A.g.R_u ? ro[r] : 0u;
-        uint32_t tot;
-        const uint32_t excl = block_exclusive_scan_u32(n, sh, &tot);
-        if (r < A.g.R_u) ro[r] = carry + excl;
-        carry += tot;
+    const int64_t run = (A.g.R_u + SAL_THREADS - 1) / SAL_THREADS;
+    const int64_t r_lo = (int64_t)threadIdx.x * run;
+    const int64_t r_hi = r_lo + run < A.g.R_u ? r_lo + run : A.g.R_u;
+    uint32_t mine = 0;
+    for (int64_t r = r_lo; r < r_hi; ++r) mine += ro[r];
+    uint32_t tot;
+    uint32_t pos = block_exclusive_scan_u32(mine, sh, &tot);
+    for (int64_t r = r_lo; r < r_hi; ++r) {
+        const uint32_t n = ro[r];
+        ro[r] = pos;
+        pos += n;
     }
 }
 

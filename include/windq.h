@@ -72,6 +72,7 @@ enum windq_call {
 #define WINDQ_N_FEAT 8
 #define WINDQ_MAX_CLIP 64    /* longest clip grid */
 #define WINDQ_MAX_CHUNK 512  /* widest chunk */
+#define WINDQ_MAX_BATCH 8    /* most matrices one *_batch call takes */
 
 /* A row-major matrix in device memory.  Never written by the library. */
 typedef struct windq_mat {
@@ -134,6 +135,27 @@ int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int3
                              const float* clip_grid /*HOST [K]*/, int32_t K,
                              float* err /*[U][6]*/, uint8_t* clip_idx /*[U][4]*/, float* ref_energy /*[U] or NULL*/,
                              void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * windq_fit_score_all_bits for up to WINDQ_MAX_BATCH matrices in ONE launch (plus one finalize
+ * launch): the matrices of a decoder block are small against this GPU, and a launch per matrix
+ * leaves it partly empty at every start and end.  Item i is one per-matrix call: the same
+ * arguments, the same workspace size, and bit for bit the same results.  All items share chunk_w,
+ * unit_rows, the clip grid and the element type.  `items` is a HOST array read during the call.
+ * WINDQ_EINVAL for n outside 1..WINDQ_MAX_BATCH or mixed element types; otherwise as the
+ * per-matrix call (nothing is launched if any item fails its checks).
+ */
+typedef struct windq_fit_item {
+    const windq_mat* W;     /* HOST descriptor of a device matrix */
+    const float* s;         /* [cols] */
+    float* err;             /* [U][6] */
+    uint8_t* clip_idx;      /* [U][4] */
+    float* ref_energy;      /* [U] or NULL */
+    void* ws;
+    size_t ws_bytes;
+} windq_fit_item;
+int windq_fit_score_all_bits_batch(const windq_fit_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w,
+                                   int64_t unit_rows, const float* clip_grid /*HOST [K]*/, int32_t K, void* stream);
 
 /* Packed bytes of one group under an action: ceil(chunk_w*b/8), ceil(chunk_w/5) for
  * ternary, 0 for skip; -1 for an action outside 0..6 or chunk_w <= 0.  HOST only. */

@@ -17,14 +17,14 @@ LIB_PATH = os.path.join(_PKG_DIR, "libwindq.so")
 WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP = range(6)
 WINDQ_F32, WINDQ_BF16 = 0, 1
 CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT, CALL_REFINE = range(8)
-N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK = 7, 6, 8, 64, 512
+N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK, MAX_BATCH = 7, 6, 8, 64, 512, 8
 
 EXPORTS = (
     "windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_bytes_per_group",
     "windq_plan_layout", "windq_apply_plan", "windq_effective_bits", "windq_workspace_bytes",
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
-    "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan",
+    "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan", "windq_fit_score_all_bits_batch",
 )
 
 
@@ -38,6 +38,12 @@ class WindqError(RuntimeError):
 class windq_mat(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("ld", ctypes.c_int64)]
+
+
+class windq_fit_item(ctypes.Structure):
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("err", ctypes.c_void_p),
+                ("clip_idx", ctypes.c_void_p), ("ref_energy", ctypes.c_void_p), ("ws", ctypes.c_void_p),
+                ("ws_bytes", ctypes.c_size_t)]
 
 
 _lib = None
@@ -78,13 +84,14 @@ def load(path: str | None = None):
     lib.windq_fallback_promote.argtypes = [vp, vp, vp, i64, c.c_float, c.POINTER(i64)]
     lib.windq_dequant_plan.argtypes = [pm, vp, i32, i64, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, sz, vp]
     lib.windq_refine_plan.argtypes = [pm, vp, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp, vp, sz, vp]
+    lib.windq_fit_score_all_bits_batch.argtypes = [c.POINTER(windq_fit_item), i32, i32, i64, vp, i32, vp]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
                  "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode",
                  "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency",
                  "windq_heuristic_plan", "windq_fallback_promote", "windq_dequant_plan",
-                 "windq_refine_plan"):
+                 "windq_refine_plan", "windq_fit_score_all_bits_batch"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -197,6 +204,35 @@ def windq_fit_score_all_bits(W: torch.Tensor, s: torch.Tensor, chunk_w: int, uni
                                                     ref.data_ptr(), ws.data_ptr(), ws.numel(), _stream()),
                "windq_fit_score_all_bits_prot")
     return err, clip_idx, ref
+
+
+def windq_fit_score_all_bits_batch(Ws, ss, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor, wss=None, outs=None):
+    """windq_fit_score_all_bits for several matrices (lists of equal length, at most MAX_BATCH) in one launch.
+    -> list of (err, clip_idx, ref_energy), one per matrix."""
+    n = len(Ws)
+    assert len(ss) == n and (wss is None or len(wss) == n) and (outs is None or len(outs) == n)
+    _require_cuda(*Ws, *ss)
+    assert not clip_grid.is_cuda and clip_grid.dtype == torch.float32 and clip_grid.is_contiguous()
+    K = clip_grid.numel()
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_fit_item * max(n, 1))()
+    res, keep = [], []
+    for i, (W, s) in enumerate(zip(Ws, ss)):
+        U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+        if outs is None:
+            o = (torch.empty(U, N_ERR, dtype=torch.float32, device=W.device),
+                 torch.empty(U, 4, dtype=torch.uint8, device=W.device),
+                 torch.empty(U, dtype=torch.float32, device=W.device))
+        else:
+            o = outs[i]
+        ws = _workspace(CALL_FIT_SCORE, W, chunk_w, unit_rows, K, None if wss is None else wss[i])
+        keep.append(ws)
+        items[i] = windq_fit_item(ctypes.pointer(mats[i]), s.data_ptr(), o[0].data_ptr(), o[1].data_ptr(), o[2].data_ptr(),
+                                  ws.data_ptr(), ws.numel())
+        res.append(o)
+    _check(load().windq_fit_score_all_bits_batch(items, n, chunk_w, unit_rows, clip_grid.data_ptr(), K, _stream()),
+           "windq_fit_score_all_bits_batch")
+    return res
 
 
 def windq_bytes_per_group(action: int, chunk_w: int) -> int:

@@ -61,19 +61,40 @@ constexpr int FS_NRED = FS_KB * 4;          // per-lane sums a pass produces
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
 constexpr int FS_HMAX = WINDQ_MAX_CHUNK / 8;   // most columns a tile may send down the exact 8-bit route on their own
 
-struct FitScoreArgs {
+// One matrix of a launch.
+struct FitScoreMat {
     const void* W;
     const float* s;
     const uint8_t* mask;   // protection mask [rows][cols/8] (masked kernels only)
     int64_t mask_ld;
     double* partial;   // [n_tiles][4K+12]
+    float* err;        // outputs of the finalize kernel
+    uint8_t* clip_idx;
+    float* ref_energy;
     Geometry g;
-    int32_t K;
-    int32_t n_kpass;   // ceil(K / FS_KB)
-    double inv_G;      // 1 / chunk_w
     float tau;         // columns with s_c^2 > tau * mean(s^2) of the chunk take the exact 8-bit route; 0: all do
+};
+
+// A launch covers up to WINDQ_MAX_BATCH matrices of one chunk width and element type: their
+// tiles (and, for the finalize kernel, their units) are numbered one matrix after the other,
+// so that one grid keeps the chip filled across matrix boundaries.
+struct FitScoreArgs {
+    int32_t n;                                   // matrices in the launch
+    int32_t K;
+    int32_t n_kpass;                             // ceil(K / FS_KB)
+    double inv_G;                                // 1 / chunk_w
+    int64_t tile_start[WINDQ_MAX_BATCH + 1];     // first tile of matrix i in the grid; [n] = grid size
+    int64_t unit_start[WINDQ_MAX_BATCH + 1];
+    FitScoreMat m[WINDQ_MAX_BATCH];
     ClipGrid grid;
 };
+
+// Which matrix of the launch holds item `idx` (a tile or a unit), by its start table.
+__device__ __forceinline__ int batch_index(const int64_t (&start)[WINDQ_MAX_BATCH + 1], int32_t n, int64_t idx) {
+    int mi = 0;
+    while (mi + 1 < n && idx >= start[mi + 1]) ++mi;
+    return mi;
+}
 
 // LDS of a workgroup, in this order: the raw tile; s_c of the chunk's columns; per wavefront a
 // 16 x FS_NRED scratch for combining rows; the column quarters' (min, max) per row; s_c with
@@ -245,9 +266,11 @@ __device__ __forceinline__ double rows_sum(const float (&v)[N], float* __restric
 // MASKED: salient weights (Sec. 3.5) marked in A.mask take no part: they are left out of
 // the group statistics, and in every error sum their activation scale counts as zero.
 template <int DT, bool MASKED>
-__global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScoreArgs A) {
+__global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScoreArgs B) {
     extern __shared__ char smem[];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const FitScoreMat& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
     constexpr int EB = Elem<DT>::bytes;
     const int32_t row_bytes = G * EB + 16;
@@ -330,7 +353,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
         __syncthreads();
     }
 
-    const int32_t K = A.K;
+    const int32_t K = B.K;
     double* __restrict__ out = A.partial + ((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) *
                                                (size_t)fit_score_ncand(K);
 
@@ -354,7 +377,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
         }
         // n is the chunk width unless weights are masked out; the product with its reciprocal (from
         // the host) rounds to the same fp32 as the quotient, but for ~1e-9 of groups when G is not 2^k
-        const float fam = MASKED ? (n_kept > 0 ? (float)(S1 / (double)n_kept) : 0.0f) : (float)(S1 * A.inv_G);
+        const float fam = MASKED ? (n_kept > 0 ? (float)(S1 / (double)n_kept) : 0.0f) : (float)(S1 * B.inv_G);
         const bool ok = fam >= FLT_MIN;
         // Fast-issue fp32 only, as in the clip passes.  y = clamp01(w/(2 gamma) + 1/2) maps
         // w/gamma in [-1, 1] onto [0, 1]; rne(2y) = q + 1 in {0, 1, 2} needs no clamp.
@@ -398,7 +421,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     // The clip grid: n_kpass passes over FS_KB clip ratios each.  Pass i goes to wavefront
     // (i + rot) % 4; rot spreads an uneven number of passes over the four SIMDs from tile to tile.
     const int rot = blockIdx.x & (FS_WAVES - 1);
-    for (int item = (wave - rot) & (FS_WAVES - 1); item < A.n_kpass; item += FS_WAVES) {
+    for (int item = (wave - rot) & (FS_WAVES - 1); item < B.n_kpass; item += FS_WAVES) {
         // The hot loop below needs every register the occupancy target allows.  The lane index
         // is therefore re-read from the hardware where it is needed (before the loop for the
         // row address, after it for the reduction) rather than kept alive across the loop,
@@ -421,7 +444,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             for (int i = 0; i < FS_KB; ++i) {
                 int k = item * FS_KB + i;
                 k = k < K ? k : K - 1;
-                const float p = A.grid.p[k];
+                const float p = B.grid.p[k];
                 const float flo = p * mn;
                 const float fhi = p * mx;
                 const float frg = fhi - flo;
@@ -524,16 +547,19 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
 // least error for each uniform bit-width (ties to the largest index), emit fp32.
 constexpr int FIN_THREADS = 1024;
 constexpr int FIN_PHASES = FIN_THREADS / 64;
-__global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const double* __restrict__ partial,
-                                                                          int64_t tiles_per_unit, int32_t K,
-                                                                          float* __restrict__ err,
-                                                                          uint8_t* __restrict__ clip_idx,
-                                                                          float* __restrict__ ref_energy) {
+__global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const FitScoreArgs B) {
     __shared__ double part[FIN_PHASES][4 * WINDQ_MAX_CLIP + 12];
     __shared__ double E[4 * WINDQ_MAX_CLIP + 12];
-    const int64_t u = blockIdx.x;
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
+    const FitScoreMat& A = B.m[mi];
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
+    const int32_t K = B.K;
+    const int64_t tiles_per_unit = A.g.tiles_per_unit;
+    float* __restrict__ err = A.err;
+    uint8_t* __restrict__ clip_idx = A.clip_idx;
+    float* __restrict__ ref_energy = A.ref_energy;
     const int32_t ncand = fit_score_ncand(K);
-    const double* base = partial + (size_t)u * (size_t)tiles_per_unit * (size_t)ncand;
+    const double* base = A.partial + (size_t)u * (size_t)tiles_per_unit * (size_t)ncand;
     const int phase = threadIdx.x >> 6;
     // phase p adds tiles p, p+16, p+32, ... in order; the 16 phase sums are then added in order
     for (int32_t cand = threadIdx.x & 63; cand < ncand; cand += 64) {
@@ -576,47 +602,88 @@ __global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const d
 
 using namespace windq;
 
-static int fit_score_impl(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, const uint8_t* mask,
-                          const float* clip_grid, int32_t K, float* err, uint8_t* clip_idx, float* ref_energy,
-                          void* ws, size_t ws_bytes, void* stream) {
+// One matrix of a launch as the entry points see it.
+struct FitItem {
+    const windq_mat* W;
+    const float* s;
+    const uint8_t* mask;
+    float* err;
+    uint8_t* clip_idx;
+    float* ref_energy;
+    void* ws;
+    size_t ws_bytes;
+};
+
+static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, int64_t unit_rows, const float* clip_grid,
+                            int32_t K, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    int st = check_clip_grid(clip_grid, K);
+    if (st != WINDQ_OK) return st;
     FitScoreArgs A;
-    int st = make_geometry(W, chunk_w, unit_rows, &A.g);
-    if (st != WINDQ_OK) return st;
-    if (s == nullptr || err == nullptr || clip_idx == nullptr) return WINDQ_EINVAL;
-    st = check_clip_grid(clip_grid, K);
-    if (st != WINDQ_OK) return st;
-    if (ws == nullptr || ws_bytes < fit_score_ws_bytes(A.g, K) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
-    A.W = W->data;
-    A.s = s;
-    A.mask = mask;
-    A.mask_ld = W->cols / 8;
-    A.partial = static_cast<double*>(ws);
+    A.n = n;
     A.K = K;
     A.n_kpass = (K + FS_KB - 1) / FS_KB;
     A.inv_G = 1.0 / (double)chunk_w;
-    // tau keeps the short route's noise in the unit's 8-bit error at 1e-6 (one sigma):
-    // 1.2e-4 sqrt(tau / (G R_u)) = 1e-6.  Below tau = 1 every column takes the exact route.
-    const float t = 7e-5f * (float)chunk_w * (float)A.g.R_u;
-    A.tau = t < 1.0f ? 0.0f : t;
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid[k < K ? k : K - 1];
+    const bool masked = items[0].mask != nullptr;
+    int64_t tiles = 0, units = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const FitItem& it = items[i];
+        FitScoreMat& M = A.m[i];
+        if (it.W == nullptr) return WINDQ_EINVAL;
+        st = make_geometry(it.W, chunk_w, unit_rows, &M.g);
+        if (st != WINDQ_OK) return st;
+        if (it.s == nullptr || it.err == nullptr || it.clip_idx == nullptr) return WINDQ_EINVAL;
+        if (it.W->dtype != items[0].W->dtype || (it.mask != nullptr) != masked) return WINDQ_EINVAL;   // one kernel per launch
+        if (it.ws == nullptr || it.ws_bytes < fit_score_ws_bytes(M.g, K) || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
+        M.W = it.W->data;
+        M.s = it.s;
+        M.mask = it.mask;
+        M.mask_ld = it.W->cols / 8;
+        M.partial = static_cast<double*>(it.ws);
+        M.err = it.err;
+        M.clip_idx = it.clip_idx;
+        M.ref_energy = it.ref_energy;
+        // tau keeps the short route's noise in the unit's 8-bit error at 1e-6 (one sigma):
+        // 1.2e-4 sqrt(tau / (G R_u)) = 1e-6.  Below tau = 1 every column takes the exact route.
+        const float t = 7e-5f * (float)chunk_w * (float)M.g.R_u;
+        M.tau = t < 1.0f ? 0.0f : t;
+        A.tile_start[i] = tiles;
+        A.unit_start[i] = units;
+        tiles += M.g.n_tiles;
+        units += M.g.U;
+    }
+    for (int32_t i = n; i <= WINDQ_MAX_BATCH; ++i) {
+        A.tile_start[i] = tiles;
+        A.unit_start[i] = units;
+    }
+    for (int32_t i = n; i < WINDQ_MAX_BATCH; ++i) A.m[i] = A.m[0];
+    if (tiles > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const bool masked = mask != nullptr;
-    const size_t lds = fit_score_lds_bytes(W->dtype, chunk_w, masked);
-    const dim3 grid((unsigned)A.g.n_tiles);
+    const int32_t dtype = items[0].W->dtype;
+    const size_t lds = fit_score_lds_bytes(dtype, chunk_w, masked);
+    const dim3 grid((unsigned)tiles);
     auto launch = [&](auto kernel) -> int {
         const int e = ensure_lds(reinterpret_cast<const void*>(kernel), lds);
         if (e != WINDQ_OK) return e;
         hipLaunchKernelGGL(kernel, grid, dim3(FS_THREADS), lds, hs, A);
         return WINDQ_OK;
     };
-    if (W->dtype == WINDQ_BF16) st = masked ? launch(&fit_score_kernel<WINDQ_BF16, true>) : launch(&fit_score_kernel<WINDQ_BF16, false>);
+    if (dtype == WINDQ_BF16) st = masked ? launch(&fit_score_kernel<WINDQ_BF16, true>) : launch(&fit_score_kernel<WINDQ_BF16, false>);
     else st = masked ? launch(&fit_score_kernel<WINDQ_F32, true>) : launch(&fit_score_kernel<WINDQ_F32, false>);
     if (st != WINDQ_OK) return st;
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
-    hipLaunchKernelGGL(fit_score_finalize_kernel, dim3((unsigned)A.g.U), dim3(FIN_THREADS), 0, hs, A.partial,
-                       A.g.tiles_per_unit, K, err, clip_idx, ref_energy);
+    hipLaunchKernelGGL(fit_score_finalize_kernel, dim3((unsigned)units), dim3(FIN_THREADS), 0, hs, A);
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     return WINDQ_OK;
+}
+
+static int fit_score_impl(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, const uint8_t* mask,
+                          const float* clip_grid, int32_t K, float* err, uint8_t* clip_idx, float* ref_energy,
+                          void* ws, size_t ws_bytes, void* stream) {
+    if (W == nullptr) return WINDQ_EINVAL;
+    const FitItem it = {W, s, mask, err, clip_idx, ref_energy, ws, ws_bytes};
+    return fit_score_launch(&it, 1, chunk_w, unit_rows, clip_grid, K, stream);
 }
 
 extern "C" int windq_fit_score_all_bits(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
@@ -631,4 +698,14 @@ extern "C" int windq_fit_score_all_bits_prot(const windq_mat* W, const float* s,
                                              void* stream) {
     if (mask == nullptr) return WINDQ_EINVAL;
     return fit_score_impl(W, s, chunk_w, unit_rows, mask, clip_grid, K, err, clip_idx, ref_energy, ws, ws_bytes, stream);
+}
+
+extern "C" int windq_fit_score_all_bits_batch(const windq_fit_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                              const float* clip_grid, int32_t K, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    FitItem its[WINDQ_MAX_BATCH];
+    for (int32_t i = 0; i < n; ++i)
+        its[i] = {items[i].W, items[i].s, nullptr, items[i].err, items[i].clip_idx, items[i].ref_energy, items[i].ws,
+                  items[i].ws_bytes};
+    return fit_score_launch(its, n, chunk_w, unit_rows, clip_grid, K, stream);
 }

@@ -137,6 +137,21 @@ int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int3
                              void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * windq_unit_features for up to WINDQ_MAX_BATCH matrices with one launch per pass instead of
+ * one per pass and matrix (see windq_fit_score_all_bits_batch for the contract: item i is one
+ * per-matrix call, results are the same bit for bit).
+ */
+typedef struct windq_feat_item {
+    const windq_mat* W;     /* HOST descriptor of a device matrix */
+    const float* s;         /* [cols] */
+    float* feat;            /* [U][8] */
+    void* ws;
+    size_t ws_bytes;
+} windq_feat_item;
+int windq_unit_features_batch(const windq_feat_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                              void* stream);
+
+/*
  * windq_fit_score_all_bits for up to WINDQ_MAX_BATCH matrices in ONE launch (plus one finalize
  * launch): the matrices of a decoder block are small against this GPU, and a launch per matrix
  * leaves it partly empty at every start and end.  Item i is one per-matrix call: the same

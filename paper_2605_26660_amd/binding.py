@@ -25,6 +25,7 @@ EXPORTS = (
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
     "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan", "windq_fit_score_all_bits_batch",
+    "windq_unit_features_batch",
 )
 
 
@@ -44,6 +45,11 @@ class windq_fit_item(ctypes.Structure):
     _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("err", ctypes.c_void_p),
                 ("clip_idx", ctypes.c_void_p), ("ref_energy", ctypes.c_void_p), ("ws", ctypes.c_void_p),
                 ("ws_bytes", ctypes.c_size_t)]
+
+
+class windq_feat_item(ctypes.Structure):
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("feat", ctypes.c_void_p),
+                ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
 
 _lib = None
@@ -85,13 +91,14 @@ def load(path: str | None = None):
     lib.windq_dequant_plan.argtypes = [pm, vp, i32, i64, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, sz, vp]
     lib.windq_refine_plan.argtypes = [pm, vp, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp, vp, sz, vp]
     lib.windq_fit_score_all_bits_batch.argtypes = [c.POINTER(windq_fit_item), i32, i32, i64, vp, i32, vp]
+    lib.windq_unit_features_batch.argtypes = [c.POINTER(windq_feat_item), i32, i32, i64, vp]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
                  "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode",
                  "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency",
                  "windq_heuristic_plan", "windq_fallback_promote", "windq_dequant_plan",
-                 "windq_refine_plan", "windq_fit_score_all_bits_batch"):
+                 "windq_refine_plan", "windq_fit_score_all_bits_batch", "windq_unit_features_batch"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -176,6 +183,26 @@ def windq_unit_features(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_row
     _check(load().windq_unit_features(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, feat.data_ptr(),
                                       ws.data_ptr(), ws.numel(), _stream()), "windq_unit_features")
     return feat
+
+
+def windq_unit_features_batch(Ws, ss, chunk_w: int, unit_rows: int, wss=None, outs=None):
+    """windq_unit_features for several matrices (lists of equal length, at most MAX_BATCH), one launch per pass.
+    -> list of feat tensors [U x 8]."""
+    n = len(Ws)
+    assert len(ss) == n and (wss is None or len(wss) == n) and (outs is None or len(outs) == n)
+    _require_cuda(*Ws, *ss)
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_feat_item * max(n, 1))()
+    res, keep = [], []
+    for i, (W, s) in enumerate(zip(Ws, ss)):
+        U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+        feat = torch.empty(U, N_FEAT, dtype=torch.float32, device=W.device) if outs is None else outs[i]
+        ws = _workspace(CALL_UNIT_FEATURES, W, chunk_w, unit_rows, 1, None if wss is None else wss[i])
+        keep.append(ws)
+        items[i] = windq_feat_item(ctypes.pointer(mats[i]), s.data_ptr(), feat.data_ptr(), ws.data_ptr(), ws.numel())
+        res.append(feat)
+    _check(load().windq_unit_features_batch(items, n, chunk_w, unit_rows, _stream()), "windq_unit_features_batch")
+    return res
 
 
 def windq_fit_score_all_bits(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor,

@@ -51,6 +51,23 @@ struct FeatArgs {
     uint64_t rank;      // ceil(0.99 n), 1-based
 };
 
+// A launch covers up to WINDQ_MAX_BATCH matrices (one chunk width, one element type): the
+// workgroups of the pass kernels, the units of the finish kernel and the counters the init
+// kernel clears are numbered one matrix after the other.
+struct FeatBatch {
+    int32_t n;
+    int64_t block_start[WINDQ_MAX_BATCH + 1];
+    int64_t unit_start[WINDQ_MAX_BATCH + 1];
+    int64_t init_start[WINDQ_MAX_BATCH + 1];     // in workgroups of 256 counters
+    FeatArgs m[WINDQ_MAX_BATCH];
+};
+
+__device__ __forceinline__ int feat_batch_index(const int64_t (&start)[WINDQ_MAX_BATCH + 1], int32_t n, int64_t idx) {
+    int mi = 0;
+    while (mi + 1 < n && idx >= start[mi + 1]) ++mi;
+    return mi;
+}
+
 template <int DT>
 __device__ __forceinline__ void load8(const void* __restrict__ data, int64_t off, float (&w)[8]) {
     if (DT == WINDQ_BF16) {
@@ -90,9 +107,12 @@ __device__ __host__ constexpr int level_bits(int level) {
 template <int DT>
 __device__ __host__ constexpr int n_levels() { return DT == WINDQ_BF16 ? 2 : 3; }
 
-__global__ __launch_bounds__(256) void feat_init_kernel(uint32_t* __restrict__ hist, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) hist[i] = 0;
+__global__ __launch_bounds__(256) void feat_init_kernel(const FeatBatch B) {
+    const int mi = feat_batch_index(B.init_start, B.n, blockIdx.x);
+    const FeatArgs& A = B.m[mi];
+    const int64_t n = (int64_t)3 * A.g.U * FEAT_BINS;
+    const int64_t i = ((int64_t)blockIdx.x - B.init_start[mi]) * 256 + threadIdx.x;
+    if (i < n) A.hist[i] = 0;
 }
 
 // Block-wide sum of a per-thread double in a fixed order (lanes by butterfly, wavefronts in order).
@@ -140,15 +160,18 @@ constexpr int FEAT_COPIES = 2;
 __host__ __device__ constexpr int feat_cstride(int mode) { return (mode == 0 ? FEAT_BINS : 32) + 17; }   // odd skew: copies of a bin sit in different banks
 __host__ __device__ constexpr size_t feat_lds_bytes(int mode) { return (size_t)feat_cstride(mode) * FEAT_COPIES * sizeof(uint32_t); }
 template <int MODE>
-__global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatArgs A, const uint32_t sparse_key) {
+__global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatBatch B, const uint32_t sparse_key) {
+    const int mi = feat_batch_index(B.block_start, B.n, blockIdx.x);
+    const FeatArgs& A = B.m[mi];
+    const int64_t wg = (int64_t)blockIdx.x - B.block_start[mi];
     constexpr int CSTRIDE = feat_cstride(MODE);
     extern __shared__ uint32_t lhist[];                          // [FEAT_COPIES][CSTRIDE]
     __shared__ double red[FT_WAVES];
     __shared__ uint32_t sh_part[FT_THREADS];
     __shared__ uint32_t sh_out[4];
     constexpr int NB = MODE == 0 ? FEAT_BINS : 32;
-    const int64_t u = blockIdx.x / A.bpu;
-    const int64_t blk = blockIdx.x - u * A.bpu;
+    const int64_t u = wg / A.bpu;
+    const int64_t blk = wg - u * A.bpu;
     const int32_t G = A.g.chunk_w;
     const int32_t pieces = G >> 3;
     const int64_t rb = u / A.g.n_chunks;
@@ -252,13 +275,16 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatAr
 //   MODE 1: histogram(s) of digit `level` under the unit's prefix.
 //   MODE 2: fp32 only: count 2|w| > P99.
 template <int DT, int MODE>
-__global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatArgs A, const int32_t level) {
+__global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatBatch B, const int32_t level) {
     __shared__ uint32_t lhist[FEAT_BINS];
     __shared__ double red[FT_WAVES];
     __shared__ uint32_t sh_part[FT_THREADS];
     __shared__ uint32_t sh_out[4];
-    const int64_t u = blockIdx.x / A.bpu;
-    const int64_t blk = blockIdx.x - u * A.bpu;
+    const int mi = feat_batch_index(B.block_start, B.n, blockIdx.x);
+    const FeatArgs& A = B.m[mi];
+    const int64_t wg = (int64_t)blockIdx.x - B.block_start[mi];
+    const int64_t u = wg / A.bpu;
+    const int64_t blk = wg - u * A.bpu;
     const int32_t G = A.g.chunk_w;
     const int32_t pieces = G >> 3;
     const int64_t rb = u / A.g.n_chunks;
@@ -390,12 +416,14 @@ __device__ __forceinline__ void block_sum_n(double (&v)[N], double* red) {
 // first round of block moments, the activation scales and the refined counters travel
 // together with the first-digit histogram.
 template <int DT>
-__global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatArgs A) {
+__global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch B) {
     __shared__ double red[6 * FT_WAVES];
     __shared__ uint32_t sh_part[FT_THREADS];
     __shared__ uint32_t sh_out[4];
     __shared__ float smax_sh[FT_THREADS];
-    const int64_t u = blockIdx.x;
+    const int mi = feat_batch_index(B.unit_start, B.n, blockIdx.x);
+    const FeatArgs& A = B.m[mi];
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
     const int32_t G = A.g.chunk_w;
     const float* __restrict__ sc = A.s + (u % A.g.n_chunks) * G;
     const int tid = threadIdx.x;
@@ -471,25 +499,25 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatArgs 
 }
 
 template <int DT>
-static int launch_features(const FeatArgs& A, hipStream_t hs) {
-    const dim3 blocks((unsigned)(A.g.U * A.bpu));
-    const int64_t n_init = (int64_t)3 * A.g.U * FEAT_BINS;
-    hipLaunchKernelGGL(feat_init_kernel, dim3((unsigned)((n_init + 255) / 256)), dim3(256), 0, hs, A.hist, n_init);
+static int launch_features(const FeatBatch& B, int64_t blocks_total, int64_t units_total, int64_t init_total,
+                           hipStream_t hs) {
+    const dim3 blocks((unsigned)blocks_total);
+    hipLaunchKernelGGL(feat_init_kernel, dim3((unsigned)init_total), dim3(256), 0, hs, B);
     if (DT == WINDQ_BF16) {
         // |w| < 1e-6 on bf16 keys: key < key of the smallest bf16 that is >= 1e-6
         uint32_t tb;
-        memcpy(&tb, &A.sparse_thr, sizeof(tb));
+        memcpy(&tb, &B.m[0].sparse_thr, sizeof(tb));
         const uint32_t sparse_key = (tb >> 16) + ((tb & 0xffffu) != 0 ? 1u : 0u);
         if (ensure_lds(reinterpret_cast<const void*>(&feat_pass_bf16_kernel<0>), feat_lds_bytes(0)) != WINDQ_OK) return WINDQ_EHIP;
-        hipLaunchKernelGGL((feat_pass_bf16_kernel<0>), blocks, dim3(FT_THREADS), feat_lds_bytes(0), hs, A, sparse_key);
-        hipLaunchKernelGGL((feat_pass_bf16_kernel<1>), blocks, dim3(FT_THREADS), feat_lds_bytes(1), hs, A, sparse_key);
+        hipLaunchKernelGGL((feat_pass_bf16_kernel<0>), blocks, dim3(FT_THREADS), feat_lds_bytes(0), hs, B, sparse_key);
+        hipLaunchKernelGGL((feat_pass_bf16_kernel<1>), blocks, dim3(FT_THREADS), feat_lds_bytes(1), hs, B, sparse_key);
     } else {
-        hipLaunchKernelGGL((feat_pass_kernel<DT, 0>), blocks, dim3(FT_THREADS), 0, hs, A, 0);
-        hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, A, 1);
-        hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, A, 2);
-        hipLaunchKernelGGL((feat_pass_kernel<DT, 2>), blocks, dim3(FT_THREADS), 0, hs, A, 0);
+        hipLaunchKernelGGL((feat_pass_kernel<DT, 0>), blocks, dim3(FT_THREADS), 0, hs, B, 0);
+        hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, B, 1);
+        hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, B, 2);
+        hipLaunchKernelGGL((feat_pass_kernel<DT, 2>), blocks, dim3(FT_THREADS), 0, hs, B, 0);
     }
-    hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)A.g.U), dim3(FT_THREADS), 0, hs, A);
+    hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)units_total), dim3(FT_THREADS), 0, hs, B);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
@@ -497,29 +525,62 @@ static int launch_features(const FeatArgs& A, hipStream_t hs) {
 
 using namespace windq;
 
-extern "C" int windq_unit_features(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, float* feat,
-                                   void* ws, size_t ws_bytes, void* stream) {
-    FeatArgs A;
-    const int st = make_geometry(W, chunk_w, unit_rows, &A.g);
-    if (st != WINDQ_OK) return st;
-    if (s == nullptr || feat == nullptr) return WINDQ_EINVAL;
-    const FeatLayout L = features_layout(A.g);
-    if (ws == nullptr || ws_bytes < L.total || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
-    if ((uint64_t)A.g.R_u * (uint64_t)chunk_w > (uint64_t)0xffffffffu) return WINDQ_ESHAPE;   // u32 bin counts
-    if (L.n_blocks > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
-    char* base = static_cast<char*>(ws);
-    A.W = W->data;
-    A.s = s;
-    A.feat = feat;
-    A.moments = reinterpret_cast<double*>(base + L.moments);
-    A.above = reinterpret_cast<uint32_t*>(base + L.above);
-    A.hist = reinterpret_cast<uint32_t*>(base + L.hist);
-    A.bpu = L.bpu;
+static int unit_features_launch(const windq_feat_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    FeatBatch B;
+    B.n = n;
+    int64_t blocks = 0, units = 0, inits = 0;
     float thr = (float)1e-6;
     if ((double)thr < 1e-6) thr = nextafterf(thr, INFINITY);
-    A.sparse_thr = thr;
-    const uint64_t n = (uint64_t)A.g.R_u * (uint64_t)chunk_w;
-    A.rank = (99 * n + 99) / 100;
+    for (int32_t i = 0; i < n; ++i) {
+        const windq_feat_item& it = items[i];
+        FeatArgs& A = B.m[i];
+        if (it.W == nullptr) return WINDQ_EINVAL;
+        const int st = make_geometry(it.W, chunk_w, unit_rows, &A.g);
+        if (st != WINDQ_OK) return st;
+        if (it.s == nullptr || it.feat == nullptr) return WINDQ_EINVAL;
+        if (it.W->dtype != items[0].W->dtype) return WINDQ_EINVAL;        // one kernel per launch
+        const FeatLayout L = features_layout(A.g);
+        if (it.ws == nullptr || it.ws_bytes < L.total || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
+        if ((uint64_t)A.g.R_u * (uint64_t)chunk_w > (uint64_t)0xffffffffu) return WINDQ_ESHAPE;   // u32 bin counts
+        char* base = static_cast<char*>(it.ws);
+        A.W = it.W->data;
+        A.s = it.s;
+        A.feat = it.feat;
+        A.moments = reinterpret_cast<double*>(base + L.moments);
+        A.above = reinterpret_cast<uint32_t*>(base + L.above);
+        A.hist = reinterpret_cast<uint32_t*>(base + L.hist);
+        A.bpu = L.bpu;
+        A.sparse_thr = thr;
+        const uint64_t nw = (uint64_t)A.g.R_u * (uint64_t)chunk_w;
+        A.rank = (99 * nw + 99) / 100;
+        B.block_start[i] = blocks;
+        B.unit_start[i] = units;
+        B.init_start[i] = inits;
+        blocks += L.n_blocks;
+        units += A.g.U;
+        inits += ((int64_t)3 * A.g.U * FEAT_BINS + 255) / 256;
+    }
+    for (int32_t i = n; i <= WINDQ_MAX_BATCH; ++i) {
+        B.block_start[i] = blocks;
+        B.unit_start[i] = units;
+        B.init_start[i] = inits;
+    }
+    for (int32_t i = n; i < WINDQ_MAX_BATCH; ++i) B.m[i] = B.m[0];
+    if (blocks > (int64_t)0x7fffffff || inits > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    return W->dtype == WINDQ_BF16 ? launch_features<WINDQ_BF16>(A, hs) : launch_features<WINDQ_F32>(A, hs);
+    return items[0].W->dtype == WINDQ_BF16 ? launch_features<WINDQ_BF16>(B, blocks, units, inits, hs)
+                                           : launch_features<WINDQ_F32>(B, blocks, units, inits, hs);
+}
+
+extern "C" int windq_unit_features(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, float* feat,
+                                   void* ws, size_t ws_bytes, void* stream) {
+    if (W == nullptr) return WINDQ_EINVAL;
+    const windq_feat_item it = {W, s, feat, ws, ws_bytes};
+    return unit_features_launch(&it, 1, chunk_w, unit_rows, stream);
+}
+
+extern "C" int windq_unit_features_batch(const windq_feat_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                         void* stream) {
+    return unit_features_launch(items, n, chunk_w, unit_rows, stream);
 }

@@ -60,3 +60,32 @@ def test_fit_score_batch_rejects_bad_batches(windq):
     with pytest.raises(windq.WindqError) as e:
         windq.windq_fit_score_all_bits_batch(Ws[:2], ss[:2], 128, 0, cg, wss=small_ws)
     assert e.value.status == windq.WINDQ_EWORKSPACE
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("G,unit_rows,shapes", [
+    (128, 0, [(256, 512), (1024, 256), (64, 128), (200, 384), (2048, 128), (192, 640), (512, 512)]),
+    (64, 64, [(128, 256), (64, 64), (320, 192)]),
+    (8, 0, [(16, 24), (8, 8)]),
+    (256, 100, [(300, 256)]),
+])
+def test_unit_features_batch_equals_single_calls(windq, dtype, G, unit_rows, shapes):
+    Ws, ss = block(dtype, shapes, 151)
+    singles = [windq.windq_unit_features(W, s, G, unit_rows) for W, s in zip(Ws, ss)]
+    batch = windq.windq_unit_features_batch(Ws, ss, G, unit_rows)
+    torch.cuda.synchronize()
+    for one, got in zip(singles, batch):
+        assert same_bits(one, got)
+
+
+def test_unit_features_batch_rejects_bad_batches(windq):
+    Ws, ss = block(torch.bfloat16, [(64, 128)] * 9, 9)
+    for bad in (lambda: windq.windq_unit_features_batch(Ws, ss, 128, 0),
+                lambda: windq.windq_unit_features_batch([], [], 128, 0),
+                lambda: windq.windq_unit_features_batch([Ws[0], Ws[1].float()], ss[:2], 128, 0)):
+        with pytest.raises(windq.WindqError) as e:
+            bad()
+        assert e.value.status == windq.WINDQ_EINVAL
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_unit_features_batch(Ws[:2], ss[:2], 128, 0, wss=[torch.empty(64, dtype=torch.uint8, device=DEV)] * 2)
+    assert e.value.status == windq.WINDQ_EWORKSPACE

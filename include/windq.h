@@ -208,6 +208,26 @@ int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t unit_rows,
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * windq_apply_plan for up to WINDQ_MAX_BATCH matrices in one launch (see
+ * windq_fit_score_all_bits_batch for the contract: item i is one per-matrix call with its own
+ * plan, code stream and outputs; results are the same bit for bit).
+ */
+typedef struct windq_apply_item {
+    const windq_mat* W;        /* HOST descriptor of a device matrix */
+    const uint8_t* action;     /* [U] */
+    const uint8_t* clip_idx;   /* [U][4] or NULL */
+    const int64_t* code_off;   /* [U+1] */
+    uint8_t* codes;
+    size_t codes_bytes;
+    float* scale;              /* [U*R_u] */
+    float* offset;             /* [U*R_u] */
+    void* ws;
+    size_t ws_bytes;
+} windq_apply_item;
+int windq_apply_plan_batch(const windq_apply_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                           const float* clip_grid /*HOST [K]*/, int32_t K, void* stream);
+
+/*
  * Effective-bit accounting of a plan (Eq. 5), HOST only, exact integers:
  *   B_i = 16 n_i for skip, else b_i (n_i - n_i^p) + 8 n_i^p,
  * in centibits (bits x 100: 1600/800/400/300/200/158/100) so that 1.58 stays integral.

@@ -25,7 +25,7 @@ EXPORTS = (
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
     "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan", "windq_fit_score_all_bits_batch",
-    "windq_unit_features_batch",
+    "windq_unit_features_batch", "windq_apply_plan_batch",
 )
 
 
@@ -50,6 +50,13 @@ class windq_fit_item(ctypes.Structure):
 class windq_feat_item(ctypes.Structure):
     _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("feat", ctypes.c_void_p),
                 ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
+
+
+class windq_apply_item(ctypes.Structure):
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("action", ctypes.c_void_p), ("clip_idx", ctypes.c_void_p),
+                ("code_off", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("codes_bytes", ctypes.c_size_t),
+                ("scale", ctypes.c_void_p), ("offset", ctypes.c_void_p), ("ws", ctypes.c_void_p),
+                ("ws_bytes", ctypes.c_size_t)]
 
 
 _lib = None
@@ -92,13 +99,14 @@ def load(path: str | None = None):
     lib.windq_refine_plan.argtypes = [pm, vp, i32, i64, vp, vp, vp, vp, i32, i32, vp, vp, sz, vp, vp, vp, vp, sz, vp]
     lib.windq_fit_score_all_bits_batch.argtypes = [c.POINTER(windq_fit_item), i32, i32, i64, vp, i32, vp]
     lib.windq_unit_features_batch.argtypes = [c.POINTER(windq_feat_item), i32, i32, i64, vp]
+    lib.windq_apply_plan_batch.argtypes = [c.POINTER(windq_apply_item), i32, i32, i64, vp, i32, vp]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
                  "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode",
                  "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency",
                  "windq_heuristic_plan", "windq_fallback_promote", "windq_dequant_plan",
-                 "windq_refine_plan", "windq_fit_score_all_bits_batch", "windq_unit_features_batch"):
+                 "windq_refine_plan", "windq_fit_score_all_bits_batch", "windq_unit_features_batch", "windq_apply_plan_batch"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -302,6 +310,29 @@ def windq_apply_plan(W: torch.Tensor, chunk_w: int, unit_rows: int, action: torc
         _check(load().windq_apply_plan_prot(ctypes.byref(m), chunk_w, unit_rows, mask.data_ptr(), *tail),
                "windq_apply_plan_prot")
     return codes, scale, offset
+
+
+def windq_apply_plan_batch(Ws, chunk_w: int, unit_rows: int, actions, clip_idxs, clip_grid, code_offs, codes, outs, wss=None):
+    """windq_apply_plan for several matrices (lists of equal length, at most MAX_BATCH) in one launch.
+    actions, clip_idxs (entries may be None), code_offs, codes: device tensors per matrix; outs: (scale, offset) per
+    matrix.  clip_grid host f32 or None.  Everything is caller-allocated."""
+    n = len(Ws)
+    assert all(len(x) == n for x in (actions, clip_idxs, code_offs, codes, outs)) and (wss is None or len(wss) == n)
+    _require_cuda(*Ws, *actions, *code_offs, *codes)
+    K = 0 if clip_grid is None else clip_grid.numel()
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_apply_item * max(n, 1))()
+    keep = []
+    for i, W in enumerate(Ws):
+        ws = _workspace(CALL_APPLY_PLAN, W, chunk_w, unit_rows, 1, None if wss is None else wss[i])
+        keep.append(ws)
+        ci = clip_idxs[i]
+        items[i] = windq_apply_item(ctypes.pointer(mats[i]), actions[i].data_ptr(), None if ci is None else ci.data_ptr(),
+                                    code_offs[i].data_ptr(), codes[i].data_ptr(), codes[i].numel(), outs[i][0].data_ptr(),
+                                    outs[i][1].data_ptr(), ws.data_ptr(), ws.numel())
+    _check(load().windq_apply_plan_batch(items, n, chunk_w, unit_rows, None if clip_grid is None else clip_grid.data_ptr(),
+                                         K, _stream()), "windq_apply_plan_batch")
+    return [(codes[i], outs[i][0], outs[i][1]) for i in range(n)]
 
 
 def windq_effective_bits(action: torch.Tensor, n_unit: torch.Tensor, n_prot: torch.Tensor | None = None):

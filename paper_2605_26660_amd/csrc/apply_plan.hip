@@ -41,14 +41,30 @@ struct ApplyArgs {
     float* scale;
     float* offset;
     Geometry g;
+};
+
+// A launch covers up to WINDQ_MAX_BATCH matrices (one chunk width, one element type, all with
+// or all without a mask): their tiles are numbered one matrix after the other.
+struct ApplyBatch {
+    int32_t n;
     int32_t K;
+    int64_t tile_start[WINDQ_MAX_BATCH + 1];
+    ApplyArgs m[WINDQ_MAX_BATCH];
     ClipGrid grid;
 };
 
+__device__ __forceinline__ int apply_batch_index(const ApplyBatch& B, int64_t tile) {
+    int mi = 0;
+    while (mi + 1 < B.n && tile >= B.tile_start[mi + 1]) ++mi;
+    return mi;
+}
+
 template <int DT>
-__global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyArgs A) {
+__global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyBatch B) {
     extern __shared__ char tile[];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = apply_batch_index(B, blockIdx.x);
+    const ApplyArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
     const int lane = threadIdx.x;
     const bool valid = lane < tc.nrows;
@@ -80,8 +96,8 @@ __global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyArgs 
         float p = 1.0f;
         if (a <= 4 && A.clip_idx != nullptr) {
             int k = A.clip_idx[tc.u * 4 + (a - 1)];
-            k = k < A.K ? k : A.K - 1;
-            p = A.grid.p[k];
+            k = k < B.K ? k : B.K - 1;
+            p = B.grid.p[k];
         }
         uint8_t* dst = reinterpret_cast<uint8_t*>(wrow);   // packed in place, behind the read position
         const uint8_t* __restrict__ mrow =
@@ -468,10 +484,12 @@ __device__ __forceinline__ TileCoord tile_coord32(const Geometry& g, uint32_t ti
 }
 
 template <int LPR, bool MASKED>
-__global__ __launch_bounds__(APS_THREADS, MASKED ? 6 : 7) void apply_plan_split_kernel(const ApplyArgs A) {
+__global__ __launch_bounds__(APS_THREADS, MASKED ? 6 : 7) void apply_plan_split_kernel(const ApplyBatch B) {
     constexpr int G = 8 * LPR, NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
     __shared__ __attribute__((aligned(16))) uint8_t trits[TILE_ROWS * G];
-    const TileCoord tc = tile_coord32(A.g, blockIdx.x);
+    const int mi = apply_batch_index(B, blockIdx.x);
+    const ApplyArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord32(A.g, (uint32_t)((int64_t)blockIdx.x - B.tile_start[mi]));
     const SplitLane<LPR> L(threadIdx.x);
 
     int a = A.action[tc.u];
@@ -507,8 +525,8 @@ __global__ __launch_bounds__(APS_THREADS, MASKED ? 6 : 7) void apply_plan_split_
     float p = 1.0f;
     if (a <= 4 && A.clip_idx != nullptr) {
         int k = A.clip_idx[tc.u * 4 + (a - 1)];
-        k = k < A.K ? k : A.K - 1;
-        p = A.grid.p[k];
+        k = k < B.K ? k : B.K - 1;
+        p = B.grid.p[k];
     }
     uint8_t* __restrict__ out = A.codes + base + tc.lrow0 * bpg;   // the tile's rows, bpg bytes each
     switch (a) {
@@ -528,62 +546,102 @@ __global__ __launch_bounds__(APS_THREADS, MASKED ? 6 : 7) void apply_plan_split_
 
 using namespace windq;
 
-static int apply_plan_impl(const windq_mat* W, int32_t chunk_w, int64_t unit_rows, const uint8_t* mask,
-                           const uint8_t* action, const uint8_t* clip_idx, const float* clip_grid, int32_t K,
-                           const int64_t* code_off, uint8_t* codes, size_t codes_bytes, float* scale, float* offset,
-                           void* ws, size_t ws_bytes, void* stream) {
-    ApplyArgs A;
-    int st = make_geometry(W, chunk_w, unit_rows, &A.g);
-    if (st != WINDQ_OK) return st;
-    if (action == nullptr || code_off == nullptr || scale == nullptr || offset == nullptr) return WINDQ_EINVAL;
-    if (codes == nullptr && codes_bytes != 0) return WINDQ_EINVAL;
-    if (codes != nullptr && !aligned(codes, 16)) return WINDQ_EINVAL;
-    if (!aligned(code_off, 8)) return WINDQ_EINVAL;
-    if (clip_idx != nullptr || clip_grid != nullptr) {
+// One matrix of a launch as the entry points see it.
+struct ApplyItem {
+    const windq_mat* W;
+    const uint8_t* mask;
+    const uint8_t* action;
+    const uint8_t* clip_idx;
+    const int64_t* code_off;
+    uint8_t* codes;
+    size_t codes_bytes;
+    float* scale;
+    float* offset;
+    void* ws;
+    size_t ws_bytes;
+};
+
+static int apply_plan_launch(const ApplyItem* items, int32_t n, int32_t chunk_w, int64_t unit_rows, const float* clip_grid,
+                             int32_t K, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    ApplyBatch B;
+    B.n = n;
+    bool any_idx = false;
+    for (int32_t i = 0; i < n; ++i) any_idx = any_idx || items[i].clip_idx != nullptr;
+    int st;
+    if (any_idx || clip_grid != nullptr) {
         st = check_clip_grid(clip_grid, K);
         if (st != WINDQ_OK) return st;
     } else {
         K = 1;
     }
-    if (ws == nullptr || ws_bytes < apply_ws_bytes(A.g) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
-    A.W = W->data;
-    A.mask = mask;
-    A.mask_ld = W->cols / 8;
-    A.action = action;
-    A.clip_idx = clip_grid != nullptr ? clip_idx : nullptr;
-    A.code_off = code_off;
-    A.codes = codes;
-    A.codes_bytes = (int64_t)codes_bytes;
-    A.scale = scale;
-    A.offset = offset;
-    A.K = K;
-    for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid != nullptr ? clip_grid[k < K ? k : K - 1] : 1.0f;
+    B.K = K;
+    for (int k = 0; k < WINDQ_MAX_CLIP; ++k) B.grid.p[k] = clip_grid != nullptr ? clip_grid[k < K ? k : K - 1] : 1.0f;
+    const bool masked = items[0].mask != nullptr;
+    int64_t tiles = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const ApplyItem& it = items[i];
+        ApplyArgs& A = B.m[i];
+        if (it.W == nullptr) return WINDQ_EINVAL;
+        st = make_geometry(it.W, chunk_w, unit_rows, &A.g);
+        if (st != WINDQ_OK) return st;
+        if (it.action == nullptr || it.code_off == nullptr || it.scale == nullptr || it.offset == nullptr) return WINDQ_EINVAL;
+        if (it.codes == nullptr && it.codes_bytes != 0) return WINDQ_EINVAL;
+        if (it.codes != nullptr && !aligned(it.codes, 16)) return WINDQ_EINVAL;
+        if (!aligned(it.code_off, 8)) return WINDQ_EINVAL;
+        if (it.W->dtype != items[0].W->dtype || (it.mask != nullptr) != masked) return WINDQ_EINVAL;   // one kernel per launch
+        if (it.ws == nullptr || it.ws_bytes < apply_ws_bytes(A.g) || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
+        A.W = it.W->data;
+        A.mask = it.mask;
+        A.mask_ld = it.W->cols / 8;
+        A.action = it.action;
+        A.clip_idx = clip_grid != nullptr ? it.clip_idx : nullptr;
+        A.code_off = it.code_off;
+        A.codes = it.codes;
+        A.codes_bytes = (int64_t)it.codes_bytes;
+        A.scale = it.scale;
+        A.offset = it.offset;
+        B.tile_start[i] = tiles;
+        tiles += A.g.n_tiles;
+    }
+    for (int32_t i = n; i <= WINDQ_MAX_BATCH; ++i) B.tile_start[i] = tiles;
+    for (int32_t i = n; i < WINDQ_MAX_BATCH; ++i) B.m[i] = B.m[0];
+    if (tiles > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w);
-    const dim3 grid((unsigned)A.g.n_tiles);
-    const bool fast = W->dtype == WINDQ_BF16;
-    const bool masked = mask != nullptr;
+    const int32_t dtype = items[0].W->dtype;
+    const size_t lds = raw_tile_lds_bytes(dtype, chunk_w);
+    const dim3 grid((unsigned)tiles);
+    const bool fast = dtype == WINDQ_BF16;
     auto launch_split = [&](auto plain, auto prot) {
-        if (masked) hipLaunchKernelGGL(prot, grid, dim3(APS_THREADS), 0, hs, A);
-        else hipLaunchKernelGGL(plain, grid, dim3(APS_THREADS), 0, hs, A);
+        if (masked) hipLaunchKernelGGL(prot, grid, dim3(APS_THREADS), 0, hs, B);
+        else hipLaunchKernelGGL(plain, grid, dim3(APS_THREADS), 0, hs, B);
     };
     if (fast && chunk_w == 128) {
         launch_split(&apply_plan_split_kernel<16, false>, &apply_plan_split_kernel<16, true>);
     } else if (fast && chunk_w == 64) {
         launch_split(&apply_plan_split_kernel<8, false>, &apply_plan_split_kernel<8, true>);
     } else if (fast && chunk_w == 32 && !masked) {      // (masked at this width: the general kernel below)
-        hipLaunchKernelGGL((apply_plan_split_kernel<4, false>), grid, dim3(APS_THREADS), 0, hs, A);
-    } else if (W->dtype == WINDQ_BF16) {
+        hipLaunchKernelGGL((apply_plan_split_kernel<4, false>), grid, dim3(APS_THREADS), 0, hs, B);
+    } else if (dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&apply_plan_kernel<WINDQ_BF16>), lds);
         if (st != WINDQ_OK) return st;
-        hipLaunchKernelGGL(apply_plan_kernel<WINDQ_BF16>, grid, dim3(AP_THREADS), lds, hs, A);
+        hipLaunchKernelGGL(apply_plan_kernel<WINDQ_BF16>, grid, dim3(AP_THREADS), lds, hs, B);
     } else {
         st = ensure_lds(reinterpret_cast<const void*>(&apply_plan_kernel<WINDQ_F32>), lds);
         if (st != WINDQ_OK) return st;
-        hipLaunchKernelGGL(apply_plan_kernel<WINDQ_F32>, grid, dim3(AP_THREADS), lds, hs, A);
+        hipLaunchKernelGGL(apply_plan_kernel<WINDQ_F32>, grid, dim3(AP_THREADS), lds, hs, B);
     }
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     return WINDQ_OK;
+}
+
+static int apply_plan_impl(const windq_mat* W, int32_t chunk_w, int64_t unit_rows, const uint8_t* mask,
+                           const uint8_t* action, const uint8_t* clip_idx, const float* clip_grid, int32_t K,
+                           const int64_t* code_off, uint8_t* codes, size_t codes_bytes, float* scale, float* offset,
+                           void* ws, size_t ws_bytes, void* stream) {
+    if (W == nullptr) return WINDQ_EINVAL;
+    const ApplyItem it = {W, mask, action, clip_idx, code_off, codes, codes_bytes, scale, offset, ws, ws_bytes};
+    return apply_plan_launch(&it, 1, chunk_w, unit_rows, clip_grid, K, stream);
 }
 
 extern "C" int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t unit_rows, const uint8_t* action,
@@ -601,4 +659,14 @@ extern "C" int windq_apply_plan_prot(const windq_mat* W, int32_t chunk_w, int64_
     if (mask == nullptr) return WINDQ_EINVAL;
     return apply_plan_impl(W, chunk_w, unit_rows, mask, action, clip_idx, clip_grid, K, code_off, codes, codes_bytes,
                            scale, offset, ws, ws_bytes, stream);
+}
+
+extern "C" int windq_apply_plan_batch(const windq_apply_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                      const float* clip_grid, int32_t K, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    ApplyItem its[WINDQ_MAX_BATCH];
+    for (int32_t i = 0; i < n; ++i)
+        its[i] = {items[i].W, nullptr, items[i].action, items[i].clip_idx, items[i].code_off, items[i].codes,
+                  items[i].codes_bytes, items[i].scale, items[i].offset, items[i].ws, items[i].ws_bytes};
+    return apply_plan_launch(its, n, chunk_w, unit_rows, clip_grid, K, stream);
 }

@@ -89,3 +89,46 @@ def test_unit_features_batch_rejects_bad_batches(windq):
     with pytest.raises(windq.WindqError) as e:
         windq.windq_unit_features_batch(Ws[:2], ss[:2], 128, 0, wss=[torch.empty(64, dtype=torch.uint8, device=DEV)] * 2)
     assert e.value.status == windq.WINDQ_EWORKSPACE
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("G,unit_rows,shapes", [
+    (128, 0, [(256, 512), (1024, 256), (64, 128), (200, 384), (2048, 128), (192, 640), (512, 512)]),
+    (64, 64, [(128, 256), (64, 64), (320, 192)]),
+    (32, 0, [(100, 96), (64, 32)]),
+    (40, 0, [(70, 120), (16, 40)]),
+])
+def test_apply_plan_batch_equals_single_calls(windq, dtype, G, unit_rows, shapes):
+    Ws, ss = block(dtype, shapes, 171)
+    K = 7
+    cg = synth.clip_grid(K)
+    actions, idxs, offs, singles, codes_b, outs_b = [], [], [], [], [], []
+    for i, (W, s) in enumerate(zip(Ws, ss)):
+        U, R_u = windq.n_units(W.shape[0], W.shape[1], G, unit_rows)
+        _, clip_idx, _ = windq.windq_fit_score_all_bits(W, s, G, unit_rows, cg)
+        action = ((torch.arange(U) + i) % 7).to(torch.uint8)
+        off = windq.windq_plan_layout(action, R_u, G)
+        actions.append(action.to(DEV)); idxs.append(clip_idx); offs.append(off.to(DEV))
+        singles.append(windq.windq_apply_plan(W, G, unit_rows, actions[-1], clip_idx, cg, offs[-1]))
+        codes_b.append(torch.full((max(int(off[-1]), 16),), 0xAB, dtype=torch.uint8, device=DEV))
+        outs_b.append((torch.full((U * R_u,), 7.0, device=DEV), torch.full((U * R_u,), 7.0, device=DEV)))
+    got = windq.windq_apply_plan_batch(Ws, G, unit_rows, actions, idxs, cg, offs, codes_b, outs_b)
+    torch.cuda.synchronize()
+    for one, b, off in zip(singles, got, offs):
+        total = int(off[-1])
+        assert same_bits(one[0][:total], b[0][:total]) and same_bits(one[1], b[1]) and same_bits(one[2], b[2])
+
+
+def test_apply_plan_batch_rejects_bad_batches(windq):
+    Ws, _ = block(torch.bfloat16, [(64, 128)] * 2, 11)
+    action = torch.ones(1, dtype=torch.uint8, device=DEV)
+    off = torch.tensor([0, 64 * 128], dtype=torch.int64, device=DEV)
+    codes = torch.zeros(64 * 128, dtype=torch.uint8, device=DEV)
+    out = (torch.zeros(64, device=DEV), torch.zeros(64, device=DEV))
+    args = lambda k: ([action] * k, [None] * k, None, [off] * k, [codes] * k, [out] * k)
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_apply_plan_batch([Ws[0]] * 9, 128, 0, *args(9))
+    assert e.value.status == windq.WINDQ_EINVAL
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_apply_plan_batch([Ws[0], Ws[1].float()], 128, 0, *args(2))
+    assert e.value.status == windq.WINDQ_EINVAL

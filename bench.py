@@ -95,18 +95,34 @@ class NoTimer:
         return fn()
 
 
-def run_step(wq, torch, cg, xs, mats, unit_rows, timer=NoTimer()):
+def run_step(wq, torch, cg, xs, mats, unit_rows, timer=NoTimer(), per_matrix=False):
+    """One pass of the whole hot path over the block.  By default the three per-matrix calls go through their
+    *_batch entry points (one launch per kernel over the block's seven matrices, the same results bit for bit);
+    per_matrix=True makes one call per matrix instead."""
     for x in xs.values():
         timer.time("calib_stats", lambda: wq.windq_calib_stats(x["X"], want_rms=False, ws=x["ws"], out=x["s"]))
+    if per_matrix:
+        for m in mats:
+            s = xs[m["spec"].x_key]["s"]
+            timer.time("unit_features", lambda: wq.windq_unit_features(m["W"], s, G, unit_rows, ws=m["ws"], out=m["feat"]))
+            timer.time("fit_score_all_bits", lambda: wq.windq_fit_score_all_bits(
+                m["W"], s, G, unit_rows, cg, ws=m["ws"], out=(m["err"], m["clip_idx"], m["ref"])))
+            timer.time("apply_plan", lambda: wq.windq_apply_plan(
+                m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"], ws=m["ws"],
+                out=(m["scale"], m["offset"])))
+    else:
+        Ws = [m["W"] for m in mats]
+        ss = [xs[m["spec"].x_key]["s"] for m in mats]
+        wss = [m["ws"] for m in mats]
+        timer.time("unit_features", lambda: wq.windq_unit_features_batch(
+            Ws, ss, G, unit_rows, wss=wss, outs=[m["feat"] for m in mats]))
+        timer.time("fit_score_all_bits", lambda: wq.windq_fit_score_all_bits_batch(
+            Ws, ss, G, unit_rows, cg, wss=wss, outs=[(m["err"], m["clip_idx"], m["ref"]) for m in mats]))
+        timer.time("apply_plan", lambda: wq.windq_apply_plan_batch(
+            Ws, G, unit_rows, [m["action_d"] for m in mats], [m["clip_idx"] for m in mats], cg,
+            [m["off_d"] for m in mats], [m["codes"] for m in mats], [(m["scale"], m["offset"]) for m in mats], wss=wss))
     total_cb = total_n = 0
     for m in mats:
-        s = xs[m["spec"].x_key]["s"]
-        timer.time("unit_features", lambda: wq.windq_unit_features(m["W"], s, G, unit_rows, ws=m["ws"], out=m["feat"]))
-        timer.time("fit_score_all_bits", lambda: wq.windq_fit_score_all_bits(
-            m["W"], s, G, unit_rows, cg, ws=m["ws"], out=(m["err"], m["clip_idx"], m["ref"])))
-        timer.time("apply_plan", lambda: wq.windq_apply_plan(
-            m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"], ws=m["ws"],
-            out=(m["scale"], m["offset"])))
         cb, n = wq.windq_effective_bits(m["action"], m["n_unit"])
         total_cb += cb
         total_n += n
@@ -225,6 +241,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--unit-rows", type=int, default=0, help="0 = the paper's units (all rows); 128 = 128 x G tiles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-matrix", action="store_true",
+                    help="one call per matrix (7 x 3 calls per step) instead of the *_batch entry points (3 calls per step)")
     ap.add_argument("--protect-ppm", type=int, default=30000,
                     help="also time the block under salient-weight protection at this rate (parts per million; 0 = skip)")
     ap.add_argument("--clip-sweep", action="store_true",
@@ -259,13 +277,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
-        run_step(wq, torch, cg, xs, mats, args.unit_rows)
+        run_step(wq, torch, cg, xs, mats, args.unit_rows, per_matrix=args.per_matrix)
     torch.cuda.synchronize()
     # timed region: K whole steps; only the dominant call carries events (for the roofline)
     fit_timer = CallTimer(torch, only=("fit_score_all_bits",))
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        total_cb, total_n = run_step(wq, torch, cg, xs, mats, args.unit_rows, fit_timer)
+        total_cb, total_n = run_step(wq, torch, cg, xs, mats, args.unit_rows, fit_timer, per_matrix=args.per_matrix)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -273,7 +291,7 @@ def main():
     # so this pass does not count toward `value`)
     timer = CallTimer(torch)
     for _ in range(args.steps):
-        run_step(wq, torch, cg, xs, mats, args.unit_rows, timer)
+        run_step(wq, torch, cg, xs, mats, args.unit_rows, timer, per_matrix=args.per_matrix)
     torch.cuda.synchronize()
     n_act = sum(x["X"].numel() for x in xs.values())
     code_bytes = sum(int(m["off"][-1]) + 8 * m["U"] * m["R_u"] for m in mats)      # codes + scale/offset written
@@ -294,6 +312,7 @@ def main():
     fit_ms = sum(fit_timer.ms("fit_score_all_bits")) / args.steps              # per step, all 7 launches
     flops = fit_score_flops_per_weight(K) * n_weights
     achieved = flops / (fit_ms * 1e-3) / 1e12
+    n_fit_launches = len(mats) if args.per_matrix else 1
 
     out = {
         "metric": "weight GB/s scored across all 6 bit-widths (units/s) + % HBM peak, 7B shape",
@@ -304,6 +323,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "configs[1]: one LLaMA-7B-shaped decoder block, bf16, chunk 128, 20 clip ratios, "
                                "512 calibration tokens, plan at 2.0 bits; a step = all five calls over the block",
+                   "launches": "per matrix" if args.per_matrix else "batched (one launch per kernel over the 7 matrices)",
                    "weights": n_weights, "units": n_units, "unit_rows": args.unit_rows, "chunk_w": G, "K": K},
         "units_per_s": n_units / (ms_per_step * 1e-3),
         "pct_hbm_peak_whole_step": 100.0 * n_weights * 2 / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -311,10 +331,12 @@ def main():
         "avg_bits": total_cb / (100.0 * total_n),
         "roofline": {"bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / FP32_VECTOR_PEAK_TFLOPS,
-                     "traffic": FIT_SCORE_TRAFFIC_BYTES_PER_STEP / len(mats), "traffic_unit": "bytes per launch (mean of a step's 7)",
-                     "algorithmic_bytes_per_launch": n_weights * 2 / len(mats),
-                     "kernel": "fit_score_kernel<bf16> (+ its finalize kernel), 7 launches per step",
-                     "avg_launch_ms": fit_ms / len(mats),
+                     "traffic": FIT_SCORE_TRAFFIC_BYTES_PER_STEP / n_fit_launches,
+                     "traffic_unit": "bytes per launch" + (" (mean of a step's 7)" if args.per_matrix else " (the block's 7 matrices)"),
+                     "algorithmic_bytes_per_launch": n_weights * 2 / n_fit_launches,
+                     "kernel": "fit_score_kernel<bf16> (+ its finalize kernel), %d launch%s per step" % (
+                         n_fit_launches, "es" if n_fit_launches > 1 else ""),
+                     "avg_launch_ms": fit_ms / n_fit_launches,
                      "flops_per_weight": fit_score_flops_per_weight(K)},
     }
     if args.protect_ppm > 0:

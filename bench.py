@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 FP32_VECTOR_PEAK_TFLOPS = 157.3    # published fp32 vector peak: 256 CU x 128 lanes x 2 flop (FMA) x 2.4 GHz
 # HBM bytes of the 7 fit_score launches of one step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # file, scaled by a plain copy of known size (profiles/hot_path_7b_block_pmc_traffic.txt).  Not measured live.
-FIT_SCORE_TRAFFIC_BYTES_PER_STEP = 424.9e6
+FIT_SCORE_TRAFFIC_BYTES_PER_STEP = 423.7e6
 
 
 def fit_score_flops_per_weight(k: int) -> int:

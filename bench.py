@@ -98,10 +98,10 @@ class NoTimer:
 def run_step(wq, torch, cg, xs, mats, unit_rows, timer=NoTimer(), per_matrix=False):
     """One pass of the whole hot path over the block.  By default the three per-matrix calls go through their
     *_batch entry points (one launch per kernel over the block's seven matrices, the same results bit for bit);
-    per_matrix=True makes one call per matrix instead."""
-    for x in xs.values():
-        timer.time("calib_stats", lambda: wq.windq_calib_stats(x["X"], want_rms=False, ws=x["ws"], out=x["s"]))
+    per_matrix=True makes one call per matrix instead.  (calib_stats likewise: its four inputs in one launch.)"""
     if per_matrix:
+        for x in xs.values():
+            timer.time("calib_stats", lambda: wq.windq_calib_stats(x["X"], want_rms=False, ws=x["ws"], out=x["s"]))
         for m in mats:
             s = xs[m["spec"].x_key]["s"]
             timer.time("unit_features", lambda: wq.windq_unit_features(m["W"], s, G, unit_rows, ws=m["ws"], out=m["feat"]))
@@ -111,6 +111,9 @@ def run_step(wq, torch, cg, xs, mats, unit_rows, timer=NoTimer(), per_matrix=Fal
                 m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"], ws=m["ws"],
                 out=(m["scale"], m["offset"])))
     else:
+        xl = list(xs.values())
+        timer.time("calib_stats", lambda: wq.windq_calib_stats_batch(
+            [x["X"] for x in xl], want_rms=False, wss=[x["ws"] for x in xl], outs=[x["s"] for x in xl]))
         Ws = [m["W"] for m in mats]
         ss = [xs[m["spec"].x_key]["s"] for m in mats]
         wss = [m["ws"] for m in mats]

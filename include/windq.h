@@ -96,6 +96,21 @@ int windq_calib_stats(const windq_mat* X, float* s_absmean /*[cols]*/, float* s_
                       void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * windq_calib_stats for up to WINDQ_MAX_BATCH activation matrices (a decoder block has four
+ * distinct inputs) of one element type; those of at most 4096 tokens share ONE launch.  Item i
+ * is one per-matrix call; results are the same bit for bit.  `items` is a HOST array read
+ * during the call.
+ */
+typedef struct windq_calib_item {
+    const windq_mat* X;     /* HOST descriptor of a device matrix [tokens][channels] */
+    float* s_absmean;       /* [channels] */
+    float* s_rms;           /* [channels] or NULL */
+    void* ws;
+    size_t ws_bytes;
+} windq_calib_item;
+int windq_calib_stats_batch(const windq_calib_item* items /*HOST [n]*/, int32_t n, void* stream);
+
+/*
  * State features of every unit (Table 1, dims 0-4 and 9-11), feat[u][8] =
  *   mean, std (population), mean|w|, fraction with |w| < 1e-6,
  *   fraction with |w| > 0.5 * P99(|w|)  (P99 = nearest-rank order statistic, rank

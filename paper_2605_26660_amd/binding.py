@@ -25,7 +25,7 @@ EXPORTS = (
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
     "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan", "windq_fit_score_all_bits_batch",
-    "windq_unit_features_batch", "windq_apply_plan_batch",
+    "windq_unit_features_batch", "windq_apply_plan_batch", "windq_calib_stats_batch",
 )
 
 
@@ -57,6 +57,11 @@ class windq_apply_item(ctypes.Structure):
                 ("code_off", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("codes_bytes", ctypes.c_size_t),
                 ("scale", ctypes.c_void_p), ("offset", ctypes.c_void_p), ("ws", ctypes.c_void_p),
                 ("ws_bytes", ctypes.c_size_t)]
+
+
+class windq_calib_item(ctypes.Structure):
+    _fields_ = [("X", ctypes.POINTER(windq_mat)), ("s_absmean", ctypes.c_void_p), ("s_rms", ctypes.c_void_p),
+                ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
 
 _lib = None
@@ -100,13 +105,14 @@ def load(path: str | None = None):
     lib.windq_fit_score_all_bits_batch.argtypes = [c.POINTER(windq_fit_item), i32, i32, i64, vp, i32, vp]
     lib.windq_unit_features_batch.argtypes = [c.POINTER(windq_feat_item), i32, i32, i64, vp]
     lib.windq_apply_plan_batch.argtypes = [c.POINTER(windq_apply_item), i32, i32, i64, vp, i32, vp]
+    lib.windq_calib_stats_batch.argtypes = [c.POINTER(windq_calib_item), i32, vp]
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
                  "windq_apply_plan", "windq_effective_bits", "windq_salient_select", "windq_salient_encode",
                  "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency",
                  "windq_heuristic_plan", "windq_fallback_promote", "windq_dequant_plan",
-                 "windq_refine_plan", "windq_fit_score_all_bits_batch", "windq_unit_features_batch", "windq_apply_plan_batch"):
+                 "windq_refine_plan", "windq_fit_score_all_bits_batch", "windq_unit_features_batch", "windq_apply_plan_batch", "windq_calib_stats_batch"):
         getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -178,6 +184,27 @@ def windq_calib_stats(X: torch.Tensor, want_rms: bool = True, ws: torch.Tensor |
     _check(load().windq_calib_stats(ctypes.byref(m), s_abs.data_ptr(), _ptr(s_rms), ws.data_ptr(), ws.numel(),
                                     _stream()), "windq_calib_stats")
     return s_abs, s_rms
+
+
+def windq_calib_stats_batch(Xs, want_rms: bool = True, wss=None, outs=None):
+    """windq_calib_stats for several activation matrices (at most MAX_BATCH) of one element type.
+    -> list of (s_absmean, s_rms or None)."""
+    n = len(Xs)
+    assert (wss is None or len(wss) == n) and (outs is None or len(outs) == n)
+    _require_cuda(*Xs)
+    mats = [as_mat(X) for X in Xs]
+    items = (windq_calib_item * max(n, 1))()
+    res, keep = [], []
+    for i, X in enumerate(Xs):
+        C = X.shape[1]
+        s_abs = outs[i] if outs is not None else torch.empty(C, dtype=torch.float32, device=X.device)
+        s_rms = torch.empty(C, dtype=torch.float32, device=X.device) if want_rms else None
+        ws = _workspace(CALL_CALIB_STATS, X, 8, 0, 1, None if wss is None else wss[i])
+        keep.append(ws)
+        items[i] = windq_calib_item(ctypes.pointer(mats[i]), s_abs.data_ptr(), _ptr(s_rms), ws.data_ptr(), ws.numel())
+        res.append((s_abs, s_rms))
+    _check(load().windq_calib_stats_batch(items, n, _stream()), "windq_calib_stats_batch")
+    return res
 
 
 def windq_unit_features(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int = 0,

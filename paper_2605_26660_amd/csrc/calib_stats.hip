@@ -87,15 +87,33 @@ constexpr int CALIB_DIRECT_STRIP = CALIB_DIRECT_LANES * CALIB_COLS_PER_LANE;
 constexpr int CALIB_DIRECT_GROUPS = CALIB_THREADS / CALIB_DIRECT_LANES;   // token groups
 constexpr int64_t CALIB_DIRECT_MAX_ROWS = 4096;
 
+// One activation matrix of a launch; a launch covers up to WINDQ_MAX_BATCH of them, their
+// column strips numbered one matrix after the other.
+struct CalibMat {
+    const void* X;
+    int64_t rows, cols, ld;
+    float* s_absmean;
+    float* s_rms;
+};
+struct CalibBatch {
+    int32_t n;
+    int64_t strip_start[WINDQ_MAX_BATCH + 1];
+    CalibMat m[WINDQ_MAX_BATCH];
+};
+
 template <int DT>
-__global__ __launch_bounds__(CALIB_THREADS) void calib_direct_kernel(const void* __restrict__ X, int64_t rows,
-                                                                     int64_t cols, int64_t ld,
-                                                                     float* __restrict__ s_absmean,
-                                                                     float* __restrict__ s_rms) {
+__global__ __launch_bounds__(CALIB_THREADS) void calib_direct_kernel(const CalibBatch B) {
     __shared__ double red[CALIB_DIRECT_GROUPS][2][CALIB_DIRECT_STRIP + 1];
+    int mi = 0;
+    while (mi + 1 < B.n && (int64_t)blockIdx.x >= B.strip_start[mi + 1]) ++mi;
+    const void* __restrict__ X = B.m[mi].X;
+    const int64_t rows = B.m[mi].rows, cols = B.m[mi].cols, ld = B.m[mi].ld;
+    float* __restrict__ s_absmean = B.m[mi].s_absmean;
+    float* __restrict__ s_rms = B.m[mi].s_rms;
+    const int64_t strip = (int64_t)blockIdx.x - B.strip_start[mi];
     const int cl = threadIdx.x % CALIB_DIRECT_LANES;
     const int tg = threadIdx.x / CALIB_DIRECT_LANES;
-    const int64_t c0 = (int64_t)blockIdx.x * CALIB_DIRECT_STRIP + (int64_t)cl * CALIB_COLS_PER_LANE;
+    const int64_t c0 = strip * CALIB_DIRECT_STRIP + (int64_t)cl * CALIB_COLS_PER_LANE;
     double sa[CALIB_COLS_PER_LANE], sq[CALIB_COLS_PER_LANE];
 #pragma unroll
     for (int j = 0; j < CALIB_COLS_PER_LANE; ++j) sa[j] = sq[j] = 0.0;
@@ -131,7 +149,7 @@ __global__ __launch_bounds__(CALIB_THREADS) void calib_direct_kernel(const void*
     }
     __syncthreads();
     if (threadIdx.x < CALIB_DIRECT_STRIP) {
-        const int64_t c = (int64_t)blockIdx.x * CALIB_DIRECT_STRIP + threadIdx.x;
+        const int64_t c = strip * CALIB_DIRECT_STRIP + threadIdx.x;
         if (c < cols) {
             double a = 0.0, q = 0.0;
 #pragma unroll
@@ -165,27 +183,41 @@ __global__ __launch_bounds__(256) void calib_finalize_kernel(const double* __res
 
 using namespace windq;
 
-extern "C" int windq_calib_stats(const windq_mat* X, float* s_absmean, float* s_rms, void* ws, size_t ws_bytes,
-                                 void* stream) {
+static int calib_check(const windq_mat* X, const float* s_absmean, const void* ws, size_t ws_bytes) {
     const int st = check_matrix(X);
     if (st != WINDQ_OK) return st;
     if (s_absmean == nullptr) return WINDQ_EINVAL;
     const size_t need = calib_ws_bytes(X->rows, X->cols);
     if (ws == nullptr || ws_bytes < need || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (X->rows <= CALIB_DIRECT_MAX_ROWS) {
-        const dim3 dgrid((unsigned)((X->cols + CALIB_DIRECT_STRIP - 1) / CALIB_DIRECT_STRIP));
-        if (X->dtype == WINDQ_BF16)
-            hipLaunchKernelGGL(calib_direct_kernel<WINDQ_BF16>, dgrid, dim3(CALIB_THREADS), 0, hs, X->data, X->rows,
-                               X->cols, X->ld, s_absmean, s_rms);
-        else
-            hipLaunchKernelGGL(calib_direct_kernel<WINDQ_F32>, dgrid, dim3(CALIB_THREADS), 0, hs, X->data, X->rows,
-                               X->cols, X->ld, s_absmean, s_rms);
-        return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+    if (X->rows > CALIB_DIRECT_MAX_ROWS && calib_slabs(X->rows) > 65535) return WINDQ_ESHAPE;
+    return WINDQ_OK;
+}
+
+// The matrices of a launch that the direct kernel takes (few tokens), all of one element type.
+static int calib_direct_launch(const windq_calib_item* items, int32_t n, hipStream_t hs) {
+    CalibBatch B;
+    B.n = n;
+    int64_t strips = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const windq_mat* X = items[i].X;
+        B.m[i] = {X->data, X->rows, X->cols, X->ld, items[i].s_absmean, items[i].s_rms};
+        B.strip_start[i] = strips;
+        strips += (X->cols + CALIB_DIRECT_STRIP - 1) / CALIB_DIRECT_STRIP;
     }
+    for (int32_t i = n; i <= WINDQ_MAX_BATCH; ++i) B.strip_start[i] = strips;
+    for (int32_t i = n; i < WINDQ_MAX_BATCH; ++i) B.m[i] = B.m[0];
+    if (strips > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
+    if (items[0].X->dtype == WINDQ_BF16)
+        hipLaunchKernelGGL(calib_direct_kernel<WINDQ_BF16>, dim3((unsigned)strips), dim3(CALIB_THREADS), 0, hs, B);
+    else
+        hipLaunchKernelGGL(calib_direct_kernel<WINDQ_F32>, dim3((unsigned)strips), dim3(CALIB_THREADS), 0, hs, B);
+    return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+}
+
+static int calib_slab_launch(const windq_calib_item& it, hipStream_t hs) {
+    const windq_mat* X = it.X;
     const int64_t n_slabs = calib_slabs(X->rows);
-    if (n_slabs > 65535) return WINDQ_ESHAPE;
-    double* partial = static_cast<double*>(ws);
+    double* partial = static_cast<double*>(it.ws);
     const dim3 grid((unsigned)((X->cols + CALIB_STRIP - 1) / CALIB_STRIP), (unsigned)n_slabs);
     if (X->dtype == WINDQ_BF16)
         hipLaunchKernelGGL(calib_partial_kernel<WINDQ_BF16>, grid, dim3(CALIB_THREADS), 0, hs, X->data, X->rows,
@@ -195,7 +227,36 @@ extern "C" int windq_calib_stats(const windq_mat* X, float* s_absmean, float* s_
                            X->cols, X->ld, partial);
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     hipLaunchKernelGGL(calib_finalize_kernel, dim3((unsigned)((X->cols + 255) / 256)), dim3(256), 0, hs, partial,
-                       n_slabs, X->rows, X->cols, s_absmean, s_rms);
-    if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
-    return WINDQ_OK;
+                       n_slabs, X->rows, X->cols, it.s_absmean, it.s_rms);
+    return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+}
+
+extern "C" int windq_calib_stats_batch(const windq_calib_item* items, int32_t n, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    for (int32_t i = 0; i < n; ++i) {
+        if (items[i].X == nullptr) return WINDQ_EINVAL;
+        const int st = calib_check(items[i].X, items[i].s_absmean, items[i].ws, items[i].ws_bytes);
+        if (st != WINDQ_OK) return st;
+        if (items[i].X->dtype != items[0].X->dtype) return WINDQ_EINVAL;      // one kernel per launch
+    }
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    // matrices of few tokens share one launch; the others take their two launches each
+    windq_calib_item direct[WINDQ_MAX_BATCH];
+    int32_t nd = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (items[i].X->rows <= CALIB_DIRECT_MAX_ROWS) {
+            direct[nd++] = items[i];
+        } else {
+            const int st = calib_slab_launch(items[i], hs);
+            if (st != WINDQ_OK) return st;
+        }
+    }
+    return nd > 0 ? calib_direct_launch(direct, nd, hs) : WINDQ_OK;
+}
+
+extern "C" int windq_calib_stats(const windq_mat* X, float* s_absmean, float* s_rms, void* ws, size_t ws_bytes,
+                                 void* stream) {
+    const windq_calib_item it = {X, s_absmean, s_rms, ws, ws_bytes};
+    if (X == nullptr) return WINDQ_EINVAL;
+    return windq_calib_stats_batch(&it, 1, stream);
 }

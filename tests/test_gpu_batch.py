@@ -132,3 +132,21 @@ def test_apply_plan_batch_rejects_bad_batches(windq):
     with pytest.raises(windq.WindqError) as e:
         windq.windq_apply_plan_batch([Ws[0], Ws[1].float()], 128, 0, *args(2))
     assert e.value.status == windq.WINDQ_EINVAL
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_calib_stats_batch_equals_single_calls(windq, dtype):
+    """Four inputs of a block (few tokens: one shared launch) and one long input (its own two launches)."""
+    shapes = [(512, 4096), (512, 4096), (100, 1032), (512, 11008), (5000, 256)]
+    Xs = [synth.activations_llm(t, c, seed=181 + i, device=DEV).to(dtype) for i, (t, c) in enumerate(shapes)]
+    singles = [windq.windq_calib_stats(X) for X in Xs]
+    batch = windq.windq_calib_stats_batch(Xs)
+    torch.cuda.synchronize()
+    for one, got in zip(singles, batch):
+        assert same_bits(one[0], got[0]) and same_bits(one[1], got[1])
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_calib_stats_batch([Xs[0]] * 9)
+    assert e.value.status == windq.WINDQ_EINVAL
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_calib_stats_batch([Xs[0], Xs[1].float() if dtype == torch.bfloat16 else Xs[1].bfloat16()])
+    assert e.value.status == windq.WINDQ_EINVAL

@@ -107,12 +107,23 @@ __device__ __host__ constexpr int level_bits(int level) {
 template <int DT>
 __device__ __host__ constexpr int n_levels() { return DT == WINDQ_BF16 ? 2 : 3; }
 
+// Counters the passes add to, per unit: bf16 uses the first-digit histogram and 2 x 16 refined
+// counters at the head of the second one; fp32 all three histograms.
+template <int DT>
+__host__ __device__ constexpr int64_t feat_init_per_unit() { return DT == WINDQ_BF16 ? FEAT_BINS + 32 : 3 * FEAT_BINS; }
+
+template <int DT>
 __global__ __launch_bounds__(256) void feat_init_kernel(const FeatBatch B) {
     const int mi = feat_batch_index(B.init_start, B.n, blockIdx.x);
     const FeatArgs& A = B.m[mi];
-    const int64_t n = (int64_t)3 * A.g.U * FEAT_BINS;
     const int64_t i = ((int64_t)blockIdx.x - B.init_start[mi]) * 256 + threadIdx.x;
-    if (i < n) A.hist[i] = 0;
+    if (DT == WINDQ_BF16) {
+        constexpr int64_t PU = feat_init_per_unit<DT>();
+        const int64_t u = i / PU, b = i - u * PU;
+        if (u < A.g.U) A.hist[b < FEAT_BINS ? u * FEAT_BINS + b : (A.g.U + u) * FEAT_BINS + (b - FEAT_BINS)] = 0;
+    } else {
+        if (i < (int64_t)3 * A.g.U * FEAT_BINS) A.hist[i] = 0;
+    }
 }
 
 // Block-wide sum of a per-thread double in a fixed order (lanes by butterfly, wavefronts in order).
@@ -502,7 +513,7 @@ template <int DT>
 static int launch_features(const FeatBatch& B, int64_t blocks_total, int64_t units_total, int64_t init_total,
                            hipStream_t hs) {
     const dim3 blocks((unsigned)blocks_total);
-    hipLaunchKernelGGL(feat_init_kernel, dim3((unsigned)init_total), dim3(256), 0, hs, B);
+    hipLaunchKernelGGL(feat_init_kernel<DT>, dim3((unsigned)init_total), dim3(256), 0, hs, B);
     if (DT == WINDQ_BF16) {
         // |w| < 1e-6 on bf16 keys: key < key of the smallest bf16 that is >= 1e-6
         uint32_t tb;
@@ -559,7 +570,7 @@ static int unit_features_launch(const windq_feat_item* items, int32_t n, int32_t
         B.init_start[i] = inits;
         blocks += L.n_blocks;
         units += A.g.U;
-        inits += ((int64_t)3 * A.g.U * FEAT_BINS + 255) / 256;
+        inits += ((items[0].W->dtype == WINDQ_BF16 ? feat_init_per_unit<WINDQ_BF16>() : feat_init_per_unit<WINDQ_F32>()) * A.g.U + 255) / 256;
     }
     for (int32_t i = n; i <= WINDQ_MAX_BATCH; ++i) {
         B.block_start[i] = blocks;

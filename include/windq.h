@@ -173,7 +173,8 @@ int windq_unit_features_batch(const windq_feat_item* items /*HOST [n]*/, int32_t
  * arguments, the same workspace size, and bit for bit the same results.  All items share chunk_w,
  * unit_rows, the clip grid and the element type.  `items` is a HOST array read during the call.
  * WINDQ_EINVAL for n outside 1..WINDQ_MAX_BATCH or mixed element types; otherwise as the
- * per-matrix call (nothing is launched if any item fails its checks).
+ * per-matrix call (nothing is launched if any item fails its checks).  The batch calls take no
+ * protection mask: the *_prot variants are per matrix.
  */
 typedef struct windq_fit_item {
     const windq_mat* W;     /* HOST descriptor of a device matrix */

@@ -150,3 +150,91 @@ def test_calib_stats_batch_equals_single_calls(windq, dtype):
     with pytest.raises(windq.WindqError) as e:
         windq.windq_calib_stats_batch([Xs[0], Xs[1].float() if dtype == torch.bfloat16 else Xs[1].bfloat16()])
     assert e.value.status == windq.WINDQ_EINVAL
+
+
+def _block_step(windq, Ws, ss, G, cg, plan, bufs):
+    """features -> fit+score -> apply-plan over a block through the batch calls, into caller-owned buffers."""
+    windq.windq_unit_features_batch(Ws, ss, G, 0, wss=bufs["ws"], outs=bufs["feat"])
+    windq.windq_fit_score_all_bits_batch(Ws, ss, G, 0, cg, wss=bufs["ws"], outs=bufs["fit"])
+    windq.windq_apply_plan_batch(Ws, G, 0, plan["action"], [f[1] for f in bufs["fit"]], cg, plan["off"], bufs["codes"],
+                                 bufs["so"], wss=bufs["ws"])
+
+
+def _block_buffers(windq, Ws, G, K, plan):
+    bufs = {"ws": [], "feat": [], "fit": [], "codes": [], "so": []}
+    for W, off in zip(Ws, plan["off_host"]):
+        U, R_u = windq.n_units(W.shape[0], W.shape[1], G, 0)
+        need = max(windq.workspace_bytes(c, windq.WINDQ_BF16, W.shape[0], W.shape[1], G, 0, K)
+                   for c in (windq.CALL_UNIT_FEATURES, windq.CALL_FIT_SCORE, windq.CALL_APPLY_PLAN))
+        bufs["ws"].append(torch.empty(need, dtype=torch.uint8, device=DEV))
+        bufs["feat"].append(torch.zeros(U, 8, device=DEV))
+        bufs["fit"].append((torch.zeros(U, 6, device=DEV), torch.zeros(U, 4, dtype=torch.uint8, device=DEV),
+                            torch.zeros(U, device=DEV)))
+        bufs["codes"].append(torch.zeros(max(int(off[-1]), 16), dtype=torch.uint8, device=DEV))
+        bufs["so"].append((torch.zeros(U * R_u, device=DEV), torch.zeros(U * R_u, device=DEV)))
+    return bufs
+
+
+def _block_plan(windq, Ws, G):
+    plan = {"action": [], "off": [], "off_host": []}
+    for i, W in enumerate(Ws):
+        U, R_u = windq.n_units(W.shape[0], W.shape[1], G, 0)
+        action = ((torch.arange(U) + i) % 7).to(torch.uint8)
+        off = windq.windq_plan_layout(action, R_u, G)
+        plan["action"].append(action.to(DEV)); plan["off"].append(off.to(DEV)); plan["off_host"].append(off)
+    return plan
+
+
+def _flat(bufs):
+    out = list(bufs["feat"]) + list(bufs["codes"])
+    for f in bufs["fit"]:
+        out += list(f)
+    for so in bufs["so"]:
+        out += list(so)
+    return out
+
+
+def test_block_step_on_a_side_stream(windq):
+    """The calls run on the caller's stream: the same step on a second stream gives the same bits."""
+    G, K = 128, 20
+    Ws, ss = block(torch.bfloat16, [(256, 512), (512, 256), (192, 384)], 191)
+    cg = synth.clip_grid(K)
+    plan = _block_plan(windq, Ws, G)
+    ref, side = _block_buffers(windq, Ws, G, K, plan), _block_buffers(windq, Ws, G, K, plan)
+    _block_step(windq, Ws, ss, G, cg, plan, ref)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        _block_step(windq, Ws, ss, G, cg, plan, side)
+    st.synchronize()
+    assert all(same_bits(a, b) for a, b in zip(_flat(ref), _flat(side)))
+
+
+def test_block_step_replays_from_a_hip_graph(windq):
+    """The library allocates nothing, never synchronises and records no memset: a step can be captured in a graph.
+    Every replay, with other work on the device in between, must reproduce the eager result bit for bit."""
+    G, K = 128, 20
+    Ws, ss = block(torch.bfloat16, [(256, 512), (512, 256), (192, 384)], 193)
+    cg = synth.clip_grid(K)
+    plan = _block_plan(windq, Ws, G)
+    ref, cap = _block_buffers(windq, Ws, G, K, plan), _block_buffers(windq, Ws, G, K, plan)
+    _block_step(windq, Ws, ss, G, cg, plan, ref)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        _block_step(windq, Ws, ss, G, cg, plan, cap)            # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(st)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):
+        _block_step(windq, Ws, ss, G, cg, plan, cap)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in _flat(cap):
+            t.fill_(1 if t.dtype == torch.uint8 else 3.0)          # poison: the replay must rewrite everything
+        _block_step(windq, Ws, ss, G, cg, plan, ref)              # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(same_bits(a, b) for a, b in zip(_flat(ref), _flat(cap))), rep

@@ -134,8 +134,8 @@ def run_step(wq, torch, cg, xs, mats, unit_rows, timer=NoTimer(), per_matrix=Fal
 
 def protected_pass(wq, torch, cg, xs, mats, unit_rows, ppm, reps):
     """The same block with salient-weight protection at `ppm` parts per million: mask selection and INT8
-    encoding once per matrix, then fit+score and apply-plan under the mask.  Timed per call with events,
-    outside the step that `value` is quoted on."""
+    encoding once per matrix, then fit+score and apply-plan under the masks (batch calls), refinement and the
+    dequantisation check per matrix.  Timed per call with events, outside the step that `value` is quoted on."""
     timer = CallTimer(torch)
     extra = []
     for m in mats:
@@ -158,11 +158,18 @@ def protected_pass(wq, torch, cg, xs, mats, unit_rows, ppm, reps):
             s = xs[m["spec"].x_key]["s"]
             timer.time("salient_select", lambda: wq.windq_salient_select(m["W"], s, G, unit_rows, ppm, ws=e["ws"], out=e["mask"]))
             timer.time("salient_encode", lambda: wq.windq_salient_encode(m["W"], s, G, unit_rows, e["mask"], ppm, ws=e["ws"], out=e["out"]))
-            timer.time("fit_score_all_bits_prot", lambda: wq.windq_fit_score_all_bits(
-                m["W"], s, G, unit_rows, cg, ws=m["ws"], out=(m["err"], m["clip_idx"], m["ref"]), mask=e["mask"]))
-            timer.time("apply_plan_prot", lambda: wq.windq_apply_plan(
-                m["W"], G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], codes=m["codes"], ws=m["ws"],
-                out=(m["scale"], m["offset"]), mask=e["mask"]))
+        # fit+score and apply-plan under the masks: the block in one launch each
+        Ws = [m["W"] for m in mats]
+        ss = [xs[m["spec"].x_key]["s"] for m in mats]
+        wss = [m["ws"] for m in mats]
+        masks = [e["mask"] for e in extra]
+        timer.time("fit_score_all_bits_prot", lambda: wq.windq_fit_score_all_bits_batch(
+            Ws, ss, G, unit_rows, cg, wss=wss, outs=[(m["err"], m["clip_idx"], m["ref"]) for m in mats], masks=masks))
+        timer.time("apply_plan_prot", lambda: wq.windq_apply_plan_batch(
+            Ws, G, unit_rows, [m["action_d"] for m in mats], [m["clip_idx"] for m in mats], cg, [m["off_d"] for m in mats],
+            [m["codes"] for m in mats], [(m["scale"], m["offset"]) for m in mats], wss=wss, masks=masks))
+        for m, e in zip(mats, extra):
+            s = xs[m["spec"].x_key]["s"]
             timer.time("refine_plan_prot_3_rounds", lambda: wq.windq_refine_plan(
                 m["W"], s, G, unit_rows, m["action_d"], m["clip_idx"], cg, m["off_d"], 3, codes=m["codes"], mask=e["mask"],
                 ws=m["ws"]))

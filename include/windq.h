@@ -173,12 +173,13 @@ int windq_unit_features_batch(const windq_feat_item* items /*HOST [n]*/, int32_t
  * arguments, the same workspace size, and bit for bit the same results.  All items share chunk_w,
  * unit_rows, the clip grid and the element type.  `items` is a HOST array read during the call.
  * WINDQ_EINVAL for n outside 1..WINDQ_MAX_BATCH or mixed element types; otherwise as the
- * per-matrix call (nothing is launched if any item fails its checks).  The batch calls take no
- * protection mask: the *_prot variants are per matrix.
+ * per-matrix call (nothing is launched if any item fails its checks).  With a protection mask in
+ * every item this is the batch form of the *_prot call.
  */
 typedef struct windq_fit_item {
     const windq_mat* W;     /* HOST descriptor of a device matrix */
     const float* s;         /* [cols] */
+    const uint8_t* mask;    /* NULL, or [rows][cols/8] as in windq_fit_score_all_bits_prot: all items or none */
     float* err;             /* [U][6] */
     uint8_t* clip_idx;      /* [U][4] */
     float* ref_energy;      /* [U] or NULL */
@@ -230,6 +231,7 @@ int windq_apply_plan(const windq_mat* W, int32_t chunk_w, int64_t unit_rows,
  */
 typedef struct windq_apply_item {
     const windq_mat* W;        /* HOST descriptor of a device matrix */
+    const uint8_t* mask;       /* NULL, or as in windq_apply_plan_prot: all items or none */
     const uint8_t* action;     /* [U] */
     const uint8_t* clip_idx;   /* [U][4] or NULL */
     const int64_t* code_off;   /* [U+1] */

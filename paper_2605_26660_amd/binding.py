@@ -42,9 +42,9 @@ class windq_mat(ctypes.Structure):
 
 
 class windq_fit_item(ctypes.Structure):
-    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("err", ctypes.c_void_p),
-                ("clip_idx", ctypes.c_void_p), ("ref_energy", ctypes.c_void_p), ("ws", ctypes.c_void_p),
-                ("ws_bytes", ctypes.c_size_t)]
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("mask", ctypes.c_void_p),
+                ("err", ctypes.c_void_p), ("clip_idx", ctypes.c_void_p), ("ref_energy", ctypes.c_void_p),
+                ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
 
 class windq_feat_item(ctypes.Structure):
@@ -53,7 +53,8 @@ class windq_feat_item(ctypes.Structure):
 
 
 class windq_apply_item(ctypes.Structure):
-    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("action", ctypes.c_void_p), ("clip_idx", ctypes.c_void_p),
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("mask", ctypes.c_void_p), ("action", ctypes.c_void_p),
+                ("clip_idx", ctypes.c_void_p),
                 ("code_off", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("codes_bytes", ctypes.c_size_t),
                 ("scale", ctypes.c_void_p), ("offset", ctypes.c_void_p), ("ws", ctypes.c_void_p),
                 ("ws_bytes", ctypes.c_size_t)]
@@ -268,12 +269,14 @@ def windq_fit_score_all_bits(W: torch.Tensor, s: torch.Tensor, chunk_w: int, uni
     return err, clip_idx, ref
 
 
-def windq_fit_score_all_bits_batch(Ws, ss, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor, wss=None, outs=None):
+def windq_fit_score_all_bits_batch(Ws, ss, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor, wss=None, outs=None,
+                                   masks=None):
     """windq_fit_score_all_bits for several matrices (lists of equal length, at most MAX_BATCH) in one launch.
-    -> list of (err, clip_idx, ref_energy), one per matrix."""
+    masks: None, or one protection mask per matrix.  -> list of (err, clip_idx, ref_energy), one per matrix."""
     n = len(Ws)
     assert len(ss) == n and (wss is None or len(wss) == n) and (outs is None or len(outs) == n)
-    _require_cuda(*Ws, *ss)
+    assert masks is None or len(masks) == n
+    _require_cuda(*Ws, *ss, *[m for m in (masks or []) if m is not None])
     assert not clip_grid.is_cuda and clip_grid.dtype == torch.float32 and clip_grid.is_contiguous()
     K = clip_grid.numel()
     mats = [as_mat(W) for W in Ws]
@@ -289,8 +292,8 @@ def windq_fit_score_all_bits_batch(Ws, ss, chunk_w: int, unit_rows: int, clip_gr
             o = outs[i]
         ws = _workspace(CALL_FIT_SCORE, W, chunk_w, unit_rows, K, None if wss is None else wss[i])
         keep.append(ws)
-        items[i] = windq_fit_item(ctypes.pointer(mats[i]), s.data_ptr(), o[0].data_ptr(), o[1].data_ptr(), o[2].data_ptr(),
-                                  ws.data_ptr(), ws.numel())
+        items[i] = windq_fit_item(ctypes.pointer(mats[i]), s.data_ptr(), None if masks is None or masks[i] is None else masks[i].data_ptr(),
+                                  o[0].data_ptr(), o[1].data_ptr(), o[2].data_ptr(), ws.data_ptr(), ws.numel())
         res.append(o)
     _check(load().windq_fit_score_all_bits_batch(items, n, chunk_w, unit_rows, clip_grid.data_ptr(), K, _stream()),
            "windq_fit_score_all_bits_batch")
@@ -339,7 +342,8 @@ def windq_apply_plan(W: torch.Tensor, chunk_w: int, unit_rows: int, action: torc
     return codes, scale, offset
 
 
-def windq_apply_plan_batch(Ws, chunk_w: int, unit_rows: int, actions, clip_idxs, clip_grid, code_offs, codes, outs, wss=None):
+def windq_apply_plan_batch(Ws, chunk_w: int, unit_rows: int, actions, clip_idxs, clip_grid, code_offs, codes, outs, wss=None,
+                           masks=None):
     """windq_apply_plan for several matrices (lists of equal length, at most MAX_BATCH) in one launch.
     actions, clip_idxs (entries may be None), code_offs, codes: device tensors per matrix; outs: (scale, offset) per
     matrix.  clip_grid host f32 or None.  Everything is caller-allocated."""
@@ -354,7 +358,8 @@ def windq_apply_plan_batch(Ws, chunk_w: int, unit_rows: int, actions, clip_idxs,
         ws = _workspace(CALL_APPLY_PLAN, W, chunk_w, unit_rows, 1, None if wss is None else wss[i])
         keep.append(ws)
         ci = clip_idxs[i]
-        items[i] = windq_apply_item(ctypes.pointer(mats[i]), actions[i].data_ptr(), None if ci is None else ci.data_ptr(),
+        items[i] = windq_apply_item(ctypes.pointer(mats[i]), None if masks is None or masks[i] is None else masks[i].data_ptr(),
+                                    actions[i].data_ptr(), None if ci is None else ci.data_ptr(),
                                     code_offs[i].data_ptr(), codes[i].data_ptr(), codes[i].numel(), outs[i][0].data_ptr(),
                                     outs[i][1].data_ptr(), ws.data_ptr(), ws.numel())
     _check(load().windq_apply_plan_batch(items, n, chunk_w, unit_rows, None if clip_grid is None else clip_grid.data_ptr(),

@@ -666,7 +666,7 @@ extern "C" int windq_apply_plan_batch(const windq_apply_item* items, int32_t n, 
     if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
     ApplyItem its[WINDQ_MAX_BATCH];
     for (int32_t i = 0; i < n; ++i)
-        its[i] = {items[i].W, nullptr, items[i].action, items[i].clip_idx, items[i].code_off, items[i].codes,
+        its[i] = {items[i].W, items[i].mask, items[i].action, items[i].clip_idx, items[i].code_off, items[i].codes,
                   items[i].codes_bytes, items[i].scale, items[i].offset, items[i].ws, items[i].ws_bytes};
     return apply_plan_launch(its, n, chunk_w, unit_rows, clip_grid, K, stream);
 }

@@ -705,7 +705,7 @@ extern "C" int windq_fit_score_all_bits_batch(const windq_fit_item* items, int32
     if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
     FitItem its[WINDQ_MAX_BATCH];
     for (int32_t i = 0; i < n; ++i)
-        its[i] = {items[i].W, items[i].s, nullptr, items[i].err, items[i].clip_idx, items[i].ref_energy, items[i].ws,
+        its[i] = {items[i].W, items[i].s, items[i].mask, items[i].err, items[i].clip_idx, items[i].ref_energy, items[i].ws,
                   items[i].ws_bytes};
     return fit_score_launch(its, n, chunk_w, unit_rows, clip_grid, K, stream);
 }

@@ -238,3 +238,32 @@ def test_block_step_replays_from_a_hip_graph(windq):
         graph.replay()
         torch.cuda.synchronize()
         assert all(same_bits(a, b) for a, b in zip(_flat(ref), _flat(cap))), rep
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_masked_batches_equal_single_prot_calls(windq, dtype):
+    G, K, ppm = 128, 7, 30000
+    Ws, ss = block(dtype, [(256, 512), (1024, 256), (200, 384)], 201)
+    cg = synth.clip_grid(K)
+    masks = [windq.windq_salient_select(W, s, G, 0, ppm) for W, s in zip(Ws, ss)]
+    singles = [windq.windq_fit_score_all_bits(W, s, G, 0, cg, mask=m) for W, s, m in zip(Ws, ss, masks)]
+    batch = windq.windq_fit_score_all_bits_batch(Ws, ss, G, 0, cg, masks=masks)
+    torch.cuda.synchronize()
+    for one, got in zip(singles, batch):
+        assert all(same_bits(a, b) for a, b in zip(one, got))
+    plan = _block_plan(windq, Ws, G)
+    ones, codes_b, outs_b = [], [], []
+    for W, m, a, off, f in zip(Ws, masks, plan["action"], plan["off"], singles):
+        U, R_u = windq.n_units(W.shape[0], W.shape[1], G, 0)
+        ones.append(windq.windq_apply_plan(W, G, 0, a, f[1], cg, off, mask=m))
+        codes_b.append(torch.full((max(int(off[-1]), 16),), 0xAB, dtype=torch.uint8, device=DEV))
+        outs_b.append((torch.full((U * R_u,), 7.0, device=DEV), torch.full((U * R_u,), 7.0, device=DEV)))
+    got = windq.windq_apply_plan_batch(Ws, G, 0, plan["action"], [f[1] for f in singles], cg, plan["off"], codes_b, outs_b,
+                                       masks=masks)
+    torch.cuda.synchronize()
+    for one, b, off in zip(ones, got, plan["off"]):
+        total = int(off[-1])
+        assert same_bits(one[0][:total], b[0][:total]) and same_bits(one[1], b[1]) and same_bits(one[2], b[2])
+    with pytest.raises(windq.WindqError) as e:                     # a mask in every item or in none
+        windq.windq_fit_score_all_bits_batch(Ws, ss, G, 0, cg, masks=[masks[0], None, masks[2]])
+    assert e.value.status == windq.WINDQ_EINVAL

@@ -32,7 +32,7 @@ FIT_SCORE_TRAFFIC_BYTES_PER_STEP = 423.7e6
 
 def fit_score_flops_per_weight(k: int) -> int:
     """Arithmetic of the definition, FMA = 2: per (weight, clip ratio) 1 subtract + 2 for the
-    clamp + 4 bit-widths x (scale 1, round 1, residual 2, weighted square-accumulate 3) = 31;
+    clamp + 4 bit-widths x (scale 1, rounding 1, residual 2, weighted square-accumulate 3) = 31;
     plus ternary 9, binary 4, reference energy 3, group statistics 3."""
     return 31 * k + 19
 

@@ -270,3 +270,62 @@ def test_workspace_sizes_of_the_later_calls(windq):
     sal = windq.workspace_bytes(windq.CALL_SALIENT, B, 4096, 4096, 128, 0, 1)
     assert sal >= 3 * 32 * 2048 * 4 + 32 * 4096 * 4 and sal % 256 == 0
     assert windq.workspace_bytes(windq.CALL_SALIENT, B, 4096, 4100, 128, 0, 1) == 0
+
+
+def test_argument_validation_of_the_batch_calls(windq):
+    """The batch calls check every item before the first launch, like the per-matrix calls."""
+    from paper_2605_26660_amd import binding as B
+    lib = windq.lib()
+    P = 4096
+    grid = torch.linspace(0.5, 1.0, 20, dtype=torch.float32)
+    gp = grid.data_ptr()
+    good = _mat(windq)
+    odd = _mat(windq, dtype=windq.WINDQ_F32)
+
+    def fit_items(mats, ws=P, wsb=1 << 30, err=P):
+        items = (B.windq_fit_item * len(mats))()
+        for i, m in enumerate(mats):
+            items[i] = B.windq_fit_item(ctypes.pointer(m), P, None, err, P, None, ws, wsb)
+        return items
+
+    assert lib.windq_fit_score_all_bits_batch(None, 1, 64, 0, gp, 20, None) == windq.WINDQ_EINVAL
+    assert lib.windq_fit_score_all_bits_batch(fit_items([good]), 0, 64, 0, gp, 20, None) == windq.WINDQ_EINVAL
+    assert lib.windq_fit_score_all_bits_batch(fit_items([good] * 9), 9, 64, 0, gp, 20, None) == windq.WINDQ_EINVAL
+    assert lib.windq_fit_score_all_bits_batch(fit_items([good, odd]), 2, 64, 0, gp, 20, None) == windq.WINDQ_EINVAL
+    assert lib.windq_fit_score_all_bits_batch(fit_items([good, good], err=None), 2, 64, 0, gp, 20, None) == windq.WINDQ_EINVAL
+    assert lib.windq_fit_score_all_bits_batch(fit_items([good, good], wsb=8), 2, 64, 0, gp, 20, None) == windq.WINDQ_EWORKSPACE
+    assert lib.windq_fit_score_all_bits_batch(fit_items([good, good]), 2, 60, 0, gp, 20, None) == windq.WINDQ_ESHAPE
+    assert lib.windq_fit_score_all_bits_batch(fit_items([good, good]), 2, 64, 0, gp, 0, None) == windq.WINDQ_EINVAL
+
+    feat = (B.windq_feat_item * 2)()
+    for i in range(2):
+        feat[i] = B.windq_feat_item(ctypes.pointer(good), P, P, P, 1 << 30)
+    assert lib.windq_unit_features_batch(None, 1, 64, 0, None) == windq.WINDQ_EINVAL
+    assert lib.windq_unit_features_batch(feat, 9, 64, 0, None) == windq.WINDQ_EINVAL
+    feat[1] = B.windq_feat_item(ctypes.pointer(good), P, None, P, 1 << 30)
+    assert lib.windq_unit_features_batch(feat, 2, 64, 0, None) == windq.WINDQ_EINVAL
+    feat[1] = B.windq_feat_item(ctypes.pointer(good), P, P, P, 16)
+    assert lib.windq_unit_features_batch(feat, 2, 64, 0, None) == windq.WINDQ_EWORKSPACE
+
+    app = (B.windq_apply_item * 2)()
+    for i in range(2):
+        app[i] = B.windq_apply_item(ctypes.pointer(good), None, P, P, P, P, 1 << 20, P, P, P, 256)
+    assert lib.windq_apply_plan_batch(None, 1, 64, 0, gp, 20, None) == windq.WINDQ_EINVAL
+    assert lib.windq_apply_plan_batch(app, 0, 64, 0, gp, 20, None) == windq.WINDQ_EINVAL
+    assert lib.windq_apply_plan_batch(app, 2, 64, 0, None, 0, None) == windq.WINDQ_EINVAL      # clip indices without a grid
+    app[1] = B.windq_apply_item(ctypes.pointer(good), None, None, P, P, P, 1 << 20, P, P, P, 256)
+    assert lib.windq_apply_plan_batch(app, 2, 64, 0, gp, 20, None) == windq.WINDQ_EINVAL
+    app[1] = B.windq_apply_item(ctypes.pointer(good), None, P, P, P, P, 1 << 20, P, P, None, 0)
+    assert lib.windq_apply_plan_batch(app, 2, 64, 0, gp, 20, None) == windq.WINDQ_EWORKSPACE
+
+    cal = (B.windq_calib_item * 2)()
+    for i in range(2):
+        cal[i] = B.windq_calib_item(ctypes.pointer(good), P, None, P, 1 << 30)
+    assert lib.windq_calib_stats_batch(None, 1, None) == windq.WINDQ_EINVAL
+    assert lib.windq_calib_stats_batch(cal, 9, None) == windq.WINDQ_EINVAL
+    cal[1] = B.windq_calib_item(ctypes.pointer(good), None, None, P, 1 << 30)
+    assert lib.windq_calib_stats_batch(cal, 2, None) == windq.WINDQ_EINVAL
+    cal[1] = B.windq_calib_item(ctypes.pointer(odd), P, None, P, 1 << 30)
+    assert lib.windq_calib_stats_batch(cal, 2, None) == windq.WINDQ_EINVAL
+    cal[1] = B.windq_calib_item(None, P, None, P, 1 << 30)
+    assert lib.windq_calib_stats_batch(cal, 2, None) == windq.WINDQ_EINVAL

@@ -53,16 +53,10 @@ struct ApplyBatch {
     ClipGrid grid;
 };
 
-__device__ __forceinline__ int apply_batch_index(const ApplyBatch& B, int64_t tile) {
-    int mi = 0;
-    while (mi + 1 < B.n && tile >= B.tile_start[mi + 1]) ++mi;
-    return mi;
-}
-
 template <int DT>
 __global__ __launch_bounds__(AP_THREADS) void apply_plan_kernel(const ApplyBatch B) {
     extern __shared__ char tile[];
-    const int mi = apply_batch_index(B, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
     const ApplyArgs& A = B.m[mi];
     const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
@@ -487,7 +481,7 @@ template <int LPR, bool MASKED>
 __global__ __launch_bounds__(APS_THREADS, MASKED ? 6 : 7) void apply_plan_split_kernel(const ApplyBatch B) {
     constexpr int G = 8 * LPR, NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
     __shared__ __attribute__((aligned(16))) uint8_t trits[TILE_ROWS * G];
-    const int mi = apply_batch_index(B, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
     const ApplyArgs& A = B.m[mi];
     const TileCoord tc = tile_coord32(A.g, (uint32_t)((int64_t)blockIdx.x - B.tile_start[mi]));
     const SplitLane<LPR> L(threadIdx.x);

@@ -104,8 +104,7 @@ struct CalibBatch {
 template <int DT>
 __global__ __launch_bounds__(CALIB_THREADS) void calib_direct_kernel(const CalibBatch B) {
     __shared__ double red[CALIB_DIRECT_GROUPS][2][CALIB_DIRECT_STRIP + 1];
-    int mi = 0;
-    while (mi + 1 < B.n && (int64_t)blockIdx.x >= B.strip_start[mi + 1]) ++mi;
+    const int mi = batch_index(B.strip_start, B.n, blockIdx.x);
     const void* __restrict__ X = B.m[mi].X;
     const int64_t rows = B.m[mi].rows, cols = B.m[mi].cols, ld = B.m[mi].ld;
     float* __restrict__ s_absmean = B.m[mi].s_absmean;

@@ -89,13 +89,6 @@ struct FitScoreArgs {
     ClipGrid grid;
 };
 
-// Which matrix of the launch holds item `idx` (a tile or a unit), by its start table.
-__device__ __forceinline__ int batch_index(const int64_t (&start)[WINDQ_MAX_BATCH + 1], int32_t n, int64_t idx) {
-    int mi = 0;
-    while (mi + 1 < n && idx >= start[mi + 1]) ++mi;
-    return mi;
-}
-
 // LDS of a workgroup, in this order: the raw tile; s_c of the chunk's columns; per wavefront a
 // 16 x FS_NRED scratch for combining rows; the column quarters' (min, max) per row; s_c with
 // the listed columns zeroed, and the list; the quarters' fp64 sums of |w| per row; under a

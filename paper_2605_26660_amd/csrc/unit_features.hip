@@ -62,12 +62,6 @@ struct FeatBatch {
     FeatArgs m[WINDQ_MAX_BATCH];
 };
 
-__device__ __forceinline__ int feat_batch_index(const int64_t (&start)[WINDQ_MAX_BATCH + 1], int32_t n, int64_t idx) {
-    int mi = 0;
-    while (mi + 1 < n && idx >= start[mi + 1]) ++mi;
-    return mi;
-}
-
 template <int DT>
 __device__ __forceinline__ void load8(const void* __restrict__ data, int64_t off, float (&w)[8]) {
     if (DT == WINDQ_BF16) {
@@ -114,7 +108,7 @@ __host__ __device__ constexpr int64_t feat_init_per_unit() { return DT == WINDQ_
 
 template <int DT>
 __global__ __launch_bounds__(256) void feat_init_kernel(const FeatBatch B) {
-    const int mi = feat_batch_index(B.init_start, B.n, blockIdx.x);
+    const int mi = batch_index(B.init_start, B.n, blockIdx.x);
     const FeatArgs& A = B.m[mi];
     const int64_t i = ((int64_t)blockIdx.x - B.init_start[mi]) * 256 + threadIdx.x;
     if (DT == WINDQ_BF16) {
@@ -172,7 +166,7 @@ __host__ __device__ constexpr int feat_cstride(int mode) { return (mode == 0 ? F
 __host__ __device__ constexpr size_t feat_lds_bytes(int mode) { return (size_t)feat_cstride(mode) * FEAT_COPIES * sizeof(uint32_t); }
 template <int MODE>
 __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatBatch B, const uint32_t sparse_key) {
-    const int mi = feat_batch_index(B.block_start, B.n, blockIdx.x);
+    const int mi = batch_index(B.block_start, B.n, blockIdx.x);
     const FeatArgs& A = B.m[mi];
     const int64_t wg = (int64_t)blockIdx.x - B.block_start[mi];
     constexpr int CSTRIDE = feat_cstride(MODE);
@@ -291,7 +285,7 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatBatch B
     __shared__ double red[FT_WAVES];
     __shared__ uint32_t sh_part[FT_THREADS];
     __shared__ uint32_t sh_out[4];
-    const int mi = feat_batch_index(B.block_start, B.n, blockIdx.x);
+    const int mi = batch_index(B.block_start, B.n, blockIdx.x);
     const FeatArgs& A = B.m[mi];
     const int64_t wg = (int64_t)blockIdx.x - B.block_start[mi];
     const int64_t u = wg / A.bpu;
@@ -432,7 +426,7 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
     __shared__ uint32_t sh_part[FT_THREADS];
     __shared__ uint32_t sh_out[4];
     __shared__ float smax_sh[FT_THREADS];
-    const int mi = feat_batch_index(B.unit_start, B.n, blockIdx.x);
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
     const FeatArgs& A = B.m[mi];
     const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
     const int32_t G = A.g.chunk_w;

@@ -202,6 +202,15 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
+// Batched launches number their items (tiles, workgroups, units, strips) one matrix after the
+// other; start[i] is the first item of matrix i and start[n] the grid size.  Which matrix holds
+// item idx: a scan over at most WINDQ_MAX_BATCH scalars.
+__device__ __forceinline__ int batch_index(const int64_t (&start)[WINDQ_MAX_BATCH + 1], int32_t n, int64_t idx) {
+    int mi = 0;
+    while (mi + 1 < n && idx >= start[mi + 1]) ++mi;
+    return mi;
+}
+
 // Sum of the n fp64 partials of one unit by a workgroup of NT threads, in a fixed order:
 // thread t adds entries t, t + NT, ...; lanes by butterfly, wavefronts in order.  Every
 // thread returns the total.

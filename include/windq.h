@@ -141,15 +141,30 @@ int windq_unit_features(const windq_mat* W, const float* s /*[cols]*/, int32_t c
  *   ref_energy [U] or NULL: sum s_c^2 w^2, to normalise err
  * Errors are accumulated in fp32 along a group and in fp64 beyond it, in a fixed order
  * (results are bit-reproducible run to run).  They agree with the definition above evaluated
- * in fp64 to ~1e-7 relative; the 8-bit error to 1e-6 (one sigma) for units whose error is
- * spread over their rows, as in weight matrices: columns of ordinary weight s_c^2 take a
- * shorter arithmetic route there than the few heavy ones.  |s_c * w| must square inside
- * fp32's normal range.
+ * in fp64 to ~1e-7 relative.  The 8-bit candidate has two arithmetic routes: an exact one
+ * (~1e-7), and a shorter one whose fp32 roundings leave noise of random sign in the unit's
+ * error.  The short route is used only where that noise is provably small for the data at
+ * hand: columns that hold much of the chunk's sum of s_c^2, and tiles in which one row holds
+ * most of the rows' squared ranges, take the exact route; and every unit's noise variance is
+ * summed from its own per-row errors (each rounding taken at its largest possible size).  A
+ * unit whose noise could exceed 3e-6 of its 8-bit error (one standard deviation; measured
+ * deviations are ~0.4 of that estimate) has its 8-bit candidates scored again on the exact
+ * route before the call's work ends, whatever the input.  |s_c * w| must square inside fp32's
+ * normal range.
  */
 int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
                              const float* clip_grid /*HOST [K]*/, int32_t K,
                              float* err /*[U][6]*/, uint8_t* clip_idx /*[U][4]*/, float* ref_energy /*[U] or NULL*/,
                              void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Diagnostic: how many units of the last windq_fit_score_all_bits (or _prot, or batch item) call
+ * that used workspace `ws` had their 8-bit candidates scored a second time on the exact route.
+ * Pass the shape arguments of that call.  Unlike every other entry point this one copies a
+ * counter to the host and therefore waits for the device: call it after the stream has finished.
+ */
+int windq_fit_score_rescored_units(const void* ws, int32_t dtype, int64_t rows, int64_t cols, int32_t chunk_w,
+                                   int64_t unit_rows, int32_t K, int64_t* n_units /*HOST*/);
 
 /*
  * windq_unit_features for up to WINDQ_MAX_BATCH matrices with one launch per pass instead of

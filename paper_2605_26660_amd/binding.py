@@ -25,7 +25,7 @@ EXPORTS = (
     "windq_status_str", "windq_n_protected", "windq_salient_select", "windq_salient_encode",
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
     "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan", "windq_fit_score_all_bits_batch",
-    "windq_unit_features_batch", "windq_apply_plan_batch", "windq_calib_stats_batch",
+    "windq_unit_features_batch", "windq_apply_plan_batch", "windq_calib_stats_batch", "windq_fit_score_rescored_units",
 )
 
 
@@ -107,6 +107,8 @@ def load(path: str | None = None):
     lib.windq_unit_features_batch.argtypes = [c.POINTER(windq_feat_item), i32, i32, i64, vp]
     lib.windq_apply_plan_batch.argtypes = [c.POINTER(windq_apply_item), i32, i32, i64, vp, i32, vp]
     lib.windq_calib_stats_batch.argtypes = [c.POINTER(windq_calib_item), i32, vp]
+    lib.windq_fit_score_rescored_units.argtypes = [vp, i32, i64, i64, i32, i64, i32, c.POINTER(i64)]
+    lib.windq_fit_score_rescored_units.restype = c.c_int
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
@@ -298,6 +300,16 @@ def windq_fit_score_all_bits_batch(Ws, ss, chunk_w: int, unit_rows: int, clip_gr
     _check(load().windq_fit_score_all_bits_batch(items, n, chunk_w, unit_rows, clip_grid.data_ptr(), K, _stream()),
            "windq_fit_score_all_bits_batch")
     return res
+
+
+def windq_fit_score_rescored_units(ws: torch.Tensor, W: torch.Tensor, chunk_w: int, unit_rows: int, K: int) -> int:
+    """Units of the last fit+score call on workspace `ws` whose 8-bit candidates were scored again on the
+    exact route (diagnostic; waits for the device)."""
+    _require_cuda(ws)
+    n = ctypes.c_int64(0)
+    _check(load().windq_fit_score_rescored_units(ws.data_ptr(), _dtype_code(W), W.shape[0], W.shape[1], chunk_w, unit_rows,
+                                                 K, ctypes.byref(n)), "windq_fit_score_rescored_units")
+    return n.value
 
 
 def windq_bytes_per_group(action: int, chunk_w: int) -> int:

@@ -26,17 +26,24 @@
 //     [0,1]): 18 per (weight, clip ratio) when all four bit-widths go this short way;
 //   * at 8 bits the residual is ~1/500 of (w - lo), so the fp32 roundings of s_c*w,
 //     s_c*(w - lo) and s_c*code show in it: ~1e-4 of its size per weight, random in sign.
-//     Summed over a unit that is harmless for the columns of ordinary weight s_c^2, but not
-//     for a column that carries much of the unit's error by itself.  The kernel therefore
-//     lists the chunk's heavy columns (s_c^2 above tau times the chunk's mean, tau chosen
-//     from the unit's size so that the noise stays at 1e-6 of the unit's error) and scores
-//     them on an exact 8-bit route instead, 20 instructions: the residual is formed
-//     unscaled, relative to an anchor c = lo + q0*step, the grid point nearest zero, as
-//     (w - (code - q0)*step) - c, where the FMA rounds once at the small magnitude |c + r|,
-//     and only then multiplied by s_c.  Small units, and chunks with many heavy columns,
-//     take the exact route for every column.  (Groups whose weights all have one sign have
-//     no grid point near zero: their wavefront uses c = lo and an error-free two-sum of
-//     (w - c), 23 instructions.)
+//     An EXACT 8-bit route, 20 instructions, forms the residual unscaled, relative to an
+//     anchor c = lo + q0*step, the grid point nearest zero, as (w - (code - q0)*step) - c,
+//     where the FMA rounds once at the small magnitude |c + r|, and only then multiplies by
+//     s_c.  (Groups whose weights all have one sign have no grid point near zero: their
+//     wavefront uses c = lo and an error-free two-sum of (w - c), 23 instructions.)
+//     Which weights may take the short route is decided from the data, at three levels:
+//       columns  a column that carries much of the chunk's sum of s_c^2 (above tau times
+//                the mean) is listed and scored on the exact route, one column at a time;
+//                small units, and chunks with many such columns, sweep every column exactly;
+//       rows     a tile in which one row holds more than two thirds of the rows' squared
+//                ranges takes the exact sweep;
+//       units    every tile that used the short route also sums, per clip index, the
+//                variance its roundings can have put into the 8-bit error (see
+//                NOISE_MAX below); the finalize kernel adds these up per unit and, where
+//                the standard deviation exceeds NOISE_MAX of the unit's 8-bit error at the
+//                chosen clip index, puts the unit on a list; a second pair of launches
+//                scores the 8-bit candidates of the listed units again, exact route only,
+//                and finalizes them again.  With nothing listed those launches end at once.
 //   * lanes accumulate in fp32 over the chunk's columns only (<= 512 terms); rows are
 //     combined in fp64 in a fixed order (LDS transpose), tiles by the finalize kernel.
 // Rounding decisions here are taken on x*(2^b-1); windq_apply_plan takes them on
@@ -57,9 +64,29 @@ namespace windq {
 constexpr int FS_THREADS = 256;
 constexpr int FS_WAVES = FS_THREADS / 64;
 constexpr int FS_KB = 5;                    // clip ratios evaluated together by one wavefront pass
-constexpr int FS_NRED = FS_KB * 4;          // per-lane sums a pass produces
+constexpr int FS_NRED = FS_KB * 5;          // per-lane sums a pass produces: 4 errors + 1 noise term per clip ratio
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
 constexpr int FS_HMAX = WINDQ_MAX_CHUNK / 8;   // most columns a tile may send down the exact 8-bit route on their own
+constexpr int FS_REDO_GRID = 1024;          // workgroups of the launch that scores listed units again
+
+// The short route's rounding noise in a unit's 8-bit error.  On the short route the residual
+// r' = s_c (w - lo - code*step) carries three roundings taken at magnitudes of at most
+// s_c*range (range = hi - lo of the group): an error e of variance <= (2^-24 s_c range)^2, of
+// random sign.  It moves the squared residual by 2 r' e, so the unit's error moves by a sum
+// of variance <= 4 * 2^-48 * sum_rows range^2 * sum_cols s_c^2 r'^2.  Taking r' independent
+// of the column (true of rounding residuals), sum_c s_c^2 r'^2 = (S4/S2) * sum_c r'^2 with
+// S4 = sum s_c^4, S2 = sum s_c^2 over the columns on the short route; sum_c r'^2 is the lane's
+// own 8-bit accumulator.  So every short-route tile emits, per clip index,
+//     V = (S4/S2) * sum_rows range^2 * acc8_row,
+// and the unit's noise has a standard deviation of at most 2^-23 sqrt(sum_tiles V).  The unit's
+// 8-bit candidates are scored again on the exact route when that exceeds NOISE_MAX times the
+// unit's 8-bit error at the chosen clip index.  (Measured against fp64, the actual deviation
+// is ~0.4 of this estimate: NOISE_MAX = 3e-6 keeps one standard deviation near 1e-6.)
+constexpr double NOISE_MAX = 3e-6;
+constexpr double NOISE_C1 = 4.0 * 3.552713678800501e-15 / (NOISE_MAX * NOISE_MAX);   // 4 * 2^-48 / NOISE_MAX^2
+// A tile takes the exact sweep when one row holds more than 1 / ROW_SHARE of the sum of the
+// rows' squared ranges (that row would carry most of the tile's 8-bit error by itself).
+constexpr float ROW_SHARE = 1.5f;
 
 // One matrix of a launch.
 struct FitScoreMat {
@@ -67,8 +94,10 @@ struct FitScoreMat {
     const float* s;
     const uint8_t* mask;   // protection mask [rows][cols/8] (masked kernels only)
     int64_t mask_ld;
-    double* partial;   // [n_tiles][4K+12]
-    float* err;        // outputs of the finalize kernel
+    double* partial;       // [n_tiles][5K+12]
+    uint32_t* redo_count;  // number of units listed for the exact 8-bit pass
+    uint32_t* redo_list;   // [U] their indices, in no particular order
+    float* err;            // outputs of the finalize kernel
     uint8_t* clip_idx;
     float* ref_energy;
     Geometry g;
@@ -92,7 +121,7 @@ struct FitScoreArgs {
 // LDS of a workgroup, in this order: the raw tile; s_c of the chunk's columns; per wavefront a
 // 16 x FS_NRED scratch for combining rows; the column quarters' (min, max) per row; s_c with
 // the listed columns zeroed, and the list; the quarters' fp64 sums of |w| per row; under a
-// mask, the quarters' kept counts and the tile's mask bytes.  28-30 KB at G = 128, small on
+// mask, the quarters' kept counts and the tile's mask bytes.  29-31 KB at G = 128, small on
 // purpose: the fast fp32 issue rate needs five resident wavefronts per SIMD (a single
 // wavefront issues at most one vector instruction per ~5 cycles), i.e. five workgroups per CU.
 inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
@@ -120,7 +149,28 @@ struct KParams {
     float nd[4];       // -step for 8, 4, 3, 2 bits (0 when degenerate)
 };
 
-// One weight against FS_KB clip ratios x 4 bit-widths.  sc = s_c, nM = -2^23 (in a VGPR).
+// The exact 8-bit residual of one weight at clip ratio P, times s_c.
+template <bool ANCHORED>
+__device__ __forceinline__ float exact_residual8(const float w, const float sc, const KParams& P, const float Q0,
+                                                 const float M, float& x) {
+    float r;
+    if (ANCHORED) {
+        x = fma_clamp01(w, P.rinv, P.h);                      // position in the clipped range, in [0, 1]
+        const float qc = fmaf(x, Q0, M) - P.Mq;               // code - q0
+        r = fmaf(qc, P.nd[0], w) + P.nc;                      // (c + r) - c
+    } else {
+        const float u0 = w + P.nc;                            // w - c, rounded
+        const float bb = u0 - w;
+        const float e = (w - (u0 - bb)) + (P.nc - bb);        // its rounding error: (w - c) = u0 + e exactly
+        x = fma_clamp01(u0, P.rinv, P.h);
+        const float qc = fmaf(x, Q0, M) - P.Mq;
+        r = fmaf(qc, P.nd[0], u0) + e;
+    }
+    return r * sc;
+}
+
+// One weight against FS_KB clip ratios x 4 bit-widths, the 8-bit one on the exact route.
+// sc = s_c, nM = -2^23 (in a VGPR).
 template <bool ANCHORED>
 __device__ __forceinline__ void score_weight(const float w, const float sc, const KParams (&P)[FS_KB],
                                              const float (&Q)[4], const float M, const float nM,
@@ -130,20 +180,8 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
 #pragma unroll
     for (int i = 0; i < FS_KB; ++i) {
         const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
-        float x, r;
-        if (ANCHORED) {
-            x = fma_clamp01(w, P[i].rinv, P[i].h);                // position in the clipped range, in [0, 1]
-            const float qc = fmaf(x, Q[0], M) - P[i].Mq;          // code - q0
-            r = fmaf(qc, P[i].nd[0], w) + P[i].nc;                // (c + r) - c
-        } else {
-            const float u0 = w + P[i].nc;                         // w - c, rounded
-            const float bb = u0 - w;
-            const float e = (w - (u0 - bb)) + (P[i].nc - bb);     // its rounding error: (w - c) = u0 + e exactly
-            x = fma_clamp01(u0, P[i].rinv, P[i].h);
-            const float qc = fmaf(x, Q[0], M) - P[i].Mq;
-            r = fmaf(qc, P[i].nd[0], u0) + e;
-        }
-        const float r8 = r * sc;
+        float x;
+        const float r8 = exact_residual8<ANCHORED>(w, sc, P[i], Q[0], M, x);
         acc[i][0] = fmaf(r8, r8, acc[i][0]);
 #pragma unroll
         for (int b = 1; b < 4; ++b) {
@@ -155,10 +193,21 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
     }
 }
 
+// The 8-bit candidate alone, exact route (the pass over listed units).
+template <bool ANCHORED>
+__device__ __forceinline__ void score_weight_8(const float w, const float sc, const KParams (&P)[FS_KB], const float Q0,
+                                               const float M, float (&acc)[FS_KB][4]) {
+#pragma unroll
+    for (int i = 0; i < FS_KB; ++i) {
+        float x;
+        const float r8 = exact_residual8<ANCHORED>(w, sc, P[i], Q0, M, x);
+        acc[i][0] = fmaf(r8, r8, acc[i][0]);
+    }
+}
+
 // The short route: all four bit-widths like the low ones, 18 instructions per (weight, clip
 // ratio).  Its 8-bit residual carries the fp32 roundings of s_c*w, s_c*(w - lo) and s_c*code:
-// ~1e-4 of its own size per weight, of random sign.  Used for the columns whose share of the
-// unit's error is bounded (see the column selection in the kernel).
+// ~1e-4 of its own size per weight, of random sign (see NOISE_MAX for how that is bounded).
 __device__ __forceinline__ void score_weight_short(const float w, const float sc, const KParams (&P)[FS_KB],
                                                    const float (&Q)[4], const float M, const float nM,
                                                    float (&acc)[FS_KB][4]) {
@@ -209,11 +258,20 @@ __device__ __forceinline__ int fresh_lane() {
     return l;
 }
 
+__device__ __forceinline__ float dpp_f32(float x, int ctrl) {
+    switch (ctrl) {   // the control word must be a compile-time constant
+        case 0xB1: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+        case 0x4E: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+        case 0x141: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));  // row_half_mirror
+        default: return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, false));     // row_mirror
+    }
+}
+
 // x + (x of the lane whose index differs in bit 0 / bit 1): after both, every lane of a
 // quad (4 adjacent rows) holds the quad's sum.
 __device__ __forceinline__ float quad_sum(float x) {
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+    x += dpp_f32(x, 0xB1);
+    x += dpp_f32(x, 0x4E);
     return x;
 }
 
@@ -221,13 +279,26 @@ __device__ __forceinline__ float quad_sum(float x) {
 // half row, the two halves of a row of 16 (DPP mirrors), then the four rows in order.
 __device__ __forceinline__ float wave_sum_f32(float x) {
     x = quad_sum(x);
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));   // row_half_mirror
-    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, false));   // row_mirror
+    x += dpp_f32(x, 0x141);
+    x += dpp_f32(x, 0x140);
     const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
     const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
     const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
     const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
     return ((r0 + r1) + r2) + r3;
+}
+
+// Largest x over the 64 lanes, by the same steps.
+__device__ __forceinline__ float wave_max_f32(float x) {
+    x = fmaxf(x, dpp_f32(x, 0xB1));
+    x = fmaxf(x, dpp_f32(x, 0x4E));
+    x = fmaxf(x, dpp_f32(x, 0x141));
+    x = fmaxf(x, dpp_f32(x, 0x140));
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
 // Sum N per-lane fp32 values over the 64 lanes (rows) of a wavefront: quads in fp32 by
@@ -256,14 +327,14 @@ __device__ __forceinline__ double rows_sum(const float (&v)[N], float* __restric
     return tot;
 }
 
+// One tile: all candidates (ONLY8 = false), or the 8-bit candidates alone on the exact route
+// (ONLY8 = true: the pass over listed units; every other partial of the tile stays as it is).
 // MASKED: salient weights (Sec. 3.5) marked in A.mask take no part: they are left out of
 // the group statistics, and in every error sum their activation scale counts as zero.
-template <int DT, bool MASKED>
-__global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScoreArgs B) {
-    extern __shared__ char smem[];
-    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
-    const FitScoreMat& A = B.m[mi];
-    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
+// rot spreads an uneven number of clip passes over the four SIMDs from tile to tile.
+template <int DT, bool MASKED, bool ONLY8>
+__device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitScoreMat& A, const TileCoord& tc,
+                                               const int rot, char* __restrict__ smem) {
     const int32_t G = A.g.chunk_w;
     constexpr int EB = Elem<DT>::bytes;
     const int32_t row_bytes = G * EB + 16;
@@ -283,16 +354,15 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     if (MASKED) load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     __syncthreads();
 
-    // Column selection for the 8-bit candidate.  A column whose s_c^2 exceeds
-    // tau times the chunk's mean carries too much of the unit's error for the short route's
-    // rounding noise: such columns are listed and scored on the exact route, one at a time;
-    // all others (s_c kept in sshort, listed ones zeroed there) go down the short route.  With
-    // the short route's ~1.2e-4/sqrt(rows) relative noise per column, the unit's 8-bit error
-    // moves by at most 1.2e-4 sqrt(tau / (G R_u)) (one sigma): 1e-6 at the tau the host sets
-    // (statistically, for units whose error is spread over their rows, as in weight matrices).
-    // Every wavefront derives the same list and writes the same values: none waits for another.
-    int32_t nh = -1;      // listed columns; -1: no list, every column takes the exact route
-    {
+    // Column selection for the 8-bit candidate.  A column whose s_c^2 exceeds tau times the
+    // chunk's mean carries much of the unit's error by itself: such columns are listed and
+    // scored on the exact route, one at a time; all others (s_c kept in sshort, listed ones
+    // zeroed there) go down the short route, and their S4/S2 = sum s_c^4 / sum s_c^2 scales the
+    // tile's noise term.  Every wavefront derives the same list and writes the same values:
+    // none waits for another.
+    int32_t nh = -1;           // listed columns; -1: no list, every column takes the exact route
+    float s4_over_s2 = 0.0f;
+    if (!ONLY8) {
         const int l = fresh_lane();
         if (A.tau > 0.0f) {
             float ss = 0.0f;
@@ -302,16 +372,25 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             }
             const float thr = A.tau * wave_sum_f32(ss) / (float)G;
             nh = 0;
+            float t2 = 0.0f, t4 = 0.0f;
             for (int32_t blk = 0; blk < G; blk += 64) {
                 const int32_t c = blk + l;
                 const float sv = c < G ? scol[c] : 0.0f;
-                const bool hv = sv * sv > thr;
+                const float s2 = sv * sv;
+                const bool hv = s2 > thr;
                 const uint64_t bal = __builtin_amdgcn_ballot_w64(hv);
                 if (c < G) sshort[c] = hv ? 0.0f : sv;
+                if (!hv) {
+                    t2 += s2;
+                    t4 = fmaf(s2, s2, t4);
+                }
                 const int32_t pos = nh + __builtin_popcountll(bal & ((1ull << l) - 1ull));
                 if (hv && pos < FS_HMAX) hlist[pos] = c;
                 nh += __builtin_popcountll(bal);
             }
+            const float S2 = wave_sum_f32(t2), S4 = wave_sum_f32(t4);
+            // (wave-uniform: parked in a scalar register across the hot loops)
+            s4_over_s2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(S2 >= FLT_MIN ? S4 / S2 : 0.0f)));
             if (nh * 8 > G) nh = -1;     // so many that one exact sweep over all columns is cheaper
         }
     }
@@ -331,18 +410,20 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             float w[8];
             read8<DT>(wr, c, w);
             const uint32_t m = MASKED ? (uint32_t)mr[c >> 3] : 0u;
-            if (MASKED) nk += 8 - __builtin_popcount(m);
+            if (MASKED && !ONLY8) nk += 8 - __builtin_popcount(m);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const bool kept = !MASKED || ((m >> j) & 1u) == 0u;
                 mn = fminf(mn, kept ? w[j] : INFINITY);
                 mx = fmaxf(mx, kept ? w[j] : -INFINITY);
-                S1 += kept ? (double)fabsf(w[j]) : 0.0;
+                if (!ONLY8) S1 += kept ? (double)fabsf(w[j]) : 0.0;
             }
         }
         gstat[wave * TILE_ROWS + lane_s] = make_float2(mn, mx);
-        s1tab[wave * TILE_ROWS + lane_s] = S1;
-        if (MASKED) nktab[wave * TILE_ROWS + lane_s] = nk;
+        if (!ONLY8) {
+            s1tab[wave * TILE_ROWS + lane_s] = S1;
+            if (MASKED) nktab[wave * TILE_ROWS + lane_s] = nk;
+        }
         __syncthreads();
     }
 
@@ -357,7 +438,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     // added in order (exact for bf16 inputs; for fp32 inputs it can differ from the strict
     // column-order sum in the last bit of the fp64, which the conversion to fp32 hides but for
     // ~1e-8 of the groups, and there by one ulp of gamma).
-    {
+    if (!ONLY8) {
         const int lane_w = fresh_lane();
         const char* __restrict__ wrow = tile + lane_w * row_bytes;
         const uint8_t* __restrict__ mrow = mtile + lane_w * mstride;
@@ -412,8 +493,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
     }
 
     // The clip grid: n_kpass passes over FS_KB clip ratios each.  Pass i goes to wavefront
-    // (i + rot) % 4; rot spreads an uneven number of passes over the four SIMDs from tile to tile.
-    const int rot = blockIdx.x & (FS_WAVES - 1);
+    // (i + rot) % 4.
     for (int item = (wave - rot) & (FS_WAVES - 1); item < B.n_kpass; item += FS_WAVES) {
         // The hot loop below needs every register the occupancy target allows.  The lane index
         // is therefore re-read from the hardware where it is needed (before the loop for the
@@ -431,6 +511,13 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
             // zero inside the closed range of every group of the wavefront?
             const bool anchored = __builtin_amdgcn_ballot_w64(!(mn <= 0.0f && mx >= 0.0f)) == 0;
+            // does one row hold most of the rows' squared ranges?  (rows past the unit's end are zeros)
+            bool rows_even = true;
+            if (!ONLY8 && nh >= 0) {
+                const float rg = mx - mn;
+                const float rg2 = rg * rg;
+                rows_even = wave_max_f32(rg2) * ROW_SHARE <= wave_sum_f32(rg2);
+            }
             KParams P[FS_KB];
             float acc[FS_KB][4];
 #pragma unroll
@@ -451,7 +538,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                     float d = (float)((double)frg * rq);
                     d = d >= FLT_MIN ? d : 0.0f;
                     if (b == 0) d8 = d;
-                    P[i].nd[b] = pin_vgpr(-d);
+                    if (!ONLY8 || b == 0) P[i].nd[b] = pin_vgpr(-d);
                     acc[i][b] = 0.0f;
                 }
                 // anchor: the 8-bit grid point nearest zero when zero lies inside the range, else lo
@@ -462,11 +549,14 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                 P[i].h = pin_vgpr((anchored ? -flo : c - flo) * rinv);
                 P[i].nc = pin_vgpr(-c);
                 P[i].Mq = pin_vgpr(RNE_POS + q0);
-                P[i].nlo = pin_vgpr(-flo);
+                if (!ONLY8) P[i].nlo = pin_vgpr(-flo);
             }
             const float Q[4] = {pin_vgpr(255.0f), pin_vgpr(15.0f), pin_vgpr(7.0f), pin_vgpr(3.0f)};
             const float M = pin_vgpr(RNE_POS);
             const float nM = pin_vgpr(-RNE_POS);
+            float nz[FS_KB];     // the noise terms of the short route (zero on the exact ones)
+#pragma unroll
+            for (int i = 0; i < FS_KB; ++i) nz[i] = 0.0f;
             // (the row addresses are formed from a fresh lane index in front of each sweep: kept
             // from here they would be spilled across the parameter set-up)
             auto sweep = [&](auto MODE) {
@@ -485,12 +575,15 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
                         drop_masked(s8, m);
                     }
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) score_weight<AN>(w[j], s8[j], P, Q, M, nM, acc);
+                    for (int j = 0; j < 8; ++j) {
+                        if (ONLY8) score_weight_8<AN>(w[j], s8[j], P, Q[0], M, acc);
+                        else score_weight<AN>(w[j], s8[j], P, Q, M, nM, acc);
+                    }
                 }
             };
             if (!anchored) {
                 sweep(std::false_type{});
-            } else if (nh < 0) {
+            } else if (ONLY8 || nh < 0 || !rows_even) {
                 sweep(std::true_type{});
             } else {
                 const int lane_v = fresh_lane();
@@ -509,6 +602,9 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
 #pragma unroll
                     for (int j = 0; j < 8; ++j) score_weight_short(w[j], s8[j], P, Q, M, nM, acc);
                 }
+                // range^2 * (the lane's short-route 8-bit sum); range = 255 * step
+#pragma unroll
+                for (int i = 0; i < FS_KB; ++i) nz[i] = acc[i][0] * (P[i].nd[0] * P[i].nd[0]) * 65025.0f;
                 for (int32_t hi = 0; hi < nh; ++hi) {
                     const int32_t c = __builtin_amdgcn_readfirstlane(hlist[hi]);
                     const float w = read1<DT>(wrow, c);
@@ -519,33 +615,90 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
             }
             float flat[FS_NRED];
 #pragma unroll
-            for (int i = 0; i < FS_KB; ++i)
+            for (int i = 0; i < FS_KB; ++i) {
 #pragma unroll
                 for (int b = 0; b < 4; ++b) flat[i * 4 + b] = acc[i][b];
+                flat[FS_KB * 4 + i] = nz[i];
+            }
             const int lane_r = fresh_lane();
             if (lane_r >= tc.nrows) {
 #pragma unroll
                 for (int j = 0; j < FS_NRED; ++j) flat[j] = 0.0f;
             }
             const double tot = rows_sum<FS_NRED>(flat, red, lane_r);
-            if (lane_r < FS_NRED) {
+            if (lane_r < FS_KB * 4) {
                 const int k = item * FS_KB + (lane_r >> 2);
-                if (k < K) out[(lane_r & 3) * K + k] = tot;
+                if (k < K && (!ONLY8 || (lane_r & 3) == 0)) out[(lane_r & 3) * K + k] = tot;
+            } else if (lane_r < FS_NRED) {
+                const int k = item * FS_KB + (lane_r - FS_KB * 4);
+                if (k < K) {
+                    float ratio = s4_over_s2;
+                    asm volatile("" : "+s"(ratio));      // converted here, not ahead of the loops
+                    out[fit_score_noise_slot(K) + k] = tot * (double)ratio;
+                }
             }
         }
     }
 }
 
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScoreArgs B) {
+    extern __shared__ char smem[];
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const FitScoreMat& A = B.m[mi];
+    const int64_t local = (int64_t)blockIdx.x - B.tile_start[mi];
+    if (local == 0 && threadIdx.x == 0) *A.redo_count = 0u;      // the list the finalize kernel fills
+    const TileCoord tc = tile_coord(A.g, local);
+    fit_score_tile<DT, MASKED, false>(B, A, tc, blockIdx.x & (FS_WAVES - 1), smem);
+}
+
+// The tiles of the listed units once more, 8-bit candidates only, exact route.  A fixed grid
+// walks the list; with nothing listed every workgroup ends after reading the counters.
+template <int DT, bool MASKED>
+__global__ __launch_bounds__(FS_THREADS, 5) void fit_score_redo_kernel(const FitScoreArgs B) {
+    extern __shared__ char smem[];
+    int64_t start[WINDQ_MAX_BATCH + 1];
+    start[0] = 0;
+#pragma unroll
+    for (int i = 0; i < WINDQ_MAX_BATCH; ++i) {
+        int64_t nt = 0;
+        if (i < B.n) {
+            int64_t cnt = (int64_t)*B.m[i].redo_count;
+            cnt = cnt < B.m[i].g.U ? cnt : B.m[i].g.U;
+            nt = cnt * B.m[i].g.tiles_per_unit;
+        }
+        start[i + 1] = start[i] + nt;
+    }
+    for (int64_t w = blockIdx.x; w < start[WINDQ_MAX_BATCH]; w += gridDim.x) {
+        const int mi = batch_index(start, B.n, w);
+        const FitScoreMat& A = B.m[mi];
+        const int64_t local = w - start[mi];
+        const int64_t li = local / A.g.tiles_per_unit;
+        const int64_t u = A.redo_list[li];
+        const TileCoord tc = tile_coord_of_unit(A.g, u, local - li * A.g.tiles_per_unit);
+        fit_score_tile<DT, MASKED, true>(B, A, tc, (int)(w & (FS_WAVES - 1)), smem);
+        __syncthreads();      // the next tile overwrites this one's LDS
+    }
+}
+
 // Per unit: add the tiles' partial errors in a fixed order, pick the clip index with the
 // least error for each uniform bit-width (ties to the largest index), emit fp32.
+// REDO = false: every unit; a unit whose 8-bit error may hold too much of the short route's
+// rounding noise (see NOISE_MAX) is put on the list.  REDO = true: the listed units only,
+// after their 8-bit partials have been replaced.
 constexpr int FIN_THREADS = 1024;
 constexpr int FIN_PHASES = FIN_THREADS / 64;
+template <bool REDO>
 __global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const FitScoreArgs B) {
-    __shared__ double part[FIN_PHASES][4 * WINDQ_MAX_CLIP + 12];
-    __shared__ double E[4 * WINDQ_MAX_CLIP + 12];
+    __shared__ double part[FIN_PHASES][5 * WINDQ_MAX_CLIP + 12];
+    __shared__ double E[5 * WINDQ_MAX_CLIP + 12];
     const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
     const FitScoreMat& A = B.m[mi];
-    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
+    int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
+    if (REDO) {
+        if (u >= (int64_t)*A.redo_count) return;
+        u = A.redo_list[u];
+    }
     const int32_t K = B.K;
     const int64_t tiles_per_unit = A.g.tiles_per_unit;
     float* __restrict__ err = A.err;
@@ -582,6 +735,10 @@ __global__ __launch_bounds__(FIN_THREADS) void fit_score_finalize_kernel(const F
         }
         err[u * WINDQ_N_ERR + tid] = (float)best;
         clip_idx[u * 4 + tid] = (uint8_t)bk;
+        if (!REDO && tid == 0 && E[fit_score_noise_slot(K) + bk] * NOISE_C1 > best * best) {
+            const uint32_t pos = atomicAdd(A.redo_count, 1u);
+            A.redo_list[pos] = (uint32_t)u;
+        }
     } else if (tid < 7) {
         // ternary, binary, reference energy: the four column quarters, in order
         const int j = tid - 4;
@@ -628,17 +785,23 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
         if (st != WINDQ_OK) return st;
         if (it.s == nullptr || it.err == nullptr || it.clip_idx == nullptr) return WINDQ_EINVAL;
         if (it.W->dtype != items[0].W->dtype || (it.mask != nullptr) != masked) return WINDQ_EINVAL;   // one kernel per launch
-        if (it.ws == nullptr || it.ws_bytes < fit_score_ws_bytes(M.g, K) || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
+        const FitScoreLayout L = fit_score_layout(M.g, K);
+        if (it.ws == nullptr || it.ws_bytes < L.total || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
         M.W = it.W->data;
         M.s = it.s;
         M.mask = it.mask;
         M.mask_ld = it.W->cols / 8;
-        M.partial = static_cast<double*>(it.ws);
+        char* base = static_cast<char*>(it.ws);
+        M.partial = reinterpret_cast<double*>(base + L.partial);
+        M.redo_count = reinterpret_cast<uint32_t*>(base + L.redo_count);
+        M.redo_list = reinterpret_cast<uint32_t*>(base + L.redo_list);
         M.err = it.err;
         M.clip_idx = it.clip_idx;
         M.ref_energy = it.ref_energy;
-        // tau keeps the short route's noise in the unit's 8-bit error at 1e-6 (one sigma):
-        // 1.2e-4 sqrt(tau / (G R_u)) = 1e-6.  Below tau = 1 every column takes the exact route.
+        // tau: with the error spread evenly over R_u rows, listing the columns above tau times the
+        // mean keeps the short route's noise in the unit's 8-bit error near 1e-6 (one standard
+        // deviation; what the rows really do is measured per unit, see NOISE_MAX).  Below
+        // tau = 1 every column takes the exact route.
         const float t = 7e-5f * (float)chunk_w * (float)M.g.R_u;
         M.tau = t < 1.0f ? 0.0f : t;
         A.tile_start[i] = tiles;
@@ -656,17 +819,24 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
     const int32_t dtype = items[0].W->dtype;
     const size_t lds = fit_score_lds_bytes(dtype, chunk_w, masked);
     const dim3 grid((unsigned)tiles);
-    auto launch = [&](auto kernel) -> int {
+    auto launch = [&](auto kernel, dim3 g) -> int {
         const int e = ensure_lds(reinterpret_cast<const void*>(kernel), lds);
         if (e != WINDQ_OK) return e;
-        hipLaunchKernelGGL(kernel, grid, dim3(FS_THREADS), lds, hs, A);
-        return WINDQ_OK;
+        hipLaunchKernelGGL(kernel, g, dim3(FS_THREADS), lds, hs, A);
+        return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
     };
-    if (dtype == WINDQ_BF16) st = masked ? launch(&fit_score_kernel<WINDQ_BF16, true>) : launch(&fit_score_kernel<WINDQ_BF16, false>);
-    else st = masked ? launch(&fit_score_kernel<WINDQ_F32, true>) : launch(&fit_score_kernel<WINDQ_F32, false>);
+    const bool bf = dtype == WINDQ_BF16;
+    if (bf) st = masked ? launch(&fit_score_kernel<WINDQ_BF16, true>, grid) : launch(&fit_score_kernel<WINDQ_BF16, false>, grid);
+    else st = masked ? launch(&fit_score_kernel<WINDQ_F32, true>, grid) : launch(&fit_score_kernel<WINDQ_F32, false>, grid);
     if (st != WINDQ_OK) return st;
+    hipLaunchKernelGGL(fit_score_finalize_kernel<false>, dim3((unsigned)units), dim3(FIN_THREADS), 0, hs, A);
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
-    hipLaunchKernelGGL(fit_score_finalize_kernel, dim3((unsigned)units), dim3(FIN_THREADS), 0, hs, A);
+    // the units the finalize kernel listed: their 8-bit candidates on the exact route, finalized again
+    const dim3 redo_grid((unsigned)(tiles < FS_REDO_GRID ? tiles : FS_REDO_GRID));
+    if (bf) st = masked ? launch(&fit_score_redo_kernel<WINDQ_BF16, true>, redo_grid) : launch(&fit_score_redo_kernel<WINDQ_BF16, false>, redo_grid);
+    else st = masked ? launch(&fit_score_redo_kernel<WINDQ_F32, true>, redo_grid) : launch(&fit_score_redo_kernel<WINDQ_F32, false>, redo_grid);
+    if (st != WINDQ_OK) return st;
+    hipLaunchKernelGGL(fit_score_finalize_kernel<true>, dim3((unsigned)units), dim3(FIN_THREADS), 0, hs, A);
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     return WINDQ_OK;
 }
@@ -701,4 +871,19 @@ extern "C" int windq_fit_score_all_bits_batch(const windq_fit_item* items, int32
         its[i] = {items[i].W, items[i].s, items[i].mask, items[i].err, items[i].clip_idx, items[i].ref_energy, items[i].ws,
                   items[i].ws_bytes};
     return fit_score_launch(its, n, chunk_w, unit_rows, clip_grid, K, stream);
+}
+
+extern "C" int windq_fit_score_rescored_units(const void* ws, int32_t dtype, int64_t rows, int64_t cols, int32_t chunk_w,
+                                              int64_t unit_rows, int32_t K, int64_t* n_units) {
+    if (ws == nullptr || n_units == nullptr || K < 1 || K > WINDQ_MAX_CLIP) return WINDQ_EINVAL;
+    windq_mat fake = {ws, dtype, 0, rows, cols, cols};      // shape checks only: the data pointer is not read
+    Geometry g;
+    const int st = make_geometry(&fake, chunk_w, unit_rows, &g);
+    if (st != WINDQ_OK) return st;
+    const FitScoreLayout L = fit_score_layout(g, K);
+    uint32_t cnt = 0;
+    if (hipMemcpy(&cnt, static_cast<const char*>(ws) + L.redo_count, sizeof(cnt), hipMemcpyDeviceToHost) != hipSuccess)
+        return WINDQ_EHIP;
+    *n_units = (int64_t)cnt;
+    return WINDQ_OK;
 }

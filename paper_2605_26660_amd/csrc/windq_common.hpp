@@ -89,6 +89,21 @@ __device__ __forceinline__ TileCoord tile_coord(const Geometry& g, int64_t tile)
     return tc;
 }
 
+// Tile t of unit u.
+__device__ __forceinline__ TileCoord tile_coord_of_unit(const Geometry& g, int64_t u, int64_t t) {
+    TileCoord tc;
+    const int64_t rb = u / g.n_chunks;
+    const int64_t j = u - rb * g.n_chunks;
+    tc.t = t;
+    tc.u = u;
+    tc.lrow0 = t * TILE_ROWS;
+    tc.row0 = rb * g.R_u + tc.lrow0;
+    const int64_t left = g.R_u - tc.lrow0;
+    tc.nrows = left < TILE_ROWS ? (int32_t)left : TILE_ROWS;
+    tc.col0 = j * g.chunk_w;
+    return tc;
+}
+
 template <int DT>
 struct Elem {
     static constexpr int bytes = DT == WINDQ_BF16 ? 2 : 4;

@@ -12,13 +12,29 @@ inline size_t calib_ws_bytes(int64_t rows, int64_t cols) {
     return round_up((size_t)calib_slabs(rows) * (size_t)cols * 2 * sizeof(double), 256);
 }
 
-// ---- fit_score: per tile, one fp64 partial error per candidate
-// candidates: [b][k] for b in 8,4,3,2 (index b*K + k), then for each quarter of the chunk's
-// columns: ternary, binary, reference energy
-__host__ __device__ inline int32_t fit_score_ncand(int32_t K) { return 4 * K + 12; }
-inline size_t fit_score_ws_bytes(const Geometry& g, int32_t K) {
-    return round_up((size_t)g.n_tiles * (size_t)fit_score_ncand(K) * sizeof(double), 256);
+// ---- fit_score: per tile, one fp64 partial per candidate, then the list of units whose 8-bit
+// candidate is scored again on the exact route
+// candidates: [b][k] for b in 8,4,3,2 (index b*K + k); then for each quarter of the chunk's
+// columns: ternary, binary, reference energy (12 slots); then [k] the variance term of the
+// 8-bit short route's rounding noise at clip index k
+__host__ __device__ inline int32_t fit_score_ncand(int32_t K) { return 5 * K + 12; }
+__host__ __device__ inline int32_t fit_score_noise_slot(int32_t K) { return 4 * K + 12; }
+struct FitScoreLayout {
+    size_t partial;      // [n_tiles][ncand] fp64
+    size_t redo_count;   // u32: units on the list
+    size_t redo_list;    // [U] u32
+    size_t total;
+};
+inline FitScoreLayout fit_score_layout(const Geometry& g, int32_t K) {
+    FitScoreLayout L;
+    size_t pos = 0;
+    L.partial = pos;     pos = round_up(pos + (size_t)g.n_tiles * (size_t)fit_score_ncand(K) * sizeof(double), 256);
+    L.redo_count = pos;  pos += 256;
+    L.redo_list = pos;   pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.total = pos;
+    return L;
 }
+inline size_t fit_score_ws_bytes(const Geometry& g, int32_t K) { return fit_score_layout(g, K).total; }
 
 // ---- unit_features
 // A workgroup covers FEAT_TPB consecutive tiles of one unit ("block" below).

@@ -73,6 +73,7 @@ enum windq_call {
 #define WINDQ_MAX_CLIP 64    /* longest clip grid */
 #define WINDQ_MAX_CHUNK 512  /* widest chunk */
 #define WINDQ_MAX_BATCH 8    /* most matrices one *_batch call takes */
+#define WINDQ_STATIC_SCRATCH_BYTES (8u << 20) /* workspace built into the library for windq_fit_score_all_bits_static */
 
 /* A row-major matrix in device memory.  Never written by the library. */
 typedef struct windq_mat {
@@ -156,6 +157,28 @@ int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int3
                              const float* clip_grid /*HOST [K]*/, int32_t K,
                              float* err /*[U][6]*/, uint8_t* clip_idx /*[U][4]*/, float* ref_energy /*[U] or NULL*/,
                              void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * windq_fit_score_all_bits for callers that can neither allocate device memory nor bring a
+ * workspace: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The workspace is an array of WINDQ_STATIC_SCRATCH_BYTES built into the library's
+ * device code (every GPU the process uses holds its own copy until the process ends); its device
+ * address is looked up once per device, on the first call made with that device current.  The
+ * call allocates and frees nothing.  Same arguments, outputs and results (bit for bit) as
+ * windq_fit_score_all_bits without `ws`.
+ *   WINDQ_EWORKSPACE  the shape needs more than WINDQ_STATIC_SCRATCH_BYTES (check beforehand with
+ *                     windq_workspace_bytes(WINDQ_CALL_FIT_SCORE, ...)): nothing is launched.
+ *                     The need is 8 (5K + 12) bytes per 64-row tile of a chunk plus 4 per unit:
+ *                     4.9 MB for 4096 x 11008 or 11008 x 4096 at chunk 128, K = 20.
+ *   WINDQ_EHIP        the address lookup failed.
+ * All calls on one GPU share that GPU's array and it keeps the previous call's contents (every
+ * slot a call reads it writes first): calls that overlap in time on one GPU - on different
+ * streams, or from different threads - race.  Calls on one stream are ordered and safe.
+ */
+int windq_fit_score_all_bits_static(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                                    const float* clip_grid /*HOST [K]*/, int32_t K,
+                                    float* err /*[U][6]*/, uint8_t* clip_idx /*[U][4]*/, float* ref_energy /*[U] or NULL*/,
+                                    void* stream);
 
 /*
  * Diagnostic: how many units of the last windq_fit_score_all_bits (or _prot, or batch item) call

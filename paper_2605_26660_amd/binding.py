@@ -18,6 +18,7 @@ WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP
 WINDQ_F32, WINDQ_BF16 = 0, 1
 CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT, CALL_REFINE = range(8)
 N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK, MAX_BATCH = 7, 6, 8, 64, 512, 8
+STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = (
     "windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_bytes_per_group",
@@ -26,6 +27,7 @@ EXPORTS = (
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
     "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan", "windq_fit_score_all_bits_batch",
     "windq_unit_features_batch", "windq_apply_plan_batch", "windq_calib_stats_batch", "windq_fit_score_rescored_units",
+    "windq_fit_score_all_bits_static",
 )
 
 
@@ -107,6 +109,8 @@ def load(path: str | None = None):
     lib.windq_unit_features_batch.argtypes = [c.POINTER(windq_feat_item), i32, i32, i64, vp]
     lib.windq_apply_plan_batch.argtypes = [c.POINTER(windq_apply_item), i32, i32, i64, vp, i32, vp]
     lib.windq_calib_stats_batch.argtypes = [c.POINTER(windq_calib_item), i32, vp]
+    lib.windq_fit_score_all_bits_static.argtypes = [pm, vp, i32, i64, vp, i32, vp, vp, vp, vp]
+    lib.windq_fit_score_all_bits_static.restype = c.c_int
     lib.windq_fit_score_rescored_units.argtypes = [vp, i32, i64, i64, i32, i64, i32, c.POINTER(i64)]
     lib.windq_fit_score_rescored_units.restype = c.c_int
     lib.windq_status_str.argtypes = [c.c_int]
@@ -300,6 +304,20 @@ def windq_fit_score_all_bits_batch(Ws, ss, chunk_w: int, unit_rows: int, clip_gr
     _check(load().windq_fit_score_all_bits_batch(items, n, chunk_w, unit_rows, clip_grid.data_ptr(), K, _stream()),
            "windq_fit_score_all_bits_batch")
     return res
+
+
+def windq_fit_score_all_bits_static(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor,
+                                    out):
+    """windq_fit_score_all_bits on the workspace built into the library: `out` = (err, clip_idx, ref_energy) is
+    caller-allocated, nothing is allocated here or in the library."""
+    _require_cuda(W, s, *out)
+    assert not clip_grid.is_cuda and clip_grid.dtype == torch.float32 and clip_grid.is_contiguous()
+    err, clip_idx, ref = out
+    m = as_mat(W)
+    _check(load().windq_fit_score_all_bits_static(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, clip_grid.data_ptr(),
+                                                  clip_grid.numel(), err.data_ptr(), clip_idx.data_ptr(), ref.data_ptr(),
+                                                  _stream()), "windq_fit_score_all_bits_static")
+    return err, clip_idx, ref
 
 
 def windq_fit_score_rescored_units(ws: torch.Tensor, W: torch.Tensor, chunk_w: int, unit_rows: int, K: int) -> int:

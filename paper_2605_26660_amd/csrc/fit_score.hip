@@ -54,6 +54,7 @@
 // (about 1e-18 .. 1e18); smaller products contribute zero.
 #include <float.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "windq_common.hpp"
@@ -871,6 +872,48 @@ extern "C" int windq_fit_score_all_bits_batch(const windq_fit_item* items, int32
         its[i] = {items[i].W, items[i].s, items[i].mask, items[i].err, items[i].clip_idx, items[i].ref_energy, items[i].ws,
                   items[i].ws_bytes};
     return fit_score_launch(its, n, chunk_w, unit_rows, clip_grid, K, stream);
+}
+
+// Scratch memory of windq_fit_score_all_bits_static: the workspace of one call, held by every
+// GPU the library runs on until the process ends.  In host code the array's name is only a
+// stand-in: its device address is looked up once per device (below) and used from then on.
+static __device__ __align__(256) unsigned char scratch[WINDQ_STATIC_SCRATCH_BYTES];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[STATIC_MAX_DEVICES];      // per device, nullptr until looked up
+
+// Device address of `scratch` on the current device.
+static int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return WINDQ_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return WINDQ_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return WINDQ_OK;
+}
+
+extern "C" int windq_fit_score_all_bits_static(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
+                                               const float* clip_grid, int32_t K, float* err, uint8_t* clip_idx,
+                                               float* ref_energy, void* stream) {
+    if (W == nullptr) return WINDQ_EINVAL;
+    int st = check_clip_grid(clip_grid, K);
+    if (st != WINDQ_OK) return st;
+    Geometry g;
+    st = make_geometry(W, chunk_w, unit_rows, &g);
+    if (st != WINDQ_OK) return st;
+    if (fit_score_ws_bytes(g, K) > (size_t)WINDQ_STATIC_SCRATCH_BYTES) return WINDQ_EWORKSPACE;
+    void* ptr = nullptr;
+    st = static_scratch(&ptr);
+    if (st != WINDQ_OK) return st;
+    // Every slot of the workspace that a call reads is written by that call first (the kernels
+    // clear the one counter themselves), so what the previous call left behind does not matter.
+    return fit_score_impl(W, s, chunk_w, unit_rows, nullptr, clip_grid, K, err, clip_idx, ref_energy, ptr,
+                          (size_t)WINDQ_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int windq_fit_score_rescored_units(const void* ws, int32_t dtype, int64_t rows, int64_t cols, int32_t chunk_w,

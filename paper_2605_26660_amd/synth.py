@@ -116,27 +116,29 @@ POLICY_MIX = (0.0865 / 4, 0.0865 / 4, 0.0865 / 4, 0.0865 / 4, 0.1565, 0.3654, 0.
 _CENTIBITS = (1600, 800, 400, 300, 200, 158, 100)
 
 
-def random_plan(n_units: int, weights_per_unit: int, target_centibits: int, seed: int) -> torch.Tensor:
+def random_plan(n_units: int, weights_per_unit, target_centibits: int, seed: int) -> torch.Tensor:
     """A random plan that meets the budget: draw actions from POLICY_MIX, then demote
     randomly chosen units one level (toward 1 bit) until the nominal total fits.
-    Returns uint8 [n_units] on the host."""
+    weights_per_unit: one size for all units, or a sequence of n_units sizes (units of
+    several matrices in one plan).  Returns uint8 [n_units] on the host."""
     g = _gen(seed, "cpu")
     probs = torch.tensor(POLICY_MIX, dtype=torch.float64)
-    action = torch.multinomial(probs, n_units, replacement=True, generator=g).to(torch.int64)
-    cb = torch.tensor(_CENTIBITS, dtype=torch.int64)
-    total = int(cb[action].sum()) * weights_per_unit
-    budget = target_centibits * n_units * weights_per_unit
+    action = torch.multinomial(probs, n_units, replacement=True, generator=g).tolist()
+    sizes = [int(weights_per_unit)] * n_units if isinstance(weights_per_unit, int) else [int(x) for x in weights_per_unit]
+    assert len(sizes) == n_units
+    total = sum(_CENTIBITS[a] * n for a, n in zip(action, sizes))
+    budget = target_centibits * sum(sizes)
     order = torch.randperm(n_units, generator=g).tolist()
     i = 0
     stalled = 0
     while total > budget and stalled < n_units:
         u = order[i % n_units]
-        a = int(action[u])
+        a = action[u]
         if a < 6:
-            total -= int(cb[a] - cb[a + 1]) * weights_per_unit
+            total -= (_CENTIBITS[a] - _CENTIBITS[a + 1]) * sizes[u]
             action[u] = a + 1
             stalled = 0
         else:
             stalled += 1
         i += 1
-    return action.to(torch.uint8)
+    return torch.tensor(action, dtype=torch.uint8)

@@ -337,6 +337,46 @@ def test_clip_choice_is_argmin_with_ties_to_least_clipping():
     assert np.array_equal(sub[0], table[3])
 
 
+@pytest.mark.parametrize("bits", [8, 4, 3, 2])
+def test_clip_grid_against_a_dense_scan_of_clip_ratios(bits):
+    """The clip search written out independently: for 2,001 clip ratios in [0.5, 1] (the 20 grid points among
+    them), the unit's error with lo = p*min, step = p*(max-min)/(2^b-1) taken in fp64 and every weight sent to
+    its nearest grid point by brute force.  At the shared points the oracle's table equals that scan; its
+    choice is the scan's minimum restricted to the grid; and the dense scan, which contains the grid, is never
+    worse than it."""
+    r = rng(90 + bits)
+    R, G, K = 6, 16, 20
+    W = (0.02 * r.standard_normal((R, G))).astype(f32)
+    W[:, 5] *= 6.0                                              # an outlier column: clipping pays at low bits
+    s = (0.2 + r.random(G)).astype(f32)
+    a = s.astype(np.float64) ** 2
+    grid = (0.5 + 0.5 * np.arange(K) / (K - 1)).astype(f32)
+    dense = np.unique(np.concatenate([np.linspace(0.5, 1.0, 2001), grid.astype(np.float64)]))
+    assert len(dense) >= 2001
+    qmax = 2 ** bits - 1
+    W64 = W.astype(np.float64)
+    mn, mx = W64.min(axis=1), W64.max(axis=1)
+
+    def scan_error(p):
+        total = 0.0
+        for g in range(R):
+            lo, step = p * mn[g], p * (mx[g] - mn[g]) / qmax
+            total += brute_force_uniform_sse(W64[g], lo, step, qmax, a)
+        return total
+
+    E_dense = np.array([scan_error(p) for p in dense])
+    E, _, _, _ = O.fit_score_unit(W, s, grid)
+    bi = O.UNIFORM_BITS.index(bits)
+    at_grid = np.array([E_dense[np.searchsorted(dense, float(pk))] for pk in grid])
+    assert np.allclose(E[bi], at_grid, rtol=1e-7 * qmax + 1e-6, atol=0)      # fp32 scale/offset against fp64 ones (96 weights)
+    k_scan = int(np.nonzero(at_grid == at_grid.min())[0][-1])
+    k_orc = O.argmin_clip(E[bi])
+    assert k_orc == k_scan or at_grid[k_orc] <= at_grid.min() * (1 + 1e-4)
+    assert E_dense.min() <= at_grid.min() * (1 + 1e-12)
+    # the grid is not a bad sample of the curve: its best point is within a few percent of the dense optimum
+    assert E[bi].min() <= E_dense.min() * 1.25
+
+
 # --------------------------------------------------------------- O4 packing / plan
 def read_pack_golden():
     rows = []

@@ -80,27 +80,30 @@ class CallTimer:
         return [e0.elapsed_time(e1) for e0, e1 in self.pairs.get(name, [])]
 
 
-def timed_steps(torch, stack, steps, warmup, per_matrix):
+def timed_steps(torch, stack, steps, warmup, per_matrix, fused=True):
     """W untimed steps, then K timed ones; only the dominant call carries events (for the roofline)."""
     for _ in range(warmup):
-        stack.run_step(per_matrix=per_matrix)
+        stack.run_step(per_matrix=per_matrix, fused=fused)
     torch.cuda.synchronize()
-    fit_timer = CallTimer(torch, only=("fit_score_all_bits",))
+    import paper_2605_26660_amd as wq
+    wq.windq_kernel_timer(True)          # an event pair around every launch of the main fit+score kernel (roofline)
     t0 = time.perf_counter()
     for _ in range(steps):
-        total_cb, total_n = stack.run_step(fit_timer, per_matrix=per_matrix)
+        total_cb, total_n = stack.run_step(per_matrix=per_matrix, fused=fused)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    fit_ms = fit_timer.ms("fit_score_all_bits")
-    return dt / steps * 1e3, fit_ms, total_cb, total_n
+    kernel_ms, n_launch = wq.windq_kernel_timer_read()
+    wq.windq_kernel_timer(False)
+    return dt / steps * 1e3, (kernel_ms, n_launch), total_cb, total_n
 
 
-def per_call_pass(torch, stack, steps, per_matrix):
+def per_call_pass(torch, stack, steps, per_matrix, fused=True):
     """The same steps with an event pair around every call (the pairs stretch a step, so this pass does
-    not count toward `value`)."""
+    not count toward `value`).  With the fused call, "fit_score_all_bits" is windq_features_fit_score: fit+score
+    with the unit features taken from the same read of W (their later passes included)."""
     timer = CallTimer(torch)
     for _ in range(steps):
-        stack.run_step(timer, per_matrix=per_matrix)
+        stack.run_step(timer, per_matrix=per_matrix, fused=fused)
     torch.cuda.synchronize()
     code_bytes = stack.code_bytes + stack.meta_bytes()
     call_bytes = {"calib_stats": stack.n_activations * stack.blocks[0].mats[0].W.element_size(),
@@ -110,6 +113,8 @@ def per_call_pass(torch, stack, steps, per_matrix):
     calls = {}
     for name, nbytes in call_bytes.items():
         ms = timer.ms(name)
+        if not ms:
+            continue
         n_per_step = len(ms) // steps
         steps_ms = sorted(sum(ms[i * n_per_step:(i + 1) * n_per_step]) for i in range(steps))
         med = steps_ms[len(steps_ms) // 2]
@@ -121,11 +126,14 @@ def per_call_pass(torch, stack, steps, per_matrix):
     return calls
 
 
-def roofline(stack, fit_ms, steps, per_matrix):
-    """fit_score_kernel against the fp32 vector peak: algorithmic flops of one launch / its duration between
-    events (the pair also spans the finalize kernel and the two launches of the second 8-bit pass)."""
-    n_launch = len(fit_ms) // steps
-    avg_ms = sum(fit_ms) / len(fit_ms)
+def roofline(stack, fit_ms, steps, per_matrix, fused=True):
+    """The main fit+score kernel against the fp32 vector peak: algorithmic flops of one launch / its duration
+    between a pair of HIP events that the library records around that kernel alone (windq_kernel_timer), over
+    the timed region.  With the fused call the kernel also makes the first pass of the unit features; its flops
+    (2 per weight for the sums of w and w^2) are not counted."""
+    kernel_ms, total_launches = fit_ms
+    n_launch = total_launches // steps
+    avg_ms = kernel_ms / total_launches
     w_per_launch = stack.n_weights / n_launch
     flops = fit_score_flops_per_weight(stack.K)
     achieved = flops * w_per_launch / (avg_ms * 1e-3) / 1e12
@@ -138,7 +146,8 @@ def roofline(stack, fit_ms, steps, per_matrix):
             "traffic": traffic if same_shape else None,
             "traffic_source": "profiles/hot_path_7b_block_pmc_traffic.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; bytes per launch)",
             "algorithmic_bytes_per_launch": w_per_launch * es,
-            "kernel": "fit_score_kernel (+ finalize and the second 8-bit pass), %d launch%s per step: %s" % (
+            "kernel": "fit_score_kernel%s, %d launch%s per step: %s" % (
+                " (with the first pass of the unit features: windq_features_fit_score)" if fused else "",
                 n_launch, "es" if n_launch > 1 else "", "one per matrix" if per_matrix else "one per decoder block"),
             "avg_launch_ms": avg_ms, "flops_per_weight": flops,
             "weight_GBps": w_per_launch * es / (avg_ms * 1e-3) / 1e9,
@@ -147,15 +156,15 @@ def roofline(stack, fit_ms, steps, per_matrix):
             "clip_grid_knee_K": profile_value("fit_score_clip_sweep.txt", "KNEE_K")}
 
 
-def one_block(torch, stack, steps, warmup):
+def one_block(torch, stack, steps, warmup, fused=True):
     """Block 0 alone, re-timed on the same buffers (405 MB of weights at the 7B shape: larger than the
     last-level cache, but the small inputs and outputs stay warm, and a launch per kernel is all there is)."""
     sub = stack.subset([0])
-    ms, fit_ms, _, _ = timed_steps(torch, sub, steps, warmup, False)
+    ms, fit_ms, _, _ = timed_steps(torch, sub, steps, warmup, False, fused)
     es = stack.blocks[0].mats[0].W.element_size()
-    fit = sum(fit_ms) / len(fit_ms)
+    fit = fit_ms[0] / fit_ms[1]
     return {"weights": sub.n_weights, "units": sub.n_units, "ms_per_step": ms, "GBps": sub.n_weights * es / (ms * 1e-3) / 1e9,
-            "fit_score_ms": fit, "fit_score_GBps": sub.n_weights * es / (fit * 1e-3) / 1e9,
+            "fit_score_kernel_ms": fit, "fit_score_GBps": sub.n_weights * es / (fit * 1e-3) / 1e9,
             "fit_score_frac_of_fp32_peak": fit_score_flops_per_weight(stack.K) * sub.n_weights / (fit * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS}
 
 
@@ -321,6 +330,9 @@ def main():
     ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--per-matrix", action="store_true",
                     help="one call per matrix instead of the *_batch entry points (one call per kernel and block)")
+    ap.add_argument("--separate-features", action="store_true",
+                    help="windq_unit_features and windq_fit_score_all_bits as two calls (W read twice more) instead of "
+                         "windq_features_fit_score")
     ap.add_argument("--protect-ppm", type=int, default=30000,
                     help="also time block 0 under salient-weight protection at this rate (parts per million; 0 = skip)")
     ap.add_argument("--clip-sweep", action="store_true",
@@ -364,7 +376,8 @@ def main():
     for G in widths:
         stack.prepare(G, args.unit_rows)
         stack.set_plan()
-        ms_per_step, fit_ms, total_cb, total_n = timed_steps(torch, stack, args.steps, args.warmup, args.per_matrix)
+        fused = not args.separate_features
+        ms_per_step, fit_ms, total_cb, total_n = timed_steps(torch, stack, args.steps, args.warmup, args.per_matrix, fused)
         stack.run_step_totals = (total_cb, total_n)
         es = stack.blocks[0].mats[0].W.element_size()
         r = {
@@ -373,11 +386,11 @@ def main():
             "avg_bits": total_cb / (100.0 * total_n), "target_bits": stack.target_centibits / 100.0,
             "budget_met": total_cb <= stack.target_centibits * total_n,
             "packed_code_bytes": stack.code_bytes, "scale_offset_bytes": stack.meta_bytes(),
-            "roofline": roofline(stack, fit_ms, args.steps, args.per_matrix),
-            "calls": per_call_pass(torch, stack, max(1, min(args.steps, 5)), args.per_matrix),
+            "roofline": roofline(stack, fit_ms, args.steps, args.per_matrix, fused),
+            "calls": per_call_pass(torch, stack, max(1, min(args.steps, 5)), args.per_matrix, fused),
         }
         if len(stack.blocks) > 1 and not args.per_matrix:
-            r["one_block"] = one_block(torch, stack, max(args.steps, 20), 10)
+            r["one_block"] = one_block(torch, stack, max(args.steps, 20), 10, fused)
         if args.protect_ppm > 0 and G == widths[-1]:
             r["protected"] = protected_pass(wq, torch, stack, args.protect_ppm, 5)
         if args.clip_sweep and G == widths[-1]:
@@ -402,6 +415,7 @@ def main():
                                    "bf16" if cfg.dtype == torch.bfloat16 else "fp32", head["chunk_w"], stack.K, cfg.tokens,
                                    cfg.target_centibits / 100.0),
                    "launches": "per matrix" if args.per_matrix else "batched (one launch per kernel and decoder block)",
+                   "features": "separate call" if args.separate_features else "fused into fit+score (windq_features_fit_score)",
                    "weights": stack.n_weights, "blocks": n_blocks, "units": head["units"], "unit_rows": args.unit_rows,
                    "chunk_w": head["chunk_w"], "K": stack.K, "resident_weight_bytes": stack.n_weights * es,
                    "generate_seconds": t_build},

@@ -64,7 +64,8 @@ enum windq_call {
     WINDQ_CALL_SALIENT = 4,       /* windq_salient_select and windq_salient_encode */
     WINDQ_CALL_UNIT_SALIENCY = 5,
     WINDQ_CALL_DEQUANT = 6,
-    WINDQ_CALL_REFINE = 7
+    WINDQ_CALL_REFINE = 7,
+    WINDQ_CALL_FEATURES_FIT_SCORE = 8
 };
 
 #define WINDQ_N_ACTIONS 7
@@ -181,6 +182,19 @@ int windq_fit_score_all_bits_static(const windq_mat* W, const float* s /*[cols]*
                                     void* stream);
 
 /*
+ * Profiling aid for the dominant kernel.  windq_kernel_timer(1) switches it on: from then on every
+ * launch of the main fit+score kernel (by any of the fit+score entry points, the fused ones included)
+ * is bracketed by a pair of HIP events on the launch stream, so that the kernel's own duration can be
+ * told apart from the small kernels that follow it in the same call.  windq_kernel_timer_read waits
+ * for the recorded launches, returns the sum of their durations in milliseconds and their number, and
+ * forgets them.  windq_kernel_timer(0) switches it off.  Off by default.  While it is on the library
+ * creates events (host-side state, nothing on the device) and must not be used under graph capture;
+ * windq_kernel_timer_read waits for the device.  HOST only.
+ */
+int windq_kernel_timer(int32_t enable);
+int windq_kernel_timer_read(double* total_ms /*HOST*/, int64_t* launches /*HOST*/);
+
+/*
  * Diagnostic: how many units of the last windq_fit_score_all_bits (or _prot, or batch item) call
  * that used workspace `ws` had their 8-bit candidates scored a second time on the exact route.
  * Pass the shape arguments of that call.  Unlike every other entry point this one copies a
@@ -225,6 +239,31 @@ typedef struct windq_fit_item {
     size_t ws_bytes;
 } windq_fit_item;
 int windq_fit_score_all_bits_batch(const windq_fit_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w,
+                                   int64_t unit_rows, const float* clip_grid /*HOST [K]*/, int32_t K, void* stream);
+
+/*
+ * windq_unit_features and windq_fit_score_all_bits from ONE read of W (Table 1 and Sec. 3.5 are both
+ * per-unit work on the same weights): the fit+score kernel, which holds every tile in LDS anyway,
+ * also takes the moments, the count of |w| < 1e-6 and the first-digit histogram of |w| from it; the
+ * feature kernels that refine P99 and finish follow on the stream.  Outputs are bit for bit those of
+ * the two separate calls.  Workspace: windq_workspace_bytes(WINDQ_CALL_FEATURES_FIT_SCORE, ...).
+ * The batch form is to this call what windq_fit_score_all_bits_batch is to the per-matrix one.
+ */
+int windq_features_fit_score(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
+                             const float* clip_grid /*HOST [K]*/, int32_t K,
+                             float* feat /*[U][8]*/, float* err /*[U][6]*/, uint8_t* clip_idx /*[U][4]*/,
+                             float* ref_energy /*[U] or NULL*/, void* ws, size_t ws_bytes, void* stream);
+typedef struct windq_fused_item {
+    const windq_mat* W;     /* HOST descriptor of a device matrix */
+    const float* s;         /* [cols] */
+    float* feat;            /* [U][8] */
+    float* err;             /* [U][6] */
+    uint8_t* clip_idx;      /* [U][4] */
+    float* ref_energy;      /* [U] or NULL */
+    void* ws;
+    size_t ws_bytes;
+} windq_fused_item;
+int windq_features_fit_score_batch(const windq_fused_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w,
                                    int64_t unit_rows, const float* clip_grid /*HOST [K]*/, int32_t K, void* stream);
 
 /* Packed bytes of one group under an action: ceil(chunk_w*b/8), ceil(chunk_w/5) for

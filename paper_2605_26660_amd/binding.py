@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libwindq.so")
 
 WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP = range(6)
 WINDQ_F32, WINDQ_BF16 = 0, 1
-CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT, CALL_REFINE = range(8)
+CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT, CALL_REFINE, CALL_FEATURES_FIT_SCORE = range(9)
 N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK, MAX_BATCH = 7, 6, 8, 64, 512, 8
 STATIC_SCRATCH_BYTES = 8 << 20
 
@@ -27,7 +27,8 @@ EXPORTS = (
     "windq_fit_score_all_bits_prot", "windq_apply_plan_prot", "windq_unit_saliency", "windq_heuristic_plan",
     "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan", "windq_fit_score_all_bits_batch",
     "windq_unit_features_batch", "windq_apply_plan_batch", "windq_calib_stats_batch", "windq_fit_score_rescored_units",
-    "windq_fit_score_all_bits_static",
+    "windq_fit_score_all_bits_static", "windq_features_fit_score", "windq_features_fit_score_batch",
+    "windq_kernel_timer", "windq_kernel_timer_read",
 )
 
 
@@ -45,6 +46,12 @@ class windq_mat(ctypes.Structure):
 
 class windq_fit_item(ctypes.Structure):
     _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("mask", ctypes.c_void_p),
+                ("err", ctypes.c_void_p), ("clip_idx", ctypes.c_void_p), ("ref_energy", ctypes.c_void_p),
+                ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
+
+
+class windq_fused_item(ctypes.Structure):
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("feat", ctypes.c_void_p),
                 ("err", ctypes.c_void_p), ("clip_idx", ctypes.c_void_p), ("ref_energy", ctypes.c_void_p),
                 ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
@@ -109,6 +116,14 @@ def load(path: str | None = None):
     lib.windq_unit_features_batch.argtypes = [c.POINTER(windq_feat_item), i32, i32, i64, vp]
     lib.windq_apply_plan_batch.argtypes = [c.POINTER(windq_apply_item), i32, i32, i64, vp, i32, vp]
     lib.windq_calib_stats_batch.argtypes = [c.POINTER(windq_calib_item), i32, vp]
+    lib.windq_features_fit_score.argtypes = [pm, vp, i32, i64, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.windq_features_fit_score.restype = c.c_int
+    lib.windq_features_fit_score_batch.argtypes = [c.POINTER(windq_fused_item), i32, i32, i64, vp, i32, vp]
+    lib.windq_features_fit_score_batch.restype = c.c_int
+    lib.windq_kernel_timer.argtypes = [i32]
+    lib.windq_kernel_timer.restype = c.c_int
+    lib.windq_kernel_timer_read.argtypes = [c.POINTER(c.c_double), c.POINTER(i64)]
+    lib.windq_kernel_timer_read.restype = c.c_int
     lib.windq_fit_score_all_bits_static.argtypes = [pm, vp, i32, i64, vp, i32, vp, vp, vp, vp]
     lib.windq_fit_score_all_bits_static.restype = c.c_int
     lib.windq_fit_score_rescored_units.argtypes = [vp, i32, i64, i64, i32, i64, i32, c.POINTER(i64)]
@@ -306,6 +321,53 @@ def windq_fit_score_all_bits_batch(Ws, ss, chunk_w: int, unit_rows: int, clip_gr
     return res
 
 
+def windq_features_fit_score(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor,
+                             ws: torch.Tensor | None = None, out=None):
+    """Unit features and fit+score from one read of W.  -> (feat [U x 8], err [U x 6], clip_idx [U x 4], ref_energy [U])."""
+    _require_cuda(W, s)
+    assert not clip_grid.is_cuda and clip_grid.dtype == torch.float32 and clip_grid.is_contiguous()
+    K = clip_grid.numel()
+    U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    if out is None:
+        out = (torch.empty(U, N_FEAT, dtype=torch.float32, device=W.device), torch.empty(U, N_ERR, dtype=torch.float32, device=W.device),
+               torch.empty(U, 4, dtype=torch.uint8, device=W.device), torch.empty(U, dtype=torch.float32, device=W.device))
+    feat, err, clip_idx, ref = out
+    ws = _workspace(CALL_FEATURES_FIT_SCORE, W, chunk_w, unit_rows, K, ws)
+    m = as_mat(W)
+    _check(load().windq_features_fit_score(ctypes.byref(m), s.data_ptr(), chunk_w, unit_rows, clip_grid.data_ptr(), K,
+                                           feat.data_ptr(), err.data_ptr(), clip_idx.data_ptr(), ref.data_ptr(),
+                                           ws.data_ptr(), ws.numel(), _stream()), "windq_features_fit_score")
+    return feat, err, clip_idx, ref
+
+
+def windq_features_fit_score_batch(Ws, ss, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor, wss=None, outs=None):
+    """windq_features_fit_score for several matrices (at most MAX_BATCH) with one launch per kernel.
+    -> list of (feat, err, clip_idx, ref_energy)."""
+    n = len(Ws)
+    assert len(ss) == n and (wss is None or len(wss) == n) and (outs is None or len(outs) == n)
+    _require_cuda(*Ws, *ss)
+    assert not clip_grid.is_cuda and clip_grid.dtype == torch.float32 and clip_grid.is_contiguous()
+    K = clip_grid.numel()
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_fused_item * max(n, 1))()
+    res, keep = [], []
+    for i, (W, s) in enumerate(zip(Ws, ss)):
+        U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+        if outs is None:
+            o = (torch.empty(U, N_FEAT, dtype=torch.float32, device=W.device), torch.empty(U, N_ERR, dtype=torch.float32, device=W.device),
+                 torch.empty(U, 4, dtype=torch.uint8, device=W.device), torch.empty(U, dtype=torch.float32, device=W.device))
+        else:
+            o = outs[i]
+        ws = _workspace(CALL_FEATURES_FIT_SCORE, W, chunk_w, unit_rows, K, None if wss is None else wss[i])
+        keep.append(ws)
+        items[i] = windq_fused_item(ctypes.pointer(mats[i]), s.data_ptr(), o[0].data_ptr(), o[1].data_ptr(), o[2].data_ptr(),
+                                    o[3].data_ptr(), ws.data_ptr(), ws.numel())
+        res.append(o)
+    _check(load().windq_features_fit_score_batch(items, n, chunk_w, unit_rows, clip_grid.data_ptr(), K, _stream()),
+           "windq_features_fit_score_batch")
+    return res
+
+
 def windq_fit_score_all_bits_static(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int, clip_grid: torch.Tensor,
                                     out):
     """windq_fit_score_all_bits on the workspace built into the library: `out` = (err, clip_idx, ref_energy) is
@@ -318,6 +380,18 @@ def windq_fit_score_all_bits_static(W: torch.Tensor, s: torch.Tensor, chunk_w: i
                                                   clip_grid.numel(), err.data_ptr(), clip_idx.data_ptr(), ref.data_ptr(),
                                                   _stream()), "windq_fit_score_all_bits_static")
     return err, clip_idx, ref
+
+
+def windq_kernel_timer(enable: bool):
+    """Switch the event pairs around every main fit+score kernel launch on or off (profiling aid)."""
+    _check(load().windq_kernel_timer(1 if enable else 0), "windq_kernel_timer")
+
+
+def windq_kernel_timer_read():
+    """-> (sum of the main fit+score kernel's durations in ms, number of launches) since the last read; waits for the device."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(load().windq_kernel_timer_read(ctypes.byref(ms), ctypes.byref(n)), "windq_kernel_timer_read")
+    return ms.value, n.value
 
 
 def windq_fit_score_rescored_units(ws: torch.Tensor, W: torch.Tensor, chunk_w: int, unit_rows: int, K: int) -> int:

@@ -56,8 +56,11 @@
 
 #include <mutex>
 #include <type_traits>
+#include <utility>
+#include <vector>
 
 #include "windq_common.hpp"
+#include "windq_feat.hpp"
 #include "windq_ws.hpp"
 
 namespace windq {
@@ -68,7 +71,12 @@ constexpr int FS_KB = 5;                    // clip ratios evaluated together by
 constexpr int FS_NRED = FS_KB * 5;          // per-lane sums a pass produces: 4 errors + 1 noise term per clip ratio
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
 constexpr int FS_HMAX = WINDQ_MAX_CHUNK / 8;   // most columns a tile may send down the exact 8-bit route on their own
-constexpr int FS_REDO_GRID = 1024;          // workgroups of the launch that scores listed units again
+constexpr int FS_REDO_GRID = 1024;
+// What a pass over a tile does.
+constexpr int FS_SCORE = 0;         // every candidate quantizer
+constexpr int FS_ONLY8 = 1;         // the 8-bit candidates alone, exact route (listed units)
+constexpr int FS_SCORE_FEAT = 2;    // every candidate, and the first pass of the unit features (Table 1)
+constexpr int FS_FEAT_ONLY = 3;     // that first pass alone          // workgroups of the launch that scores listed units again
 
 // The short route's rounding noise in a unit's 8-bit error.  On the short route the residual
 // r' = s_c (w - lo - code*step) carries three roundings taken at magnitudes of at most
@@ -103,6 +111,10 @@ struct FitScoreMat {
     float* ref_energy;
     Geometry g;
     float tau;         // columns with s_c^2 > tau * mean(s^2) of the chunk take the exact 8-bit route; 0: all do
+    // first pass of the unit features (FS_SCORE_FEAT, FS_FEAT_ONLY), else unused
+    double* fmoments;      // [n_tiles][4 column quarters][4]: sum w, sum w^2, sum |w|, count(|w| < 1e-6)
+    uint32_t* fhist;       // [U][FEAT_BINS]: histogram of the first radix digit of |w|
+    float sparse_thr;      // smallest fp32 that is >= 1e-6
 };
 
 // A launch covers up to WINDQ_MAX_BATCH matrices of one chunk width and element type: their
@@ -328,14 +340,24 @@ __device__ __forceinline__ double rows_sum(const float (&v)[N], float* __restric
     return tot;
 }
 
-// One tile: all candidates (ONLY8 = false), or the 8-bit candidates alone on the exact route
-// (ONLY8 = true: the pass over listed units; every other partial of the tile stays as it is).
+// One tile in one of the FS_* modes.  FS_ONLY8 leaves every other partial of the tile as it is.
+// The feature modes add, in the scan that finds the groups' min / max / sum |w| anyway: per
+// wavefront (column quarter) the sums of w and w^2 (fp32 per lane over <= 128 weights, products
+// of bf16 are exact; fp64 beyond), the count of |w| < 1e-6, and the tile's histogram of the
+// first radix digit of |w| (bits 20-30 of the fp32 pattern: exponent + 3 mantissa bits, for
+// bf16 the first 11 of its 15 magnitude bits) in LDS -- 2048 bins of 16 bits, two to a dword,
+// in the space the row-combining scratch uses later -- which is then added to the unit's
+// histogram in global memory (integer atomics: order does not matter).
 // MASKED: salient weights (Sec. 3.5) marked in A.mask take no part: they are left out of
 // the group statistics, and in every error sum their activation scale counts as zero.
 // rot spreads an uneven number of clip passes over the four SIMDs from tile to tile.
-template <int DT, bool MASKED, bool ONLY8>
+template <int DT, bool MASKED, int MODE>
 __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitScoreMat& A, const TileCoord& tc,
                                                const int rot, char* __restrict__ smem) {
+    constexpr bool ONLY8 = MODE == FS_ONLY8;
+    constexpr bool FEAT = MODE == FS_SCORE_FEAT || MODE == FS_FEAT_ONLY;
+    constexpr bool SCORE = MODE != FS_FEAT_ONLY;
+    static_assert(!(FEAT && MASKED), "the features are those of all the unit's weights");
     const int32_t G = A.g.chunk_w;
     constexpr int EB = Elem<DT>::bytes;
     const int32_t row_bytes = G * EB + 16;
@@ -350,9 +372,14 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(nktab + (MASKED ? FS_WAVES * TILE_ROWS : 0));
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
 
+    uint32_t* __restrict__ lhist = reinterpret_cast<uint32_t*>(scol + G);     // [FEAT_BINS / 2], over the rows' scratch
+    static_assert(FS_WAVES * 16 * FS_NRED * sizeof(float) >= FEAT_BINS / 2 * sizeof(uint32_t), "histogram fits the scratch");
     load_tile_raw<DT, 1>(A.W, A.g.ld, tc, G, tile);      // 256 threads: four short steps, few registers
     for (int32_t c = threadIdx.x; c < G; c += FS_THREADS) scol[c] = A.s[tc.col0 + c];
     if (MASKED) load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
+    if (FEAT) {
+        for (int32_t b = threadIdx.x; b < FEAT_BINS / 2; b += FS_THREADS) lhist[b] = 0u;
+    }
     __syncthreads();
 
     // Column selection for the 8-bit candidate.  A column whose s_c^2 exceeds tau times the
@@ -363,7 +390,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     // none waits for another.
     int32_t nh = -1;           // listed columns; -1: no list, every column takes the exact route
     float s4_over_s2 = 0.0f;
-    if (!ONLY8) {
+    if (SCORE && !ONLY8) {
         const int l = fresh_lane();
         if (A.tau > 0.0f) {
             float ss = 0.0f;
@@ -400,10 +427,13 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     // in column order -- and the quarters are combined through LDS, in order.
     const int32_t runs = G >> 3;
     const int32_t qc0 = ((wave * runs) >> 2) << 3, qc1 = (((wave + 1) * runs) >> 2) << 3;   // this wavefront's columns
+    float f_sw = 0.0f, f_sw2 = 0.0f, f_cnt = 0.0f;     // features: this lane's row over this wavefront's columns
+    double f_sabs = 0.0;
     {
         const int lane_s = fresh_lane();
         const char* __restrict__ wr = tile + lane_s * row_bytes;
         const uint8_t* __restrict__ mr = mtile + lane_s * mstride;
+        const bool valid = lane_s < tc.nrows;             // rows past the unit's end are zeros, not weights
         float mn = INFINITY, mx = -INFINITY;
         double S1 = 0.0;
         int32_t nk = 0;
@@ -419,20 +449,105 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
                 mx = fmaxf(mx, kept ? w[j] : -INFINITY);
                 if (!ONLY8) S1 += kept ? (double)fabsf(w[j]) : 0.0;
             }
+            if (FEAT) {
+                // bin of |w| = bits 20..30 of the pattern: dword (bin & 1023) of the LDS histogram, half
+                // (bin >> 10).  The upper half is |w| >= 2: rare, so the wavefront asks once per eight
+                // columns whether any of its rows needs it.
+                uint32_t any_bits = 0u;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    f_sw += w[j];
+                    f_sw2 = fmaf(w[j], w[j], f_sw2);
+                    any_bits |= __float_as_uint(w[j]);
+                }
+                if (valid) {
+                    char* __restrict__ lh = reinterpret_cast<char*>(lhist);
+                    if (__builtin_amdgcn_ballot_w64((any_bits & 0x40000000u) != 0u) == 0) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            atomicAdd(reinterpret_cast<uint32_t*>(lh + ((__float_as_uint(w[j]) >> 18) & 0xFFCu)), 1u);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const uint32_t bits = __float_as_uint(w[j]);
+                            atomicAdd(reinterpret_cast<uint32_t*>(lh + ((bits >> 18) & 0xFFCu)), 1u << ((bits >> 26) & 16u));
+                        }
+                    }
+                }
+            }
         }
         gstat[wave * TILE_ROWS + lane_s] = make_float2(mn, mx);
         if (!ONLY8) {
             s1tab[wave * TILE_ROWS + lane_s] = S1;
             if (MASKED) nktab[wave * TILE_ROWS + lane_s] = nk;
         }
+        if (FEAT) f_sabs = S1;
         __syncthreads();
     }
+
+    float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
+
+    if (FEAT) {
+        // the tile's histogram into the unit's (every bin at most 8192: the halves never carry)
+        uint32_t* __restrict__ gh = A.fhist + (size_t)tc.u * FEAT_BINS;
+        const uint32_t thr_bin = (__float_as_uint(A.sparse_thr) >> 20) & 1023u;      // 1e-6 lies far below 2: lower half
+        int tiny = 0;           // does the tile hold a weight at or below the bin of 1e-6?
+        for (int32_t b = threadIdx.x; b < FEAT_BINS / 2; b += FS_THREADS) {
+            const uint32_t v = lhist[b];
+            if ((v & 0xffffu) != 0u) {
+                atomicAdd(&gh[b], v & 0xffffu);
+                tiny |= (uint32_t)b <= thr_bin ? 1 : 0;
+            }
+            if ((v >> 16) != 0u) atomicAdd(&gh[b + FEAT_BINS / 2], v >> 16);
+        }
+        tiny = __syncthreads_or(tiny);          // also: the scratch is free for the sums from here on
+        if (tiny) {
+            // count |w| < 1e-6 exactly: only tiles that hold such small weights pay for it
+            const int lane_c = fresh_lane();
+            const char* __restrict__ wr = tile + lane_c * row_bytes;
+            uint32_t cnt = 0;
+            for (int32_t c = qc0; c < qc1; c += 8) {
+                float w[8];
+                read8<DT>(wr, c, w);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) cnt += fabsf(w[j]) < A.sparse_thr ? 1u : 0u;
+            }
+            f_cnt = lane_c < tc.nrows ? (float)cnt : 0.0f;
+        }
+        const int lane_f = fresh_lane();
+        const float v3[3] = {f_sw, f_sw2, f_cnt};
+        const double m3 = rows_sum<3>(v3, red, lane_f);
+        // sum |w| stays fp64: lanes through the wavefront's scratch, four at a time, then sixteen, in order
+        double* __restrict__ dred = reinterpret_cast<double*>(red);
+        dred[lane_f] = f_sabs;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        double q4 = 0.0;
+        if (lane_f < 16) q4 = ((dred[4 * lane_f] + dred[4 * lane_f + 1]) + dred[4 * lane_f + 2]) + dred[4 * lane_f + 3];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        if (lane_f < 16) dred[64 + lane_f] = q4;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        double* __restrict__ dst = A.fmoments + (((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) * FEAT_QUARTERS +
+                                                 (size_t)wave) * 4;
+        if (lane_f < 3) dst[lane_f == 2 ? 3 : lane_f] = m3;
+        if (lane_f == 3) {
+            double tot = 0.0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tot += dred[64 + i];
+            dst[2] = tot;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (!SCORE) return;
 
     const int32_t K = B.K;
     double* __restrict__ out = A.partial + ((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) *
                                                (size_t)fit_score_ncand(K);
-
-    float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
 
     // Ternary absmean, binary sign*mean|w| and the reference energy: every wavefront scores
     // its quarter of the columns.  gamma = alpha = fp32(S1 / n), S1 = the quarters' sums of |w|
@@ -560,8 +675,8 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
             for (int i = 0; i < FS_KB; ++i) nz[i] = 0.0f;
             // (the row addresses are formed from a fresh lane index in front of each sweep: kept
             // from here they would be spilled across the parameter set-up)
-            auto sweep = [&](auto MODE) {
-                constexpr bool AN = decltype(MODE)::value;
+            auto sweep = [&](auto anchored_t) {
+                constexpr bool AN = decltype(anchored_t)::value;
                 const int lane_v = fresh_lane();
                 const char* __restrict__ wrow = tile + lane_v * row_bytes;
                 const uint8_t* __restrict__ mrow = mtile + lane_v * mstride;
@@ -642,15 +757,15 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     }
 }
 
-template <int DT, bool MASKED>
+template <int DT, bool MASKED, int MODE>
 __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScoreArgs B) {
     extern __shared__ char smem[];
     const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
     const FitScoreMat& A = B.m[mi];
     const int64_t local = (int64_t)blockIdx.x - B.tile_start[mi];
-    if (local == 0 && threadIdx.x == 0) *A.redo_count = 0u;      // the list the finalize kernel fills
+    if (MODE != FS_FEAT_ONLY && local == 0 && threadIdx.x == 0) *A.redo_count = 0u;      // the list the finalize kernel fills
     const TileCoord tc = tile_coord(A.g, local);
-    fit_score_tile<DT, MASKED, false>(B, A, tc, blockIdx.x & (FS_WAVES - 1), smem);
+    fit_score_tile<DT, MASKED, MODE>(B, A, tc, blockIdx.x & (FS_WAVES - 1), smem);
 }
 
 // The tiles of the listed units once more, 8-bit candidates only, exact route.  A fixed grid
@@ -677,7 +792,7 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_redo_kernel(const Fit
         const int64_t li = local / A.g.tiles_per_unit;
         const int64_t u = A.redo_list[li];
         const TileCoord tc = tile_coord_of_unit(A.g, u, local - li * A.g.tiles_per_unit);
-        fit_score_tile<DT, MASKED, true>(B, A, tc, (int)(w & (FS_WAVES - 1)), smem);
+        fit_score_tile<DT, MASKED, FS_ONLY8>(B, A, tc, (int)(w & (FS_WAVES - 1)), smem);
         __syncthreads();      // the next tile overwrites this one's LDS
     }
 }
@@ -765,8 +880,65 @@ struct FitItem {
     size_t ws_bytes;
 };
 
+template <int MODE>
+static int launch_tiles_untimed(const FitScoreArgs& A, int32_t dtype, bool masked, size_t lds, dim3 grid, hipStream_t hs);
+
+// Profiling aid (windq_kernel_timer): while switched on, every launch of the main fit+score kernel is
+// bracketed by a pair of HIP events on the launch stream.  Off by default; the only state the library keeps.
+namespace {
+struct KernelTimer {
+    std::mutex mu;
+    bool on = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;
+} g_ktimer;
+
+void ktimer_drop_locked() {
+    for (auto& p : g_ktimer.pairs) {
+        (void)hipEventDestroy(p.first);
+        (void)hipEventDestroy(p.second);
+    }
+    g_ktimer.pairs.clear();
+}
+}  // namespace
+
+template <int MODE>
+static int launch_tiles(const FitScoreArgs& A, int32_t dtype, bool masked, size_t lds, dim3 grid, hipStream_t hs) {
+    std::unique_lock<std::mutex> lock(g_ktimer.mu);
+    const bool timed = g_ktimer.on && MODE != FS_FEAT_ONLY;
+    lock.unlock();
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (timed && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) return WINDQ_EHIP;
+    if (timed && hipEventRecord(e0, hs) != hipSuccess) return WINDQ_EHIP;
+    const int st = launch_tiles_untimed<MODE>(A, dtype, masked, lds, grid, hs);
+    if (timed) {
+        if (hipEventRecord(e1, hs) != hipSuccess) return WINDQ_EHIP;
+        lock.lock();
+        g_ktimer.pairs.emplace_back(e0, e1);
+    }
+    return st;
+}
+
+template <int MODE>
+static int launch_tiles_untimed(const FitScoreArgs& A, int32_t dtype, bool masked, size_t lds, dim3 grid, hipStream_t hs) {
+    auto launch = [&](auto kernel) -> int {
+        const int e = ensure_lds(reinterpret_cast<const void*>(kernel), lds);
+        if (e != WINDQ_OK) return e;
+        hipLaunchKernelGGL(kernel, grid, dim3(FS_THREADS), lds, hs, A);
+        return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+    };
+    constexpr bool CAN_MASK = MODE == FS_SCORE;
+    if (dtype == WINDQ_BF16) {
+        if (CAN_MASK && masked) return launch(&fit_score_kernel<WINDQ_BF16, CAN_MASK, MODE>);
+        return launch(&fit_score_kernel<WINDQ_BF16, false, MODE>);
+    }
+    if (CAN_MASK && masked) return launch(&fit_score_kernel<WINDQ_F32, CAN_MASK, MODE>);
+    return launch(&fit_score_kernel<WINDQ_F32, false, MODE>);
+}
+
+// feat: nullptr, or the filled feature batch of the same matrices: the main kernel then also makes the
+// first pass of the unit features, and the feature kernels that follow it are launched from here.
 static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, int64_t unit_rows, const float* clip_grid,
-                            int32_t K, void* stream) {
+                            int32_t K, const FeatBatch* feat, void* stream) {
     if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
     int st = check_clip_grid(clip_grid, K);
     if (st != WINDQ_OK) return st;
@@ -777,6 +949,7 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
     A.inv_G = 1.0 / (double)chunk_w;
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid[k < K ? k : K - 1];
     const bool masked = items[0].mask != nullptr;
+    if (masked && feat != nullptr) return WINDQ_EINVAL;
     int64_t tiles = 0, units = 0;
     for (int32_t i = 0; i < n; ++i) {
         const FitItem& it = items[i];
@@ -799,6 +972,9 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
         M.err = it.err;
         M.clip_idx = it.clip_idx;
         M.ref_energy = it.ref_energy;
+        M.fmoments = feat != nullptr ? feat->m[i].moments : nullptr;
+        M.fhist = feat != nullptr ? feat->m[i].hist : nullptr;
+        M.sparse_thr = feat != nullptr ? feat->m[i].sparse_thr : 0.0f;
         // tau: with the error spread evenly over R_u rows, listing the columns above tau times the
         // mean keeps the short route's noise in the unit's 8-bit error near 1e-6 (one standard
         // deviation; what the rows really do is measured per unit, see NOISE_MAX).  Below
@@ -820,26 +996,66 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
     const int32_t dtype = items[0].W->dtype;
     const size_t lds = fit_score_lds_bytes(dtype, chunk_w, masked);
     const dim3 grid((unsigned)tiles);
-    auto launch = [&](auto kernel, dim3 g) -> int {
-        const int e = ensure_lds(reinterpret_cast<const void*>(kernel), lds);
-        if (e != WINDQ_OK) return e;
-        hipLaunchKernelGGL(kernel, g, dim3(FS_THREADS), lds, hs, A);
-        return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
-    };
-    const bool bf = dtype == WINDQ_BF16;
-    if (bf) st = masked ? launch(&fit_score_kernel<WINDQ_BF16, true>, grid) : launch(&fit_score_kernel<WINDQ_BF16, false>, grid);
-    else st = masked ? launch(&fit_score_kernel<WINDQ_F32, true>, grid) : launch(&fit_score_kernel<WINDQ_F32, false>, grid);
+    if (feat != nullptr) {
+        st = features_launch_init(*feat, hs);
+        if (st != WINDQ_OK) return st;
+        st = launch_tiles<FS_SCORE_FEAT>(A, dtype, false, lds, grid, hs);
+    } else {
+        st = launch_tiles<FS_SCORE>(A, dtype, masked, lds, grid, hs);
+    }
     if (st != WINDQ_OK) return st;
     hipLaunchKernelGGL(fit_score_finalize_kernel<false>, dim3((unsigned)units), dim3(FIN_THREADS), 0, hs, A);
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     // the units the finalize kernel listed: their 8-bit candidates on the exact route, finalized again
     const dim3 redo_grid((unsigned)(tiles < FS_REDO_GRID ? tiles : FS_REDO_GRID));
-    if (bf) st = masked ? launch(&fit_score_redo_kernel<WINDQ_BF16, true>, redo_grid) : launch(&fit_score_redo_kernel<WINDQ_BF16, false>, redo_grid);
-    else st = masked ? launch(&fit_score_redo_kernel<WINDQ_F32, true>, redo_grid) : launch(&fit_score_redo_kernel<WINDQ_F32, false>, redo_grid);
+    auto launch_redo = [&](auto kernel) -> int {
+        const int e = ensure_lds(reinterpret_cast<const void*>(kernel), lds);
+        if (e != WINDQ_OK) return e;
+        hipLaunchKernelGGL(kernel, redo_grid, dim3(FS_THREADS), lds, hs, A);
+        return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+    };
+    if (dtype == WINDQ_BF16) st = masked ? launch_redo(&fit_score_redo_kernel<WINDQ_BF16, true>) : launch_redo(&fit_score_redo_kernel<WINDQ_BF16, false>);
+    else st = masked ? launch_redo(&fit_score_redo_kernel<WINDQ_F32, true>) : launch_redo(&fit_score_redo_kernel<WINDQ_F32, false>);
     if (st != WINDQ_OK) return st;
     hipLaunchKernelGGL(fit_score_finalize_kernel<true>, dim3((unsigned)units), dim3(FIN_THREADS), 0, hs, A);
     if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
+    if (feat != nullptr) return features_launch_rest(*feat, hs);
     return WINDQ_OK;
+}
+
+// The first pass of the unit features by itself (windq_unit_features): the same tile kernel, scoring nothing.
+int windq::features_launch_tiles(const FeatBatch& F, hipStream_t hs) {
+    FitScoreArgs A;
+    A.n = F.n;
+    A.K = 1;
+    A.n_kpass = 0;
+    A.inv_G = 0.0;
+    for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = 1.0f;
+    int64_t tiles = 0, units = 0;
+    for (int32_t i = 0; i < WINDQ_MAX_BATCH; ++i) {
+        const FeatArgs& f = F.m[i < F.n ? i : 0];
+        FitScoreMat& M = A.m[i];
+        M = FitScoreMat{};
+        M.W = f.W;
+        M.s = f.s;
+        M.g = f.g;
+        M.fmoments = f.moments;
+        M.fhist = f.hist;
+        M.sparse_thr = f.sparse_thr;
+        if (i < F.n) {
+            A.tile_start[i] = tiles;
+            A.unit_start[i] = units;
+            tiles += f.g.n_tiles;
+            units += f.g.U;
+        }
+    }
+    for (int32_t i = F.n; i <= WINDQ_MAX_BATCH; ++i) {
+        A.tile_start[i] = tiles;
+        A.unit_start[i] = units;
+    }
+    if (tiles > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
+    const size_t lds = fit_score_lds_bytes(F.dtype, F.m[0].g.chunk_w, false);
+    return launch_tiles<FS_FEAT_ONLY>(A, F.dtype, false, lds, dim3((unsigned)tiles), hs);
 }
 
 static int fit_score_impl(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, const uint8_t* mask,
@@ -847,7 +1063,7 @@ static int fit_score_impl(const windq_mat* W, const float* s, int32_t chunk_w, i
                           void* ws, size_t ws_bytes, void* stream) {
     if (W == nullptr) return WINDQ_EINVAL;
     const FitItem it = {W, s, mask, err, clip_idx, ref_energy, ws, ws_bytes};
-    return fit_score_launch(&it, 1, chunk_w, unit_rows, clip_grid, K, stream);
+    return fit_score_launch(&it, 1, chunk_w, unit_rows, clip_grid, K, nullptr, stream);
 }
 
 extern "C" int windq_fit_score_all_bits(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
@@ -871,7 +1087,43 @@ extern "C" int windq_fit_score_all_bits_batch(const windq_fit_item* items, int32
     for (int32_t i = 0; i < n; ++i)
         its[i] = {items[i].W, items[i].s, items[i].mask, items[i].err, items[i].clip_idx, items[i].ref_energy, items[i].ws,
                   items[i].ws_bytes};
-    return fit_score_launch(its, n, chunk_w, unit_rows, clip_grid, K, stream);
+    return fit_score_launch(its, n, chunk_w, unit_rows, clip_grid, K, nullptr, stream);
+}
+
+// Features and fit+score from one read of W.  The workspace holds the features layout first, then fit+score's.
+static int fused_launch(const windq_fused_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows, const float* clip_grid,
+                        int32_t K, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    if (K < 1 || K > WINDQ_MAX_CLIP) return WINDQ_EINVAL;
+    FeatItem fi[WINDQ_MAX_BATCH];
+    FitItem si[WINDQ_MAX_BATCH];
+    for (int32_t i = 0; i < n; ++i) {
+        const windq_fused_item& it = items[i];
+        if (it.W == nullptr) return WINDQ_EINVAL;
+        Geometry g;
+        const int st = make_geometry(it.W, chunk_w, unit_rows, &g);
+        if (st != WINDQ_OK) return st;
+        const size_t fbytes = features_ws_bytes(g, it.W->dtype);
+        if (it.ws == nullptr || it.ws_bytes < fbytes + fit_score_ws_bytes(g, K) || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
+        fi[i] = {it.W, it.s, it.feat, it.ws, fbytes};
+        si[i] = {it.W, it.s, nullptr, it.err, it.clip_idx, it.ref_energy, static_cast<char*>(it.ws) + fbytes, it.ws_bytes - fbytes};
+    }
+    FeatBatch F;
+    const int st = features_fill(fi, n, chunk_w, unit_rows, &F);
+    if (st != WINDQ_OK) return st;
+    return fit_score_launch(si, n, chunk_w, unit_rows, clip_grid, K, &F, stream);
+}
+
+extern "C" int windq_features_fit_score(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
+                                        const float* clip_grid, int32_t K, float* feat, float* err, uint8_t* clip_idx,
+                                        float* ref_energy, void* ws, size_t ws_bytes, void* stream) {
+    const windq_fused_item it = {W, s, feat, err, clip_idx, ref_energy, ws, ws_bytes};
+    return fused_launch(&it, 1, chunk_w, unit_rows, clip_grid, K, stream);
+}
+
+extern "C" int windq_features_fit_score_batch(const windq_fused_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                              const float* clip_grid, int32_t K, void* stream) {
+    return fused_launch(items, n, chunk_w, unit_rows, clip_grid, K, stream);
 }
 
 // Scratch memory of windq_fit_score_all_bits_static: the workspace of one call, held by every
@@ -914,6 +1166,31 @@ extern "C" int windq_fit_score_all_bits_static(const windq_mat* W, const float* 
     // clear the one counter themselves), so what the previous call left behind does not matter.
     return fit_score_impl(W, s, chunk_w, unit_rows, nullptr, clip_grid, K, err, clip_idx, ref_energy, ptr,
                           (size_t)WINDQ_STATIC_SCRATCH_BYTES, stream);
+}
+
+extern "C" int windq_kernel_timer(int32_t enable) {
+    std::lock_guard<std::mutex> lock(g_ktimer.mu);
+    ktimer_drop_locked();
+    g_ktimer.on = enable != 0;
+    return WINDQ_OK;
+}
+
+extern "C" int windq_kernel_timer_read(double* total_ms, int64_t* launches) {
+    if (total_ms == nullptr || launches == nullptr) return WINDQ_EINVAL;
+    std::lock_guard<std::mutex> lock(g_ktimer.mu);
+    double sum = 0.0;
+    for (auto& p : g_ktimer.pairs) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(p.second) != hipSuccess || hipEventElapsedTime(&ms, p.first, p.second) != hipSuccess) {
+            ktimer_drop_locked();
+            return WINDQ_EHIP;
+        }
+        sum += (double)ms;
+    }
+    *total_ms = sum;
+    *launches = (int64_t)g_ktimer.pairs.size();
+    ktimer_drop_locked();
+    return WINDQ_OK;
 }
 
 extern "C" int windq_fit_score_rescored_units(const void* ws, int32_t dtype, int64_t rows, int64_t cols, int32_t chunk_w,

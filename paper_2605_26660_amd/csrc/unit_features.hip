@@ -6,10 +6,12 @@
 // P99 is the exact nearest-rank order statistic of |w|, found by most-significant-digit
 // radix selection on the bit pattern of |w| (monotone in |w| for non-negative floats).
 //
-// bf16 (15-bit keys, digits of 11 + 4 bits): TWO passes over W.
-//   pass A  moments, counts, and the histogram of the first digit (exponent + 3 mantissa
-//           bits: spreads Gaussian-like weights over enough bins to keep LDS atomics from
-//           piling up on one address).
+// The FIRST pass over W -- moments, the count of |w| < 1e-6 and the histogram of the first
+// digit (11 bits: exponent + 3 mantissa bits) -- is made by the tile kernel of fit_score.hip:
+// either alone (windq_unit_features) or as part of the fit+score kernel, which has the tile
+// in LDS anyway (windq_features_fit_score: W is then read once for both).  This file holds
+// what follows.
+// bf16 (15-bit keys, digits of 11 + 4 bits): one more pass over W.
 //   pass B  every workgroup first re-derives, from the finished first-digit histogram,
 //           the bin e0 that holds the wanted rank (a 2048-bin scan: cheaper than a launch
 //           and than any cross-workgroup handshake, which on this multi-die GPU costs an
@@ -20,7 +22,7 @@
 //           of P99 turn out to be.
 //   finish  per unit: P99 exactly, the exact count of |w| > 0.5 P99 = (first-digit bins
 //           above) + (refined bins above), and the eight features.  No third pass.
-// fp32 (31-bit keys, digits 11 + 11 + 9): one pass per digit plus a counting pass
+// fp32 (31-bit keys, digits 11 + 11 + 9): one pass per further digit plus a counting pass
 // (2|w| > P99, exact in fp32), each re-deriving the prefix from the finished histograms.
 // Passes after the first re-read a matrix that was just streamed; up to the 256 MB
 // last-level cache they are served on chip.  Integer atomics only, fixed-order fp64
@@ -29,38 +31,15 @@
 #include <string.h>
 
 #include "windq_common.hpp"
-#include "windq_ws.hpp"
+#include "windq_feat.hpp"
 #include "windq_select.hpp"
+#include "windq_ws.hpp"
 
 namespace windq {
 
 constexpr int FT_THREADS = 256;
 constexpr int FT_WAVES = FT_THREADS / 64;
 constexpr int FEAT_BATCH = 8;   // 128-bit loads a thread keeps in flight
-
-struct FeatArgs {
-    const void* W;
-    const float* s;
-    float* feat;
-    double* moments;
-    uint32_t* above;
-    uint32_t* hist;     // [3][U][FEAT_BINS]
-    Geometry g;
-    int64_t bpu;        // workgroups per unit
-    float sparse_thr;   // smallest fp32 that is >= 1e-6: (|w| < 1e-6) == (|w| < sparse_thr) for fp32 |w|
-    uint64_t rank;      // ceil(0.99 n), 1-based
-};
-
-// A launch covers up to WINDQ_MAX_BATCH matrices (one chunk width, one element type): the
-// workgroups of the pass kernels, the units of the finish kernel and the counters the init
-// kernel clears are numbered one matrix after the other.
-struct FeatBatch {
-    int32_t n;
-    int64_t block_start[WINDQ_MAX_BATCH + 1];
-    int64_t unit_start[WINDQ_MAX_BATCH + 1];
-    int64_t init_start[WINDQ_MAX_BATCH + 1];     // in workgroups of 256 counters
-    FeatArgs m[WINDQ_MAX_BATCH];
-};
 
 template <int DT>
 __device__ __forceinline__ void load8(const void* __restrict__ data, int64_t off, float (&w)[8]) {
@@ -154,27 +133,20 @@ __device__ __forceinline__ void select_prefix(const FeatArgs& A, int64_t u, int 
 // bf16: first-digit bin that holds the key of 0.5 * P99, given P99's first-digit bin.
 __device__ __forceinline__ uint32_t half_bin_of(uint32_t e0) { return e0 >= 16u ? e0 - 8u : e0 >> 1; }
 
-// bf16 passes work on the packed 16-bit patterns directly (two weights per dword): the
-// first digit is a bit-field extract, no conversion to float; the LDS histogram is kept
-// in FEAT_COPIES copies indexed by lane, which thins out the same-address collisions of
-// the LDS atomics (Gaussian-like weights fall into ~40 hot bins; more copies cost more in
-// clearing and flushing than they save); each thread sums its <= 64 weights in fp32
-// (products of bf16 are exact in fp32) and hands fp64 to the block-wide sums.
-//   MODE 0: moments + histogram of digit 0.   MODE 1: refine bins e0 and half_bin_of(e0).
+// The bf16 refining pass works on the packed 16-bit patterns directly (two weights per dword): the
+// first digit is a bit-field extract, no conversion to float.  It refines bins e0 and
+// half_bin_of(e0) to the remaining 4 bits; the 2 x 16 counters live in LDS in FEAT_COPIES copies
+// indexed by lane, which thins out the same-address collisions of the LDS atomics.
 constexpr int FEAT_COPIES = 2;
-__host__ __device__ constexpr int feat_cstride(int mode) { return (mode == 0 ? FEAT_BINS : 32) + 17; }   // odd skew: copies of a bin sit in different banks
-__host__ __device__ constexpr size_t feat_lds_bytes(int mode) { return (size_t)feat_cstride(mode) * FEAT_COPIES * sizeof(uint32_t); }
-template <int MODE>
-__global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatBatch B, const uint32_t sparse_key) {
+constexpr int FEAT_REFINE_BINS = 32;
+constexpr int FEAT_CSTRIDE = FEAT_REFINE_BINS + 17;   // odd skew: copies of a bin sit in different banks
+__global__ __launch_bounds__(FT_THREADS) void feat_refine_bf16_kernel(const FeatBatch B) {
     const int mi = batch_index(B.block_start, B.n, blockIdx.x);
     const FeatArgs& A = B.m[mi];
     const int64_t wg = (int64_t)blockIdx.x - B.block_start[mi];
-    constexpr int CSTRIDE = feat_cstride(MODE);
-    extern __shared__ uint32_t lhist[];                          // [FEAT_COPIES][CSTRIDE]
-    __shared__ double red[FT_WAVES];
+    __shared__ uint32_t lhist[FEAT_COPIES * FEAT_CSTRIDE];
     __shared__ uint32_t sh_part[FT_THREADS];
     __shared__ uint32_t sh_out[4];
-    constexpr int NB = MODE == 0 ? FEAT_BINS : 32;
     const int64_t u = wg / A.bpu;
     const int64_t blk = wg - u * A.bpu;
     const int32_t G = A.g.chunk_w;
@@ -186,7 +158,7 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatBa
     const int32_t nrows = (int32_t)(left < FEAT_TPB * TILE_ROWS ? left : FEAT_TPB * TILE_ROWS);
     const int64_t row0 = rb * A.g.R_u + lrow0;
     // The first batch of loads is issued before anything else, so that it is in flight while
-    // the histogram is cleared and (pass B) the rank's first-digit bin is looked up.
+    // the counters are cleared and the rank's first-digit bin is looked up.
     const uint16_t* __restrict__ Wp = static_cast<const uint16_t*>(A.W);
     const bool by_rows = FT_THREADS % pieces == 0;          // a thread keeps its column piece and steps down the rows
     const int32_t rstep = by_rows ? FT_THREADS / pieces : 1;
@@ -197,41 +169,23 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatBa
     for (int b = 0; b < FEAT_BATCH; ++b)
         if (r_first + b * rstep < nrows)
             first[b] = *reinterpret_cast<const uint4*>(Wp + (row0 + r_first + b * rstep) * A.g.ld + cbase);
-    for (int32_t b = threadIdx.x; b < CSTRIDE * FEAT_COPIES; b += FT_THREADS) lhist[b] = 0;
-    uint32_t e0 = 0, eh = 0;
-    if (MODE == 1) {
-        uint64_t rank_left;
-        select_prefix<WINDQ_BF16>(A, u, 1, sh_part, sh_out, &e0, &rank_left);
-        eh = half_bin_of(e0);
-    }
+    for (int32_t b = threadIdx.x; b < FEAT_CSTRIDE * FEAT_COPIES; b += FT_THREADS) lhist[b] = 0;
+    uint32_t e0 = 0;
+    uint64_t rank_left;
+    select_prefix<WINDQ_BF16>(A, u, 1, sh_part, sh_out, &e0, &rank_left);
+    const uint32_t eh = half_bin_of(e0);
     __syncthreads();
-    uint32_t* __restrict__ myhist = lhist + (threadIdx.x & (FEAT_COPIES - 1)) * CSTRIDE;
+    uint32_t* __restrict__ myhist = lhist + (threadIdx.x & (FEAT_COPIES - 1)) * FEAT_CSTRIDE;
 
-    float sw = 0.0f, sw2 = 0.0f, sabs = 0.0f;
-    uint32_t cnt = 0;
     auto consume = [&](const uint4& raw) {
         const uint32_t x[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t dlo = (x[j] >> 4) & 0x7ffu, dhi = (x[j] >> 20) & 0x7ffu;
-            if (MODE == 0) {
-                atomicAdd(&myhist[dlo], 1u);
-                atomicAdd(&myhist[dhi], 1u);
-                const float wlo = __uint_as_float(x[j] << 16), whi = __uint_as_float(x[j] & 0xffff0000u);
-                sw += wlo;
-                sw += whi;
-                sw2 = fmaf(wlo, wlo, sw2);
-                sw2 = fmaf(whi, whi, sw2);
-                sabs += fabsf(wlo);
-                sabs += fabsf(whi);
-                cnt += (x[j] & 0x7fffu) < sparse_key ? 1u : 0u;
-                cnt += ((x[j] >> 16) & 0x7fffu) < sparse_key ? 1u : 0u;
-            } else {
-                // one atomic per weight: the two bins are distinct unless both are bin 0, and
-                // then the single histogram serves both (the finish kernel reads it twice)
-                if (dlo == e0 || dlo == eh) atomicAdd(&myhist[(dlo == e0 ? 0u : 16u) + (x[j] & 15u)], 1u);
-                if (dhi == e0 || dhi == eh) atomicAdd(&myhist[(dhi == e0 ? 0u : 16u) + ((x[j] >> 16) & 15u)], 1u);
-            }
+            // one atomic per weight: the two bins are distinct unless both are bin 0, and
+            // then the single histogram serves both (the finish kernel reads it twice)
+            if (dlo == e0 || dlo == eh) atomicAdd(&myhist[(dlo == e0 ? 0u : 16u) + (x[j] & 15u)], 1u);
+            if (dhi == e0 || dhi == eh) atomicAdd(&myhist[(dhi == e0 ? 0u : 16u) + ((x[j] >> 16) & 15u)], 1u);
         }
     };
     if (by_rows) {
@@ -256,27 +210,17 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_bf16_kernel(const FeatBa
             consume(*reinterpret_cast<const uint4*>(Wp + (row0 + r) * A.g.ld + col0 + (int64_t)pc * 8));
         }
     }
-
-    if (MODE == 0) {
-        const double r0 = block_sum((double)sw, red), r1 = block_sum((double)sw2, red);
-        const double r2 = block_sum((double)sabs, red), r3 = block_sum((double)cnt, red);
-        if (threadIdx.x == 0) {
-            double* dst = A.moments + ((size_t)u * (size_t)A.bpu + (size_t)blk) * 4;
-            dst[0] = r0; dst[1] = r1; dst[2] = r2; dst[3] = r3;
-        }
-    }
     __syncthreads();
-    uint32_t* __restrict__ gh = A.hist + ((size_t)MODE * (size_t)A.g.U + (size_t)u) * FEAT_BINS;
-    for (int32_t b = threadIdx.x; b < NB; b += FT_THREADS) {
+    uint32_t* __restrict__ gh = A.hist + ((size_t)A.g.U + (size_t)u) * FEAT_BINS;
+    for (int32_t b = threadIdx.x; b < FEAT_REFINE_BINS; b += FT_THREADS) {
         uint32_t v = 0;
 #pragma unroll
-        for (int c = 0; c < FEAT_COPIES; ++c) v += lhist[c * CSTRIDE + b];
+        for (int c = 0; c < FEAT_COPIES; ++c) v += lhist[c * FEAT_CSTRIDE + b];
         if (v != 0) atomicAdd(&gh[b], v);
     }
 }
 
 // One pass over FEAT_TPB tiles of one unit (generic element type; used for fp32 inputs).
-//   MODE 0: moments + histogram of digit 0.
 //   MODE 1: histogram(s) of digit `level` under the unit's prefix.
 //   MODE 2: fp32 only: count 2|w| > P99.
 template <int DT, int MODE>
@@ -319,20 +263,12 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatBatch B
     }
     __syncthreads();
 
-    double sw = 0.0, sw2 = 0.0, sabs = 0.0;
     uint32_t cnt = 0;
     auto consume = [&](const float (&w)[8]) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float aw = fabsf(w[j]);
-            if (MODE == 0) {
-                const double x = (double)w[j];
-                sw += x;
-                sw2 = fma(x, x, sw2);
-                sabs += (double)aw;
-                cnt += aw < A.sparse_thr ? 1u : 0u;
-                atomicAdd(&lhist[key_of<DT>(w[j]) >> shift], 1u);
-            } else if (MODE == 1) {
+            if (MODE == 1) {
                 const uint32_t key = key_of<DT>(w[j]);
                 if (DT == WINDQ_BF16) {
                     const uint32_t b = key >> 4;
@@ -372,14 +308,7 @@ __global__ __launch_bounds__(FT_THREADS) void feat_pass_kernel(const FeatBatch B
     }
 
     const size_t slot = (size_t)u * (size_t)A.bpu + (size_t)blk;
-    if (MODE == 0) {
-        const double r0 = block_sum(sw, red), r1 = block_sum(sw2, red), r2 = block_sum(sabs, red);
-        const double r3 = block_sum((double)cnt, red);
-        if (threadIdx.x == 0) {
-            double* dst = A.moments + slot * 4;
-            dst[0] = r0; dst[1] = r1; dst[2] = r2; dst[3] = r3;
-        }
-    } else if (MODE == 2) {
+    if (MODE == 2) {
         const double r3 = block_sum((double)cnt, red);
         if (threadIdx.x == 0) A.above[slot] = (uint32_t)r3;
     }
@@ -435,8 +364,8 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
     // requested now, used after the selection
     static_assert(WINDQ_MAX_CHUNK <= 2 * FT_THREADS, "two activation scales per thread cover a chunk");
     double mv[4] = {0.0, 0.0, 0.0, 0.0};
-    if (tid < A.bpu) {
-        const double* src = A.moments + ((size_t)u * (size_t)A.bpu + (size_t)tid) * 4;
+    if (tid < A.mparts) {
+        const double* src = A.moments + ((size_t)u * (size_t)A.mparts + (size_t)tid) * 4;
         mv[0] = src[0]; mv[1] = src[1]; mv[2] = src[2]; mv[3] = src[3];
     }
     const bool has0 = tid < G, has1 = tid + FT_THREADS < G;
@@ -468,8 +397,8 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
     }
 
     double m[4] = {mv[0], mv[1], mv[2], mv[3]};
-    for (int64_t b = tid + FT_THREADS; b < A.bpu; b += FT_THREADS) {
-        const double* src = A.moments + ((size_t)u * (size_t)A.bpu + (size_t)b) * 4;
+    for (int64_t b = tid + FT_THREADS; b < A.mparts; b += FT_THREADS) {
+        const double* src = A.moments + ((size_t)u * (size_t)A.mparts + (size_t)b) * 4;
         m[0] += src[0]; m[1] += src[1]; m[2] += src[2]; m[3] += src[3];
     }
     double ssum = 0.0;
@@ -504,41 +433,38 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
 }
 
 template <int DT>
-static int launch_features(const FeatBatch& B, int64_t blocks_total, int64_t units_total, int64_t init_total,
-                           hipStream_t hs) {
-    const dim3 blocks((unsigned)blocks_total);
-    hipLaunchKernelGGL(feat_init_kernel<DT>, dim3((unsigned)init_total), dim3(256), 0, hs, B);
+static int launch_rest(const FeatBatch& B, hipStream_t hs) {
+    const dim3 blocks((unsigned)B.blocks_total);
     if (DT == WINDQ_BF16) {
-        // |w| < 1e-6 on bf16 keys: key < key of the smallest bf16 that is >= 1e-6
-        uint32_t tb;
-        memcpy(&tb, &B.m[0].sparse_thr, sizeof(tb));
-        const uint32_t sparse_key = (tb >> 16) + ((tb & 0xffffu) != 0 ? 1u : 0u);
-        if (ensure_lds(reinterpret_cast<const void*>(&feat_pass_bf16_kernel<0>), feat_lds_bytes(0)) != WINDQ_OK) return WINDQ_EHIP;
-        hipLaunchKernelGGL((feat_pass_bf16_kernel<0>), blocks, dim3(FT_THREADS), feat_lds_bytes(0), hs, B, sparse_key);
-        hipLaunchKernelGGL((feat_pass_bf16_kernel<1>), blocks, dim3(FT_THREADS), feat_lds_bytes(1), hs, B, sparse_key);
+        hipLaunchKernelGGL(feat_refine_bf16_kernel, blocks, dim3(FT_THREADS), 0, hs, B);
     } else {
-        hipLaunchKernelGGL((feat_pass_kernel<DT, 0>), blocks, dim3(FT_THREADS), 0, hs, B, 0);
         hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, B, 1);
         hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, B, 2);
         hipLaunchKernelGGL((feat_pass_kernel<DT, 2>), blocks, dim3(FT_THREADS), 0, hs, B, 0);
     }
-    hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)units_total), dim3(FT_THREADS), 0, hs, B);
+    hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)B.units_total), dim3(FT_THREADS), 0, hs, B);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
-}  // namespace windq
+int features_launch_init(const FeatBatch& B, hipStream_t hs) {
+    if (B.dtype == WINDQ_BF16) hipLaunchKernelGGL(feat_init_kernel<WINDQ_BF16>, dim3((unsigned)B.init_total), dim3(256), 0, hs, B);
+    else hipLaunchKernelGGL(feat_init_kernel<WINDQ_F32>, dim3((unsigned)B.init_total), dim3(256), 0, hs, B);
+    return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+}
 
-using namespace windq;
+int features_launch_rest(const FeatBatch& B, hipStream_t hs) {
+    return B.dtype == WINDQ_BF16 ? launch_rest<WINDQ_BF16>(B, hs) : launch_rest<WINDQ_F32>(B, hs);
+}
 
-static int unit_features_launch(const windq_feat_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows, void* stream) {
+int features_fill(const FeatItem* items, int32_t n, int32_t chunk_w, int64_t unit_rows, FeatBatch* Bp) {
     if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
-    FeatBatch B;
+    FeatBatch& B = *Bp;
     B.n = n;
     int64_t blocks = 0, units = 0, inits = 0;
     float thr = (float)1e-6;
     if ((double)thr < 1e-6) thr = nextafterf(thr, INFINITY);
     for (int32_t i = 0; i < n; ++i) {
-        const windq_feat_item& it = items[i];
+        const FeatItem& it = items[i];
         FeatArgs& A = B.m[i];
         if (it.W == nullptr) return WINDQ_EINVAL;
         const int st = make_geometry(it.W, chunk_w, unit_rows, &A.g);
@@ -556,6 +482,7 @@ static int unit_features_launch(const windq_feat_item* items, int32_t n, int32_t
         A.above = reinterpret_cast<uint32_t*>(base + L.above);
         A.hist = reinterpret_cast<uint32_t*>(base + L.hist);
         A.bpu = L.bpu;
+        A.mparts = L.mparts;
         A.sparse_thr = thr;
         const uint64_t nw = (uint64_t)A.g.R_u * (uint64_t)chunk_w;
         A.rank = (99 * nw + 99) / 100;
@@ -573,9 +500,29 @@ static int unit_features_launch(const windq_feat_item* items, int32_t n, int32_t
     }
     for (int32_t i = n; i < WINDQ_MAX_BATCH; ++i) B.m[i] = B.m[0];
     if (blocks > (int64_t)0x7fffffff || inits > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
+    B.dtype = items[0].W->dtype;
+    B.blocks_total = blocks;
+    B.units_total = units;
+    B.init_total = inits;
+    return WINDQ_OK;
+}
+
+}  // namespace windq
+
+using namespace windq;
+
+static int unit_features_launch(const windq_feat_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    FeatItem its[WINDQ_MAX_BATCH];
+    for (int32_t i = 0; i < n; ++i) its[i] = {items[i].W, items[i].s, items[i].feat, items[i].ws, items[i].ws_bytes};
+    FeatBatch B;
+    int st = features_fill(its, n, chunk_w, unit_rows, &B);
+    if (st != WINDQ_OK) return st;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    return items[0].W->dtype == WINDQ_BF16 ? launch_features<WINDQ_BF16>(B, blocks, units, inits, hs)
-                                           : launch_features<WINDQ_F32>(B, blocks, units, inits, hs);
+    st = features_launch_init(B, hs);
+    if (st == WINDQ_OK) st = features_launch_tiles(B, hs);
+    if (st == WINDQ_OK) st = features_launch_rest(B, hs);
+    return st;
 }
 
 extern "C" int windq_unit_features(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, float* feat,

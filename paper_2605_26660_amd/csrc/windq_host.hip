@@ -140,6 +140,9 @@ size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, in
         case WINDQ_CALL_UNIT_SALIENCY: return unit_saliency_ws_bytes(g);
         case WINDQ_CALL_DEQUANT: return dequant_ws_bytes(g);
         case WINDQ_CALL_REFINE: return unit_saliency_ws_bytes(g);
+        case WINDQ_CALL_FEATURES_FIT_SCORE:
+            if (K < 1 || K > WINDQ_MAX_CLIP) return 0;
+            return features_ws_bytes(g, dtype) + fit_score_ws_bytes(g, K);
         default: return 0;
     }
 }

@@ -37,24 +37,29 @@ inline FitScoreLayout fit_score_layout(const Geometry& g, int32_t K) {
 inline size_t fit_score_ws_bytes(const Geometry& g, int32_t K) { return fit_score_layout(g, K).total; }
 
 // ---- unit_features
-// A workgroup covers FEAT_TPB consecutive tiles of one unit ("block" below).
-//   moments  [n_blocks][4] fp64   sum w, sum w^2, sum |w|, count(|w| < 1e-6)
+// The first pass (moments, counts, histogram of the first radix digit) works tile by tile, each of the
+// four wavefronts of a workgroup on a quarter of the chunk's columns; the later passes cover
+// FEAT_TPB consecutive tiles of one unit per workgroup ("block" below).
+//   moments  [n_tiles][4][4] fp64   per (tile, column quarter): sum w, sum w^2, sum |w|, count(|w| < 1e-6)
 //   above    [n_blocks]    u32    count(|w| > 0.5 P99)            (fp32 inputs only)
 //   hist     [3][U][FEAT_BINS] u32  histogram of radix digit 0, 1, 2
 constexpr int FEAT_DIGIT_BITS = 11;
 constexpr int FEAT_BINS = 1 << FEAT_DIGIT_BITS;
 constexpr int FEAT_TPB = 2;
+constexpr int FEAT_QUARTERS = 4;
 struct FeatLayout {
-    int64_t bpu;       // workgroups per unit
+    int64_t bpu;       // workgroups per unit (later passes)
     int64_t n_blocks;
+    int64_t mparts;    // moment records per unit: tiles x column quarters
     size_t moments, above, hist, total;
 };
 inline FeatLayout features_layout(const Geometry& g) {
     FeatLayout L;
     L.bpu = (g.tiles_per_unit + FEAT_TPB - 1) / FEAT_TPB;
     L.n_blocks = g.U * L.bpu;
+    L.mparts = g.tiles_per_unit * FEAT_QUARTERS;
     size_t pos = 0;
-    L.moments = pos; pos = round_up(pos + (size_t)L.n_blocks * 4 * sizeof(double), 256);
+    L.moments = pos; pos = round_up(pos + (size_t)g.n_tiles * FEAT_QUARTERS * 4 * sizeof(double), 256);
     L.above = pos;   pos = round_up(pos + (size_t)L.n_blocks * sizeof(uint32_t), 256);
     L.hist = pos;    pos = round_up(pos + (size_t)3 * g.U * FEAT_BINS * sizeof(uint32_t), 256);
     L.total = pos;

@@ -119,7 +119,7 @@ class Stack:
             for m in blk.mats:
                 m.codes = m.scale = m.offset = None
         self.ws = [torch.empty(max(wq.workspace_bytes(c, dt, sp.rows, sp.cols, G, unit_rows, self.K)
-                                   for c in (wq.CALL_UNIT_FEATURES, wq.CALL_FIT_SCORE, wq.CALL_APPLY_PLAN)),
+                                   for c in (wq.CALL_UNIT_FEATURES, wq.CALL_FIT_SCORE, wq.CALL_APPLY_PLAN, wq.CALL_FEATURES_FIT_SCORE)),
                                dtype=torch.uint8, device=dev) for sp in self.specs]
         self.n_units = 0
         for blk in self.blocks:
@@ -183,9 +183,10 @@ class Stack:
         return sub
 
     # ------------------------------------------------------------------ one pass of the hot path
-    def run_step(self, timer=None, per_matrix: bool = False):
+    def run_step(self, timer=None, per_matrix: bool = False, fused: bool = True):
         """All five calls over every block, in sequence, on the current stream.  Returns Eq. 5's (total centibits,
-        total weights).  timer: object with time(name, fn) (an event pair per call) or None."""
+        total weights).  timer: object with time(name, fn) (an event pair per call) or None.  fused: unit features and
+        fit+score through windq_features_fit_score (one read of W for both) instead of the two separate calls."""
         G, ur, cg = self.G, self.unit_rows, self.clip_grid
         t = timer.time if timer is not None else (lambda name, fn: fn())
         for blk in self.blocks:
@@ -196,9 +197,13 @@ class Stack:
                     t("calib_stats", lambda: wq.windq_calib_stats(x["X"], want_rms=False, ws=self.calib_ws[key], out=x["s"]))
                 for i, m in enumerate(mats):
                     s = blk.xs[m.spec.x_key]["s"]
-                    t("unit_features", lambda: wq.windq_unit_features(m.W, s, G, ur, ws=self.ws[i], out=m.feat))
-                    t("fit_score_all_bits", lambda: wq.windq_fit_score_all_bits(m.W, s, G, ur, cg, ws=self.ws[i],
-                                                                                out=(m.err, m.clip_idx, m.ref)))
+                    if fused:
+                        t("fit_score_all_bits", lambda: wq.windq_features_fit_score(
+                            m.W, s, G, ur, cg, ws=self.ws[i], out=(m.feat, m.err, m.clip_idx, m.ref)))
+                    else:
+                        t("unit_features", lambda: wq.windq_unit_features(m.W, s, G, ur, ws=self.ws[i], out=m.feat))
+                        t("fit_score_all_bits", lambda: wq.windq_fit_score_all_bits(m.W, s, G, ur, cg, ws=self.ws[i],
+                                                                                    out=(m.err, m.clip_idx, m.ref)))
                     t("apply_plan", lambda: wq.windq_apply_plan(m.W, G, ur, m.action_d, m.clip_idx, cg, m.off_d, codes=m.codes,
                                                                 ws=self.ws[i], out=(m.scale, m.offset)))
                 continue
@@ -206,9 +211,13 @@ class Stack:
                 [x["X"] for _, x in xl], want_rms=False, wss=[self.calib_ws[k] for k, _ in xl], outs=[x["s"] for _, x in xl]))
             Ws = [m.W for m in mats]
             ss = [blk.xs[m.spec.x_key]["s"] for m in mats]
-            t("unit_features", lambda: wq.windq_unit_features_batch(Ws, ss, G, ur, wss=self.ws, outs=[m.feat for m in mats]))
-            t("fit_score_all_bits", lambda: wq.windq_fit_score_all_bits_batch(
-                Ws, ss, G, ur, cg, wss=self.ws, outs=[(m.err, m.clip_idx, m.ref) for m in mats]))
+            if fused:
+                t("fit_score_all_bits", lambda: wq.windq_features_fit_score_batch(
+                    Ws, ss, G, ur, cg, wss=self.ws, outs=[(m.feat, m.err, m.clip_idx, m.ref) for m in mats]))
+            else:
+                t("unit_features", lambda: wq.windq_unit_features_batch(Ws, ss, G, ur, wss=self.ws, outs=[m.feat for m in mats]))
+                t("fit_score_all_bits", lambda: wq.windq_fit_score_all_bits_batch(
+                    Ws, ss, G, ur, cg, wss=self.ws, outs=[(m.err, m.clip_idx, m.ref) for m in mats]))
             t("apply_plan", lambda: wq.windq_apply_plan_batch(
                 Ws, G, ur, [m.action_d for m in mats], [m.clip_idx for m in mats], cg, [m.off_d for m in mats],
                 [m.codes for m in mats], [(m.scale, m.offset) for m in mats], wss=self.ws))

@@ -267,3 +267,63 @@ def test_masked_batches_equal_single_prot_calls(windq, dtype):
     with pytest.raises(windq.WindqError) as e:                     # a mask in every item or in none
         windq.windq_fit_score_all_bits_batch(Ws, ss, G, 0, cg, masks=[masks[0], None, masks[2]])
     assert e.value.status == windq.WINDQ_EINVAL
+
+
+# ------------------------------------------------ features + fit+score from one read of W
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("G,unit_rows,K,shapes", [
+    (128, 0, 20, [(256, 512), (1024, 256), (64, 128), (200, 384), (2048, 128), (192, 640), (512, 512)]),
+    (64, 64, 7, [(128, 256), (64, 64), (320, 192)]),
+    (8, 0, 3, [(16, 24), (8, 8)]),
+    (512, 0, 5, [(72, 1024)]),
+    (256, 100, 40, [(300, 256)]),
+])
+def test_fused_features_fit_score_equals_the_separate_calls(windq, dtype, G, unit_rows, K, shapes):
+    """windq_features_fit_score(_batch) takes the first pass of the unit features out of the fit+score kernel's tiles:
+    every output must be, bit for bit, what windq_unit_features and windq_fit_score_all_bits give."""
+    Ws, ss = block(dtype, shapes, 171)
+    Ws[0][:, :G] = 0                      # a chunk of zeros: |w| < 1e-6 everywhere, P99 = 0
+    Ws[-1][0, 0] = 3.0                    # |w| >= 2: the upper half of the first-digit histogram
+    cg = synth.clip_grid(K)
+    feats = [windq.windq_unit_features(W, s, G, unit_rows) for W, s in zip(Ws, ss)]
+    fits = [windq.windq_fit_score_all_bits(W, s, G, unit_rows, cg) for W, s in zip(Ws, ss)]
+    one = [windq.windq_features_fit_score(W, s, G, unit_rows, cg) for W, s in zip(Ws, ss)]
+    batch = windq.windq_features_fit_score_batch(Ws, ss, G, unit_rows, cg)
+    torch.cuda.synchronize()
+    for f, (e, c, r), o, b in zip(feats, fits, one, batch):
+        for want, got1, got2 in zip((f, e, c, r), o, b):
+            assert same_bits(want, got1) and same_bits(want, got2)
+
+
+def test_fused_call_checks_its_arguments(windq):
+    Ws, ss = block(torch.bfloat16, [(64, 128)] * 2, 9)
+    cg = synth.clip_grid(4)
+    small = [torch.empty(windq.workspace_bytes(windq.CALL_FIT_SCORE, windq.WINDQ_BF16, 64, 128, 128, 0, 4), dtype=torch.uint8,
+                         device=DEV)] * 2
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_features_fit_score_batch(Ws, ss, 128, 0, cg, wss=small)        # fit+score's size alone is too small
+    assert e.value.status == windq.WINDQ_EWORKSPACE
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_features_fit_score_batch(Ws, ss, 96, 0, cg)
+    assert e.value.status == windq.WINDQ_ESHAPE
+    need = windq.workspace_bytes(windq.CALL_FEATURES_FIT_SCORE, windq.WINDQ_BF16, 64, 128, 128, 0, 4)
+    assert need == (windq.workspace_bytes(windq.CALL_UNIT_FEATURES, windq.WINDQ_BF16, 64, 128, 128, 0, 4) +
+                    windq.workspace_bytes(windq.CALL_FIT_SCORE, windq.WINDQ_BF16, 64, 128, 128, 0, 4))
+
+
+def test_kernel_timer_brackets_the_main_fit_score_kernel(windq):
+    Ws, ss = block(torch.bfloat16, [(512, 512), (256, 384)], 19)
+    cg = synth.clip_grid(20)
+    windq.windq_kernel_timer(True)
+    a = windq.windq_fit_score_all_bits_batch(Ws, ss, 128, 0, cg)
+    windq.windq_features_fit_score(Ws[0], ss[0], 128, 0, cg)
+    windq.windq_unit_features(Ws[0], ss[0], 128, 0)                  # no fit+score kernel in this one
+    ms, n = windq.windq_kernel_timer_read()
+    assert n == 2 and 0.0 < ms < 100.0
+    assert windq.windq_kernel_timer_read() == (0.0, 0)              # read forgets
+    windq.windq_kernel_timer(False)
+    b = windq.windq_fit_score_all_bits_batch(Ws, ss, 128, 0, cg)
+    torch.cuda.synchronize()
+    assert windq.windq_kernel_timer_read() == (0.0, 0)
+    for x, y in zip(a, b):
+        assert all(same_bits(p, q) for p, q in zip(x, y))

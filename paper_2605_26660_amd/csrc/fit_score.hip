@@ -71,7 +71,7 @@ constexpr int FS_KB = 5;                    // clip ratios evaluated together by
 constexpr int FS_NRED = FS_KB * 5;          // per-lane sums a pass produces: 4 errors + 1 noise term per clip ratio
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
 constexpr int FS_HMAX = WINDQ_MAX_CHUNK / 8;   // most columns a tile may send down the exact 8-bit route on their own
-constexpr int FS_REDO_GRID = 1024;
+constexpr int FS_REDO_GRID = 512; 
 // What a pass over a tile does.
 constexpr int FS_SCORE = 0;         // every candidate quantizer
 constexpr int FS_ONLY8 = 1;         // the 8-bit candidates alone, exact route (listed units)
@@ -183,7 +183,8 @@ __device__ __forceinline__ float exact_residual8(const float w, const float sc, 
 }
 
 // One weight against FS_KB clip ratios x 4 bit-widths, the 8-bit one on the exact route.
-// sc = s_c, nM = -2^23 (in a VGPR).
+// sc = s_c, nM = -2^23 (in a VGPR).  Candidate after candidate: the fewest registers, for the sweeps
+// that need every parameter of KParams live (all columns on the exact route).
 template <bool ANCHORED>
 __device__ __forceinline__ void score_weight(const float w, const float sc, const KParams (&P)[FS_KB],
                                              const float (&Q)[4], const float M, const float nM,
@@ -224,19 +225,30 @@ __device__ __forceinline__ void score_weight_8(const float w, const float sc, co
 __device__ __forceinline__ void score_weight_short(const float w, const float sc, const KParams (&P)[FS_KB],
                                                    const float (&Q)[4], const float M, const float nM,
                                                    float (&acc)[FS_KB][4]) {
+    // Instruction ORDER matters as much as instruction count here: the four bit-widths of a clip ratio
+    // advance side by side, stage by stage, so that every instruction's inputs are four instructions
+    // old and a wavefront does not wait on its own results.  The barriers pin that order (left alone,
+    // the compiler finishes one candidate before it starts the next, to save registers: 6 % slower).
     const float w1 = w * sc;
     const float ms = sc * nM;
 #pragma unroll
     for (int i = 0; i < FS_KB; ++i) {
         const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
         const float x = fma_clamp01(w, P[i].rinv, P[i].h);        // position in the clipped range, in [0, 1]
+        float t[4];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const float tM = fmaf(x, Q[b], M);
-            const float q1 = fmaf(tM, sc, ms);
-            const float r1 = fmaf(q1, P[i].nd[b], u1);
-            acc[i][b] = fmaf(r1, r1, acc[i][b]);
-        }
+        for (int b = 0; b < 4; ++b) t[b] = fmaf(x, Q[b], M);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) t[b] = fmaf(t[b], sc, ms);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) t[b] = fmaf(t[b], P[i].nd[b], u1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[i][b] = fmaf(t[b], t[b], acc[i][b]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 

@@ -207,6 +207,50 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
     }
 }
 
+// score_weight with the four bit-widths side by side, stage by stage (see score_weight_short): six live
+// temporaries instead of two, for the sweeps over all columns, which read four columns at a time to
+// make room for them.  The 8-bit candidate's two extra steps run into the next ratio's first ones.
+template <bool ANCHORED>
+__device__ __forceinline__ void score_weight_staged(const float w, const float sc, const KParams (&P)[FS_KB],
+                                                    const float (&Q)[4], const float M, const float nM,
+                                                    float (&acc)[FS_KB][4]) {
+    const float w1 = w * sc;
+    const float ms = sc * nM;
+#pragma unroll
+    for (int i = 0; i < FS_KB; ++i) {
+        const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
+        float x, base = w, fix = P[i].nc;
+        if (ANCHORED) {
+            x = fma_clamp01(w, P[i].rinv, P[i].h);                // position in the clipped range, in [0, 1]
+        } else {
+            const float u0 = w + P[i].nc;                         // w - c, rounded
+            const float bb = u0 - w;
+            fix = (w - (u0 - bb)) + (P[i].nc - bb);               // its rounding error: (w - c) = u0 + fix exactly
+            x = fma_clamp01(u0, P[i].rinv, P[i].h);
+            base = u0;
+        }
+        float t[4];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) t[b] = fmaf(x, Q[b], M);
+        __builtin_amdgcn_sched_barrier(0);
+        t[0] = t[0] - P[i].Mq;                                    // code - q0
+#pragma unroll
+        for (int b = 1; b < 4; ++b) t[b] = fmaf(t[b], sc, ms);
+        __builtin_amdgcn_sched_barrier(0);
+        t[0] = fmaf(t[0], P[i].nd[0], base);                      // (c + r), small
+#pragma unroll
+        for (int b = 1; b < 4; ++b) t[b] = fmaf(t[b], P[i].nd[b], u1);
+        __builtin_amdgcn_sched_barrier(0);
+        t[0] = t[0] + fix;                                        // r
+#pragma unroll
+        for (int b = 1; b < 4; ++b) acc[i][b] = fmaf(t[b], t[b], acc[i][b]);
+        __builtin_amdgcn_sched_barrier(0);
+        const float r8 = t[0] * sc;
+        acc[i][0] = fmaf(r8, r8, acc[i][0]);
+    }
+}
+
 // The 8-bit candidate alone, exact route (the pass over listed units).
 template <bool ANCHORED>
 __device__ __forceinline__ void score_weight_8(const float w, const float sc, const KParams (&P)[FS_KB], const float Q0,
@@ -692,20 +736,33 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
                 const int lane_v = fresh_lane();
                 const char* __restrict__ wrow = tile + lane_v * row_bytes;
                 const uint8_t* __restrict__ mrow = mtile + lane_v * mstride;
-                for (int32_t c = 0; c < G; c += 8) {
-                    float w[8];
-                    read8<DT>(wrow, c, w);
-                    const float4 sa = *reinterpret_cast<const float4*>(scol + c);
-                    const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
-                    float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
-                    if (MASKED) {
-                        const uint32_t m = mrow[c >> 3];
-                        drop_masked(s8, m);
-                    }
+                if (ONLY8) {
+                    for (int32_t c = 0; c < G; c += 8) {
+                        float w[8];
+                        read8<DT>(wrow, c, w);
+                        const float4 sa = *reinterpret_cast<const float4*>(scol + c);
+                        const float4 sb = *reinterpret_cast<const float4*>(scol + c + 4);
+                        float s8[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
+                        if (MASKED) {
+                            const uint32_t m = mrow[c >> 3];
+                            drop_masked(s8, m);
+                        }
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        if (ONLY8) score_weight_8<AN>(w[j], s8[j], P, Q[0], M, acc);
-                        else score_weight<AN>(w[j], s8[j], P, Q, M, nM, acc);
+                        for (int j = 0; j < 8; ++j) score_weight_8<AN>(w[j], s8[j], P, Q[0], M, acc);
+                    }
+                } else {
+                    for (int32_t c = 0; c < G; c += 4) {
+                        float w[4];
+                        read4<DT>(wrow, c, w);
+                        const float4 sa = *reinterpret_cast<const float4*>(scol + c);
+                        float s4[4] = {sa.x, sa.y, sa.z, sa.w};
+                        if (MASKED) {
+                            const uint32_t m = (uint32_t)mrow[c >> 3] >> (c & 4);
+                            s4[0] = drop_if_set<0>(s4[0], m); s4[1] = drop_if_set<1>(s4[1], m);
+                            s4[2] = drop_if_set<2>(s4[2], m); s4[3] = drop_if_set<3>(s4[3], m);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) score_weight_staged<AN>(w[j], s4[j], P, Q, M, nM, acc);
                     }
                 }
             };

@@ -195,6 +195,19 @@ __device__ __forceinline__ void read8(const char* __restrict__ wrow, int32_t c, 
     }
 }
 
+// Four consecutive weights of a lane's row, starting at column c (a multiple of 4).
+template <int DT>
+__device__ __forceinline__ void read4(const char* __restrict__ wrow, int32_t c, float (&w)[4]) {
+    if (DT == WINDQ_BF16) {
+        const uint2 raw = *reinterpret_cast<const uint2*>(wrow + c * 2);
+        w[0] = bf16_bits_to_f32(raw.x & 0xffffu); w[1] = __uint_as_float(raw.x & 0xffff0000u);
+        w[2] = bf16_bits_to_f32(raw.y & 0xffffu); w[3] = __uint_as_float(raw.y & 0xffff0000u);
+    } else {
+        const float4 a = *reinterpret_cast<const float4*>(wrow + c * 4);
+        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+    }
+}
+
 // Keeps a value in a VGPR and hides its origin from the optimiser, so that it is never
 // folded into an SGPR, literal or negated operand (any of which drops the instruction
 // to the slow issue rate).

@@ -170,8 +170,8 @@ def one_block(torch, stack, steps, warmup, fused=True):
 
 def protected_pass(wq, torch, stack, ppm, reps):
     """Block 0 with salient-weight protection at `ppm` parts per million: mask selection and INT8
-    encoding once per matrix, then fit+score and apply-plan under the masks (batch calls), refinement and the
-    dequantisation check per matrix.  Timed per call with events, outside the step that `value` is quoted on."""
+    encoding, then fit+score and apply-plan under the masks, refinement and the dequantisation check: every one a
+    batch call over the block's matrices.  Timed per call with events, outside the step that `value` is quoted on."""
     G, unit_rows, cg = stack.G, stack.unit_rows, stack.clip_grid
     blk = stack.blocks[0]
     mats = blk.mats
@@ -186,34 +186,36 @@ def protected_pass(wq, torch, stack, ppm, reps):
         extra.append(dict(
             mask=torch.empty(sp.rows, sp.cols // 8, dtype=torch.uint8, device=m.W.device),
             ws=torch.empty(need, dtype=torch.uint8, device=m.W.device),
-            out=(torch.empty(m.U, max(n_p, 1), dtype=torch.int8, device=m.W.device),
+            out=(torch.empty(m.U, n_p, dtype=torch.int8, device=m.W.device),
                  torch.empty(m.U, dtype=torch.float32, device=m.W.device),
                  torch.empty(m.U, dtype=torch.float32, device=m.W.device)),
+            err=torch.empty(m.U, dtype=torch.float32, device=m.W.device),
             n_prot=torch.full((m.U,), n_p, dtype=torch.int64)))
     total_cb = total_n = 0
     for rep in range(reps + 1):
         if rep == 1:
             timer = CallTimer(torch)          # the first round is the warm-up
         total_cb = total_n = 0
-        for m, e in zip(mats, extra):
-            s = blk.xs[m.spec.x_key]["s"]
-            timer.time("salient_select", lambda: wq.windq_salient_select(m.W, s, G, unit_rows, ppm, ws=e["ws"], out=e["mask"]))
-            timer.time("salient_encode", lambda: wq.windq_salient_encode(m.W, s, G, unit_rows, e["mask"], ppm, ws=e["ws"], out=e["out"]))
         Ws = [m.W for m in mats]
         ss = [blk.xs[m.spec.x_key]["s"] for m in mats]
         masks = [e["mask"] for e in extra]
+        wss = [e["ws"] for e in extra]
+        timer.time("salient_select", lambda: wq.windq_salient_select_batch(Ws, ss, G, unit_rows, ppm, wss=wss, outs=masks))
+        timer.time("salient_encode", lambda: wq.windq_salient_encode_batch(Ws, ss, G, unit_rows, masks, ppm, wss=wss,
+                                                                           outs=[e["out"] for e in extra]))
         timer.time("fit_score_all_bits_prot", lambda: wq.windq_fit_score_all_bits_batch(
             Ws, ss, G, unit_rows, cg, wss=stack.ws, outs=[(m.err, m.clip_idx, m.ref) for m in mats], masks=masks))
         timer.time("apply_plan_prot", lambda: wq.windq_apply_plan_batch(
             Ws, G, unit_rows, [m.action_d for m in mats], [m.clip_idx for m in mats], cg, [m.off_d for m in mats],
             [m.codes for m in mats], [(m.scale, m.offset) for m in mats], wss=stack.ws, masks=masks))
+        timer.time("refine_plan_prot_3_rounds", lambda: wq.windq_refine_plan_batch(
+            Ws, ss, G, unit_rows, [m.action_d for m in mats], [m.clip_idx for m in mats], cg, [m.off_d for m in mats], 3,
+            [m.codes for m in mats], outs=[(m.scale, m.offset, e["err"]) for m, e in zip(mats, extra)], masks=masks, wss=wss))
+        timer.time("dequant_plan_prot", lambda: wq.windq_dequant_plan_batch(
+            Ws, ss, G, unit_rows, [m.action_d for m in mats], [m.off_d for m in mats], [m.codes for m in mats],
+            [m.scale for m in mats], [m.offset for m in mats], masks=masks, wss=wss,
+            outs=[(e["err"], None) for e in extra]))
         for m, e in zip(mats, extra):
-            s = blk.xs[m.spec.x_key]["s"]
-            timer.time("refine_plan_prot_3_rounds", lambda: wq.windq_refine_plan(
-                m.W, s, G, unit_rows, m.action_d, m.clip_idx, cg, m.off_d, 3, codes=m.codes, mask=e["mask"], ws=e["ws"]))
-            timer.time("dequant_plan_prot", lambda: wq.windq_dequant_plan(
-                m.W, s, G, unit_rows, m.action_d, m.off_d, m.codes, m.scale, m.offset, mask=e["mask"],
-                want_w_hat=False, ws=e["ws"]))
             cb, n = wq.windq_effective_bits(m.action, m.n_unit, e["n_prot"])
             total_cb += cb
             total_n += n

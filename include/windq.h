@@ -373,6 +373,31 @@ int windq_salient_encode(const windq_mat* W, const float* s /*[cols]*/, int32_t 
                          void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * windq_salient_select / windq_salient_encode for up to WINDQ_MAX_BATCH matrices with one
+ * launch per kernel instead of one per kernel and matrix (a decoder block has seven
+ * matrices: ten launches to select, four to encode).  Results are bit-identical to the
+ * per-matrix calls.  One chunk width, unit_rows, rate and element type for all items; every
+ * item brings its own workspace (WINDQ_CALL_SALIENT for its shape).  select reads W, s and
+ * writes mask; encode reads W, s, mask and writes prot_codes, prot_scale, err_prot (select
+ * ignores those three).  All items are checked before the first launch; WINDQ_EINVAL for n
+ * outside 1..WINDQ_MAX_BATCH or mixed element types, otherwise as the per-matrix calls.
+ */
+typedef struct windq_salient_item {
+    const windq_mat* W;
+    const float* s;           /* [cols] */
+    uint8_t* mask;            /* [rows][cols/8]: select writes it, encode reads it */
+    int8_t* prot_codes;       /* [U][n_p]   (encode) */
+    float* prot_scale;        /* [U]        (encode) */
+    float* err_prot;          /* [U]        (encode) */
+    void* ws;
+    size_t ws_bytes;
+} windq_salient_item;
+int windq_salient_select_batch(const windq_salient_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w,
+                               int64_t unit_rows, uint32_t rate_ppm, void* stream);
+int windq_salient_encode_batch(const windq_salient_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w,
+                               int64_t unit_rows, uint32_t rate_ppm, void* stream);
+
+/*
  * windq_fit_score_all_bits and windq_apply_plan under a protection mask (Sec. 3.5: the
  * remaining weights use the selected bit-width).  Protected weights take no part in the
  * fit: a group's min, max and mean |w| run over its kept weights (mean = sum / number
@@ -451,6 +476,31 @@ int windq_dequant_plan(const windq_mat* W, const float* s /*[cols]*/, int32_t ch
                        void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * windq_dequant_plan for up to WINDQ_MAX_BATCH matrices in one launch (plus one that sums the
+ * errors): bit-identical to the per-matrix calls.  One chunk width, unit_rows and element
+ * type for all items; every item brings its own workspace (WINDQ_CALL_DEQUANT for its shape).
+ * Matrices whose pointers or leading dimension are not 16-byte aligned take a second pair of
+ * launches, as they take a slower kernel alone.
+ */
+typedef struct windq_dequant_item {
+    const windq_mat* W;
+    const float* s;           /* [cols] */
+    const uint8_t* mask;      /* [rows][cols/8] or NULL */
+    const uint8_t* action;    /* [U] */
+    const int64_t* code_off;  /* [U+1] */
+    const uint8_t* codes;
+    size_t codes_bytes;
+    const float* scale;       /* [U*R_u] */
+    const float* offset;      /* [U*R_u] */
+    float* err;               /* [U] or NULL */
+    float* w_hat;             /* [rows][cols] or NULL */
+    void* ws;
+    size_t ws_bytes;
+} windq_dequant_item;
+int windq_dequant_plan_batch(const windq_dequant_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w,
+                             int64_t unit_rows, void* stream);
+
+/*
  * windq_apply_plan with refined scales (App. "Per-unit Scale Optimization": each operator fits
  * its scale by a short local optimisation of the reconstruction loss on the unit).  Every
  * group is seeded with its grid fit (clip ratio clip_grid[clip_idx[u][a-1]], p = 1 when
@@ -472,6 +522,30 @@ int windq_refine_plan(const windq_mat* W, const float* s /*[cols]*/, int32_t chu
                       const int64_t* code_off /*[U+1]*/, uint8_t* codes, size_t codes_bytes,
                       float* scale /*[U*R_u]*/, float* offset /*[U*R_u]*/, float* err /*[U]*/,
                       void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * windq_refine_plan for up to WINDQ_MAX_BATCH matrices in one launch (plus one that sums the
+ * errors): bit-identical to the per-matrix calls.  One chunk width, unit_rows, clip grid,
+ * round count and element type for all items; masks and clip indices may be NULL item by
+ * item; every item brings its own workspace (WINDQ_CALL_REFINE for its shape).
+ */
+typedef struct windq_refine_item {
+    const windq_mat* W;
+    const float* s;           /* [cols] */
+    const uint8_t* mask;      /* [rows][cols/8] or NULL */
+    const uint8_t* action;    /* [U] */
+    const uint8_t* clip_idx;  /* [U][4] or NULL */
+    const int64_t* code_off;  /* [U+1] */
+    uint8_t* codes;
+    size_t codes_bytes;
+    float* scale;             /* [U*R_u] */
+    float* offset;            /* [U*R_u] */
+    float* err;               /* [U] */
+    void* ws;
+    size_t ws_bytes;
+} windq_refine_item;
+int windq_refine_plan_batch(const windq_refine_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                            const float* clip_grid /*HOST [K]*/, int32_t K, int32_t n_iter, void* stream);
 
 /* Workspace bytes a call needs for these shapes (0 if the shape is invalid). HOST only. */
 size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, int64_t cols,

@@ -28,7 +28,8 @@ EXPORTS = (
     "windq_fallback_promote", "windq_dequant_plan", "windq_refine_plan", "windq_fit_score_all_bits_batch",
     "windq_unit_features_batch", "windq_apply_plan_batch", "windq_calib_stats_batch", "windq_fit_score_rescored_units",
     "windq_fit_score_all_bits_static", "windq_features_fit_score", "windq_features_fit_score_batch",
-    "windq_kernel_timer", "windq_kernel_timer_read",
+    "windq_kernel_timer", "windq_kernel_timer_read", "windq_salient_select_batch", "windq_salient_encode_batch",
+    "windq_refine_plan_batch", "windq_dequant_plan_batch",
 )
 
 
@@ -66,6 +67,28 @@ class windq_apply_item(ctypes.Structure):
                 ("clip_idx", ctypes.c_void_p),
                 ("code_off", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("codes_bytes", ctypes.c_size_t),
                 ("scale", ctypes.c_void_p), ("offset", ctypes.c_void_p), ("ws", ctypes.c_void_p),
+                ("ws_bytes", ctypes.c_size_t)]
+
+
+class windq_salient_item(ctypes.Structure):
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("mask", ctypes.c_void_p),
+                ("prot_codes", ctypes.c_void_p), ("prot_scale", ctypes.c_void_p), ("err_prot", ctypes.c_void_p),
+                ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
+
+
+class windq_refine_item(ctypes.Structure):
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("mask", ctypes.c_void_p),
+                ("action", ctypes.c_void_p), ("clip_idx", ctypes.c_void_p), ("code_off", ctypes.c_void_p),
+                ("codes", ctypes.c_void_p), ("codes_bytes", ctypes.c_size_t), ("scale", ctypes.c_void_p),
+                ("offset", ctypes.c_void_p), ("err", ctypes.c_void_p), ("ws", ctypes.c_void_p),
+                ("ws_bytes", ctypes.c_size_t)]
+
+
+class windq_dequant_item(ctypes.Structure):
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("s", ctypes.c_void_p), ("mask", ctypes.c_void_p),
+                ("action", ctypes.c_void_p), ("code_off", ctypes.c_void_p), ("codes", ctypes.c_void_p),
+                ("codes_bytes", ctypes.c_size_t), ("scale", ctypes.c_void_p), ("offset", ctypes.c_void_p),
+                ("err", ctypes.c_void_p), ("w_hat", ctypes.c_void_p), ("ws", ctypes.c_void_p),
                 ("ws_bytes", ctypes.c_size_t)]
 
 
@@ -128,6 +151,14 @@ def load(path: str | None = None):
     lib.windq_fit_score_all_bits_static.restype = c.c_int
     lib.windq_fit_score_rescored_units.argtypes = [vp, i32, i64, i64, i32, i64, i32, c.POINTER(i64)]
     lib.windq_fit_score_rescored_units.restype = c.c_int
+    lib.windq_salient_select_batch.argtypes = [c.POINTER(windq_salient_item), i32, i32, i64, u32, vp]
+    lib.windq_salient_select_batch.restype = c.c_int
+    lib.windq_salient_encode_batch.argtypes = [c.POINTER(windq_salient_item), i32, i32, i64, u32, vp]
+    lib.windq_salient_encode_batch.restype = c.c_int
+    lib.windq_refine_plan_batch.argtypes = [c.POINTER(windq_refine_item), i32, i32, i64, vp, i32, i32, vp]
+    lib.windq_refine_plan_batch.restype = c.c_int
+    lib.windq_dequant_plan_batch.argtypes = [c.POINTER(windq_dequant_item), i32, i32, i64, vp]
+    lib.windq_dequant_plan_batch.restype = c.c_int
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
@@ -518,6 +549,54 @@ def windq_salient_encode(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_ro
     return codes, scale, err
 
 
+def _salient_outs(W, chunk_w, unit_rows, rate_ppm):
+    U, R_u = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+    n_p = windq_n_protected(R_u * chunk_w, rate_ppm)
+    return (torch.empty(U, n_p, dtype=torch.int8, device=W.device), torch.empty(U, dtype=torch.float32, device=W.device),
+            torch.empty(U, dtype=torch.float32, device=W.device))
+
+
+def windq_salient_select_batch(Ws, ss, chunk_w: int, unit_rows: int, rate_ppm: int, wss=None, outs=None):
+    """windq_salient_select for several matrices (lists of equal length, at most MAX_BATCH): one launch per kernel.
+    -> [mask u8 [rows x cols/8]] per matrix."""
+    n = len(Ws)
+    assert len(ss) == n and (wss is None or len(wss) == n) and (outs is None or len(outs) == n)
+    _require_cuda(*Ws, *ss)
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_salient_item * max(n, 1))()
+    masks, keep = [], []
+    for i, W in enumerate(Ws):
+        mask = outs[i] if outs is not None else torch.empty(W.shape[0], W.shape[1] // 8, dtype=torch.uint8, device=W.device)
+        ws = _workspace(CALL_SALIENT, W, chunk_w, unit_rows, 1, None if wss is None else wss[i])
+        masks.append(mask)
+        keep.append(ws)
+        items[i] = windq_salient_item(ctypes.pointer(mats[i]), ss[i].data_ptr(), mask.data_ptr(), None, None, None,
+                                      ws.data_ptr(), ws.numel())
+    _check(load().windq_salient_select_batch(items, n, chunk_w, unit_rows, rate_ppm, _stream()), "windq_salient_select_batch")
+    return masks
+
+
+def windq_salient_encode_batch(Ws, ss, chunk_w: int, unit_rows: int, masks, rate_ppm: int, wss=None, outs=None):
+    """windq_salient_encode for several matrices: one launch per kernel.
+    -> [(prot_codes i8 [U x n_p], prot_scale f32 [U], err_prot f32 [U])] per matrix."""
+    n = len(Ws)
+    assert len(ss) == n and len(masks) == n and (wss is None or len(wss) == n) and (outs is None or len(outs) == n)
+    _require_cuda(*Ws, *ss, *masks)
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_salient_item * max(n, 1))()
+    res, keep = [], []
+    for i, W in enumerate(Ws):
+        codes, scale, err = outs[i] if outs is not None else _salient_outs(W, chunk_w, unit_rows, rate_ppm)
+        ws = _workspace(CALL_SALIENT, W, chunk_w, unit_rows, 1, None if wss is None else wss[i])
+        res.append((codes, scale, err))
+        keep.append(ws)
+        items[i] = windq_salient_item(ctypes.pointer(mats[i]), ss[i].data_ptr(), masks[i].data_ptr(),
+                                      codes.data_ptr() if codes.numel() > 0 else None, scale.data_ptr(), err.data_ptr(),
+                                      ws.data_ptr(), ws.numel())
+    _check(load().windq_salient_encode_batch(items, n, chunk_w, unit_rows, rate_ppm, _stream()), "windq_salient_encode_batch")
+    return res
+
+
 # --------------------------------------------- heuristic allocator and fallback
 def windq_unit_saliency(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows: int = 0,
                         ws: torch.Tensor | None = None, out: torch.Tensor | None = None):
@@ -595,3 +674,63 @@ def windq_refine_plan(W: torch.Tensor, s: torch.Tensor, chunk_w: int, unit_rows:
                                     offset.data_ptr(), err.data_ptr(), ws.data_ptr(), ws.numel(), _stream()),
            "windq_refine_plan")
     return codes, scale, offset, err
+
+
+def windq_refine_plan_batch(Ws, ss, chunk_w: int, unit_rows: int, actions, clip_idxs, clip_grid, code_offs, n_iter: int,
+                            codes, outs=None, masks=None, wss=None):
+    """windq_refine_plan for several matrices (lists of equal length, at most MAX_BATCH) in one launch.
+    clip_idxs and masks: lists whose entries may be None (masks itself may be None); codes: caller-allocated u8
+    tensors; outs: (scale, offset, err) per matrix or None.  -> [(codes, scale, offset, err)] per matrix."""
+    n = len(Ws)
+    assert all(len(x) == n for x in (ss, actions, clip_idxs, code_offs, codes))
+    _require_cuda(*Ws, *ss, *actions, *code_offs, *codes)
+    K = 0 if clip_grid is None else clip_grid.numel()
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_refine_item * max(n, 1))()
+    res, keep = [], []
+    for i, W in enumerate(Ws):
+        U, R_u = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+        if outs is not None:
+            scale, offset, err = outs[i]
+        else:
+            scale = torch.empty(U * R_u, dtype=torch.float32, device=W.device)
+            offset = torch.empty(U * R_u, dtype=torch.float32, device=W.device)
+            err = torch.empty(U, dtype=torch.float32, device=W.device)
+        ws = _workspace(CALL_REFINE, W, chunk_w, unit_rows, 1, None if wss is None else wss[i])
+        keep.append(ws)
+        res.append((codes[i], scale, offset, err))
+        items[i] = windq_refine_item(ctypes.pointer(mats[i]), ss[i].data_ptr(), None if masks is None else _ptr(masks[i]),
+                                     actions[i].data_ptr(), _ptr(clip_idxs[i]), code_offs[i].data_ptr(),
+                                     codes[i].data_ptr(), codes[i].numel(), scale.data_ptr(), offset.data_ptr(),
+                                     err.data_ptr(), ws.data_ptr(), ws.numel())
+    _check(load().windq_refine_plan_batch(items, n, chunk_w, unit_rows, None if clip_grid is None else clip_grid.data_ptr(),
+                                          K, n_iter, _stream()), "windq_refine_plan_batch")
+    return res
+
+
+def windq_dequant_plan_batch(Ws, ss, chunk_w: int, unit_rows: int, actions, code_offs, codes, scales, offsets, masks=None,
+                             want_w_hat: bool = True, wss=None, outs=None):
+    """windq_dequant_plan for several matrices (lists of equal length, at most MAX_BATCH) in one launch.
+    outs: (err, w_hat or None) per matrix, or None to allocate.  -> [(err f32 [U], w_hat f32 [rows x cols] or None)]."""
+    n = len(Ws)
+    assert all(len(x) == n for x in (ss, actions, code_offs, codes, scales, offsets))
+    _require_cuda(*Ws, *ss, *actions, *code_offs, *codes, *scales, *offsets)
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_dequant_item * max(n, 1))()
+    res, keep = [], []
+    for i, W in enumerate(Ws):
+        U, _ = n_units(W.shape[0], W.shape[1], chunk_w, unit_rows)
+        if outs is not None:
+            err, w_hat = outs[i]
+        else:
+            err = torch.empty(U, dtype=torch.float32, device=W.device)
+            w_hat = torch.empty(W.shape[0], W.shape[1], dtype=torch.float32, device=W.device) if want_w_hat else None
+        ws = _workspace(CALL_DEQUANT, W, chunk_w, unit_rows, 1, None if wss is None else wss[i])
+        keep.append(ws)
+        res.append((err, w_hat))
+        items[i] = windq_dequant_item(ctypes.pointer(mats[i]), ss[i].data_ptr(), None if masks is None else _ptr(masks[i]),
+                                      actions[i].data_ptr(), code_offs[i].data_ptr(), codes[i].data_ptr(), codes[i].numel(),
+                                      scales[i].data_ptr(), offsets[i].data_ptr(), _ptr(err), _ptr(w_hat), ws.data_ptr(),
+                                      ws.numel())
+    _check(load().windq_dequant_plan_batch(items, n, chunk_w, unit_rows, _stream()), "windq_dequant_plan_batch")
+    return res

@@ -33,7 +33,18 @@ struct DequantArgs {
     Geometry g;
     float* what;               // [rows][what_ld] or null
     int64_t what_ld;
-    double* part;              // [n_tiles]
+    double* part;              // [n_tiles] or [n_tiles][passes]
+    float* err;                // [U] or null
+    int64_t per_unit;          // partials per unit
+};
+
+// A launch covers up to WINDQ_MAX_BATCH matrices (one chunk width, one element type): their
+// tiles and units are numbered one matrix after the other.
+struct DequantBatch {
+    int32_t n;
+    int64_t tile_start[WINDQ_MAX_BATCH + 1];
+    int64_t unit_start[WINDQ_MAX_BATCH + 1];
+    DequantArgs m[WINDQ_MAX_BATCH];
 };
 
 __device__ __forceinline__ int64_t dq_bytes_per_group(int a, int G) {
@@ -49,9 +60,11 @@ __device__ __forceinline__ int64_t dq_bytes_per_group(int a, int G) {
 }
 
 template <int DT>
-__global__ __launch_bounds__(64) void dequant_tile_kernel(const DequantArgs A) {
+__global__ __launch_bounds__(64) void dequant_tile_kernel(const DequantBatch B) {
     extern __shared__ char smem[];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const DequantArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
     constexpr int EB = Elem<DT>::bytes;
     const int32_t row_bytes = G * EB + 16;
@@ -153,12 +166,14 @@ __device__ __forceinline__ void load8_global(const void* __restrict__ p, float (
 // of a workgroup's loads are in flight together.
 constexpr int DQ_THREADS = 256;
 template <int DT>
-__global__ __launch_bounds__(DQ_THREADS) void dequant_split_kernel(const DequantArgs A, const int lpr_shift) {
+__global__ __launch_bounds__(DQ_THREADS) void dequant_split_kernel(const DequantBatch B, const int lpr_shift) {
     __shared__ double red[DQ_THREADS / 64];
-    const int32_t passes = dequant_passes(A.g.chunk_w);
-    const int64_t tile = blockIdx.x / passes;
-    const int32_t pass = (int32_t)(blockIdx.x - tile * passes);
-    const TileCoord tc = tile_coord(A.g, tile);
+    const int32_t passes = dequant_passes(8 << lpr_shift);
+    const int64_t tile_b = blockIdx.x / passes;                 // tile of the launch
+    const int32_t pass = (int32_t)(blockIdx.x - tile_b * passes);
+    const int mi = batch_index(B.tile_start, B.n, tile_b);
+    const DequantArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, tile_b - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
     constexpr int EB = Elem<DT>::bytes;
     const int sub = threadIdx.x & ((1 << lpr_shift) - 1);      // which 8 columns of the row
@@ -282,71 +297,126 @@ __global__ __launch_bounds__(DQ_THREADS) void dequant_split_kernel(const Dequant
 }
 
 // err[u] = the sum of unit u's per_unit partials; one workgroup per unit.
-__global__ __launch_bounds__(256) void dequant_finalize_kernel(const double* __restrict__ part, const int64_t per_unit,
-                                                              float* __restrict__ err) {
+__global__ __launch_bounds__(256) void dequant_finalize_kernel(const DequantBatch B) {
     __shared__ double red[4];
-    const double t = unit_partial_sum<256>(part + (size_t)blockIdx.x * (size_t)per_unit, per_unit, red);
-    if (threadIdx.x == 0) err[blockIdx.x] = (float)t;
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
+    const DequantArgs& A = B.m[mi];
+    if (A.err == nullptr) return;
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
+    const double t = unit_partial_sum<256>(A.part + (size_t)u * (size_t)A.per_unit, A.per_unit, red);
+    if (threadIdx.x == 0) A.err[u] = (float)t;
+}
+
+// Numbers the tiles and units of the first B->n matrices.
+static int64_t dequant_number(DequantBatch* B) {
+    int64_t tiles = 0, units = 0;
+    for (int32_t i = 0; i < B->n; ++i) {
+        B->tile_start[i] = tiles;
+        B->unit_start[i] = units;
+        tiles += B->m[i].g.n_tiles;
+        units += B->m[i].g.U;
+    }
+    for (int32_t i = B->n; i <= WINDQ_MAX_BATCH; ++i) {
+        B->tile_start[i] = tiles;
+        B->unit_start[i] = units;
+    }
+    for (int32_t i = B->n; i < WINDQ_MAX_BATCH; ++i) B->m[i] = B->m[0];
+    return tiles;
 }
 
 }  // namespace windq
 
 using namespace windq;
 
-extern "C" int windq_dequant_plan(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
-                                  const uint8_t* mask, const uint8_t* action, const int64_t* code_off,
-                                  const uint8_t* codes, size_t codes_bytes, const float* scale, const float* offset,
-                                  float* err, float* w_hat, void* ws, size_t ws_bytes, void* stream) {
-    DequantArgs A;
-    int st = make_geometry(W, chunk_w, unit_rows, &A.g);
-    if (st != WINDQ_OK) return st;
-    if (s == nullptr || action == nullptr || code_off == nullptr || scale == nullptr || offset == nullptr)
-        return WINDQ_EINVAL;
-    if (codes == nullptr && codes_bytes != 0) return WINDQ_EINVAL;
-    if (err == nullptr && w_hat == nullptr) return WINDQ_EINVAL;
-    if (!aligned(code_off, 8) || (w_hat != nullptr && !aligned(w_hat, 4))) return WINDQ_EINVAL;
-    if (ws == nullptr || ws_bytes < dequant_ws_bytes(A.g) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
-    A.W = W->data;
-    A.s = s;
-    A.mask = mask;
-    A.mask_ld = W->cols / 8;
-    A.action = action;
-    A.code_off = code_off;
-    A.codes = codes;
-    A.codes_bytes = (int64_t)codes_bytes;
-    A.scale = scale;
-    A.offset = offset;
-    A.what = w_hat;
-    A.what_ld = W->cols;
-    A.part = static_cast<double*>(ws);
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
-    const dim3 tiles((unsigned)A.g.n_tiles);
+// Matrices whose layout allows it go through the lanes-per-row kernel, the others through the
+// tile kernel, exactly as each would alone: at most two sub-batches per call.
+static int dequant_launch(const windq_dequant_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
     // lanes-per-row kernel: 8 x 2^k columns, 16-byte pieces of W and of w_hat aligned
     int lpr_shift = -1;
     for (int k = 0; k <= 6; ++k)
         if (chunk_w == (8 << k)) lpr_shift = k;
-    const size_t eb = W->dtype == WINDQ_BF16 ? 2 : 4;
-    const bool split = lpr_shift >= 0 && aligned(W->data, 16) && ((size_t)W->ld * eb) % 16 == 0 &&
-                       (w_hat == nullptr || aligned(w_hat, 16)) && aligned(codes, 8);
-    int64_t per_unit = A.g.tiles_per_unit;
-    if (split) {
-        const int32_t passes = dequant_passes(chunk_w);
-        if (A.g.n_tiles * passes > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
-        const dim3 grid((unsigned)(A.g.n_tiles * passes));
-        per_unit *= passes;
-        if (W->dtype == WINDQ_BF16) hipLaunchKernelGGL(dequant_split_kernel<WINDQ_BF16>, grid, dim3(DQ_THREADS), 0, hs, A, lpr_shift);
-        else hipLaunchKernelGGL(dequant_split_kernel<WINDQ_F32>, grid, dim3(DQ_THREADS), 0, hs, A, lpr_shift);
-    } else if (W->dtype == WINDQ_BF16) {
-        st = ensure_lds(reinterpret_cast<const void*>(&dequant_tile_kernel<WINDQ_BF16>), lds);
+    const int32_t passes = dequant_passes(chunk_w);
+    DequantBatch S, T;          // lanes-per-row, tile
+    S.n = T.n = 0;
+    bool any_err_s = false, any_err_t = false;
+    for (int32_t i = 0; i < n; ++i) {
+        const windq_dequant_item& it = items[i];
+        DequantArgs A;
+        if (it.W == nullptr) return WINDQ_EINVAL;
+        const int st = make_geometry(it.W, chunk_w, unit_rows, &A.g);
         if (st != WINDQ_OK) return st;
-        hipLaunchKernelGGL(dequant_tile_kernel<WINDQ_BF16>, tiles, dim3(64), lds, hs, A);
-    } else {
-        st = ensure_lds(reinterpret_cast<const void*>(&dequant_tile_kernel<WINDQ_F32>), lds);
-        if (st != WINDQ_OK) return st;
-        hipLaunchKernelGGL(dequant_tile_kernel<WINDQ_F32>, tiles, dim3(64), lds, hs, A);
+        if (it.s == nullptr || it.action == nullptr || it.code_off == nullptr || it.scale == nullptr || it.offset == nullptr)
+            return WINDQ_EINVAL;
+        if (it.codes == nullptr && it.codes_bytes != 0) return WINDQ_EINVAL;
+        if (it.err == nullptr && it.w_hat == nullptr) return WINDQ_EINVAL;
+        if (!aligned(it.code_off, 8) || (it.w_hat != nullptr && !aligned(it.w_hat, 4))) return WINDQ_EINVAL;
+        if (it.W->dtype != items[0].W->dtype) return WINDQ_EINVAL;      // one kernel per launch
+        if (it.ws == nullptr || it.ws_bytes < dequant_ws_bytes(A.g) || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
+        A.W = it.W->data;
+        A.s = it.s;
+        A.mask = it.mask;
+        A.mask_ld = it.W->cols / 8;
+        A.action = it.action;
+        A.code_off = it.code_off;
+        A.codes = it.codes;
+        A.codes_bytes = (int64_t)it.codes_bytes;
+        A.scale = it.scale;
+        A.offset = it.offset;
+        A.what = it.w_hat;
+        A.what_ld = it.W->cols;
+        A.part = static_cast<double*>(it.ws);
+        A.err = it.err;
+        const size_t eb = it.W->dtype == WINDQ_BF16 ? 2 : 4;
+        const bool split = lpr_shift >= 0 && aligned(it.W->data, 16) && ((size_t)it.W->ld * eb) % 16 == 0 &&
+                           (it.w_hat == nullptr || aligned(it.w_hat, 16)) && aligned(it.codes, 8);
+        A.per_unit = split ? A.g.tiles_per_unit * passes : A.g.tiles_per_unit;
+        if (split) {
+            S.m[S.n++] = A;
+            any_err_s = any_err_s || it.err != nullptr;
+        } else {
+            T.m[T.n++] = A;
+            any_err_t = any_err_t || it.err != nullptr;
+        }
     }
-    if (err != nullptr)
-        hipLaunchKernelGGL(dequant_finalize_kernel, dim3((unsigned)A.g.U), dim3(256), 0, hs, A.part, per_unit, err);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int32_t dtype = items[0].W->dtype;
+    if (S.n > 0) {
+        const int64_t tiles = dequant_number(&S);
+        if (tiles * passes > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
+        const dim3 grid((unsigned)(tiles * passes));
+        if (dtype == WINDQ_BF16) hipLaunchKernelGGL(dequant_split_kernel<WINDQ_BF16>, grid, dim3(DQ_THREADS), 0, hs, S, lpr_shift);
+        else hipLaunchKernelGGL(dequant_split_kernel<WINDQ_F32>, grid, dim3(DQ_THREADS), 0, hs, S, lpr_shift);
+        if (any_err_s) hipLaunchKernelGGL(dequant_finalize_kernel, dim3((unsigned)S.unit_start[S.n]), dim3(256), 0, hs, S);
+    }
+    if (T.n > 0) {
+        const int64_t tiles = dequant_number(&T);
+        if (tiles > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
+        const size_t lds = raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
+        const dim3 grid((unsigned)tiles);
+        if (dtype == WINDQ_BF16) {
+            const int st = ensure_lds(reinterpret_cast<const void*>(&dequant_tile_kernel<WINDQ_BF16>), lds);
+            if (st != WINDQ_OK) return st;
+            hipLaunchKernelGGL(dequant_tile_kernel<WINDQ_BF16>, grid, dim3(64), lds, hs, T);
+        } else {
+            const int st = ensure_lds(reinterpret_cast<const void*>(&dequant_tile_kernel<WINDQ_F32>), lds);
+            if (st != WINDQ_OK) return st;
+            hipLaunchKernelGGL(dequant_tile_kernel<WINDQ_F32>, grid, dim3(64), lds, hs, T);
+        }
+        if (any_err_t) hipLaunchKernelGGL(dequant_finalize_kernel, dim3((unsigned)T.unit_start[T.n]), dim3(256), 0, hs, T);
+    }
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+}
+
+extern "C" int windq_dequant_plan(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
+                                  const uint8_t* mask, const uint8_t* action, const int64_t* code_off,
+                                  const uint8_t* codes, size_t codes_bytes, const float* scale, const float* offset,
+                                  float* err, float* w_hat, void* ws, size_t ws_bytes, void* stream) {
+    const windq_dequant_item it = {W, s, mask, action, code_off, codes, codes_bytes, scale, offset, err, w_hat, ws, ws_bytes};
+    return dequant_launch(&it, 1, chunk_w, unit_rows, stream);
+}
+
+extern "C" int windq_dequant_plan_batch(const windq_dequant_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                        void* stream) {
+    return dequant_launch(items, n, chunk_w, unit_rows, stream);
 }

@@ -35,41 +35,73 @@ struct RefineArgs {
     float* scale;
     float* offset;
     double* part;              // [n_tiles]
+    float* err;                // [U]
     Geometry g;
+};
+
+// A launch covers up to WINDQ_MAX_BATCH matrices (one chunk width, one element type, one clip
+// grid and round count): their tiles and units are numbered one matrix after the other.
+struct RefineBatch {
+    int32_t n;
     int32_t K;
     int32_t n_iter;
+    int64_t tile_start[WINDQ_MAX_BATCH + 1];
+    int64_t unit_start[WINDQ_MAX_BATCH + 1];
+    RefineArgs m[WINDQ_MAX_BATCH];
     ClipGrid grid;
 };
 
 __device__ __forceinline__ bool kept_bit(uint32_t m, int j) { return ((m >> j) & 1u) == 0u; }
 
+// The sums of one round of the uniform refinement over a group.  S0 = sum a and T0 = sum a w do
+// not depend on the codes: the first round computes them (FIRST), later rounds reuse them; the
+// order of every sum is the column order either way.
+template <int DT, bool FIRST>
+__device__ __forceinline__ void uniform_sums(const char* wrow, const uint8_t* mrow, const double* acol, int32_t G,
+                                             float lo, float inv, float qmax, double* S0_io, double* T0_io,
+                                             double* S1_o, double* S2_o, double* T1_o) {
+    double S0 = 0.0, S1 = 0.0, S2 = 0.0, T0 = 0.0, T1 = 0.0;
+    for (int32_t c = 0; c < G; c += 8) {
+        float w[8];
+        read8<DT>(wrow, c, w);
+        const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float u = w[j] - lo;
+            const float t = u * inv;
+            const double q = (double)__builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, qmax);
+            const double a = kept_bit(m, j) ? acol[c + j] : 0.0;      // a masked weight adds zeros
+            const double wd = (double)w[j];
+            const double aq = a * q;
+            if (FIRST) {
+                S0 = S0 + a;
+                T0 = T0 + a * wd;
+            }
+            S1 = S1 + aq;
+            S2 = S2 + aq * q;
+            T1 = T1 + aq * wd;
+        }
+    }
+    if (FIRST) {
+        *S0_io = S0;
+        *T0_io = T0;
+    }
+    *S1_o = S1;
+    *S2_o = S2;
+    *T1_o = T1;
+}
+
 template <int DT>
 __device__ __forceinline__ void refine_uniform(const char* wrow, const uint8_t* mrow, const double* acol,
                                                int32_t G, float qmax, int n_iter, float* lo_io, float* d_io) {
     float lo = *lo_io, d = *d_io;
+    double S0 = 0.0, T0 = 0.0;
     for (int it = 0; it < n_iter; ++it) {
         if (!(d >= FLT_MIN)) break;
         const float inv = 1.0f / d;
-        double S0 = 0.0, S1 = 0.0, S2 = 0.0, T0 = 0.0, T1 = 0.0;
-        for (int32_t c = 0; c < G; c += 8) {
-            float w[8];
-            read8<DT>(wrow, c, w);
-            const uint32_t m = mrow != nullptr ? mrow[c >> 3] : 0u;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float u = w[j] - lo;
-                const float t = u * inv;
-                const double q = (double)__builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, qmax);
-                const double a = kept_bit(m, j) ? acol[c + j] : 0.0;      // a masked weight adds zeros
-                const double wd = (double)w[j];
-                const double aq = a * q;
-                S0 = S0 + a;
-                S1 = S1 + aq;
-                S2 = S2 + aq * q;
-                T0 = T0 + a * wd;
-                T1 = T1 + aq * wd;
-            }
-        }
+        double S1, S2, T1;
+        if (it == 0) uniform_sums<DT, true>(wrow, mrow, acol, G, lo, inv, qmax, &S0, &T0, &S1, &S2, &T1);
+        else uniform_sums<DT, false>(wrow, mrow, acol, G, lo, inv, qmax, &S0, &T0, &S1, &S2, &T1);
         const double det = S0 * S2 - S1 * S1;
         if (!(det > 0.0)) break;
         const double d_new = (S0 * T1 - S1 * T0) / det;
@@ -165,9 +197,11 @@ __device__ __forceinline__ double group_error(const char* wrow, const uint8_t* m
 constexpr int RF_THREADS = 64;
 
 template <int DT>
-__global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArgs A) {
+__global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineBatch B) {
     extern __shared__ char smem[];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const RefineArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
     const int32_t row_bytes = G * Elem<DT>::bytes + 16;
     char* tile = smem;
@@ -213,15 +247,15 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
             float p = 1.0f;
             if (A.clip_idx != nullptr) {
                 int k = A.clip_idx[tc.u * 4 + (a - 1)];
-                k = k < A.K ? k : A.K - 1;
-                p = A.grid.p[k];
+                k = k < B.K ? k : B.K - 1;
+                p = B.grid.p[k];
             }
             const int bits = a == 1 ? 8 : (a == 2 ? 4 : (a == 3 ? 3 : 2));
             const float qmax = (float)((1 << bits) - 1);
             float mn, mx;
             group_min_max<DT>(wrow, mrow, G, &mn, &mx);
             uniform_params(mn, mx, p, qmax, &of, &sc);
-            refine_uniform<DT>(wrow, mrow, acol, G, qmax, A.n_iter, &of, &sc);
+            refine_uniform<DT>(wrow, mrow, acol, G, qmax, B.n_iter, &of, &sc);
             err = group_error<DT>(wrow, mrow, acol, G, a, sc, of);
             switch (a) {
                 case 1: uniform_pack<DT, 8>(wrow, mrow, G, of, sc, dst); break;
@@ -232,12 +266,12 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
         } else if (a == 5) {
             sc = group_abs_mean<DT>(wrow, mrow, G);
             sc = sc >= FLT_MIN ? sc : 0.0f;
-            sc = refine_ternary<DT>(wrow, mrow, acol, G, A.n_iter, sc);
+            sc = refine_ternary<DT>(wrow, mrow, acol, G, B.n_iter, sc);
             err = group_error<DT>(wrow, mrow, acol, G, a, sc, 0.0f);
             ternary_pack<DT>(wrow, mrow, G, sc, dst);
         } else {
             sc = group_abs_mean<DT>(wrow, mrow, G);
-            if (A.n_iter > 0) sc = refine_binary<DT>(wrow, mrow, acol, G, sc);
+            if (B.n_iter > 0) sc = refine_binary<DT>(wrow, mrow, acol, G, sc);
             err = group_error<DT>(wrow, mrow, acol, G, a, sc, 0.0f);
             binary_pack<DT>(wrow, mrow, G, dst);
         }
@@ -254,66 +288,107 @@ __global__ __launch_bounds__(RF_THREADS) void refine_plan_kernel(const RefineArg
 }
 
 // err[u] = the sum of unit u's tile partials; one workgroup per unit.
-__global__ __launch_bounds__(256) void refine_finalize_kernel(const double* __restrict__ part, const int64_t per_unit,
-                                                             float* __restrict__ err) {
+__global__ __launch_bounds__(256) void refine_finalize_kernel(const RefineBatch B) {
     __shared__ double red[4];
-    const double t = unit_partial_sum<256>(part + (size_t)blockIdx.x * (size_t)per_unit, per_unit, red);
-    if (threadIdx.x == 0) err[blockIdx.x] = (float)t;
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
+    const RefineArgs& A = B.m[mi];
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
+    const double t = unit_partial_sum<256>(A.part + (size_t)u * (size_t)A.g.tiles_per_unit, A.g.tiles_per_unit, red);
+    if (threadIdx.x == 0) A.err[u] = (float)t;
 }
 
 }  // namespace windq
 
 using namespace windq;
 
-extern "C" int windq_refine_plan(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
-                                 const uint8_t* mask, const uint8_t* action, const uint8_t* clip_idx,
-                                 const float* clip_grid, int32_t K, int32_t n_iter, const int64_t* code_off,
-                                 uint8_t* codes, size_t codes_bytes, float* scale, float* offset, float* err, void* ws,
-                                 size_t ws_bytes, void* stream) {
-    RefineArgs A;
-    int st = make_geometry(W, chunk_w, unit_rows, &A.g);
-    if (st != WINDQ_OK) return st;
-    if (s == nullptr || action == nullptr || code_off == nullptr || scale == nullptr || offset == nullptr || err == nullptr)
-        return WINDQ_EINVAL;
+static int refine_launch(const windq_refine_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                         const float* clip_grid, int32_t K, int32_t n_iter, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
     if (n_iter < 0 || n_iter > 64) return WINDQ_EINVAL;
-    if (codes == nullptr && codes_bytes != 0) return WINDQ_EINVAL;
-    if (codes != nullptr && !aligned(codes, 16)) return WINDQ_EINVAL;
-    if (!aligned(code_off, 8)) return WINDQ_EINVAL;
-    if (clip_idx != nullptr || clip_grid != nullptr) {
+    bool any_idx = false, any_mask = false;
+    for (int32_t i = 0; i < n; ++i) {
+        any_idx = any_idx || items[i].clip_idx != nullptr;
+        any_mask = any_mask || items[i].mask != nullptr;
+    }
+    int st;
+    if (any_idx || clip_grid != nullptr) {
         st = check_clip_grid(clip_grid, K);
         if (st != WINDQ_OK) return st;
     } else {
         K = 1;
     }
-    if (ws == nullptr || ws_bytes < unit_saliency_ws_bytes(A.g) || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
-    A.W = W->data;
-    A.s = s;
-    A.mask = mask;
-    A.mask_ld = W->cols / 8;
-    A.action = action;
-    A.clip_idx = clip_grid != nullptr ? clip_idx : nullptr;
-    A.code_off = code_off;
-    A.codes = codes;
-    A.codes_bytes = (int64_t)codes_bytes;
-    A.scale = scale;
-    A.offset = offset;
-    A.part = static_cast<double*>(ws);
-    A.K = K;
-    A.n_iter = n_iter;
-    for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid != nullptr ? clip_grid[k < K ? k : K - 1] : 1.0f;
+    RefineBatch B;
+    B.n = n;
+    B.K = K;
+    B.n_iter = n_iter;
+    for (int k = 0; k < WINDQ_MAX_CLIP; ++k) B.grid.p[k] = clip_grid != nullptr ? clip_grid[k < K ? k : K - 1] : 1.0f;
+    int64_t tiles = 0, units = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const windq_refine_item& it = items[i];
+        RefineArgs& A = B.m[i];
+        if (it.W == nullptr) return WINDQ_EINVAL;
+        st = make_geometry(it.W, chunk_w, unit_rows, &A.g);
+        if (st != WINDQ_OK) return st;
+        if (it.s == nullptr || it.action == nullptr || it.code_off == nullptr || it.scale == nullptr ||
+            it.offset == nullptr || it.err == nullptr)
+            return WINDQ_EINVAL;
+        if (it.codes == nullptr && it.codes_bytes != 0) return WINDQ_EINVAL;
+        if (it.codes != nullptr && !aligned(it.codes, 16)) return WINDQ_EINVAL;
+        if (!aligned(it.code_off, 8)) return WINDQ_EINVAL;
+        if (it.W->dtype != items[0].W->dtype) return WINDQ_EINVAL;      // one kernel per launch
+        if (it.ws == nullptr || it.ws_bytes < unit_saliency_ws_bytes(A.g) || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
+        A.W = it.W->data;
+        A.s = it.s;
+        A.mask = it.mask;
+        A.mask_ld = it.W->cols / 8;
+        A.action = it.action;
+        A.clip_idx = clip_grid != nullptr ? it.clip_idx : nullptr;
+        A.code_off = it.code_off;
+        A.codes = it.codes;
+        A.codes_bytes = (int64_t)it.codes_bytes;
+        A.scale = it.scale;
+        A.offset = it.offset;
+        A.part = static_cast<double*>(it.ws);
+        A.err = it.err;
+        B.tile_start[i] = tiles;
+        B.unit_start[i] = units;
+        tiles += A.g.n_tiles;
+        units += A.g.U;
+    }
+    for (int32_t i = n; i <= WINDQ_MAX_BATCH; ++i) {
+        B.tile_start[i] = tiles;
+        B.unit_start[i] = units;
+    }
+    for (int32_t i = n; i < WINDQ_MAX_BATCH; ++i) B.m[i] = B.m[0];
+    if (tiles > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const size_t lds = raw_tile_lds_bytes(W->dtype, chunk_w) + (size_t)chunk_w * sizeof(double) +
-                       (mask != nullptr ? mask_tile_lds_bytes(chunk_w) : 0);
-    const dim3 tiles((unsigned)A.g.n_tiles);
-    if (W->dtype == WINDQ_BF16) {
+    const int32_t dtype = items[0].W->dtype;
+    const size_t lds = raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(double) +
+                       (any_mask ? mask_tile_lds_bytes(chunk_w) : 0);
+    const dim3 grid((unsigned)tiles);
+    if (dtype == WINDQ_BF16) {
         st = ensure_lds(reinterpret_cast<const void*>(&refine_plan_kernel<WINDQ_BF16>), lds);
         if (st != WINDQ_OK) return st;
-        hipLaunchKernelGGL(refine_plan_kernel<WINDQ_BF16>, tiles, dim3(RF_THREADS), lds, hs, A);
+        hipLaunchKernelGGL(refine_plan_kernel<WINDQ_BF16>, grid, dim3(RF_THREADS), lds, hs, B);
     } else {
         st = ensure_lds(reinterpret_cast<const void*>(&refine_plan_kernel<WINDQ_F32>), lds);
         if (st != WINDQ_OK) return st;
-        hipLaunchKernelGGL(refine_plan_kernel<WINDQ_F32>, tiles, dim3(RF_THREADS), lds, hs, A);
+        hipLaunchKernelGGL(refine_plan_kernel<WINDQ_F32>, grid, dim3(RF_THREADS), lds, hs, B);
     }
-    hipLaunchKernelGGL(refine_finalize_kernel, dim3((unsigned)A.g.U), dim3(256), 0, hs, A.part, A.g.tiles_per_unit, err);
+    hipLaunchKernelGGL(refine_finalize_kernel, dim3((unsigned)units), dim3(256), 0, hs, B);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+}
+
+extern "C" int windq_refine_plan(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
+                                 const uint8_t* mask, const uint8_t* action, const uint8_t* clip_idx,
+                                 const float* clip_grid, int32_t K, int32_t n_iter, const int64_t* code_off,
+                                 uint8_t* codes, size_t codes_bytes, float* scale, float* offset, float* err, void* ws,
+                                 size_t ws_bytes, void* stream) {
+    const windq_refine_item it = {W, s, mask, action, clip_idx, code_off, codes, codes_bytes, scale, offset, err, ws, ws_bytes};
+    return refine_launch(&it, 1, chunk_w, unit_rows, clip_grid, K, n_iter, stream);
+}
+
+extern "C" int windq_refine_plan_batch(const windq_refine_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                       const float* clip_grid, int32_t K, int32_t n_iter, void* stream) {
+    return refine_launch(items, n, chunk_w, unit_rows, clip_grid, K, n_iter, stream);
 }

@@ -7,14 +7,18 @@
 //   the bit pattern of the fp32 saliency (digits of 11 + 11 + 9 bits, one pass over W per
 //   digit, LDS histograms flushed by integer atomics); weights above T are protected,
 //   and of those equal to T the first (n_p - #above) in flat-index order inside the unit
-//   (counted per tile, prefix over the unit's tiles, then rank inside the tile row by
-//   row).  The result is a bit mask in the layout of W: one byte per 8 columns.
+//   (only where a unit's ties are split between kept and protected: counted per tile,
+//   prefix over the unit's tiles, then rank inside the tile row by row).  The result is a
+//   bit mask in the layout of W: one byte per 8 columns.
 // windq_salient_encode  stores the protected weights: per unit one symmetric scale
 //   sigma = fp32(max|w_p| / 127), codes clamp(rne(w * fp32(1/sigma)), -127, 127) in
 //   flat-index order, and the activation-weighted error of that INT8 part.
-// Everything is integer or fixed-order fp64: bit-reproducible.  All five passes over W
-// are plain streaming reads; none of this is on the per-step hot path (the mask of a
-// matrix is computed once per protection rate).
+// Everything is integer or fixed-order fp64: bit-reproducible.  Select streams W four times
+// (three digits, the mask) and a fifth time only for the tiles of units whose ties are split;
+// encode reads the mask twice and of W only the protected elements.  Every kernel takes a
+// batch of matrices, so a decoder block costs ten launches for select and four for encode.
+// None of this is on the per-step hot path (the mask of a matrix is computed once per
+// protection rate).
 #include <float.h>
 
 #include "windq_common.hpp"
@@ -48,6 +52,16 @@ struct SalArgs {
     double* err_part;       // [n_tiles]
 };
 
+// A launch covers up to WINDQ_MAX_BATCH matrices (one chunk width, one element type): tiles,
+// units and the workgroups that clear the histograms are numbered one matrix after the other.
+struct SalBatch {
+    int32_t n;
+    int64_t tile_start[WINDQ_MAX_BATCH + 1];
+    int64_t unit_start[WINDQ_MAX_BATCH + 1];
+    int64_t fill_start[WINDQ_MAX_BATCH + 1];     // in workgroups of 256 counters
+    SalArgs m[WINDQ_MAX_BATCH];
+};
+
 __host__ __device__ constexpr int sal_shift(int level) { return level == 0 ? 20 : (level == 1 ? 9 : 0); }
 __host__ __device__ constexpr int sal_bits(int level) { return level == 2 ? 9 : 11; }
 
@@ -71,9 +85,19 @@ __device__ __forceinline__ void load8g(const void* __restrict__ data, int64_t of
     }
 }
 
-__global__ __launch_bounds__(256) void sal_fill_u32_kernel(uint32_t* __restrict__ p, int64_t n, uint32_t v) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
+// One element of W.
+template <int DT>
+__device__ __forceinline__ float load1g(const void* __restrict__ data, int64_t off) {
+    if (DT == WINDQ_BF16) return bf16_bits_to_f32(static_cast<const uint16_t*>(data)[off]);
+    return static_cast<const float*>(data)[off];
+}
+
+// Zeroes the digit histograms of every matrix of the launch.
+__global__ __launch_bounds__(256) void sal_clear_hist_kernel(const SalBatch B) {
+    const int mi = batch_index(B.fill_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const int64_t i = ((int64_t)blockIdx.x - B.fill_start[mi]) * 256 + threadIdx.x;
+    if (i < (int64_t)3 * A.g.U * FEAT_BINS) A.hist[i] = 0u;
 }
 
 // Clears the mask of a matrix (rows x mask_ld bytes, dense).
@@ -96,10 +120,12 @@ __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* sh) {
 
 // Histogram of digit `level` of the keys of one tile that carry the unit's prefix.
 template <int DT>
-__global__ __launch_bounds__(SAL_THREADS) void sal_hist_kernel(const SalArgs A, const int level) {
+__global__ __launch_bounds__(SAL_THREADS) void sal_hist_kernel(const SalBatch B, const int level) {
     __shared__ uint32_t lhist[FEAT_BINS];
     __shared__ float scol[WINDQ_MAX_CHUNK];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
     const int32_t nbins = 1 << sal_bits(level);
     for (int32_t b = threadIdx.x; b < nbins; b += SAL_THREADS) lhist[b] = 0;
@@ -128,11 +154,16 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_hist_kernel(const SalArgs A, 
     }
 }
 
-// Per unit: the bin of digit `level` that holds the wanted rank; extends the prefix.
-__global__ __launch_bounds__(SAL_THREADS) void sal_prefix_kernel(const SalArgs A, const int level) {
+// Per unit: the bin of digit `level` that holds the wanted rank; extends the prefix.  After the
+// last digit the prefix is the threshold T, every key of the bin equals T, and the rank left
+// over, r, says that the wanted key is the r-th of those e ties in ascending order: r - 1 of
+// them count among the kept weights and need = e - r + 1 among the protected ones.
+__global__ __launch_bounds__(SAL_THREADS) void sal_prefix_kernel(const SalBatch B, const int level) {
     __shared__ uint32_t sh_part[SAL_THREADS];
     __shared__ uint32_t sh_out[4];
-    const int64_t u = blockIdx.x;
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
     const uint32_t rank = level == 0 ? A.rank0 : A.rank[u];
     const uint32_t prefix = level == 0 ? 0u : A.prefix[u];
     const uint32_t* h = A.hist + ((size_t)level * (size_t)A.g.U + (size_t)u) * FEAT_BINS;
@@ -140,42 +171,42 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_prefix_kernel(const SalArgs A
     uint64_t below;
     select_bin<SAL_THREADS>(h, 1 << sal_bits(level), rank, sh_part, sh_out, &bin, &below);
     if (threadIdx.x == 0) {
+        const uint32_t left = rank - (uint32_t)below;
         A.prefix[u] = (prefix << sal_bits(level)) | bin;
-        A.rank[u] = rank - (uint32_t)below;
+        A.rank[u] = left;
+        if (level == 2) A.need[u] = h[bin] - left + 1u;
     }
 }
 
-// Per tile: how many keys lie above the unit's threshold, how many equal it.
+// Which of a unit's ties are protected depends on their order only when some of them are not
+// (rank left over above 1); otherwise all are, and nothing has to be counted.
+__device__ __forceinline__ bool ties_split(const SalArgs& A, int64_t u) { return A.rank[u] > 1u; }
+
+// Per tile of a unit whose ties are split: how many keys equal the threshold.
 template <int DT>
-__global__ __launch_bounds__(SAL_THREADS) void sal_count_kernel(const SalArgs A) {
+__global__ __launch_bounds__(SAL_THREADS) void sal_count_kernel(const SalBatch B) {
     __shared__ float scol[WINDQ_MAX_CHUNK];
     __shared__ uint32_t sh[SAL_THREADS / 64];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
+    if (!ties_split(A, tc.u)) return;
     const int32_t G = A.g.chunk_w;
     for (int32_t c = threadIdx.x; c < G; c += SAL_THREADS) scol[c] = A.s[tc.col0 + c];
     const uint32_t T = A.prefix[tc.u];
     __syncthreads();
     const int32_t pieces = G >> 3;
     const int32_t total = tc.nrows * pieces;
-    uint32_t gt = 0, eq = 0;
+    uint32_t eq = 0;
     for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS) {
         const int32_t r = i / pieces, pc = i - r * pieces;
         float w[8];
         load8g<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + pc * 8, w);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t key = sal_key(w[j], scol[pc * 8 + j]);
-            gt += key > T ? 1u : 0u;
-            eq += key == T ? 1u : 0u;
-        }
+        for (int j = 0; j < 8; ++j) eq += sal_key(w[j], scol[pc * 8 + j]) == T ? 1u : 0u;
     }
-    gt = block_sum_u32(gt, sh);
     eq = block_sum_u32(eq, sh);
-    if (threadIdx.x == 0) {
-        const size_t idx = (size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t;
-        A.cnt[idx * 2] = gt;
-        A.cnt[idx * 2 + 1] = eq;
-    }
+    if (threadIdx.x == 0) A.cnt[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] = eq;
 }
 
 // Exclusive prefix sum over a workgroup, in thread order (all SAL_THREADS threads call it);
@@ -200,32 +231,34 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_u32(uint32_t v, uint32_
     return excl;
 }
 
-// Per unit: ties in earlier tiles (tile order = row order), and how many ties to protect.
-__global__ __launch_bounds__(SAL_THREADS) void sal_scan_kernel(const SalArgs A) {
+// Per unit: ties in earlier tiles (tile order = row order); zeros where the ties are not split.
+__global__ __launch_bounds__(SAL_THREADS) void sal_scan_kernel(const SalBatch B) {
     __shared__ uint32_t sh[SAL_THREADS / 64];
-    const int64_t u = blockIdx.x;
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
     const int64_t T = A.g.tiles_per_unit;
     const size_t base = (size_t)u * (size_t)T;
-    uint32_t carry = 0, gt_total = 0;
+    const bool split = ties_split(A, u);
+    uint32_t carry = 0;
     for (int64_t t0 = 0; t0 < T; t0 += SAL_THREADS) {
         const int64_t t = t0 + threadIdx.x;
-        const uint32_t eq = t < T ? A.cnt[(base + t) * 2 + 1] : 0u;
-        const uint32_t gt = t < T ? A.cnt[(base + t) * 2] : 0u;
+        const uint32_t eq = split && t < T ? A.cnt[base + t] : 0u;
         uint32_t tot;
         const uint32_t excl = block_exclusive_scan_u32(eq, sh, &tot);
         if (t < T) A.eq_before[base + t] = carry + excl;
         carry += tot;
-        gt_total += block_sum_u32(gt, sh);
     }
-    if (threadIdx.x == 0) A.need[u] = A.n_p > gt_total ? A.n_p - gt_total : 0u;
 }
 
 // Per tile, one lane per row: the protection bits of the row.  A tie is protected when its
 // rank among the unit's ties, in flat-index order, is below `need`.
 template <int DT>
-__global__ __launch_bounds__(64) void sal_mask_kernel(const SalArgs A) {
+__global__ __launch_bounds__(64) void sal_mask_kernel(const SalBatch B) {
     extern __shared__ char smem[];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
     constexpr int EB = Elem<DT>::bytes;
     const int32_t row_bytes = G * EB + 16;
@@ -276,35 +309,35 @@ __global__ __launch_bounds__(64) void sal_mask_kernel(const SalArgs A) {
 }
 
 // ---------------------------------------------------------------------------- encode
+// The encode kernels stage only the tile's mask bytes (a sixteenth of the weights' bytes at
+// bf16) and fetch the few protected weights straight from HBM, one element at a time.
+// LDS: [mask tile][s_c of the chunk].
+
 // Per tile, one lane per row: protected weights in the row, largest protected magnitude.
 template <int DT>
-__global__ __launch_bounds__(64) void sal_rows_kernel(const SalArgs A) {
+__global__ __launch_bounds__(64) void sal_rows_kernel(const SalBatch B) {
     extern __shared__ char smem[];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
-    constexpr int EB = Elem<DT>::bytes;
-    const int32_t row_bytes = G * EB + 16;
     const int lane = threadIdx.x;
-    uint8_t* mtile = reinterpret_cast<uint8_t*>(smem + TILE_ROWS * row_bytes + G * sizeof(float));
-    load_tile_raw<DT>(A.W, A.g.ld, tc, G, smem);
+    uint8_t* mtile = reinterpret_cast<uint8_t*>(smem);
     load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     __syncthreads();
     const bool valid = lane < tc.nrows;
     uint32_t n = 0;
     float mx = 0.0f;
     if (valid) {
-        const char* wrow = smem + lane * row_bytes;
+        const int64_t woff = (tc.row0 + lane) * A.g.ld + tc.col0;
         const uint8_t* mrow = mtile + lane * mask_row_stride(G);
         for (int32_t c = 0; c < G; c += 8) {
-            const uint32_t m = mrow[c >> 3];
-            float w[8];
-            read8<DT>(wrow, c, w);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if ((m >> j) & 1u) {
-                    ++n;
-                    mx = fmaxf(mx, fabsf(w[j]));
-                }
+            uint32_t m = mrow[c >> 3];
+            n += __popc(m);
+            while (m != 0) {
+                const int j = __ffs(m) - 1;
+                m &= m - 1;
+                mx = fmaxf(mx, fabsf(load1g<DT>(A.W, woff + c + j)));
             }
         }
         A.row_off[tc.u * A.g.R_u + tc.lrow0 + lane] = n;
@@ -315,10 +348,12 @@ __global__ __launch_bounds__(64) void sal_rows_kernel(const SalArgs A) {
 }
 
 // Per unit: the INT8 scale, and the row counts turned into offsets (exclusive prefix in row order).
-__global__ __launch_bounds__(SAL_THREADS) void sal_unit_kernel(const SalArgs A) {
+__global__ __launch_bounds__(SAL_THREADS) void sal_unit_kernel(const SalBatch B) {
     __shared__ uint32_t sh[SAL_THREADS / 64];
     __shared__ float shm[SAL_THREADS / 64];
-    const int64_t u = blockIdx.x;
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
     float mx = 0.0f;
     for (int64_t t = threadIdx.x; t < A.g.tiles_per_unit; t += SAL_THREADS)
         mx = fmaxf(mx, A.tile_max[(size_t)u * (size_t)A.g.tiles_per_unit + (size_t)t]);
@@ -353,16 +388,15 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_unit_kernel(const SalArgs A) 
 // Per tile, one lane per row: INT8 codes of the row's protected weights at their place in
 // the unit's stream, and the activation-weighted error of the tile's INT8 part.
 template <int DT>
-__global__ __launch_bounds__(64) void sal_encode_kernel(const SalArgs A) {
+__global__ __launch_bounds__(64) void sal_encode_kernel(const SalBatch B) {
     extern __shared__ char smem[];
-    const TileCoord tc = tile_coord(A.g, blockIdx.x);
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
-    constexpr int EB = Elem<DT>::bytes;
-    const int32_t row_bytes = G * EB + 16;
-    float* scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
     const int lane = threadIdx.x;
-    uint8_t* mtile = reinterpret_cast<uint8_t*>(scol + G);
-    load_tile_raw<DT>(A.W, A.g.ld, tc, G, smem);
+    uint8_t* mtile = reinterpret_cast<uint8_t*>(smem);
+    float* scol = reinterpret_cast<float*>(smem + TILE_ROWS * mask_row_stride(G));
     load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     for (int32_t c = lane; c < G; c += 64) scol[c] = A.s[tc.col0 + c];
     __syncthreads();
@@ -370,26 +404,23 @@ __global__ __launch_bounds__(64) void sal_encode_kernel(const SalArgs A) {
     const float inv = sg > 0.0f ? 1.0f / sg : 0.0f;
     double err = 0.0;
     if (lane < tc.nrows) {
-        const char* wrow = smem + lane * row_bytes;
+        const int64_t woff = (tc.row0 + lane) * A.g.ld + tc.col0;
         const uint8_t* mrow = mtile + lane * mask_row_stride(G);
         uint32_t pos = A.row_off[tc.u * A.g.R_u + tc.lrow0 + lane];
         int8_t* __restrict__ dst = A.prot_codes + (size_t)tc.u * (size_t)A.n_p;
         for (int32_t c = 0; c < G; c += 8) {
-            const uint32_t m = mrow[c >> 3];
-            if (m == 0) continue;
-            float w[8];
-            read8<DT>(wrow, c, w);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if ((m >> j) & 1u) {
-                    const float t = w[j] * inv;
-                    const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -127.0f, 127.0f);
-                    if (pos < A.n_p) dst[pos] = (int8_t)(int32_t)q;     // a mask with more bits than n_p writes nothing past the unit
-                    ++pos;
-                    const double d = (double)w[j] - (double)q * (double)sg;
-                    const double a = (double)scol[c + j] * (double)scol[c + j];
-                    err = fma(a * d, d, err);
-                }
+            uint32_t m = mrow[c >> 3];
+            while (m != 0) {
+                const int j = __ffs(m) - 1;
+                m &= m - 1;
+                const float w = load1g<DT>(A.W, woff + c + j);
+                const float t = w * inv;
+                const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -127.0f, 127.0f);
+                if (pos < A.n_p) dst[pos] = (int8_t)(int32_t)q;     // a mask with more bits than n_p writes nothing past the unit
+                ++pos;
+                const double d = (double)w - (double)q * (double)sg;
+                const double a = (double)scol[c + j] * (double)scol[c + j];
+                err = fma(a * d, d, err);
             }
         }
     }
@@ -397,9 +428,11 @@ __global__ __launch_bounds__(64) void sal_encode_kernel(const SalArgs A) {
     if (lane == 0) A.err_part[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] = err;
 }
 
-__global__ __launch_bounds__(256) void sal_err_kernel(const SalArgs A) {
+__global__ __launch_bounds__(256) void sal_err_kernel(const SalBatch B) {
     __shared__ double red[4];
-    const int64_t u = blockIdx.x;
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
     const double e = unit_partial_sum<256>(A.err_part + (size_t)u * (size_t)A.g.tiles_per_unit, A.g.tiles_per_unit, red);
     if (threadIdx.x == 0) A.err_prot[u] = (float)e;
 }
@@ -444,10 +477,12 @@ __global__ __launch_bounds__(256) void unit_saliency_finalize_kernel(const doubl
     if (threadIdx.x == 0) sal[u] = (float)(t / ((double)g.R_u * (double)g.chunk_w));
 }
 
-// raw tile, s_c of the chunk, the tile's mask bytes
+// select's mask kernel: raw tile, s_c of the chunk
 static size_t sal_tile_lds(int32_t dtype, int32_t chunk_w) {
-    return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) + mask_tile_lds_bytes(chunk_w);
+    return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
 }
+// encode's kernels: the tile's mask bytes, s_c of the chunk
+static size_t sal_gather_lds(int32_t chunk_w) { return mask_tile_lds_bytes(chunk_w) + (size_t)chunk_w * sizeof(float); }
 
 static void carve(SalArgs& A, void* ws, const SalientLayout& L) {
     char* base = static_cast<char*>(ws);
@@ -463,33 +498,32 @@ static void carve(SalArgs& A, void* ws, const SalientLayout& L) {
 }
 
 template <int DT>
-static int launch_select(const SalArgs& A, hipStream_t hs, size_t lds) {
-    const dim3 tiles((unsigned)A.g.n_tiles), units((unsigned)A.g.U);
-    const int64_t n_hist = (int64_t)3 * A.g.U * FEAT_BINS;
-    hipLaunchKernelGGL(sal_fill_u32_kernel, dim3((unsigned)((n_hist + 255) / 256)), dim3(256), 0, hs, A.hist, n_hist, 0u);
+static int launch_select(const SalBatch& B, hipStream_t hs, size_t lds) {
+    const dim3 tiles((unsigned)B.tile_start[B.n]), units((unsigned)B.unit_start[B.n]);
+    hipLaunchKernelGGL(sal_clear_hist_kernel, dim3((unsigned)B.fill_start[B.n]), dim3(256), 0, hs, B);
     for (int level = 0; level < 3; ++level) {
-        hipLaunchKernelGGL(sal_hist_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, A, level);
-        hipLaunchKernelGGL(sal_prefix_kernel, units, dim3(SAL_THREADS), 0, hs, A, level);
+        hipLaunchKernelGGL(sal_hist_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B, level);
+        hipLaunchKernelGGL(sal_prefix_kernel, units, dim3(SAL_THREADS), 0, hs, B, level);
     }
-    hipLaunchKernelGGL(sal_count_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, A);
-    hipLaunchKernelGGL(sal_scan_kernel, units, dim3(SAL_THREADS), 0, hs, A);
+    hipLaunchKernelGGL(sal_count_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B);
+    hipLaunchKernelGGL(sal_scan_kernel, units, dim3(SAL_THREADS), 0, hs, B);
     int st = ensure_lds(reinterpret_cast<const void*>(&sal_mask_kernel<DT>), lds);
     if (st != WINDQ_OK) return st;
-    hipLaunchKernelGGL(sal_mask_kernel<DT>, tiles, dim3(64), lds, hs, A);
+    hipLaunchKernelGGL(sal_mask_kernel<DT>, tiles, dim3(64), lds, hs, B);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
 template <int DT>
-static int launch_encode(const SalArgs& A, hipStream_t hs, size_t lds) {
-    const dim3 tiles((unsigned)A.g.n_tiles), units((unsigned)A.g.U);
+static int launch_encode(const SalBatch& B, hipStream_t hs, size_t lds) {
+    const dim3 tiles((unsigned)B.tile_start[B.n]), units((unsigned)B.unit_start[B.n]);
     int st = ensure_lds(reinterpret_cast<const void*>(&sal_rows_kernel<DT>), lds);
     if (st != WINDQ_OK) return st;
     st = ensure_lds(reinterpret_cast<const void*>(&sal_encode_kernel<DT>), lds);
     if (st != WINDQ_OK) return st;
-    hipLaunchKernelGGL(sal_rows_kernel<DT>, tiles, dim3(64), lds, hs, A);
-    hipLaunchKernelGGL(sal_unit_kernel, units, dim3(SAL_THREADS), 0, hs, A);
-    hipLaunchKernelGGL(sal_encode_kernel<DT>, tiles, dim3(64), lds, hs, A);
-    hipLaunchKernelGGL(sal_err_kernel, units, dim3(256), 0, hs, A);
+    hipLaunchKernelGGL(sal_rows_kernel<DT>, tiles, dim3(64), lds, hs, B);
+    hipLaunchKernelGGL(sal_unit_kernel, units, dim3(SAL_THREADS), 0, hs, B);
+    hipLaunchKernelGGL(sal_encode_kernel<DT>, tiles, dim3(64), lds, hs, B);
+    hipLaunchKernelGGL(sal_err_kernel, units, dim3(256), 0, hs, B);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
@@ -504,13 +538,14 @@ extern "C" int64_t windq_n_protected(int64_t n_unit, uint32_t rate_ppm) {
 }
 
 static int salient_common(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, uint32_t rate_ppm,
-                          const uint8_t* mask, void* ws, size_t ws_bytes, SalArgs* A, SalientLayout* L) {
+                          const uint8_t* mask, void* ws, size_t ws_bytes, SalArgs* A) {
+    if (W == nullptr) return WINDQ_EINVAL;
     const int st = make_geometry(W, chunk_w, unit_rows, &A->g);
     if (st != WINDQ_OK) return st;
     if (s == nullptr || mask == nullptr || rate_ppm > 1000000u) return WINDQ_EINVAL;
     if ((uint64_t)A->g.R_u * (uint64_t)chunk_w > (uint64_t)0xffffffffu) return WINDQ_ESHAPE;   // u32 counts
-    *L = salient_layout(A->g);
-    if (ws == nullptr || ws_bytes < L->total || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
+    const SalientLayout L = salient_layout(A->g);
+    if (ws == nullptr || ws_bytes < L.total || !aligned(ws, 256)) return WINDQ_EWORKSPACE;
     A->W = W->data;
     A->s = s;
     A->mask = const_cast<uint8_t*>(mask);
@@ -521,41 +556,109 @@ static int salient_common(const windq_mat* W, const float* s, int32_t chunk_w, i
     A->prot_codes = nullptr;
     A->prot_scale = nullptr;
     A->err_prot = nullptr;
-    carve(*A, ws, *L);
+    carve(*A, ws, L);
     return WINDQ_OK;
+}
+
+// Numbers the tiles, units and histogram-clearing workgroups of the first B->n matrices.
+static int salient_number(SalBatch* B) {
+    int64_t tiles = 0, units = 0, fill = 0;
+    for (int32_t i = 0; i < B->n; ++i) {
+        B->tile_start[i] = tiles;
+        B->unit_start[i] = units;
+        B->fill_start[i] = fill;
+        tiles += B->m[i].g.n_tiles;
+        units += B->m[i].g.U;
+        fill += ((int64_t)3 * B->m[i].g.U * FEAT_BINS + 255) / 256;
+    }
+    for (int32_t i = B->n; i <= WINDQ_MAX_BATCH; ++i) {
+        B->tile_start[i] = tiles;
+        B->unit_start[i] = units;
+        B->fill_start[i] = fill;
+    }
+    for (int32_t i = B->n; i < WINDQ_MAX_BATCH; ++i) B->m[i] = B->m[0];
+    return tiles > (int64_t)0x7fffffff || fill > (int64_t)0x7fffffff ? WINDQ_ESHAPE : WINDQ_OK;
+}
+
+static int salient_select_launch(const windq_salient_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                 uint32_t rate_ppm, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    SalBatch B;
+    B.n = 0;
+    const uint8_t* empty[WINDQ_MAX_BATCH];      // masks of matrices whose units protect nothing
+    int64_t empty_bytes[WINDQ_MAX_BATCH];
+    int32_t n_empty = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        SalArgs& A = B.m[B.n];
+        const int st = salient_common(items[i].W, items[i].s, chunk_w, unit_rows, rate_ppm, items[i].mask, items[i].ws,
+                                      items[i].ws_bytes, &A);
+        if (st != WINDQ_OK) return st;
+        if (items[i].W->dtype != items[0].W->dtype) return WINDQ_EINVAL;      // one kernel per launch
+        if (A.n_p == 0) {
+            empty[n_empty] = items[i].mask;
+            empty_bytes[n_empty++] = items[i].W->rows * A.mask_ld;
+        } else {
+            ++B.n;
+        }
+    }
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    for (int32_t i = 0; i < n_empty; ++i)
+        hipLaunchKernelGGL(sal_clear_mask_kernel, dim3((unsigned)((empty_bytes[i] + 255) / 256)), dim3(256), 0, hs,
+                           const_cast<uint8_t*>(empty[i]), empty_bytes[i]);
+    if (B.n == 0) return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
+    const int st = salient_number(&B);
+    if (st != WINDQ_OK) return st;
+    const int32_t dtype = items[0].W->dtype;
+    const size_t lds = sal_tile_lds(dtype, chunk_w);
+    return dtype == WINDQ_BF16 ? launch_select<WINDQ_BF16>(B, hs, lds) : launch_select<WINDQ_F32>(B, hs, lds);
+}
+
+static int salient_encode_launch(const windq_salient_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                 uint32_t rate_ppm, void* stream) {
+    if (items == nullptr || n < 1 || n > WINDQ_MAX_BATCH) return WINDQ_EINVAL;
+    SalBatch B;
+    B.n = n;
+    for (int32_t i = 0; i < n; ++i) {
+        SalArgs& A = B.m[i];
+        const int st = salient_common(items[i].W, items[i].s, chunk_w, unit_rows, rate_ppm, items[i].mask, items[i].ws,
+                                      items[i].ws_bytes, &A);
+        if (st != WINDQ_OK) return st;
+        if (items[i].W->dtype != items[0].W->dtype) return WINDQ_EINVAL;
+        if (items[i].prot_scale == nullptr || items[i].err_prot == nullptr) return WINDQ_EINVAL;
+        if (items[i].prot_codes == nullptr && A.n_p != 0) return WINDQ_EINVAL;
+        A.prot_codes = items[i].prot_codes;
+        A.prot_scale = items[i].prot_scale;
+        A.err_prot = items[i].err_prot;
+    }
+    const int st = salient_number(&B);
+    if (st != WINDQ_OK) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int32_t dtype = items[0].W->dtype;
+    const size_t lds = sal_gather_lds(chunk_w);
+    return dtype == WINDQ_BF16 ? launch_encode<WINDQ_BF16>(B, hs, lds) : launch_encode<WINDQ_F32>(B, hs, lds);
 }
 
 extern "C" int windq_salient_select(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
                                     uint32_t rate_ppm, uint8_t* mask, void* ws, size_t ws_bytes, void* stream) {
-    SalArgs A;
-    SalientLayout L;
-    const int st = salient_common(W, s, chunk_w, unit_rows, rate_ppm, mask, ws, ws_bytes, &A, &L);
-    if (st != WINDQ_OK) return st;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (A.n_p == 0) {
-        const int64_t n = W->rows * A.mask_ld;
-        hipLaunchKernelGGL(sal_clear_mask_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, hs, mask, n);
-        return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
-    }
-    const size_t lds = sal_tile_lds(W->dtype, chunk_w);
-    return W->dtype == WINDQ_BF16 ? launch_select<WINDQ_BF16>(A, hs, lds) : launch_select<WINDQ_F32>(A, hs, lds);
+    const windq_salient_item it = {W, s, mask, nullptr, nullptr, nullptr, ws, ws_bytes};
+    return salient_select_launch(&it, 1, chunk_w, unit_rows, rate_ppm, stream);
+}
+
+extern "C" int windq_salient_select_batch(const windq_salient_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                          uint32_t rate_ppm, void* stream) {
+    return salient_select_launch(items, n, chunk_w, unit_rows, rate_ppm, stream);
 }
 
 extern "C" int windq_salient_encode(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows,
                                     const uint8_t* mask, uint32_t rate_ppm, int8_t* prot_codes, float* prot_scale,
                                     float* err_prot, void* ws, size_t ws_bytes, void* stream) {
-    SalArgs A;
-    SalientLayout L;
-    const int st = salient_common(W, s, chunk_w, unit_rows, rate_ppm, mask, ws, ws_bytes, &A, &L);
-    if (st != WINDQ_OK) return st;
-    if (prot_scale == nullptr || err_prot == nullptr) return WINDQ_EINVAL;
-    if (prot_codes == nullptr && A.n_p != 0) return WINDQ_EINVAL;
-    A.prot_codes = prot_codes;
-    A.prot_scale = prot_scale;
-    A.err_prot = err_prot;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    const size_t lds = sal_tile_lds(W->dtype, chunk_w);
-    return W->dtype == WINDQ_BF16 ? launch_encode<WINDQ_BF16>(A, hs, lds) : launch_encode<WINDQ_F32>(A, hs, lds);
+    const windq_salient_item it = {W, s, const_cast<uint8_t*>(mask), prot_codes, prot_scale, err_prot, ws, ws_bytes};
+    return salient_encode_launch(&it, 1, chunk_w, unit_rows, rate_ppm, stream);
+}
+
+extern "C" int windq_salient_encode_batch(const windq_salient_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
+                                          uint32_t rate_ppm, void* stream) {
+    return salient_encode_launch(items, n, chunk_w, unit_rows, rate_ppm, stream);
 }
 
 extern "C" int windq_unit_saliency(const windq_mat* W, const float* s, int32_t chunk_w, int64_t unit_rows, float* sal,

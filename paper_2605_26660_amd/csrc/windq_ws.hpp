@@ -70,7 +70,7 @@ inline size_t features_ws_bytes(const Geometry& g, int32_t /*dtype*/) { return f
 // ---- salient-weight protection (select and encode share one layout)
 //   hist      [3][U][FEAT_BINS] u32   histograms of the three saliency-key digits
 //   prefix, rank, need  [U] u32       selection state per unit
-//   cnt       [n_tiles][2] u32        keys above / equal to the threshold per tile
+//   cnt       [n_tiles] u32           keys equal to the threshold per tile (units with split ties)
 //   eq_before [n_tiles] u32           ties in earlier tiles of the unit
 //   tile_max  [n_tiles] f32           largest protected magnitude per tile
 //   row_off   [U * R_u] u32           protected weights in earlier rows of the unit
@@ -85,7 +85,7 @@ inline SalientLayout salient_layout(const Geometry& g) {
     L.prefix = pos;    pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
     L.rank = pos;      pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
     L.need = pos;      pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
-    L.cnt = pos;       pos = round_up(pos + (size_t)g.n_tiles * 2 * sizeof(uint32_t), 256);
+    L.cnt = pos;       pos = round_up(pos + (size_t)g.n_tiles * sizeof(uint32_t), 256);
     L.eq_before = pos; pos = round_up(pos + (size_t)g.n_tiles * sizeof(uint32_t), 256);
     L.tile_max = pos;  pos = round_up(pos + (size_t)g.n_tiles * sizeof(float), 256);
     L.row_off = pos;   pos = round_up(pos + (size_t)g.U * (size_t)g.R_u * sizeof(uint32_t), 256);

@@ -327,3 +327,120 @@ def test_kernel_timer_brackets_the_main_fit_score_kernel(windq):
     assert windq.windq_kernel_timer_read() == (0.0, 0)
     for x, y in zip(a, b):
         assert all(same_bits(p, q) for p, q in zip(x, y))
+
+
+# ------------------------------------------- protection, refinement, the way back: batch forms
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("G,unit_rows,ppm,shapes,flat_scale", [
+    (128, 0, 30000, [(256, 512), (1024, 256), (64, 128), (200, 384), (2048, 128), (192, 640), (512, 512)], False),
+    (128, 0, 30000, [(320, 256), (192, 128), (64, 384)], True),      # constant scale: most thresholds are shared
+    (64, 64, 20000, [(128, 256), (64, 64), (320, 192)], False),
+    (128, 0, 500, [(8, 128), (2048, 128), (16, 256)], False),         # the small matrices protect nothing
+    (8, 4, 250000, [(16, 24), (8, 8)], False),
+])
+def test_salient_batches_equal_single_calls(windq, dtype, G, unit_rows, ppm, shapes, flat_scale):
+    Ws, ss = block(dtype, shapes, 311)
+    if flat_scale:
+        ss = [torch.ones_like(s) for s in ss]
+    singles = [windq.windq_salient_select(W, s, G, unit_rows, ppm) for W, s in zip(Ws, ss)]
+    outs = [torch.full((W.shape[0], W.shape[1] // 8), 0xAB, dtype=torch.uint8, device=DEV) for W in Ws]
+    masks = windq.windq_salient_select_batch(Ws, ss, G, unit_rows, ppm, outs=outs)
+    torch.cuda.synchronize()
+    for one, got in zip(singles, masks):
+        assert same_bits(one, got)
+    enc1 = [windq.windq_salient_encode(W, s, G, unit_rows, m, ppm) for W, s, m in zip(Ws, ss, singles)]
+    encb = windq.windq_salient_encode_batch(Ws, ss, G, unit_rows, masks, ppm)
+    torch.cuda.synchronize()
+    for one, got in zip(enc1, encb):
+        assert all(same_bits(a, b) for a, b in zip(one, got))
+
+
+def test_salient_batches_check_their_arguments(windq):
+    Ws, ss = block(torch.bfloat16, [(64, 128)] * 9, 7)
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_salient_select_batch(Ws, ss, 128, 0, 30000)                    # more than MAX_BATCH
+    assert e.value.status == windq.WINDQ_EINVAL
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_salient_select_batch([Ws[0], Ws[1].float()], ss[:2], 128, 0, 30000)
+    assert e.value.status == windq.WINDQ_EINVAL
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_salient_select_batch(Ws[:2], ss[:2], 128, 0, 1000001)
+    assert e.value.status == windq.WINDQ_EINVAL
+    small = [torch.empty(256, dtype=torch.uint8, device=DEV)] * 2
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_salient_select_batch(Ws[:2], ss[:2], 128, 0, 30000, wss=small)
+    assert e.value.status == windq.WINDQ_EWORKSPACE
+    masks = windq.windq_salient_select_batch(Ws[:2], ss[:2], 128, 0, 30000)
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_salient_encode_batch(Ws[:2], ss[:2], 96, 0, masks, 30000)
+    assert e.value.status == windq.WINDQ_ESHAPE
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("G,unit_rows,K,n_iter,shapes,masked", [
+    (128, 0, 7, 3, [(256, 512), (1024, 256), (64, 128), (200, 384), (2048, 128), (192, 640), (512, 512)], False),
+    (128, 0, 7, 2, [(256, 512), (200, 384), (64, 128)], True),
+    (64, 64, 5, 4, [(128, 256), (64, 64), (320, 192)], True),
+    (24, 0, 3, 1, [(16, 48), (70, 24)], False),                       # a width the lanes-per-row kernels do not take
+])
+def test_refine_and_dequant_batches_equal_single_calls(windq, dtype, G, unit_rows, K, n_iter, shapes, masked):
+    Ws, ss = block(dtype, shapes, 401)
+    cg = synth.clip_grid(K)
+    ppm = 30000
+    masks = [windq.windq_salient_select(W, s, G, unit_rows, ppm) if masked and i != 1 else None
+             for i, (W, s) in enumerate(zip(Ws, ss))]                # masks item by item
+    acts, offs, cis = [], [], []
+    for i, (W, s) in enumerate(zip(Ws, ss)):
+        U, R_u = windq.n_units(W.shape[0], W.shape[1], G, unit_rows)
+        gen = torch.Generator().manual_seed(600 + i)
+        a = torch.randint(0, 7, (U,), generator=gen, dtype=torch.uint8)
+        offs.append(windq.windq_plan_layout(a, R_u, G).to(DEV))
+        acts.append(a.to(DEV))
+        cis.append(torch.randint(0, K, (U, 4), generator=gen, dtype=torch.uint8).to(DEV) if i != 2 else None)
+    ones = [windq.windq_refine_plan(W, s, G, unit_rows, a, ci, cg, off, n_iter, mask=m)
+            for W, s, a, ci, off, m in zip(Ws, ss, acts, cis, offs, masks)]
+    codes_b = [torch.full((max(int(off[-1]), 16),), 0xAB, dtype=torch.uint8, device=DEV) for off in offs]
+    got = windq.windq_refine_plan_batch(Ws, ss, G, unit_rows, acts, cis, cg, offs, n_iter, codes_b, masks=masks)
+    torch.cuda.synchronize()
+    for one, b, off in zip(ones, got, offs):
+        total = int(off[-1])
+        assert same_bits(one[0][:total], b[0][:total])
+        assert all(same_bits(x, y) for x, y in zip(one[1:], b[1:]))
+    deq1 = [windq.windq_dequant_plan(W, s, G, unit_rows, a, off, r[0], r[1], r[2], mask=m)
+            for W, s, a, off, r, m in zip(Ws, ss, acts, offs, ones, masks)]
+    deqb = windq.windq_dequant_plan_batch(Ws, ss, G, unit_rows, acts, offs, [r[0] for r in got], [r[1] for r in got],
+                                          [r[2] for r in got], masks=masks)
+    torch.cuda.synchronize()
+    for one, b in zip(deq1, deqb):
+        assert same_bits(one[0], b[0]) and same_bits(one[1], b[1])
+    # errors only, and the reconstruction only
+    errs = windq.windq_dequant_plan_batch(Ws, ss, G, unit_rows, acts, offs, [r[0] for r in got], [r[1] for r in got],
+                                          [r[2] for r in got], masks=masks, want_w_hat=False)
+    torch.cuda.synchronize()
+    assert all(same_bits(one[0], b[0]) and b[1] is None for one, b in zip(deq1, errs))
+
+
+def test_refine_and_dequant_batches_check_their_arguments(windq):
+    Ws, ss = block(torch.bfloat16, [(64, 128)] * 9, 9)
+    cg = synth.clip_grid(4)
+    acts = [torch.full((1,), 2, dtype=torch.uint8, device=DEV) for _ in Ws]
+    offs = [windq.windq_plan_layout(torch.full((1,), 2, dtype=torch.uint8), 64, 128).to(DEV) for _ in Ws]
+    codes = [torch.zeros(int(off[-1]), dtype=torch.uint8, device=DEV) for off in offs]
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_refine_plan_batch(Ws, ss, 128, 0, acts, [None] * 9, cg, offs, 1, codes)
+    assert e.value.status == windq.WINDQ_EINVAL
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_refine_plan_batch(Ws[:2], ss[:2], 128, 0, acts[:2], [None] * 2, cg, offs[:2], 65, codes[:2])
+    assert e.value.status == windq.WINDQ_EINVAL
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_refine_plan_batch([Ws[0], Ws[1].float()], ss[:2], 128, 0, acts[:2], [None] * 2, cg, offs[:2], 1, codes[:2])
+    assert e.value.status == windq.WINDQ_EINVAL
+    sc = [torch.zeros(64, device=DEV) for _ in Ws]
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_dequant_plan_batch(Ws, ss, 128, 0, acts, offs, codes, sc, sc)
+    assert e.value.status == windq.WINDQ_EINVAL
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_dequant_plan_batch(Ws[:2], ss[:2], 96, 0, acts[:2], offs[:2], codes[:2], sc[:2], sc[:2])
+    assert e.value.status == windq.WINDQ_ESHAPE
+    torch.cuda.synchronize()

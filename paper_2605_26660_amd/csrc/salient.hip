@@ -251,60 +251,63 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_scan_kernel(const SalBatch B)
     }
 }
 
-// Per tile, one lane per row: the protection bits of the row.  A tie is protected when its
-// rank among the unit's ties, in flat-index order, is below `need`.
+// Per tile: the protection bits.  A thread takes eight consecutive columns of a row, i.e. one
+// byte of the mask, straight from HBM; threads walk the tile in flat-index order.  Where the
+// unit's ties are split, a tie is protected when its rank among the unit's ties, in flat-index
+// order, is below `need`: ties in earlier tiles, plus a scan over the workgroup's threads, plus
+// the thread's own eight in order.  Elsewhere every tie is protected and nothing is ranked.
 template <int DT>
-__global__ __launch_bounds__(64) void sal_mask_kernel(const SalBatch B) {
-    extern __shared__ char smem[];
+__global__ __launch_bounds__(SAL_THREADS) void sal_mask_kernel(const SalBatch B) {
+    __shared__ float scol[WINDQ_MAX_CHUNK];
+    __shared__ uint32_t sh[SAL_THREADS / 64];
     const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
     const SalArgs& A = B.m[mi];
     const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
     const int32_t G = A.g.chunk_w;
-    constexpr int EB = Elem<DT>::bytes;
-    const int32_t row_bytes = G * EB + 16;
-    char* tile = smem;
-    float* scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
-    const int lane = threadIdx.x;
-    load_tile_raw<DT>(A.W, A.g.ld, tc, G, tile);
-    for (int32_t c = lane; c < G; c += 64) scol[c] = A.s[tc.col0 + c];
-    __syncthreads();
+    for (int32_t c = threadIdx.x; c < G; c += SAL_THREADS) scol[c] = A.s[tc.col0 + c];
     const uint32_t T = A.prefix[tc.u];
     const uint32_t need = A.need[tc.u];
-    const bool valid = lane < tc.nrows;
-    const char* wrow = tile + lane * row_bytes;
-    uint32_t eq_row = 0;
-    if (valid) {
-        for (int32_t c = 0; c < G; c += 8) {
+    const bool split = ties_split(A, tc.u);
+    uint32_t carry = split ? A.eq_before[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] : 0u;
+    __syncthreads();
+    const int32_t pieces = G >> 3;
+    const int32_t total = tc.nrows * pieces;
+    for (int32_t i0 = 0; i0 < total; i0 += SAL_THREADS) {
+        const int32_t i = i0 + threadIdx.x;
+        const bool valid = i < total;
+        const int32_t r = i / pieces, pc = i - r * pieces;
+        uint32_t key[8];
+        uint32_t eq = 0;
+        if (valid) {
             float w[8];
-            read8<DT>(wrow, c, w);
+            load8g<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + pc * 8, w);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) eq_row += sal_key(w[j], scol[c + j]) == T ? 1u : 0u;
-        }
-    }
-    uint32_t inc = eq_row;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t t = __shfl_up(inc, d, 64);
-        if (lane >= d) inc += t;
-    }
-    uint32_t tie_rank = A.eq_before[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] + (inc - eq_row);
-    if (!valid) return;
-    uint8_t* __restrict__ mrow = A.mask + (tc.row0 + lane) * A.mask_ld + (tc.col0 >> 3);
-    for (int32_t c = 0; c < G; c += 8) {
-        float w[8];
-        read8<DT>(wrow, c, w);
-        uint32_t byte = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t key = sal_key(w[j], scol[c + j]);
-            bool prot = key > T;
-            if (key == T) {
-                prot = tie_rank < need;
-                ++tie_rank;
+            for (int j = 0; j < 8; ++j) {
+                key[j] = sal_key(w[j], scol[pc * 8 + j]);
+                eq += key[j] == T ? 1u : 0u;
             }
-            byte |= (prot ? 1u : 0u) << j;
         }
-        mrow[c >> 3] = (uint8_t)byte;
+        uint32_t byte = 0;
+        if (split) {                                   // uniform over the workgroup
+            uint32_t tot;
+            uint32_t tie_rank = carry + block_exclusive_scan_u32(eq, sh, &tot);
+            carry += tot;
+            if (valid) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    bool prot = key[j] > T;
+                    if (key[j] == T) {
+                        prot = tie_rank < need;
+                        ++tie_rank;
+                    }
+                    byte |= (prot ? 1u : 0u) << j;
+                }
+            }
+        } else if (valid) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) byte |= (key[j] >= T ? 1u : 0u) << j;
+        }
+        if (valid) A.mask[(tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) + pc] = (uint8_t)byte;
     }
 }
 
@@ -477,10 +480,6 @@ __global__ __launch_bounds__(256) void unit_saliency_finalize_kernel(const doubl
     if (threadIdx.x == 0) sal[u] = (float)(t / ((double)g.R_u * (double)g.chunk_w));
 }
 
-// select's mask kernel: raw tile, s_c of the chunk
-static size_t sal_tile_lds(int32_t dtype, int32_t chunk_w) {
-    return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float);
-}
 // encode's kernels: the tile's mask bytes, s_c of the chunk
 static size_t sal_gather_lds(int32_t chunk_w) { return mask_tile_lds_bytes(chunk_w) + (size_t)chunk_w * sizeof(float); }
 
@@ -498,7 +497,7 @@ static void carve(SalArgs& A, void* ws, const SalientLayout& L) {
 }
 
 template <int DT>
-static int launch_select(const SalBatch& B, hipStream_t hs, size_t lds) {
+static int launch_select(const SalBatch& B, hipStream_t hs) {
     const dim3 tiles((unsigned)B.tile_start[B.n]), units((unsigned)B.unit_start[B.n]);
     hipLaunchKernelGGL(sal_clear_hist_kernel, dim3((unsigned)B.fill_start[B.n]), dim3(256), 0, hs, B);
     for (int level = 0; level < 3; ++level) {
@@ -507,9 +506,7 @@ static int launch_select(const SalBatch& B, hipStream_t hs, size_t lds) {
     }
     hipLaunchKernelGGL(sal_count_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B);
     hipLaunchKernelGGL(sal_scan_kernel, units, dim3(SAL_THREADS), 0, hs, B);
-    int st = ensure_lds(reinterpret_cast<const void*>(&sal_mask_kernel<DT>), lds);
-    if (st != WINDQ_OK) return st;
-    hipLaunchKernelGGL(sal_mask_kernel<DT>, tiles, dim3(64), lds, hs, B);
+    hipLaunchKernelGGL(sal_mask_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
@@ -609,8 +606,7 @@ static int salient_select_launch(const windq_salient_item* items, int32_t n, int
     const int st = salient_number(&B);
     if (st != WINDQ_OK) return st;
     const int32_t dtype = items[0].W->dtype;
-    const size_t lds = sal_tile_lds(dtype, chunk_w);
-    return dtype == WINDQ_BF16 ? launch_select<WINDQ_BF16>(B, hs, lds) : launch_select<WINDQ_F32>(B, hs, lds);
+    return dtype == WINDQ_BF16 ? launch_select<WINDQ_BF16>(B, hs) : launch_select<WINDQ_F32>(B, hs);
 }
 
 static int salient_encode_launch(const windq_salient_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,

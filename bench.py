@@ -391,6 +391,11 @@ def main():
             "roofline": roofline(stack, fit_ms, args.steps, args.per_matrix, fused),
             "calls": per_call_pass(torch, stack, max(1, min(args.steps, 5)), args.per_matrix, fused),
         }
+        # units of the last block whose P99 needed the exact pass over their weights (the workspaces are
+        # shared by the blocks and hold the last one's counters)
+        last = stack.blocks[-1].mats
+        r["features_exact_units_last_block"] = sum(
+            wq.windq_unit_features_exact_units(stack.ws[i], m.W, G, stack.unit_rows) for i, m in enumerate(last))
         if len(stack.blocks) > 1 and not args.per_matrix:
             r["one_block"] = one_block(torch, stack, max(args.steps, 20), 10, fused)
         if args.protect_ppm > 0 and G == widths[-1]:
@@ -431,7 +436,7 @@ def main():
         "calls": head["calls"], "calls_note": "separate pass after the timed region, an event pair around every call",
         "roofline": head["roofline"],
     }
-    for key in ("one_block", "protected", "clip_sweep", "parity", "cpu_baseline"):
+    for key in ("features_exact_units_last_block", "one_block", "protected", "clip_sweep", "parity", "cpu_baseline"):
         if key in head:
             out[key] = head[key]
     if len(widths) > 1:

@@ -208,6 +208,16 @@ int windq_fit_score_rescored_units(const void* ws, int32_t dtype, int64_t rows, 
  * one per pass and matrix (see windq_fit_score_all_bits_batch for the contract: item i is one
  * per-matrix call, results are the same bit for bit).
  */
+/*
+ * Diagnostic: how many units of the last windq_unit_features or windq_features_fit_score call (or
+ * batch item) that used workspace `ws` needed the exact pass over their weights for P99 (bf16
+ * inputs: units whose 99th percentile lies far from the bulk of one of their tiles, or outside
+ * 2^-20 .. 13.5; always 0 for fp32 inputs).  Pass the shape arguments of that call.  Copies a
+ * counter to the host and therefore waits for the device: call it after the stream has finished.
+ */
+int windq_unit_features_exact_units(const void* ws, int32_t dtype, int64_t rows, int64_t cols, int32_t chunk_w,
+                                    int64_t unit_rows, int64_t* n_units /*HOST*/);
+
 typedef struct windq_feat_item {
     const windq_mat* W;     /* HOST descriptor of a device matrix */
     const float* s;         /* [cols] */

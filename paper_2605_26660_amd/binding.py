@@ -29,7 +29,7 @@ EXPORTS = (
     "windq_unit_features_batch", "windq_apply_plan_batch", "windq_calib_stats_batch", "windq_fit_score_rescored_units",
     "windq_fit_score_all_bits_static", "windq_features_fit_score", "windq_features_fit_score_batch",
     "windq_kernel_timer", "windq_kernel_timer_read", "windq_salient_select_batch", "windq_salient_encode_batch",
-    "windq_refine_plan_batch", "windq_dequant_plan_batch",
+    "windq_refine_plan_batch", "windq_dequant_plan_batch", "windq_unit_features_exact_units",
 )
 
 
@@ -159,6 +159,8 @@ def load(path: str | None = None):
     lib.windq_refine_plan_batch.restype = c.c_int
     lib.windq_dequant_plan_batch.argtypes = [c.POINTER(windq_dequant_item), i32, i32, i64, vp]
     lib.windq_dequant_plan_batch.restype = c.c_int
+    lib.windq_unit_features_exact_units.argtypes = [vp, i32, i64, i64, i32, i64, c.POINTER(i64)]
+    lib.windq_unit_features_exact_units.restype = c.c_int
     lib.windq_status_str.argtypes = [c.c_int]
     lib.windq_status_str.restype = c.c_char_p
     for name in ("windq_calib_stats", "windq_unit_features", "windq_fit_score_all_bits", "windq_plan_layout",
@@ -432,6 +434,16 @@ def windq_fit_score_rescored_units(ws: torch.Tensor, W: torch.Tensor, chunk_w: i
     n = ctypes.c_int64(0)
     _check(load().windq_fit_score_rescored_units(ws.data_ptr(), _dtype_code(W), W.shape[0], W.shape[1], chunk_w, unit_rows,
                                                  K, ctypes.byref(n)), "windq_fit_score_rescored_units")
+    return n.value
+
+
+def windq_unit_features_exact_units(ws: torch.Tensor, W: torch.Tensor, chunk_w: int, unit_rows: int) -> int:
+    """Units of the last unit-features (or fused) call on workspace `ws` that needed the exact pass over
+    their weights (diagnostic; waits for the device)."""
+    _require_cuda(ws)
+    n = ctypes.c_int64(0)
+    _check(load().windq_unit_features_exact_units(ws.data_ptr(), _dtype_code(W), W.shape[0], W.shape[1], chunk_w, unit_rows,
+                                                  ctypes.byref(n)), "windq_unit_features_exact_units")
     return n.value
 
 

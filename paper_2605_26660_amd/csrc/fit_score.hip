@@ -114,7 +114,10 @@ struct FitScoreMat {
     // first pass of the unit features (FS_SCORE_FEAT, FS_FEAT_ONLY), else unused
     double* fmoments;      // [n_tiles][4 column quarters][4]: sum w, sum w^2, sum |w|, count(|w| < 1e-6)
     uint32_t* fhist;       // [U][FEAT_BINS]: histogram of the first radix digit of |w|
+    uint32_t* ffine;       // bf16: [n_tiles][FEAT_WIN][8] full-resolution counts of the bins around each tile's bulk
+    uint32_t* fanchor;     // bf16: [n_tiles] last bin of that record, and (<< 16) the bin of the tile's largest key
     float sparse_thr;      // smallest fp32 that is >= 1e-6
+    uint32_t sparse_key;   // bf16: smallest key whose value is >= 1e-6
 };
 
 // A launch covers up to WINDQ_MAX_BATCH matrices of one chunk width and element type: their
@@ -428,13 +431,18 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(nktab + (MASKED ? FS_WAVES * TILE_ROWS : 0));
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
 
-    uint32_t* __restrict__ lhist = reinterpret_cast<uint32_t*>(scol + G);     // [FEAT_BINS / 2], over the rows' scratch
-    static_assert(FS_WAVES * 16 * FS_NRED * sizeof(float) >= FEAT_BINS / 2 * sizeof(uint32_t), "histogram fits the scratch");
+    // the features' LDS histogram, over the rows' scratch: fp32 inputs, the first radix digit
+    // (FEAT_BINS 16-bit counters); bf16 inputs, FEAT_FINE_NCOARSE first-digit bins key by key
+    // (FEAT_FINE_PAIRS dwords of two 16-bit counters: even key low, odd key high)
+    constexpr bool FINE = FEAT && DT == WINDQ_BF16;
+    constexpr int LH_DWORDS = FINE ? FEAT_FINE_PAIRS : FEAT_BINS / 2;
+    uint32_t* __restrict__ lhist = reinterpret_cast<uint32_t*>(scol + G);
+    static_assert(FS_WAVES * 16 * FS_NRED * sizeof(float) >= LH_DWORDS * sizeof(uint32_t), "histogram fits the scratch");
     load_tile_raw<DT, 1>(A.W, A.g.ld, tc, G, tile);      // 256 threads: four short steps, few registers
     for (int32_t c = threadIdx.x; c < G; c += FS_THREADS) scol[c] = A.s[tc.col0 + c];
     if (MASKED) load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     if (FEAT) {
-        for (int32_t b = threadIdx.x; b < FEAT_BINS / 2; b += FS_THREADS) lhist[b] = 0u;
+        for (int32_t b = threadIdx.x; b < LH_DWORDS; b += FS_THREADS) lhist[b] = 0u;
     }
     __syncthreads();
 
@@ -506,16 +514,33 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
                 if (!ONLY8) S1 += kept ? (double)fabsf(w[j]) : 0.0;
             }
             if (FEAT) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    f_sw += w[j];
+                    f_sw2 = fmaf(w[j], w[j], f_sw2);
+                }
+            }
+            if (FINE) {
+                // key = bits 16..30 of the pattern; its pair (key >> 1) is dword pair - 8 * FEAT_FINE_COARSE0
+                // of the histogram, clamped: everything below the resolved range lands in the first
+                // dword, everything above in the last.  Bit 16 picks the half.
+                if (valid) {
+                    char* __restrict__ lh = reinterpret_cast<char*>(lhist);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t bits = __float_as_uint(w[j]);
+                        int32_t off = (int32_t)((bits >> 15) & 0xFFFCu) - 32 * FEAT_FINE_COARSE0;
+                        off = min(max(off, 0), 4 * (FEAT_FINE_PAIRS - 1));
+                        atomicAdd(reinterpret_cast<uint32_t*>(lh + off), max(bits & 0x10000u, 1u));
+                    }
+                }
+            } else if (FEAT) {
                 // bin of |w| = bits 20..30 of the pattern: dword (bin & 1023) of the LDS histogram, half
                 // (bin >> 10).  The upper half is |w| >= 2: rare, so the wavefront asks once per eight
                 // columns whether any of its rows needs it.
                 uint32_t any_bits = 0u;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    f_sw += w[j];
-                    f_sw2 = fmaf(w[j], w[j], f_sw2);
-                    any_bits |= __float_as_uint(w[j]);
-                }
+                for (int j = 0; j < 8; ++j) any_bits |= __float_as_uint(w[j]);
                 if (valid) {
                     char* __restrict__ lh = reinterpret_cast<char*>(lhist);
                     if (__builtin_amdgcn_ballot_w64((any_bits & 0x40000000u) != 0u) == 0) {
@@ -543,7 +568,56 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
 
     float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
 
-    if (FEAT) {
+    if (FINE) {
+        // (every counter at most 8192: the halves never carry)
+        // The tile's largest key and its mean |w|, from the quarters' row minima, maxima and sums:
+        // every wavefront takes all 4 x 64 of them, in the same order, so none waits for another.
+        // The record covers the FEAT_WIN first-digit bins that end 5 octaves above the mean: P99
+        // and half of it lie 0.7-2.7 octaves above the mean |w| of Gaussian to heavy-tailed
+        // weights, wherever single outliers sit.
+        const int lane_a = fresh_lane();
+        float amax = 0.0f;
+        double sabs = 0.0;
+#pragma unroll
+        for (int q = 0; q < FS_WAVES; ++q) {
+            const float2 st = gstat[q * TILE_ROWS + lane_a];
+            if (st.x <= st.y) amax = fmaxf(amax, fmaxf(fabsf(st.x), fabsf(st.y)));
+            sabs += s1tab[q * TILE_ROWS + lane_a];
+        }
+        const float mean = (float)wave_sum(sabs) / (float)(tc.nrows * G);
+        const int32_t tmax = (int32_t)(__float_as_uint(wave_max_f32(amax)) >> 20);     // first-digit bin of the largest key
+        const int32_t ct = (int32_t)(__float_as_uint(mean) >> 20) + 40;               // top bin of the record
+        // first-digit sums into the unit's histogram: bin FEAT_FINE_COARSE0 + b is dwords 8b .. 8b+7
+        uint32_t* __restrict__ gh = A.fhist + (size_t)tc.u * FEAT_BINS;
+        if (threadIdx.x < FEAT_FINE_NCOARSE) {
+            uint32_t sum = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t v = lhist[threadIdx.x * 8 + i];
+                sum += (v & 0xffffu) + (v >> 16);
+            }
+            if (sum != 0u) atomicAdd(&gh[FEAT_FINE_COARSE0 + threadIdx.x], sum);
+        }
+        // the record: the FEAT_WIN first-digit bins that end at ct, key by key
+        const size_t tidx = (size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t;
+        uint32_t* __restrict__ rec = A.ffine + tidx * (FEAT_WIN * 8);
+        for (int32_t i = threadIdx.x; i < FEAT_WIN * 8; i += FS_THREADS) {
+            const int32_t b = ct - (FEAT_WIN - 1) + (i >> 3) - FEAT_FINE_COARSE0;      // resolved bins: 1 .. NCOARSE - 2
+            rec[i] = b >= 1 && b <= FEAT_FINE_NCOARSE - 2 ? lhist[b * 8 + (i & 7)] : 0u;
+        }
+        if (threadIdx.x == 0) A.fanchor[tidx] = (uint32_t)ct | ((uint32_t)tmax << 16);
+        // |w| < 1e-6: the keys below sparse_key (inside the resolved range, above the first lumping bin)
+        if (wave == 0) {
+            const int32_t nlow = (int32_t)A.sparse_key - 16 * FEAT_FINE_COARSE0;      // counters below the threshold
+            uint32_t cnt = 0;
+            for (int32_t d = lane_a; 2 * d < nlow; d += 64) {
+                const uint32_t v = lhist[d];
+                cnt += (v & 0xffffu) + (2 * d + 1 < nlow ? v >> 16 : 0u);
+            }
+            f_cnt = (float)cnt;
+        }
+        __syncthreads();        // the scratch is free for the sums from here on
+    } else if (FEAT) {
         // the tile's histogram into the unit's (every bin at most 8192: the halves never carry)
         uint32_t* __restrict__ gh = A.fhist + (size_t)tc.u * FEAT_BINS;
         const uint32_t thr_bin = (__float_as_uint(A.sparse_thr) >> 20) & 1023u;      // 1e-6 lies far below 2: lower half
@@ -570,6 +644,8 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
             }
             f_cnt = lane_c < tc.nrows ? (float)cnt : 0.0f;
         }
+    }
+    if (FEAT) {
         const int lane_f = fresh_lane();
         const float v3[3] = {f_sw, f_sw2, f_cnt};
         const double m3 = rows_sum<3>(v3, red, lane_f);
@@ -1043,7 +1119,10 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
         M.ref_energy = it.ref_energy;
         M.fmoments = feat != nullptr ? feat->m[i].moments : nullptr;
         M.fhist = feat != nullptr ? feat->m[i].hist : nullptr;
+        M.ffine = feat != nullptr ? feat->m[i].fine : nullptr;
+        M.fanchor = feat != nullptr ? feat->m[i].anchor : nullptr;
         M.sparse_thr = feat != nullptr ? feat->m[i].sparse_thr : 0.0f;
+        M.sparse_key = feat != nullptr ? feat->m[i].sparse_key : 0u;
         // tau: with the error spread evenly over R_u rows, listing the columns above tau times the
         // mean keeps the short route's noise in the unit's 8-bit error near 1e-6 (one standard
         // deviation; what the rows really do is measured per unit, see NOISE_MAX).  Below
@@ -1110,7 +1189,10 @@ int windq::features_launch_tiles(const FeatBatch& F, hipStream_t hs) {
         M.g = f.g;
         M.fmoments = f.moments;
         M.fhist = f.hist;
+        M.ffine = f.fine;
+        M.fanchor = f.anchor;
         M.sparse_thr = f.sparse_thr;
+        M.sparse_key = f.sparse_key;
         if (i < F.n) {
             A.tile_start[i] = tiles;
             A.unit_start[i] = units;

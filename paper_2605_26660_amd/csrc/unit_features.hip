@@ -6,22 +6,26 @@
 // P99 is the exact nearest-rank order statistic of |w|, found by most-significant-digit
 // radix selection on the bit pattern of |w| (monotone in |w| for non-negative floats).
 //
-// The FIRST pass over W -- moments, the count of |w| < 1e-6 and the histogram of the first
-// digit (11 bits: exponent + 3 mantissa bits) -- is made by the tile kernel of fit_score.hip:
-// either alone (windq_unit_features) or as part of the fit+score kernel, which has the tile
-// in LDS anyway (windq_features_fit_score: W is then read once for both).  This file holds
-// what follows.
-// bf16 (15-bit keys, digits of 11 + 4 bits): one more pass over W.
-//   pass B  every workgroup first re-derives, from the finished first-digit histogram,
-//           the bin e0 that holds the wanted rank (a 2048-bin scan: cheaper than a launch
-//           and than any cross-workgroup handshake, which on this multi-die GPU costs an
-//           L2 write-back per workgroup).  It then refines two bins to all 4 remaining
-//           bits: e0, and the bin that holds the key of 0.5*P99.  Halving a bf16 lowers its
-//           key by 128 (one exponent step), or halves the key below 256 where keys are
-//           linear in the value, so that bin is e0 - 8 (or e0 >> 1) whatever the low bits
-//           of P99 turn out to be.
-//   finish  per unit: P99 exactly, the exact count of |w| > 0.5 P99 = (first-digit bins
-//           above) + (refined bins above), and the eight features.  No third pass.
+// The FIRST pass over W -- moments, the count of |w| < 1e-6 and the histograms -- is made by
+// the tile kernel of fit_score.hip: either alone (windq_unit_features) or as part of the
+// fit+score kernel, which has the tile in LDS anyway (windq_features_fit_score: W is then read
+// once for both).  This file holds what follows.
+// bf16 (15-bit keys, digits of 11 + 4 bits): NO further pass over W.  The tile kernel counts
+//   its tile key by key in LDS, adds the first-digit sums to the unit's histogram, and records
+//   the full-resolution counts of 64 first-digit bins (8 octaves: 3 below to 5 above the
+//   tile's mean |w|) together with the bin of its largest key.
+//   finish  per unit: the first-digit bin e0 of the rank; the 16 + 16 full-resolution counters
+//           of e0 and of the bin that holds the key of 0.5*P99, gathered from the unit's tiles'
+//           records (a tile whose largest key lies below a bin holds nothing in it).  Halving a
+//           bf16 lowers its key by 128 (one exponent step), so that bin is e0 - 8 whatever the
+//           low bits of P99 turn out to be.  Then P99 exactly, the exact count of
+//           |w| > 0.5 P99 = (first-digit bins above) + (refined counters above), and the eight
+//           features.
+//   exact   a unit whose bins lie outside the record of one of its tiles (P99 or its half
+//           far from 1.6-3.2 times that tile's mean |w|), or whose P99 lies outside the range the tile kernel
+//           resolves (below 2^-20 or above 13.5), is listed by the finish kernel; a last kernel
+//           takes the listed units one workgroup each, selects P99 by two digit passes over the
+//           unit and counts in a third.  It reads W only for such units.
 // fp32 (31-bit keys, digits 11 + 11 + 9): one pass per further digit plus a counting pass
 // (2|w| > P99, exact in fp32), each re-deriving the prefix from the finished histograms.
 // Passes after the first re-read a matrix that was just streamed; up to the 256 MB
@@ -80,23 +84,18 @@ __device__ __host__ constexpr int level_bits(int level) {
 template <int DT>
 __device__ __host__ constexpr int n_levels() { return DT == WINDQ_BF16 ? 2 : 3; }
 
-// Counters the passes add to, per unit: bf16 uses the first-digit histogram and 2 x 16 refined
-// counters at the head of the second one; fp32 all three histograms.
+// Counters the passes add to: bf16, the first-digit histogram of every unit (and the length of
+// the list of units for the exact pass); fp32, all three histograms.
 template <int DT>
-__host__ __device__ constexpr int64_t feat_init_per_unit() { return DT == WINDQ_BF16 ? FEAT_BINS + 32 : 3 * FEAT_BINS; }
+__host__ __device__ constexpr int64_t feat_init_per_unit() { return DT == WINDQ_BF16 ? FEAT_BINS : 3 * FEAT_BINS; }
 
 template <int DT>
 __global__ __launch_bounds__(256) void feat_init_kernel(const FeatBatch B) {
     const int mi = batch_index(B.init_start, B.n, blockIdx.x);
     const FeatArgs& A = B.m[mi];
     const int64_t i = ((int64_t)blockIdx.x - B.init_start[mi]) * 256 + threadIdx.x;
-    if (DT == WINDQ_BF16) {
-        constexpr int64_t PU = feat_init_per_unit<DT>();
-        const int64_t u = i / PU, b = i - u * PU;
-        if (u < A.g.U) A.hist[b < FEAT_BINS ? u * FEAT_BINS + b : (A.g.U + u) * FEAT_BINS + (b - FEAT_BINS)] = 0;
-    } else {
-        if (i < (int64_t)3 * A.g.U * FEAT_BINS) A.hist[i] = 0;
-    }
+    if (i < feat_init_per_unit<DT>() * A.g.U) A.hist[i] = 0;
+    if (DT == WINDQ_BF16 && i == 0) *A.list_count = 0u;
 }
 
 // Block-wide sum of a per-thread double in a fixed order (lanes by butterfly, wavefronts in order).
@@ -132,93 +131,6 @@ __device__ __forceinline__ void select_prefix(const FeatArgs& A, int64_t u, int 
 
 // bf16: first-digit bin that holds the key of 0.5 * P99, given P99's first-digit bin.
 __device__ __forceinline__ uint32_t half_bin_of(uint32_t e0) { return e0 >= 16u ? e0 - 8u : e0 >> 1; }
-
-// The bf16 refining pass works on the packed 16-bit patterns directly (two weights per dword): the
-// first digit is a bit-field extract, no conversion to float.  It refines bins e0 and
-// half_bin_of(e0) to the remaining 4 bits; the 2 x 16 counters live in LDS in FEAT_COPIES copies
-// indexed by lane, which thins out the same-address collisions of the LDS atomics.
-constexpr int FEAT_COPIES = 2;
-constexpr int FEAT_REFINE_BINS = 32;
-constexpr int FEAT_CSTRIDE = FEAT_REFINE_BINS + 17;   // odd skew: copies of a bin sit in different banks
-__global__ __launch_bounds__(FT_THREADS) void feat_refine_bf16_kernel(const FeatBatch B) {
-    const int mi = batch_index(B.block_start, B.n, blockIdx.x);
-    const FeatArgs& A = B.m[mi];
-    const int64_t wg = (int64_t)blockIdx.x - B.block_start[mi];
-    __shared__ uint32_t lhist[FEAT_COPIES * FEAT_CSTRIDE];
-    __shared__ uint32_t sh_part[FT_THREADS];
-    __shared__ uint32_t sh_out[4];
-    const int64_t u = wg / A.bpu;
-    const int64_t blk = wg - u * A.bpu;
-    const int32_t G = A.g.chunk_w;
-    const int32_t pieces = G >> 3;
-    const int64_t rb = u / A.g.n_chunks;
-    const int64_t col0 = (u - rb * A.g.n_chunks) * G;
-    const int64_t lrow0 = blk * FEAT_TPB * TILE_ROWS;
-    const int64_t left = A.g.R_u - lrow0;
-    const int32_t nrows = (int32_t)(left < FEAT_TPB * TILE_ROWS ? left : FEAT_TPB * TILE_ROWS);
-    const int64_t row0 = rb * A.g.R_u + lrow0;
-    // The first batch of loads is issued before anything else, so that it is in flight while
-    // the counters are cleared and the rank's first-digit bin is looked up.
-    const uint16_t* __restrict__ Wp = static_cast<const uint16_t*>(A.W);
-    const bool by_rows = FT_THREADS % pieces == 0;          // a thread keeps its column piece and steps down the rows
-    const int32_t rstep = by_rows ? FT_THREADS / pieces : 1;
-    const int32_t r_first = by_rows ? (int32_t)threadIdx.x / pieces : nrows;
-    const int64_t cbase = col0 + (int64_t)(by_rows ? (int32_t)threadIdx.x % pieces : 0) * 8;
-    uint4 first[FEAT_BATCH];
-#pragma unroll
-    for (int b = 0; b < FEAT_BATCH; ++b)
-        if (r_first + b * rstep < nrows)
-            first[b] = *reinterpret_cast<const uint4*>(Wp + (row0 + r_first + b * rstep) * A.g.ld + cbase);
-    for (int32_t b = threadIdx.x; b < FEAT_CSTRIDE * FEAT_COPIES; b += FT_THREADS) lhist[b] = 0;
-    uint32_t e0 = 0;
-    uint64_t rank_left;
-    select_prefix<WINDQ_BF16>(A, u, 1, sh_part, sh_out, &e0, &rank_left);
-    const uint32_t eh = half_bin_of(e0);
-    __syncthreads();
-    uint32_t* __restrict__ myhist = lhist + (threadIdx.x & (FEAT_COPIES - 1)) * FEAT_CSTRIDE;
-
-    auto consume = [&](const uint4& raw) {
-        const uint32_t x[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t dlo = (x[j] >> 4) & 0x7ffu, dhi = (x[j] >> 20) & 0x7ffu;
-            // one atomic per weight: the two bins are distinct unless both are bin 0, and
-            // then the single histogram serves both (the finish kernel reads it twice)
-            if (dlo == e0 || dlo == eh) atomicAdd(&myhist[(dlo == e0 ? 0u : 16u) + (x[j] & 15u)], 1u);
-            if (dhi == e0 || dhi == eh) atomicAdd(&myhist[(dhi == e0 ? 0u : 16u) + ((x[j] >> 16) & 15u)], 1u);
-        }
-    };
-    if (by_rows) {
-#pragma unroll
-        for (int b = 0; b < FEAT_BATCH; ++b)
-            if (r_first + b * rstep < nrows) consume(first[b]);
-        for (int32_t r = r_first + FEAT_BATCH * rstep; r < nrows; r += FEAT_BATCH * rstep) {
-            uint4 raw[FEAT_BATCH];
-#pragma unroll
-            for (int b = 0; b < FEAT_BATCH; ++b)
-                if (r + b * rstep < nrows)
-                    raw[b] = *reinterpret_cast<const uint4*>(Wp + (row0 + r + b * rstep) * A.g.ld + cbase);
-#pragma unroll
-            for (int b = 0; b < FEAT_BATCH; ++b)
-                if (r + b * rstep < nrows) consume(raw[b]);
-        }
-    } else {
-        const int32_t total = nrows * pieces;
-        for (int32_t i = threadIdx.x; i < total; i += FT_THREADS) {
-            const int32_t r = i / pieces;
-            const int32_t pc = i - r * pieces;
-            consume(*reinterpret_cast<const uint4*>(Wp + (row0 + r) * A.g.ld + col0 + (int64_t)pc * 8));
-        }
-    }
-    __syncthreads();
-    uint32_t* __restrict__ gh = A.hist + ((size_t)A.g.U + (size_t)u) * FEAT_BINS;
-    for (int32_t b = threadIdx.x; b < FEAT_REFINE_BINS; b += FT_THREADS) {
-        uint32_t v = 0;
-#pragma unroll
-        for (int c = 0; c < FEAT_COPIES; ++c) v += lhist[c * FEAT_CSTRIDE + b];
-        if (v != 0) atomicAdd(&gh[b], v);
-    }
-}
 
 // One pass over FEAT_TPB tiles of one unit (generic element type; used for fp32 inputs).
 //   MODE 1: histogram(s) of digit `level` under the unit's prefix.
@@ -372,26 +284,78 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
     const float sv0 = has0 ? sc[tid] : 0.0f;
     const float sv1 = has1 ? sc[tid + FT_THREADS] : 0.0f;
     const uint32_t* h0 = A.hist + (size_t)u * FEAT_BINS;
-    const uint32_t* h1 = A.hist + ((size_t)A.g.U + (size_t)u) * FEAT_BINS;
-    uint32_t h1v = 0;
-    if (DT == WINDQ_BF16 && tid < 32) h1v = h1[tid];      // both refined bins: 2 x 16 counters
 
     double above = 0.0;
+    bool listed = false;        // bf16: left to the exact pass
     if (DT == WINDQ_BF16) {
+        __shared__ uint32_t sub[32];          // full-resolution counters of bins e0 and e0 - 8
+        __shared__ uint32_t wsub[FT_WAVES * 32];
+        __shared__ int miss;
         uint32_t e0, l1;
         uint64_t rank1, below;
-        select_prefix<DT>(A, u, 1, sh_part, sh_out, &e0, &rank1);
-        select_bin<FT_THREADS>(h1, 16, rank1, sh_part, sh_out, &l1, &below);
-        // Key of 0.5 * P99: one exponent step down, or half the key where keys are linear in
-        // the value (below 256: subnormals and the first binade).
-        const uint32_t pk = (e0 << 4) | l1;
-        const uint32_t tk = pk >= 256u ? pk - 128u : pk >> 1;
-        const uint32_t tbin = tk >> 4, tlow = tk & 15u;        // tbin == half_bin_of(e0) by construction
-        for (int32_t b = tid; b < FEAT_BINS; b += FT_THREADS)
-            if ((uint32_t)b > tbin) above += (double)h0[b];
-        // (when both refined bins are bin 0 they share the first 16 counters)
-        const int first = tbin == e0 ? 0 : 16;
-        if (tid >= first && tid < first + 16 && (uint32_t)(tid - first) > tlow) above += (double)h1v;
+        if (tid == 0) miss = 0;
+        select_prefix<DT>(A, u, 1, sh_part, sh_out, &e0, &rank1);       // (its barriers publish the zero)
+        const uint32_t eh = half_bin_of(e0);
+        // both bins inside the range the tile kernel resolves key by key?
+        const bool resolved = eh > (uint32_t)FEAT_FINE_COARSE0 && e0 < (uint32_t)(FEAT_FINE_COARSE0 + FEAT_FINE_NCOARSE - 1);
+        uint32_t cnt[32];                     // this thread's tiles (LDS atomics on 32 shared counters crawl)
+#pragma unroll
+        for (int k = 0; k < 32; ++k) cnt[k] = 0u;
+        if (resolved) {
+            for (int64_t t = tid; t < A.g.tiles_per_unit; t += FT_THREADS) {
+                const size_t tidx = (size_t)u * (size_t)A.g.tiles_per_unit + (size_t)t;
+                const uint32_t an = A.anchor[tidx];
+                const uint32_t ct = an & 0xffffu, tmax = an >> 16;     // record = bins ct - 63 .. ct; nothing above tmax
+                const uint32_t* __restrict__ rec = A.fine + tidx * (FEAT_WIN * 8);
+#pragma unroll
+                for (int which = 0; which < 2; ++which) {
+                    const uint32_t c = which == 0 ? e0 : eh;
+                    if (c > tmax) continue;
+                    if (c > ct || c + (FEAT_WIN - 1) < ct) {           // outside the tile's record
+                        miss = 1;
+                        continue;
+                    }
+                    const uint4* __restrict__ src = reinterpret_cast<const uint4*>(rec + (c + (FEAT_WIN - 1) - ct) * 8);
+                    const uint4 a = src[0], b = src[1];
+                    const uint32_t v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        cnt[which * 16 + 2 * i] += v[i] & 0xffffu;
+                        cnt[which * 16 + 2 * i + 1] += v[i] >> 16;
+                    }
+                }
+            }
+        }
+        // threads by butterfly, wavefronts through LDS
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            uint32_t v = cnt[k];
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+            if ((tid & 63) == 0) wsub[(tid >> 6) * 32 + k] = v;
+        }
+        __syncthreads();
+        if (tid < 32) {
+            uint32_t v = 0;
+#pragma unroll
+            for (int w = 0; w < FT_WAVES; ++w) v += wsub[w * 32 + tid];
+            sub[tid] = v;
+        }
+        __syncthreads();
+        listed = !resolved || miss != 0;
+        if (!listed) {
+            select_bin<FT_THREADS>(sub, 16, rank1, sh_part, sh_out, &l1, &below);
+            // Key of 0.5 * P99: one exponent step down (the resolved range lies far above the
+            // first binade, where keys are linear in the value).
+            const uint32_t pk = (e0 << 4) | l1;
+            const uint32_t tk = pk - 128u;
+            const uint32_t tbin = tk >> 4, tlow = tk & 15u;        // tbin == eh by construction
+            for (int32_t b = tid; b < FEAT_BINS; b += FT_THREADS)
+                if ((uint32_t)b > tbin) above += (double)h0[b];
+            if (tid < 16 && (uint32_t)tid > tlow) above += (double)sub[16 + tid];
+        } else if (tid == 0) {
+            A.list[atomicAdd(A.list_count, 1u)] = (uint32_t)u;
+        }
     } else {
         for (int64_t b = tid; b < A.bpu; b += FT_THREADS) above += (double)A.above[(size_t)u * A.bpu + b];
     }
@@ -425,24 +389,98 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
         f[1] = (float)sqrt(var);
         f[2] = (float)(r6[3] / n);
         f[3] = (float)(r6[4] / n);
-        f[4] = (float)(r6[0] / n);
+        if (!listed) f[4] = (float)(r6[0] / n);
         f[5] = (float)smean;
         f[6] = (float)sqrt(sdev / (double)G);
         f[7] = mx;
     }
 }
 
+// bf16: the units the finish kernel listed, one workgroup each (workgroups stride over the lists
+// of the launch's matrices).  P99 by two digit passes over the unit's keys (8 + 7 bits), then the
+// count of keys above the key of 0.5 * P99: feature 4, the only one that depends on P99.
+constexpr int FEAT_EXACT_GRID = 256;
+__global__ __launch_bounds__(FT_THREADS) void feat_exact_bf16_kernel(const FeatBatch B) {
+    __shared__ uint32_t h[256];
+    __shared__ uint32_t sh_part[FT_THREADS];
+    __shared__ uint32_t sh_out[4];
+    __shared__ uint32_t wsum[FT_WAVES];
+    const int tid = threadIdx.x;
+    for (int mi = 0; mi < B.n; ++mi) {
+        const FeatArgs& A = B.m[mi];
+        const uint32_t n_listed = *A.list_count;
+        const int32_t G = A.g.chunk_w;
+        const int32_t pieces = G >> 3;
+        const int64_t total = A.g.R_u * pieces;
+        const uint16_t* __restrict__ Wp = static_cast<const uint16_t*>(A.W);
+        for (uint32_t l = blockIdx.x; l < n_listed; l += gridDim.x) {
+            const int64_t u = A.list[l];
+            const int64_t rb = u / A.g.n_chunks;
+            const int64_t col0 = (u - rb * A.g.n_chunks) * G;
+            const int64_t row0 = rb * A.g.R_u;
+            // calls f(key) for every weight of the unit
+            auto sweep = [&](auto f) {
+                for (int64_t i = tid; i < total; i += FT_THREADS) {
+                    const int64_t r = i / pieces;
+                    const int64_t pc = i - r * pieces;
+                    const uint4 raw = *reinterpret_cast<const uint4*>(Wp + (row0 + r) * A.g.ld + col0 + pc * 8);
+                    const uint32_t x[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        f(x[j] & 0x7fffu);
+                        f((x[j] >> 16) & 0x7fffu);
+                    }
+                }
+            };
+            h[tid] = 0u;
+            __syncthreads();
+            sweep([&](uint32_t key) { atomicAdd(&h[key >> 7], 1u); });
+            __syncthreads();
+            uint32_t d0, d1;
+            uint64_t below;
+            select_bin<FT_THREADS>(h, 256, A.rank, sh_part, sh_out, &d0, &below);
+            const uint64_t rank1 = A.rank - below;
+            __syncthreads();
+            h[tid] = 0u;
+            __syncthreads();
+            sweep([&](uint32_t key) {
+                if ((key >> 7) == d0) atomicAdd(&h[key & 127u], 1u);
+            });
+            __syncthreads();
+            select_bin<FT_THREADS>(h, 128, rank1, sh_part, sh_out, &d1, &below);
+            // Key of 0.5 * P99: one exponent step down, or half the key where keys are linear in
+            // the value (below 256: subnormals and the first binade).
+            const uint32_t pk = (d0 << 7) | d1;
+            const uint32_t tk = pk >= 256u ? pk - 128u : pk >> 1;
+            uint32_t cnt = 0;
+            sweep([&](uint32_t key) { cnt += key > tk ? 1u : 0u; });
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) cnt += __shfl_xor(cnt, m, 64);
+            __syncthreads();
+            if ((tid & 63) == 0) wsum[tid >> 6] = cnt;
+            __syncthreads();
+            if (tid == 0) {
+                uint64_t above = 0;
+                for (int w = 0; w < FT_WAVES; ++w) above += wsum[w];
+                A.feat[u * WINDQ_N_FEAT + 4] = (float)((double)above / ((double)A.g.R_u * (double)G));
+            }
+            __syncthreads();
+        }
+    }
+}
+
 template <int DT>
 static int launch_rest(const FeatBatch& B, hipStream_t hs) {
-    const dim3 blocks((unsigned)B.blocks_total);
     if (DT == WINDQ_BF16) {
-        hipLaunchKernelGGL(feat_refine_bf16_kernel, blocks, dim3(FT_THREADS), 0, hs, B);
+        hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)B.units_total), dim3(FT_THREADS), 0, hs, B);
+        hipLaunchKernelGGL(feat_exact_bf16_kernel, dim3(FEAT_EXACT_GRID), dim3(FT_THREADS), 0, hs, B);
     } else {
+        const dim3 blocks((unsigned)B.blocks_total);
         hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, B, 1);
         hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, B, 2);
         hipLaunchKernelGGL((feat_pass_kernel<DT, 2>), blocks, dim3(FT_THREADS), 0, hs, B, 0);
+        hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)B.units_total), dim3(FT_THREADS), 0, hs, B);
     }
-    hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)B.units_total), dim3(FT_THREADS), 0, hs, B);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
@@ -463,6 +501,11 @@ int features_fill(const FeatItem* items, int32_t n, int32_t chunk_w, int64_t uni
     int64_t blocks = 0, units = 0, inits = 0;
     float thr = (float)1e-6;
     if ((double)thr < 1e-6) thr = nextafterf(thr, INFINITY);
+    // bf16 keys order like their values: the smallest key whose value reaches the threshold
+    uint32_t thr_bits;
+    memcpy(&thr_bits, &thr, sizeof thr_bits);
+    const uint32_t sparse_key = (thr_bits >> 16) + ((thr_bits & 0xffffu) != 0u ? 1u : 0u);
+    static_assert(FEAT_FINE_COARSE0 == 847 && FEAT_FINE_NCOARSE == 200, "1e-6 lies inside the range the tile kernel resolves");
     for (int32_t i = 0; i < n; ++i) {
         const FeatItem& it = items[i];
         FeatArgs& A = B.m[i];
@@ -471,7 +514,7 @@ int features_fill(const FeatItem* items, int32_t n, int32_t chunk_w, int64_t uni
         if (st != WINDQ_OK) return st;
         if (it.s == nullptr || it.feat == nullptr) return WINDQ_EINVAL;
         if (it.W->dtype != items[0].W->dtype) return WINDQ_EINVAL;        // one kernel per launch
-        const FeatLayout L = features_layout(A.g);
+        const FeatLayout L = features_layout(A.g, it.W->dtype);
         if (it.ws == nullptr || it.ws_bytes < L.total || !aligned(it.ws, 256)) return WINDQ_EWORKSPACE;
         if ((uint64_t)A.g.R_u * (uint64_t)chunk_w > (uint64_t)0xffffffffu) return WINDQ_ESHAPE;   // u32 bin counts
         char* base = static_cast<char*>(it.ws);
@@ -481,6 +524,11 @@ int features_fill(const FeatItem* items, int32_t n, int32_t chunk_w, int64_t uni
         A.moments = reinterpret_cast<double*>(base + L.moments);
         A.above = reinterpret_cast<uint32_t*>(base + L.above);
         A.hist = reinterpret_cast<uint32_t*>(base + L.hist);
+        A.fine = reinterpret_cast<uint32_t*>(base + L.fine);
+        A.anchor = reinterpret_cast<uint32_t*>(base + L.anchor);
+        A.list_count = reinterpret_cast<uint32_t*>(base + L.list_count);
+        A.list = reinterpret_cast<uint32_t*>(base + L.list);
+        A.sparse_key = sparse_key;
         A.bpu = L.bpu;
         A.mparts = L.mparts;
         A.sparse_thr = thr;
@@ -535,4 +583,21 @@ extern "C" int windq_unit_features(const windq_mat* W, const float* s, int32_t c
 extern "C" int windq_unit_features_batch(const windq_feat_item* items, int32_t n, int32_t chunk_w, int64_t unit_rows,
                                          void* stream) {
     return unit_features_launch(items, n, chunk_w, unit_rows, stream);
+}
+
+extern "C" int windq_unit_features_exact_units(const void* ws, int32_t dtype, int64_t rows, int64_t cols, int32_t chunk_w,
+                                               int64_t unit_rows, int64_t* n_units) {
+    if (ws == nullptr || n_units == nullptr) return WINDQ_EINVAL;
+    windq_mat fake = {ws, dtype, 0, rows, cols, cols};      // shape checks only: the data pointer is not read
+    Geometry g;
+    const int st = make_geometry(&fake, chunk_w, unit_rows, &g);
+    if (st != WINDQ_OK) return st;
+    *n_units = 0;
+    if (dtype != WINDQ_BF16) return WINDQ_OK;
+    const FeatLayout L = features_layout(g, dtype);
+    uint32_t cnt = 0;
+    if (hipMemcpy(&cnt, static_cast<const char*>(ws) + L.list_count, sizeof(cnt), hipMemcpyDeviceToHost) != hipSuccess)
+        return WINDQ_EHIP;
+    *n_units = (int64_t)cnt;
+    return WINDQ_OK;
 }

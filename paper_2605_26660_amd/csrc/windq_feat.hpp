@@ -12,8 +12,13 @@ struct FeatArgs {
     const float* s;
     float* feat;
     double* moments;    // [n_tiles][4][4]
-    uint32_t* above;
-    uint32_t* hist;     // [3][U][FEAT_BINS]
+    uint32_t* above;    // fp32 inputs
+    uint32_t* hist;     // [U][FEAT_BINS] (bf16), [3][U][FEAT_BINS] (fp32)
+    uint32_t* fine;     // bf16 inputs: [n_tiles][FEAT_WIN][8] full-resolution counts around each tile's bulk
+    uint32_t* anchor;   //              [n_tiles] last bin of that record; << 16, bin of the tile's largest key
+    uint32_t* list_count;   //          units whose P99 the tiles' records do not decide ...
+    uint32_t* list;     //              ... [U] their indices, in no particular order
+    uint32_t sparse_key;    //          smallest bf16 key whose value is >= 1e-6
     Geometry g;
     int64_t bpu;        // workgroups per unit (passes after the first)
     int64_t mparts;     // moment records per unit
@@ -49,7 +54,8 @@ int features_fill(const FeatItem* items, int32_t n, int32_t chunk_w, int64_t uni
 int features_launch_init(const FeatBatch& B, hipStream_t hs);
 // The first pass by itself: per tile, moments, counts and the first-digit histogram.  (fit_score.hip)
 int features_launch_tiles(const FeatBatch& B, hipStream_t hs);
-// Everything after the first pass: the refining passes and the finish kernel.  (unit_features.hip)
+// Everything after the first pass: bf16, the finish kernel and the exact pass over the units it lists;
+// fp32, the refining passes and the finish kernel.  (unit_features.hip)
 int features_launch_rest(const FeatBatch& B, hipStream_t hs);
 
 }  // namespace windq

@@ -37,35 +37,59 @@ inline FitScoreLayout fit_score_layout(const Geometry& g, int32_t K) {
 inline size_t fit_score_ws_bytes(const Geometry& g, int32_t K) { return fit_score_layout(g, K).total; }
 
 // ---- unit_features
-// The first pass (moments, counts, histogram of the first radix digit) works tile by tile, each of the
-// four wavefronts of a workgroup on a quarter of the chunk's columns; the later passes cover
-// FEAT_TPB consecutive tiles of one unit per workgroup ("block" below).
+// The first pass (moments, counts, histograms) works tile by tile, each of the four wavefronts of a
+// workgroup on a quarter of the chunk's columns.
 //   moments  [n_tiles][4][4] fp64   per (tile, column quarter): sum w, sum w^2, sum |w|, count(|w| < 1e-6)
-//   above    [n_blocks]    u32    count(|w| > 0.5 P99)            (fp32 inputs only)
+// bf16 inputs (15-bit keys = the magnitude bits; first radix digit = key >> 4, 2048 bins):
+//   hist     [U][FEAT_BINS] u32     histogram of the first digit; keys below / above the range the tile
+//                                   kernel resolves are lumped into its first / last bin
+//   fine     [n_tiles][FEAT_WIN][8] u32   per tile, the full-resolution counts (two 16-bit counters per
+//                                   dword: even key low, odd key high) of FEAT_WIN first-digit bins
+//                                   around the tile's bulk
+//   anchor   [n_tiles] u32          the last of those bins; << 16, the bin of the tile's largest key
+//   list_count u32, list [U] u32    units whose P99 the records do not decide
+// fp32 inputs (31-bit keys, digits 11 + 11 + 9): the later passes cover FEAT_TPB consecutive tiles of one
+// unit per workgroup ("block" below)
+//   above    [n_blocks]    u32    count(|w| > 0.5 P99)
 //   hist     [3][U][FEAT_BINS] u32  histogram of radix digit 0, 1, 2
 constexpr int FEAT_DIGIT_BITS = 11;
 constexpr int FEAT_BINS = 1 << FEAT_DIGIT_BITS;
 constexpr int FEAT_TPB = 2;
 constexpr int FEAT_QUARTERS = 4;
+// bf16: the tile kernel's LDS histogram resolves FEAT_FINE_NCOARSE first-digit bins key by key,
+// 2^-21.1 <= |w| < 13.5 between its two lumping end bins (8 dwords of two counters per first-digit bin).
+constexpr int FEAT_FINE_COARSE0 = 847;
+constexpr int FEAT_FINE_NCOARSE = 200;
+constexpr int FEAT_FINE_PAIRS = FEAT_FINE_NCOARSE * 8;
+constexpr int FEAT_WIN = 64;
 struct FeatLayout {
-    int64_t bpu;       // workgroups per unit (later passes)
+    int64_t bpu;       // workgroups per unit (later passes, fp32)
     int64_t n_blocks;
     int64_t mparts;    // moment records per unit: tiles x column quarters
-    size_t moments, above, hist, total;
+    size_t moments, above, hist, fine, anchor, list_count, list, total;
 };
-inline FeatLayout features_layout(const Geometry& g) {
+inline FeatLayout features_layout(const Geometry& g, int32_t dtype) {
     FeatLayout L;
     L.bpu = (g.tiles_per_unit + FEAT_TPB - 1) / FEAT_TPB;
     L.n_blocks = g.U * L.bpu;
     L.mparts = g.tiles_per_unit * FEAT_QUARTERS;
     size_t pos = 0;
     L.moments = pos; pos = round_up(pos + (size_t)g.n_tiles * FEAT_QUARTERS * 4 * sizeof(double), 256);
-    L.above = pos;   pos = round_up(pos + (size_t)L.n_blocks * sizeof(uint32_t), 256);
-    L.hist = pos;    pos = round_up(pos + (size_t)3 * g.U * FEAT_BINS * sizeof(uint32_t), 256);
+    L.above = L.fine = L.anchor = L.list_count = L.list = 0;
+    if (dtype == WINDQ_BF16) {
+        L.hist = pos;       pos = round_up(pos + (size_t)g.U * FEAT_BINS * sizeof(uint32_t), 256);
+        L.list_count = pos; pos += 256;
+        L.list = pos;       pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+        L.anchor = pos;     pos = round_up(pos + (size_t)g.n_tiles * sizeof(uint32_t), 256);
+        L.fine = pos;       pos = round_up(pos + (size_t)g.n_tiles * FEAT_WIN * 8 * sizeof(uint32_t), 256);
+    } else {
+        L.above = pos;   pos = round_up(pos + (size_t)L.n_blocks * sizeof(uint32_t), 256);
+        L.hist = pos;    pos = round_up(pos + (size_t)3 * g.U * FEAT_BINS * sizeof(uint32_t), 256);
+    }
     L.total = pos;
     return L;
 }
-inline size_t features_ws_bytes(const Geometry& g, int32_t /*dtype*/) { return features_layout(g).total; }
+inline size_t features_ws_bytes(const Geometry& g, int32_t dtype) { return features_layout(g, dtype).total; }
 
 // ---- salient-weight protection (select and encode share one layout)
 //   hist      [3][U][FEAT_BINS] u32   histograms of the three saliency-key digits

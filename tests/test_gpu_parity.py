@@ -138,6 +138,66 @@ def test_features_exact_zeros_ties_and_tiny_values(windq):
     check_features(windq, W.to(torch.bfloat16), s, 64, 64)
 
 
+def features_listed_units(windq, W, G, unit_rows, ws):
+    return windq.windq_unit_features_exact_units(ws, W, G, unit_rows)
+
+
+def test_features_bf16_units_outside_the_tile_records(windq):
+    """bf16 units whose P99 the per-tile records do not decide take the exact pass; their neighbours do not.
+    Chunks of a [256 x 1024] matrix, G = 128, one unit per chunk:
+      0 ordinary  1 all zero  2 99.5 % of the weights below 2^-21  3 one tile 2^-7 times the rest, with one large weight (the unit's P99 outside that tile's record)
+      4 2 % of the weights at 16 and above  5 P99 near 2^-21 (0.5 P99 below the resolved range)
+      6 bulk near 2^-17 (inside it)  7 ordinary with many exact zeros"""
+    gen = torch.Generator().manual_seed(5)
+    R, C, G = 256, 1024, 128
+    W = (torch.randn(R, C, generator=gen) * 0.02)
+    W[:, 128:256] = 0
+    tiny = torch.randn(R, 128, generator=gen) * 1e-7
+    tiny.view(-1)[torch.randperm(R * 128, generator=gen)[:160]] = 0.3
+    W[:, 256:384] = tiny
+    W[:, 384:512] = torch.randn(R, 128, generator=gen) * 1e-3
+    W[192:, 384:512] *= 2.0 ** -7        # the unit's P99 lies above this tile's record, and ...
+    W[200, 400] = 0.02                   # ... below its largest weight
+    big = torch.randn(R, 128, generator=gen) * 0.5
+    big.view(-1)[torch.randperm(R * 128, generator=gen)[:700]] = 20.0
+    W[:, 512:640] = big
+    W[:, 640:768] = torch.randn(R, 128, generator=gen) * 2e-7
+    W[:, 768:896] = torch.randn(R, 128, generator=gen) * 3e-6
+    z = torch.randn(R, 128, generator=gen) * 0.05
+    z[torch.rand(R, 128, generator=gen) < 0.6] = 0
+    W[:, 896:] = z
+    W = W.to(torch.bfloat16).to(DEV)
+    s = torch.rand(C, device=DEV) + 0.1
+    for unit_rows, listed in ((0, {1, 2, 3, 4, 5}), (64, None)):
+        U, _ = windq.n_units(R, C, G, unit_rows)
+        ws = torch.zeros(windq.workspace_bytes(windq.CALL_UNIT_FEATURES, windq.WINDQ_BF16, R, C, G, unit_rows, 1),
+                         dtype=torch.uint8, device=DEV)
+        feat = windq.windq_unit_features(W, s, G, unit_rows, ws=ws)
+        torch.cuda.synchronize()
+        want = O.unit_features(to_np(W), to_np(s), G, unit_rows)
+        got = to_np(feat).astype(np.float64)
+        n = (R if unit_rows == 0 else unit_rows) * G
+        assert np.array_equal(np.rint(got[:, 3] * n), np.rint(want[:, 3] * n)), "sparsity count"
+        assert np.array_equal(np.rint(got[:, 4] * n), np.rint(want[:, 4] * n)), "outlier count"
+        assert_close(got[:, 1:3], want[:, 1:3], what="std/absmean")
+        n_listed = features_listed_units(windq, W, G, unit_rows, ws)
+        if listed is not None:
+            assert n_listed == len(listed), n_listed
+        else:
+            assert 0 < n_listed < U           # with 64-row units every tile is a unit: chunk 3 needs no exact pass
+
+
+def test_features_bf16_ordinary_units_need_no_exact_pass(windq):
+    W = synth.weights_llm(1024, 1024, seed=12, device=DEV)
+    s = torch.rand(1024, device=DEV) + 0.1
+    ws = torch.zeros(windq.workspace_bytes(windq.CALL_UNIT_FEATURES, windq.WINDQ_BF16, 1024, 1024, 128, 0, 1),
+                     dtype=torch.uint8, device=DEV)
+    windq.windq_unit_features(W, s, 128, 0, ws=ws)
+    torch.cuda.synchronize()
+    assert features_listed_units(windq, W, 128, 0, ws) == 0
+    check_features(windq, W, s, 128, 0)
+
+
 # ------------------------------------------------------------------- fit + score
 def test_fit_score_small_config(windq):
     """512x512 fp32, 4 outlier columns, calibration scales from X, G = 64, 20 clip points."""

@@ -402,11 +402,17 @@ __device__ __forceinline__ double rows_sum(const float (&v)[N], float* __restric
 // One tile in one of the FS_* modes.  FS_ONLY8 leaves every other partial of the tile as it is.
 // The feature modes add, in the scan that finds the groups' min / max / sum |w| anyway: per
 // wavefront (column quarter) the sums of w and w^2 (fp32 per lane over <= 128 weights, products
-// of bf16 are exact; fp64 beyond), the count of |w| < 1e-6, and the tile's histogram of the
-// first radix digit of |w| (bits 20-30 of the fp32 pattern: exponent + 3 mantissa bits, for
-// bf16 the first 11 of its 15 magnitude bits) in LDS -- 2048 bins of 16 bits, two to a dword,
-// in the space the row-combining scratch uses later -- which is then added to the unit's
-// histogram in global memory (integer atomics: order does not matter).
+// of bf16 are exact; fp64 beyond), the count of |w| < 1e-6, and a histogram of |w| in LDS, in
+// the space the row-combining scratch uses later.
+//   fp32 inputs: the first radix digit of |w| (bits 20-30 of the pattern: exponent + 3 mantissa
+//   bits), 2048 bins of 16 bits, two to a dword; added to the unit's histogram in global memory
+//   (integer atomics: order does not matter).
+//   bf16 inputs: all 15 magnitude bits, key by key, over 198 first-digit bins (2^-21 <= |w| <
+//   13.5; what lies beyond is lumped into one bin at either end): 3200 counters of 16 bits.
+//   The first-digit sums go to the unit's histogram as above; the counters of the 64
+//   first-digit bins from 3 octaves below to 5 above the tile's mean |w| are written out as the
+//   tile's record, with the bin of the tile's largest key, so that the unit's P99 can be
+//   refined to the last bit without reading W again; the count of |w| < 1e-6 is a sum of counters.
 // MASKED: salient weights (Sec. 3.5) marked in A.mask take no part: they are left out of
 // the group statistics, and in every error sum their activation scale counts as zero.
 // rot spreads an uneven number of clip passes over the four SIMDs from tile to tile.

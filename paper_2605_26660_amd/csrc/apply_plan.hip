@@ -139,7 +139,9 @@ constexpr int APS_WAVE_ROWS = 16;
 
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+    // (every lane has a source lane under the controls used here; bound_ctrl only tells the
+    // compiler that the destination needs no initial value)
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, true);
 }
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float x) {
@@ -174,6 +176,33 @@ WINDQ_ROW_REDUCE(row_max_u32, uint32_t, dpp_u32, (x > y ? x : y))
 WINDQ_ROW_REDUCE(row_sum_f64, double, dpp_f64, x + y)
 WINDQ_ROW_REDUCE(row_sum_u32, uint32_t, dpp_u32, x + y)
 #undef WINDQ_ROW_REDUCE
+
+constexpr int DPP_ROR4 = 0x124;         // lane i <- lane (i + 4) mod 16 of its row of 16
+constexpr int DPP_ROR8 = 0x128;
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_any(uint32_t x) { return dpp_u32<CTRL>(x); }
+template <int CTRL> __device__ __forceinline__ float dpp_any(float x) { return dpp_f32<CTRL>(x); }
+template <int CTRL> __device__ __forceinline__ double dpp_any(double x) { return dpp_f64<CTRL>(x); }
+
+// Sixteen lanes share a row and hold four values each (one per iteration): reduces value k over
+// the sixteen lanes and leaves the result in the lanes with (piece & 3) == k, the ones that
+// derive the parameters of iteration k.  Lanes trade the values they do not keep (two, then one)
+// inside their quad, then the four quads combine by rotation: 5 combining steps per lane where
+// four all-reduces take 16.  The order of combination differs from a butterfly's; it is used
+// only for exact sums and for min / max.
+template <typename T, typename Op>
+__device__ __forceinline__ T row_scatter_reduce16(const T (&v)[4], int piece, Op op) {
+    const bool b0 = (piece & 1) != 0, b1 = (piece & 2) != 0;
+    T keep_a = b0 ? v[1] : v[0], send_a = b0 ? v[0] : v[1];
+    T keep_b = b0 ? v[3] : v[2], send_b = b0 ? v[2] : v[3];
+    keep_a = op(keep_a, dpp_any<DPP_XOR1>(send_a));
+    keep_b = op(keep_b, dpp_any<DPP_XOR1>(send_b));
+    T keep = b1 ? keep_b : keep_a;
+    const T send = b1 ? keep_a : keep_b;
+    keep = op(keep, dpp_any<DPP_XOR2>(send));
+    keep = op(keep, dpp_any<DPP_ROR8>(keep));
+    keep = op(keep, dpp_any<DPP_ROR4>(keep));
+    return keep;
+}
 
 // Value held by lane IT of the caller's quad.
 template <int IT>
@@ -219,6 +248,7 @@ __device__ __forceinline__ void split_uniform(const ApplyArgs& A, const TileCoor
     constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI;
     float w[8];
     float smn = 0.0f, smx = 0.0f;
+    float mns[NI], mxs[NI];
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
         unpack8(raw[it], w);
@@ -236,14 +266,24 @@ __device__ __forceinline__ void split_uniform(const ApplyArgs& A, const TileCoor
                 mx = fmaxf(mx, kept ? w[j] : -INFINITY);
             }
         }
-        mn = row_min_f32<LPR>(mn);
-        mx = row_max_f32<LPR>(mx);
-        if (MASKED && mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
-        if (it == 0 || L.sel == it) {
-            smn = mn;
-            smx = mx;
+        mns[it] = mn;
+        mxs[it] = mx;
+    }
+    if constexpr (NI == 4) {
+        smn = row_scatter_reduce16(mns, L.piece, [](float x, float y) { return fminf(x, y); });
+        smx = row_scatter_reduce16(mxs, L.piece, [](float x, float y) { return fmaxf(x, y); });
+    } else {
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            const float mn = row_min_f32<LPR>(mns[it]);
+            const float mx = row_max_f32<LPR>(mxs[it]);
+            if (it == 0 || L.sel == it) {
+                smn = mn;
+                smx = mx;
+            }
         }
     }
+    if (MASKED && smn > smx) smn = smx = 0.0f;      // no weight of the group is kept
     const float qmax = (float)((1 << BITS) - 1);
     const float lo = p * smn;
     const float hi = p * smx;
@@ -309,15 +349,15 @@ __device__ __forceinline__ void split_uniform(const ApplyArgs& A, const TileCoor
     }
 }
 
-// Mean |w| over the kept weights of each row of every iteration, as stored (fp64 sum divided
-// by the number kept, rounded to fp32; 0 when none is kept); the return value is that of the
-// row this lane derives parameters for (iteration L.sel).
+// Mean |w| over the kept weights of the row this lane derives parameters for (iteration
+// L.sel), as stored: the fp64 sum divided by the number kept, rounded to fp32; 0 when none is kept.
 template <int LPR, bool MASKED>
 __device__ __forceinline__ float split_abs_mean(const ApplyArgs& A, const TileCoord& tc, const SplitLane<LPR>& L,
                                                 const uint4 (&raw)[SplitLane<LPR>::NI],
                                                 const uint32_t (&prot)[SplitLane<LPR>::NI]) {
     constexpr int NI = SplitLane<LPR>::NI, RPI = SplitLane<LPR>::RPI, G = 8 * LPR;
-    float smean = 0.0f;
+    double sums[NI];
+    uint32_t kmaxs[NI], kmins[NI], kepts[NI];
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
         float w[8];
@@ -325,40 +365,59 @@ __device__ __forceinline__ float split_abs_mean(const ApplyArgs& A, const TileCo
         double S1 = 0.0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) S1 += MASKED && ((prot[it] >> j) & 1u) != 0u ? 0.0 : (double)fabsf(w[j]);
-        S1 = row_sum_f64<LPR>(S1);
-        uint32_t n_kept = G;
-        if (MASKED) n_kept = row_sum_u32<LPR>(8u - (uint32_t)__builtin_popcount(prot[it]));
-        // largest and smallest non-zero magnitude keys of the row (zero maps to 0xffff in the minimum)
-        uint32_t kmax = 0u, kmin = 0xffffu;
+        sums[it] = S1;
+        kepts[it] = 8u - (uint32_t)__builtin_popcount(prot[it]);
+        // largest magnitude key, and smallest non-zero one less 1 (a zero wraps to 2^32 - 1)
+        uint32_t kmax = 0u, kmin = 0xffffffffu;
         const uint32_t dws[4] = {raw[it].x, raw[it].y, raw[it].z, raw[it].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t h = (dws[i] >> 16) & 0x7fffu, l = dws[i] & 0x7fffu;
             kmax = max(kmax, max(h, l));
-            kmin = min(kmin, min((h - 1u) & 0xffffu, (l - 1u) & 0xffffu));
+            kmin = min(kmin, min(h - 1u, l - 1u));
         }
-        kmax = row_max_u32<LPR>(kmax);
-        kmin = row_min_u32<LPR>(kmin);
-        const int emax = (int)(kmax >> 7);
-        const int emin = max((int)(((kmin + 1u) & 0xffffu) >> 7), 1);
-        if (kmax != 0u && emax - emin > 36) {
-            // partial sums may round: take the sum in column order instead
-            const int r = L.row0 + it * RPI;
-            S1 = 0.0;
-            if (r < tc.nrows) {
-                const uint16_t* __restrict__ wrow =
-                    static_cast<const uint16_t*>(A.W) + (tc.row0 + r) * A.g.ld + tc.col0;
-                const uint8_t* __restrict__ mrow = MASKED ? A.mask + (tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) : nullptr;
-                for (int c = 0; c < G; ++c) {
-                    const bool kept = !MASKED || ((mrow[c >> 3] >> (c & 7)) & 1u) == 0u;
-                    S1 += kept ? (double)fabsf(bf16_bits_to_f32(wrow[c])) : 0.0;
-                }
+        kmaxs[it] = kmax;
+        kmins[it] = kmin;
+    }
+    // the row of iteration L.sel: its sum, its kept count, its largest and smallest keys
+    double S1 = 0.0;
+    uint32_t n_kept = G, kmax = 0u, kmin = 0xffffffffu;
+    if constexpr (NI == 4) {
+        S1 = row_scatter_reduce16(sums, L.piece, [](double x, double y) { return x + y; });
+        kmax = row_scatter_reduce16(kmaxs, L.piece, [](uint32_t x, uint32_t y) { return x > y ? x : y; });
+        kmin = row_scatter_reduce16(kmins, L.piece, [](uint32_t x, uint32_t y) { return x < y ? x : y; });
+        if (MASKED) n_kept = row_scatter_reduce16(kepts, L.piece, [](uint32_t x, uint32_t y) { return x + y; });
+    } else {
+#pragma unroll
+        for (int it = 0; it < NI; ++it) {
+            const double s = row_sum_f64<LPR>(sums[it]);
+            const uint32_t kx = row_max_u32<LPR>(kmaxs[it]), kn = row_min_u32<LPR>(kmins[it]);
+            const uint32_t nk = MASKED ? row_sum_u32<LPR>(kepts[it]) : (uint32_t)G;
+            if (it == 0 || L.sel == it) {
+                S1 = s;
+                kmax = kx;
+                kmin = kn;
+                n_kept = nk;
             }
         }
-        const float mean = n_kept > 0u ? (float)(S1 / (double)n_kept) : 0.0f;
-        if (it == 0 || L.sel == it) smean = mean;
     }
-    return smean;
+    const int emax = (int)(kmax >> 7);
+    const int emin = max((int)((kmin + 1u) >> 7), 1);      // (an all-zero row: kmin + 1 wraps to 0, and kmax is 0)
+    if (kmax != 0u && emax - emin > 36) {
+        // partial sums may round: take the sum in column order instead
+        const int r = L.row0 + L.sel * RPI;
+        S1 = 0.0;
+        if (r < tc.nrows) {
+            const uint16_t* __restrict__ wrow =
+                static_cast<const uint16_t*>(A.W) + (tc.row0 + r) * A.g.ld + tc.col0;
+            const uint8_t* __restrict__ mrow = MASKED ? A.mask + (tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) : nullptr;
+            for (int c = 0; c < G; ++c) {
+                const bool kept = !MASKED || ((mrow[c >> 3] >> (c & 7)) & 1u) == 0u;
+                S1 += kept ? (double)fabsf(bf16_bits_to_f32(wrow[c])) : 0.0;
+            }
+        }
+    }
+    return n_kept > 0u ? (float)(S1 / (double)n_kept) : 0.0f;
 }
 
 template <int LPR, bool MASKED>

@@ -393,9 +393,11 @@ def main():
         }
         # units of the last block whose P99 needed the exact pass over their weights (the workspaces are
         # shared by the blocks and hold the last one's counters)
-        last = stack.blocks[-1].mats
-        r["features_exact_units_last_block"] = sum(
-            wq.windq_unit_features_exact_units(stack.ws[i], m.W, G, stack.unit_rows) for i, m in enumerate(last))
+        # (fused call only: as separate calls, fit+score reuses the workspace after the features)
+        if fused:
+            last = stack.blocks[-1].mats
+            r["features_exact_units_last_block"] = sum(
+                wq.windq_unit_features_exact_units(stack.ws[i], m.W, G, stack.unit_rows) for i, m in enumerate(last))
         if len(stack.blocks) > 1 and not args.per_matrix:
             r["one_block"] = one_block(torch, stack, max(args.steps, 20), 10, fused)
         if args.protect_ppm > 0 and G == widths[-1]:

@@ -4,19 +4,24 @@
 //
 // windq_salient_select  finds the protected set EXACTLY: the saliency threshold T of a
 //   unit is the n_p-th largest key, located by most-significant-digit radix selection on
-//   the bit pattern of the fp32 saliency (digits of 11 + 11 + 9 bits, one pass over W per
-//   digit, LDS histograms flushed by integer atomics); weights above T are protected,
-//   and of those equal to T the first (n_p - #above) in flat-index order inside the unit
-//   (only where a unit's ties are split between kept and protected: counted per tile,
-//   prefix over the unit's tiles, then rank inside the tile row by row).  The result is a
-//   bit mask in the layout of W: one byte per 8 columns.
+//   the bit pattern of the fp32 saliency (digits of 11 + 11 + 9 bits).  The first digit
+//   takes one histogram pass over W (LDS histograms flushed by integer atomics).  Its bin
+//   e0 holds well under 1 % of a unit's keys, so a second pass over W writes every mask bit
+//   that e0 decides and lists the keys of that bin with their positions; the remaining
+//   digits, the ties (weights equal to T are taken in the order of their flat index inside
+//   the unit: the first n_p - #above of them) and the listed weights' mask bits are then
+//   settled per unit from the list alone.  Units whose bin outgrows the list (a thirty-
+//   second of the unit: constant weights, say) take the remaining digits by histogram
+//   passes over W instead, count their ties per tile where they are split between kept and
+//   protected, and rank them in a last pass.  The result is a bit mask in the layout of W:
+//   one byte per 8 columns.
 // windq_salient_encode  stores the protected weights: per unit one symmetric scale
 //   sigma = fp32(max|w_p| / 127), codes clamp(rne(w * fp32(1/sigma)), -127, 127) in
 //   flat-index order, and the activation-weighted error of that INT8 part.
-// Everything is integer or fixed-order fp64: bit-reproducible.  Select streams W four times
-// (three digits, the mask) and a fifth time only for the tiles of units whose ties are split;
+// Everything is integer or fixed-order fp64: bit-reproducible.  Select streams W twice (the
+// units that fall back: four times, and a fifth for the tiles of those whose ties are split);
 // encode reads the mask twice and of W only the protected elements.  Every kernel takes a
-// batch of matrices, so a decoder block costs ten launches for select and four for encode.
+// batch of matrices, so a decoder block costs twelve launches for select and four for encode.
 // None of this is on the per-step hot path (the mask of a matrix is computed once per
 // protection rate).
 #include <float.h>
@@ -41,6 +46,13 @@ struct SalArgs {
     uint32_t* cnt;          // [n_tiles][2]  keys above T, keys equal to T
     uint32_t* eq_before;    // [n_tiles]     ties in earlier tiles of the unit
     uint32_t* need;         // [U]  ties to protect
+    uint32_t* flag;         // [U]  1: selected by digit passes over W; 0: from the unit's candidate list
+    uint32_t* n_flagged;    // how many units are flagged, and ...
+    uint32_t* flagged;      // [U]  ... which, in no particular order
+    uint32_t* cand_count;   // [U]  candidates listed
+    uint2* cand;            // [U][cap]  (key, flat position in the unit) of the keys in the threshold's first-digit bin
+    uint32_t cap;
+    uint32_t use_list;      // 0: every unit takes the digit passes (mask not addressable in whole dwords)
     uint32_t n_p;           // protected weights per unit
     uint32_t rank0;         // ascending rank of T: n - n_p + 1
     // encode
@@ -85,6 +97,40 @@ __device__ __forceinline__ void load8g(const void* __restrict__ data, int64_t of
     }
 }
 
+// The same eight weights in two steps: the raw bytes (4 or 8 registers), then the values.
+template <int DT>
+struct Raw8 {
+    uint4 a, b;
+};
+template <>
+struct Raw8<WINDQ_BF16> {
+    uint4 a;
+};
+template <int DT>
+__device__ __forceinline__ Raw8<DT> load8raw(const void* __restrict__ data, int64_t off) {
+    Raw8<DT> r;
+    if constexpr (DT == WINDQ_BF16) {
+        r.a = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(data) + off);
+    } else {
+        const uint4* src = reinterpret_cast<const uint4*>(static_cast<const float*>(data) + off);
+        r.a = src[0];
+        r.b = src[1];
+    }
+    return r;
+}
+template <int DT>
+__device__ __forceinline__ void unpack8raw(const Raw8<DT>& r, float (&w)[8]) {
+    if constexpr (DT == WINDQ_BF16) {
+        w[0] = bf16_bits_to_f32(r.a.x & 0xffffu); w[1] = __uint_as_float(r.a.x & 0xffff0000u);
+        w[2] = bf16_bits_to_f32(r.a.y & 0xffffu); w[3] = __uint_as_float(r.a.y & 0xffff0000u);
+        w[4] = bf16_bits_to_f32(r.a.z & 0xffffu); w[5] = __uint_as_float(r.a.z & 0xffff0000u);
+        w[6] = bf16_bits_to_f32(r.a.w & 0xffffu); w[7] = __uint_as_float(r.a.w & 0xffff0000u);
+    } else {
+        w[0] = __uint_as_float(r.a.x); w[1] = __uint_as_float(r.a.y); w[2] = __uint_as_float(r.a.z); w[3] = __uint_as_float(r.a.w);
+        w[4] = __uint_as_float(r.b.x); w[5] = __uint_as_float(r.b.y); w[6] = __uint_as_float(r.b.z); w[7] = __uint_as_float(r.b.w);
+    }
+}
+
 // One element of W.
 template <int DT>
 __device__ __forceinline__ float load1g(const void* __restrict__ data, int64_t off) {
@@ -98,6 +144,7 @@ __global__ __launch_bounds__(256) void sal_clear_hist_kernel(const SalBatch B) {
     const SalArgs& A = B.m[mi];
     const int64_t i = ((int64_t)blockIdx.x - B.fill_start[mi]) * 256 + threadIdx.x;
     if (i < (int64_t)3 * A.g.U * FEAT_BINS) A.hist[i] = 0u;
+    if (i == 0) *A.n_flagged = 0u;
 }
 
 // Clears the mask of a matrix (rows x mask_ld bytes, dense).
@@ -120,12 +167,8 @@ __device__ __forceinline__ uint32_t block_sum_u32(uint32_t v, uint32_t* sh) {
 
 // Histogram of digit `level` of the keys of one tile that carry the unit's prefix.
 template <int DT>
-__global__ __launch_bounds__(SAL_THREADS) void sal_hist_kernel(const SalBatch B, const int level) {
-    __shared__ uint32_t lhist[FEAT_BINS];
-    __shared__ float scol[WINDQ_MAX_CHUNK];
-    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
-    const SalArgs& A = B.m[mi];
-    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
+__device__ __forceinline__ void sal_hist_tile(const SalArgs& A, const TileCoord& tc, const int level, uint32_t* lhist,
+                                              float* scol) {
     const int32_t G = A.g.chunk_w;
     const int32_t nbins = 1 << sal_bits(level);
     for (int32_t b = threadIdx.x; b < nbins; b += SAL_THREADS) lhist[b] = 0;
@@ -154,6 +197,16 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_hist_kernel(const SalBatch B,
     }
 }
 
+// The first digit: every tile of the launch.
+template <int DT>
+__global__ __launch_bounds__(SAL_THREADS) void sal_hist_kernel(const SalBatch B) {
+    __shared__ uint32_t lhist[FEAT_BINS];
+    __shared__ float scol[WINDQ_MAX_CHUNK];
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    sal_hist_tile<DT>(A, tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]), 0, lhist, scol);
+}
+
 // Per unit: the bin of digit `level` that holds the wanted rank; extends the prefix.  After the
 // last digit the prefix is the threshold T, every key of the bin equals T, and the rank left
 // over, r, says that the wanted key is the r-th of those e ties in ascending order: r - 1 of
@@ -164,6 +217,7 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_prefix_kernel(const SalBatch 
     const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
     const SalArgs& A = B.m[mi];
     const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
+    if (level > 0 && A.flag[u] == 0u) return;
     const uint32_t rank = level == 0 ? A.rank0 : A.rank[u];
     const uint32_t prefix = level == 0 ? 0u : A.prefix[u];
     const uint32_t* h = A.hist + ((size_t)level * (size_t)A.g.U + (size_t)u) * FEAT_BINS;
@@ -175,6 +229,13 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_prefix_kernel(const SalBatch 
         A.prefix[u] = (prefix << sal_bits(level)) | bin;
         A.rank[u] = left;
         if (level == 2) A.need[u] = h[bin] - left + 1u;
+        if (level == 0) {
+            // the keys of this bin decide the rest: few enough for the unit's list?
+            const bool listed = A.use_list != 0u && h[bin] <= A.cap;
+            A.flag[u] = listed ? 0u : 1u;
+            A.cand_count[u] = 0u;
+            if (!listed) A.flagged[atomicAdd(A.n_flagged, 1u)] = (uint32_t)u;
+        }
     }
 }
 
@@ -184,12 +245,7 @@ __device__ __forceinline__ bool ties_split(const SalArgs& A, int64_t u) { return
 
 // Per tile of a unit whose ties are split: how many keys equal the threshold.
 template <int DT>
-__global__ __launch_bounds__(SAL_THREADS) void sal_count_kernel(const SalBatch B) {
-    __shared__ float scol[WINDQ_MAX_CHUNK];
-    __shared__ uint32_t sh[SAL_THREADS / 64];
-    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
-    const SalArgs& A = B.m[mi];
-    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
+__device__ __forceinline__ void sal_count_tile(const SalArgs& A, const TileCoord& tc, float* scol, uint32_t* sh) {
     if (!ties_split(A, tc.u)) return;
     const int32_t G = A.g.chunk_w;
     for (int32_t c = threadIdx.x; c < G; c += SAL_THREADS) scol[c] = A.s[tc.col0 + c];
@@ -237,6 +293,7 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_scan_kernel(const SalBatch B)
     const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
     const SalArgs& A = B.m[mi];
     const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
+    if (A.flag[u] == 0u) return;
     const int64_t T = A.g.tiles_per_unit;
     const size_t base = (size_t)u * (size_t)T;
     const bool split = ties_split(A, u);
@@ -257,12 +314,7 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_scan_kernel(const SalBatch B)
 // order, is below `need`: ties in earlier tiles, plus a scan over the workgroup's threads, plus
 // the thread's own eight in order.  Elsewhere every tie is protected and nothing is ranked.
 template <int DT>
-__global__ __launch_bounds__(SAL_THREADS) void sal_mask_kernel(const SalBatch B) {
-    __shared__ float scol[WINDQ_MAX_CHUNK];
-    __shared__ uint32_t sh[SAL_THREADS / 64];
-    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
-    const SalArgs& A = B.m[mi];
-    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
+__device__ __forceinline__ void sal_mask_tile(const SalArgs& A, const TileCoord& tc, float* scol, uint32_t* sh) {
     const int32_t G = A.g.chunk_w;
     for (int32_t c = threadIdx.x; c < G; c += SAL_THREADS) scol[c] = A.s[tc.col0 + c];
     const uint32_t T = A.prefix[tc.u];
@@ -308,6 +360,197 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_mask_kernel(const SalBatch B)
             for (int j = 0; j < 8; ++j) byte |= (key[j] >= T ? 1u : 0u) << j;
         }
         if (valid) A.mask[(tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) + pc] = (uint8_t)byte;
+    }
+}
+
+// The later digits, the tie counts and the masks of the units that do not select from a list: a
+// fixed grid walks the tiles of the listed ("flagged") units of every matrix of the launch; with
+// none flagged it returns at once.
+constexpr int SAL_FLAGGED_GRID = 1024;
+constexpr int SAL_WHAT_HIST = 0, SAL_WHAT_COUNT = 1, SAL_WHAT_MASK = 2;
+template <int DT, int WHAT>
+__global__ __launch_bounds__(SAL_THREADS) void sal_flagged_kernel(const SalBatch B, const int level) {
+    __shared__ uint32_t lhist[WHAT == SAL_WHAT_HIST ? FEAT_BINS : 1];
+    __shared__ float scol[WINDQ_MAX_CHUNK];
+    __shared__ uint32_t sh[SAL_THREADS / 64];
+    for (int mi = 0; mi < B.n; ++mi) {
+        const SalArgs& A = B.m[mi];
+        const int64_t items = (int64_t)*A.n_flagged * A.g.tiles_per_unit;
+        for (int64_t it = blockIdx.x; it < items; it += gridDim.x) {
+            const int64_t f = it / A.g.tiles_per_unit;
+            const TileCoord tc = tile_coord_of_unit(A.g, (int64_t)A.flagged[f], it - f * A.g.tiles_per_unit);
+            __syncthreads();        // the previous tile's shared state is no longer read
+            if (WHAT == SAL_WHAT_HIST) sal_hist_tile<DT>(A, tc, level, lhist, scol);
+            else if (WHAT == SAL_WHAT_COUNT) sal_count_tile<DT>(A, tc, scol, sh);
+            else sal_mask_tile<DT>(A, tc, scol, sh);
+        }
+    }
+}
+
+// ------------------------------------------------- selection from the unit's candidate list
+// Units whose threshold bin (first digit e0) is small enough -- all but degenerate ones -- need no
+// further digit pass over W.  One pass writes the mask bits that e0 already decides (first digit
+// above e0: protected; below: not) and lists the keys whose first digit IS e0 with their flat
+// position; one workgroup per unit then finds the threshold, and the ties to take, in the list and
+// sets the remaining bits.  Two reads of W in all.
+constexpr int SAL_CAND_ITERS = 4;       // 16-byte pieces a thread holds at once
+template <int DT>
+__global__ __launch_bounds__(SAL_THREADS) void sal_cand_kernel(const SalBatch B) {
+    __shared__ float scol[WINDQ_MAX_CHUNK];
+    __shared__ uint32_t sh[SAL_THREADS / 64];
+    __shared__ uint32_t sh_base;
+    const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const TileCoord tc = tile_coord(A.g, (int64_t)blockIdx.x - B.tile_start[mi]);
+    if (A.flag[tc.u] != 0u) return;
+    const int32_t G = A.g.chunk_w;
+    for (int32_t c = threadIdx.x; c < G; c += SAL_THREADS) scol[c] = A.s[tc.col0 + c];
+    const uint32_t e0 = A.prefix[tc.u];
+    uint2* __restrict__ list = A.cand + (size_t)tc.u * (size_t)A.cap;
+    __syncthreads();
+    const int32_t pieces = G >> 3;
+    const int32_t total = tc.nrows * pieces;
+    for (int32_t i0 = 0; i0 < total; i0 += SAL_CAND_ITERS * SAL_THREADS) {
+        Raw8<DT> raw[SAL_CAND_ITERS];           // kept as loaded: the keys of a candidate piece are formed again
+        uint32_t cm[SAL_CAND_ITERS];            // which of a piece's eight keys are candidates
+        uint32_t n_mine = 0;
+#pragma unroll
+        for (int k = 0; k < SAL_CAND_ITERS; ++k) {
+            const int32_t i = i0 + k * SAL_THREADS + (int32_t)threadIdx.x;
+            if (i < total) {
+                const int32_t r = i / pieces, pc = i - r * pieces;
+                raw[k] = load8raw<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + pc * 8);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < SAL_CAND_ITERS; ++k) {
+            const int32_t i = i0 + k * SAL_THREADS + (int32_t)threadIdx.x;
+            cm[k] = 0u;
+            if (i < total) {
+                const int32_t r = i / pieces, pc = i - r * pieces;
+                float w[8];
+                unpack8raw<DT>(raw[k], w);
+                uint32_t byte = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t d0 = sal_key(w[j], scol[pc * 8 + j]) >> sal_shift(0);
+                    byte |= (d0 > e0 ? 1u : 0u) << j;
+                    cm[k] |= (d0 == e0 ? 1u : 0u) << j;
+                }
+                A.mask[(tc.row0 + r) * A.mask_ld + (tc.col0 >> 3) + pc] = (uint8_t)byte;
+                n_mine += (uint32_t)__builtin_popcount(cm[k]);
+            }
+        }
+        // one place in the unit's list for the workgroup's candidates, then each thread's share of it
+        // (one atomic per tile: four per tile, one a wavefront, took 2.5 times as long - the answers to
+        // atomics on one counter come back one after the other)
+        uint32_t tot;
+        uint32_t at = block_exclusive_scan_u32(n_mine, sh, &tot);
+        if (threadIdx.x == 0) sh_base = tot != 0u ? atomicAdd(&A.cand_count[tc.u], tot) : 0u;
+        __syncthreads();
+        at += sh_base;
+#pragma unroll
+        for (int k = 0; k < SAL_CAND_ITERS; ++k) {
+            if (cm[k] != 0u) {
+                const int32_t i = i0 + k * SAL_THREADS + (int32_t)threadIdx.x;
+                const int32_t r = i / pieces, pc = i - r * pieces;
+                const uint32_t pos0 = (uint32_t)(tc.lrow0 + r) * (uint32_t)G + (uint32_t)pc * 8u;
+                float w[8];
+                unpack8raw<DT>(raw[k], w);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if ((cm[k] >> j) & 1u) {
+                        if (at < A.cap) list[at] = make_uint2(sal_key(w[j], scol[pc * 8 + j]), pos0 + (uint32_t)j);
+                        ++at;
+                    }
+                }
+            }
+        }
+        __syncthreads();        // sh_base is read before the next round overwrites it
+    }
+}
+
+// Histogram of `bits` bits at `shift` of field x (0: key, 1: position) of the list's entries that
+// satisfy pred, then the bin of 1-based ascending rank `rank`; returns the bin, the count below it
+// and the bin's own count.  All SAL_THREADS threads call it.
+template <typename Pred>
+__device__ __forceinline__ void list_digit(const uint2* __restrict__ list, uint32_t n, int field, int shift, int bits,
+                                           uint32_t rank, Pred pred, uint32_t* lh, uint32_t* sh_part, uint32_t* sh_out,
+                                           uint32_t* bin, uint32_t* below, uint32_t* in_bin) {
+    const int32_t nbins = 1 << bits;
+    __syncthreads();
+    for (int32_t b = threadIdx.x; b < nbins; b += SAL_THREADS) lh[b] = 0u;
+    __syncthreads();
+    for (uint32_t i0 = threadIdx.x; i0 < n; i0 += 4 * SAL_THREADS) {       // four loads in flight per thread
+        uint2 e[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (i0 + k * SAL_THREADS < n) e[k] = list[i0 + k * SAL_THREADS];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (i0 + k * SAL_THREADS < n && pred(e[k]))
+                atomicAdd(&lh[((field == 0 ? e[k].x : e[k].y) >> shift) & (uint32_t)(nbins - 1)], 1u);
+    }
+    __syncthreads();
+    uint64_t bl;
+    select_bin<SAL_THREADS>(lh, nbins, rank, sh_part, sh_out, bin, &bl);
+    *below = (uint32_t)bl;
+    *in_bin = lh[*bin];
+}
+
+// Per unit: the threshold among the listed keys (their first digit is e0; digits of 11 and 9 bits
+// remain), the ties to take (by smallest flat position: three digits of the position), and the
+// mask bits of every listed weight that is protected.
+__global__ __launch_bounds__(SAL_THREADS) void sal_list_kernel(const SalBatch B) {
+    __shared__ uint32_t lh[FEAT_BINS];
+    __shared__ uint32_t sh_part[SAL_THREADS];
+    __shared__ uint32_t sh_out[4];
+    const int mi = batch_index(B.unit_start, B.n, blockIdx.x);
+    const SalArgs& A = B.m[mi];
+    const int64_t u = (int64_t)blockIdx.x - B.unit_start[mi];
+    if (A.flag[u] != 0u) return;
+    const uint2* __restrict__ list = A.cand + (size_t)u * (size_t)A.cap;
+    const uint32_t n = min(A.cand_count[u], A.cap);
+    uint32_t b1, b2, below, in_bin;
+    list_digit(list, n, 0, sal_shift(1), sal_bits(1), A.rank[u], [](const uint2&) { return true; }, lh, sh_part, sh_out,
+               &b1, &below, &in_bin);
+    const uint32_t r1 = A.rank[u] - below;
+    list_digit(list, n, 0, sal_shift(2), sal_bits(2), r1,
+               [=](const uint2& e) { return ((e.x >> sal_shift(1)) & ((1u << sal_bits(1)) - 1u)) == b1; }, lh, sh_part,
+               sh_out, &b2, &below, &in_bin);
+    const uint32_t T = (A.prefix[u] << (sal_bits(1) + sal_bits(2))) | (b1 << sal_bits(2)) | b2;
+    const uint32_t ties = in_bin;
+    const uint32_t need = ties - (r1 - below) + 1u;      // the rank left over counts the ties that stay unprotected, plus one
+    uint32_t pos_max = 0xffffffffu;                        // ties up to this position are protected
+    if (need < ties) {
+        // the need-th smallest position among the ties (positions are distinct): digits of 11, 11, 10 bits
+        uint32_t p1, p2, p3, bl;
+        list_digit(list, n, 1, 21, 11, need, [=](const uint2& e) { return e.x == T; }, lh, sh_part, sh_out, &p1, &bl, &in_bin);
+        const uint32_t n1 = need - bl;
+        list_digit(list, n, 1, 10, 11, n1, [=](const uint2& e) { return e.x == T && (e.y >> 21) == p1; }, lh, sh_part, sh_out,
+                   &p2, &bl, &in_bin);
+        const uint32_t n2 = n1 - bl;
+        list_digit(list, n, 1, 0, 10, n2, [=](const uint2& e) { return e.x == T && (e.y >> 10) == ((p1 << 11) | p2); }, lh,
+                   sh_part, sh_out, &p3, &bl, &in_bin);
+        pos_max = (p1 << 21) | (p2 << 10) | p3;
+    }
+    const int64_t rb = u / A.g.n_chunks;
+    const int64_t col0 = (u - rb * A.g.n_chunks) * A.g.chunk_w;
+    const uint32_t G = (uint32_t)A.g.chunk_w;
+    for (uint32_t i0 = threadIdx.x; i0 < n; i0 += 4 * SAL_THREADS) {
+        uint2 e[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (i0 + k * SAL_THREADS < n) e[k] = list[i0 + k * SAL_THREADS];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (i0 + k * SAL_THREADS < n && (e[k].x > T || (e[k].x == T && e[k].y <= pos_max))) {
+                const uint32_t r = e[k].y / G, c = e[k].y - r * G;
+                const int64_t byte = (rb * A.g.R_u + (int64_t)r) * A.mask_ld + ((col0 + (int64_t)c) >> 3);
+                atomicOr(reinterpret_cast<uint32_t*>(A.mask + (byte & ~(int64_t)3)),
+                         1u << (8u * (uint32_t)(byte & 3) + (c & 7u)));
+            }
+        }
     }
 }
 
@@ -491,6 +734,12 @@ static void carve(SalArgs& A, void* ws, const SalientLayout& L) {
     A.cnt = reinterpret_cast<uint32_t*>(base + L.cnt);
     A.eq_before = reinterpret_cast<uint32_t*>(base + L.eq_before);
     A.need = reinterpret_cast<uint32_t*>(base + L.need);
+    A.flag = reinterpret_cast<uint32_t*>(base + L.flag);
+    A.n_flagged = reinterpret_cast<uint32_t*>(base + L.n_flagged);
+    A.flagged = reinterpret_cast<uint32_t*>(base + L.flagged);
+    A.cand_count = reinterpret_cast<uint32_t*>(base + L.cand_count);
+    A.cand = reinterpret_cast<uint2*>(base + L.cand);
+    A.cap = L.cap;
     A.tile_max = reinterpret_cast<float*>(base + L.tile_max);
     A.row_off = reinterpret_cast<uint32_t*>(base + L.row_off);
     A.err_part = reinterpret_cast<double*>(base + L.err_part);
@@ -498,15 +747,21 @@ static void carve(SalArgs& A, void* ws, const SalientLayout& L) {
 
 template <int DT>
 static int launch_select(const SalBatch& B, hipStream_t hs) {
-    const dim3 tiles((unsigned)B.tile_start[B.n]), units((unsigned)B.unit_start[B.n]);
+    const dim3 tiles((unsigned)B.tile_start[B.n]), units((unsigned)B.unit_start[B.n]), some(SAL_FLAGGED_GRID);
     hipLaunchKernelGGL(sal_clear_hist_kernel, dim3((unsigned)B.fill_start[B.n]), dim3(256), 0, hs, B);
-    for (int level = 0; level < 3; ++level) {
-        hipLaunchKernelGGL(sal_hist_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B, level);
+    hipLaunchKernelGGL(sal_hist_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B);
+    hipLaunchKernelGGL(sal_prefix_kernel, units, dim3(SAL_THREADS), 0, hs, B, 0);
+    // units that select from their candidate list ...
+    hipLaunchKernelGGL(sal_cand_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B);
+    hipLaunchKernelGGL(sal_list_kernel, units, dim3(SAL_THREADS), 0, hs, B);
+    // ... and the others
+    for (int level = 1; level < 3; ++level) {
+        hipLaunchKernelGGL((sal_flagged_kernel<DT, SAL_WHAT_HIST>), some, dim3(SAL_THREADS), 0, hs, B, level);
         hipLaunchKernelGGL(sal_prefix_kernel, units, dim3(SAL_THREADS), 0, hs, B, level);
     }
-    hipLaunchKernelGGL(sal_count_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B);
+    hipLaunchKernelGGL((sal_flagged_kernel<DT, SAL_WHAT_COUNT>), some, dim3(SAL_THREADS), 0, hs, B, 0);
     hipLaunchKernelGGL(sal_scan_kernel, units, dim3(SAL_THREADS), 0, hs, B);
-    hipLaunchKernelGGL(sal_mask_kernel<DT>, tiles, dim3(SAL_THREADS), 0, hs, B);
+    hipLaunchKernelGGL((sal_flagged_kernel<DT, SAL_WHAT_MASK>), some, dim3(SAL_THREADS), 0, hs, B, 0);
     return hipPeekAtLastError() == hipSuccess ? WINDQ_OK : WINDQ_EHIP;
 }
 
@@ -550,6 +805,8 @@ static int salient_common(const windq_mat* W, const float* s, int32_t chunk_w, i
     const uint64_t n = (uint64_t)A->g.R_u * (uint64_t)chunk_w;
     A->n_p = (uint32_t)windq_n_protected((int64_t)n, rate_ppm);
     A->rank0 = (uint32_t)(n - A->n_p + 1);
+    // the list route sets mask bits with 32-bit atomics: the mask has to be addressable in whole dwords
+    A->use_list = aligned(mask, 4) && ((uint64_t)W->rows * (uint64_t)A->mask_ld) % 4 == 0 ? 1u : 0u;
     A->prot_codes = nullptr;
     A->prot_scale = nullptr;
     A->err_prot = nullptr;

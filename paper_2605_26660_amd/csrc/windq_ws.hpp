@@ -94,21 +94,40 @@ inline size_t features_ws_bytes(const Geometry& g, int32_t dtype) { return featu
 // ---- salient-weight protection (select and encode share one layout)
 //   hist      [3][U][FEAT_BINS] u32   histograms of the three saliency-key digits
 //   prefix, rank, need  [U] u32       selection state per unit
-//   cnt       [n_tiles] u32           keys equal to the threshold per tile (units with split ties)
+//   flag      [U] u32                 1: the unit's threshold bin holds more keys than its candidate list
+//   n_flagged u32, flagged [U] u32    those units
+//   cand_count [U] u32, cand [U][cap] (key, position) u32 pairs: the keys of the threshold's first-digit bin
+//   cnt       [n_tiles] u32           keys equal to the threshold per tile (flagged units with split ties)
 //   eq_before [n_tiles] u32           ties in earlier tiles of the unit
 //   tile_max  [n_tiles] f32           largest protected magnitude per tile
 //   row_off   [U * R_u] u32           protected weights in earlier rows of the unit
 //   err_part  [n_tiles] f64           INT8 error per tile
 struct SalientLayout {
-    size_t hist, prefix, rank, need, cnt, eq_before, tile_max, row_off, err_part, total;
+    size_t hist, prefix, rank, need, flag, n_flagged, flagged, cand_count, cand, cnt, eq_before, tile_max, row_off, err_part, total;
+    uint32_t cap;      // candidates a unit can list
 };
+// A thirty-second of the unit's weights, at least 256 (a first-digit bin is an eighth of an octave:
+// around the 97th-99.5th percentile of the saliencies it holds well under 1 % of a unit).
+inline uint32_t salient_cand_cap(const Geometry& g) {
+    const uint64_t n = (uint64_t)g.R_u * (uint64_t)g.chunk_w;
+    uint64_t c = n / 32;
+    if (c < 256) c = 256;
+    if (c > n) c = n;
+    return (uint32_t)c;
+}
 inline SalientLayout salient_layout(const Geometry& g) {
     SalientLayout L;
+    L.cap = salient_cand_cap(g);
     size_t pos = 0;
     L.hist = pos;      pos = round_up(pos + (size_t)3 * g.U * FEAT_BINS * sizeof(uint32_t), 256);
     L.prefix = pos;    pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
     L.rank = pos;      pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
     L.need = pos;      pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.flag = pos;      pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.n_flagged = pos; pos += 256;
+    L.flagged = pos;   pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.cand_count = pos; pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.cand = pos;      pos = round_up(pos + (size_t)g.U * (size_t)L.cap * 2 * sizeof(uint32_t), 256);
     L.cnt = pos;       pos = round_up(pos + (size_t)g.n_tiles * sizeof(uint32_t), 256);
     L.eq_before = pos; pos = round_up(pos + (size_t)g.n_tiles * sizeof(uint32_t), 256);
     L.tile_max = pos;  pos = round_up(pos + (size_t)g.n_tiles * sizeof(float), 256);

@@ -70,6 +70,27 @@ def test_ties_are_taken_in_flat_index_order(windq):
         check_encode(windq, Wc, s[:128], 64, 96, ppm, mask, keep)
 
 
+def test_select_routes_agree(windq):
+    """Selection from the units' candidate lists (the usual route) and by digit passes over W (taken when the
+    mask cannot be addressed in whole dwords, or a unit's threshold bin outgrows its list) give the same mask."""
+    W = synth.weights_llm(256, 512, seed=75, device=DEV)
+    X = synth.activations_llm(64, 512, seed=76, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    for G, unit_rows, ppm in ((128, 0, 30000), (64, 64, 5000), (128, 128, 300000)):
+        mask, keep = check_select(windq, W, s, G, unit_rows, ppm)
+        buf = torch.zeros(256 * 64 + 8, dtype=torch.uint8, device=DEV)
+        odd = buf[1:1 + 256 * 64].view(256, 64)                  # one byte off a dword boundary
+        assert odd.data_ptr() % 4 != 0
+        windq.windq_salient_select(W, s, G, unit_rows, ppm, out=odd)
+        torch.cuda.synchronize()
+        assert torch.equal(odd, mask)
+    # a mask whose size is no multiple of four bytes
+    W2 = synth.weights_llm(70, 24, seed=77, device=DEV)
+    s2 = torch.rand(24, device=DEV) + 0.1
+    check_select(windq, W2, s2, 8, 0, 100000)
+    check_select(windq, W2, s2, 24, 35, 30000)
+
+
 def test_all_zero_unit_has_zero_scale(windq):
     W = synth.weights_llm(128, 256, seed=74, device=DEV)
     W[:, :128] = 0

@@ -131,6 +131,20 @@ __device__ __forceinline__ void unpack8raw(const Raw8<DT>& r, float (&w)[8]) {
     }
 }
 
+// Weight j (0..7, a run-time index) of the eight.
+template <int DT>
+__device__ __forceinline__ float raw_elem(const Raw8<DT>& r, int j) {
+    if constexpr (DT == WINDQ_BF16) {
+        const int d = j >> 1;
+        const uint32_t dw = d == 0 ? r.a.x : (d == 1 ? r.a.y : (d == 2 ? r.a.z : r.a.w));
+        return __uint_as_float((j & 1) != 0 ? dw & 0xffff0000u : dw << 16);
+    } else {
+        const int d = j & 3;
+        const uint4& q = j < 4 ? r.a : r.b;
+        return __uint_as_float(d == 0 ? q.x : (d == 1 ? q.y : (d == 2 ? q.z : q.w)));
+    }
+}
+
 // One element of W.
 template <int DT>
 __device__ __forceinline__ float load1g(const void* __restrict__ data, int64_t off) {
@@ -455,14 +469,10 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_cand_kernel(const SalBatch B)
                 const int32_t i = i0 + k * SAL_THREADS + (int32_t)threadIdx.x;
                 const int32_t r = i / pieces, pc = i - r * pieces;
                 const uint32_t pos0 = (uint32_t)(tc.lrow0 + r) * (uint32_t)G + (uint32_t)pc * 8u;
-                float w[8];
-                unpack8raw<DT>(raw[k], w);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if ((cm[k] >> j) & 1u) {
-                        if (at < A.cap) list[at] = make_uint2(sal_key(w[j], scol[pc * 8 + j]), pos0 + (uint32_t)j);
-                        ++at;
-                    }
+                for (uint32_t m = cm[k]; m != 0u; m &= m - 1u) {        // usually one bit
+                    const int j = __ffs(m) - 1;
+                    if (at < A.cap) list[at] = make_uint2(sal_key(raw_elem<DT>(raw[k], j), scol[pc * 8 + j]), pos0 + (uint32_t)j);
+                    ++at;
                 }
             }
         }
@@ -556,8 +566,50 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_list_kernel(const SalBatch B)
 
 // ---------------------------------------------------------------------------- encode
 // The encode kernels stage only the tile's mask bytes (a sixteenth of the weights' bytes at
-// bf16) and fetch the few protected weights straight from HBM, one element at a time.
-// LDS: [mask tile][s_c of the chunk].
+// bf16) and fetch the few protected weights straight from HBM, one element at a time but
+// SAL_GATHER of them in flight per lane: a lane first notes the columns of its next protected
+// weights (in LDS: a register array indexed by a running count would live in scratch memory),
+// then requests them together, then works through them in column order.
+// LDS: [mask tile][s_c of the chunk][SAL_GATHER x 64 column slots].
+constexpr int SAL_GATHER = 8;
+static size_t sal_gather_lds(int32_t chunk_w);
+
+// Calls f(column, weight) for the protected weights of the lane's row, in column order.
+template <int DT, typename F>
+__device__ __forceinline__ void for_protected(const void* __restrict__ W, int64_t woff, const uint8_t* __restrict__ mrow,
+                                              int32_t G, uint16_t* __restrict__ slots, F f) {
+    int32_t c = 0;          // first column of the next mask byte
+    uint32_t m = 0;         // bits of the current byte still to take (it covers columns c - 8 .. c - 1)
+    for (;;) {
+        int n = 0;
+        while (n < SAL_GATHER) {
+            if (m == 0u) {
+                if (c >= G) break;
+                m = mrow[c >> 3];
+                c += 8;
+                continue;
+            }
+            const int j = __ffs(m) - 1;
+            m &= m - 1u;
+            slots[n * 64] = (uint16_t)(c - 8 + j);
+            ++n;
+        }
+        if (n == 0) break;
+        float w[SAL_GATHER];
+        uint32_t col[SAL_GATHER];
+#pragma unroll
+        for (int k = 0; k < SAL_GATHER; ++k) {
+            if (k < n) {
+                col[k] = slots[k * 64];
+                w[k] = load1g<DT>(W, woff + col[k]);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < SAL_GATHER; ++k)
+            if (k < n) f((int32_t)col[k], w[k]);
+        if (n < SAL_GATHER) break;       // the row is exhausted
+    }
+}
 
 // Per tile, one lane per row: protected weights in the row, largest protected magnitude.
 template <int DT>
@@ -569,6 +621,7 @@ __global__ __launch_bounds__(64) void sal_rows_kernel(const SalBatch B) {
     const int32_t G = A.g.chunk_w;
     const int lane = threadIdx.x;
     uint8_t* mtile = reinterpret_cast<uint8_t*>(smem);
+    uint16_t* slots = reinterpret_cast<uint16_t*>(smem + TILE_ROWS * mask_row_stride(G) + G * sizeof(float)) + lane;
     load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     __syncthreads();
     const bool valid = lane < tc.nrows;
@@ -577,15 +630,10 @@ __global__ __launch_bounds__(64) void sal_rows_kernel(const SalBatch B) {
     if (valid) {
         const int64_t woff = (tc.row0 + lane) * A.g.ld + tc.col0;
         const uint8_t* mrow = mtile + lane * mask_row_stride(G);
-        for (int32_t c = 0; c < G; c += 8) {
-            uint32_t m = mrow[c >> 3];
-            n += __popc(m);
-            while (m != 0) {
-                const int j = __ffs(m) - 1;
-                m &= m - 1;
-                mx = fmaxf(mx, fabsf(load1g<DT>(A.W, woff + c + j)));
-            }
-        }
+        for_protected<DT>(A.W, woff, mrow, G, slots, [&](int32_t, float w) {
+            ++n;
+            mx = fmaxf(mx, fabsf(w));
+        });
         A.row_off[tc.u * A.g.R_u + tc.lrow0 + lane] = n;
     }
 #pragma unroll
@@ -643,6 +691,7 @@ __global__ __launch_bounds__(64) void sal_encode_kernel(const SalBatch B) {
     const int lane = threadIdx.x;
     uint8_t* mtile = reinterpret_cast<uint8_t*>(smem);
     float* scol = reinterpret_cast<float*>(smem + TILE_ROWS * mask_row_stride(G));
+    uint16_t* slots = reinterpret_cast<uint16_t*>(scol + G) + lane;
     load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     for (int32_t c = lane; c < G; c += 64) scol[c] = A.s[tc.col0 + c];
     __syncthreads();
@@ -654,21 +703,15 @@ __global__ __launch_bounds__(64) void sal_encode_kernel(const SalBatch B) {
         const uint8_t* mrow = mtile + lane * mask_row_stride(G);
         uint32_t pos = A.row_off[tc.u * A.g.R_u + tc.lrow0 + lane];
         int8_t* __restrict__ dst = A.prot_codes + (size_t)tc.u * (size_t)A.n_p;
-        for (int32_t c = 0; c < G; c += 8) {
-            uint32_t m = mrow[c >> 3];
-            while (m != 0) {
-                const int j = __ffs(m) - 1;
-                m &= m - 1;
-                const float w = load1g<DT>(A.W, woff + c + j);
-                const float t = w * inv;
-                const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -127.0f, 127.0f);
-                if (pos < A.n_p) dst[pos] = (int8_t)(int32_t)q;     // a mask with more bits than n_p writes nothing past the unit
-                ++pos;
-                const double d = (double)w - (double)q * (double)sg;
-                const double a = (double)scol[c + j] * (double)scol[c + j];
-                err = fma(a * d, d, err);
-            }
-        }
+        for_protected<DT>(A.W, woff, mrow, G, slots, [&](int32_t c, float w) {
+            const float t = w * inv;
+            const float q = __builtin_amdgcn_fmed3f(__builtin_rintf(t), -127.0f, 127.0f);
+            if (pos < A.n_p) dst[pos] = (int8_t)(int32_t)q;     // a mask with more bits than n_p writes nothing past the unit
+            ++pos;
+            const double d = (double)w - (double)q * (double)sg;
+            const double a = (double)scol[c] * (double)scol[c];
+            err = fma(a * d, d, err);
+        });
     }
     err = wave_sum(err);
     if (lane == 0) A.err_part[(size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t] = err;
@@ -723,8 +766,10 @@ __global__ __launch_bounds__(256) void unit_saliency_finalize_kernel(const doubl
     if (threadIdx.x == 0) sal[u] = (float)(t / ((double)g.R_u * (double)g.chunk_w));
 }
 
-// encode's kernels: the tile's mask bytes, s_c of the chunk
-static size_t sal_gather_lds(int32_t chunk_w) { return mask_tile_lds_bytes(chunk_w) + (size_t)chunk_w * sizeof(float); }
+// encode's kernels: the tile's mask bytes, s_c of the chunk, the lanes' column slots
+static size_t sal_gather_lds(int32_t chunk_w) {
+    return mask_tile_lds_bytes(chunk_w) + (size_t)chunk_w * sizeof(float) + (size_t)SAL_GATHER * 64 * sizeof(uint16_t);
+}
 
 static void carve(SalArgs& A, void* ws, const SalientLayout& L) {
     char* base = static_cast<char*>(ws);

@@ -129,7 +129,7 @@ def per_call_pass(torch, stack, steps, per_matrix, fused=True):
 def roofline(stack, fit_ms, steps, per_matrix, fused=True):
     """The main fit+score kernel against the fp32 vector peak: algorithmic flops of one launch / its duration
     between a pair of HIP events that the library records around that kernel alone (windq_kernel_timer), over
-    the timed region.  With the fused call the kernel also makes the first pass of the unit features; its flops
+    the timed region.  With the fused call the kernel also makes the unit features' pass over W; its flops
     (2 per weight for the sums of w and w^2) are not counted."""
     kernel_ms, total_launches = fit_ms
     n_launch = total_launches // steps
@@ -147,7 +147,7 @@ def roofline(stack, fit_ms, steps, per_matrix, fused=True):
             "traffic_source": "profiles/hot_path_7b_block_pmc_traffic.txt (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; bytes per launch)",
             "algorithmic_bytes_per_launch": w_per_launch * es,
             "kernel": "fit_score_kernel%s, %d launch%s per step: %s" % (
-                " (with the first pass of the unit features: windq_features_fit_score)" if fused else "",
+                " (with the unit features' pass over W: windq_features_fit_score)" if fused else "",
                 n_launch, "es" if n_launch > 1 else "", "one per matrix" if per_matrix else "one per decoder block"),
             "avg_launch_ms": avg_ms, "flops_per_weight": flops,
             "weight_GBps": w_per_launch * es / (avg_ms * 1e-3) / 1e9,

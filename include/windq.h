@@ -254,9 +254,10 @@ int windq_fit_score_all_bits_batch(const windq_fit_item* items /*HOST [n]*/, int
 /*
  * windq_unit_features and windq_fit_score_all_bits from ONE read of W (Table 1 and Sec. 3.5 are both
  * per-unit work on the same weights): the fit+score kernel, which holds every tile in LDS anyway,
- * also takes the moments, the count of |w| < 1e-6 and the first-digit histogram of |w| from it; the
- * feature kernels that refine P99 and finish follow on the stream.  Outputs are bit for bit those of
- * the two separate calls.  Workspace: windq_workspace_bytes(WINDQ_CALL_FEATURES_FIT_SCORE, ...).
+ * also takes the moments, the count of |w| < 1e-6 and the histograms of |w| that decide P99 from it;
+ * the small feature kernels that finish follow on the stream (bf16 inputs: W is not read again; a unit
+ * whose P99 lies far from the bulk of one of its tiles gets an exact pass of its own).  Outputs are bit
+ * for bit those of the two separate calls.  Workspace: windq_workspace_bytes(WINDQ_CALL_FEATURES_FIT_SCORE, ...).
  * The batch form is to this call what windq_fit_score_all_bits_batch is to the per-matrix one.
  */
 int windq_features_fit_score(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,

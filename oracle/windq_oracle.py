@@ -623,6 +623,25 @@ def dequant_error(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int, action, 
     return err
 
 
+def dequant_gemv(W: np.ndarray, G: int, unit_rows: int, action, code_off, codes, scale, offset, x: np.ndarray,
+                 rows=None):
+    """y = W_hat x from the packed artefact (the first piece of a serving path): W_hat as
+    dequant_plan reconstructs it (fp32 values; skip units keep their weights), every product
+    and the sum over the columns in fp64, columns in order.  `rows`: compute only these rows
+    of y (the others come out as 0).  Returns (y [rows] fp64, scale [rows] fp64) where
+    scale[r] = sum_c |w_hat[r][c] x[c]|, the natural size of the terms of y[r]."""
+    What = dequant_plan(W, G, unit_rows, action, code_off, codes, scale, offset).astype(f64)
+    xv = np.asarray(x, dtype=f32).astype(f64)
+    pick = np.arange(W.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
+    y = np.zeros(W.shape[0], dtype=f64)
+    mag = np.zeros(W.shape[0], dtype=f64)
+    for c in range(W.shape[1]):
+        term = What[pick, c] * xv[c]
+        y[pick] += term
+        mag[pick] += np.abs(term)
+    return y, mag
+
+
 # ------------------------------------------- salient-weight protection (Sec. 3.5)
 def n_protected(n_unit: int, rate_ppm: int) -> int:
     """Number of protected weights of a unit of n_unit weights at a protection rate given

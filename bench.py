@@ -182,7 +182,7 @@ def protected_pass(wq, torch, stack, ppm, reps):
         sp = m.spec
         n_p = wq.windq_n_protected(m.R_u * G, ppm)
         need = max(wq.workspace_bytes(c, dt, sp.rows, sp.cols, G, unit_rows, stack.K)
-                   for c in (wq.CALL_SALIENT, wq.CALL_DEQUANT, wq.CALL_REFINE))
+                   for c in (wq.CALL_SALIENT, wq.CALL_DEQUANT, wq.CALL_REFINE, wq.CALL_DEQUANT_GEMV))
         extra.append(dict(
             mask=torch.empty(sp.rows, sp.cols // 8, dtype=torch.uint8, device=m.W.device),
             ws=torch.empty(need, dtype=torch.uint8, device=m.W.device),
@@ -190,6 +190,7 @@ def protected_pass(wq, torch, stack, ppm, reps):
                  torch.empty(m.U, dtype=torch.float32, device=m.W.device),
                  torch.empty(m.U, dtype=torch.float32, device=m.W.device)),
             err=torch.empty(m.U, dtype=torch.float32, device=m.W.device),
+            x=torch.randn(sp.cols, device=m.W.device), y=torch.empty(sp.rows, dtype=torch.float32, device=m.W.device),
             n_prot=torch.full((m.U,), n_p, dtype=torch.int64)))
     total_cb = total_n = 0
     for rep in range(reps + 1):
@@ -215,6 +216,10 @@ def protected_pass(wq, torch, stack, ppm, reps):
             Ws, ss, G, unit_rows, [m.action_d for m in mats], [m.off_d for m in mats], [m.codes for m in mats],
             [m.scale for m in mats], [m.offset for m in mats], masks=masks, wss=wss,
             outs=[(e["err"], None) for e in extra]))
+        timer.time("dequant_gemv_prot", lambda: wq.windq_dequant_gemv_batch(
+            Ws, G, unit_rows, [m.action_d for m in mats], [m.off_d for m in mats], [m.codes for m in mats],
+            [m.scale for m in mats], [m.offset for m in mats], [e["x"] for e in extra], masks=masks, wss=wss,
+            outs=[e["y"] for e in extra]))
         for m, e in zip(mats, extra):
             cb, n = wq.windq_effective_bits(m.action, m.n_unit, e["n_prot"])
             total_cb += cb
@@ -224,7 +229,7 @@ def protected_pass(wq, torch, stack, ppm, reps):
     es = mats[0].W.element_size()
     res = {"workload": "block 0 of the stack", "rate_ppm": ppm, "avg_bits": total_cb / (100.0 * total_n)}
     for name in ("salient_select", "salient_encode", "fit_score_all_bits_prot", "apply_plan_prot", "refine_plan_prot_3_rounds",
-                 "dequant_plan_prot"):
+                 "dequant_plan_prot", "dequant_gemv_prot"):
         ms = timer.ms(name)
         per = len(ms) // reps
         steps = sorted(sum(ms[i * per:(i + 1) * per]) for i in range(reps))

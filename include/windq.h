@@ -65,7 +65,8 @@ enum windq_call {
     WINDQ_CALL_UNIT_SALIENCY = 5,
     WINDQ_CALL_DEQUANT = 6,
     WINDQ_CALL_REFINE = 7,
-    WINDQ_CALL_FEATURES_FIT_SCORE = 8
+    WINDQ_CALL_FEATURES_FIT_SCORE = 8,
+    WINDQ_CALL_DEQUANT_GEMV = 9
 };
 
 #define WINDQ_N_ACTIONS 7
@@ -509,6 +510,42 @@ typedef struct windq_dequant_item {
     size_t ws_bytes;
 } windq_dequant_item;
 int windq_dequant_plan_batch(const windq_dequant_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w,
+                             int64_t unit_rows, void* stream);
+
+/*
+ * The product of the reconstruction with a vector, from the packed artefact alone (the first piece of
+ * a path that serves the quantized weights): for every row r
+ *   y[r] = sum_c w_hat[r][c] * x[c],   w_hat as windq_dequant_plan reconstructs it (fp32, one fused
+ *          multiply-add per weight; skip units keep their weights: W is read for them only;
+ *          protected weights of a mask count as 0: their values live in the INT8 side stream).
+ * Eight columns at a time are multiplied and summed in fp32 (fused multiply-adds in column order), those
+ * runs in fp64 (a row's runs of one chunk, then the chunks in order), and y is rounded once: results are
+ * bit-reproducible and differ from the exact product by at most ~1e-6 of sum_c |w_hat x|.
+ *   x [cols] f32, y [rows] f32 (every element written).  Workspace: WINDQ_CALL_DEQUANT_GEMV.
+ * Plan entries are checked as in windq_dequant_plan (a malformed one counts as skip).  The batch form
+ * takes up to WINDQ_MAX_BATCH matrices (one chunk width, unit_rows, element type) in one launch plus
+ * one that sums the chunks.
+ */
+int windq_dequant_gemv(const windq_mat* W, int32_t chunk_w, int64_t unit_rows,
+                       const uint8_t* mask /*[rows][cols/8] or NULL*/, const uint8_t* action /*[U]*/,
+                       const int64_t* code_off /*[U+1]*/, const uint8_t* codes, size_t codes_bytes,
+                       const float* scale /*[U*R_u]*/, const float* offset /*[U*R_u]*/,
+                       const float* x /*[cols]*/, float* y /*[rows]*/, void* ws, size_t ws_bytes, void* stream);
+typedef struct windq_gemv_item {
+    const windq_mat* W;
+    const uint8_t* mask;      /* [rows][cols/8] or NULL */
+    const uint8_t* action;    /* [U] */
+    const int64_t* code_off;  /* [U+1] */
+    const uint8_t* codes;
+    size_t codes_bytes;
+    const float* scale;       /* [U*R_u] */
+    const float* offset;      /* [U*R_u] */
+    const float* x;           /* [cols] */
+    float* y;                 /* [rows] */
+    void* ws;
+    size_t ws_bytes;
+} windq_gemv_item;
+int windq_dequant_gemv_batch(const windq_gemv_item* items /*HOST [n]*/, int32_t n, int32_t chunk_w,
                              int64_t unit_rows, void* stream);
 
 /*

@@ -624,13 +624,13 @@ def dequant_error(W: np.ndarray, s: np.ndarray, G: int, unit_rows: int, action, 
 
 
 def dequant_gemv(W: np.ndarray, G: int, unit_rows: int, action, code_off, codes, scale, offset, x: np.ndarray,
-                 rows=None):
+                 rows=None, keep=None):
     """y = W_hat x from the packed artefact (the first piece of a serving path): W_hat as
-    dequant_plan reconstructs it (fp32 values; skip units keep their weights), every product
-    and the sum over the columns in fp64, columns in order.  `rows`: compute only these rows
+    dequant_plan reconstructs it (fp32 values; skip units keep their weights; protected slots,
+    keep False, count as 0), every product and the sum over the columns in fp64, columns in order.  `rows`: compute only these rows
     of y (the others come out as 0).  Returns (y [rows] fp64, scale [rows] fp64) where
     scale[r] = sum_c |w_hat[r][c] x[c]|, the natural size of the terms of y[r]."""
-    What = dequant_plan(W, G, unit_rows, action, code_off, codes, scale, offset).astype(f64)
+    What = dequant_plan(W, G, unit_rows, action, code_off, codes, scale, offset, keep=keep).astype(f64)
     xv = np.asarray(x, dtype=f32).astype(f64)
     pick = np.arange(W.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
     y = np.zeros(W.shape[0], dtype=f64)

@@ -7,5 +7,6 @@ from .binding import (  # noqa: F401
     windq_apply_plan_batch, windq_calib_stats, windq_calib_stats_batch, windq_dequant_plan, windq_effective_bits, windq_fit_score_all_bits, windq_fit_score_all_bits_batch, windq_fit_score_rescored_units, windq_fit_score_all_bits_static, STATIC_SCRATCH_BYTES, windq_mat, windq_plan_layout, windq_refine_plan,
     windq_fallback_promote, windq_heuristic_plan, windq_n_protected, windq_salient_encode, windq_unit_saliency, windq_salient_select, windq_unit_features, windq_unit_features_batch, workspace_bytes,
     windq_salient_select_batch, windq_salient_encode_batch, windq_refine_plan_batch, windq_dequant_plan_batch, windq_unit_features_exact_units,
+    CALL_DEQUANT_GEMV, windq_dequant_gemv, windq_dequant_gemv_batch,
 )
 from . import synth  # noqa: F401

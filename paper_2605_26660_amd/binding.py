@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libwindq.so")
 
 WINDQ_OK, WINDQ_EINVAL, WINDQ_ESHAPE, WINDQ_EDTYPE, WINDQ_EWORKSPACE, WINDQ_EHIP = range(6)
 WINDQ_F32, WINDQ_BF16 = 0, 1
-CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT, CALL_REFINE, CALL_FEATURES_FIT_SCORE = range(9)
+CALL_CALIB_STATS, CALL_UNIT_FEATURES, CALL_FIT_SCORE, CALL_APPLY_PLAN, CALL_SALIENT, CALL_UNIT_SALIENCY, CALL_DEQUANT, CALL_REFINE, CALL_FEATURES_FIT_SCORE, CALL_DEQUANT_GEMV = range(10)
 N_ACTIONS, N_ERR, N_FEAT, MAX_CLIP, MAX_CHUNK, MAX_BATCH = 7, 6, 8, 64, 512, 8
 STATIC_SCRATCH_BYTES = 8 << 20
 
@@ -30,6 +30,7 @@ EXPORTS = (
     "windq_fit_score_all_bits_static", "windq_features_fit_score", "windq_features_fit_score_batch",
     "windq_kernel_timer", "windq_kernel_timer_read", "windq_salient_select_batch", "windq_salient_encode_batch",
     "windq_refine_plan_batch", "windq_dequant_plan_batch", "windq_unit_features_exact_units",
+    "windq_dequant_gemv", "windq_dequant_gemv_batch",
 )
 
 
@@ -90,6 +91,13 @@ class windq_dequant_item(ctypes.Structure):
                 ("codes_bytes", ctypes.c_size_t), ("scale", ctypes.c_void_p), ("offset", ctypes.c_void_p),
                 ("err", ctypes.c_void_p), ("w_hat", ctypes.c_void_p), ("ws", ctypes.c_void_p),
                 ("ws_bytes", ctypes.c_size_t)]
+
+
+class windq_gemv_item(ctypes.Structure):
+    _fields_ = [("W", ctypes.POINTER(windq_mat)), ("mask", ctypes.c_void_p), ("action", ctypes.c_void_p),
+                ("code_off", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("codes_bytes", ctypes.c_size_t),
+                ("scale", ctypes.c_void_p), ("offset", ctypes.c_void_p), ("x", ctypes.c_void_p), ("y", ctypes.c_void_p),
+                ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
 
 class windq_calib_item(ctypes.Structure):
@@ -159,6 +167,10 @@ def load(path: str | None = None):
     lib.windq_refine_plan_batch.restype = c.c_int
     lib.windq_dequant_plan_batch.argtypes = [c.POINTER(windq_dequant_item), i32, i32, i64, vp]
     lib.windq_dequant_plan_batch.restype = c.c_int
+    lib.windq_dequant_gemv.argtypes = [pm, i32, i64, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, sz, vp]
+    lib.windq_dequant_gemv.restype = c.c_int
+    lib.windq_dequant_gemv_batch.argtypes = [c.POINTER(windq_gemv_item), i32, i32, i64, vp]
+    lib.windq_dequant_gemv_batch.restype = c.c_int
     lib.windq_unit_features_exact_units.argtypes = [vp, i32, i64, i64, i32, i64, c.POINTER(i64)]
     lib.windq_unit_features_exact_units.restype = c.c_int
     lib.windq_status_str.argtypes = [c.c_int]
@@ -746,3 +758,40 @@ def windq_dequant_plan_batch(Ws, ss, chunk_w: int, unit_rows: int, actions, code
                                       ws.numel())
     _check(load().windq_dequant_plan_batch(items, n, chunk_w, unit_rows, _stream()), "windq_dequant_plan_batch")
     return res
+
+
+def windq_dequant_gemv(W: torch.Tensor, chunk_w: int, unit_rows: int, action: torch.Tensor, code_off: torch.Tensor,
+                       codes: torch.Tensor, scale: torch.Tensor, offset: torch.Tensor, x: torch.Tensor,
+                       mask: torch.Tensor | None = None, ws: torch.Tensor | None = None, out: torch.Tensor | None = None):
+    """y = W_hat x from the packed plan (device tensors as windq_apply_plan wrote them; x f32 [cols]).  -> y f32 [rows]."""
+    _require_cuda(W, action, code_off, codes, scale, offset, x, mask)
+    assert x.dtype == torch.float32 and x.is_contiguous()
+    y = out if out is not None else torch.empty(W.shape[0], dtype=torch.float32, device=W.device)
+    ws = _workspace(CALL_DEQUANT_GEMV, W, chunk_w, unit_rows, 1, ws)
+    m = as_mat(W)
+    _check(load().windq_dequant_gemv(ctypes.byref(m), chunk_w, unit_rows, _ptr(mask), action.data_ptr(), code_off.data_ptr(),
+                                     codes.data_ptr(), codes.numel(), scale.data_ptr(), offset.data_ptr(), x.data_ptr(),
+                                     y.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "windq_dequant_gemv")
+    return y
+
+
+def windq_dequant_gemv_batch(Ws, chunk_w: int, unit_rows: int, actions, code_offs, codes, scales, offsets, xs, masks=None,
+                             wss=None, outs=None):
+    """windq_dequant_gemv for several matrices (lists of equal length, at most MAX_BATCH) in one launch.  -> [y]."""
+    n = len(Ws)
+    assert all(len(v) == n for v in (actions, code_offs, codes, scales, offsets, xs))
+    _require_cuda(*Ws, *actions, *code_offs, *codes, *scales, *offsets, *xs)
+    mats = [as_mat(W) for W in Ws]
+    items = (windq_gemv_item * max(n, 1))()
+    ys, keep = [], []
+    for i, W in enumerate(Ws):
+        assert xs[i].dtype == torch.float32 and xs[i].is_contiguous()
+        y = outs[i] if outs is not None else torch.empty(W.shape[0], dtype=torch.float32, device=W.device)
+        ws = _workspace(CALL_DEQUANT_GEMV, W, chunk_w, unit_rows, 1, None if wss is None else wss[i])
+        ys.append(y)
+        keep.append(ws)
+        items[i] = windq_gemv_item(ctypes.pointer(mats[i]), None if masks is None else _ptr(masks[i]), actions[i].data_ptr(),
+                                   code_offs[i].data_ptr(), codes[i].data_ptr(), codes[i].numel(), scales[i].data_ptr(),
+                                   offsets[i].data_ptr(), xs[i].data_ptr(), y.data_ptr(), ws.data_ptr(), ws.numel())
+    _check(load().windq_dequant_gemv_batch(items, n, chunk_w, unit_rows, _stream()), "windq_dequant_gemv_batch")
+    return ys

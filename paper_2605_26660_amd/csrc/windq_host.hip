@@ -137,6 +137,7 @@ size_t windq_workspace_bytes(int32_t which_call, int32_t dtype, int64_t rows, in
             return fit_score_ws_bytes(g, K);
         case WINDQ_CALL_APPLY_PLAN: return apply_ws_bytes(g);
         case WINDQ_CALL_SALIENT: return salient_ws_bytes(g);
+        case WINDQ_CALL_DEQUANT_GEMV: return dequant_gemv_ws_bytes(g);
         case WINDQ_CALL_UNIT_SALIENCY: return unit_saliency_ws_bytes(g);
         case WINDQ_CALL_DEQUANT: return dequant_ws_bytes(g);
         case WINDQ_CALL_REFINE: return unit_saliency_ws_bytes(g);

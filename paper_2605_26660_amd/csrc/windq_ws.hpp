@@ -148,6 +148,11 @@ inline size_t dequant_ws_bytes(const Geometry& g) {
     return round_up((size_t)g.n_tiles * (size_t)dequant_passes(g.chunk_w) * sizeof(double), 256);
 }
 
+// ---- the product from the artefact: one fp64 partial per (row, chunk)
+inline size_t dequant_gemv_ws_bytes(const Geometry& g) {
+    return round_up((size_t)g.rows * (size_t)g.n_chunks * sizeof(double), 256);
+}
+
 // ---- apply_plan needs no scratch; a token size keeps "ws != NULL" uniform across calls
 inline size_t apply_ws_bytes(const Geometry&) { return 256; }
 

@@ -97,3 +97,102 @@ def test_malformed_entries_read_nothing(windq):
     err, w_hat = windq.windq_dequant_plan(W, s, 128, 0, action.to(DEV), odd.to(DEV), big, scale, offset)
     torch.cuda.synchronize()
     assert float(err[0]) == 0.0 and torch.equal(w_hat, W.float())
+
+
+# ------------------------------------------------------- the product from the artefact
+def gemv_case(windq, W, s, G, unit_rows, K, ppm=0):
+    cg = synth.clip_grid(K)
+    mask = keep = None
+    if ppm:
+        mask = windq.windq_salient_select(W, s, G, unit_rows, ppm)
+        keep = O.salient_select(to_np(W), s.cpu().numpy(), G, unit_rows, ppm)
+    err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, G, unit_rows, cg, mask=mask)
+    U, R_u = windq.n_units(W.shape[0], W.shape[1], G, unit_rows)
+    gen = torch.Generator().manual_seed(7)
+    x = (torch.randn(W.shape[1], generator=gen) * torch.exp(torch.randn(W.shape[1], generator=gen))).to(DEV)
+    for shift in (0, 4):
+        action = ((torch.arange(U) + shift) % 7).to(torch.uint8)
+        off = windq.windq_plan_layout(action, R_u, G)
+        codes, scale, offset = windq.windq_apply_plan(W, G, unit_rows, action.to(DEV), clip_idx, cg, off.to(DEV), mask=mask)
+        y = windq.windq_dequant_gemv(W, G, unit_rows, action.to(DEV), off.to(DEV), codes, scale, offset, x, mask=mask)
+        torch.cuda.synchronize()
+        args = (action.numpy(), off.numpy(), codes.cpu().numpy(), scale.cpu().numpy(), offset.cpu().numpy())
+        want, mag = O.dequant_gemv(to_np(W), G, unit_rows, *args, x.cpu().numpy(), keep=keep)
+        got = y.cpu().numpy().astype(np.float64)
+        # y is a sum of signed terms: its natural scale is sum |w_hat x| (and y itself is rounded to fp32)
+        assert np.all(np.abs(got - want) <= REL * mag + 1e-7 * np.abs(want)), np.max(np.abs(got - want) / (mag + 1e-300))
+
+
+@pytest.mark.parametrize("R,C,G,unit_rows,K,dtype", [
+    (256, 512, 128, 0, 20, torch.bfloat16), (200, 256, 64, 100, 7, torch.bfloat16),
+    (512, 512, 64, 0, 20, torch.float32), (24, 80, 40, 3, 5, torch.bfloat16), (70, 96, 32, 0, 4, torch.bfloat16),
+    (64, 512, 256, 0, 6, torch.bfloat16), (130, 1024, 512, 0, 3, torch.bfloat16), (16, 24, 8, 4, 3, torch.float32)])
+def test_gemv_from_the_artefact(windq, R, C, G, unit_rows, K, dtype):
+    W = synth.weights_llm(R, C, seed=111, device=DEV, dtype=dtype)
+    X = synth.activations_llm(64, C, seed=112, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    gemv_case(windq, W, s, G, unit_rows, K)
+
+
+@pytest.mark.parametrize("R,C,G,unit_rows,ppm", [(256, 512, 128, 0, 30000), (70, 96, 32, 0, 300000), (24, 80, 40, 3, 100000)])
+def test_gemv_under_a_protection_mask(windq, R, C, G, unit_rows, ppm):
+    W = synth.weights_llm(R, C, seed=113, device=DEV)
+    X = synth.activations_llm(64, C, seed=114, device=DEV)
+    s, _ = windq.windq_calib_stats(X)
+    gemv_case(windq, W, s, G, unit_rows, 8, ppm=ppm)
+
+
+def test_gemv_full_size_against_the_reconstruction_and_in_a_batch(windq):
+    """4096 x 11008 and 11008 x 4096 bf16: y against the fp64 product of the device's own reconstruction (which
+    the oracle checks elsewhere), and sampled rows against the oracle; the batch call gives the same bits."""
+    cg = synth.clip_grid(20)
+    Ws, acts, offs, cods, scs, ofs, xs, ys = [], [], [], [], [], [], [], []
+    for i, (R, C) in enumerate(((4096, 11008), (11008, 4096))):
+        W = synth.weights_llm(R, C, seed=115 + i, device=DEV)
+        X = synth.activations_llm(512, C, seed=117 + i, device=DEV)
+        s, _ = windq.windq_calib_stats(X)
+        err, clip_idx, ref = windq.windq_fit_score_all_bits(W, s, 128, 0, cg)
+        U, R_u = windq.n_units(R, C, 128, 0)
+        gen = torch.Generator().manual_seed(40 + i)
+        action = torch.randint(0, 7, (U,), generator=gen, dtype=torch.uint8)
+        off = windq.windq_plan_layout(action, R_u, 128)
+        codes, scale, offset = windq.windq_apply_plan(W, 128, 0, action.to(DEV), clip_idx, cg, off.to(DEV))
+        x = torch.randn(C, generator=gen).to(DEV)
+        y = windq.windq_dequant_gemv(W, 128, 0, action.to(DEV), off.to(DEV), codes, scale, offset, x)
+        _, w_hat = windq.windq_dequant_plan(W, s, 128, 0, action.to(DEV), off.to(DEV), codes, scale, offset)
+        torch.cuda.synchronize()
+        ref64 = w_hat.double() @ x.double()
+        mag = w_hat.double().abs() @ x.double().abs()
+        assert bool(torch.all((y.double() - ref64).abs() <= REL * mag + 1e-7 * ref64.abs()))
+        rows = [0, 63, 64, R // 2 + 1, R - 1]
+        want, omag = O.dequant_gemv(to_np(W), 128, 0, action.numpy(), off.numpy(), codes.cpu().numpy(), scale.cpu().numpy(),
+                                    offset.cpu().numpy(), x.cpu().numpy(), rows=rows)
+        got = y.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got[rows] - want[rows]) <= REL * omag[rows] + 1e-7 * np.abs(want[rows]))
+        for lst, v in zip((Ws, acts, offs, cods, scs, ofs, xs, ys), (W, action.to(DEV), off.to(DEV), codes, scale, offset, x, y)):
+            lst.append(v)
+    both = windq.windq_dequant_gemv_batch(Ws, 128, 0, acts, offs, cods, scs, ofs, xs)
+    torch.cuda.synchronize()
+    for one, b in zip(ys, both):
+        assert torch.equal(one.view(torch.int32), b.view(torch.int32))
+
+
+def test_gemv_checks_its_arguments(windq):
+    W = synth.weights_llm(64, 128, seed=119, device=DEV)
+    a = torch.full((1,), 2, dtype=torch.uint8)
+    off = windq.windq_plan_layout(a, 64, 128).to(DEV)
+    codes = torch.zeros(int(off[-1]), dtype=torch.uint8, device=DEV)
+    z = torch.zeros(64, device=DEV)
+    x = torch.ones(128, device=DEV)
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_dequant_gemv(W, 96, 0, a.to(DEV), off, codes, z, z, x)
+    assert e.value.status == windq.WINDQ_ESHAPE
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_dequant_gemv(W, 128, 0, a.to(DEV), off, codes, z, z, x, ws=torch.empty(64, dtype=torch.uint8, device=DEV))
+    assert e.value.status == windq.WINDQ_EWORKSPACE
+    with pytest.raises(windq.WindqError) as e:
+        windq.windq_dequant_gemv_batch([W] * 9, 128, 0, [a.to(DEV)] * 9, [off] * 9, [codes] * 9, [z] * 9, [z] * 9, [x] * 9)
+    assert e.value.status == windq.WINDQ_EINVAL
+    y = windq.windq_dequant_gemv(W, 128, 0, a.to(DEV), off, codes, z, z, x)      # scale 0, offset 0: a zero matrix
+    torch.cuda.synchronize()
+    assert float(y.abs().max()) == 0.0

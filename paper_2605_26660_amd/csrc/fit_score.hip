@@ -70,7 +70,8 @@ constexpr int FS_WAVES = FS_THREADS / 64;
 constexpr int FS_KB = 5;                    // clip ratios evaluated together by one wavefront pass
 constexpr int FS_NRED = FS_KB * 5;          // per-lane sums a pass produces: 4 errors + 1 noise term per clip ratio
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
-constexpr int FS_HMAX = WINDQ_MAX_CHUNK / 8;   // most columns a tile may send down the exact 8-bit route on their own
+constexpr int FS_PREP_CHUNKS = FS_THREADS / 64;     // chunks a workgroup of the preparing kernel takes, one per wavefront
+constexpr int FS_PREP_CLEAR = FS_THREADS * 4;       // counters one of its workgroups clears
 constexpr int FS_REDO_GRID = 512; 
 // What a pass over a tile does.
 constexpr int FS_SCORE = 0;         // every candidate quantizer
@@ -111,6 +112,7 @@ struct FitScoreMat {
     float* ref_energy;
     Geometry g;
     float tau;         // columns with s_c^2 > tau * mean(s^2) of the chunk take the exact 8-bit route; 0: all do
+    float* colsel;     // [n_chunks][colsel_words]: the chunks' column selection, written by the preparing kernel
     // first pass of the unit features (FS_SCORE_FEAT, FS_FEAT_ONLY), else unused
     double* fmoments;      // [n_tiles][4 column quarters][4]: sum w, sum w^2, sum |w|, count(|w| < 1e-6)
     uint32_t* fhist;       // [U][FEAT_BINS]: histogram of the first radix digit of |w|
@@ -118,6 +120,9 @@ struct FitScoreMat {
     uint32_t* fanchor;     // bf16: [n_tiles] last bin of that record, and (<< 16) the bin of the tile's largest key
     float sparse_thr;      // smallest fp32 that is >= 1e-6
     uint32_t sparse_key;   // bf16: smallest key whose value is >= 1e-6
+    uint32_t* fclear;      // the features' counters that start a call at zero, [fclear_words] ...
+    int64_t fclear_words;
+    uint32_t* flist_count; // ... and one more (bf16), or null
 };
 
 // A launch covers up to WINDQ_MAX_BATCH matrices of one chunk width and element type: their
@@ -130,6 +135,7 @@ struct FitScoreArgs {
     double inv_G;                                // 1 / chunk_w
     int64_t tile_start[WINDQ_MAX_BATCH + 1];     // first tile of matrix i in the grid; [n] = grid size
     int64_t unit_start[WINDQ_MAX_BATCH + 1];
+    int64_t prep_start[WINDQ_MAX_BATCH + 1];     // first workgroup of matrix i in the preparing kernel's grid
     FitScoreMat m[WINDQ_MAX_BATCH];
     ClipGrid grid;
 };
@@ -450,48 +456,20 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     if (FEAT) {
         for (int32_t b = threadIdx.x; b < LH_DWORDS; b += FS_THREADS) lhist[b] = 0u;
     }
+    // Column selection for the 8-bit candidate, prepared per chunk (fit_score_prepare_kernel): s_c
+    // of the columns on the short route (0 for the listed ones) and the list lie next to each
+    // other, in the record as in LDS.
+    int32_t nh = -1;           // listed columns; -1: no list, every column takes the exact route
+    float s4_over_s2 = 0.0f;   // sum s_c^4 / sum s_c^2 over the short route: scales the tile's noise term
+    if (SCORE && !ONLY8) {
+        const float* __restrict__ rec = A.colsel + (size_t)(tc.col0 / G) * (size_t)colsel_words(G);
+        for (int32_t c = threadIdx.x; c < G + FS_HMAX; c += FS_THREADS) sshort[c] = rec[c];
+        // (wave-uniform: parked in scalar registers across the hot loops)
+        nh = __builtin_amdgcn_readfirstlane(__float_as_int(rec[G + FS_HMAX]));
+        s4_over_s2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(rec[G + FS_HMAX + 1])));
+    }
     __syncthreads();
 
-    // Column selection for the 8-bit candidate.  A column whose s_c^2 exceeds tau times the
-    // chunk's mean carries much of the unit's error by itself: such columns are listed and
-    // scored on the exact route, one at a time; all others (s_c kept in sshort, listed ones
-    // zeroed there) go down the short route, and their S4/S2 = sum s_c^4 / sum s_c^2 scales the
-    // tile's noise term.  Every wavefront derives the same list and writes the same values:
-    // none waits for another.
-    int32_t nh = -1;           // listed columns; -1: no list, every column takes the exact route
-    float s4_over_s2 = 0.0f;
-    if (SCORE && !ONLY8) {
-        const int l = fresh_lane();
-        if (A.tau > 0.0f) {
-            float ss = 0.0f;
-            for (int32_t c = l; c < G; c += 64) {
-                const float sv = scol[c];
-                ss = fmaf(sv, sv, ss);
-            }
-            const float thr = A.tau * wave_sum_f32(ss) / (float)G;
-            nh = 0;
-            float t2 = 0.0f, t4 = 0.0f;
-            for (int32_t blk = 0; blk < G; blk += 64) {
-                const int32_t c = blk + l;
-                const float sv = c < G ? scol[c] : 0.0f;
-                const float s2 = sv * sv;
-                const bool hv = s2 > thr;
-                const uint64_t bal = __builtin_amdgcn_ballot_w64(hv);
-                if (c < G) sshort[c] = hv ? 0.0f : sv;
-                if (!hv) {
-                    t2 += s2;
-                    t4 = fmaf(s2, s2, t4);
-                }
-                const int32_t pos = nh + __builtin_popcountll(bal & ((1ull << l) - 1ull));
-                if (hv && pos < FS_HMAX) hlist[pos] = c;
-                nh += __builtin_popcountll(bal);
-            }
-            const float S2 = wave_sum_f32(t2), S4 = wave_sum_f32(t4);
-            // (wave-uniform: parked in a scalar register across the hot loops)
-            s4_over_s2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(S2 >= FLT_MIN ? S4 / S2 : 0.0f)));
-            if (nh * 8 > G) nh = -1;     // so many that one exact sweep over all columns is cheaper
-        }
-    }
     // Group statistics (of the kept weights), once per tile: each wavefront scans a quarter of
     // the chunk's 8-column runs for all 64 rows -- minimum, maximum, and the sum of |w| in fp64
     // in column order -- and the quarters are combined through LDS, in order.
@@ -908,13 +886,71 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     }
 }
 
+// What a scoring call sets up before its tiles run, per matrix: the column selection of every
+// chunk, one wavefront each; the empty list of units for the exact 8-bit pass; and, with the
+// unit features riding along, their counters at zero.
+//   Column selection for the 8-bit candidate: a column whose s_c^2 exceeds tau times the chunk's
+//   mean carries much of a unit's error by itself.  Such columns are listed and scored on the
+//   exact route, one at a time; all others go down the short route, and their
+//   S4/S2 = sum s_c^4 / sum s_c^2 scales a tile's noise term.  It depends on s alone, so the
+//   chunk's tiles read it instead of deriving it again.
+__global__ __launch_bounds__(FS_THREADS) void fit_score_prepare_kernel(const FitScoreArgs B) {
+    const int mi = batch_index(B.prep_start, B.n, blockIdx.x);
+    const FitScoreMat& A = B.m[mi];
+    const int64_t local = (int64_t)blockIdx.x - B.prep_start[mi];
+    const int64_t sel_groups = (A.g.n_chunks + FS_PREP_CHUNKS - 1) / FS_PREP_CHUNKS;
+    if (local >= sel_groups) {
+        const int64_t i = ((local - sel_groups) * FS_THREADS + (int64_t)threadIdx.x) * 4;
+        if (i < A.fclear_words) *reinterpret_cast<uint4*>(A.fclear + i) = make_uint4(0u, 0u, 0u, 0u);
+        if (i == 0 && A.flist_count != nullptr) *A.flist_count = 0u;
+        return;
+    }
+    if (local == 0 && threadIdx.x == 0) *A.redo_count = 0u;      // the list the finalize kernel fills
+    const int64_t j = local * FS_PREP_CHUNKS + (int64_t)(threadIdx.x >> 6);
+    if (j >= A.g.n_chunks) return;
+    const int l = threadIdx.x & 63;
+    const int32_t G = A.g.chunk_w;
+    const float* __restrict__ scol = A.s + j * G;
+    float* __restrict__ sshort = A.colsel + (size_t)j * (size_t)colsel_words(G);    // s_c, 0 for the listed columns
+    int32_t* __restrict__ hlist = reinterpret_cast<int32_t*>(sshort + G);            // the listed columns
+    float ss = 0.0f;
+    for (int32_t c = l; c < G; c += 64) {
+        const float sv = scol[c];
+        ss = fmaf(sv, sv, ss);
+    }
+    // below tau = 1 (never a positive tau) nothing is listed short: the threshold 0 lists every column with s_c != 0
+    const float thr = A.tau * wave_sum_f32(ss) / (float)G;
+    int32_t nh = 0;
+    float t2 = 0.0f, t4 = 0.0f;
+    for (int32_t blk = 0; blk < G; blk += 64) {
+        const int32_t c = blk + l;
+        const float sv = c < G ? scol[c] : 0.0f;
+        const float s2 = sv * sv;
+        const bool hv = s2 > thr;
+        const uint64_t bal = __builtin_amdgcn_ballot_w64(hv);
+        if (c < G) sshort[c] = hv ? 0.0f : sv;
+        if (!hv) {
+            t2 += s2;
+            t4 = fmaf(s2, s2, t4);
+        }
+        const int32_t pos = nh + __builtin_popcountll(bal & ((1ull << l) - 1ull));
+        if (hv && pos < FS_HMAX) hlist[pos] = c;
+        nh += __builtin_popcountll(bal);
+    }
+    const float S2 = wave_sum_f32(t2), S4 = wave_sum_f32(t4);
+    if (nh * 8 > G || !(A.tau > 0.0f)) nh = -1;      // so many that one exact sweep over all columns is cheaper
+    if (l == 0) {
+        hlist[FS_HMAX] = nh;
+        sshort[G + FS_HMAX + 1] = S2 >= FLT_MIN ? S4 / S2 : 0.0f;
+    }
+}
+
 template <int DT, bool MASKED, int MODE>
 __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScoreArgs B) {
     extern __shared__ char smem[];
     const int mi = batch_index(B.tile_start, B.n, blockIdx.x);
     const FitScoreMat& A = B.m[mi];
     const int64_t local = (int64_t)blockIdx.x - B.tile_start[mi];
-    if (MODE != FS_FEAT_ONLY && local == 0 && threadIdx.x == 0) *A.redo_count = 0u;      // the list the finalize kernel fills
     const TileCoord tc = tile_coord(A.g, local);
     fit_score_tile<DT, MASKED, MODE>(B, A, tc, blockIdx.x & (FS_WAVES - 1), smem);
 }
@@ -1101,7 +1137,7 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
     for (int k = 0; k < WINDQ_MAX_CLIP; ++k) A.grid.p[k] = clip_grid[k < K ? k : K - 1];
     const bool masked = items[0].mask != nullptr;
     if (masked && feat != nullptr) return WINDQ_EINVAL;
-    int64_t tiles = 0, units = 0;
+    int64_t tiles = 0, units = 0, preps = 0;
     for (int32_t i = 0; i < n; ++i) {
         const FitItem& it = items[i];
         FitScoreMat& M = A.m[i];
@@ -1120,6 +1156,7 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
         M.partial = reinterpret_cast<double*>(base + L.partial);
         M.redo_count = reinterpret_cast<uint32_t*>(base + L.redo_count);
         M.redo_list = reinterpret_cast<uint32_t*>(base + L.redo_list);
+        M.colsel = reinterpret_cast<float*>(base + L.colsel);
         M.err = it.err;
         M.clip_idx = it.clip_idx;
         M.ref_energy = it.ref_energy;
@@ -1129,6 +1166,9 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
         M.fanchor = feat != nullptr ? feat->m[i].anchor : nullptr;
         M.sparse_thr = feat != nullptr ? feat->m[i].sparse_thr : 0.0f;
         M.sparse_key = feat != nullptr ? feat->m[i].sparse_key : 0u;
+        M.fclear = M.fhist;
+        M.fclear_words = feat != nullptr ? (feat->dtype == WINDQ_BF16 ? 1 : 3) * (int64_t)FEAT_BINS * M.g.U : 0;
+        M.flist_count = feat != nullptr && feat->dtype == WINDQ_BF16 ? feat->m[i].list_count : nullptr;
         // tau: with the error spread evenly over R_u rows, listing the columns above tau times the
         // mean keeps the short route's noise in the unit's 8-bit error near 1e-6 (one standard
         // deviation; what the rows really do is measured per unit, see NOISE_MAX).  Below
@@ -1137,22 +1177,25 @@ static int fit_score_launch(const FitItem* items, int32_t n, int32_t chunk_w, in
         M.tau = t < 1.0f ? 0.0f : t;
         A.tile_start[i] = tiles;
         A.unit_start[i] = units;
+        A.prep_start[i] = preps;
         tiles += M.g.n_tiles;
         units += M.g.U;
+        preps += (M.g.n_chunks + FS_PREP_CHUNKS - 1) / FS_PREP_CHUNKS + (M.fclear_words + FS_PREP_CLEAR - 1) / FS_PREP_CLEAR;
     }
     for (int32_t i = n; i <= WINDQ_MAX_BATCH; ++i) {
         A.tile_start[i] = tiles;
         A.unit_start[i] = units;
+        A.prep_start[i] = preps;
     }
     for (int32_t i = n; i < WINDQ_MAX_BATCH; ++i) A.m[i] = A.m[0];
-    if (tiles > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
+    if (tiles > (int64_t)0x7fffffff || preps > (int64_t)0x7fffffff) return WINDQ_ESHAPE;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const int32_t dtype = items[0].W->dtype;
     const size_t lds = fit_score_lds_bytes(dtype, chunk_w, masked);
     const dim3 grid((unsigned)tiles);
+    hipLaunchKernelGGL(fit_score_prepare_kernel, dim3((unsigned)preps), dim3(FS_THREADS), 0, hs, A);
+    if (hipPeekAtLastError() != hipSuccess) return WINDQ_EHIP;
     if (feat != nullptr) {
-        st = features_launch_init(*feat, hs);
-        if (st != WINDQ_OK) return st;
         st = launch_tiles<FS_SCORE_FEAT>(A, dtype, false, lds, grid, hs);
     } else {
         st = launch_tiles<FS_SCORE>(A, dtype, masked, lds, grid, hs);

@@ -19,10 +19,17 @@ inline size_t calib_ws_bytes(int64_t rows, int64_t cols) {
 // 8-bit short route's rounding noise at clip index k
 __host__ __device__ inline int32_t fit_score_ncand(int32_t K) { return 5 * K + 12; }
 __host__ __device__ inline int32_t fit_score_noise_slot(int32_t K) { return 4 * K + 12; }
+// What fit+score prepares once per chunk of columns (it depends on s alone): the activation scales
+// of the columns that take the short 8-bit route (0 for the others), the list of the others, their
+// number (-1: every column takes the exact route) and sum s_c^4 / sum s_c^2 over the short route.
+constexpr int FS_HMAX = WINDQ_MAX_CHUNK / 8;   // most columns a chunk may send down the exact 8-bit route on their own
+inline __host__ __device__ int32_t colsel_words(int32_t chunk_w) { return chunk_w + FS_HMAX + 4; }   // 4-byte words per chunk
+
 struct FitScoreLayout {
     size_t partial;      // [n_tiles][ncand] fp64
     size_t redo_count;   // u32: units on the list
     size_t redo_list;    // [U] u32
+    size_t colsel;       // [n_chunks][colsel_words] the chunks' column selection
     size_t total;
 };
 inline FitScoreLayout fit_score_layout(const Geometry& g, int32_t K) {
@@ -31,6 +38,7 @@ inline FitScoreLayout fit_score_layout(const Geometry& g, int32_t K) {
     L.partial = pos;     pos = round_up(pos + (size_t)g.n_tiles * (size_t)fit_score_ncand(K) * sizeof(double), 256);
     L.redo_count = pos;  pos += 256;
     L.redo_list = pos;   pos = round_up(pos + (size_t)g.U * sizeof(uint32_t), 256);
+    L.colsel = pos;      pos = round_up(pos + (size_t)g.n_chunks * (size_t)colsel_words(g.chunk_w) * 4, 256);
     L.total = pos;
     return L;
 }

@@ -88,9 +88,12 @@ def test_effective_bits_hand_totals(windq):
 def test_workspace_sizes(windq):
     B, F = windq.WINDQ_BF16, windq.WINDQ_F32
     # fit-score: one fp64 per (64-row tile, candidate): 32 units x 64 tiles x (4*20 errors + 3 per column quarter
-    # + 20 noise terms), then a counter (256 bytes) and a list of unit indices (4 bytes each, rounded up to 256)
-    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4096, 128, 0, 20) == 32 * 64 * 112 * 8 + 256 + 256
-    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4096, 128, 128, 20) == 1024 * 2 * 112 * 8 + 256 + 4096
+    # + 20 noise terms), then a counter (256 bytes), a list of unit indices (4 bytes each, rounded up to 256) and
+    # per chunk of columns 128 + 64 + 4 words of column selection
+    colsel = 32 * (128 + 64 + 4) * 4
+    assert colsel % 256 == 0
+    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4096, 128, 0, 20) == 32 * 64 * 112 * 8 + 256 + 256 + colsel
+    assert windq.workspace_bytes(windq.CALL_FIT_SCORE, B, 4096, 4096, 128, 128, 20) == 1024 * 2 * 112 * 8 + 256 + 4096 + colsel
     # calib: two fp64 per (32-token slab, channel)
     assert windq.workspace_bytes(windq.CALL_CALIB_STATS, F, 256, 512) == 8 * 512 * 16
     assert windq.workspace_bytes(windq.CALL_UNIT_FEATURES, B, 4096, 4096, 128, 0, 1) > 32 * 2048 * 4

@@ -69,6 +69,8 @@ constexpr int FS_THREADS = 256;
 constexpr int FS_WAVES = FS_THREADS / 64;
 constexpr int FS_KB = 5;                    // clip ratios evaluated together by one wavefront pass
 constexpr int FS_NRED = FS_KB * 5;          // per-lane sums a pass produces: 4 errors + 1 noise term per clip ratio
+constexpr int FS_NEXTRA = 6;                // sums a tile produces once: 3 of the unit features, then ternary / binary / reference
+constexpr int FS_NROW = FS_NRED + FS_NEXTRA;    // row of a wavefront's scratch for combining rows
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
 constexpr int FS_PREP_CHUNKS = FS_THREADS / 64;     // chunks a workgroup of the preparing kernel takes, one per wavefront
 constexpr int FS_PREP_CLEAR = FS_THREADS * 4;       // counters one of its workgroups clears
@@ -141,14 +143,14 @@ struct FitScoreArgs {
 };
 
 // LDS of a workgroup, in this order: the raw tile; s_c of the chunk's columns; per wavefront a
-// 16 x FS_NRED scratch for combining rows; the column quarters' (min, max) per row; s_c with
+// 16 x FS_NROW scratch for combining rows; the column quarters' (min, max) per row; s_c with
 // the listed columns zeroed, and the list; the quarters' fp64 sums of |w| per row; under a
 // mask, the quarters' kept counts and the tile's mask bytes.  29-31 KB at G = 128, small on
 // purpose: the fast fp32 issue rate needs five resident wavefronts per SIMD (a single
 // wavefront issues at most one vector instruction per ~5 cycles), i.e. five workgroups per CU.
 inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
-           (size_t)FS_WAVES * 16 * FS_NRED * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
+           (size_t)FS_WAVES * 16 * FS_NROW * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
            (size_t)chunk_w * sizeof(float) + (size_t)FS_HMAX * sizeof(int32_t) +
            (size_t)FS_WAVES * TILE_ROWS * sizeof(double) +
            (masked ? (size_t)FS_WAVES * TILE_ROWS * sizeof(int32_t) + mask_tile_lds_bytes(chunk_w) : 0);
@@ -379,26 +381,29 @@ __device__ __forceinline__ float wave_max_f32(float x) {
     return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
-// Sum N per-lane fp32 values over the 64 lanes (rows) of a wavefront: quads in fp32 by
-// DPP (two adds), the 16 quad sums in fp64 in row order through the wavefront's private
-// LDS scratch.  Lane j < N returns total j.  Fixed order: bit-reproducible.
+// Sums of per-lane fp32 values over the 64 lanes (rows) of a wavefront, in two steps, so that sums
+// that become ready at different times share the second.  rows_deposit: N values, quads in fp32 by
+// DPP (two adds), the 16 quad sums into columns col0 .. col0+N-1 of the wavefront's private LDS
+// scratch.  rows_collect: lane j < n returns the total of column j, the 16 quad sums in fp64 in row
+// order.  Fixed order: bit-reproducible.
 template <int N>
-__device__ __forceinline__ double rows_sum(const float (&v)[N], float* __restrict__ red, int lane) {
-    static_assert(N <= FS_NRED, "scratch row too short");
+__device__ __forceinline__ void rows_deposit(const float (&v)[N], float* __restrict__ red, int lane, int col0) {
     float qs[N];
 #pragma unroll
     for (int j = 0; j < N; ++j) qs[j] = quad_sum(v[j]);
     if ((lane & 3) == 0) {
 #pragma unroll
-        for (int j = 0; j < N; ++j) red[(lane >> 2) * FS_NRED + j] = qs[j];
+        for (int j = 0; j < N; ++j) red[(lane >> 2) * FS_NROW + col0 + j] = qs[j];
     }
+}
+__device__ __forceinline__ double rows_collect(const float* __restrict__ red, int lane, int n) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     double tot = 0.0;
-    if (lane < N) {
+    if (lane < n) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) tot += (double)red[i * FS_NRED + lane];
+        for (int i = 0; i < 16; ++i) tot += (double)red[i * FS_NROW + lane];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
@@ -435,7 +440,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     char* __restrict__ tile = smem;
     float* __restrict__ scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
     const int32_t mstride = mask_row_stride(G);
-    float2* __restrict__ gstat = reinterpret_cast<float2*>(scol + G + FS_WAVES * 16 * FS_NRED);   // [FS_WAVES][TILE_ROWS] (min, max)
+    float2* __restrict__ gstat = reinterpret_cast<float2*>(scol + G + FS_WAVES * 16 * FS_NROW);   // [FS_WAVES][TILE_ROWS] (min, max)
     float* __restrict__ sshort = reinterpret_cast<float*>(gstat + FS_WAVES * TILE_ROWS);   // s_c, 0 for the listed columns
     int32_t* __restrict__ hlist = reinterpret_cast<int32_t*>(sshort + G);   // the listed columns
     double* __restrict__ s1tab = reinterpret_cast<double*>(hlist + FS_HMAX);   // [FS_WAVES][TILE_ROWS] sum |w| of a quarter
@@ -449,7 +454,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     constexpr bool FINE = FEAT && DT == WINDQ_BF16;
     constexpr int LH_DWORDS = FINE ? FEAT_FINE_PAIRS : FEAT_BINS / 2;
     uint32_t* __restrict__ lhist = reinterpret_cast<uint32_t*>(scol + G);
-    static_assert(FS_WAVES * 16 * FS_NRED * sizeof(float) >= LH_DWORDS * sizeof(uint32_t), "histogram fits the scratch");
+    static_assert(FS_WAVES * 16 * FS_NROW * sizeof(float) >= LH_DWORDS * sizeof(uint32_t), "histogram fits the scratch");
     load_tile_raw<DT, 1>(A.W, A.g.ld, tc, G, tile);      // 256 threads: four short steps, few registers
     for (int32_t c = threadIdx.x; c < G; c += FS_THREADS) scol[c] = A.s[tc.col0 + c];
     if (MASKED) load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
@@ -550,7 +555,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
         __syncthreads();
     }
 
-    float* __restrict__ red = scol + G + wave * 16 * FS_NRED;
+    float* __restrict__ red = scol + G + wave * 16 * FS_NROW;
 
     if (FINE) {
         // (every counter at most 8192: the halves never carry)
@@ -629,10 +634,11 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
             f_cnt = lane_c < tc.nrows ? (float)cnt : 0.0f;
         }
     }
+    // The tile's sums over rows wait in the scratch (columns FS_NRED ..) for the first clip pass,
+    // whose sums they are collected with; a wavefront without a pass collects them by themselves.
+    const size_t tile_index = (size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t;
     if (FEAT) {
         const int lane_f = fresh_lane();
-        const float v3[3] = {f_sw, f_sw2, f_cnt};
-        const double m3 = rows_sum<3>(v3, red, lane_f);
         // sum |w| stays fp64: lanes through the wavefront's scratch, four at a time, then sixteen, in order
         double* __restrict__ dred = reinterpret_cast<double*>(red);
         dred[lane_f] = f_sabs;
@@ -647,23 +653,39 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        double* __restrict__ dst = A.fmoments + (((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) * FEAT_QUARTERS +
-                                                 (size_t)wave) * 4;
-        if (lane_f < 3) dst[lane_f == 2 ? 3 : lane_f] = m3;
         if (lane_f == 3) {
             double tot = 0.0;
 #pragma unroll
             for (int i = 0; i < 16; ++i) tot += dred[64 + i];
-            dst[2] = tot;
+            A.fmoments[(tile_index * FEAT_QUARTERS + (size_t)wave) * 4 + 2] = tot;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_wave_barrier();
+        const float v3[3] = {f_sw, f_sw2, f_cnt};
+        rows_deposit<3>(v3, red, lane_f, FS_NRED);
     }
-    if (!SCORE) return;
+    // what lane FS_NRED + j of a collecting wavefront does with the tile's sum j
+    // (the lane's part of an address as an unsigned 32-bit byte offset from a wave-uniform base: a
+    // 64-bit index would have its upper half carried, as a register of zeros, across the hot loops)
+    auto store_extra = [&](int lane, double tot) {
+        const uint32_t j = (uint32_t)(lane - FS_NRED);
+        if (FEAT && j < 3u) {
+            char* base = reinterpret_cast<char*>(A.fmoments + (tile_index * FEAT_QUARTERS + (size_t)wave) * 4);
+            *reinterpret_cast<double*>(base + (j == 2u ? 24u : j * 8u)) = tot;
+        }
+        if (SCORE && !ONLY8 && j - 3u < 3u) {
+            char* base = reinterpret_cast<char*>(A.partial + tile_index * (size_t)fit_score_ncand(B.K) + 4 * B.K + 3 * wave);
+            *reinterpret_cast<double*>(base + (j - 3u) * 8u) = tot;
+        }
+    };
+    if (!SCORE) {
+        const int lane_f = fresh_lane();
+        store_extra(lane_f, rows_collect(red, lane_f, FS_NROW));
+        return;
+    }
 
     const int32_t K = B.K;
-    double* __restrict__ out = A.partial + ((size_t)tc.u * (size_t)A.g.tiles_per_unit + (size_t)tc.t) *
-                                               (size_t)fit_score_ncand(K);
+    double* __restrict__ out = A.partial + tile_index * (size_t)fit_score_ncand(K);
 
     // Ternary absmean, binary sign*mean|w| and the reference energy: every wavefront scores
     // its quarter of the columns.  gamma = alpha = fp32(S1 / n), S1 = the quarters' sums of |w|
@@ -720,9 +742,9 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
         }
         const int lane_r = fresh_lane();
         if (lane_r >= tc.nrows) acc3[0] = acc3[1] = acc3[2] = 0.0f;
-        const double tot = rows_sum<3>(acc3, red, lane_r);
-        if (lane_r < 3) out[4 * K + 3 * wave + lane_r] = tot;
+        rows_deposit<3>(acc3, red, lane_r, FS_NRED + 3);
     }
+    int32_t ncollect = ONLY8 ? FS_NRED : FS_NROW;      // columns the next collection takes
 
     // The clip grid: n_kpass passes over FS_KB clip ratios each.  Pass i goes to wavefront
     // (i + rot) % 4.
@@ -870,7 +892,10 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
 #pragma unroll
                 for (int j = 0; j < FS_NRED; ++j) flat[j] = 0.0f;
             }
-            const double tot = rows_sum<FS_NRED>(flat, red, lane_r);
+            rows_deposit<FS_NRED>(flat, red, lane_r, 0);
+            const double tot = rows_collect(red, lane_r, ncollect);
+            if (!ONLY8 && ncollect > FS_NRED) store_extra(lane_r, tot);
+            ncollect = FS_NRED;
             if (lane_r < FS_KB * 4) {
                 const int k = item * FS_KB + (lane_r >> 2);
                 if (k < K && (!ONLY8 || (lane_r & 3) == 0)) out[(lane_r & 3) * K + k] = tot;
@@ -883,6 +908,10 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
                 }
             }
         }
+    }
+    if (!ONLY8 && ncollect > FS_NRED) {     // no clip pass fell to this wavefront
+        const int lane_r = fresh_lane();
+        store_extra(lane_r, rows_collect(red, lane_r, FS_NROW));
     }
 }
 

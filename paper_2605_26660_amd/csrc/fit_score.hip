@@ -565,15 +565,14 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
         // and half of it lie 0.7-2.7 octaves above the mean |w| of Gaussian to heavy-tailed
         // weights, wherever single outliers sit.
         const int lane_a = fresh_lane();
-        float amax = 0.0f;
-        double sabs = 0.0;
+        float amax = 0.0f, sabs = 0.0f;     // (the mean only places the record: fp32 will do)
 #pragma unroll
         for (int q = 0; q < FS_WAVES; ++q) {
             const float2 st = gstat[q * TILE_ROWS + lane_a];
             if (st.x <= st.y) amax = fmaxf(amax, fmaxf(fabsf(st.x), fabsf(st.y)));
-            sabs += s1tab[q * TILE_ROWS + lane_a];
+            sabs += (float)s1tab[q * TILE_ROWS + lane_a];
         }
-        const float mean = (float)wave_sum(sabs) / (float)(tc.nrows * G);
+        const float mean = wave_sum_f32(sabs) * __builtin_amdgcn_rcpf((float)(tc.nrows * G));
         const int32_t tmax = (int32_t)(__float_as_uint(wave_max_f32(amax)) >> 20);     // first-digit bin of the largest key
         const int32_t ct = (int32_t)(__float_as_uint(mean) >> 20) + 40;               // top bin of the record
         // first-digit sums into the unit's histogram: bin FEAT_FINE_COARSE0 + b is dwords 8b .. 8b+7

@@ -455,7 +455,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     constexpr int LH_DWORDS = FINE ? FEAT_FINE_PAIRS : FEAT_BINS / 2;
     uint32_t* __restrict__ lhist = reinterpret_cast<uint32_t*>(scol + G);
     static_assert(FS_WAVES * 16 * FS_NROW * sizeof(float) >= LH_DWORDS * sizeof(uint32_t), "histogram fits the scratch");
-    load_tile_raw<DT, 1>(A.W, A.g.ld, tc, G, tile);      // 256 threads: four short steps, few registers
+    load_tile_raw<DT, 2>(A.W, A.g.ld, tc, G, tile);      // 256 threads: four pieces each, two loads in flight at a time
     for (int32_t c = threadIdx.x; c < G; c += FS_THREADS) scol[c] = A.s[tc.col0 + c];
     if (MASKED) load_mask_tile(A.mask, A.mask_ld, tc, G, mtile);
     if (FEAT) {

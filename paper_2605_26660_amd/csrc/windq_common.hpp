@@ -74,12 +74,15 @@ struct TileCoord {
 // Tiles are numbered so that consecutive workgroups walk across the chunks of one band
 // of rows: a band of 64 rows is contiguous in HBM row by row, and neighbouring
 // workgroups (which land on different XCDs round-robin) share DRAM pages, not L2 lines.
+// (A matrix has fewer than 2^31 tiles, checked on the host: the two divisions are 32-bit ones.)
 __device__ __forceinline__ TileCoord tile_coord(const Geometry& g, int64_t tile) {
     TileCoord tc;
-    const int64_t j = tile % g.n_chunks;
-    const int64_t band = tile / g.n_chunks;          // band = rb * tiles_per_unit + t
-    const int64_t rb = band / g.tiles_per_unit;
-    tc.t = band - rb * g.tiles_per_unit;
+    const uint32_t nc = (uint32_t)g.n_chunks, tpu = (uint32_t)g.tiles_per_unit;
+    const uint32_t band32 = (uint32_t)tile / nc;     // band = rb * tiles_per_unit + t
+    const int64_t j = (int64_t)((uint32_t)tile - band32 * nc);
+    const uint32_t rb32 = band32 / tpu;
+    const int64_t rb = (int64_t)rb32;
+    tc.t = (int64_t)(band32 - rb32 * tpu);
     tc.u = rb * g.n_chunks + j;
     tc.lrow0 = tc.t * TILE_ROWS;
     tc.row0 = rb * g.R_u + tc.lrow0;
@@ -92,7 +95,7 @@ __device__ __forceinline__ TileCoord tile_coord(const Geometry& g, int64_t tile)
 // Tile t of unit u.
 __device__ __forceinline__ TileCoord tile_coord_of_unit(const Geometry& g, int64_t u, int64_t t) {
     TileCoord tc;
-    const int64_t rb = u / g.n_chunks;
+    const int64_t rb = (int64_t)((uint32_t)u / (uint32_t)g.n_chunks);
     const int64_t j = u - rb * g.n_chunks;
     tc.t = t;
     tc.u = u;
@@ -118,27 +121,45 @@ template <int DT, int NB = 4>
 __device__ __forceinline__ void load_tile_raw(const void* __restrict__ data, int64_t ld, const TileCoord& tc,
                                               int32_t chunk_w, char* __restrict__ tile) {
     constexpr int EB = Elem<DT>::bytes;
-    const int32_t pieces = (chunk_w * EB) >> 4;              // 16-byte pieces per row
+    const uint32_t pieces = (uint32_t)(chunk_w * EB) >> 4;   // 16-byte pieces per row
     const int32_t row_bytes = chunk_w * EB + 16;
-    const int32_t total = TILE_ROWS * pieces;
-    const char* __restrict__ base = static_cast<const char*>(data);
-    for (int32_t i0 = threadIdx.x; i0 < total; i0 += NB * blockDim.x) {
+    const int32_t total = TILE_ROWS * (int32_t)pieces;
+    const uint32_t nthreads = blockDim.x;
+    // A thread's pieces lie nthreads apart: (row, piece) of the first by one division, of the others
+    // by stepping (dr rows and dpc pieces further, one more row when the piece index wraps).
+    uint32_t r = threadIdx.x / pieces;
+    uint32_t pc = threadIdx.x - r * pieces;
+    const uint32_t dr = nthreads / pieces, dpc = nthreads - dr * pieces;          // wave-uniform
+    const int64_t row_step = ld * EB;
+    const int64_t src_step = (int64_t)dr * row_step + (int64_t)dpc * 16;
+    const int64_t src_wrap = row_step - (int64_t)pieces * 16;
+    const int32_t dst_step = (int32_t)dr * row_bytes + (int32_t)dpc * 16;
+    const int32_t dst_wrap = row_bytes - (int32_t)pieces * 16;
+    const char* __restrict__ src = static_cast<const char*>(data) + ((tc.row0 + (int64_t)r) * ld + tc.col0) * EB + (int64_t)pc * 16;
+    int32_t dst = (int32_t)r * row_bytes + (int32_t)pc * 16;
+    for (int32_t i0 = threadIdx.x; i0 < total; i0 += NB * (int32_t)nthreads) {
         uint4 v[NB];
+        int32_t at[NB];
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
-            const int32_t i = i0 + k * blockDim.x;
-            const int32_t r = i / pieces;
-            const int32_t pc = i - r * pieces;
+            const int32_t i = i0 + k * (int32_t)nthreads;
             v[k] = make_uint4(0u, 0u, 0u, 0u);
-            if (i < total && r < tc.nrows)
-                v[k] = *reinterpret_cast<const uint4*>(base + ((tc.row0 + r) * ld + tc.col0) * EB + (int64_t)pc * 16);
+            at[k] = dst;
+            if (i < total && (int32_t)r < tc.nrows) v[k] = *reinterpret_cast<const uint4*>(src);
+            r += dr;
+            pc += dpc;
+            src += src_step;
+            dst += dst_step;
+            if (pc >= pieces) {
+                pc -= pieces;
+                r += 1u;
+                src += src_wrap;
+                dst += dst_wrap;
+            }
         }
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
-            const int32_t i = i0 + k * blockDim.x;
-            const int32_t r = i / pieces;
-            const int32_t pc = i - r * pieces;
-            if (i < total) *reinterpret_cast<uint4*>(tile + r * row_bytes + pc * 16) = v[k];
+            if (i0 + k * (int32_t)nthreads < total) *reinterpret_cast<uint4*>(tile + at[k]) = v[k];
         }
     }
 }

@@ -381,6 +381,33 @@ __device__ __forceinline__ float wave_max_f32(float x) {
     return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
+// Sums of s[] and maxima of m[] over the 64 lanes, each by the steps of wave_sum_f32 / wave_max_f32
+// (the same bits), all of them advancing together: a reduction is a chain of dependent cross-lane
+// steps that a wavefront waits out one by one, and several chains side by side wait only once.
+template <int NS, int NM>
+__device__ __forceinline__ void wave_sums_maxes(float (&s)[NS], float (&m)[NM]) {
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+        const int ctrl = st == 0 ? 0xB1 : (st == 1 ? 0x4E : (st == 2 ? 0x141 : 0x140));
+#pragma unroll
+        for (int i = 0; i < NS; ++i) s[i] += dpp_f32(s[i], ctrl);
+#pragma unroll
+        for (int j = 0; j < NM; ++j) m[j] = fmaxf(m[j], dpp_f32(m[j], ctrl));
+    }
+    float rs[NS][4], rm[NM][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) rs[i][r] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s[i]), 16 * r));
+#pragma unroll
+        for (int j = 0; j < NM; ++j) rm[j][r] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m[j]), 16 * r));
+    }
+#pragma unroll
+    for (int i = 0; i < NS; ++i) s[i] = ((rs[i][0] + rs[i][1]) + rs[i][2]) + rs[i][3];
+#pragma unroll
+    for (int j = 0; j < NM; ++j) m[j] = fmaxf(fmaxf(rm[j][0], rm[j][1]), fmaxf(rm[j][2], rm[j][3]));
+}
+
 // Sums of per-lane fp32 values over the 64 lanes (rows) of a wavefront, in two steps, so that sums
 // that become ready at different times share the second.  rows_deposit: N values, quads in fp32 by
 // DPP (two adds), the 16 quad sums into columns col0 .. col0+N-1 of the wavefront's private LDS
@@ -557,23 +584,47 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
 
     float* __restrict__ red = scol + G + wave * 16 * FS_NROW;
 
+    // What a wavefront needs of the tile's rows as a whole, from the quarters' row minima, maxima and
+    // sums (every wavefront takes all 4 x 64 of them, in the same order, so none waits for another):
+    // does one row hold most of the rows' squared ranges (rows past the unit's end are zeros)?  For
+    // the record of the feature pass, the tile's largest |w| and the sum of |w| (it only places the
+    // record: fp32 will do).
+    bool rows_even = true;
+    float tile_amax = 0.0f, tile_sabs = 0.0f;
+    if (FINE || (SCORE && !ONLY8 && nh >= 0)) {
+        const int lane_t = fresh_lane();
+        float mn = INFINITY, mx = -INFINITY, sabs = 0.0f;
+#pragma unroll
+        for (int q = 0; q < FS_WAVES; ++q) {
+            const float2 st = gstat[q * TILE_ROWS + lane_t];
+            mn = fminf(mn, st.x);
+            mx = fmaxf(mx, st.y);
+            if (FINE) sabs += (float)s1tab[q * TILE_ROWS + lane_t];
+        }
+        if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
+        const float rg = mx - mn;
+        float sums[FINE ? 2 : 1], maxes[FINE ? 2 : 1];
+        sums[0] = maxes[0] = rg * rg;
+        if (FINE) {
+            sums[1] = sabs;
+            maxes[1] = fmaxf(fabsf(mn), fabsf(mx));
+        }
+        wave_sums_maxes(sums, maxes);
+        rows_even = maxes[0] * ROW_SHARE <= sums[0];
+        if (FINE) {
+            tile_sabs = sums[1];
+            tile_amax = maxes[1];
+        }
+    }
+
     if (FINE) {
         // (every counter at most 8192: the halves never carry)
-        // The tile's largest key and its mean |w|, from the quarters' row minima, maxima and sums:
-        // every wavefront takes all 4 x 64 of them, in the same order, so none waits for another.
         // The record covers the FEAT_WIN first-digit bins that end 5 octaves above the mean: P99
         // and half of it lie 0.7-2.7 octaves above the mean |w| of Gaussian to heavy-tailed
         // weights, wherever single outliers sit.
         const int lane_a = fresh_lane();
-        float amax = 0.0f, sabs = 0.0f;     // (the mean only places the record: fp32 will do)
-#pragma unroll
-        for (int q = 0; q < FS_WAVES; ++q) {
-            const float2 st = gstat[q * TILE_ROWS + lane_a];
-            if (st.x <= st.y) amax = fmaxf(amax, fmaxf(fabsf(st.x), fabsf(st.y)));
-            sabs += (float)s1tab[q * TILE_ROWS + lane_a];
-        }
-        const float mean = wave_sum_f32(sabs) * __builtin_amdgcn_rcpf((float)(tc.nrows * G));
-        const int32_t tmax = (int32_t)(__float_as_uint(wave_max_f32(amax)) >> 20);     // first-digit bin of the largest key
+        const float mean = tile_sabs * __builtin_amdgcn_rcpf((float)(tc.nrows * G));
+        const int32_t tmax = (int32_t)(__float_as_uint(tile_amax) >> 20);               // first-digit bin of the largest key
         const int32_t ct = (int32_t)(__float_as_uint(mean) >> 20) + 40;               // top bin of the record
         // first-digit sums into the unit's histogram: bin FEAT_FINE_COARSE0 + b is dwords 8b .. 8b+7
         uint32_t* __restrict__ gh = A.fhist + (size_t)tc.u * FEAT_BINS;
@@ -764,13 +815,6 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
             if (mn > mx) mn = mx = 0.0f;      // no weight of the group is kept
             // zero inside the closed range of every group of the wavefront?
             const bool anchored = __builtin_amdgcn_ballot_w64(!(mn <= 0.0f && mx >= 0.0f)) == 0;
-            // does one row hold most of the rows' squared ranges?  (rows past the unit's end are zeros)
-            bool rows_even = true;
-            if (!ONLY8 && nh >= 0) {
-                const float rg = mx - mn;
-                const float rg2 = rg * rg;
-                rows_even = wave_max_f32(rg2) * ROW_SHARE <= wave_sum_f32(rg2);
-            }
             KParams P[FS_KB];
             float acc[FS_KB][4];
 #pragma unroll

@@ -23,9 +23,9 @@
 //           features.
 //   exact   a unit whose bins lie outside the record of one of its tiles (P99 or its half
 //           far from 1.6-3.2 times that tile's mean |w|), or whose P99 lies outside the range the tile kernel
-//           resolves (below 2^-20 or above 13.5), is listed by the finish kernel; a last kernel
-//           takes the listed units one workgroup each, selects P99 by two digit passes over the
-//           unit and counts in a third.  It reads W only for such units.
+//           resolves (below 2^-20 or above 13.5), is counted and listed (for the caller to ask about),
+//           and the workgroup that finishes it goes on to select P99 by two digit passes over the
+//           unit's weights and to count in a third.  W is read only for such units.
 // fp32 (31-bit keys, digits 11 + 11 + 9): one pass per further digit plus a counting pass
 // (2|w| > P99, exact in fp32), each re-deriving the prefix from the finished histograms.
 // Passes after the first re-read a matrix that was just streamed; up to the 256 MB
@@ -255,6 +255,69 @@ __device__ __forceinline__ void block_sum_n(double (&v)[N], double* red) {
     }
 }
 
+// bf16: a unit whose P99 the tiles' records do not decide, by the workgroup that finishes it.  P99 by
+// two digit passes over the unit's keys (8 + 7 bits), then the count of keys above the key of
+// 0.5 * P99: feature 4, the only one that depends on P99.  Called by all threads of the workgroup.
+__device__ __forceinline__ void feat_exact_bf16_unit(const FeatArgs& A, int64_t u, uint32_t* h, uint32_t* sh_part,
+                                                     uint32_t* sh_out, uint32_t* wsum) {
+    static_assert(FT_THREADS == 256, "one thread per bin of the first digit");
+    const int tid = threadIdx.x;
+    const int32_t G = A.g.chunk_w;
+    const int32_t pieces = G >> 3;
+    const int64_t total = A.g.R_u * pieces;
+    const uint16_t* __restrict__ Wp = static_cast<const uint16_t*>(A.W);
+    const int64_t rb = u / A.g.n_chunks;
+    const int64_t col0 = (u - rb * A.g.n_chunks) * G;
+    const int64_t row0 = rb * A.g.R_u;
+    // calls f(key) for every weight of the unit
+    auto sweep = [&](auto f) {
+        for (int64_t i = tid; i < total; i += FT_THREADS) {
+            const int64_t r = i / pieces;
+            const int64_t pc = i - r * pieces;
+            const uint4 raw = *reinterpret_cast<const uint4*>(Wp + (row0 + r) * A.g.ld + col0 + pc * 8);
+            const uint32_t x[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f(x[j] & 0x7fffu);
+                f((x[j] >> 16) & 0x7fffu);
+            }
+        }
+    };
+    __syncthreads();
+    h[tid] = 0u;
+    __syncthreads();
+    sweep([&](uint32_t key) { atomicAdd(&h[key >> 7], 1u); });
+    __syncthreads();
+    uint32_t d0, d1;
+    uint64_t below;
+    select_bin<FT_THREADS>(h, 256, A.rank, sh_part, sh_out, &d0, &below);
+    const uint64_t rank1 = A.rank - below;
+    __syncthreads();
+    h[tid] = 0u;
+    __syncthreads();
+    sweep([&](uint32_t key) {
+        if ((key >> 7) == d0) atomicAdd(&h[key & 127u], 1u);
+    });
+    __syncthreads();
+    select_bin<FT_THREADS>(h, 128, rank1, sh_part, sh_out, &d1, &below);
+    // Key of 0.5 * P99: one exponent step down, or half the key where keys are linear in
+    // the value (below 256: subnormals and the first binade).
+    const uint32_t pk = (d0 << 7) | d1;
+    const uint32_t tk = pk >= 256u ? pk - 128u : pk >> 1;
+    uint32_t cnt = 0;
+    sweep([&](uint32_t key) { cnt += key > tk ? 1u : 0u; });
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) cnt += __shfl_xor(cnt, m, 64);
+    __syncthreads();
+    if ((tid & 63) == 0) wsum[tid >> 6] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t above = 0;
+        for (int w = 0; w < FT_WAVES; ++w) above += wsum[w];
+        A.feat[u * WINDQ_N_FEAT + 4] = (float)((double)above / ((double)A.g.R_u * (double)G));
+    }
+}
+
 // Per unit: P99's key from the finished histograms, the count above half of it, the
 // moments in block order, the statistics of s over the chunk; writes the eight features.
 // The kernel is a chain of memory latencies (32-86 workgroups, nothing to overlap them
@@ -394,78 +457,10 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
         f[6] = (float)sqrt(sdev / (double)G);
         f[7] = mx;
     }
-}
-
-// bf16: the units the finish kernel listed, one workgroup each (workgroups stride over the lists
-// of the launch's matrices).  P99 by two digit passes over the unit's keys (8 + 7 bits), then the
-// count of keys above the key of 0.5 * P99: feature 4, the only one that depends on P99.
-constexpr int FEAT_EXACT_GRID = 256;
-__global__ __launch_bounds__(FT_THREADS) void feat_exact_bf16_kernel(const FeatBatch B) {
-    __shared__ uint32_t h[256];
-    __shared__ uint32_t sh_part[FT_THREADS];
-    __shared__ uint32_t sh_out[4];
-    __shared__ uint32_t wsum[FT_WAVES];
-    const int tid = threadIdx.x;
-    for (int mi = 0; mi < B.n; ++mi) {
-        const FeatArgs& A = B.m[mi];
-        const uint32_t n_listed = *A.list_count;
-        const int32_t G = A.g.chunk_w;
-        const int32_t pieces = G >> 3;
-        const int64_t total = A.g.R_u * pieces;
-        const uint16_t* __restrict__ Wp = static_cast<const uint16_t*>(A.W);
-        for (uint32_t l = blockIdx.x; l < n_listed; l += gridDim.x) {
-            const int64_t u = A.list[l];
-            const int64_t rb = u / A.g.n_chunks;
-            const int64_t col0 = (u - rb * A.g.n_chunks) * G;
-            const int64_t row0 = rb * A.g.R_u;
-            // calls f(key) for every weight of the unit
-            auto sweep = [&](auto f) {
-                for (int64_t i = tid; i < total; i += FT_THREADS) {
-                    const int64_t r = i / pieces;
-                    const int64_t pc = i - r * pieces;
-                    const uint4 raw = *reinterpret_cast<const uint4*>(Wp + (row0 + r) * A.g.ld + col0 + pc * 8);
-                    const uint32_t x[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        f(x[j] & 0x7fffu);
-                        f((x[j] >> 16) & 0x7fffu);
-                    }
-                }
-            };
-            h[tid] = 0u;
-            __syncthreads();
-            sweep([&](uint32_t key) { atomicAdd(&h[key >> 7], 1u); });
-            __syncthreads();
-            uint32_t d0, d1;
-            uint64_t below;
-            select_bin<FT_THREADS>(h, 256, A.rank, sh_part, sh_out, &d0, &below);
-            const uint64_t rank1 = A.rank - below;
-            __syncthreads();
-            h[tid] = 0u;
-            __syncthreads();
-            sweep([&](uint32_t key) {
-                if ((key >> 7) == d0) atomicAdd(&h[key & 127u], 1u);
-            });
-            __syncthreads();
-            select_bin<FT_THREADS>(h, 128, rank1, sh_part, sh_out, &d1, &below);
-            // Key of 0.5 * P99: one exponent step down, or half the key where keys are linear in
-            // the value (below 256: subnormals and the first binade).
-            const uint32_t pk = (d0 << 7) | d1;
-            const uint32_t tk = pk >= 256u ? pk - 128u : pk >> 1;
-            uint32_t cnt = 0;
-            sweep([&](uint32_t key) { cnt += key > tk ? 1u : 0u; });
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) cnt += __shfl_xor(cnt, m, 64);
-            __syncthreads();
-            if ((tid & 63) == 0) wsum[tid >> 6] = cnt;
-            __syncthreads();
-            if (tid == 0) {
-                uint64_t above = 0;
-                for (int w = 0; w < FT_WAVES; ++w) above += wsum[w];
-                A.feat[u * WINDQ_N_FEAT + 4] = (float)((double)above / ((double)A.g.R_u * (double)G));
-            }
-            __syncthreads();
-        }
+    if (DT == WINDQ_BF16 && listed) {          // (the same decision in every thread)
+        __shared__ uint32_t xh[256];
+        __shared__ uint32_t xsum[FT_WAVES];
+        feat_exact_bf16_unit(A, u, xh, sh_part, sh_out, xsum);
     }
 }
 
@@ -473,7 +468,6 @@ template <int DT>
 static int launch_rest(const FeatBatch& B, hipStream_t hs) {
     if (DT == WINDQ_BF16) {
         hipLaunchKernelGGL((feat_finish_kernel<DT>), dim3((unsigned)B.units_total), dim3(FT_THREADS), 0, hs, B);
-        hipLaunchKernelGGL(feat_exact_bf16_kernel, dim3(FEAT_EXACT_GRID), dim3(FT_THREADS), 0, hs, B);
     } else {
         const dim3 blocks((unsigned)B.blocks_total);
         hipLaunchKernelGGL((feat_pass_kernel<DT, 1>), blocks, dim3(FT_THREADS), 0, hs, B, 1);

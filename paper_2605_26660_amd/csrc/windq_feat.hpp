@@ -54,7 +54,7 @@ int features_fill(const FeatItem* items, int32_t n, int32_t chunk_w, int64_t uni
 int features_launch_init(const FeatBatch& B, hipStream_t hs);
 // The first pass by itself: per tile, moments, counts and the first-digit histogram.  (fit_score.hip)
 int features_launch_tiles(const FeatBatch& B, hipStream_t hs);
-// Everything after the first pass: bf16, the finish kernel and the exact pass over the units it lists;
+// Everything after the first pass: bf16, the finish kernel (with the exact pass over the units it lists);
 // fp32, the refining passes and the finish kernel.  (unit_features.hip)
 int features_launch_rest(const FeatBatch& B, hipStream_t hs);
 

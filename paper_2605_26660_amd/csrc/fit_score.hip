@@ -368,21 +368,8 @@ __device__ __forceinline__ float wave_sum_f32(float x) {
     return ((r0 + r1) + r2) + r3;
 }
 
-// Largest x over the 64 lanes, by the same steps.
-__device__ __forceinline__ float wave_max_f32(float x) {
-    x = fmaxf(x, dpp_f32(x, 0xB1));
-    x = fmaxf(x, dpp_f32(x, 0x4E));
-    x = fmaxf(x, dpp_f32(x, 0x141));
-    x = fmaxf(x, dpp_f32(x, 0x140));
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
-    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
-}
-
-// Sums of s[] and maxima of m[] over the 64 lanes, each by the steps of wave_sum_f32 / wave_max_f32
-// (the same bits), all of them advancing together: a reduction is a chain of dependent cross-lane
+// Sums of s[] and maxima of m[] over the 64 lanes, each by the steps of wave_sum_f32 (the same bits
+// for a sum), all of them advancing together: a reduction is a chain of dependent cross-lane
 // steps that a wavefront waits out one by one, and several chains side by side wait only once.
 template <int NS, int NM>
 __device__ __forceinline__ void wave_sums_maxes(float (&s)[NS], float (&m)[NM]) {

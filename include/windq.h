@@ -230,8 +230,9 @@ int windq_unit_features_batch(const windq_feat_item* items /*HOST [n]*/, int32_t
                               void* stream);
 
 /*
- * windq_fit_score_all_bits for up to WINDQ_MAX_BATCH matrices in ONE launch (plus one finalize
- * launch): the matrices of a decoder block are small against this GPU, and a launch per matrix
+ * windq_fit_score_all_bits for up to WINDQ_MAX_BATCH matrices with ONE launch of the scoring
+ * kernel (and of each small kernel around it: one that prepares, per-unit sums, the second 8-bit
+ * pass): the matrices of a decoder block are small against this GPU, and a launch per matrix
  * leaves it partly empty at every start and end.  Item i is one per-matrix call: the same
  * arguments, the same workspace size, and bit for bit the same results.  All items share chunk_w,
  * unit_rows, the clip grid and the element type.  `items` is a HOST array read during the call.
@@ -387,7 +388,7 @@ int windq_salient_encode(const windq_mat* W, const float* s /*[cols]*/, int32_t 
 /*
  * windq_salient_select / windq_salient_encode for up to WINDQ_MAX_BATCH matrices with one
  * launch per kernel instead of one per kernel and matrix (a decoder block has seven
- * matrices: ten launches to select, four to encode).  Results are bit-identical to the
+ * matrices: twelve launches to select, four to encode).  Results are bit-identical to the
  * per-matrix calls.  One chunk width, unit_rows, rate and element type for all items; every
  * item brings its own workspace (WINDQ_CALL_SALIENT for its shape).  select reads W, s and
  * writes mask; encode reads W, s, mask and writes prot_codes, prot_scale, err_prot (select

@@ -193,8 +193,9 @@ __device__ __forceinline__ void sal_hist_tile(const SalArgs& A, const TileCoord&
     const uint32_t dmask = (1u << bits) - 1u;
     const int32_t pieces = G >> 3;
     const int32_t total = tc.nrows * pieces;
-    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS) {
-        const int32_t r = i / pieces, pc = i - r * pieces;
+    PieceWalk at((int32_t)threadIdx.x, SAL_THREADS, pieces);
+    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS, at.next()) {
+        const int32_t r = at.r, pc = at.pc;
         float w[8];
         load8g<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + pc * 8, w);
 #pragma unroll
@@ -268,8 +269,9 @@ __device__ __forceinline__ void sal_count_tile(const SalArgs& A, const TileCoord
     const int32_t pieces = G >> 3;
     const int32_t total = tc.nrows * pieces;
     uint32_t eq = 0;
-    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS) {
-        const int32_t r = i / pieces, pc = i - r * pieces;
+    PieceWalk at((int32_t)threadIdx.x, SAL_THREADS, pieces);
+    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS, at.next()) {
+        const int32_t r = at.r, pc = at.pc;
         float w[8];
         load8g<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + pc * 8, w);
 #pragma unroll
@@ -338,10 +340,11 @@ __device__ __forceinline__ void sal_mask_tile(const SalArgs& A, const TileCoord&
     __syncthreads();
     const int32_t pieces = G >> 3;
     const int32_t total = tc.nrows * pieces;
-    for (int32_t i0 = 0; i0 < total; i0 += SAL_THREADS) {
+    PieceWalk at((int32_t)threadIdx.x, SAL_THREADS, pieces);
+    for (int32_t i0 = 0; i0 < total; i0 += SAL_THREADS, at.next()) {
         const int32_t i = i0 + threadIdx.x;
         const bool valid = i < total;
-        const int32_t r = i / pieces, pc = i - r * pieces;
+        const int32_t r = at.r, pc = at.pc;
         uint32_t key[8];
         uint32_t eq = 0;
         if (valid) {
@@ -424,24 +427,26 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_cand_kernel(const SalBatch B)
     __syncthreads();
     const int32_t pieces = G >> 3;
     const int32_t total = tc.nrows * pieces;
+    PieceWalk walk((int32_t)threadIdx.x, SAL_THREADS, pieces);
     for (int32_t i0 = 0; i0 < total; i0 += SAL_CAND_ITERS * SAL_THREADS) {
         Raw8<DT> raw[SAL_CAND_ITERS];           // kept as loaded: the keys of a candidate piece are formed again
         uint32_t cm[SAL_CAND_ITERS];            // which of a piece's eight keys are candidates
+        int32_t rk[SAL_CAND_ITERS], pk[SAL_CAND_ITERS];      // row and piece of each
         uint32_t n_mine = 0;
 #pragma unroll
         for (int k = 0; k < SAL_CAND_ITERS; ++k) {
             const int32_t i = i0 + k * SAL_THREADS + (int32_t)threadIdx.x;
-            if (i < total) {
-                const int32_t r = i / pieces, pc = i - r * pieces;
-                raw[k] = load8raw<DT>(A.W, (tc.row0 + r) * A.g.ld + tc.col0 + pc * 8);
-            }
+            rk[k] = walk.r;
+            pk[k] = walk.pc;
+            walk.next();
+            if (i < total) raw[k] = load8raw<DT>(A.W, (tc.row0 + rk[k]) * A.g.ld + tc.col0 + pk[k] * 8);
         }
 #pragma unroll
         for (int k = 0; k < SAL_CAND_ITERS; ++k) {
             const int32_t i = i0 + k * SAL_THREADS + (int32_t)threadIdx.x;
             cm[k] = 0u;
             if (i < total) {
-                const int32_t r = i / pieces, pc = i - r * pieces;
+                const int32_t r = rk[k], pc = pk[k];
                 float w[8];
                 unpack8raw<DT>(raw[k], w);
                 uint32_t byte = 0;
@@ -466,8 +471,7 @@ __global__ __launch_bounds__(SAL_THREADS) void sal_cand_kernel(const SalBatch B)
 #pragma unroll
         for (int k = 0; k < SAL_CAND_ITERS; ++k) {
             if (cm[k] != 0u) {
-                const int32_t i = i0 + k * SAL_THREADS + (int32_t)threadIdx.x;
-                const int32_t r = i / pieces, pc = i - r * pieces;
+                const int32_t r = rk[k], pc = pk[k];
                 const uint32_t pos0 = (uint32_t)(tc.lrow0 + r) * (uint32_t)G + (uint32_t)pc * 8u;
                 for (uint32_t m = cm[k]; m != 0u; m &= m - 1u) {        // usually one bit
                     const int j = __ffs(m) - 1;
@@ -741,8 +745,9 @@ __global__ __launch_bounds__(SAL_THREADS) void unit_saliency_tile_kernel(const v
     const int32_t pieces = G >> 3;
     const int32_t total = tc.nrows * pieces;
     double acc = 0.0;
-    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS) {
-        const int32_t r = i / pieces, pc = i - r * pieces;
+    PieceWalk at((int32_t)threadIdx.x, SAL_THREADS, pieces);
+    for (int32_t i = threadIdx.x; i < total; i += SAL_THREADS, at.next()) {
+        const int32_t r = at.r, pc = at.pc;
         float w[8];
         load8g<DT>(W, (tc.row0 + r) * g.ld + tc.col0 + pc * 8, w);
 #pragma unroll

@@ -112,6 +112,27 @@ struct Elem {
     static constexpr int bytes = DT == WINDQ_BF16 ? 2 : 4;
 };
 
+// The pieces first, first + stride, first + 2 stride, ... of a tile whose rows hold `pieces` pieces each:
+// row and piece in the row by stepping (one division at the start instead of one per piece).
+struct PieceWalk {
+    int32_t r, pc;                  // row of the tile, piece in the row
+    int32_t dr, dpc, pieces;
+    __device__ __forceinline__ PieceWalk(int32_t first, int32_t stride, int32_t pieces_per_row) : pieces(pieces_per_row) {
+        r = (int32_t)((uint32_t)first / (uint32_t)pieces);
+        pc = first - r * pieces;
+        dr = (int32_t)((uint32_t)stride / (uint32_t)pieces);
+        dpc = stride - dr * pieces;
+    }
+    __device__ __forceinline__ void next() {
+        r += dr;
+        pc += dpc;
+        if (pc >= pieces) {
+            pc -= pieces;
+            ++r;
+        }
+    }
+};
+
 // Cooperative load of one tile into LDS, element type unchanged.  Each thread moves 16
 // bytes per step; 16 (bf16, chunk 128) neighbouring threads cover one contiguous row
 // segment.  Rows past the end of the unit are filled with zeros.

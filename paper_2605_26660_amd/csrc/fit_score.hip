@@ -71,6 +71,9 @@ constexpr int FS_KB = 5;                    // clip ratios evaluated together by
 constexpr int FS_NRED = FS_KB * 5;          // per-lane sums a pass produces: 4 errors + 1 noise term per clip ratio
 constexpr int FS_NEXTRA = 6;                // sums a tile produces once: 3 of the unit features, then ternary / binary / reference
 constexpr int FS_NROW = FS_NRED + FS_NEXTRA;    // row of a wavefront's scratch for combining rows
+// (Under a mask there are no feature sums, and the row is three columns shorter: with the mask bytes the
+// workgroup's LDS would otherwise pass the 32 KB that let five workgroups share a CU.)
+__host__ __device__ constexpr int fs_nrow(bool masked) { return masked ? FS_NRED + 3 : FS_NROW; }
 constexpr float RNE_POS = 8388608.0f;       // 2^23: x + 2^23 rounds x >= 0 to the nearest-even integer
 constexpr int FS_PREP_CHUNKS = FS_THREADS / 64;     // chunks a workgroup of the preparing kernel takes, one per wavefront
 constexpr int FS_PREP_CLEAR = FS_THREADS * 4;       // counters one of its workgroups clears
@@ -145,15 +148,16 @@ struct FitScoreArgs {
 // LDS of a workgroup, in this order: the raw tile; s_c of the chunk's columns; per wavefront a
 // 16 x FS_NROW scratch for combining rows; the column quarters' (min, max) per row; s_c with
 // the listed columns zeroed, and the list; the quarters' fp64 sums of |w| per row; under a
-// mask, the quarters' kept counts and the tile's mask bytes.  29-31 KB at G = 128, small on
+// mask, the quarters' kept counts (16 bits each) and the tile's mask bytes.  30.0 KB at G = 128
+// (bf16), 31.75 KB under a mask: within the 32 KB that let five workgroups share a CU's 160 KB, on
 // purpose: the fast fp32 issue rate needs five resident wavefronts per SIMD (a single
-// wavefront issues at most one vector instruction per ~5 cycles), i.e. five workgroups per CU.
+// wavefront issues at most one vector instruction per ~5 cycles).
 inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = false) {
     return raw_tile_lds_bytes(dtype, chunk_w) + (size_t)chunk_w * sizeof(float) +
-           (size_t)FS_WAVES * 16 * FS_NROW * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
+           (size_t)FS_WAVES * 16 * fs_nrow(masked) * sizeof(float) + (size_t)FS_WAVES * TILE_ROWS * 2 * sizeof(float) +
            (size_t)chunk_w * sizeof(float) + (size_t)FS_HMAX * sizeof(int32_t) +
            (size_t)FS_WAVES * TILE_ROWS * sizeof(double) +
-           (masked ? (size_t)FS_WAVES * TILE_ROWS * sizeof(int32_t) + mask_tile_lds_bytes(chunk_w) : 0);
+           (masked ? (size_t)FS_WAVES * TILE_ROWS * sizeof(uint16_t) + mask_tile_lds_bytes(chunk_w) : 0);
 }
 
 // The 8-bit residual is ~1/500 of the range, so it is taken relative to an ANCHOR c: a grid
@@ -400,16 +404,17 @@ __device__ __forceinline__ void wave_sums_maxes(float (&s)[NS], float (&m)[NM]) 
 // DPP (two adds), the 16 quad sums into columns col0 .. col0+N-1 of the wavefront's private LDS
 // scratch.  rows_collect: lane j < n returns the total of column j, the 16 quad sums in fp64 in row
 // order.  Fixed order: bit-reproducible.
-template <int N>
+template <int NROW, int N>
 __device__ __forceinline__ void rows_deposit(const float (&v)[N], float* __restrict__ red, int lane, int col0) {
     float qs[N];
 #pragma unroll
     for (int j = 0; j < N; ++j) qs[j] = quad_sum(v[j]);
     if ((lane & 3) == 0) {
 #pragma unroll
-        for (int j = 0; j < N; ++j) red[(lane >> 2) * FS_NROW + col0 + j] = qs[j];
+        for (int j = 0; j < N; ++j) red[(lane >> 2) * NROW + col0 + j] = qs[j];
     }
 }
+template <int NROW>
 __device__ __forceinline__ double rows_collect(const float* __restrict__ red, int lane, int n) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
@@ -417,7 +422,7 @@ __device__ __forceinline__ double rows_collect(const float* __restrict__ red, in
     double tot = 0.0;
     if (lane < n) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) tot += (double)red[i * FS_NROW + lane];
+        for (int i = 0; i < 16; ++i) tot += (double)red[i * NROW + lane];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
@@ -454,11 +459,13 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     char* __restrict__ tile = smem;
     float* __restrict__ scol = reinterpret_cast<float*>(smem + TILE_ROWS * row_bytes);
     const int32_t mstride = mask_row_stride(G);
-    float2* __restrict__ gstat = reinterpret_cast<float2*>(scol + G + FS_WAVES * 16 * FS_NROW);   // [FS_WAVES][TILE_ROWS] (min, max)
+    constexpr int NROW = fs_nrow(MASKED);          // row of the scratch; its last three columns: ternary / binary / reference
+    constexpr int ACC3_COL = NROW - 3;
+    float2* __restrict__ gstat = reinterpret_cast<float2*>(scol + G + FS_WAVES * 16 * NROW);   // [FS_WAVES][TILE_ROWS] (min, max)
     float* __restrict__ sshort = reinterpret_cast<float*>(gstat + FS_WAVES * TILE_ROWS);   // s_c, 0 for the listed columns
     int32_t* __restrict__ hlist = reinterpret_cast<int32_t*>(sshort + G);   // the listed columns
     double* __restrict__ s1tab = reinterpret_cast<double*>(hlist + FS_HMAX);   // [FS_WAVES][TILE_ROWS] sum |w| of a quarter
-    int32_t* __restrict__ nktab = reinterpret_cast<int32_t*>(s1tab + FS_WAVES * TILE_ROWS);   // kept weights of a quarter (masked)
+    uint16_t* __restrict__ nktab = reinterpret_cast<uint16_t*>(s1tab + FS_WAVES * TILE_ROWS);   // kept weights of a quarter (masked): <= 128
     uint8_t* __restrict__ mtile = reinterpret_cast<uint8_t*>(nktab + (MASKED ? FS_WAVES * TILE_ROWS : 0));
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: lives in a scalar register
 
@@ -468,7 +475,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     constexpr bool FINE = FEAT && DT == WINDQ_BF16;
     constexpr int LH_DWORDS = FINE ? FEAT_FINE_PAIRS : FEAT_BINS / 2;
     uint32_t* __restrict__ lhist = reinterpret_cast<uint32_t*>(scol + G);
-    static_assert(FS_WAVES * 16 * FS_NROW * sizeof(float) >= LH_DWORDS * sizeof(uint32_t), "histogram fits the scratch");
+    static_assert(!FEAT || FS_WAVES * 16 * NROW * sizeof(float) >= LH_DWORDS * sizeof(uint32_t), "histogram fits the scratch");
     // Everything around the clip sweeps waits a lot (loads, barriers, cross-lane chains, the parameters'
     // divisions) and issues little: it runs at a raised wave priority, so that it is over sooner and the
     // SIMD's other wavefronts, in their sweeps, lose only the few issue slots it needs (1.2 % faster).
@@ -567,13 +574,13 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
         gstat[wave * TILE_ROWS + lane_s] = make_float2(mn, mx);
         if (!ONLY8) {
             s1tab[wave * TILE_ROWS + lane_s] = S1;
-            if (MASKED) nktab[wave * TILE_ROWS + lane_s] = nk;
+            if (MASKED) nktab[wave * TILE_ROWS + lane_s] = (uint16_t)nk;
         }
         if (FEAT) f_sabs = S1;
         __syncthreads();
     }
 
-    float* __restrict__ red = scol + G + wave * 16 * FS_NROW;
+    float* __restrict__ red = scol + G + wave * 16 * NROW;
 
     // What a wavefront needs of the tile's rows as a whole, from the quarters' row minima, maxima and
     // sums (every wavefront takes all 4 x 64 of them, in the same order, so none waits for another):
@@ -703,7 +710,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_wave_barrier();
         const float v3[3] = {f_sw, f_sw2, f_cnt};
-        rows_deposit<3>(v3, red, lane_f, FS_NRED);
+        rows_deposit<NROW>(v3, red, lane_f, FS_NRED);
     }
     // what lane FS_NRED + j of a collecting wavefront does with the tile's sum j
     // (the lane's part of an address as an unsigned 32-bit byte offset from a wave-uniform base: a
@@ -714,14 +721,15 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
             char* base = reinterpret_cast<char*>(A.fmoments + (tile_index * FEAT_QUARTERS + (size_t)wave) * 4);
             *reinterpret_cast<double*>(base + (j == 2u ? 24u : j * 8u)) = tot;
         }
-        if (SCORE && !ONLY8 && j - 3u < 3u) {
+        const uint32_t j3 = (uint32_t)(lane - ACC3_COL);
+        if (SCORE && !ONLY8 && j3 < 3u) {
             char* base = reinterpret_cast<char*>(A.partial + tile_index * (size_t)fit_score_ncand(B.K) + 4 * B.K + 3 * wave);
-            *reinterpret_cast<double*>(base + (j - 3u) * 8u) = tot;
+            *reinterpret_cast<double*>(base + j3 * 8u) = tot;
         }
     };
     if (!SCORE) {
         const int lane_f = fresh_lane();
-        store_extra(lane_f, rows_collect(red, lane_f, FS_NROW));
+        store_extra(lane_f, rows_collect<NROW>(red, lane_f, NROW));
         return;
     }
 
@@ -742,7 +750,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
 #pragma unroll
         for (int q = 0; q < FS_WAVES; ++q) {
             S1 += s1tab[q * TILE_ROWS + lane_w];
-            if (MASKED) n_kept += nktab[q * TILE_ROWS + lane_w];
+            if (MASKED) n_kept += (int32_t)nktab[q * TILE_ROWS + lane_w];
         }
         // n is the chunk width unless weights are masked out; the product with its reciprocal (from
         // the host) rounds to the same fp32 as the quotient, but for ~1e-9 of groups when G is not 2^k
@@ -783,9 +791,9 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
         }
         const int lane_r = fresh_lane();
         if (lane_r >= tc.nrows) acc3[0] = acc3[1] = acc3[2] = 0.0f;
-        rows_deposit<3>(acc3, red, lane_r, FS_NRED + 3);
+        rows_deposit<NROW>(acc3, red, lane_r, ACC3_COL);
     }
-    int32_t ncollect = ONLY8 ? FS_NRED : FS_NROW;      // columns the next collection takes
+    int32_t ncollect = ONLY8 ? FS_NRED : NROW;         // columns the next collection takes
 
     // The clip grid: n_kpass passes over FS_KB clip ratios each.  Pass i goes to wavefront
     // (i + rot) % 4.
@@ -928,8 +936,8 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
 #pragma unroll
                 for (int j = 0; j < FS_NRED; ++j) flat[j] = 0.0f;
             }
-            rows_deposit<FS_NRED>(flat, red, lane_r, 0);
-            const double tot = rows_collect(red, lane_r, ncollect);
+            rows_deposit<NROW>(flat, red, lane_r, 0);
+            const double tot = rows_collect<NROW>(red, lane_r, ncollect);
             if (!ONLY8 && ncollect > FS_NRED) store_extra(lane_r, tot);
             ncollect = FS_NRED;
             if (lane_r < FS_KB * 4) {
@@ -947,7 +955,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
     }
     if (!ONLY8 && ncollect > FS_NRED) {     // no clip pass fell to this wavefront
         const int lane_r = fresh_lane();
-        store_extra(lane_r, rows_collect(red, lane_r, FS_NROW));
+        store_extra(lane_r, rows_collect<NROW>(red, lane_r, NROW));
     }
 }
 

@@ -45,7 +45,12 @@
 //                scores the 8-bit candidates of the listed units again, exact route only,
 //                and finalizes them again.  With nothing listed those launches end at once.
 //   * lanes accumulate in fp32 over the chunk's columns only (<= 512 terms); rows are
-//     combined in fp64 in a fixed order (LDS transpose), tiles by the finalize kernel.
+//     combined in fp64 in a fixed order (LDS transpose), tiles by the finalize kernel;
+//   * what depends on s alone (the column list, s_c of the other columns) is prepared once per
+//     chunk by a small kernel ahead of the tiles, which copy it into LDS with their load;
+//   * the phases around the sweeps wait more than they issue (loads, barriers, cross-lane
+//     chains): they run at a raised wave priority, so that a SIMD's other wavefronts, which are
+//     in their sweeps, give up only the few issue slots those phases need.
 // Rounding decisions here are taken on x*(2^b-1); windq_apply_plan takes them on
 // (w-lo)*(1/step) in fp32.  Where they differ the weight sits within ~3e-5 steps of a
 // rounding boundary, where both codes give the same squared error to ~1e-4 of itself,

@@ -352,11 +352,13 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
     bool listed = false;        // bf16: left to the exact pass
     if (DT == WINDQ_BF16) {
         __shared__ uint32_t sub[32];          // full-resolution counters of bins e0 and e0 - 8
-        __shared__ uint32_t wsub[FT_WAVES * 32];
+        __shared__ uint32_t tcnt[FT_THREADS * 33];
         __shared__ int miss;
         uint32_t e0, l1;
         uint64_t rank1, below;
         if (tid == 0) miss = 0;
+        // (requested ahead of the selection, like the moments: where this thread's first tile's record lies)
+        const uint32_t an_first = tid < A.g.tiles_per_unit ? A.anchor[(size_t)u * (size_t)A.g.tiles_per_unit + (size_t)tid] : 0u;
         select_prefix<DT>(A, u, 1, sh_part, sh_out, &e0, &rank1);       // (its barriers publish the zero)
         const uint32_t eh = half_bin_of(e0);
         // both bins inside the range the tile kernel resolves key by key?
@@ -367,7 +369,7 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
         if (resolved) {
             for (int64_t t = tid; t < A.g.tiles_per_unit; t += FT_THREADS) {
                 const size_t tidx = (size_t)u * (size_t)A.g.tiles_per_unit + (size_t)t;
-                const uint32_t an = A.anchor[tidx];
+                const uint32_t an = t == tid ? an_first : A.anchor[tidx];
                 const uint32_t ct = an & 0xffffu, tmax = an >> 16;     // record = bins ct - 63 .. ct; nothing above tmax
                 const uint32_t* __restrict__ rec = A.fine + tidx * (FEAT_WIN * 8);
 #pragma unroll
@@ -389,19 +391,17 @@ __global__ __launch_bounds__(FT_THREADS) void feat_finish_kernel(const FeatBatch
                 }
             }
         }
-        // threads by butterfly, wavefronts through LDS
+        // the threads that took tiles lay their counters out in LDS (rows of 33: no bank shared by a
+        // column), and thread k adds up column k (a butterfly of 32 x 6 shuffles took several times as long)
+        const int nact = A.g.tiles_per_unit < (int64_t)FT_THREADS ? (int)A.g.tiles_per_unit : FT_THREADS;
+        if (tid < nact) {
 #pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            uint32_t v = cnt[k];
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-            if ((tid & 63) == 0) wsub[(tid >> 6) * 32 + k] = v;
+            for (int k = 0; k < 32; ++k) tcnt[tid * 33 + k] = cnt[k];
         }
         __syncthreads();
         if (tid < 32) {
             uint32_t v = 0;
-#pragma unroll
-            for (int w = 0; w < FT_WAVES; ++w) v += wsub[w * 32 + tid];
+            for (int r = 0; r < nact; ++r) v += tcnt[r * 33 + tid];
             sub[tid] = v;
         }
         __syncthreads();

@@ -277,6 +277,8 @@ def test_masked_batches_equal_single_prot_calls(windq, dtype):
     (8, 0, 3, [(16, 24), (8, 8)]),
     (512, 0, 5, [(72, 1024)]),
     (256, 100, 40, [(300, 256)]),
+    (128, 0, 21, [(256, 256), (100, 128)]),        # two clip passes on one wavefront of a tile, one on the others
+    (64, 64, 64, [(128, 128)]),                    # the largest grid
 ])
 def test_fused_features_fit_score_equals_the_separate_calls(windq, dtype, G, unit_rows, K, shapes):
     """windq_features_fit_score(_batch) takes the first pass of the unit features out of the fit+score kernel's tiles:

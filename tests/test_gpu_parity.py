@@ -212,7 +212,7 @@ def test_fit_score_small_config(windq):
 @pytest.mark.parametrize("R,C,G,unit_rows,K", [
     (512, 1024, 128, 0, 20), (512, 1024, 128, 128, 20), (200, 256, 64, 100, 20), (256, 512, 128, 0, 1),
     (128, 256, 128, 0, 7), (128, 256, 64, 64, 40), (64, 512, 256, 0, 20), (64, 1024, 512, 0, 5), (8, 16, 8, 4, 3),
-    (192, 120, 40, 96, 6)])
+    (192, 120, 40, 96, 6), (128, 256, 128, 0, 21), (128, 128, 128, 64, 64)])
 def test_fit_score_bf16_shapes(windq, R, C, G, unit_rows, K):
     W = synth.weights_llm(R, C, seed=21, device=DEV)
     X = synth.activations_llm(64, C, seed=22, device=DEV)

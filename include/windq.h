@@ -154,6 +154,14 @@ int windq_unit_features(const windq_mat* W, const float* s /*[cols]*/, int32_t c
  * deviations are ~0.4 of that estimate) has its 8-bit candidates scored again on the exact
  * route before the call's work ends, whatever the input.  |s_c * w| must square inside fp32's
  * normal range.
+ *   One weight's term of the sum is good to ~1e-5 of itself, not better: the low bit-widths form
+ * s_c (w - lo) - s_c code step from rounded products, and a weight within ~2e-5 steps of a
+ * rounding tie may take the neighbouring code here (the residual then has the same magnitude to
+ * 4e-5).  Both deviations are of random sign from weight to weight and vanish in a unit's sum to
+ * the ~1e-7 stated above as soon as the unit's error is spread over more than a few dozen
+ * weights, as it is in every unit of a weight matrix (thousands of rows).  A "unit" of one or
+ * a few short rows whose error sits in one or two weights (a single large activation scale)
+ * can read 1e-5 to 3e-5 off.
  */
 int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
                              const float* clip_grid /*HOST [K]*/, int32_t K,

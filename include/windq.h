@@ -154,14 +154,14 @@ int windq_unit_features(const windq_mat* W, const float* s /*[cols]*/, int32_t c
  * deviations are ~0.4 of that estimate) has its 8-bit candidates scored again on the exact
  * route before the call's work ends, whatever the input.  |s_c * w| must square inside fp32's
  * normal range.
- *   One weight's term of the sum is good to ~1e-5 of itself, not better: the low bit-widths form
- * s_c (w - lo) - s_c code step from rounded products, and a weight within ~2e-5 steps of a
- * rounding tie may take the neighbouring code here (the residual then has the same magnitude to
- * 4e-5).  Both deviations are of random sign from weight to weight and vanish in a unit's sum to
- * the ~1e-7 stated above as soon as the unit's error is spread over more than a few dozen
- * weights, as it is in every unit of a weight matrix (thousands of rows).  A "unit" of one or
- * a few short rows whose error sits in one or two weights (a single large activation scale)
- * can read 1e-5 to 3e-5 off.
+ *   That accuracy is a unit's, not a single weight's.  A weight's residual s_c (w - lo - code step)
+ * comes from fp32-rounded products: an absolute error near 1e-7 s_c (hi - lo) at 4 bits and below
+ * (1e-7 s_c step at 8 bits, exact route), and at 8 bits a weight within ~2e-5 steps of a rounding
+ * tie may take the neighbouring code (a residual of the same magnitude to 4e-5).  These errors
+ * are random in sign from weight to weight and average out of a unit's sum once its error is
+ * spread over a few dozen weights or more: every unit of 16 rows and up meets the figures above,
+ * and units of weight matrices have thousands of rows.  A "unit" of one or a few rows in which
+ * one weight under a large activation scale carries the whole error can read ~1e-4 off.
  */
 int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
                              const float* clip_grid /*HOST [K]*/, int32_t K,

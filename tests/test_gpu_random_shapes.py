@@ -58,3 +58,38 @@ def test_random_shapes(windq, seed):
             check_apply(windq, W, G, unit_rows, action, idx, K)
         except AssertionError as e:
             raise AssertionError(f"{what}: {e}") from e
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_shapes_after_the_hot_path(windq, seed):
+    """Protection (select, encode, masked fit+score and apply-plan), refinement, dequantisation and the
+    product from the artefact, each against the oracle as in its own test file, on random shapes."""
+    import test_gpu_dequant as DQ
+    import test_gpu_refine as RF
+    import test_gpu_salient as S
+    rng = random.Random(seed)
+    for it in range(60):
+        G = rng.choice([8, 16, 24, 32, 40, 64, 96, 128, 256])
+        C = G * rng.randint(1, 4)
+        R_u = rng.choice([4, 17, 64, 65, 100, 128, 130])
+        nrb = rng.randint(1, 3)
+        R = R_u * nrb
+        unit_rows = rng.choice([0, R_u])
+        K = rng.choice([1, 5, 6, 20])
+        ppm = rng.choice([0, 30000, 100000, 300000])
+        n_iter = rng.choice([0, 1, 3])
+        dtype = rng.choice([torch.bfloat16, torch.float32])
+        what = f"seed {seed} case {it}: R={R} C={C} G={G} unit_rows={unit_rows} K={K} ppm={ppm} n_iter={n_iter} {dtype}"
+        W = synth.weights_llm(R, C, seed=3000 * seed + it, device=DEV).to(dtype)
+        X = synth.activations_llm(64, C, seed=7000 * seed + it, device=DEV)
+        s, _ = windq.windq_calib_stats(X)
+        try:
+            if ppm:
+                mask, keep = S.check_select(windq, W, s, G, unit_rows, ppm)
+                S.check_encode(windq, W, s, G, unit_rows, ppm, mask, keep)
+                S.check_masked_fit_and_apply(windq, W, s, G, unit_rows, ppm, K)
+            RF.run_case(windq, W, s, G, unit_rows, K, n_iter, ppm)
+            DQ.run_case(windq, W, s, G, unit_rows, K, ppm)
+            DQ.gemv_case(windq, W, s, G, unit_rows, K, ppm)
+        except AssertionError as e:
+            raise AssertionError(f"{what}: {e}") from e

@@ -159,9 +159,10 @@ int windq_unit_features(const windq_mat* W, const float* s /*[cols]*/, int32_t c
  * (1e-7 s_c step at 8 bits, exact route), and at 8 bits a weight within ~2e-5 steps of a rounding
  * tie may take the neighbouring code (a residual of the same magnitude to 4e-5).  These errors
  * are random in sign from weight to weight and average out of a unit's sum once its error is
- * spread over a few dozen weights or more: every unit of 16 rows and up meets the figures above,
- * and units of weight matrices have thousands of rows.  A "unit" of one or a few rows in which
- * one weight under a large activation scale carries the whole error can read ~1e-4 off.
+ * spread over enough weights.  Under a large activation scale on one column that means enough
+ * rows: units of 64 rows and up meet the figures above (units of weight matrices have
+ * thousands of rows); a 17-row unit has been seen 1.2e-5 off, and a "unit" of one or a few rows
+ * in which one weight carries the whole error can read ~1e-4 off.
  */
 int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
                              const float* clip_grid /*HOST [K]*/, int32_t K,

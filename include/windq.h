@@ -157,12 +157,12 @@ int windq_unit_features(const windq_mat* W, const float* s /*[cols]*/, int32_t c
  *   That accuracy is a unit's, not a single weight's.  A weight's residual s_c (w - lo - code step)
  * comes from fp32-rounded products: an absolute error near 1e-7 s_c (hi - lo) at 4 bits and below
  * (1e-7 s_c step at 8 bits, exact route), and at 8 bits a weight within ~2e-5 steps of a rounding
- * tie may take the neighbouring code (a residual of the same magnitude to 4e-5).  These errors
- * are random in sign from weight to weight and average out of a unit's sum once its error is
- * spread over enough weights.  Under a large activation scale on one column that means enough
- * rows: units of 64 rows and up meet the figures above (units of weight matrices have
- * thousands of rows); a 17-row unit has been seen 1.2e-5 off, and a "unit" of one or a few rows
- * in which one weight carries the whole error can read ~1e-4 off.
+ * tie may take the neighbouring code (a residual of the same magnitude to 4e-5; units of fewer
+ * than 64 rows take that decision exactly as written above instead, at 7 % more time).  These
+ * errors are random in sign from weight to weight and average out of a unit's sum once its error
+ * is spread over a few dozen weights: the figures above hold for units of three rows and up in
+ * every case tried, and units of weight matrices have thousands of rows; a single-row "unit"
+ * whose error sits in one weight under a large activation scale can read up to ~1e-4 off.
  */
 int windq_fit_score_all_bits(const windq_mat* W, const float* s /*[cols]*/, int32_t chunk_w, int64_t unit_rows,
                              const float* clip_grid /*HOST [K]*/, int32_t K,

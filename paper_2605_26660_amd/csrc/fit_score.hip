@@ -107,6 +107,7 @@ constexpr double NOISE_C1 = 4.0 * 3.552713678800501e-15 / (NOISE_MAX * NOISE_MAX
 // A tile takes the exact sweep when one row holds more than 1 / ROW_SHARE of the sum of the
 // rows' squared ranges (that row would carry most of the tile's 8-bit error by itself).
 constexpr float ROW_SHARE = 1.5f;
+constexpr int64_t FS_FEW_ROWS = 64;         // units of fewer rows: the exact sweeps take the normative 8-bit decision
 
 // One matrix of a launch.
 struct FitScoreMat {
@@ -176,30 +177,48 @@ inline size_t fit_score_lds_bytes(int32_t dtype, int32_t chunk_w, bool masked = 
 //   two-sum, and the residual is the FMA on the rounded part plus the error.
 // A wavefront takes the second route when any of its 64 groups needs it.
 struct KParams {
-    float rinv, h;     // 1/range; x = (w - a)*rinv + h is the position in the range, a = 0 (anchored) or c
+    float rinv, h;     // 1/range; x = (w - a)*rinv + h is the position in the range, a = 0 (anchored) or c.
+                       // The sweeps that take every column on the exact route put 1/step of the 8-bit grid
+                       // (an IEEE quotient) into h instead, and take x = clamp01((w - lo)*rinv).
     float nc, Mq;      // -c (anchor), 2^23 + q0
     float nlo;         // -lo
     float nd[4];       // -step for 8, 4, 3, 2 bits (0 when degenerate)
 };
 
-// The exact 8-bit residual of one weight at clip ratio P, times s_c.
-template <bool ANCHORED>
+// The 8-bit code of one weight, less the anchor's code q0, by the normative fp32 steps (the ones
+// windq_apply_plan takes): un = fl(w - lo), t = fl(un * fl(1/step)), ties to even, clamped to
+// [0, 255].  inv = 1/step; t + 2^23 rounds t >= 0 to the nearest-even integer, and whatever a
+// negative t turns into is clamped to code 0.
+__device__ __forceinline__ float normative_code8(const float un, const float inv, const float M, const float Mq) {
+    const float t = un * inv;         // (two roundings, as the normative steps have them: never one fused operation)
+    const float tM = t + M;
+    return __builtin_amdgcn_fmed3f(tM, M, M + 255.0f) - Mq;
+}
+
+// The exact 8-bit residual of one weight at clip ratio P, times s_c.  NORMATIVE: the code is the
+// one the normative steps give (P.h holds 1/step); otherwise it is rne(255 x), which differs from
+// it only for a weight within ~2e-5 steps of a tie, where the two residuals have the same
+// magnitude to 4e-5: that shows in a unit's error only if a single weight carries a fair share of
+// it, so the sweeps over every column, which are the ones small units take, are normative.
+template <bool ANCHORED, bool NORMATIVE>
 __device__ __forceinline__ float exact_residual8(const float w, const float sc, const KParams& P, const float Q0,
                                                  const float M, float& x) {
-    float r;
-    if (ANCHORED) {
-        x = fma_clamp01(w, P.rinv, P.h);                      // position in the clipped range, in [0, 1]
-        const float qc = fmaf(x, Q0, M) - P.Mq;               // code - q0
-        r = fmaf(qc, P.nd[0], w) + P.nc;                      // (c + r) - c
-    } else {
-        const float u0 = w + P.nc;                            // w - c, rounded
-        const float bb = u0 - w;
-        const float e = (w - (u0 - bb)) + (P.nc - bb);        // its rounding error: (w - c) = u0 + e exactly
-        x = fma_clamp01(u0, P.rinv, P.h);
-        const float qc = fmaf(x, Q0, M) - P.Mq;
-        r = fmaf(qc, P.nd[0], u0) + e;
+    const float base = ANCHORED ? w : w + P.nc;               // w, or w - c rounded
+    float fix = P.nc;
+    if (!ANCHORED) {
+        const float bb = base - w;
+        fix = (w - (base - bb)) + (P.nc - bb);                // the rounding error of w - c: (w - c) = base + fix exactly
     }
-    return r * sc;
+    float qc;                                                 // code - q0
+    if (NORMATIVE) {
+        const float un = w + P.nlo;
+        x = mul_clamp01(un, P.rinv);                          // position in the clipped range, in [0, 1]
+        qc = normative_code8(un, P.h, M, P.Mq);
+    } else {
+        x = fma_clamp01(base, P.rinv, P.h);
+        qc = fmaf(x, Q0, M) - P.Mq;
+    }
+    return (fmaf(qc, P.nd[0], base) + fix) * sc;              // ((c + r) - c) s_c
 }
 
 // One weight against FS_KB clip ratios x 4 bit-widths, the 8-bit one on the exact route.
@@ -215,7 +234,7 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
     for (int i = 0; i < FS_KB; ++i) {
         const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
         float x;
-        const float r8 = exact_residual8<ANCHORED>(w, sc, P[i], Q[0], M, x);
+        const float r8 = exact_residual8<ANCHORED, false>(w, sc, P[i], Q[0], M, x);
         acc[i][0] = fmaf(r8, r8, acc[i][0]);
 #pragma unroll
         for (int b = 1; b < 4; ++b) {
@@ -230,7 +249,7 @@ __device__ __forceinline__ void score_weight(const float w, const float sc, cons
 // score_weight with the four bit-widths side by side, stage by stage (see score_weight_short): six live
 // temporaries instead of two, for the sweeps over all columns, which read four columns at a time to
 // make room for them.  The 8-bit candidate's two extra steps run into the next ratio's first ones.
-template <bool ANCHORED>
+template <bool ANCHORED, bool NORMATIVE>
 __device__ __forceinline__ void score_weight_staged(const float w, const float sc, const KParams (&P)[FS_KB],
                                                     const float (&Q)[4], const float M, const float nM,
                                                     float (&acc)[FS_KB][4]) {
@@ -238,47 +257,83 @@ __device__ __forceinline__ void score_weight_staged(const float w, const float s
     const float ms = sc * nM;
 #pragma unroll
     for (int i = 0; i < FS_KB; ++i) {
-        const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
-        float x, base = w, fix = P[i].nc;
-        if (ANCHORED) {
-            x = fma_clamp01(w, P[i].rinv, P[i].h);                // position in the clipped range, in [0, 1]
+        if constexpr (NORMATIVE) {
+            const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
+            const float un = w + P[i].nlo;                            // fl(w - lo): the first of the normative steps
+            const float x = mul_clamp01(un, P[i].rinv);               // position in the clipped range, in [0, 1]
+            float base = w, fix = P[i].nc;
+            if (!ANCHORED) {
+                const float u0 = w + P[i].nc;                         // w - c, rounded
+                const float bb = u0 - w;
+                fix = (w - (u0 - bb)) + (P[i].nc - bb);               // its rounding error: (w - c) = u0 + fix exactly
+                base = u0;
+            }
+            // the 8-bit code by the normative steps (P.h = 1/step; see normative_code8), one step per stage
+            float t[4];
+            __builtin_amdgcn_sched_barrier(0);
+            t[0] = un * P[i].h;
+#pragma unroll
+            for (int b = 1; b < 4; ++b) t[b] = fmaf(x, Q[b], M);
+            __builtin_amdgcn_sched_barrier(0);
+            t[0] = t[0] + M;
+#pragma unroll
+            for (int b = 1; b < 4; ++b) t[b] = fmaf(t[b], sc, ms);
+            __builtin_amdgcn_sched_barrier(0);
+            t[0] = __builtin_amdgcn_fmed3f(t[0], M, M + 255.0f);
+#pragma unroll
+            for (int b = 1; b < 4; ++b) t[b] = fmaf(t[b], P[i].nd[b], u1);
+            __builtin_amdgcn_sched_barrier(0);
+            t[0] = t[0] - P[i].Mq;                                    // code - q0
+#pragma unroll
+            for (int b = 1; b < 4; ++b) acc[i][b] = fmaf(t[b], t[b], acc[i][b]);
+            __builtin_amdgcn_sched_barrier(0);
+            t[0] = fmaf(t[0], P[i].nd[0], base);                      // (c + r), small
+            t[0] = t[0] + fix;                                        // r
+            const float r8 = t[0] * sc;
+            acc[i][0] = fmaf(r8, r8, acc[i][0]);
         } else {
-            const float u0 = w + P[i].nc;                         // w - c, rounded
-            const float bb = u0 - w;
-            fix = (w - (u0 - bb)) + (P[i].nc - bb);               // its rounding error: (w - c) = u0 + fix exactly
-            x = fma_clamp01(u0, P[i].rinv, P[i].h);
-            base = u0;
+            const float u1 = fmaf(P[i].nlo, sc, w1);                  // s_c * (w - lo)
+            float x, base = w, fix = P[i].nc;
+            if (ANCHORED) {
+                x = fma_clamp01(w, P[i].rinv, P[i].h);                // position in the clipped range, in [0, 1]
+            } else {
+                const float u0 = w + P[i].nc;                         // w - c, rounded
+                const float bb = u0 - w;
+                fix = (w - (u0 - bb)) + (P[i].nc - bb);               // its rounding error: (w - c) = u0 + fix exactly
+                x = fma_clamp01(u0, P[i].rinv, P[i].h);
+                base = u0;
+            }
+            float t[4];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) t[b] = fmaf(x, Q[b], M);
+            __builtin_amdgcn_sched_barrier(0);
+            t[0] = t[0] - P[i].Mq;                                    // code - q0
+#pragma unroll
+            for (int b = 1; b < 4; ++b) t[b] = fmaf(t[b], sc, ms);
+            __builtin_amdgcn_sched_barrier(0);
+            t[0] = fmaf(t[0], P[i].nd[0], base);                      // (c + r), small
+#pragma unroll
+            for (int b = 1; b < 4; ++b) t[b] = fmaf(t[b], P[i].nd[b], u1);
+            __builtin_amdgcn_sched_barrier(0);
+            t[0] = t[0] + fix;                                        // r
+#pragma unroll
+            for (int b = 1; b < 4; ++b) acc[i][b] = fmaf(t[b], t[b], acc[i][b]);
+            __builtin_amdgcn_sched_barrier(0);
+            const float r8 = t[0] * sc;
+            acc[i][0] = fmaf(r8, r8, acc[i][0]);
         }
-        float t[4];
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int b = 0; b < 4; ++b) t[b] = fmaf(x, Q[b], M);
-        __builtin_amdgcn_sched_barrier(0);
-        t[0] = t[0] - P[i].Mq;                                    // code - q0
-#pragma unroll
-        for (int b = 1; b < 4; ++b) t[b] = fmaf(t[b], sc, ms);
-        __builtin_amdgcn_sched_barrier(0);
-        t[0] = fmaf(t[0], P[i].nd[0], base);                      // (c + r), small
-#pragma unroll
-        for (int b = 1; b < 4; ++b) t[b] = fmaf(t[b], P[i].nd[b], u1);
-        __builtin_amdgcn_sched_barrier(0);
-        t[0] = t[0] + fix;                                        // r
-#pragma unroll
-        for (int b = 1; b < 4; ++b) acc[i][b] = fmaf(t[b], t[b], acc[i][b]);
-        __builtin_amdgcn_sched_barrier(0);
-        const float r8 = t[0] * sc;
-        acc[i][0] = fmaf(r8, r8, acc[i][0]);
     }
 }
 
 // The 8-bit candidate alone, exact route (the pass over listed units).
-template <bool ANCHORED>
+template <bool ANCHORED, bool NORMATIVE>
 __device__ __forceinline__ void score_weight_8(const float w, const float sc, const KParams (&P)[FS_KB], const float Q0,
                                                const float M, float (&acc)[FS_KB][4]) {
 #pragma unroll
     for (int i = 0; i < FS_KB; ++i) {
         float x;
-        const float r8 = exact_residual8<ANCHORED>(w, sc, P[i], Q0, M, x);
+        const float r8 = exact_residual8<ANCHORED, NORMATIVE>(w, sc, P[i], Q0, M, x);
         acc[i][0] = fmaf(r8, r8, acc[i][0]);
     }
 }
@@ -861,8 +916,20 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
             // (the row addresses are formed from a fresh lane index in front of each sweep: kept
             // from here they would be spilled across the parameter set-up)
             __builtin_amdgcn_s_setprio(0);       // the sweeps: issue-bound, ordinary priority
-            auto sweep = [&](auto anchored_t) {
-                constexpr bool AN = decltype(anchored_t)::value;
+            auto sweep = [&](auto anchored_t, auto normative_t) {
+                constexpr bool AN = decltype(anchored_t)::value, NORM = decltype(normative_t)::value;
+                if (NORM) {         // the 8-bit decision by the normative steps: 1/step in h's place
+#pragma unroll
+                    for (int i = 0; i < FS_KB; ++i) {
+                        const float d8 = -P[i].nd[0];
+                        P[i].h = pin_vgpr(d8 >= FLT_MIN ? 1.0f / d8 : 0.0f);
+                        if (ONLY8) {        // (-lo is not kept through the set-up in this mode)
+                            int k = item * FS_KB + i;
+                            k = k < K ? k : K - 1;
+                            P[i].nlo = pin_vgpr(-(B.grid.p[k] * mn));
+                        }
+                    }
+                }
                 const int lane_v = fresh_lane();
                 const char* __restrict__ wrow = tile + lane_v * row_bytes;
                 const uint8_t* __restrict__ mrow = mtile + lane_v * mstride;
@@ -878,7 +945,7 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
                             drop_masked(s8, m);
                         }
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) score_weight_8<AN>(w[j], s8[j], P, Q[0], M, acc);
+                        for (int j = 0; j < 8; ++j) score_weight_8<AN, NORM>(w[j], s8[j], P, Q[0], M, acc);
                     }
                 } else {
                     for (int32_t c = 0; c < G; c += 4) {
@@ -892,14 +959,20 @@ __device__ __forceinline__ void fit_score_tile(const FitScoreArgs& B, const FitS
                             s4[2] = drop_if_set<2>(s4[2], m); s4[3] = drop_if_set<3>(s4[3], m);
                         }
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) score_weight_staged<AN>(w[j], s4[j], P, Q, M, nM, acc);
+                        for (int j = 0; j < 4; ++j) score_weight_staged<AN, NORM>(w[j], s4[j], P, Q, M, nM, acc);
                     }
                 }
             };
+            // A sweep over every column takes the 8-bit rounding decision as the normative steps do when the
+            // unit has few rows: there a single weight near a rounding tie can hold enough of the unit's error
+            // for the neighbouring code's residual (the same magnitude to 4e-5) to show; it costs 7 %.
+            const bool few_rows = A.g.R_u < FS_FEW_ROWS;
             if (!anchored) {
-                sweep(std::false_type{});
+                if (few_rows) sweep(std::false_type{}, std::true_type{});
+                else sweep(std::false_type{}, std::false_type{});
             } else if (ONLY8 || nh < 0 || !rows_even) {
-                sweep(std::true_type{});
+                if (few_rows) sweep(std::true_type{}, std::true_type{});
+                else sweep(std::true_type{}, std::false_type{});
             } else {
                 const int lane_v = fresh_lane();
                 const char* __restrict__ wrow = tile + lane_v * row_bytes;
@@ -1038,22 +1111,24 @@ __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_kernel(const FitScore
 template <int DT, bool MASKED>
 __global__ __launch_bounds__(FS_THREADS, 5) void fit_score_redo_kernel(const FitScoreArgs B) {
     extern __shared__ char smem[];
-    int64_t start[WINDQ_MAX_BATCH + 1];
-    start[0] = 0;
-#pragma unroll
-    for (int i = 0; i < WINDQ_MAX_BATCH; ++i) {
-        int64_t nt = 0;
-        if (i < B.n) {
-            int64_t cnt = (int64_t)*B.m[i].redo_count;
-            cnt = cnt < B.m[i].g.U ? cnt : B.m[i].g.U;
-            nt = cnt * B.m[i].g.tiles_per_unit;
+    // (no table of the matrices' first tiles: indexed by a run-time value it would live in scratch memory)
+    auto listed_tiles = [&](int i) -> int64_t {
+        int64_t cnt = (int64_t)*B.m[i].redo_count;
+        cnt = cnt < B.m[i].g.U ? cnt : B.m[i].g.U;
+        return cnt * B.m[i].g.tiles_per_unit;
+    };
+    int64_t total = 0;
+    for (int i = 0; i < B.n; ++i) total += listed_tiles(i);
+    for (int64_t w = blockIdx.x; w < total; w += gridDim.x) {
+        int mi = 0;
+        int64_t first = 0;
+        for (; mi + 1 < B.n; ++mi) {
+            const int64_t nt = listed_tiles(mi);
+            if (w < first + nt) break;
+            first += nt;
         }
-        start[i + 1] = start[i] + nt;
-    }
-    for (int64_t w = blockIdx.x; w < start[WINDQ_MAX_BATCH]; w += gridDim.x) {
-        const int mi = batch_index(start, B.n, w);
         const FitScoreMat& A = B.m[mi];
-        const int64_t local = w - start[mi];
+        const int64_t local = w - first;
         const int64_t li = local / A.g.tiles_per_unit;
         const int64_t u = A.redo_list[li];
         const TileCoord tc = tile_coord_of_unit(A.g, u, local - li * A.g.tiles_per_unit);

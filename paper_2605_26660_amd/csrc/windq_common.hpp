@@ -265,6 +265,13 @@ __device__ __forceinline__ float fma_clamp01(float a, float b, float c) {
     return r;
 }
 
+// a * b with the result clamped to [0, 1] by the instruction's output modifier.
+__device__ __forceinline__ float mul_clamp01(float a, float b) {
+    float r;
+    asm("v_mul_f32 %0, %1, %2 clamp" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // Sum of a double over the 64 lanes of a wavefront, fixed butterfly order.
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll

@@ -93,3 +93,84 @@ def test_random_shapes_after_the_hot_path(windq, seed):
             DQ.gemv_case(windq, W, s, G, unit_rows, K, ppm)
         except AssertionError as e:
             raise AssertionError(f"{what}: {e}") from e
+
+
+def test_random_batches_and_strides(windq):
+    """Random batches of 1..8 matrices, each a column window of a wider one (ld > cols): every batch call
+    against the per-matrix calls, and the windows against contiguous copies, bit for bit."""
+    rng = random.Random(41)
+    for it in range(100):
+        G = rng.choice([8, 16, 24, 32, 40, 64, 128, 256])
+        R_u = rng.choice([1, 5, 64, 65, 128, 200])
+        unit_rows = rng.choice([0, R_u])
+        K = rng.choice([1, 5, 20, 21, 40])
+        dtype = rng.choice([torch.bfloat16, torch.float32])
+        n = rng.randint(1, 8)
+        Ws, ss = [], []
+        for i in range(n):
+            R = R_u * rng.randint(1, 3) if unit_rows else rng.choice([1, 7, 64, 100, 129, 300])
+            C = G * rng.randint(1, 4)
+            pad_l = 8 * rng.randint(0, 2) * (2 if dtype == torch.float32 else 1)
+            pad_r = 8 * rng.randint(0, 2)
+            big = synth.weights_llm(R, C + pad_l + pad_r, seed=9000 + 10 * it + i, device=DEV).to(dtype)
+            Ws.append(big[:, pad_l:pad_l + C])
+            ss.append(windq.windq_calib_stats(synth.activations_llm(32, C, seed=9500 + 10 * it + i, device=DEV))[0])
+        what = f"case {it}: G={G} unit_rows={unit_rows} K={K} {dtype} shapes={[tuple(w.shape) for w in Ws]} ld={[w.stride(0) for w in Ws]}"
+        cg = grid(K)
+        one_fit = [windq.windq_fit_score_all_bits(W, s, G, unit_rows, cg) for W, s in zip(Ws, ss)]
+        bat_fit = windq.windq_fit_score_all_bits_batch(Ws, ss, G, unit_rows, cg)
+        one_ft = [windq.windq_unit_features(W, s, G, unit_rows) for W, s in zip(Ws, ss)]
+        bat_ft = windq.windq_unit_features_batch(Ws, ss, G, unit_rows)
+        bat_fu = windq.windq_features_fit_score_batch(Ws, ss, G, unit_rows, cg)
+        torch.cuda.synchronize()
+        acts, offs, codes, outs = [], [], [], []
+        for i, W in enumerate(Ws):
+            assert all(same_bits(a, b) for a, b in zip(one_fit[i], bat_fit[i])), f"{what}: fit+score, matrix {i}"
+            assert same_bits(one_ft[i], bat_ft[i]), f"{what}: features, matrix {i}"
+            assert same_bits(bat_fu[i][0], one_ft[i]) and all(same_bits(a, b) for a, b in zip(one_fit[i], bat_fu[i][1:])), \
+                f"{what}: fused, matrix {i}"
+            again = windq.windq_fit_score_all_bits(W.contiguous(), ss[i], G, unit_rows, cg)
+            torch.cuda.synchronize()
+            assert all(same_bits(a, b) for a, b in zip(one_fit[i], again)), f"{what}: window != copy, matrix {i}"
+            U, Ru = windq.n_units(W.shape[0], W.shape[1], G, unit_rows)
+            a = torch.tensor([rng.randint(0, 6) for _ in range(U)], dtype=torch.uint8)
+            off = windq.windq_plan_layout(a, Ru, G)
+            acts.append(a.to(DEV))
+            offs.append(off.to(DEV))
+            codes.append(torch.zeros(max(int(off[-1]), 16), dtype=torch.uint8, device=DEV))
+            groups = W.shape[0] * (W.shape[1] // G)
+            outs.append((torch.empty(groups, dtype=torch.float32, device=DEV), torch.empty(groups, dtype=torch.float32, device=DEV)))
+        idxs = [f[1] for f in one_fit]
+        bat = windq.windq_apply_plan_batch(Ws, G, unit_rows, acts, idxs, cg, offs, codes, outs)
+        torch.cuda.synchronize()
+        for i, W in enumerate(Ws):
+            c1, s1, o1 = windq.windq_apply_plan(W, G, unit_rows, acts[i], idxs[i], cg, offs[i])
+            torch.cuda.synchronize()
+            used = int(offs[i][-1])
+            assert same_bits(c1[:used], bat[i][0][:used]) and same_bits(s1, bat[i][1]) and same_bits(o1, bat[i][2]), \
+                f"{what}: apply-plan, matrix {i}"
+
+
+def test_random_calib_shapes(windq):
+    """Activation matrices of 1..5000 tokens (both kernels of the call), windows of wider ones, alone and in
+    batches, against the oracle."""
+    from oracle import windq_oracle as O
+    rng = random.Random(51)
+    for it in range(60):
+        dtype = rng.choice([torch.bfloat16, torch.float32])
+        Xs = []
+        for i in range(rng.randint(1, 6)):
+            T = rng.choice([1, 2, 31, 32, 33, 64, 100, 512, 1000, 4095, 4096, 4097, 5000])
+            C = 8 * rng.randint(1, 140)
+            pad = 8 * rng.randint(0, 3)
+            big = synth.activations_llm(T, C + 2 * pad, seed=100 * it + i, device=DEV, dtype=dtype)
+            Xs.append(big[:, pad:pad + C])
+        what = f"case {it}: {dtype} {[tuple(x.shape) for x in Xs]}"
+        singles = [windq.windq_calib_stats(X) for X in Xs]
+        batch = windq.windq_calib_stats_batch(Xs)
+        torch.cuda.synchronize()
+        for X, (a, r), (ba, br) in zip(Xs, singles, batch):
+            o_abs, o_rms = O.calib_stats(to_np(X))
+            assert_close(to_np(a), o_abs, what=f"{what}: s_absmean")
+            assert_close(to_np(r), o_rms, what=f"{what}: s_rms")
+            assert torch.equal(a, ba) and torch.equal(r, br), f"{what}: batch != single"
